@@ -1,0 +1,185 @@
+/*
+ * stx — sparse-incidence training step for translation-based knowledge-graph embeddings
+ *       (TransE, TorusE, TransH, TransR) on AMD MI355X (gfx950).
+ *
+ * The method (SparseTransX, arXiv 2502.16949): a batch of (head, relation, tail) triplets and their
+ * corrupted negatives is written as a sparse incidence matrix A with three nonzeros per row, so that
+ * the forward pass is one sparse-dense product A.[E;R] = h + r - t per row (Sec. 4.2) followed by a
+ * distance and a margin-ranking loss (Sec. 5.3), and the backward pass is the transposed product
+ * A^T.(dL/dC) (Appendix G), which replaces the per-index scatter-adds.
+ *
+ * Conventions for every entry point
+ *   - Unless a parameter says "host", pointers are DEVICE pointers owned by the caller.  The library
+ *     never allocates or frees device memory: its scratch lives in the workspace given to stx_create.
+ *   - All work is enqueued on the stream given to stx_create and the calls return without waiting;
+ *     only stx_check_indices synchronises.  Calls on one context must not overlap in time.
+ *   - Every call returns a stx_status.  Host-detectable argument errors (null pointers, sizes beyond
+ *     the configured maxima, bad enums) are reported before anything is launched.
+ *   - Indices are int32, counts int64.  Tables are fp32, row-major, 16-byte aligned, with
+ *     dim % 4 == 0 and rel_dim % 4 == 0, both <= 1024.
+ */
+#ifndef STX_H
+#define STX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    STX_OK = 0,
+    STX_ERR_NULL = 1,        /* a required pointer is null */
+    STX_ERR_BAD_ARG = 2,     /* enum out of range, negative size, dim not a multiple of 4, ... */
+    STX_ERR_INDEX_RANGE = 3, /* stx_check_indices: some triplet index was outside its table */
+    STX_ERR_WORKSPACE = 4,   /* workspace smaller than stx_workspace_bytes, or misaligned */
+    STX_ERR_STATE = 5,       /* call order violated (e.g. backward before forward) */
+    STX_ERR_UNSUPPORTED = 6, /* valid request this build does not implement */
+    STX_ERR_HIP = 7          /* a HIP runtime call failed */
+} stx_status;
+
+/* Score functions of Table 2 (Sec. 4.2): which incidence form is used and what follows it. */
+enum { STX_TRANSE = 0, STX_TRANSH = 1, STX_TRANSR = 2, STX_TORUSE = 3 };
+/* Norm applied to the translated vector (Sec. 4.3, 4.6): L1, unsquared L2, or their torus
+ * versions, taken on the fractional part f = y - floor(y) as sum / root-sum-square of min(f, 1-f). */
+enum { STX_L1 = 0, STX_L2 = 1, STX_TORUS_L1 = 2, STX_TORUS_L2 = 3 };
+/* Reduction of the margin-ranking loss over the b*k (positive, negative) pairs. */
+enum { STX_SUM = 0, STX_MEAN = 1 };
+
+#define STX_FLAG_RENORM_W 1u  /* TransH: rescale every touched normal w_r to unit length after the update */
+#define STX_FLAG_BF16_PROJ 2u /* TransR: bfloat16 operands, fp32 accumulation in the projection products */
+
+typedef struct {
+    int32_t model;     /* STX_TRANSE ... */
+    int32_t dist;      /* STX_L1 ... */
+    int32_t reduce;    /* STX_SUM / STX_MEAN */
+    int32_t dim;       /* entity embedding width d */
+    int32_t rel_dim;   /* TransR: relation space width k; other models: ignored (taken as dim) */
+    int64_t n_ent;     /* N */
+    int64_t n_rel;     /* R;  N + R < 2^31 */
+    float margin;      /* gamma of the hinge max(0, gamma + d_pos - d_neg) */
+    int32_t max_batch; /* largest b (positives per batch) any call will pass */
+    int32_t max_neg;   /* largest k (negatives per positive) any call will pass; 3*b*(1+k) < 2^31 */
+    uint32_t flags;    /* STX_FLAG_* */
+} stx_config;
+
+/* Parameter tables (device, fp32, row-major), updated in place by stx_sgd_step.
+ *   TransE / TorusE : ent = X = [E;R], (n_ent + n_rel) x dim, relation r in row n_ent + r (Sec. 4.2.2);
+ *                     rel, w, proj unused.
+ *   TransH          : ent = E (n_ent x dim), rel = d_r (n_rel x dim), w = w_r (n_rel x dim)  (Sec. 4.5).
+ *   TransR          : ent = E (n_ent x dim), rel = r (n_rel x rel_dim),
+ *                     proj = M_r (n_rel x rel_dim x dim, each matrix row-major)               (Sec. 4.4). */
+typedef struct {
+    float *ent;
+    float *rel;
+    float *w;
+    float *proj;
+} stx_params;
+
+/* One batch as a sparse incidence matrix and its transpose (Sec. 4.2; Appendix G).
+ * The caller allocates every array (device) for the configured maxima:
+ *   rows_max = max_batch * (1 + max_neg), nnz_max = 3 * rows_max, cols_max = min(nnz_max, n_ent + n_rel).
+ * stx_build_incidence fills the arrays (asynchronously) and the host-side scalars b, k, n_rows, nnz.
+ *
+ * A, `hrt` form, CSR: row i holds its three entries in the order (head, n_ent + relation, tail) with
+ * values (+1, +1, -1); the `ht` form of Sec. 4.2.1 is entries 0 and 2 of each row.  Rows 0..b-1 are the
+ * positives; the kk-th negative of positive i is row b + i*k + kk and keeps the relation of i.
+ * Equal head and tail stay two entries.
+ *
+ * A^T, doubly compressed and sorted by column: only the U columns holding an entry appear, ascending;
+ * entries of one column keep their order of appearance in A (position 3*row + slot).                 */
+typedef struct {
+    int32_t b, k;             /* host, filled by stx_build_incidence */
+    int64_t n_rows, nnz;      /* host, filled: b*(1+k), 3*n_rows */
+    int32_t *a_rowptr;        /* [rows_max + 1]  = 3*i */
+    int32_t *a_colidx;        /* [nnz_max] */
+    float *a_vals;            /* [nnz_max] */
+    int32_t *at_touched_cols; /* [cols_max]      column id of segment s, ascending */
+    int32_t *at_seg_ptr;      /* [cols_max + 1]  first sorted entry of segment s; [U] = nnz */
+    int32_t *at_row_idx;      /* [nnz_max]       row of sorted entry e */
+    int8_t *at_sign;          /* [nnz_max]       value of sorted entry e: +1 or -1 */
+    int32_t *at_seg_id;       /* [nnz_max]       segment of sorted entry e */
+    int32_t *at_packed;       /* [nnz_max]       row_idx << 2 | (entry starts its segment) << 1 | (sign < 0);
+                                                 what the transposed-product kernels read */
+    int32_t *n_touched;       /* [1]             U */
+} stx_incidence;
+
+/* Gradients, row-sparse and aligned with the segments of A^T: row s belongs to column
+ * at_touched_cols[s].  ld = max(dim, rel_dim) floats per row; cols_max rows each (device, caller-owned).
+ *   rows   : segments of entity columns   -> dL/dE rows (width dim);
+ *            segments of relation columns -> TransE/TorusE: dL/dR row (these are rows of X too);
+ *                                            TransH: dL/d(d_r);  TransR: dL/dr (width rel_dim).
+ *   w_rows : TransH only: dL/dw_r in the rows of relation segments; other rows are not written.
+ *   proj   : TransR only: dL/dM_r, dense n_rel x rel_dim x dim; only matrices of relations present in
+ *            the batch are written.                                                                   */
+typedef struct {
+    float *rows;
+    float *w_rows;
+    float *proj;
+} stx_grads;
+
+typedef struct stx_ctx stx_ctx;
+
+/* Bytes of device workspace a context with this configuration needs. */
+stx_status stx_workspace_bytes(const stx_config *cfg, size_t *bytes /* host, out */);
+
+/* Create a context.  workspace: device memory, 256-byte aligned, at least stx_workspace_bytes, owned by
+ * the caller and kept alive until stx_destroy.  stream: a hipStream_t (NULL = the default stream).
+ * Enqueues one small kernel that clears the library's counters.                                       */
+stx_status stx_create(const stx_config *cfg, void *workspace, size_t workspace_bytes, void *stream,
+                      stx_ctx **out /* host, out */);
+stx_status stx_destroy(stx_ctx *ctx);
+
+/* Negative sampling (Sec. 5.3: one pre-generated negative set; Sec. 6.1: as many negatives as
+ * positives per slot).  For positive i of this call (global index g = global_offset + i) and slot kk:
+ *   u = SplitMix64 output number (epoch*m_total + g)*k + kk of the sequence seeded with `seed`;
+ *   the head is replaced if the top bit of u is set, else the tail;
+ *   replacement entity = floor((u mod 2^32) * n_ent / 2^32).  The relation is kept, nothing is filtered.
+ * h, r, t: [m] in; neg_h, neg_t: [m*k] out.                                                           */
+stx_status stx_sample_negatives(stx_ctx *ctx, const int32_t *h, const int32_t *r, const int32_t *t,
+                                int64_t m, int32_t k, uint64_t seed, uint64_t epoch, int64_t m_total,
+                                int64_t global_offset, int32_t *neg_h, int32_t *neg_t);
+
+/* Build A and A^T for one batch (Sec. 4.2.1, 4.2.2): h, r, t [b]; neg_h, neg_t [b*k] (may be null when
+ * k == 0).  Out-of-range indices are clamped into their table and counted (see stx_check_indices), so
+ * later kernels never read outside the tables.  b == 0 gives an empty matrix.                         */
+stx_status stx_build_incidence(stx_ctx *ctx, const int32_t *h, const int32_t *r, const int32_t *t,
+                               const int32_t *neg_h, const int32_t *neg_t, int32_t b, int32_t k,
+                               stx_incidence *inc /* host struct of device arrays */);
+
+/* Waits for the stream, then reports whether any index seen by stx_build_incidence since the last
+ * check was out of range: *n_bad (host, may be null) receives the count; returns STX_ERR_INDEX_RANGE
+ * when it is nonzero.  The counter is reset.                                                          */
+stx_status stx_check_indices(stx_ctx *ctx, int64_t *n_bad);
+
+/* C = A.X (Sec. 4.2): row i of C (n_rows x dim, fp32) = (X[h] + X[n_ent + r]) - X[t] for TransE/TorusE,
+ * E[h] - E[t] for TransH/TransR, each operation rounded once, in that order.                          */
+stx_status stx_spmm(stx_ctx *ctx, const stx_incidence *inc, const stx_params *p, float *c_out);
+
+/* Forward (Sec. 4.3-4.6, 5.3): scores[i] = distance of row i (n_rows, fp32); *loss (device, fp32) =
+ * sum (or mean) over pairs of max(0, margin + score[i] - score[b + i*k + kk]).  Also stores dL/dy of
+ * every row in the workspace for stx_backward: the pair is active when margin + d_pos - d_neg > 0
+ * (evaluated in fp32 as (margin + d_pos) - d_neg); subgradient 0 at every tie (sign(0) = 0, zero
+ * vector at zero distance, 0 at torus fractional part 0 or 1/2).                                      */
+stx_status stx_forward(stx_ctx *ctx, const stx_incidence *inc, const stx_params *p, float *scores,
+                       float *loss);
+
+/* Backward (Appendix G): g->rows[s] = sum over the entries e of segment s of sign[e] * (dL/dx of row
+ * row_idx[e]), summed without atomics in a fixed order (bitwise reproducible); TransH and TransR first
+ * pass dL/dy back through their projection (Sec. 4.4, 4.5) and also fill w_rows / proj.
+ * Needs the stx_forward of the same incidence immediately before it on this context.                  */
+stx_status stx_backward(stx_ctx *ctx, const stx_incidence *inc, const stx_params *p, stx_grads *g);
+
+/* SGD on the touched rows only: row <- row - lr * grad (product and difference rounded separately).
+ * TorusE: then v <- v - floor(v) (0 if that rounds to 1): only fractional parts are kept (Sec. 4.6).
+ * TransH with STX_FLAG_RENORM_W: touched w_r are rescaled to unit length.                             */
+stx_status stx_sgd_step(stx_ctx *ctx, stx_params *p, const stx_incidence *inc, const stx_grads *g,
+                        float lr);
+
+const char *stx_status_string(stx_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STX_H */

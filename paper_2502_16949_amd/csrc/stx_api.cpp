@@ -1,0 +1,280 @@
+// C-ABI entry points of libstx: argument checks, workspace layout, call-order state, and dispatch to
+// the kernel launchers.  No arithmetic of the method happens here.
+#include <new>
+
+#include "stx_internal.h"
+
+using namespace stx;
+
+namespace {
+
+inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+struct Layout {
+    size_t ctrl, keys[2], pay[2], table, tile_heads, loss_partials, partials, gbuf[4], total;
+    int64_t rows_max, nnz_max, cols_max;
+    int ld, out_dim, ntiles_max, fwd_blocks_max, n_gbuf;
+    int sort_bits, sort_passes, digit_bits;
+};
+
+stx_status check_config(const stx_config *c)
+{
+    if (!c) return STX_ERR_NULL;
+    if (c->model < STX_TRANSE || c->model > STX_TORUSE) return STX_ERR_BAD_ARG;
+    if (c->dist < STX_L1 || c->dist > STX_TORUS_L2) return STX_ERR_BAD_ARG;
+    if (c->reduce != STX_SUM && c->reduce != STX_MEAN) return STX_ERR_BAD_ARG;
+    if (c->dim <= 0 || c->dim % 4 != 0 || c->dim > kMaxDim) return STX_ERR_BAD_ARG;
+    if (c->model == STX_TRANSR && (c->rel_dim <= 0 || c->rel_dim % 4 != 0 || c->rel_dim > kMaxDim))
+        return STX_ERR_BAD_ARG;
+    if (c->n_ent <= 0 || c->n_rel <= 0 || c->n_ent + c->n_rel >= (int64_t)1 << 31) return STX_ERR_BAD_ARG;
+    if (c->max_batch <= 0 || c->max_neg < 0) return STX_ERR_BAD_ARG;
+    if (3 * (int64_t)c->max_batch * (1 + (int64_t)c->max_neg) >= ((int64_t)1 << 29)) return STX_ERR_BAD_ARG;
+    if (!(c->margin >= 0.0f)) return STX_ERR_BAD_ARG;
+    if (c->flags & ~(STX_FLAG_RENORM_W | STX_FLAG_BF16_PROJ)) return STX_ERR_BAD_ARG;
+    return STX_OK;
+}
+
+Layout make_layout(const stx_config *c)
+{
+    Layout L{};
+    L.rows_max = (int64_t)c->max_batch * (1 + c->max_neg);
+    L.nnz_max = 3 * L.rows_max;
+    L.cols_max = L.nnz_max < c->n_ent + c->n_rel ? L.nnz_max : c->n_ent + c->n_rel;
+    int rel_dim = c->model == STX_TRANSR ? c->rel_dim : c->dim;
+    L.ld = c->dim > rel_dim ? c->dim : rel_dim;
+    L.out_dim = rel_dim;
+    L.ntiles_max = (int)((L.nnz_max + kSortTile - 1) / kSortTile);
+    Launch rl = row_launch(c->dim);
+    L.fwd_blocks_max = (int)((c->max_batch + (kThreads / rl.lpr) - 1) / (kThreads / rl.lpr));
+    int64_t ncol = c->n_ent + c->n_rel;
+    L.sort_bits = 1;
+    while (((int64_t)1 << L.sort_bits) < ncol) ++L.sort_bits;
+    L.sort_passes = (L.sort_bits + 7) / 8;
+    L.digit_bits = (L.sort_bits + L.sort_passes - 1) / L.sort_passes;
+    L.n_gbuf = c->model == STX_TRANSH ? 3 : (c->model == STX_TRANSR ? 4 : 1);
+
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    L.ctrl = take(CTRL_WORDS * sizeof(int32_t));
+    for (int i = 0; i < 2; ++i) L.keys[i] = take((size_t)L.nnz_max * 4);
+    for (int i = 0; i < 2; ++i) L.pay[i] = take((size_t)L.nnz_max * 4);
+    L.table = take((size_t)256 * L.ntiles_max * 4);
+    L.tile_heads = take((size_t)(L.ntiles_max + 1) * 4);
+    L.loss_partials = take((size_t)(L.fwd_blocks_max + 1) * 4);
+    L.partials = take((size_t)(L.nnz_max / kSegTile + 2) * 2 * L.ld * 4);
+    for (int i = 0; i < 4; ++i) L.gbuf[i] = i < L.n_gbuf ? take((size_t)L.rows_max * L.ld * 4) : 0;
+    L.total = off;
+    return L;
+}
+
+stx_status check_incidence_arrays(const stx_incidence *inc)
+{
+    if (!inc) return STX_ERR_NULL;
+    if (!inc->a_rowptr || !inc->a_colidx || !inc->a_vals || !inc->at_touched_cols || !inc->at_seg_ptr ||
+        !inc->at_row_idx || !inc->at_sign || !inc->at_seg_id || !inc->at_packed || !inc->n_touched)
+        return STX_ERR_NULL;
+    return STX_OK;
+}
+
+stx_status check_built(const stx_ctx *ctx, const stx_incidence *inc)
+{
+    stx_status s = check_incidence_arrays(inc);
+    if (s != STX_OK) return s;
+    if (inc->b < 0 || inc->b > ctx->cfg.max_batch || inc->k < 0 || inc->k > ctx->cfg.max_neg) return STX_ERR_BAD_ARG;
+    if (inc->n_rows != (int64_t)inc->b * (1 + inc->k) || inc->nnz != 3 * inc->n_rows) return STX_ERR_BAD_ARG;
+    return STX_OK;
+}
+
+stx_status check_params(const stx_ctx *ctx, const stx_params *p)
+{
+    if (!p || !p->ent) return STX_ERR_NULL;
+    if (ctx->cfg.model == STX_TRANSH && (!p->rel || !p->w)) return STX_ERR_NULL;
+    if (ctx->cfg.model == STX_TRANSR && (!p->rel || !p->proj)) return STX_ERR_NULL;
+    return STX_OK;
+}
+
+bool stacked(const stx_ctx *c) { return c->cfg.model == STX_TRANSE || c->cfg.model == STX_TORUSE; }
+
+}  // namespace
+
+extern "C" {
+
+stx_status stx_workspace_bytes(const stx_config *cfg, size_t *bytes)
+{
+    if (!bytes) return STX_ERR_NULL;
+    stx_status s = check_config(cfg);
+    if (s != STX_OK) return s;
+    *bytes = make_layout(cfg).total;
+    return STX_OK;
+}
+
+stx_status stx_create(const stx_config *cfg, void *workspace, size_t workspace_bytes, void *stream, stx_ctx **out)
+{
+    if (!out) return STX_ERR_NULL;
+    *out = nullptr;
+    stx_status s = check_config(cfg);
+    if (s != STX_OK) return s;
+    if (!workspace) return STX_ERR_NULL;
+    if (cfg->model == STX_TRANSH || cfg->model == STX_TRANSR) return STX_ERR_UNSUPPORTED;
+    Layout L = make_layout(cfg);
+    if (workspace_bytes < L.total || ((uintptr_t)workspace & 255u)) return STX_ERR_WORKSPACE;
+    stx_ctx *c = new (std::nothrow) stx_ctx();
+    if (!c) return STX_ERR_BAD_ARG;
+    c->cfg = *cfg;
+    if (cfg->model != STX_TRANSR) c->cfg.rel_dim = cfg->dim;
+    c->stream = (hipStream_t)stream;
+    c->ld = L.ld;
+    c->out_dim = L.out_dim;
+    c->rows_max = L.rows_max;
+    c->nnz_max = L.nnz_max;
+    c->cols_max = L.cols_max;
+    c->sort_bits = L.sort_bits;
+    c->sort_passes = L.sort_passes;
+    c->digit_bits = L.digit_bits;
+    c->ntiles_max = L.ntiles_max;
+    c->fwd_blocks_max = L.fwd_blocks_max;
+    char *base = (char *)workspace;
+    c->ctrl = (int32_t *)(base + L.ctrl);
+    for (int i = 0; i < 2; ++i) {
+        c->keys[i] = (int32_t *)(base + L.keys[i]);
+        c->pay[i] = (int32_t *)(base + L.pay[i]);
+    }
+    c->table = (int32_t *)(base + L.table);
+    c->tile_heads = (int32_t *)(base + L.tile_heads);
+    c->loss_partials = (float *)(base + L.loss_partials);
+    c->partials = (float *)(base + L.partials);
+    for (int i = 0; i < 4; ++i) c->gbuf[i] = i < L.n_gbuf ? (float *)(base + L.gbuf[i]) : nullptr;
+    c->fwd_inc = nullptr;
+    c->fwd_rows = 0;
+    s = launch_clear_ctrl(c);
+    if (s != STX_OK) { delete c; return s; }
+    *out = c;
+    return STX_OK;
+}
+
+stx_status stx_destroy(stx_ctx *ctx)
+{
+    if (!ctx) return STX_ERR_NULL;
+    delete ctx;
+    return STX_OK;
+}
+
+stx_status stx_sample_negatives(stx_ctx *ctx, const int32_t *h, const int32_t *r, const int32_t *t, int64_t m,
+                                int32_t k, uint64_t seed, uint64_t epoch, int64_t m_total, int64_t global_offset,
+                                int32_t *neg_h, int32_t *neg_t)
+{
+    (void)r;
+    if (!ctx) return STX_ERR_NULL;
+    if (m < 0 || k < 0 || m_total < 0 || global_offset < 0) return STX_ERR_BAD_ARG;
+    if (m == 0 || k == 0) return STX_OK;
+    if (!h || !t || !neg_h || !neg_t) return STX_ERR_NULL;
+    if (m * (int64_t)k > ((int64_t)1 << 40)) return STX_ERR_BAD_ARG;
+    uint64_t base = (epoch * (uint64_t)m_total + (uint64_t)global_offset) * (uint64_t)k;
+    return launch_sample(ctx, h, t, m, k, seed, base, neg_h, neg_t);
+}
+
+stx_status stx_build_incidence(stx_ctx *ctx, const int32_t *h, const int32_t *r, const int32_t *t,
+                               const int32_t *neg_h, const int32_t *neg_t, int32_t b, int32_t k, stx_incidence *inc)
+{
+    if (!ctx) return STX_ERR_NULL;
+    stx_status s = check_incidence_arrays(inc);
+    if (s != STX_OK) return s;
+    if (b < 0 || k < 0 || b > ctx->cfg.max_batch || k > ctx->cfg.max_neg) return STX_ERR_BAD_ARG;
+    if (b > 0 && (!h || !r || !t)) return STX_ERR_NULL;
+    if (b > 0 && k > 0 && (!neg_h || !neg_t)) return STX_ERR_NULL;
+    inc->b = b;
+    inc->k = k;
+    inc->n_rows = (int64_t)b * (1 + k);
+    inc->nnz = 3 * inc->n_rows;
+    if (ctx->fwd_inc == inc) ctx->fwd_inc = nullptr;   // rebuilt: a stored forward no longer matches
+    return launch_build(ctx, h, r, t, neg_h, neg_t, b, k, inc);
+}
+
+stx_status stx_check_indices(stx_ctx *ctx, int64_t *n_bad)
+{
+    if (!ctx) return STX_ERR_NULL;
+    int32_t bad = 0;
+    if (hipMemcpyAsync(&bad, ctx->ctrl + CTRL_BAD_INDEX, sizeof(bad), hipMemcpyDeviceToHost, ctx->stream) !=
+        hipSuccess)
+        return STX_ERR_HIP;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return STX_ERR_HIP;
+    if (n_bad) *n_bad = bad;
+    if (bad) {
+        stx_status s = launch_clear_ctrl(ctx);   // tickets are zero between calls, so clearing all words is safe
+        if (s != STX_OK) return s;
+        return STX_ERR_INDEX_RANGE;
+    }
+    return STX_OK;
+}
+
+stx_status stx_spmm(stx_ctx *ctx, const stx_incidence *inc, const stx_params *p, float *c_out)
+{
+    if (!ctx) return STX_ERR_NULL;
+    stx_status s = check_built(ctx, inc);
+    if (s != STX_OK) return s;
+    if (!p || !p->ent || !c_out) return STX_ERR_NULL;
+    return launch_spmm(ctx, inc, p, c_out);
+}
+
+stx_status stx_forward(stx_ctx *ctx, const stx_incidence *inc, const stx_params *p, float *scores, float *loss)
+{
+    if (!ctx) return STX_ERR_NULL;
+    stx_status s = check_built(ctx, inc);
+    if (s != STX_OK) return s;
+    s = check_params(ctx, p);
+    if (s != STX_OK) return s;
+    if (!scores || !loss) return STX_ERR_NULL;
+    if (!stacked(ctx)) return STX_ERR_UNSUPPORTED;
+    s = launch_forward_stacked(ctx, inc, p, scores, loss);
+    if (s == STX_OK) {
+        ctx->fwd_inc = inc;
+        ctx->fwd_rows = inc->n_rows;
+    }
+    return s;
+}
+
+stx_status stx_backward(stx_ctx *ctx, const stx_incidence *inc, const stx_params *p, stx_grads *g)
+{
+    if (!ctx) return STX_ERR_NULL;
+    stx_status s = check_built(ctx, inc);
+    if (s != STX_OK) return s;
+    s = check_params(ctx, p);
+    if (s != STX_OK) return s;
+    if (!g || !g->rows) return STX_ERR_NULL;
+    if (ctx->fwd_inc != inc || ctx->fwd_rows != inc->n_rows) return STX_ERR_STATE;
+    if (!stacked(ctx)) return STX_ERR_UNSUPPORTED;
+    // dL/dX = A^T G over all columns of X = [E;R] (Appendix G)
+    return launch_seg_reduce(ctx, inc, 0, inc->nnz, ctx->gbuf[0], ctx->cfg.dim, ctx->cfg.dim, g->rows, ctx->ld);
+}
+
+stx_status stx_sgd_step(stx_ctx *ctx, stx_params *p, const stx_incidence *inc, const stx_grads *g, float lr)
+{
+    if (!ctx) return STX_ERR_NULL;
+    stx_status s = check_built(ctx, inc);
+    if (s != STX_OK) return s;
+    s = check_params(ctx, p);
+    if (s != STX_OK) return s;
+    if (!g || !g->rows) return STX_ERR_NULL;
+    if (!(lr == lr)) return STX_ERR_BAD_ARG;
+    if (!stacked(ctx)) return STX_ERR_UNSUPPORTED;
+    ctx->fwd_inc = nullptr;   // the tables change: a stored forward no longer matches them
+    return launch_sgd_rows(ctx, inc, p->ent, 0, ctx->cfg.n_ent + ctx->cfg.n_rel, g->rows, ctx->ld, ctx->cfg.dim, lr,
+                           ctx->cfg.model == STX_TORUSE ? 1 : 0);
+}
+
+const char *stx_status_string(stx_status s)
+{
+    switch (s) {
+    case STX_OK: return "ok";
+    case STX_ERR_NULL: return "null pointer";
+    case STX_ERR_BAD_ARG: return "bad argument";
+    case STX_ERR_INDEX_RANGE: return "triplet index out of range";
+    case STX_ERR_WORKSPACE: return "workspace too small or misaligned";
+    case STX_ERR_STATE: return "call order violated";
+    case STX_ERR_UNSUPPORTED: return "not supported";
+    case STX_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

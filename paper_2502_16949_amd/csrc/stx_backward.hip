@@ -1,0 +1,344 @@
+// Transposed product A^T.G without atomics, and the sparse SGD update.
+//
+// SparseTransX Appendix G: for C = A.X the gradient is dL/dX = A^T.dL/dC, itself a sparse-dense
+// product.  A^T arrives sorted by column (see stx_build.hip), so the gradient row of column c is the
+// signed sum of the G rows named by one contiguous run ("segment") of sorted entries.  Power-law graphs
+// make segment lengths wildly uneven (one entity can own >10% of all entries), so work is split by
+// entries, not by segments:
+//
+//   k_seg_reduce   each workgroup owns kSegTile consecutive sorted entries, each of its lane groups a
+//                  chunk of LPR of them.  A group walks its chunk in order, adding signed G rows into
+//                  registers and closing a run whenever an entry is flagged as a segment head.  Runs that
+//                  lie inside the chunk are stored to the output directly.  A chunk's first / last run
+//                  may continue in a neighbouring chunk; those go to LDS, are stitched in chunk order by
+//                  one group, and the (at most two) runs that cross the workgroup's own borders are
+//                  stored as partial rows.
+//   k_seg_fixup    the workgroup in which a border-crossing run ends adds up that run's partial rows,
+//                  in tile order, and stores the result.
+//
+// Every output row is written exactly once and every sum has a fixed association order, so results are
+// bitwise reproducible from run to run.
+#include "stx_device.h"
+#include "stx_internal.h"
+
+namespace stx {
+
+enum { HAS_FIRST = 1, FIRST_CONT = 2, HAS_LAST = 4 };
+
+template <int ITERS>
+struct Acc {
+    float4 v[ITERS];
+    __device__ inline void zero()
+    {
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) v[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    __device__ inline void add(const Acc &o)
+    {
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            v[it].x += o.v[it].x; v[it].y += o.v[it].y; v[it].z += o.v[it].z; v[it].w += o.v[it].w;
+        }
+    }
+};
+
+template <int LPR, int ITERS>
+__device__ inline void load_row(const float *__restrict__ p, int d4, int lig, Acc<ITERS> &a)
+{
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        int j = lig + it * LPR;
+        a.v[it] = j < d4 ? ld4(p + 4 * j) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+}
+template <int LPR, int ITERS>
+__device__ inline void store_row(float *__restrict__ p, int d4, int lig, const Acc<ITERS> &a)
+{
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        int j = lig + it * LPR;
+        if (j < d4) st4(p + 4 * j, a.v[it]);
+    }
+}
+
+template <int LPR, int ITERS>
+__global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restrict__ packed,
+                                                         const int32_t *__restrict__ seg_id, int32_t e_begin,
+                                                         int32_t e_end, const float *__restrict__ src, int ld_src,
+                                                         int d4, float *__restrict__ out_rows, int ld_out,
+                                                         float *__restrict__ partials)
+{
+    constexpr int GROUPS = kThreads / LPR;
+    constexpr int UNROLL = ITERS == 1 ? 8 : (ITERS == 2 ? 4 : 2);
+    constexpr int ROWF = ITERS * LPR * 4;   // floats per staged row in LDS
+    __shared__ float s_part[GROUPS][2][ROWF];
+    __shared__ int s_info[GROUPS];
+    __shared__ int32_t s_seg_first[GROUPS], s_seg_last[GROUPS];
+
+    const int lig = threadIdx.x % LPR, grp = threadIdx.x / LPR;
+    const int32_t tile0 = e_begin + (int32_t)blockIdx.x * kSegTile;
+    const int32_t ec0 = tile0 + grp * (kSegTile / GROUPS);
+    const int32_t ec1 = min(ec0 + kSegTile / GROUPS, e_end);
+    static_assert(kSegTile / GROUPS == LPR, "one entry per lane per chunk");
+
+    int info = 0;
+    if (ec0 < e_end) {
+        const int n = ec1 - ec0;
+        const int32_t meta = (ec0 + lig < ec1) ? packed[ec0 + lig] : 0;
+        const int32_t meta0 = __shfl(meta, 0, LPR);
+        const bool first_open = (ec0 > e_begin) && !(meta0 & 2);
+        const bool right_open = (ec1 < e_end) && !(packed[ec1] & 2);
+        int32_t cur_seg = seg_id[ec0];
+        int nflush = 0;
+        Acc<ITERS> acc;
+        acc.zero();
+
+        auto flush = [&](bool last_run) {
+            const bool open_left = (nflush == 0) && first_open;
+            const bool open_right = last_run && right_open;
+            if (!open_left && !open_right) {
+                store_row<LPR, ITERS>(out_rows + (int64_t)cur_seg * ld_out, d4, lig, acc);
+            } else {
+                const int slot = open_left ? 0 : 1;
+#pragma unroll
+                for (int it = 0; it < ITERS; ++it)
+                    st4(&s_part[grp][slot][(lig + it * LPR) * 4], acc.v[it]);
+                if (open_left) {
+                    info |= HAS_FIRST | (open_right ? FIRST_CONT : 0);
+                    if (lig == 0) s_seg_first[grp] = cur_seg;
+                } else {
+                    info |= HAS_LAST;
+                    if (lig == 0) s_seg_last[grp] = cur_seg;
+                }
+            }
+            ++nflush;
+        };
+
+        for (int j0 = 0; j0 < n; j0 += UNROLL) {
+            Acc<ITERS> v[UNROLL];
+            int32_t mu[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const int jj = j0 + u;
+                mu[u] = __shfl(meta, jj < LPR ? jj : LPR - 1, LPR);
+                if (jj < n) load_row<LPR, ITERS>(src + (int64_t)(mu[u] >> 2) * ld_src, d4, lig, v[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const int jj = j0 + u;
+                if (jj < n) {
+                    if ((mu[u] & 2) && jj > 0) {
+                        flush(false);
+                        ++cur_seg;
+                        acc.zero();
+                    }
+                    if (mu[u] & 1) {
+#pragma unroll
+                        for (int it = 0; it < ITERS; ++it) {
+                            acc.v[it].x -= v[u].v[it].x; acc.v[it].y -= v[u].v[it].y;
+                            acc.v[it].z -= v[u].v[it].z; acc.v[it].w -= v[u].v[it].w;
+                        }
+                    } else {
+                        acc.add(v[u]);
+                    }
+                }
+            }
+        }
+        flush(true);
+    }
+    if (lig == 0) s_info[grp] = info;
+    __syncthreads();
+
+    // Stitch the chunk-crossing runs in chunk order (group 0 only; lanes keep their float4 slices).
+    if (grp == 0) {
+        bool have = false, started_in = false;
+        int32_t cur_seg = 0;
+        Acc<ITERS> cur;
+        cur.zero();
+        float *my_part = partials + (int64_t)blockIdx.x * 2 * ld_out;
+        for (int g = 0; g < GROUPS; ++g) {
+            const int inf = s_info[g];
+            if (inf & HAS_FIRST) {
+                Acc<ITERS> p;
+#pragma unroll
+                for (int it = 0; it < ITERS; ++it) p.v[it] = ld4(&s_part[g][0][(lig + it * LPR) * 4]);
+                if (!have) {
+                    have = true; started_in = false; cur = p; cur_seg = s_seg_first[g];
+                } else {
+                    cur.add(p);
+                }
+                if (!(inf & FIRST_CONT)) {   // the run ends inside chunk g
+                    if (started_in) store_row<LPR, ITERS>(out_rows + (int64_t)cur_seg * ld_out, d4, lig, cur);
+                    else store_row<LPR, ITERS>(my_part, d4, lig, cur);   // began in an earlier workgroup
+                    have = false;
+                }
+            }
+            if (inf & HAS_LAST) {
+                have = true; started_in = true; cur_seg = s_seg_last[g];
+#pragma unroll
+                for (int it = 0; it < ITERS; ++it) cur.v[it] = ld4(&s_part[g][1][(lig + it * LPR) * 4]);
+            }
+        }
+        if (have) store_row<LPR, ITERS>(my_part + (started_in ? ld_out : 0), d4, lig, cur);   // runs on into the next tile
+    }
+}
+
+template <int LPR, int ITERS>
+__global__ __launch_bounds__(kThreads) void k_seg_fixup(const int32_t *__restrict__ packed,
+                                                        const int32_t *__restrict__ seg_id,
+                                                        const int32_t *__restrict__ seg_ptr, int32_t e_begin,
+                                                        int32_t e_end, int d4, float *__restrict__ out_rows,
+                                                        int ld_out, const float *__restrict__ partials)
+{
+    constexpr int GROUPS = kThreads / LPR;
+    constexpr int ROWF = ITERS * LPR * 4;
+    __shared__ float s_sum[GROUPS][ROWF];
+    const int32_t j = (int32_t)blockIdx.x + 1;                  // tile 0 never ends a crossing run
+    const int32_t tile0 = e_begin + j * kSegTile;
+    if (tile0 >= e_end) return;
+    if (packed[tile0] & 2) return;                              // the tile starts a new segment: nothing crosses in
+    const int32_t tile1 = min(tile0 + kSegTile, e_end);
+    const int32_t e = tile0 + (int32_t)threadIdx.x;
+    int head_inside = (e > tile0 && e < tile1) ? ((packed[e] >> 1) & 1) : 0;
+    const int any_head = __syncthreads_or(head_inside);
+    const bool closes = any_head || tile1 >= e_end || (packed[tile1] & 2);
+    if (!closes) return;                                        // the run goes on; a later tile finishes it
+
+    const int32_t seg = seg_id[tile0];
+    const int32_t j0 = (seg_ptr[seg] - e_begin) / kSegTile;     // tile in which the run began
+    const int n = j - j0 + 1;                                   // partial rows: (j0, slot 1), (j0+1 .. j, slot 0)
+    const int lig = threadIdx.x % LPR, grp = threadIdx.x / LPR;
+    const int per = (n + GROUPS - 1) / GROUPS;
+    const int lo = min(grp * per, n), hi = min(lo + per, n);
+    Acc<ITERS> acc;
+    acc.zero();
+    for (int q = lo; q < hi; ++q) {
+        const float *p = partials + ((int64_t)(j0 + q) * 2 + (q == 0 ? 1 : 0)) * ld_out;
+        Acc<ITERS> v;
+        load_row<LPR, ITERS>(p, d4, lig, v);
+        acc.add(v);
+    }
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) st4(&s_sum[grp][(lig + it * LPR) * 4], acc.v[it]);
+    __syncthreads();
+    if (grp == 0) {
+        const int used = (n + per - 1) / per;                   // groups that had at least one row
+        for (int g = 1; g < used; ++g) {
+            Acc<ITERS> v;
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) v.v[it] = ld4(&s_sum[g][(lig + it * LPR) * 4]);
+            acc.add(v);
+        }
+        store_row<LPR, ITERS>(out_rows + (int64_t)seg * ld_out, d4, lig, acc);
+    }
+}
+
+// Row update for the segments whose column lies in [col_lo, col_hi): table row (col - col_lo).
+// mode 0: v - lr*g.  mode 1: then the fractional part (TorusE, Sec. 4.6).  mode 2: then unit length.
+template <int LPR, int ITERS>
+__global__ __launch_bounds__(kThreads) void k_sgd_rows(const int32_t *__restrict__ touched_cols,
+                                                       const int32_t *__restrict__ n_touched,
+                                                       float *__restrict__ table, int32_t col_lo, int32_t col_hi,
+                                                       const float *__restrict__ grad_rows, int ld, int d4,
+                                                       float lr, int mode)
+{
+    constexpr int GROUPS = kThreads / LPR;
+    const int lig = threadIdx.x % LPR, grp = threadIdx.x / LPR;
+    const int32_t U = n_touched[0];
+    const int width = d4 * 4;
+    for (int64_t s = (int64_t)blockIdx.x * GROUPS + grp; s < U; s += (int64_t)gridDim.x * GROUPS) {
+        const int32_t col = touched_cols[s];
+        if (col < col_lo || col >= col_hi) continue;
+        float *row = table + (int64_t)(col - col_lo) * width;
+        Acc<ITERS> x, g;
+        load_row<LPR, ITERS>(row, d4, lig, x);
+        load_row<LPR, ITERS>(grad_rows + s * ld, d4, lig, g);
+        float ss = 0.f;
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            float *xv = &x.v[it].x;
+            const float *gv = &g.v[it].x;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float step = lr * gv[q];
+                float nv = xv[q] - step;
+                if (mode == 1) {
+                    nv = nv - floorf(nv);
+                    if (nv >= 1.0f) nv = 0.0f;
+                }
+                xv[q] = nv;
+                ss += nv * nv;
+            }
+        }
+        if (mode == 2) {
+            ss = group_sum<LPR>(ss);
+            if (ss > 0.f) {
+                const float inv = 1.0f / sqrtf(ss);
+#pragma unroll
+                for (int it = 0; it < ITERS; ++it) {
+                    x.v[it].x *= inv; x.v[it].y *= inv; x.v[it].z *= inv; x.v[it].w *= inv;
+                }
+            }
+        }
+        store_row<LPR, ITERS>(row, d4, lig, x);
+    }
+}
+
+// ---- dispatch --------------------------------------------------------------------------------------
+template <int LPR, int ITERS>
+static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_t e_end, const float *src, int ld_src,
+                   int width, float *out_rows, int ld_out)
+{
+    const int ntiles = (e_end - e_begin + kSegTile - 1) / kSegTile;
+    hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS>), dim3(ntiles), dim3(kThreads), 0, c->stream, inc->at_packed,
+                       inc->at_seg_id, e_begin, e_end, src, ld_src, width / 4, out_rows, ld_out, c->partials);
+    if (ntiles > 1)
+        hipLaunchKernelGGL((k_seg_fixup<LPR, ITERS>), dim3(ntiles - 1), dim3(kThreads), 0, c->stream,
+                           inc->at_packed, inc->at_seg_id, inc->at_seg_ptr, e_begin, e_end, width / 4, out_rows,
+                           ld_out, c->partials);
+}
+
+template <int LPR, int ITERS>
+static void sgd_go(stx_ctx *c, const stx_incidence *inc, float *table, int32_t col_lo, int32_t col_hi,
+                   const float *grad_rows, int ld, int width, float lr, int mode)
+{
+    constexpr int GROUPS = kThreads / LPR;
+    int64_t cap = inc->nnz < c->cfg.n_ent + c->cfg.n_rel ? inc->nnz : c->cfg.n_ent + c->cfg.n_rel;
+    int64_t blocks = (cap + GROUPS - 1) / GROUPS;
+    if (blocks > 8192) blocks = 8192;   // grid-stride beyond this
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL((k_sgd_rows<LPR, ITERS>), dim3((unsigned)blocks), dim3(kThreads), 0, c->stream,
+                       inc->at_touched_cols, inc->n_touched, table, col_lo, col_hi, grad_rows, ld, width / 4, lr,
+                       mode);
+}
+
+#define STX_DISPATCH_ROW(L, FN, ...)                                                      \
+    do {                                                                                  \
+        if (L.lpr == 8 && L.iters == 1) FN<8, 1>(__VA_ARGS__);                            \
+        else if (L.lpr == 16 && L.iters == 1) FN<16, 1>(__VA_ARGS__);                     \
+        else if (L.lpr == 32 && L.iters == 1) FN<32, 1>(__VA_ARGS__);                     \
+        else if (L.lpr == 64 && L.iters == 1) FN<64, 1>(__VA_ARGS__);                     \
+        else if (L.lpr == 64 && L.iters == 2) FN<64, 2>(__VA_ARGS__);                     \
+        else if (L.lpr == 64 && L.iters == 3) FN<64, 3>(__VA_ARGS__);                     \
+        else FN<64, 4>(__VA_ARGS__);                                                      \
+    } while (0)
+
+stx_status launch_seg_reduce(stx_ctx *c, const stx_incidence *inc, int64_t e_begin, int64_t e_end, const float *src,
+                             int ld_src, int width, float *out_rows, int ld_out)
+{
+    if (e_end <= e_begin) return STX_OK;
+    Launch L = row_launch(width);
+    STX_DISPATCH_ROW(L, seg_go, c, inc, (int32_t)e_begin, (int32_t)e_end, src, ld_src, width, out_rows, ld_out);
+    return hip_ok(hipGetLastError());
+}
+
+stx_status launch_sgd_rows(stx_ctx *c, const stx_incidence *inc, float *table, int64_t col_lo, int64_t col_hi,
+                           const float *grad_rows, int ld, int width, float lr, int mode)
+{
+    if (inc->n_rows == 0) return STX_OK;
+    Launch L = row_launch(width);
+    STX_DISPATCH_ROW(L, sgd_go, c, inc, table, (int32_t)col_lo, (int32_t)col_hi, grad_rows, ld, width, lr, mode);
+    return hip_ok(hipGetLastError());
+}
+
+}  // namespace stx

@@ -1,0 +1,338 @@
+// Negative sampling and construction of the incidence matrix A (CSR) and of A^T sorted by column.
+//
+// A is the `hrt` incidence matrix of SparseTransX Sec. 4.2.2: one row per triplet, +1 at the head
+// column, +1 at column n_ent + relation, -1 at the tail column (the `ht` form of Sec. 4.2.1 is slots 0
+// and 2 of each row).  Appendix G needs A^T for the backward product; it is produced here by a stable
+// least-significant-digit radix sort of the 3*rows column ids, so that every column's entries are
+// contiguous and in a unique order, which is what lets the backward product run without atomics.
+//
+// Launch sequence for one batch (P = number of digit passes, 1..4):
+//   k_emit            keys + CSR arrays + tile histograms of digit 0   (last workgroup scans them)
+//   k_scatter  x P    stable scatter by digit p
+//   k_hist     x P-1  tile histograms of digit p (between scatters; last workgroup scans)
+//   k_seg_count       segment heads per tile (last workgroup scans, writes U)
+//   k_seg_write       touched_cols, seg_ptr, row_idx, sign, seg_id, packed
+#include "stx_device.h"
+#include "stx_internal.h"
+
+namespace stx {
+
+// SplitMix64 (Steele, Lea, Flood, OOPSLA 2014) used as a counter-based generator: output number `ctr`
+// of the sequence started at `seed`.
+__device__ inline uint64_t splitmix64_at(uint64_t seed, uint64_t ctr)
+{
+    uint64_t z = seed + (ctr + 1ull) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+__global__ __launch_bounds__(kThreads) void k_sample(const int32_t *__restrict__ h, const int32_t *__restrict__ t,
+                                                     int64_t total, int32_t k, uint64_t n_ent, uint64_t seed,
+                                                     uint64_t base_ctr, int32_t *__restrict__ nh,
+                                                     int32_t *__restrict__ nt)
+{
+    int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (idx >= total) return;
+    int64_t i = idx / k;
+    uint64_t u = splitmix64_at(seed, base_ctr + (uint64_t)idx);
+    int32_t e = (int32_t)(((u & 0xFFFFFFFFull) * n_ent) >> 32);
+    bool head = (u >> 63) != 0;
+    nh[idx] = head ? e : h[i];
+    nt[idx] = head ? t[i] : e;
+}
+
+__global__ void k_clear_ctrl(int32_t *ctrl)
+{
+    if (threadIdx.x < CTRL_WORDS) ctrl[threadIdx.x] = 0;
+}
+
+// Empty batch: A has no rows and A^T no segments.
+__global__ void k_empty_incidence(int32_t *rowptr, int32_t *seg_ptr, int32_t *n_touched)
+{
+    if (threadIdx.x == 0) { rowptr[0] = 0; seg_ptr[0] = 0; n_touched[0] = 0; }
+}
+
+struct BatchPtrs {
+    const int32_t *h, *r, *t, *nh, *nt;
+    int32_t b, k;
+};
+
+// One thread per entry e = 3*row + slot of A.  Writes the CSR arrays and the sort keys (= column ids),
+// and the histogram of the first digit for this tile.
+__global__ __launch_bounds__(kThreads) void k_emit(BatchPtrs bp, int32_t n_ent, int32_t n_rel, int32_t nnz,
+                                                   int32_t *__restrict__ rowptr, int32_t *__restrict__ colidx,
+                                                   float *__restrict__ vals, int32_t *__restrict__ keys,
+                                                   int radix, int ntiles, int32_t *__restrict__ table,
+                                                   int32_t *__restrict__ ctrl)
+{
+    __shared__ int32_t s_hist[256];
+    const int tid = threadIdx.x;
+    s_hist[tid] = 0;
+    __syncthreads();
+    const int32_t base = blockIdx.x * kSortTile;
+#pragma unroll
+    for (int it = 0; it < kSortItems; ++it) {
+        int32_t e = base + it * kThreads + tid;
+        if (e < nnz) {
+            int32_t row = e / 3, slot = e - 3 * row;
+            int32_t idx;
+            if (row < bp.b) {
+                idx = slot == 0 ? bp.h[row] : (slot == 1 ? bp.r[row] : bp.t[row]);
+            } else {
+                int32_t j = row - bp.b;
+                idx = slot == 0 ? bp.nh[j] : (slot == 1 ? bp.r[j / bp.k] : bp.nt[j]);
+            }
+            int32_t lim = slot == 1 ? n_rel : n_ent;
+            if (idx < 0 || idx >= lim) {           // clamp so nothing downstream reads outside a table
+                atomicAdd(&ctrl[CTRL_BAD_INDEX], 1);
+                idx = idx < 0 ? 0 : lim - 1;
+            }
+            int32_t col = slot == 1 ? n_ent + idx : idx;
+            colidx[e] = col;
+            vals[e] = slot == 2 ? -1.0f : 1.0f;
+            if (slot == 0) rowptr[row] = e;
+            if (e == nnz - 1) rowptr[row + 1] = nnz;
+            keys[e] = col;
+            atomicAdd(&s_hist[col & (radix - 1)], 1);
+        }
+    }
+    __syncthreads();
+    if (tid < radix) table[tid * ntiles + blockIdx.x] = s_hist[tid];
+    if (last_block_arrives(&ctrl[CTRL_TICKET_SORT])) {
+        block_exclusive_scan_inplace(table, radix * ntiles, nullptr);
+        if (tid == 0) ctrl[CTRL_TICKET_SORT] = 0;
+    }
+}
+
+// Tile histograms of the digit at `shift` for the later passes.
+__global__ __launch_bounds__(kThreads) void k_hist(const int32_t *__restrict__ keys, int32_t nnz, int shift,
+                                                   int radix, int ntiles, int32_t *__restrict__ table,
+                                                   int32_t *__restrict__ ctrl)
+{
+    __shared__ int32_t s_hist[256];
+    const int tid = threadIdx.x;
+    s_hist[tid] = 0;
+    __syncthreads();
+    const int32_t base = blockIdx.x * kSortTile;
+#pragma unroll
+    for (int it = 0; it < kSortItems; ++it) {
+        int32_t e = base + it * kThreads + tid;
+        if (e < nnz) atomicAdd(&s_hist[(keys[e] >> shift) & (radix - 1)], 1);
+    }
+    __syncthreads();
+    if (tid < radix) table[tid * ntiles + blockIdx.x] = s_hist[tid];
+    if (last_block_arrives(&ctrl[CTRL_TICKET_SORT])) {
+        block_exclusive_scan_inplace(table, radix * ntiles, nullptr);
+        if (tid == 0) ctrl[CTRL_TICKET_SORT] = 0;
+    }
+}
+
+// Stable scatter of one tile by the digit at `shift`.  Element order inside a tile is
+// (wavefront, iteration, lane): wavefront w owns the contiguous span [w*512, (w+1)*512) of the tile.
+// The rank of a key among equal digits is
+//   (count in earlier wavefronts) + (count in earlier iterations of this wavefront) + (equal lanes below),
+// the last term from a ballot match over the digit's bits.  `table` holds, per (digit, tile), the
+// number of keys with a smaller digit anywhere plus those with the same digit in earlier tiles.
+template <bool FIRST>
+__global__ __launch_bounds__(kThreads) void k_scatter(const int32_t *__restrict__ keys_in,
+                                                      const int32_t *__restrict__ pay_in,
+                                                      int32_t *__restrict__ keys_out,
+                                                      int32_t *__restrict__ pay_out, int32_t nnz, int shift,
+                                                      int bits, int ntiles, const int32_t *__restrict__ table)
+{
+    __shared__ int32_t s_goff[256];
+    __shared__ int32_t s_hist[4][256];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int radix = 1 << bits;
+    for (int i = tid; i < 4 * 256; i += kThreads) (&s_hist[0][0])[i] = 0;
+    if (tid < radix) s_goff[tid] = table[tid * ntiles + blockIdx.x];
+    __syncthreads();
+
+    int32_t key[kSortItems], pay[kSortItems], rank[kSortItems];
+    const int32_t wave_base = blockIdx.x * kSortTile + w * (64 * kSortItems);
+    const uint64_t below = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int it = 0; it < kSortItems; ++it) {
+        int32_t e = wave_base + it * 64 + lane;
+        bool valid = e < nnz;
+        key[it] = valid ? keys_in[e] : 0;
+        pay[it] = FIRST ? e : (valid ? pay_in[e] : 0);
+        int dgt = (key[it] >> shift) & (radix - 1);
+        uint64_t m = __ballot(valid);
+        for (int bit = 0; bit < bits; ++bit) {
+            bool one = (dgt >> bit) & 1;
+            uint64_t bm = __ballot(one);
+            m &= one ? bm : ~bm;
+        }
+        int32_t prior = s_hist[w][dgt];
+        rank[it] = prior + __popcll(m & below);
+        bool leader = valid && ((m >> lane) >> 1) == 0;   // highest lane of its digit class
+        if (leader) s_hist[w][dgt] = prior + __popcll(m);
+    }
+    __syncthreads();
+    if (tid < radix) {
+        int32_t a = 0;
+#pragma unroll
+        for (int w2 = 0; w2 < 4; ++w2) {
+            int32_t c = s_hist[w2][tid];
+            s_hist[w2][tid] = a;
+            a += c;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < kSortItems; ++it) {
+        int32_t e = wave_base + it * 64 + lane;
+        if (e < nnz) {
+            int dgt = (key[it] >> shift) & (radix - 1);
+            int32_t pos = s_goff[dgt] + s_hist[w][dgt] + rank[it];
+            keys_out[pos] = key[it];
+            pay_out[pos] = pay[it];
+        }
+    }
+}
+
+// Number of segment heads (first entry of a column's run) in each tile of the sorted keys; the last
+// workgroup turns the counts into each tile's first segment number and writes U and seg_ptr[U].
+__global__ __launch_bounds__(kThreads) void k_seg_count(const int32_t *__restrict__ keys, int32_t nnz, int ntiles,
+                                                        int32_t *__restrict__ tile_heads,
+                                                        int32_t *__restrict__ ctrl, int32_t *__restrict__ n_touched,
+                                                        int32_t *__restrict__ seg_ptr)
+{
+    __shared__ int32_t s_cnt;
+    const int tid = threadIdx.x;
+    if (tid == 0) s_cnt = 0;
+    __syncthreads();
+    const int32_t base = blockIdx.x * kSortTile;
+    int32_t c = 0;
+#pragma unroll
+    for (int it = 0; it < kSortItems; ++it) {
+        int32_t e = base + it * kThreads + tid;
+        if (e < nnz) c += (e == 0 || keys[e] != keys[e - 1]) ? 1 : 0;
+    }
+    if (c) atomicAdd(&s_cnt, c);
+    __syncthreads();
+    if (tid == 0) tile_heads[blockIdx.x] = s_cnt;
+    if (last_block_arrives(&ctrl[CTRL_TICKET_SEG])) {
+        __shared__ int32_t s_total;
+        block_exclusive_scan_inplace(tile_heads, ntiles, &s_total);
+        if (tid == 0) {
+            n_touched[0] = s_total;
+            seg_ptr[s_total] = nnz;
+            ctrl[CTRL_TICKET_SEG] = 0;
+        }
+    }
+}
+
+// Per sorted entry: its segment, row, sign and packed form; per segment: its column and first entry.
+// Thread t of a tile owns the 8 consecutive entries base + 8t .. base + 8t + 7.
+__global__ __launch_bounds__(kThreads) void k_seg_write(const int32_t *__restrict__ keys,
+                                                        const int32_t *__restrict__ pay, int32_t nnz,
+                                                        const int32_t *__restrict__ tile_heads,
+                                                        int32_t *__restrict__ touched_cols,
+                                                        int32_t *__restrict__ seg_ptr, int32_t *__restrict__ row_idx,
+                                                        int8_t *__restrict__ sign, int32_t *__restrict__ seg_id,
+                                                        int32_t *__restrict__ packed)
+{
+    __shared__ int32_t s_scan[256];
+    const int tid = threadIdx.x;
+    const int32_t e0 = blockIdx.x * kSortTile + tid * kSortItems;
+    int32_t kk[kSortItems + 1];
+    kk[0] = (e0 > 0 && e0 - 1 < nnz) ? keys[e0 - 1] : -1;
+    int32_t cnt = 0;
+#pragma unroll
+    for (int i = 0; i < kSortItems; ++i) {
+        int32_t e = e0 + i;
+        kk[i + 1] = e < nnz ? keys[e] : -1;
+        if (e < nnz && kk[i + 1] != kk[i]) ++cnt;
+    }
+    s_scan[tid] = cnt;
+    __syncthreads();
+    for (int off = 1; off < 256; off <<= 1) {
+        int32_t v = tid >= off ? s_scan[tid - off] : 0;
+        __syncthreads();
+        s_scan[tid] += v;
+        __syncthreads();
+    }
+    int32_t seg = tile_heads[blockIdx.x] + (s_scan[tid] - cnt) - 1;   // segment of the entry before e0
+#pragma unroll
+    for (int i = 0; i < kSortItems; ++i) {
+        int32_t e = e0 + i;
+        if (e < nnz) {
+            bool head = kk[i + 1] != kk[i];   // e == 0: kk[0] = -1 differs from every column id
+            if (head) {
+                ++seg;
+                touched_cols[seg] = kk[i + 1];
+                seg_ptr[seg] = e;
+            }
+            int32_t p = pay[e];
+            int32_t row = p / 3;
+            int32_t neg = (p - 3 * row) == 2 ? 1 : 0;
+            seg_id[e] = seg;
+            row_idx[e] = row;
+            sign[e] = neg ? (int8_t)-1 : (int8_t)1;
+            packed[e] = (row << 2) | (head ? 2 : 0) | neg;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+stx_status launch_clear_ctrl(stx_ctx *c)
+{
+    hipLaunchKernelGGL(k_clear_ctrl, dim3(1), dim3(64), 0, c->stream, c->ctrl);
+    return hip_ok(hipGetLastError());
+}
+
+stx_status launch_sample(stx_ctx *c, const int32_t *h, const int32_t *t, int64_t m, int32_t k, uint64_t seed,
+                         uint64_t base_ctr, int32_t *nh, int32_t *nt)
+{
+    int64_t total = m * k;
+    if (total == 0) return STX_OK;
+    int64_t blocks = (total + kThreads - 1) / kThreads;
+    hipLaunchKernelGGL(k_sample, dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, h, t, total, k,
+                       (uint64_t)c->cfg.n_ent, seed, base_ctr, nh, nt);
+    return hip_ok(hipGetLastError());
+}
+
+stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const int32_t *t, const int32_t *nh,
+                        const int32_t *nt, int32_t b, int32_t k, stx_incidence *inc)
+{
+    hipStream_t s = c->stream;
+    if (b == 0) {
+        hipLaunchKernelGGL(k_empty_incidence, dim3(1), dim3(64), 0, s, inc->a_rowptr, inc->at_seg_ptr,
+                           inc->n_touched);
+        return hip_ok(hipGetLastError());
+    }
+    const int32_t nnz = (int32_t)inc->nnz;
+    const int ntiles = (nnz + kSortTile - 1) / kSortTile;
+    const int n_ent = (int)c->cfg.n_ent, n_rel = (int)c->cfg.n_rel;
+    BatchPtrs bp{h, r, t, nh, nt, b, k > 0 ? k : 1};
+
+    int bits0 = c->sort_bits < c->digit_bits ? c->sort_bits : c->digit_bits;
+    hipLaunchKernelGGL(k_emit, dim3(ntiles), dim3(kThreads), 0, s, bp, n_ent, n_rel, nnz, inc->a_rowptr,
+                       inc->a_colidx, inc->a_vals, c->keys[0], 1 << bits0, ntiles, c->table, c->ctrl);
+    int cur = 0;
+    for (int p = 0; p < c->sort_passes; ++p) {
+        int shift = p * c->digit_bits;
+        int bits = c->sort_bits - shift < c->digit_bits ? c->sort_bits - shift : c->digit_bits;
+        if (p > 0)
+            hipLaunchKernelGGL(k_hist, dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], nnz, shift, 1 << bits,
+                               ntiles, c->table, c->ctrl);
+        if (p == 0)
+            hipLaunchKernelGGL(k_scatter<true>, dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], c->pay[cur],
+                               c->keys[cur ^ 1], c->pay[cur ^ 1], nnz, shift, bits, ntiles, c->table);
+        else
+            hipLaunchKernelGGL(k_scatter<false>, dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], c->pay[cur],
+                               c->keys[cur ^ 1], c->pay[cur ^ 1], nnz, shift, bits, ntiles, c->table);
+        cur ^= 1;
+    }
+    hipLaunchKernelGGL(k_seg_count, dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], nnz, ntiles, c->tile_heads,
+                       c->ctrl, inc->n_touched, inc->at_seg_ptr);
+    hipLaunchKernelGGL(k_seg_write, dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], c->pay[cur], nnz,
+                       c->tile_heads, inc->at_touched_cols, inc->at_seg_ptr, inc->at_row_idx, inc->at_sign,
+                       inc->at_seg_id, inc->at_packed);
+    return hip_ok(hipGetLastError());
+}
+
+}  // namespace stx

@@ -1,0 +1,251 @@
+// Forward product C = A.X and the fused TransE / TorusE forward step.
+//
+// Every row of the incidence matrix A has exactly three entries (SparseTransX Sec. 4.2.2, Appendix B),
+// so the sparse-dense product is a three-row gather: x_i = (X[h] + X[n_ent + r]) - X[t], with the `ht`
+// form (Sec. 4.2.1) dropping the middle term.  A sub-wavefront group of LPR lanes owns one row and
+// moves it as float4 per lane, so a 128-wide fp32 row is one 512-byte coalesced access by 32 lanes.
+//
+// The fused forward kernel gives one group a positive row and its k negatives: it computes the
+// distances (Sec. 4.3, 4.6), the margin-ranking hinge (Sec. 5.3) and writes dL/dx of each of those
+// rows straight away, so x itself never goes to memory.
+#include "stx_device.h"
+#include "stx_internal.h"
+
+namespace stx {
+
+template <int ITERS>
+struct RowVec {
+    float4 v[ITERS];
+};
+
+// x = (X[c0] + X[c1]) - X[c2] (hrt) or X[c0] - X[c2] (ht): each operation rounded once, in this order.
+template <int LPR, int ITERS, bool HRT>
+__device__ inline void gather_row(const float *__restrict__ X, int dim, int d4, int lig, int32_t c0, int32_t c1,
+                                  int32_t c2, RowVec<ITERS> &x)
+{
+    const float *p0 = X + (int64_t)c0 * dim, *p1 = X + (int64_t)c1 * dim, *p2 = X + (int64_t)c2 * dim;
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        int j = lig + it * LPR;
+        if (j < d4) {
+            float4 a = ld4(p0 + 4 * j), c = ld4(p2 + 4 * j);
+            if (HRT) {
+                float4 b = ld4(p1 + 4 * j);
+                a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+            }
+            x.v[it] = make_float4(a.x - c.x, a.y - c.y, a.z - c.z, a.w - c.w);
+        } else {
+            x.v[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
+}
+
+template <int LPR, int ITERS, bool HRT>
+__global__ __launch_bounds__(kThreads) void k_spmm(const int32_t *__restrict__ colidx, const float *__restrict__ X,
+                                                   int64_t n_rows, int dim, int32_t rel_off, float *__restrict__ C)
+{
+    const int lig = threadIdx.x % LPR;
+    const int64_t row = ((int64_t)blockIdx.x * kThreads + threadIdx.x) / LPR;
+    if (row >= n_rows) return;
+    const int d4 = dim / 4;
+    int32_t c0 = colidx[3 * row], c1 = colidx[3 * row + 1] - rel_off, c2 = colidx[3 * row + 2];
+    RowVec<ITERS> x;
+    gather_row<LPR, ITERS, HRT>(X, dim, d4, lig, c0, c1, c2, x);
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        int j = lig + it * LPR;
+        if (j < d4) st4(C + row * dim + 4 * j, x.v[it]);
+    }
+}
+
+// ---- distance pieces -------------------------------------------------------------------------------
+template <int DIST>
+__device__ inline float term(float y)
+{
+    if (DIST == STX_L1) return fabsf(y);
+    if (DIST == STX_L2) return y * y;
+    float f = y - floorf(y);
+    float m = fminf(f, 1.0f - f);
+    return DIST == STX_TORUS_L1 ? m : m * m;
+}
+template <int DIST>
+__device__ inline float finish(float acc)
+{
+    return (DIST == STX_L2 || DIST == STX_TORUS_L2) ? sqrtf(acc) : acc;
+}
+// d(dist)/dy times coef.  cs = coef for the L1 kinds, coef / dist (0 if dist == 0) for the L2 kinds.
+template <int DIST>
+__device__ inline float dterm(float y, float cs)
+{
+    if (DIST == STX_L1) return y > 0.f ? cs : (y < 0.f ? -cs : 0.f);
+    if (DIST == STX_L2) return y * cs;
+    float f = y - floorf(y);
+    float sg = (f > 0.f && f < 0.5f) ? 1.f : (f > 0.5f ? -1.f : 0.f);
+    if (DIST == STX_TORUS_L1) return sg * cs;
+    return sg * fminf(f, 1.0f - f) * cs;
+}
+
+template <int LPR, int ITERS, int DIST>
+__device__ inline float row_distance(const RowVec<ITERS> &x)
+{
+    float acc = 0.f;
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        acc += term<DIST>(x.v[it].x);
+        acc += term<DIST>(x.v[it].y);
+        acc += term<DIST>(x.v[it].z);
+        acc += term<DIST>(x.v[it].w);
+    }
+    return finish<DIST>(group_sum<LPR>(acc));
+}
+
+template <int LPR, int ITERS, int DIST>
+__device__ inline void write_grad_row(float *__restrict__ g, int d4, int lig, const RowVec<ITERS> &x, float coef,
+                                      float dist)
+{
+    float cs = coef;
+    if (DIST == STX_L2 || DIST == STX_TORUS_L2) cs = dist > 0.f ? coef / dist : 0.f;
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        int j = lig + it * LPR;
+        if (j < d4)
+            st4(g + 4 * j, make_float4(dterm<DIST>(x.v[it].x, cs), dterm<DIST>(x.v[it].y, cs),
+                                       dterm<DIST>(x.v[it].z, cs), dterm<DIST>(x.v[it].w, cs)));
+    }
+}
+
+// Sum of the per-workgroup loss partials in a fixed order, by the last workgroup to finish.
+__device__ inline void finish_loss(const float *partials, int n, float scale, float *loss)
+{
+    __shared__ double s_acc[kThreads];
+    const int tid = threadIdx.x;
+    double a = 0.0;
+    for (int i = tid; i < n; i += kThreads) a += (double)partials[i];
+    s_acc[tid] = a;
+    __syncthreads();
+    for (int off = kThreads / 2; off >= 1; off >>= 1) {
+        if (tid < off) s_acc[tid] += s_acc[tid + off];
+        __syncthreads();
+    }
+    if (tid == 0) loss[0] = (float)(s_acc[0] * (double)scale);
+}
+
+// One group per positive i: rows i and b + i*k + kk (kk < k).
+template <int LPR, int ITERS, int DIST>
+__global__ __launch_bounds__(kThreads) void k_forward_stacked(const int32_t *__restrict__ colidx,
+                                                              const float *__restrict__ X, int32_t b, int32_t k,
+                                                              int dim, float margin, float scale,
+                                                              float *__restrict__ scores, float *__restrict__ G,
+                                                              float *__restrict__ loss_partials,
+                                                              int32_t *__restrict__ ctrl, float *__restrict__ loss)
+{
+    constexpr int GROUPS = kThreads / LPR;
+    __shared__ float s_loss[GROUPS];
+    const int lig = threadIdx.x % LPR, grp = threadIdx.x / LPR;
+    const int64_t i = (int64_t)blockIdx.x * GROUPS + grp;
+    const int d4 = dim / 4;
+    float hinge_sum = 0.f;
+    if (i < b) {   // uniform within the group; shuffles below stay inside the group
+        RowVec<ITERS> xp;
+        gather_row<LPR, ITERS, true>(X, dim, d4, lig, colidx[3 * i], colidx[3 * i + 1], colidx[3 * i + 2], xp);
+        const float dpos = row_distance<LPR, ITERS, DIST>(xp);
+        if (lig == 0) scores[i] = dpos;
+        int n_active = 0;
+        for (int kk = 0; kk < k; ++kk) {
+            const int64_t row = (int64_t)b + i * k + kk;
+            RowVec<ITERS> xn;
+            gather_row<LPR, ITERS, true>(X, dim, d4, lig, colidx[3 * row], colidx[3 * row + 1],
+                                         colidx[3 * row + 2], xn);
+            const float dneg = row_distance<LPR, ITERS, DIST>(xn);
+            const float arg = (margin + dpos) - dneg;
+            const bool active = arg > 0.f;
+            if (lig == 0) scores[row] = dneg;
+            if (active) { hinge_sum += arg; ++n_active; }
+            write_grad_row<LPR, ITERS, DIST>(G + row * dim, d4, lig, xn, active ? -scale : 0.f, dneg);
+        }
+        write_grad_row<LPR, ITERS, DIST>(G + i * dim, d4, lig, xp, (float)n_active * scale, dpos);
+    }
+    if (lig == 0) s_loss[grp] = hinge_sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float a = 0.f;
+#pragma unroll
+        for (int g = 0; g < GROUPS; ++g) a += s_loss[g];
+        loss_partials[blockIdx.x] = a;
+    }
+    if (last_block_arrives(&ctrl[CTRL_TICKET_LOSS])) {
+        finish_loss(loss_partials, (int)gridDim.x, scale, loss);
+        if (threadIdx.x == 0) ctrl[CTRL_TICKET_LOSS] = 0;
+    }
+}
+
+__global__ void k_zero_loss(float *loss) { loss[0] = 0.f; }
+
+// ---- dispatch --------------------------------------------------------------------------------------
+template <int LPR, int ITERS>
+static void spmm_go(stx_ctx *c, const stx_incidence *inc, const stx_params *p, float *out, bool hrt)
+{
+    int64_t threads = inc->n_rows * LPR;
+    dim3 grid((unsigned)((threads + kThreads - 1) / kThreads));
+    if (hrt)
+        hipLaunchKernelGGL((k_spmm<LPR, ITERS, true>), grid, dim3(kThreads), 0, c->stream, inc->a_colidx, p->ent,
+                           inc->n_rows, c->cfg.dim, 0, out);
+    else
+        hipLaunchKernelGGL((k_spmm<LPR, ITERS, false>), grid, dim3(kThreads), 0, c->stream, inc->a_colidx, p->ent,
+                           inc->n_rows, c->cfg.dim, 0, out);
+}
+
+#define STX_DISPATCH_ROW(L, FN, ...)                                                      \
+    do {                                                                                  \
+        if (L.lpr == 8 && L.iters == 1) FN<8, 1>(__VA_ARGS__);                            \
+        else if (L.lpr == 16 && L.iters == 1) FN<16, 1>(__VA_ARGS__);                     \
+        else if (L.lpr == 32 && L.iters == 1) FN<32, 1>(__VA_ARGS__);                     \
+        else if (L.lpr == 64 && L.iters == 1) FN<64, 1>(__VA_ARGS__);                     \
+        else if (L.lpr == 64 && L.iters == 2) FN<64, 2>(__VA_ARGS__);                     \
+        else if (L.lpr == 64 && L.iters == 3) FN<64, 3>(__VA_ARGS__);                     \
+        else FN<64, 4>(__VA_ARGS__);                                                      \
+    } while (0)
+
+stx_status launch_spmm(stx_ctx *c, const stx_incidence *inc, const stx_params *p, float *out)
+{
+    if (inc->n_rows == 0) return STX_OK;
+    Launch L = row_launch(c->cfg.dim);
+    bool hrt = c->cfg.model == STX_TRANSE || c->cfg.model == STX_TORUSE;
+    STX_DISPATCH_ROW(L, spmm_go, c, inc, p, out, hrt);
+    return hip_ok(hipGetLastError());
+}
+
+template <int LPR, int ITERS>
+static void forward_go(stx_ctx *c, const stx_incidence *inc, const stx_params *p, float *scores, float *loss,
+                       float scale)
+{
+    constexpr int GROUPS = kThreads / LPR;
+    dim3 grid((unsigned)((inc->b + GROUPS - 1) / GROUPS));
+#define STX_FWD(D)                                                                                              \
+    hipLaunchKernelGGL((k_forward_stacked<LPR, ITERS, D>), grid, dim3(kThreads), 0, c->stream, inc->a_colidx,   \
+                       p->ent, inc->b, inc->k, c->cfg.dim, c->cfg.margin, scale, scores, c->gbuf[0],            \
+                       c->loss_partials, c->ctrl, loss)
+    switch (c->cfg.dist) {
+    case STX_L1: STX_FWD(STX_L1); break;
+    case STX_L2: STX_FWD(STX_L2); break;
+    case STX_TORUS_L1: STX_FWD(STX_TORUS_L1); break;
+    default: STX_FWD(STX_TORUS_L2); break;
+    }
+#undef STX_FWD
+}
+
+stx_status launch_forward_stacked(stx_ctx *c, const stx_incidence *inc, const stx_params *p, float *scores,
+                                  float *loss)
+{
+    if (inc->n_rows == 0) {
+        hipLaunchKernelGGL(k_zero_loss, dim3(1), dim3(1), 0, c->stream, loss);
+        return hip_ok(hipGetLastError());
+    }
+    float scale = 1.0f;
+    if (c->cfg.reduce == STX_MEAN && inc->k > 0) scale = 1.0f / (float)((int64_t)inc->b * inc->k);
+    Launch L = row_launch(c->cfg.dim);
+    STX_DISPATCH_ROW(L, forward_go, c, inc, p, scores, loss, scale);
+    return hip_ok(hipGetLastError());
+}
+
+}  // namespace stx

@@ -1,0 +1,75 @@
+// Internal declarations shared by the HIP translation units of libstx.  Not part of the C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "stx.h"
+
+namespace stx {
+
+constexpr int kThreads = 256;          // every kernel here runs 256-thread workgroups (4 wavefronts)
+constexpr int kSortItems = 8;          // keys per thread in the radix-sort kernels
+constexpr int kSortTile = kThreads * kSortItems;
+constexpr int kSegTile = 256;          // sorted entries per workgroup in the transposed product
+constexpr int kMaxDim = 1024;
+
+// Slots of the control block at the start of the workspace (int32 each).
+enum { CTRL_TICKET_SORT = 0, CTRL_TICKET_SEG = 1, CTRL_TICKET_LOSS = 2, CTRL_BAD_INDEX = 3, CTRL_WORDS = 64 };
+
+struct Launch {            // how a row of `width` floats maps onto lanes
+    int lpr;               // lanes per row: power of two in 8..64
+    int iters;             // float4 per lane: ceil(width/4 / lpr), 1..4
+};
+inline Launch row_launch(int width)
+{
+    int q = width / 4, lpr = 8;
+    while (lpr < 64 && lpr < q) lpr <<= 1;
+    return {lpr, (q + lpr - 1) / lpr};
+}
+
+}  // namespace stx
+
+struct stx_ctx {
+    stx_config cfg;
+    hipStream_t stream;
+    int ld;                        // floats per gradient row: max(dim, rel_dim)
+    int out_dim;                   // width of y: rel_dim for TransR, dim otherwise
+    int64_t rows_max, nnz_max, cols_max;
+    int sort_bits, sort_passes, digit_bits;
+    int ntiles_max;                // radix-sort tiles at nnz_max
+    int fwd_blocks_max;
+    // workspace partitions (device)
+    int32_t *ctrl;
+    int32_t *keys[2];
+    int32_t *pay[2];
+    int32_t *table;                // [256 * ntiles_max] digit-major tile histograms / offsets
+    int32_t *tile_heads;           // [ntiles_max + 1]
+    float *loss_partials;          // [fwd_blocks_max]
+    float *partials;               // [(nnz_max/kSegTile + 2) * 2 * ld]
+    float *gbuf[4];                // per-row buffers, rows_max x ld each (how many depends on the model)
+    // host-side call-order state
+    const stx_incidence *fwd_inc;  // incidence of the last stx_forward, null if none
+    int64_t fwd_rows;
+};
+
+namespace stx {
+
+// stx_build.hip
+stx_status launch_sample(stx_ctx *, const int32_t *h, const int32_t *t, int64_t m, int32_t k, uint64_t seed,
+                         uint64_t base_ctr, int32_t *nh, int32_t *nt);
+stx_status launch_build(stx_ctx *, const int32_t *h, const int32_t *r, const int32_t *t, const int32_t *nh,
+                        const int32_t *nt, int32_t b, int32_t k, stx_incidence *inc);
+stx_status launch_clear_ctrl(stx_ctx *);
+// stx_forward.hip
+stx_status launch_spmm(stx_ctx *, const stx_incidence *, const stx_params *, float *c_out);
+stx_status launch_forward_stacked(stx_ctx *, const stx_incidence *, const stx_params *, float *scores, float *loss);
+// stx_backward.hip
+stx_status launch_seg_reduce(stx_ctx *, const stx_incidence *, int64_t e_begin, int64_t e_end, const float *src,
+                             int ld_src, int width, float *out_rows, int ld_out);
+stx_status launch_sgd_rows(stx_ctx *, const stx_incidence *, float *table, int64_t col_lo, int64_t col_hi,
+                           const float *grad_rows, int ld, int width, float lr, int mode);
+
+inline stx_status hip_ok(hipError_t e) { return e == hipSuccess ? STX_OK : STX_ERR_HIP; }
+
+}  // namespace stx

@@ -1,0 +1,206 @@
+"""GPU parity for the integer structures and the TransE / TorusE step: HIP library (through the C ABI)
+against the CPU oracle, element by element, on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import stxo
+from paper_2502_16949_amd import binding as B
+from paper_2502_16949_amd import workloads as W
+from tests import gpu_util as G
+from tests.util import oracle_batch, oracle_config, oracle_tables, small_problem
+
+pytestmark = pytest.mark.gpu
+
+
+def _problem(model, dist, n_ent, n_rel, b, k, dim, seed, zipf=0.0, margin=1.0):
+    wl = W.Workload("case", 7, model, dist, n_ent, n_rel, b, dim, dim, b, k, margin, 0.01, 1, zipf, zipf)
+    h, r, t = W.make_graph(wl.scaled(index=seed))
+    tabs = W.make_tables(wl.scaled(index=seed))
+    bt = oracle_batch(wl, h, r, t, 0, b, seed=seed)
+    return wl, tabs, bt
+
+
+# ----------------------------------------------------------------------------------------- sampler
+@pytest.mark.parametrize("m,k,n_ent,off,epoch", [(1, 1, 10, 0, 0), (1000, 1, 977, 0, 0), (5000, 4, 4_000_000, 12345, 3),
+                                                 (2049, 3, 15_000, 7, 1)])
+def test_negatives_bit_exact(m, k, n_ent, off, epoch):
+    rng = np.random.default_rng(m + k)
+    h, t = (rng.integers(0, n_ent, m).astype(np.int32) for _ in range(2))
+    r = rng.integers(0, 5, m).astype(np.int32)
+    m_total = off + m + 11
+    want_h, want_t = stxo.sample_negatives(h, r, t, k, n_ent, seed=99, epoch=epoch, m_total=m_total, global_offset=off)
+    ctx = B.Context(B.make_config("transe", "l1", n_ent, 5, 8, max_batch=m, max_neg=k), G.DEV)
+    nh = torch.empty(m * k, dtype=torch.int32, device=G.DEV)
+    nt = torch.empty(m * k, dtype=torch.int32, device=G.DEV)
+    B.stx_sample_negatives(ctx, G.dev_i32(h), G.dev_i32(r), G.dev_i32(t), k, 99, epoch, m_total, off, nh, nt)
+    torch.cuda.synchronize()
+    assert np.array_equal(nh.cpu().numpy(), want_h) and np.array_equal(nt.cpu().numpy(), want_t)
+
+
+# ----------------------------------------------------------------------------------------- incidence
+INC_CASES = [
+    # n_ent, n_rel, b, k, zipf      what it exercises
+    (10, 2, 1, 0, 0.0),           # one row, no negatives
+    (10, 2, 3, 1, 0.0),           # smaller than one lane group
+    (1000, 20, 1024, 1, 0.0),     # config "tiny": 6,144 entries, 3 sort tiles, two 5/6-bit digit passes
+    (300, 7, 683, 2, 1.1),        # 6,147 entries: ragged last tile (3 entries), skewed columns
+    (70_000, 300, 4096, 1, 1.1),  # 17-bit column ids: three digit passes
+    (5, 1, 3000, 1, 0.0),         # six columns only: every segment spans many tiles
+    (200_000, 10, 1500, 3, 0.0),  # more columns than entries
+]
+
+
+@pytest.mark.parametrize("n_ent,n_rel,b,k,zipf", INC_CASES)
+def test_incidence_bit_exact(n_ent, n_rel, b, k, zipf):
+    wl, tabs, bt = _problem("transe", "l1", n_ent, n_rel, b, k, 8, seed=b + k, zipf=zipf)
+    m = G.GpuModel(wl, tabs)
+    m.build(bt)
+    G.check_incidence(m.incidence_numpy(), stxo.build_incidence(bt, n_ent, n_rel))
+    assert B.stx_check_indices(m.ctx) == 0
+
+
+def test_incidence_self_loops_and_rebuild_smaller():
+    wl, tabs, bt = _problem("transe", "l1", 50, 3, 700, 2, 8, seed=5)
+    bt = stxo.Batch(bt.h, bt.r, bt.h, bt.nh, bt.nh)          # h == t everywhere: +1 and -1 in one column
+    m = G.GpuModel(wl, tabs)
+    m.build(bt)
+    G.check_incidence(m.incidence_numpy(), stxo.build_incidence(bt, 50, 3))
+    small = stxo.Batch(bt.h[:33], bt.r[:33], bt.t[:33], bt.nh[:66], bt.nt[:66])   # same arrays reused
+    m.build(small)
+    G.check_incidence(m.incidence_numpy(), stxo.build_incidence(small, 50, 3))
+
+
+def test_incidence_empty_batch():
+    wl, tabs, bt = _problem("transe", "l1", 50, 3, 16, 1, 8, seed=6)
+    m = G.GpuModel(wl, tabs)
+    e = np.empty(0, np.int32)
+    m.build(stxo.Batch(e, e, e, e, e))
+    got = m.incidence_numpy()
+    assert got["n_touched"] == 0 and got["rowptr"].tolist() == [0] and got["seg_ptr"].tolist() == [0]
+    m.forward()
+    _, loss = m.scores_numpy()
+    assert loss == 0.0
+    m.backward()
+    m.sgd(0.1)
+    torch.cuda.synchronize()
+    assert np.array_equal(m.params.ent.cpu().numpy(), tabs["ent"])
+
+
+def test_out_of_range_indices_are_clamped_and_reported():
+    wl, tabs, bt = _problem("transe", "l1", 50, 3, 64, 1, 8, seed=7)
+    h = bt.h.copy(); h[5] = 50; h[9] = -1
+    r = bt.r.copy(); r[2] = 3
+    m = G.GpuModel(wl, tabs)
+    m.build(stxo.Batch(h, r, bt.t, bt.nh, bt.nt))
+    assert B.stx_check_indices(m.ctx) == 4                    # entries of A: the bad relation is in 2 rows
+    assert B.stx_check_indices(m.ctx) == 0                    # the counter was reset
+    got = m.incidence_numpy()
+    assert got["colidx"].min() >= 0 and got["colidx"].max() < 53
+    assert got["colidx"][3 * 5] == 49 and got["colidx"][3 * 9] == 0 and got["colidx"][3 * 2 + 1] == 52
+
+
+# ----------------------------------------------------------------------------------------- A.X
+@pytest.mark.parametrize("dim", [8, 32, 100, 128, 256, 512, 1024])
+def test_spmm_bitwise(dim):
+    wl, tabs, bt = _problem("transe", "l1", 500, 11, 333, 2, dim, seed=dim)
+    m = G.GpuModel(wl, tabs)
+    m.build(bt)
+    out = torch.empty(bt.rows, dim, dtype=torch.float32, device=G.DEV)
+    B.stx_spmm(m.ctx, m.inc, m.params, out)
+    torch.cuda.synchronize()
+    fw = stxo.forward(oracle_config(wl), oracle_tables(tabs), bt)
+    assert np.array_equal(out.cpu().numpy(), fw.x)            # == also accepts -0 vs +0
+
+
+# ----------------------------------------------------------------------------------------- full step
+STEP_CASES = [
+    # model, dist, n_ent, n_rel, b, k, dim, zipf
+    ("transe", "l2", 1000, 20, 1024, 1, 32, 0.0),      # config "tiny"
+    ("transe", "l1", 1000, 20, 1000, 1, 128, 1.1),
+    ("transe", "l2", 400, 9, 777, 3, 128, 1.1),
+    ("transe", "l1", 64, 4, 2500, 2, 100, 0.0),        # long segments, width not a power of two
+    ("transe", "l2", 300, 5, 300, 1, 8, 0.0),
+    ("transe", "l2", 300, 5, 300, 2, 256, 0.0),
+    ("transe", "l1", 300, 5, 300, 1, 512, 1.1),
+    ("transe", "l2", 200, 5, 200, 1, 1024, 0.0),
+    ("toruse", "torus_l1", 1000, 20, 1024, 4, 128, 1.05),
+    ("toruse", "torus_l2", 500, 7, 600, 2, 64, 1.05),
+]
+
+
+@pytest.mark.parametrize("reduce", [B.STX_SUM, B.STX_MEAN])
+@pytest.mark.parametrize("model,dist,n_ent,n_rel,b,k,dim,zipf", STEP_CASES)
+def test_training_step_matches_oracle(model, dist, n_ent, n_rel, b, k, dim, zipf, reduce):
+    wl, tabs, bt = _problem(model, dist, n_ent, n_rel, b, k, dim, seed=dim + b, zipf=zipf)
+    lr = 0.01
+    cfg = oracle_config(wl, reduce=reduce)
+    m = G.GpuModel(wl, tabs, reduce=reduce)
+    m.build(bt)
+    m.forward()
+    scores, loss = m.scores_numpy()
+    fw = stxo.forward(cfg, oracle_tables(tabs), bt, want_x=False)
+    G.check_scores_and_loss(scores, loss, fw, reduce == B.STX_MEAN)
+    active = G.resolve_active(scores, fw, bt, wl.margin)
+    g = stxo.backward(cfg, oracle_tables(tabs), bt, active=active)
+    m.backward()
+    cols, rows = m.grad_rows_numpy()
+    G.check_grad_rows(cols, rows, g.ent, g.ent_abs, dim)
+    # update: compare against the oracle's update of its own table with its own gradient
+    tb = oracle_tables(tabs)
+    touched, _ = stxo.touched_masks(cfg, bt)
+    stxo.sgd(tb.ent, g.ent, touched, lr, 1 if model == "toruse" else 0)
+    m.sgd(lr)
+    torch.cuda.synchronize()
+    new = m.params.ent.cpu().numpy()
+    untouched = touched == 0
+    assert np.array_equal(new[untouched], tabs["ent"][untouched])
+    step_scale = lr * g.ent_abs + np.abs(tabs["ent"]) * 2.0**-23          # gradient error + one rounding of the row
+    diff = np.abs(new.astype(np.float64) - tb.ent)
+    if model == "toruse":
+        diff = np.minimum(diff, 1.0 - diff)                              # distance on the circle
+        assert new.min() >= 0.0 and new.max() < 1.0
+    assert np.all(diff <= G.REL_TOL * step_scale + 2.0**-23), float(diff.max())
+
+
+def test_backward_is_bitwise_reproducible_and_needs_forward():
+    wl, tabs, bt = _problem("transe", "l2", 64, 4, 3000, 2, 128, seed=3, zipf=1.1)
+    m = G.GpuModel(wl, tabs)
+    m.build(bt)
+    with pytest.raises(B.StxError) as ei:
+        m.backward()
+    assert ei.value.status == B.STX_ERR_STATE
+    outs = []
+    for _ in range(3):
+        m.forward()
+        m.backward()
+        outs.append(m.grad_rows_numpy()[1].copy())
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    m.sgd(0.01)
+    with pytest.raises(B.StxError):                                      # tables changed: forward again first
+        m.backward()
+
+
+def test_tiny_config_trajectory():
+    """Config "tiny": 5 epochs of 10 batches, GPU and oracle each advancing their own tables."""
+    wl = W.WORKLOADS["tiny"]
+    h, r, t = W.make_graph(wl)
+    tabs = W.make_tables(wl)
+    cfg = oracle_config(wl)
+    tb = oracle_tables(tabs)
+    m = G.GpuModel(wl, tabs)
+    losses_gpu, losses_ref = [], []
+    for epoch in range(wl.epochs):
+        for lo, hi in W.batch_slices(wl):
+            bt = oracle_batch(wl, h, r, t, lo, hi)                        # negatives fixed across epochs
+            m.build(bt)
+            m.forward()
+            m.backward()
+            m.sgd(wl.lr)
+            losses_gpu.append(m.scores_numpy()[1])
+            fw, _ = stxo.train_step(cfg, tb, bt, wl.lr)
+            losses_ref.append(fw.loss)
+    np.testing.assert_allclose(losses_gpu, losses_ref, rtol=1e-4)        # drift over 50 dependent steps
+    np.testing.assert_allclose(m.params.ent.cpu().numpy(), tb.ent, rtol=0, atol=2e-5)
+    per_epoch = np.array(losses_ref).reshape(wl.epochs, -1).sum(1)
+    assert np.all(np.diff(per_epoch) < 0)                                 # training loss decreases every epoch
