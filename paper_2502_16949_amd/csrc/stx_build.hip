@@ -7,11 +7,14 @@
 // contiguous and in a unique order, which is what lets the backward product run without atomics.
 //
 // Launch sequence for one batch (P = number of digit passes, 1..4):
-//   k_emit            keys + CSR arrays + tile histograms of digit 0   (last workgroup scans them)
+//   k_emit            keys + CSR arrays + tile histograms of digit 0
 //   k_scatter  x P    stable scatter by digit p
-//   k_hist     x P-1  tile histograms of digit p (between scatters; last workgroup scans)
-//   k_seg_count       segment heads per tile (last workgroup scans, writes U)
-//   k_seg_write       touched_cols, seg_ptr, row_idx, sign, seg_id, packed
+//   k_hist     x P-1  tile histograms of digit p (between scatters)
+//   k_seg_count       segment heads per tile
+//   k_seg_write       touched_cols, seg_ptr, row_idx, sign, seg_id, packed, U
+// The tile histograms (tile-major table[tile][digit]) must become global offsets before a scatter.
+// With few tiles every scatter workgroup derives its own offsets from the raw table (a few coalesced
+// reads per thread); with many tiles a one-workgroup k_scan_table does it once in between.
 #include "stx_device.h"
 #include "stx_internal.h"
 
@@ -98,17 +101,12 @@ __global__ __launch_bounds__(kThreads) void k_emit(BatchPtrs bp, int32_t n_ent, 
         }
     }
     __syncthreads();
-    if (tid < radix) table[tid * ntiles + blockIdx.x] = s_hist[tid];
-    if (last_block_arrives(&ctrl[CTRL_TICKET_SORT])) {
-        block_exclusive_scan_inplace(table, radix * ntiles, nullptr);
-        if (tid == 0) ctrl[CTRL_TICKET_SORT] = 0;
-    }
+    if (tid < radix) table[blockIdx.x * radix + tid] = s_hist[tid];
 }
 
 // Tile histograms of the digit at `shift` for the later passes.
 __global__ __launch_bounds__(kThreads) void k_hist(const int32_t *__restrict__ keys, int32_t nnz, int shift,
-                                                   int radix, int ntiles, int32_t *__restrict__ table,
-                                                   int32_t *__restrict__ ctrl)
+                                                   int radix, int32_t *__restrict__ table)
 {
     __shared__ int32_t s_hist[256];
     const int tid = threadIdx.x;
@@ -121,20 +119,34 @@ __global__ __launch_bounds__(kThreads) void k_hist(const int32_t *__restrict__ k
         if (e < nnz) atomicAdd(&s_hist[(keys[e] >> shift) & (radix - 1)], 1);
     }
     __syncthreads();
-    if (tid < radix) table[tid * ntiles + blockIdx.x] = s_hist[tid];
-    if (last_block_arrives(&ctrl[CTRL_TICKET_SORT])) {
-        block_exclusive_scan_inplace(table, radix * ntiles, nullptr);
-        if (tid == 0) ctrl[CTRL_TICKET_SORT] = 0;
-    }
+    if (tid < radix) table[blockIdx.x * radix + tid] = s_hist[tid];
+}
+
+// One workgroup: table[tile][digit] counts -> number of keys that sort before the first key of that
+// (digit, tile): all keys of smaller digits, plus the same digit in earlier tiles.
+__global__ __launch_bounds__(kThreads) void k_scan_table(int32_t *__restrict__ table, int radix, int ntiles)
+{
+    const int tid = threadIdx.x;
+    int32_t total = 0;
+    if (tid < radix)
+        for (int t = 0; t < ntiles; ++t) total += table[t * radix + tid];
+    int32_t run = block_exclusive_scan(total, nullptr);
+    if (tid < radix)
+        for (int t = 0; t < ntiles; ++t) {
+            int32_t v = table[t * radix + tid];
+            table[t * radix + tid] = run;
+            run += v;
+        }
 }
 
 // Stable scatter of one tile by the digit at `shift`.  Element order inside a tile is
 // (wavefront, iteration, lane): wavefront w owns the contiguous span [w*512, (w+1)*512) of the tile.
 // The rank of a key among equal digits is
 //   (count in earlier wavefronts) + (count in earlier iterations of this wavefront) + (equal lanes below),
-// the last term from a ballot match over the digit's bits.  `table` holds, per (digit, tile), the
-// number of keys with a smaller digit anywhere plus those with the same digit in earlier tiles.
-template <bool FIRST>
+// the last term from a ballot match over the digit's bits.  The base offset of a (digit, tile) is the
+// number of keys with a smaller digit anywhere plus those with the same digit in earlier tiles: read
+// from `table` when SELF_SCAN is false (k_scan_table ran), else derived here from the raw counts.
+template <bool FIRST, bool SELF_SCAN>
 __global__ __launch_bounds__(kThreads) void k_scatter(const int32_t *__restrict__ keys_in,
                                                       const int32_t *__restrict__ pay_in,
                                                       int32_t *__restrict__ keys_out,
@@ -146,7 +158,40 @@ __global__ __launch_bounds__(kThreads) void k_scatter(const int32_t *__restrict_
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int radix = 1 << bits;
     for (int i = tid; i < 4 * 256; i += kThreads) (&s_hist[0][0])[i] = 0;
-    if (tid < radix) s_goff[tid] = table[tid * ntiles + blockIdx.x];
+    if (SELF_SCAN) {
+        // all 256 threads share the table: thread (digit d, part q) sums tiles q, q+parts, ...
+        __shared__ int32_t s_tot[256], s_bel[256];
+        const int parts = kThreads >> bits, d = tid & (radix - 1), q = tid >> bits;
+        const int me = (int)blockIdx.x;
+        int32_t below = 0, total = 0;
+        int t = q;
+        for (; t + 3 * parts < ntiles; t += 4 * parts) {   // four independent loads in flight
+            int32_t v0 = table[t * radix + d], v1 = table[(t + parts) * radix + d];
+            int32_t v2 = table[(t + 2 * parts) * radix + d], v3 = table[(t + 3 * parts) * radix + d];
+            total += (v0 + v1) + (v2 + v3);
+            below += (t < me ? v0 : 0) + (t + parts < me ? v1 : 0) + (t + 2 * parts < me ? v2 : 0) +
+                     (t + 3 * parts < me ? v3 : 0);
+        }
+        for (; t < ntiles; t += parts) {
+            int32_t v = table[t * radix + d];
+            total += v;
+            below += t < me ? v : 0;
+        }
+        s_tot[tid] = total;
+        s_bel[tid] = below;
+        __syncthreads();
+        total = 0;
+        below = 0;
+        if (tid < radix)
+            for (int qq = 0; qq < parts; ++qq) {
+                total += s_tot[qq * radix + tid];
+                below += s_bel[qq * radix + tid];
+            }
+        int32_t base = block_exclusive_scan(total, nullptr);
+        s_goff[tid] = base + below;
+    } else if (tid < radix) {
+        s_goff[tid] = table[blockIdx.x * radix + tid];
+    }
     __syncthreads();
 
     int32_t key[kSortItems], pay[kSortItems], rank[kSortItems];
@@ -193,12 +238,9 @@ __global__ __launch_bounds__(kThreads) void k_scatter(const int32_t *__restrict_
     }
 }
 
-// Number of segment heads (first entry of a column's run) in each tile of the sorted keys; the last
-// workgroup turns the counts into each tile's first segment number and writes U and seg_ptr[U].
-__global__ __launch_bounds__(kThreads) void k_seg_count(const int32_t *__restrict__ keys, int32_t nnz, int ntiles,
-                                                        int32_t *__restrict__ tile_heads,
-                                                        int32_t *__restrict__ ctrl, int32_t *__restrict__ n_touched,
-                                                        int32_t *__restrict__ seg_ptr)
+// Number of segment heads (first entry of a column's run) in each tile of the sorted keys.
+__global__ __launch_bounds__(kThreads) void k_seg_count(const int32_t *__restrict__ keys, int32_t nnz,
+                                                        int32_t *__restrict__ tile_heads)
 {
     __shared__ int32_t s_cnt;
     const int tid = threadIdx.x;
@@ -214,15 +256,6 @@ __global__ __launch_bounds__(kThreads) void k_seg_count(const int32_t *__restric
     if (c) atomicAdd(&s_cnt, c);
     __syncthreads();
     if (tid == 0) tile_heads[blockIdx.x] = s_cnt;
-    if (last_block_arrives(&ctrl[CTRL_TICKET_SEG])) {
-        __shared__ int32_t s_total;
-        block_exclusive_scan_inplace(tile_heads, ntiles, &s_total);
-        if (tid == 0) {
-            n_touched[0] = s_total;
-            seg_ptr[s_total] = nnz;
-            ctrl[CTRL_TICKET_SEG] = 0;
-        }
-    }
 }
 
 // Per sorted entry: its segment, row, sign and packed form; per segment: its column and first entry.
@@ -230,13 +263,21 @@ __global__ __launch_bounds__(kThreads) void k_seg_count(const int32_t *__restric
 __global__ __launch_bounds__(kThreads) void k_seg_write(const int32_t *__restrict__ keys,
                                                         const int32_t *__restrict__ pay, int32_t nnz,
                                                         const int32_t *__restrict__ tile_heads,
+                                                        int32_t *__restrict__ n_touched,
                                                         int32_t *__restrict__ touched_cols,
                                                         int32_t *__restrict__ seg_ptr, int32_t *__restrict__ row_idx,
                                                         int8_t *__restrict__ sign, int32_t *__restrict__ seg_id,
                                                         int32_t *__restrict__ packed)
 {
-    __shared__ int32_t s_scan[256];
+    __shared__ int32_t s_base;
     const int tid = threadIdx.x;
+    if (tid == 0) s_base = 0;
+    __syncthreads();
+    {   // segments that start in earlier tiles
+        int32_t a = 0;
+        for (int t = tid; t < (int)blockIdx.x; t += kThreads) a += tile_heads[t];
+        if (a) atomicAdd(&s_base, a);
+    }
     const int32_t e0 = blockIdx.x * kSortTile + tid * kSortItems;
     int32_t kk[kSortItems + 1];
     kk[0] = (e0 > 0 && e0 - 1 < nnz) ? keys[e0 - 1] : -1;
@@ -247,15 +288,13 @@ __global__ __launch_bounds__(kThreads) void k_seg_write(const int32_t *__restric
         kk[i + 1] = e < nnz ? keys[e] : -1;
         if (e < nnz && kk[i + 1] != kk[i]) ++cnt;
     }
-    s_scan[tid] = cnt;
-    __syncthreads();
-    for (int off = 1; off < 256; off <<= 1) {
-        int32_t v = tid >= off ? s_scan[tid - off] : 0;
-        __syncthreads();
-        s_scan[tid] += v;
-        __syncthreads();
+    int32_t tile_total;
+    const int32_t before = block_exclusive_scan(cnt, &tile_total);   // its barriers also publish s_base
+    int32_t seg = s_base + before - 1;                               // segment of the entry before e0
+    if (blockIdx.x == gridDim.x - 1 && tid == 0) {
+        n_touched[0] = s_base + tile_total;
+        seg_ptr[s_base + tile_total] = nnz;
     }
-    int32_t seg = tile_heads[blockIdx.x] + (s_scan[tid] - cnt) - 1;   // segment of the entry before e0
 #pragma unroll
     for (int i = 0; i < kSortItems; ++i) {
         int32_t e = e0 + i;
@@ -312,26 +351,27 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
     int bits0 = c->sort_bits < c->digit_bits ? c->sort_bits : c->digit_bits;
     hipLaunchKernelGGL(k_emit, dim3(ntiles), dim3(kThreads), 0, s, bp, n_ent, n_rel, nnz, inc->a_rowptr,
                        inc->a_colidx, inc->a_vals, c->keys[0], 1 << bits0, ntiles, c->table, c->ctrl);
+    const bool self_scan = ntiles <= kSelfScanTiles;
     int cur = 0;
     for (int p = 0; p < c->sort_passes; ++p) {
         int shift = p * c->digit_bits;
         int bits = c->sort_bits - shift < c->digit_bits ? c->sort_bits - shift : c->digit_bits;
         if (p > 0)
             hipLaunchKernelGGL(k_hist, dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], nnz, shift, 1 << bits,
-                               ntiles, c->table, c->ctrl);
-        if (p == 0)
-            hipLaunchKernelGGL(k_scatter<true>, dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], c->pay[cur],
-                               c->keys[cur ^ 1], c->pay[cur ^ 1], nnz, shift, bits, ntiles, c->table);
-        else
-            hipLaunchKernelGGL(k_scatter<false>, dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], c->pay[cur],
-                               c->keys[cur ^ 1], c->pay[cur ^ 1], nnz, shift, bits, ntiles, c->table);
+                               c->table);
+        if (!self_scan) hipLaunchKernelGGL(k_scan_table, dim3(1), dim3(kThreads), 0, s, c->table, 1 << bits, ntiles);
+#define STX_SCATTER(F, S)                                                                                     \
+    hipLaunchKernelGGL((k_scatter<F, S>), dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], c->pay[cur],       \
+                       c->keys[cur ^ 1], c->pay[cur ^ 1], nnz, shift, bits, ntiles, c->table)
+        if (p == 0) { if (self_scan) STX_SCATTER(true, true); else STX_SCATTER(true, false); }
+        else        { if (self_scan) STX_SCATTER(false, true); else STX_SCATTER(false, false); }
+#undef STX_SCATTER
         cur ^= 1;
     }
-    hipLaunchKernelGGL(k_seg_count, dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], nnz, ntiles, c->tile_heads,
-                       c->ctrl, inc->n_touched, inc->at_seg_ptr);
+    hipLaunchKernelGGL(k_seg_count, dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], nnz, c->tile_heads);
     hipLaunchKernelGGL(k_seg_write, dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], c->pay[cur], nnz,
-                       c->tile_heads, inc->at_touched_cols, inc->at_seg_ptr, inc->at_row_idx, inc->at_sign,
-                       inc->at_seg_id, inc->at_packed);
+                       c->tile_heads, inc->n_touched, inc->at_touched_cols, inc->at_seg_ptr, inc->at_row_idx,
+                       inc->at_sign, inc->at_seg_id, inc->at_packed);
     return hip_ok(hipGetLastError());
 }
 

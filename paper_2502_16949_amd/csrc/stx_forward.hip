@@ -114,8 +114,9 @@ __device__ inline void write_grad_row(float *__restrict__ g, int d4, int lig, co
     }
 }
 
-// Sum of the per-workgroup loss partials in a fixed order, by the last workgroup to finish.
-__device__ inline void finish_loss(const float *partials, int n, float scale, float *loss)
+// Sum of the per-workgroup loss partials in a fixed order (one workgroup, launched after the forward).
+__global__ __launch_bounds__(kThreads) void k_finish_loss(const float *__restrict__ partials, int n, float scale,
+                                                          float *__restrict__ loss)
 {
     __shared__ double s_acc[kThreads];
     const int tid = threadIdx.x;
@@ -136,8 +137,7 @@ __global__ __launch_bounds__(kThreads) void k_forward_stacked(const int32_t *__r
                                                               const float *__restrict__ X, int32_t b, int32_t k,
                                                               int dim, float margin, float scale,
                                                               float *__restrict__ scores, float *__restrict__ G,
-                                                              float *__restrict__ loss_partials,
-                                                              int32_t *__restrict__ ctrl, float *__restrict__ loss)
+                                                              float *__restrict__ loss_partials)
 {
     constexpr int GROUPS = kThreads / LPR;
     __shared__ float s_loss[GROUPS];
@@ -172,10 +172,6 @@ __global__ __launch_bounds__(kThreads) void k_forward_stacked(const int32_t *__r
 #pragma unroll
         for (int g = 0; g < GROUPS; ++g) a += s_loss[g];
         loss_partials[blockIdx.x] = a;
-    }
-    if (last_block_arrives(&ctrl[CTRL_TICKET_LOSS])) {
-        finish_loss(loss_partials, (int)gridDim.x, scale, loss);
-        if (threadIdx.x == 0) ctrl[CTRL_TICKET_LOSS] = 0;
     }
 }
 
@@ -224,7 +220,7 @@ static void forward_go(stx_ctx *c, const stx_incidence *inc, const stx_params *p
 #define STX_FWD(D)                                                                                              \
     hipLaunchKernelGGL((k_forward_stacked<LPR, ITERS, D>), grid, dim3(kThreads), 0, c->stream, inc->a_colidx,   \
                        p->ent, inc->b, inc->k, c->cfg.dim, c->cfg.margin, scale, scores, c->gbuf[0],            \
-                       c->loss_partials, c->ctrl, loss)
+                       c->loss_partials)
     switch (c->cfg.dist) {
     case STX_L1: STX_FWD(STX_L1); break;
     case STX_L2: STX_FWD(STX_L2); break;
@@ -232,6 +228,8 @@ static void forward_go(stx_ctx *c, const stx_incidence *inc, const stx_params *p
     default: STX_FWD(STX_TORUS_L2); break;
     }
 #undef STX_FWD
+    hipLaunchKernelGGL(k_finish_loss, dim3(1), dim3(kThreads), 0, c->stream, c->loss_partials, (int)grid.x, scale,
+                       loss);
 }
 
 stx_status launch_forward_stacked(stx_ctx *c, const stx_incidence *inc, const stx_params *p, float *scores,

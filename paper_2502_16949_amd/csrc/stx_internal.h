@@ -12,10 +12,11 @@ constexpr int kThreads = 256;          // every kernel here runs 256-thread work
 constexpr int kSortItems = 8;          // keys per thread in the radix-sort kernels
 constexpr int kSortTile = kThreads * kSortItems;
 constexpr int kSegTile = 256;          // sorted entries per workgroup in the transposed product
+constexpr int kSelfScanTiles = 128;   // up to this many sort tiles, scatter workgroups scan the histograms themselves
 constexpr int kMaxDim = 1024;
 
 // Slots of the control block at the start of the workspace (int32 each).
-enum { CTRL_TICKET_SORT = 0, CTRL_TICKET_SEG = 1, CTRL_TICKET_LOSS = 2, CTRL_BAD_INDEX = 3, CTRL_WORDS = 64 };
+enum { CTRL_BAD_INDEX = 0, CTRL_WORDS = 64 };
 
 struct Launch {            // how a row of `width` floats maps onto lanes
     int lpr;               // lanes per row: power of two in 8..64
