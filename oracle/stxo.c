@@ -238,29 +238,37 @@ static void row_x(const stxo_cfg *c, const stxo_tables *tb, int32_t hh, int32_t 
     }
 }
 
-/* y of one row in double (length out_dim), and s = w.x for TransH. */
-static void row_y(const stxo_cfg *c, const stxo_tables *tb, int32_t rr, const float *x, double *y, double *s_out)
+/* y of one row in double (length out_dim), and s = w.x for TransH.  yabs (optional): for every
+ * element of y the sum of the absolute values of the terms it is made of, i.e. the scale against
+ * which an fp32 evaluation of y can be off. */
+static void row_y(const stxo_cfg *c, const stxo_tables *tb, int32_t rr, const float *x, double *y, double *s_out,
+                  double *yabs)
 {
     int32_t d = c->dim;
     if (is_stacked(c)) {
-        for (int32_t j = 0; j < d; ++j) y[j] = (double)x[j];
+        for (int32_t j = 0; j < d; ++j) { y[j] = (double)x[j]; if (yabs) yabs[j] = fabs((double)x[j]); }
     } else if (c->model == STXO_TRANSH) {
         const float *w = tb->w + (int64_t)rr * d, *dr = tb->rel + (int64_t)rr * d;
         double s = 0.0;
         for (int32_t j = 0; j < d; ++j) s += (double)w[j] * (double)x[j];
-        for (int32_t j = 0; j < d; ++j) y[j] = ((double)x[j] + (double)dr[j]) - s * (double)w[j];
+        for (int32_t j = 0; j < d; ++j) {
+            y[j] = ((double)x[j] + (double)dr[j]) - s * (double)w[j];
+            if (yabs) yabs[j] = fabs((double)x[j]) + fabs((double)dr[j]) + fabs(s * (double)w[j]);
+        }
         if (s_out) *s_out = s;
     } else { /* TransR */
         int32_t kd = c->rel_dim;
         const float *M = tb->proj + (int64_t)rr * kd * d, *rv = tb->rel + (int64_t)rr * kd;
         for (int32_t a = 0; a < kd; ++a) {
-            double acc = 0.0;
+            double acc = 0.0, aacc = 0.0;
             for (int32_t j = 0; j < d; ++j) {
                 float m = M[(int64_t)a * d + j], xv = x[j];
                 if (c->bf16_proj) { m = bf16_round(m); xv = bf16_round(xv); }
                 acc += (double)m * (double)xv;
+                aacc += fabs((double)m * (double)xv);
             }
             y[a] = acc + (double)rv[a];
+            if (yabs) yabs[a] = aacc + fabs((double)rv[a]);
         }
     }
 }
@@ -324,7 +332,7 @@ int stxo_forward(const stxo_cfg *c, const stxo_tables *tb, const stxo_batch *bt,
         batch_row(bt, i, &hh, &rr, &tt);
         row_x(c, tb, hh, rr, tt, x);
         if (x_out) memcpy(x_out + i * d, x, sizeof(float) * (size_t)d);
-        row_y(c, tb, rr, x, y, NULL);
+        row_y(c, tb, rr, x, y, NULL, NULL);
         scores[i] = row_dist(c, y, n);
     }
     double total = 0.0;
@@ -345,16 +353,25 @@ int stxo_forward(const stxo_cfg *c, const stxo_tables *tb, const stxo_batch *bt,
  * active_override (b*k bytes, may be NULL): use these hinge flags instead of the oracle's own
  * (margin + d_pos - d_neg > 0, strict).
  * Outputs are dense, caller-zeroed, double; each has a twin `a_*` receiving the sum of the
- * absolute values of the terms added to the same element (the comparison scale):
+ * absolute values of the separately rounded terms that make up the same element (the comparison
+ * scale; e.g. for TransH's gx = gy - a w both |gy| and |a w| count, for TransR's gx = M^T gy every
+ * |gy_a M_aj|):
  *   g_ent : stacked models (n_ent+n_rel) x dim; otherwise n_ent x dim
  *   g_rel : TransH n_rel x dim (d_r); TransR n_rel x rel_dim (r); unused for stacked models
  *   g_w   : TransH n_rel x dim
  *   g_proj: TransR n_rel x rel_dim x dim
- * gy_out (optional, rows x out_dim doubles): dL/dy of every row.                              */
+ * For TransH and TransR, y itself is a computed quantity, so the scale of dL/dy_j used in those sums
+ * is max(|dL/dy_j|, |coef|/dist * sum|terms of y_j|) for the L2 kinds.
+ * gy_out (optional, rows x out_dim doubles): dL/dy of every row.
+ * ambiguous (optional, rows bytes): set to 1 for rows of TransH/TransR with an L1-kind distance in
+ * which some y_j lies within 1e-5 * sum|terms of y_j| of a point where the subgradient jumps (0, or
+ * fractional part 0 / one half on the torus): there an fp32 evaluation may pick the other branch. */
+#define STXO_TIE_WIDTH 1e-5
 int stxo_backward(const stxo_cfg *c, const stxo_tables *tb, const stxo_batch *bt,
                   const uint8_t *active_override,
                   double *g_ent, double *a_ent, double *g_rel, double *a_rel,
-                  double *g_w, double *a_w, double *g_proj, double *a_proj, double *gy_out)
+                  double *g_w, double *a_w, double *g_proj, double *a_proj, double *gy_out,
+                  uint8_t *ambiguous)
 {
     int32_t d = c->dim, n = out_dim(c), b = bt->b, k = bt->k;
     int64_t rows = (int64_t)b * (1 + k);
@@ -363,15 +380,18 @@ int stxo_backward(const stxo_cfg *c, const stxo_tables *tb, const stxo_batch *bt
     double *y = (double *)malloc(sizeof(double) * (size_t)n);
     double *gd = (double *)malloc(sizeof(double) * (size_t)n);
     double *gx = (double *)malloc(sizeof(double) * (size_t)d);
+    double *ax = (double *)malloc(sizeof(double) * (size_t)d); /* sum of |products| that make up gx */
+    double *yabs = (double *)malloc(sizeof(double) * (size_t)n);
+    double *ug = (double *)malloc(sizeof(double) * (size_t)n);  /* scale of each dL/dy_j */
     double *dist = (double *)malloc(sizeof(double) * (size_t)rows);
     double *coef = (double *)calloc((size_t)rows, sizeof(double));
-    if (!x || !y || !gd || !gx || !dist || !coef) return 2;
+    if (!x || !y || !gd || !gx || !ax || !yabs || !ug || !dist || !coef) return 2;
 
     for (int64_t i = 0; i < rows; ++i) {
         int32_t hh, rr, tt;
         batch_row(bt, i, &hh, &rr, &tt);
         row_x(c, tb, hh, rr, tt, x);
-        row_y(c, tb, rr, x, y, NULL);
+        row_y(c, tb, rr, x, y, NULL, NULL);
         dist[i] = row_dist(c, y, n);
     }
     for (int64_t i = 0; i < b; ++i)
@@ -386,52 +406,74 @@ int stxo_backward(const stxo_cfg *c, const stxo_tables *tb, const stxo_batch *bt
         double s = 0.0;
         batch_row(bt, i, &hh, &rr, &tt);
         row_x(c, tb, hh, rr, tt, x);
-        row_y(c, tb, rr, x, y, &s);
+        row_y(c, tb, rr, x, y, &s, yabs);
         row_ddist(c, y, n, dist[i], gd);
         for (int32_t j = 0; j < n; ++j) gd[j] *= coef[i]; /* gd is now dL/dy */
         if (gy_out) memcpy(gy_out + i * n, gd, sizeof(double) * (size_t)n);
+        {
+            int l2kind = c->dist == STXO_L2 || c->dist == STXO_TORUS_L2, amb = 0;
+            for (int32_t j = 0; j < n; ++j) {
+                ug[j] = fabs(gd[j]);
+                if (is_stacked(c)) continue;            /* there y is the exact fp32 x */
+                if (l2kind) {
+                    double alt = dist[i] > 0 ? fabs(coef[i]) / dist[i] * yabs[j] : 0.0;
+                    if (alt > ug[j]) ug[j] = alt;
+                } else if (c->dist == STXO_L1) {
+                    if (fabs(y[j]) <= STXO_TIE_WIDTH * yabs[j]) amb = 1;
+                } else {
+                    double f = y[j] - floor(y[j]);
+                    double dd = fmin(fmin(f, 1.0 - f), fabs(f - 0.5));
+                    if (dd <= STXO_TIE_WIDTH * yabs[j]) amb = 1;
+                }
+            }
+            if (ambiguous) ambiguous[i] = (uint8_t)amb;
+        }
 
         if (is_stacked(c)) {
-            for (int32_t j = 0; j < d; ++j) gx[j] = gd[j];
+            for (int32_t j = 0; j < d; ++j) { gx[j] = gd[j]; ax[j] = fabs(gd[j]); }
             double *gr = g_ent + (c->n_ent + rr) * (int64_t)d, *ar = a_ent + (c->n_ent + rr) * (int64_t)d;
             for (int32_t j = 0; j < d; ++j) { gr[j] += gx[j]; ar[j] += fabs(gx[j]); }
         } else if (c->model == STXO_TRANSH) {
             const float *w = tb->w + (int64_t)rr * d;
             double a = 0.0;
             for (int32_t j = 0; j < d; ++j) a += gd[j] * (double)w[j];
-            for (int32_t j = 0; j < d; ++j) gx[j] = gd[j] - a * (double)w[j];
+            for (int32_t j = 0; j < d; ++j) {
+                gx[j] = gd[j] - a * (double)w[j];
+                ax[j] = ug[j] + fabs(a * (double)w[j]);
+            }
             double *gr = g_rel + (int64_t)rr * d, *ar = a_rel + (int64_t)rr * d;
             double *gw = g_w + (int64_t)rr * d, *aw = a_w + (int64_t)rr * d;
             for (int32_t j = 0; j < d; ++j) {
-                gr[j] += gd[j]; ar[j] += fabs(gd[j]);
+                gr[j] += gd[j]; ar[j] += ug[j];
                 double term = -(a * (double)x[j] + s * gd[j]);
-                gw[j] += term; aw[j] += fabs(term);
+                gw[j] += term; aw[j] += fabs(a * (double)x[j]) + fabs(s) * ug[j];
             }
         } else { /* TransR: y = M x + r */
             int32_t kd = c->rel_dim;
             const float *M = tb->proj + (int64_t)rr * kd * d;
             double *gM = g_proj + (int64_t)rr * kd * d, *aM = a_proj + (int64_t)rr * kd * d;
             double *gr = g_rel + (int64_t)rr * kd, *ar = a_rel + (int64_t)rr * kd;
-            for (int32_t j = 0; j < d; ++j) gx[j] = 0.0;
+            for (int32_t j = 0; j < d; ++j) { gx[j] = 0.0; ax[j] = 0.0; }
             for (int32_t a = 0; a < kd; ++a) {
                 double gya = gd[a];
-                gr[a] += gya; ar[a] += fabs(gya);
+                gr[a] += gya; ar[a] += ug[a];
                 double gq = c->bf16_proj ? (double)bf16_round((float)gya) : gya;
                 for (int32_t j = 0; j < d; ++j) {
                     float m = M[(int64_t)a * d + j], xv = x[j];
                     if (c->bf16_proj) { m = bf16_round(m); xv = bf16_round(xv); }
                     gx[j] += gq * (double)m;
+                    ax[j] += ug[a] * fabs((double)m);
                     double term = gq * (double)xv;
-                    gM[(int64_t)a * d + j] += term; aM[(int64_t)a * d + j] += fabs(term);
+                    gM[(int64_t)a * d + j] += term; aM[(int64_t)a * d + j] += ug[a] * fabs((double)xv);
                 }
             }
         }
         double *gh = g_ent + (int64_t)hh * d, *ah = a_ent + (int64_t)hh * d;
         double *gt = g_ent + (int64_t)tt * d, *at = a_ent + (int64_t)tt * d;
-        for (int32_t j = 0; j < d; ++j) { gh[j] += gx[j]; ah[j] += fabs(gx[j]); }
-        for (int32_t j = 0; j < d; ++j) { gt[j] -= gx[j]; at[j] += fabs(gx[j]); }
+        for (int32_t j = 0; j < d; ++j) { gh[j] += gx[j]; ah[j] += ax[j]; }
+        for (int32_t j = 0; j < d; ++j) { gt[j] -= gx[j]; at[j] += ax[j]; }
     }
-    free(x); free(y); free(gd); free(gx); free(dist); free(coef);
+    free(x); free(y); free(gd); free(gx); free(ax); free(yabs); free(ug); free(dist); free(coef);
     return 0;
 }
 
@@ -501,7 +543,7 @@ int stxo_grad_column_stacked(const stxo_cfg *c, const stxo_tables *tb, const stx
         if (i < b) { for (int32_t kk = 0; kk < k; ++kk) if (active[i * k + kk]) coef += scale; }
         else if (active[i - b]) coef = -scale;
         row_x(c, tb, hh, rr, tt, x);
-        row_y(c, tb, rr, x, y, NULL);
+        row_y(c, tb, rr, x, y, NULL, NULL);
         double dist = row_dist(c, y, d);
         row_ddist(c, y, d, dist, gd);
         for (int32_t j = 0; j < d; ++j) {

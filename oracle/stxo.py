@@ -71,7 +71,7 @@ def lib():
         _lib.stxo_forward.restype = C.c_int
         _lib.stxo_forward.argtypes = [C.c_void_p] * 7
         _lib.stxo_backward.restype = C.c_int
-        _lib.stxo_backward.argtypes = [C.c_void_p] * 13
+        _lib.stxo_backward.argtypes = [C.c_void_p] * 14
         _lib.stxo_sgd.restype = None
         _lib.stxo_sgd.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p,
                                   C.c_float, C.c_int32]
@@ -253,6 +253,7 @@ class Grads:
     proj: np.ndarray | None = None
     proj_abs: np.ndarray | None = None
     gy: np.ndarray | None = None
+    ambiguous: np.ndarray | None = None   # per row: an L1-kind subgradient of TransH/TransR sits on a jump
 
 
 def backward(cfg: Config, tb: Tables, bt: Batch, active=None, want_gy: bool = False) -> Grads:
@@ -268,10 +269,11 @@ def backward(cfg: Config, tb: Tables, bt: Batch, active=None, want_gy: bool = Fa
     if want_gy:
         g.gy = np.empty((bt.rows, cfg.out_dim), np.float64)
     act = None if active is None else np.ascontiguousarray(active, dtype=np.uint8)
+    g.ambiguous = np.zeros(bt.rows, np.uint8)
     cc, ct, cb = cfg.c(), tb.c(), bt.c()
     rc = lib().stxo_backward(C.byref(cc), C.byref(ct), C.byref(cb), _p(act),
                              _p(g.ent), _p(g.ent_abs), _p(g.rel), _p(g.rel_abs), _p(g.w), _p(g.w_abs),
-                             _p(g.proj), _p(g.proj_abs), _p(g.gy))
+                             _p(g.proj), _p(g.proj_abs), _p(g.gy), _p(g.ambiguous))
     if rc != 0:
         raise RuntimeError(f"stxo_backward failed with code {rc}")
     return g

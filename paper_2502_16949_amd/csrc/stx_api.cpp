@@ -115,7 +115,7 @@ stx_status stx_create(const stx_config *cfg, void *workspace, size_t workspace_b
     stx_status s = check_config(cfg);
     if (s != STX_OK) return s;
     if (!workspace) return STX_ERR_NULL;
-    if (cfg->model == STX_TRANSH || cfg->model == STX_TRANSR) return STX_ERR_UNSUPPORTED;
+    if (cfg->model == STX_TRANSR) return STX_ERR_UNSUPPORTED;
     Layout L = make_layout(cfg);
     if (workspace_bytes < L.total || ((uintptr_t)workspace & 255u)) return STX_ERR_WORKSPACE;
     stx_ctx *c = new (std::nothrow) stx_ctx();
@@ -224,8 +224,9 @@ stx_status stx_forward(stx_ctx *ctx, const stx_incidence *inc, const stx_params 
     s = check_params(ctx, p);
     if (s != STX_OK) return s;
     if (!scores || !loss) return STX_ERR_NULL;
-    if (!stacked(ctx)) return STX_ERR_UNSUPPORTED;
-    s = launch_forward_stacked(ctx, inc, p, scores, loss);
+    if (stacked(ctx)) s = launch_forward_stacked(ctx, inc, p, scores, loss);
+    else if (ctx->cfg.model == STX_TRANSH) s = launch_forward_transh(ctx, inc, p, scores, loss);
+    else return STX_ERR_UNSUPPORTED;
     if (s == STX_OK) {
         ctx->fwd_inc = inc;
         ctx->fwd_rows = inc->n_rows;
@@ -241,10 +242,21 @@ stx_status stx_backward(stx_ctx *ctx, const stx_incidence *inc, const stx_params
     s = check_params(ctx, p);
     if (s != STX_OK) return s;
     if (!g || !g->rows) return STX_ERR_NULL;
+    if (ctx->cfg.model == STX_TRANSH && !g->w_rows) return STX_ERR_NULL;
     if (ctx->fwd_inc != inc || ctx->fwd_rows != inc->n_rows) return STX_ERR_STATE;
-    if (!stacked(ctx)) return STX_ERR_UNSUPPORTED;
-    // dL/dX = A^T G over all columns of X = [E;R] (Appendix G)
-    return launch_seg_reduce(ctx, inc, 0, inc->nnz, ctx->gbuf[0], ctx->cfg.dim, ctx->cfg.dim, g->rows, ctx->ld);
+    const int dim = ctx->cfg.dim;
+    const int64_t ent_end = 2 * inc->n_rows;   // sorted entries of entity columns come first, then relation columns
+    if (stacked(ctx))   // dL/dX = A^T G over all columns of X = [E;R] (Appendix G)
+        return launch_seg_reduce(ctx, inc, 0, inc->nnz, ctx->gbuf[0], ctx->gbuf[0], inc->nnz, dim, dim, g->rows,
+                                 ctx->ld);
+    if (ctx->cfg.model == STX_TRANSH) {
+        // entity columns: signed sums of gx; relation columns: sums of gy (-> d_r) and of gw (-> w_r)
+        s = launch_seg_reduce(ctx, inc, 0, inc->nnz, ctx->gbuf[0], ctx->gbuf[1], ent_end, dim, dim, g->rows, ctx->ld);
+        if (s != STX_OK) return s;
+        return launch_seg_reduce(ctx, inc, ent_end, inc->nnz, ctx->gbuf[2], ctx->gbuf[2], inc->nnz, dim, dim,
+                                 g->w_rows, ctx->ld);
+    }
+    return STX_ERR_UNSUPPORTED;
 }
 
 stx_status stx_sgd_step(stx_ctx *ctx, stx_params *p, const stx_incidence *inc, const stx_grads *g, float lr)
@@ -256,10 +268,17 @@ stx_status stx_sgd_step(stx_ctx *ctx, stx_params *p, const stx_incidence *inc, c
     if (s != STX_OK) return s;
     if (!g || !g->rows) return STX_ERR_NULL;
     if (!(lr == lr)) return STX_ERR_BAD_ARG;
-    if (!stacked(ctx)) return STX_ERR_UNSUPPORTED;
+    if (ctx->cfg.model == STX_TRANSH && !g->w_rows) return STX_ERR_NULL;
+    if (ctx->cfg.model == STX_TRANSR) return STX_ERR_UNSUPPORTED;
     ctx->fwd_inc = nullptr;   // the tables change: a stored forward no longer matches them
-    return launch_sgd_rows(ctx, inc, p->ent, 0, ctx->cfg.n_ent + ctx->cfg.n_rel, g->rows, ctx->ld, ctx->cfg.dim, lr,
-                           ctx->cfg.model == STX_TORUSE ? 1 : 0);
+    const int dim = ctx->cfg.dim;
+    if (stacked(ctx)) {
+        SgdTables T{p->ent, dim, ctx->cfg.model == STX_TORUSE ? 1 : 0, ctx->cfg.n_ent + ctx->cfg.n_rel, nullptr, dim,
+                    nullptr, 0};
+        return launch_sgd_rows(ctx, inc, T, g->rows, nullptr, lr);
+    }
+    SgdTables T{p->ent, dim, 0, ctx->cfg.n_ent, p->rel, dim, p->w, (ctx->cfg.flags & STX_FLAG_RENORM_W) ? 2 : 0};
+    return launch_sgd_rows(ctx, inc, T, g->rows, g->w_rows, lr);
 }
 
 const char *stx_status_string(stx_status s)

@@ -18,8 +18,7 @@
 //
 // Every output row is written exactly once and every sum has a fixed association order, so results are
 // bitwise reproducible from run to run.
-#include "stx_device.h"
-#include "stx_internal.h"
+#include "stx_rowops.h"
 
 namespace stx {
 
@@ -64,9 +63,10 @@ __device__ inline void store_row(float *__restrict__ p, int d4, int lig, const A
 template <int LPR, int ITERS>
 __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restrict__ packed,
                                                          const int32_t *__restrict__ seg_id, int32_t e_begin,
-                                                         int32_t e_end, const float *__restrict__ src, int ld_src,
-                                                         int d4, float *__restrict__ out_rows, int ld_out,
-                                                         float *__restrict__ partials)
+                                                         int32_t e_end, const float *__restrict__ src_a,
+                                                         const float *__restrict__ src_b, int32_t split,
+                                                         int ld_src, int d4, float *__restrict__ out_rows,
+                                                         int ld_out, float *__restrict__ partials)
 {
     constexpr int GROUPS = kThreads / LPR;
     constexpr int UNROLL = ITERS == 1 ? 8 : (ITERS == 2 ? 4 : 2);
@@ -121,7 +121,9 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
             for (int u = 0; u < UNROLL; ++u) {
                 const int jj = j0 + u;
                 mu[u] = __shfl(meta, jj < LPR ? jj : LPR - 1, LPR);
-                if (jj < n) load_row<LPR, ITERS>(src + (int64_t)(mu[u] >> 2) * ld_src, d4, lig, v[u]);
+                if (jj < n)   // entries before `split` read src_a, the rest src_b (entity vs relation columns)
+                    load_row<LPR, ITERS>((ec0 + jj < split ? src_a : src_b) + (int64_t)(mu[u] >> 2) * ld_src, d4,
+                                         lig, v[u]);
             }
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
@@ -233,65 +235,82 @@ __global__ __launch_bounds__(kThreads) void k_seg_fixup(const int32_t *__restric
     }
 }
 
-// Row update for the segments whose column lies in [col_lo, col_hi): table row (col - col_lo).
-// mode 0: v - lr*g.  mode 1: then the fractional part (TorusE, Sec. 4.6).  mode 2: then unit length.
+// Row update for every segment s (column c = touched_cols[s]):
+//   c <  n_split : table_a row c            -= lr * grad_rows[s]   (width 4*d4_a, mode_a)
+//   c >= n_split : table_b row c - n_split  -= lr * grad_rows[s]   (width 4*d4_b, mode 0), if table_b
+//                  table_w row c - n_split  -= lr * w_rows[s]      (width 4*d4_a, mode_w), if table_w
+// Each product and each difference is rounded once.  mode 1: then keep the fractional part (TorusE,
+// Sec. 4.6).  mode 2: then rescale the row to unit length (TransH normals).
+template <int LPR, int ITERS>
+__device__ inline void sgd_row(float *__restrict__ row, const float *__restrict__ grad, int d4, int lig, float lr,
+                               int mode)
+{
+    Acc<ITERS> x, g;
+    load_row<LPR, ITERS>(row, d4, lig, x);
+    load_row<LPR, ITERS>(grad, d4, lig, g);
+    float ss = 0.f;
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        float *xv = &x.v[it].x;
+        const float *gv = &g.v[it].x;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            float step = lr * gv[q];
+            float nv = xv[q] - step;
+            if (mode == 1) {
+                nv = nv - floorf(nv);
+                if (nv >= 1.0f) nv = 0.0f;
+            }
+            xv[q] = nv;
+            ss += nv * nv;
+        }
+    }
+    if (mode == 2) {
+        ss = group_sum<LPR>(ss);
+        if (ss > 0.f) {
+            const float inv = 1.0f / sqrtf(ss);
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) {
+                x.v[it].x *= inv; x.v[it].y *= inv; x.v[it].z *= inv; x.v[it].w *= inv;
+            }
+        }
+    }
+    store_row<LPR, ITERS>(row, d4, lig, x);
+}
+
 template <int LPR, int ITERS>
 __global__ __launch_bounds__(kThreads) void k_sgd_rows(const int32_t *__restrict__ touched_cols,
                                                        const int32_t *__restrict__ n_touched,
-                                                       float *__restrict__ table, int32_t col_lo, int32_t col_hi,
-                                                       const float *__restrict__ grad_rows, int ld, int d4,
-                                                       float lr, int mode)
+                                                       float *__restrict__ table_a, int d4_a, int mode_a,
+                                                       int32_t n_split, float *__restrict__ table_b, int d4_b,
+                                                       float *__restrict__ table_w, int mode_w,
+                                                       const float *__restrict__ grad_rows,
+                                                       const float *__restrict__ w_rows, int ld, float lr)
 {
     constexpr int GROUPS = kThreads / LPR;
     const int lig = threadIdx.x % LPR, grp = threadIdx.x / LPR;
     const int32_t U = n_touched[0];
-    const int width = d4 * 4;
     for (int64_t s = (int64_t)blockIdx.x * GROUPS + grp; s < U; s += (int64_t)gridDim.x * GROUPS) {
         const int32_t col = touched_cols[s];
-        if (col < col_lo || col >= col_hi) continue;
-        float *row = table + (int64_t)(col - col_lo) * width;
-        Acc<ITERS> x, g;
-        load_row<LPR, ITERS>(row, d4, lig, x);
-        load_row<LPR, ITERS>(grad_rows + s * ld, d4, lig, g);
-        float ss = 0.f;
-#pragma unroll
-        for (int it = 0; it < ITERS; ++it) {
-            float *xv = &x.v[it].x;
-            const float *gv = &g.v[it].x;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float step = lr * gv[q];
-                float nv = xv[q] - step;
-                if (mode == 1) {
-                    nv = nv - floorf(nv);
-                    if (nv >= 1.0f) nv = 0.0f;
-                }
-                xv[q] = nv;
-                ss += nv * nv;
-            }
+        if (col < n_split) {
+            sgd_row<LPR, ITERS>(table_a + (int64_t)col * d4_a * 4, grad_rows + s * ld, d4_a, lig, lr, mode_a);
+        } else {
+            const int64_t r = col - n_split;
+            if (table_b) sgd_row<LPR, ITERS>(table_b + r * d4_b * 4, grad_rows + s * ld, d4_b, lig, lr, 0);
+            if (table_w) sgd_row<LPR, ITERS>(table_w + r * d4_a * 4, w_rows + s * ld, d4_a, lig, lr, mode_w);
         }
-        if (mode == 2) {
-            ss = group_sum<LPR>(ss);
-            if (ss > 0.f) {
-                const float inv = 1.0f / sqrtf(ss);
-#pragma unroll
-                for (int it = 0; it < ITERS; ++it) {
-                    x.v[it].x *= inv; x.v[it].y *= inv; x.v[it].z *= inv; x.v[it].w *= inv;
-                }
-            }
-        }
-        store_row<LPR, ITERS>(row, d4, lig, x);
     }
 }
 
 // ---- dispatch --------------------------------------------------------------------------------------
 template <int LPR, int ITERS>
-static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_t e_end, const float *src, int ld_src,
-                   int width, float *out_rows, int ld_out)
+static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_t e_end, const float *src_a,
+                   const float *src_b, int32_t split, int ld_src, int width, float *out_rows, int ld_out)
 {
     const int ntiles = (e_end - e_begin + kSegTile - 1) / kSegTile;
     hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS>), dim3(ntiles), dim3(kThreads), 0, c->stream, inc->at_packed,
-                       inc->at_seg_id, e_begin, e_end, src, ld_src, width / 4, out_rows, ld_out, c->partials);
+                       inc->at_seg_id, e_begin, e_end, src_a, src_b, split, ld_src, width / 4, out_rows, ld_out,
+                       c->partials);
     if (ntiles > 1)
         hipLaunchKernelGGL((k_seg_fixup<LPR, ITERS>), dim3(ntiles - 1), dim3(kThreads), 0, c->stream,
                            inc->at_packed, inc->at_seg_id, inc->at_seg_ptr, e_begin, e_end, width / 4, out_rows,
@@ -299,8 +318,8 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
 }
 
 template <int LPR, int ITERS>
-static void sgd_go(stx_ctx *c, const stx_incidence *inc, float *table, int32_t col_lo, int32_t col_hi,
-                   const float *grad_rows, int ld, int width, float lr, int mode)
+static void sgd_go(stx_ctx *c, const stx_incidence *inc, const SgdTables &T, const float *grad_rows,
+                   const float *w_rows, float lr)
 {
     constexpr int GROUPS = kThreads / LPR;
     int64_t cap = inc->nnz < c->cfg.n_ent + c->cfg.n_rel ? inc->nnz : c->cfg.n_ent + c->cfg.n_rel;
@@ -308,36 +327,27 @@ static void sgd_go(stx_ctx *c, const stx_incidence *inc, float *table, int32_t c
     if (blocks > 8192) blocks = 8192;   // grid-stride beyond this
     if (blocks < 1) blocks = 1;
     hipLaunchKernelGGL((k_sgd_rows<LPR, ITERS>), dim3((unsigned)blocks), dim3(kThreads), 0, c->stream,
-                       inc->at_touched_cols, inc->n_touched, table, col_lo, col_hi, grad_rows, ld, width / 4, lr,
-                       mode);
+                       inc->at_touched_cols, inc->n_touched, T.table_a, T.width_a / 4, T.mode_a, (int32_t)T.n_split,
+                       T.table_b, T.width_b / 4, T.table_w, T.mode_w, grad_rows, w_rows, c->ld, lr);
 }
 
-#define STX_DISPATCH_ROW(L, FN, ...)                                                      \
-    do {                                                                                  \
-        if (L.lpr == 8 && L.iters == 1) FN<8, 1>(__VA_ARGS__);                            \
-        else if (L.lpr == 16 && L.iters == 1) FN<16, 1>(__VA_ARGS__);                     \
-        else if (L.lpr == 32 && L.iters == 1) FN<32, 1>(__VA_ARGS__);                     \
-        else if (L.lpr == 64 && L.iters == 1) FN<64, 1>(__VA_ARGS__);                     \
-        else if (L.lpr == 64 && L.iters == 2) FN<64, 2>(__VA_ARGS__);                     \
-        else if (L.lpr == 64 && L.iters == 3) FN<64, 3>(__VA_ARGS__);                     \
-        else FN<64, 4>(__VA_ARGS__);                                                      \
-    } while (0)
-
-stx_status launch_seg_reduce(stx_ctx *c, const stx_incidence *inc, int64_t e_begin, int64_t e_end, const float *src,
-                             int ld_src, int width, float *out_rows, int ld_out)
+stx_status launch_seg_reduce(stx_ctx *c, const stx_incidence *inc, int64_t e_begin, int64_t e_end,
+                             const float *src_a, const float *src_b, int64_t split, int ld_src, int width,
+                             float *out_rows, int ld_out)
 {
     if (e_end <= e_begin) return STX_OK;
     Launch L = row_launch(width);
-    STX_DISPATCH_ROW(L, seg_go, c, inc, (int32_t)e_begin, (int32_t)e_end, src, ld_src, width, out_rows, ld_out);
+    STX_DISPATCH_ROW(L, seg_go, c, inc, (int32_t)e_begin, (int32_t)e_end, src_a, src_b, (int32_t)split, ld_src, width,
+                     out_rows, ld_out);
     return hip_ok(hipGetLastError());
 }
 
-stx_status launch_sgd_rows(stx_ctx *c, const stx_incidence *inc, float *table, int64_t col_lo, int64_t col_hi,
-                           const float *grad_rows, int ld, int width, float lr, int mode)
+stx_status launch_sgd_rows(stx_ctx *c, const stx_incidence *inc, const SgdTables &T, const float *grad_rows,
+                           const float *w_rows, float lr)
 {
     if (inc->n_rows == 0) return STX_OK;
-    Launch L = row_launch(width);
-    STX_DISPATCH_ROW(L, sgd_go, c, inc, table, (int32_t)col_lo, (int32_t)col_hi, grad_rows, ld, width, lr, mode);
+    Launch L = row_launch(T.width_a > T.width_b ? T.width_a : T.width_b);
+    STX_DISPATCH_ROW(L, sgd_go, c, inc, T, grad_rows, w_rows, lr);
     return hip_ok(hipGetLastError());
 }
 

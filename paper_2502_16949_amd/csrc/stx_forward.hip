@@ -8,37 +8,9 @@
 // The fused forward kernel gives one group a positive row and its k negatives: it computes the
 // distances (Sec. 4.3, 4.6), the margin-ranking hinge (Sec. 5.3) and writes dL/dx of each of those
 // rows straight away, so x itself never goes to memory.
-#include "stx_device.h"
-#include "stx_internal.h"
+#include "stx_rowops.h"
 
 namespace stx {
-
-template <int ITERS>
-struct RowVec {
-    float4 v[ITERS];
-};
-
-// x = (X[c0] + X[c1]) - X[c2] (hrt) or X[c0] - X[c2] (ht): each operation rounded once, in this order.
-template <int LPR, int ITERS, bool HRT>
-__device__ inline void gather_row(const float *__restrict__ X, int dim, int d4, int lig, int32_t c0, int32_t c1,
-                                  int32_t c2, RowVec<ITERS> &x)
-{
-    const float *p0 = X + (int64_t)c0 * dim, *p1 = X + (int64_t)c1 * dim, *p2 = X + (int64_t)c2 * dim;
-#pragma unroll
-    for (int it = 0; it < ITERS; ++it) {
-        int j = lig + it * LPR;
-        if (j < d4) {
-            float4 a = ld4(p0 + 4 * j), c = ld4(p2 + 4 * j);
-            if (HRT) {
-                float4 b = ld4(p1 + 4 * j);
-                a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
-            }
-            x.v[it] = make_float4(a.x - c.x, a.y - c.y, a.z - c.z, a.w - c.w);
-        } else {
-            x.v[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-        }
-    }
-}
 
 template <int LPR, int ITERS, bool HRT>
 __global__ __launch_bounds__(kThreads) void k_spmm(const int32_t *__restrict__ colidx, const float *__restrict__ X,
@@ -58,53 +30,11 @@ __global__ __launch_bounds__(kThreads) void k_spmm(const int32_t *__restrict__ c
     }
 }
 
-// ---- distance pieces -------------------------------------------------------------------------------
-template <int DIST>
-__device__ inline float term(float y)
-{
-    if (DIST == STX_L1) return fabsf(y);
-    if (DIST == STX_L2) return y * y;
-    float f = y - floorf(y);
-    float m = fminf(f, 1.0f - f);
-    return DIST == STX_TORUS_L1 ? m : m * m;
-}
-template <int DIST>
-__device__ inline float finish(float acc)
-{
-    return (DIST == STX_L2 || DIST == STX_TORUS_L2) ? sqrtf(acc) : acc;
-}
-// d(dist)/dy times coef.  cs = coef for the L1 kinds, coef / dist (0 if dist == 0) for the L2 kinds.
-template <int DIST>
-__device__ inline float dterm(float y, float cs)
-{
-    if (DIST == STX_L1) return y > 0.f ? cs : (y < 0.f ? -cs : 0.f);
-    if (DIST == STX_L2) return y * cs;
-    float f = y - floorf(y);
-    float sg = (f > 0.f && f < 0.5f) ? 1.f : (f > 0.5f ? -1.f : 0.f);
-    if (DIST == STX_TORUS_L1) return sg * cs;
-    return sg * fminf(f, 1.0f - f) * cs;
-}
-
-template <int LPR, int ITERS, int DIST>
-__device__ inline float row_distance(const RowVec<ITERS> &x)
-{
-    float acc = 0.f;
-#pragma unroll
-    for (int it = 0; it < ITERS; ++it) {
-        acc += term<DIST>(x.v[it].x);
-        acc += term<DIST>(x.v[it].y);
-        acc += term<DIST>(x.v[it].z);
-        acc += term<DIST>(x.v[it].w);
-    }
-    return finish<DIST>(group_sum<LPR>(acc));
-}
-
 template <int LPR, int ITERS, int DIST>
 __device__ inline void write_grad_row(float *__restrict__ g, int d4, int lig, const RowVec<ITERS> &x, float coef,
                                       float dist)
 {
-    float cs = coef;
-    if (DIST == STX_L2 || DIST == STX_TORUS_L2) cs = dist > 0.f ? coef / dist : 0.f;
+    const float cs = coef_scale<DIST>(coef, dist);
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
         int j = lig + it * LPR;
@@ -177,6 +107,15 @@ __global__ __launch_bounds__(kThreads) void k_forward_stacked(const int32_t *__r
 
 __global__ void k_zero_loss(float *loss) { loss[0] = 0.f; }
 
+stx_status launch_finish_loss(stx_ctx *c, int n_partials, float scale, float *loss)
+{
+    if (n_partials <= 0) hipLaunchKernelGGL(k_zero_loss, dim3(1), dim3(1), 0, c->stream, loss);
+    else
+        hipLaunchKernelGGL(k_finish_loss, dim3(1), dim3(kThreads), 0, c->stream, c->loss_partials, n_partials, scale,
+                           loss);
+    return hip_ok(hipGetLastError());
+}
+
 // ---- dispatch --------------------------------------------------------------------------------------
 template <int LPR, int ITERS>
 static void spmm_go(stx_ctx *c, const stx_incidence *inc, const stx_params *p, float *out, bool hrt)
@@ -190,17 +129,6 @@ static void spmm_go(stx_ctx *c, const stx_incidence *inc, const stx_params *p, f
         hipLaunchKernelGGL((k_spmm<LPR, ITERS, false>), grid, dim3(kThreads), 0, c->stream, inc->a_colidx, p->ent,
                            inc->n_rows, c->cfg.dim, 0, out);
 }
-
-#define STX_DISPATCH_ROW(L, FN, ...)                                                      \
-    do {                                                                                  \
-        if (L.lpr == 8 && L.iters == 1) FN<8, 1>(__VA_ARGS__);                            \
-        else if (L.lpr == 16 && L.iters == 1) FN<16, 1>(__VA_ARGS__);                     \
-        else if (L.lpr == 32 && L.iters == 1) FN<32, 1>(__VA_ARGS__);                     \
-        else if (L.lpr == 64 && L.iters == 1) FN<64, 1>(__VA_ARGS__);                     \
-        else if (L.lpr == 64 && L.iters == 2) FN<64, 2>(__VA_ARGS__);                     \
-        else if (L.lpr == 64 && L.iters == 3) FN<64, 3>(__VA_ARGS__);                     \
-        else FN<64, 4>(__VA_ARGS__);                                                      \
-    } while (0)
 
 stx_status launch_spmm(stx_ctx *c, const stx_incidence *inc, const stx_params *p, float *out)
 {
@@ -228,17 +156,13 @@ static void forward_go(stx_ctx *c, const stx_incidence *inc, const stx_params *p
     default: STX_FWD(STX_TORUS_L2); break;
     }
 #undef STX_FWD
-    hipLaunchKernelGGL(k_finish_loss, dim3(1), dim3(kThreads), 0, c->stream, c->loss_partials, (int)grid.x, scale,
-                       loss);
+    launch_finish_loss(c, (int)grid.x, scale, loss);
 }
 
 stx_status launch_forward_stacked(stx_ctx *c, const stx_incidence *inc, const stx_params *p, float *scores,
                                   float *loss)
 {
-    if (inc->n_rows == 0) {
-        hipLaunchKernelGGL(k_zero_loss, dim3(1), dim3(1), 0, c->stream, loss);
-        return hip_ok(hipGetLastError());
-    }
+    if (inc->n_rows == 0) return launch_finish_loss(c, 0, 1.0f, loss);
     float scale = 1.0f;
     if (c->cfg.reduce == STX_MEAN && inc->k > 0) scale = 1.0f / (float)((int64_t)inc->b * inc->k);
     Launch L = row_launch(c->cfg.dim);

@@ -66,10 +66,21 @@ stx_status launch_clear_ctrl(stx_ctx *);
 stx_status launch_spmm(stx_ctx *, const stx_incidence *, const stx_params *, float *c_out);
 stx_status launch_forward_stacked(stx_ctx *, const stx_incidence *, const stx_params *, float *scores, float *loss);
 // stx_backward.hip
-stx_status launch_seg_reduce(stx_ctx *, const stx_incidence *, int64_t e_begin, int64_t e_end, const float *src,
-                             int ld_src, int width, float *out_rows, int ld_out);
-stx_status launch_sgd_rows(stx_ctx *, const stx_incidence *, float *table, int64_t col_lo, int64_t col_hi,
-                           const float *grad_rows, int ld, int width, float lr, int mode);
+// out_rows[segment] = signed sum of source rows over the sorted entries [e_begin, e_end); entries
+// before `split` read src_a, the others src_b (both with ld_src floats per row, `width` of them used).
+stx_status launch_seg_reduce(stx_ctx *, const stx_incidence *, int64_t e_begin, int64_t e_end, const float *src_a,
+                             const float *src_b, int64_t split, int ld_src, int width, float *out_rows, int ld_out);
+struct SgdTables {
+    float *table_a; int width_a; int mode_a;   // columns [0, n_split)
+    int64_t n_split;
+    float *table_b; int width_b;               // columns >= n_split, gradient in the same rows array (may be null)
+    float *table_w; int mode_w;                // columns >= n_split, gradient in w_rows, width_a (may be null)
+};
+stx_status launch_sgd_rows(stx_ctx *, const stx_incidence *, const SgdTables &, const float *grad_rows,
+                           const float *w_rows, float lr);
+// stx_transh.hip
+stx_status launch_forward_transh(stx_ctx *, const stx_incidence *, const stx_params *, float *scores, float *loss);
+stx_status launch_finish_loss(stx_ctx *, int n_partials, float scale, float *loss);
 
 inline stx_status hip_ok(hipError_t e) { return e == hipSuccess ? STX_OK : STX_ERR_HIP; }
 

@@ -111,16 +111,19 @@ def resolve_active(scores, fw: stxo.Forward, bt: stxo.Batch, margin: float, tol=
     return act_gpu
 
 
-def check_grad_rows(cols, rows, g_dense, g_abs, width, tol=REL_TOL, what="rows"):
+def check_grad_rows(cols, rows, g_dense, g_abs, width, tol=REL_TOL, what="rows", all_cols=None):
     """Row-sparse GPU gradient against the oracle's dense table: elementwise within tol * sum|terms|,
-    and in the infinity norm within tol * ||ref||_inf."""
+    and in the infinity norm within tol * ||ref||_inf.  all_cols: every column the GPU listed (when
+    `cols` is a subset of them), for the check that unlisted columns received nothing."""
     ref = g_dense[cols][:, :width]
     scale = g_abs[cols][:, :width]
+    if len(cols) == 0:
+        return
     err = np.abs(rows[:, :width].astype(np.float64) - ref)
     bad = err > tol * scale + 1e-30
     assert not bad.any(), (what, int(bad.sum()), float(err.max()), float((err / (scale + 1e-30)).max()))
     assert err.max() <= tol * max(np.abs(ref).max(), 1e-30) + 1e-30, (what, err.max(), np.abs(ref).max())
     # columns not in the touched list received nothing
     mask = np.ones(g_dense.shape[0], bool)
-    mask[cols] = False
+    mask[cols if all_cols is None else all_cols] = False
     assert not np.any(g_abs[mask]), what

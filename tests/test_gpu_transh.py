@@ -1,0 +1,120 @@
+"""GPU parity for the TransH step (hyperplane projection layered on the ht product) against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import stxo
+from paper_2502_16949_amd import binding as B
+from paper_2502_16949_amd import workloads as W
+from tests import gpu_util as G
+from tests.util import oracle_batch, oracle_config, oracle_tables
+
+pytestmark = pytest.mark.gpu
+
+
+def check_transh_step(wl, tabs, bt, reduce, renorm=True, lr=0.01):
+    cfg = oracle_config(wl, reduce=reduce)
+    m = G.GpuModel(wl, tabs, reduce=reduce, flags=B.STX_FLAG_RENORM_W if renorm else 0)
+    m.build(bt)
+    # the ht product: E[h] - E[t], bitwise
+    out = torch.empty(bt.rows, wl.dim, dtype=torch.float32, device=G.DEV)
+    B.stx_spmm(m.ctx, m.inc, m.params, out)
+    m.forward()
+    scores, loss = m.scores_numpy()
+    fw = stxo.forward(cfg, oracle_tables(tabs), bt)
+    assert np.array_equal(out.cpu().numpy(), fw.x)
+    G.check_scores_and_loss(scores, loss, fw, reduce == B.STX_MEAN)
+    active = G.resolve_active(scores, fw, bt, wl.margin)
+    g = stxo.backward(cfg, oracle_tables(tabs), bt, active=active)
+    m.backward()
+    torch.cuda.synchronize()
+    u = int(m.inc.n_touched.item())
+    cols = m.inc.at_touched_cols[:u].cpu().numpy()
+    rows = m.grads.rows[:u].cpu().numpy()
+    w_rows = m.grads.w_rows[:u].cpu().numpy()
+    is_ent = cols < wl.n_ent
+    # Rows in which an L1-kind subgradient sits on a jump (y_j within 1e-5 of its own rounding scale
+    # from 0) may legitimately take the other branch in fp32: the columns they feed are only checked
+    # loosely.  They must be rare.
+    amb = g.ambiguous.astype(bool)
+    assert amb.mean() <= 0.01
+    hh = np.concatenate([bt.h, bt.nh]); tt = np.concatenate([bt.t, bt.nt]); rr = np.concatenate([bt.r, np.repeat(bt.r, bt.k)])
+    loose_ent = np.zeros(wl.n_ent, bool); loose_ent[hh[amb]] = True; loose_ent[tt[amb]] = True
+    loose_rel = np.zeros(wl.n_rel, bool); loose_rel[rr[amb]] = True
+    ec, rc = cols[is_ent], cols[~is_ent] - wl.n_ent
+    ke, kr = ~loose_ent[ec], ~loose_rel[rc]
+    G.check_grad_rows(ec[ke], rows[is_ent][ke], g.ent, g.ent_abs, wl.dim, what="dE", all_cols=ec)
+    G.check_grad_rows(rc[kr], rows[~is_ent][kr], g.rel, g.rel_abs, wl.dim, what="d(d_r)", all_cols=rc)
+    G.check_grad_rows(rc[kr], w_rows[~is_ent][kr], g.w, g.w_abs, wl.dim, what="dw", all_cols=rc)
+    scale = 1.0 / (bt.b * bt.k) if reduce == B.STX_MEAN else 1.0
+    for got, ref, sel in ((rows[is_ent][~ke], g.ent[ec[~ke]], None), (rows[~is_ent][~kr], g.rel[rc[~kr]], None)):
+        if len(got):                                                    # a flipped sign moves an element by <= 2*coef
+            assert np.abs(got - ref).max() <= 2.0 * bt.k * scale * amb.sum() + 1e-4
+    # update
+    tb = oracle_tables(tabs)
+    m_ent, m_rel = stxo.touched_masks(cfg, bt)
+    stxo.sgd(tb.ent, g.ent, m_ent, lr, 0)
+    stxo.sgd(tb.rel, g.rel, m_rel, lr, 0)
+    stxo.sgd(tb.w, g.w, m_rel, lr, 2 if renorm else 0)
+    m.sgd(lr)
+    torch.cuda.synchronize()
+    for name, new, ref, old, gabs, mask in (("ent", m.params.ent, tb.ent, tabs["ent"], g.ent_abs, m_ent),
+                                            ("rel", m.params.rel, tb.rel, tabs["rel"], g.rel_abs, m_rel),
+                                            ("w", m.params.w, tb.w, tabs["w"], g.w_abs, m_rel)):
+        new = new.cpu().numpy()
+        assert np.array_equal(new[mask == 0], old[mask == 0]), name
+        diff = np.abs(new.astype(np.float64) - ref)
+        slack = 4 if (name == "w" and renorm) else 1                    # the rescale adds a norm and a product
+        assert np.all(diff <= slack * (G.REL_TOL * (lr * gabs + np.abs(old) * 2.0**-23) + 2.0**-23)), (name, diff.max())
+    if renorm:
+        wn = np.linalg.norm(m.params.w.cpu().numpy().astype(np.float64), axis=1)
+        np.testing.assert_allclose(wn[m_rel == 1], 1.0, atol=1e-6)
+
+
+CASES = [
+    # dist, n_ent, n_rel, b, k, dim, zipf
+    ("l2", 1000, 20, 1024, 1, 128, 1.1),
+    ("l1", 400, 9, 777, 3, 128, 1.1),
+    ("l2", 64, 4, 2500, 2, 100, 0.0),
+    ("l2", 300, 5, 300, 1, 8, 0.0),
+    ("l1", 300, 5, 300, 2, 256, 0.0),
+    ("l2", 200, 5, 200, 1, 1024, 0.0),
+    ("torus_l2", 300, 6, 400, 2, 64, 1.1),
+]
+
+
+@pytest.mark.parametrize("reduce", [B.STX_SUM, B.STX_MEAN])
+@pytest.mark.parametrize("dist,n_ent,n_rel,b,k,dim,zipf", CASES)
+def test_transh_step_matches_oracle(dist, n_ent, n_rel, b, k, dim, zipf, reduce):
+    wl = W.Workload("case", 7, "transh", dist, n_ent, n_rel, b, dim, dim, b, k, 1.0, 0.01, 1, zipf, zipf)
+    seed = dim + b
+    h, r, t = W.make_graph(wl.scaled(index=seed))
+    tabs = W.make_tables(wl.scaled(index=seed))
+    bt = oracle_batch(wl, h, r, t, 0, b, seed=seed)
+    check_transh_step(wl, tabs, bt, reduce, renorm=(reduce == B.STX_SUM))
+
+
+@pytest.mark.parametrize("which", ["first", "last_partial"])
+def test_transh_config_full_batch(which):
+    wl = W.WORKLOADS["transh"]
+    h, r, t = W.make_graph(wl)
+    tabs = W.make_tables(wl)
+    lo, hi = W.batch_slices(wl)[0 if which == "first" else -1]
+    check_transh_step(wl, tabs, oracle_batch(wl, h, r, t, lo, hi), B.STX_SUM, lr=wl.lr)
+
+
+def test_transh_zero_normal_is_a_translation():
+    """w_r = 0 reduces TransH to a translation by d_r: same scores as TransE on [E; d_r]."""
+    wl = W.Workload("case", 7, "transh", "l2", 300, 6, 512, 128, 128, 512, 1, 1.0, 0.01, 1, 0.0, 0.0)
+    h, r, t = W.make_graph(wl)
+    tabs = W.make_tables(wl)
+    tabs["w"][:] = 0
+    bt = oracle_batch(wl, h, r, t, 0, 512)
+    mh = G.GpuModel(wl, tabs)
+    mh.build(bt); mh.forward()
+    wle = wl.scaled(model="transe")
+    me = G.GpuModel(wle, {"ent": np.concatenate([tabs["ent"], tabs["rel"]])})
+    me.build(bt); me.forward()
+    sh, _ = mh.scores_numpy()
+    se, _ = me.scores_numpy()
+    np.testing.assert_allclose(sh, se, rtol=2e-6)                      # (h-t)+d vs (h+d)-t: one rounding apart
