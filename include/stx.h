@@ -16,7 +16,9 @@
  *   - Every call returns a stx_status.  Host-detectable argument errors (null pointers, sizes beyond
  *     the configured maxima, bad enums) are reported before anything is launched.
  *   - Indices are int32, counts int64.  Tables are fp32, row-major, 16-byte aligned, with
- *     dim % 4 == 0 and rel_dim % 4 == 0, both <= 1024.
+ *     dim % 4 == 0, dim <= 1024.  TransR runs its projections on the matrix cores in 32-wide tiles:
+ *     dim % 32 == 0, rel_dim % 32 == 0, both <= 256, and STX_FLAG_BF16_PROJ must be set
+ *     (anything else: STX_ERR_UNSUPPORTED).
  */
 #ifndef STX_H
 #define STX_H
@@ -48,7 +50,8 @@ enum { STX_L1 = 0, STX_L2 = 1, STX_TORUS_L1 = 2, STX_TORUS_L2 = 3 };
 enum { STX_SUM = 0, STX_MEAN = 1 };
 
 #define STX_FLAG_RENORM_W 1u  /* TransH: rescale every touched normal w_r to unit length after the update */
-#define STX_FLAG_BF16_PROJ 2u /* TransR: bfloat16 operands, fp32 accumulation in the projection products */
+#define STX_FLAG_BF16_PROJ 2u /* TransR: h - t, M_r and dL/dy are rounded to bfloat16 (nearest even) as operands
+                                 of the three projection products; accumulation is fp32 */
 
 typedef struct {
     int32_t model;     /* STX_TRANSE ... */
@@ -60,7 +63,7 @@ typedef struct {
     int64_t n_rel;     /* R;  N + R < 2^31 */
     float margin;      /* gamma of the hinge max(0, gamma + d_pos - d_neg) */
     int32_t max_batch; /* largest b (positives per batch) any call will pass */
-    int32_t max_neg;   /* largest k (negatives per positive) any call will pass; 3*b*(1+k) < 2^31 */
+    int32_t max_neg;   /* largest k (negatives per positive) any call will pass; 3*b*(1+k) < 2^29 */
     uint32_t flags;    /* STX_FLAG_* */
 } stx_config;
 

@@ -26,6 +26,10 @@ stx_status check_config(const stx_config *c)
     if (c->dim <= 0 || c->dim % 4 != 0 || c->dim > kMaxDim) return STX_ERR_BAD_ARG;
     if (c->model == STX_TRANSR && (c->rel_dim <= 0 || c->rel_dim % 4 != 0 || c->rel_dim > kMaxDim))
         return STX_ERR_BAD_ARG;
+    // the matrix-core path of TransR works on 32-wide tiles and bfloat16 operands
+    if (c->model == STX_TRANSR && (c->dim % 32 != 0 || c->rel_dim % 32 != 0 || c->dim > kMaxProjDim ||
+                                   c->rel_dim > kMaxProjDim || !(c->flags & STX_FLAG_BF16_PROJ)))
+        return STX_ERR_UNSUPPORTED;
     if (c->n_ent <= 0 || c->n_rel <= 0 || c->n_ent + c->n_rel >= (int64_t)1 << 31) return STX_ERR_BAD_ARG;
     if (c->max_batch <= 0 || c->max_neg < 0) return STX_ERR_BAD_ARG;
     if (3 * (int64_t)c->max_batch * (1 + (int64_t)c->max_neg) >= ((int64_t)1 << 29)) return STX_ERR_BAD_ARG;
@@ -51,7 +55,7 @@ Layout make_layout(const stx_config *c)
     while (((int64_t)1 << L.sort_bits) < ncol) ++L.sort_bits;
     L.sort_passes = (L.sort_bits + 7) / 8;
     L.digit_bits = (L.sort_bits + L.sort_passes - 1) / L.sort_passes;
-    L.n_gbuf = c->model == STX_TRANSH ? 3 : (c->model == STX_TRANSR ? 4 : 1);
+    L.n_gbuf = (c->model == STX_TRANSH || c->model == STX_TRANSR) ? 3 : 1;
 
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
@@ -62,7 +66,12 @@ Layout make_layout(const stx_config *c)
     L.tile_heads = take((size_t)(L.ntiles_max + 1) * 4);
     L.loss_partials = take((size_t)(L.fwd_blocks_max + 1) * 4);
     L.partials = take((size_t)(L.nnz_max / kSegTile + 2) * 2 * L.ld * 4);
-    for (int i = 0; i < 4; ++i) L.gbuf[i] = i < L.n_gbuf ? take((size_t)L.rows_max * L.ld * 4) : 0;
+    for (int i = 0; i < 4; ++i) {
+        size_t bytes = (size_t)L.rows_max * L.ld * 4;
+        if (c->model == STX_TRANSR && i == 2)   // partial dL/dM_r matrices: two per chunk of the dM product
+            bytes = (size_t)(L.rows_max / kProjRowsDm + 2) * 2 * (size_t)c->rel_dim * c->dim * 4;
+        L.gbuf[i] = i < L.n_gbuf ? take(bytes) : 0;
+    }
     L.total = off;
     return L;
 }
@@ -115,7 +124,6 @@ stx_status stx_create(const stx_config *cfg, void *workspace, size_t workspace_b
     stx_status s = check_config(cfg);
     if (s != STX_OK) return s;
     if (!workspace) return STX_ERR_NULL;
-    if (cfg->model == STX_TRANSR) return STX_ERR_UNSUPPORTED;
     Layout L = make_layout(cfg);
     if (workspace_bytes < L.total || ((uintptr_t)workspace & 255u)) return STX_ERR_WORKSPACE;
     stx_ctx *c = new (std::nothrow) stx_ctx();
@@ -226,7 +234,13 @@ stx_status stx_forward(stx_ctx *ctx, const stx_incidence *inc, const stx_params 
     if (!scores || !loss) return STX_ERR_NULL;
     if (stacked(ctx)) s = launch_forward_stacked(ctx, inc, p, scores, loss);
     else if (ctx->cfg.model == STX_TRANSH) s = launch_forward_transh(ctx, inc, p, scores, loss);
-    else return STX_ERR_UNSUPPORTED;
+    else {   // TransR: y = M_r (h - t) + r on the matrix cores, then distances / hinge / dL/dy over the rows of y
+        if (inc->n_rows == 0) s = launch_finish_loss(ctx, 0, 1.0f, loss);
+        else {
+            s = launch_transr_project(ctx, inc, p);
+            if (s == STX_OK) s = launch_forward_from_y(ctx, inc, p, scores, loss);
+        }
+    }
     if (s == STX_OK) {
         ctx->fwd_inc = inc;
         ctx->fwd_rows = inc->n_rows;
@@ -243,6 +257,7 @@ stx_status stx_backward(stx_ctx *ctx, const stx_incidence *inc, const stx_params
     if (s != STX_OK) return s;
     if (!g || !g->rows) return STX_ERR_NULL;
     if (ctx->cfg.model == STX_TRANSH && !g->w_rows) return STX_ERR_NULL;
+    if (ctx->cfg.model == STX_TRANSR && !g->proj) return STX_ERR_NULL;
     if (ctx->fwd_inc != inc || ctx->fwd_rows != inc->n_rows) return STX_ERR_STATE;
     const int dim = ctx->cfg.dim;
     const int64_t ent_end = 2 * inc->n_rows;   // sorted entries of entity columns come first, then relation columns
@@ -256,7 +271,14 @@ stx_status stx_backward(stx_ctx *ctx, const stx_incidence *inc, const stx_params
         return launch_seg_reduce(ctx, inc, ent_end, inc->nnz, ctx->gbuf[2], ctx->gbuf[2], inc->nnz, dim, dim,
                                  g->w_rows, ctx->ld);
     }
-    return STX_ERR_UNSUPPORTED;
+    // TransR: gx = M_r^T gy and dL/dM_r on the matrix cores, then entity columns sum gx (signed, width dim)
+    // and relation columns sum gy (width rel_dim)
+    s = launch_transr_backward(ctx, inc, p, g);
+    if (s != STX_OK) return s;
+    s = launch_seg_reduce(ctx, inc, 0, ent_end, ctx->gbuf[1], ctx->gbuf[1], ent_end, dim, dim, g->rows, ctx->ld);
+    if (s != STX_OK) return s;
+    return launch_seg_reduce(ctx, inc, ent_end, inc->nnz, ctx->gbuf[0], ctx->gbuf[0], inc->nnz, ctx->cfg.rel_dim,
+                             ctx->cfg.rel_dim, g->rows, ctx->ld);
 }
 
 stx_status stx_sgd_step(stx_ctx *ctx, stx_params *p, const stx_incidence *inc, const stx_grads *g, float lr)
@@ -269,7 +291,7 @@ stx_status stx_sgd_step(stx_ctx *ctx, stx_params *p, const stx_incidence *inc, c
     if (!g || !g->rows) return STX_ERR_NULL;
     if (!(lr == lr)) return STX_ERR_BAD_ARG;
     if (ctx->cfg.model == STX_TRANSH && !g->w_rows) return STX_ERR_NULL;
-    if (ctx->cfg.model == STX_TRANSR) return STX_ERR_UNSUPPORTED;
+    if (ctx->cfg.model == STX_TRANSR && !g->proj) return STX_ERR_NULL;
     ctx->fwd_inc = nullptr;   // the tables change: a stored forward no longer matches them
     const int dim = ctx->cfg.dim;
     if (stacked(ctx)) {
@@ -277,8 +299,14 @@ stx_status stx_sgd_step(stx_ctx *ctx, stx_params *p, const stx_incidence *inc, c
                     nullptr, 0};
         return launch_sgd_rows(ctx, inc, T, g->rows, nullptr, lr);
     }
-    SgdTables T{p->ent, dim, 0, ctx->cfg.n_ent, p->rel, dim, p->w, (ctx->cfg.flags & STX_FLAG_RENORM_W) ? 2 : 0};
-    return launch_sgd_rows(ctx, inc, T, g->rows, g->w_rows, lr);
+    if (ctx->cfg.model == STX_TRANSH) {
+        SgdTables T{p->ent, dim, 0, ctx->cfg.n_ent, p->rel, dim, p->w, (ctx->cfg.flags & STX_FLAG_RENORM_W) ? 2 : 0};
+        return launch_sgd_rows(ctx, inc, T, g->rows, g->w_rows, lr);
+    }
+    SgdTables T{p->ent, dim, 0, ctx->cfg.n_ent, p->rel, ctx->cfg.rel_dim, nullptr, 0};
+    s = launch_sgd_rows(ctx, inc, T, g->rows, nullptr, lr);
+    if (s != STX_OK) return s;
+    return launch_transr_sgd_proj(ctx, inc, p, g, lr);
 }
 
 const char *stx_status_string(stx_status s)

@@ -62,11 +62,15 @@ __global__ __launch_bounds__(kThreads) void k_finish_loss(const float *__restric
 }
 
 // One group per positive i: rows i and b + i*k + kk (kk < k).
-template <int LPR, int ITERS, int DIST>
+// FROM_Y = false: the translated vector of a row is gathered from the stacked table X (TransE/TorusE).
+// FROM_Y = true : it is row `row` of the dense buffer G (TransR: y = M_r (h - t) + r was put there by
+//                 the projection kernel), and dL/dy overwrites it in place; every row is read and then
+//                 written by one group only.
+template <int LPR, int ITERS, int DIST, bool FROM_Y>
 __global__ __launch_bounds__(kThreads) void k_forward_stacked(const int32_t *__restrict__ colidx,
                                                               const float *__restrict__ X, int32_t b, int32_t k,
                                                               int dim, float margin, float scale,
-                                                              float *__restrict__ scores, float *__restrict__ G,
+                                                              float *__restrict__ scores, float *G,
                                                               float *__restrict__ loss_partials)
 {
     constexpr int GROUPS = kThreads / LPR;
@@ -77,15 +81,17 @@ __global__ __launch_bounds__(kThreads) void k_forward_stacked(const int32_t *__r
     float hinge_sum = 0.f;
     if (i < b) {   // uniform within the group; shuffles below stay inside the group
         RowVec<ITERS> xp;
-        gather_row<LPR, ITERS, true>(X, dim, d4, lig, colidx[3 * i], colidx[3 * i + 1], colidx[3 * i + 2], xp);
+        if (FROM_Y) load_vec<LPR, ITERS>(G + i * dim, d4, lig, xp);
+        else gather_row<LPR, ITERS, true>(X, dim, d4, lig, colidx[3 * i], colidx[3 * i + 1], colidx[3 * i + 2], xp);
         const float dpos = row_distance<LPR, ITERS, DIST>(xp);
         if (lig == 0) scores[i] = dpos;
         int n_active = 0;
         for (int kk = 0; kk < k; ++kk) {
             const int64_t row = (int64_t)b + i * k + kk;
             RowVec<ITERS> xn;
-            gather_row<LPR, ITERS, true>(X, dim, d4, lig, colidx[3 * row], colidx[3 * row + 1],
-                                         colidx[3 * row + 2], xn);
+            if (FROM_Y) load_vec<LPR, ITERS>(G + row * dim, d4, lig, xn);
+            else gather_row<LPR, ITERS, true>(X, dim, d4, lig, colidx[3 * row], colidx[3 * row + 1],
+                                              colidx[3 * row + 2], xn);
             const float dneg = row_distance<LPR, ITERS, DIST>(xn);
             const float arg = (margin + dpos) - dneg;
             const bool active = arg > 0.f;
@@ -141,20 +147,22 @@ stx_status launch_spmm(stx_ctx *c, const stx_incidence *inc, const stx_params *p
 
 template <int LPR, int ITERS>
 static void forward_go(stx_ctx *c, const stx_incidence *inc, const stx_params *p, float *scores, float *loss,
-                       float scale)
+                       float scale, bool from_y, int width)
 {
     constexpr int GROUPS = kThreads / LPR;
     dim3 grid((unsigned)((inc->b + GROUPS - 1) / GROUPS));
-#define STX_FWD(D)                                                                                              \
-    hipLaunchKernelGGL((k_forward_stacked<LPR, ITERS, D>), grid, dim3(kThreads), 0, c->stream, inc->a_colidx,   \
-                       p->ent, inc->b, inc->k, c->cfg.dim, c->cfg.margin, scale, scores, c->gbuf[0],            \
+#define STX_FWD(D, Y)                                                                                           \
+    hipLaunchKernelGGL((k_forward_stacked<LPR, ITERS, D, Y>), grid, dim3(kThreads), 0, c->stream,               \
+                       inc->a_colidx, p->ent, inc->b, inc->k, width, c->cfg.margin, scale, scores, c->gbuf[0],  \
                        c->loss_partials)
+#define STX_FWD2(D) do { if (from_y) STX_FWD(D, true); else STX_FWD(D, false); } while (0)
     switch (c->cfg.dist) {
-    case STX_L1: STX_FWD(STX_L1); break;
-    case STX_L2: STX_FWD(STX_L2); break;
-    case STX_TORUS_L1: STX_FWD(STX_TORUS_L1); break;
-    default: STX_FWD(STX_TORUS_L2); break;
+    case STX_L1: STX_FWD2(STX_L1); break;
+    case STX_L2: STX_FWD2(STX_L2); break;
+    case STX_TORUS_L1: STX_FWD2(STX_TORUS_L1); break;
+    default: STX_FWD2(STX_TORUS_L2); break;
     }
+#undef STX_FWD2
 #undef STX_FWD
     launch_finish_loss(c, (int)grid.x, scale, loss);
 }
@@ -166,7 +174,18 @@ stx_status launch_forward_stacked(stx_ctx *c, const stx_incidence *inc, const st
     float scale = 1.0f;
     if (c->cfg.reduce == STX_MEAN && inc->k > 0) scale = 1.0f / (float)((int64_t)inc->b * inc->k);
     Launch L = row_launch(c->cfg.dim);
-    STX_DISPATCH_ROW(L, forward_go, c, inc, p, scores, loss, scale);
+    STX_DISPATCH_ROW(L, forward_go, c, inc, p, scores, loss, scale, false, c->cfg.dim);
+    return hip_ok(hipGetLastError());
+}
+
+// Distances, hinge and dL/dy over rows of y already stored in gbuf[0] (row width = out_dim).
+stx_status launch_forward_from_y(stx_ctx *c, const stx_incidence *inc, const stx_params *p, float *scores,
+                                 float *loss)
+{
+    float scale = 1.0f;
+    if (c->cfg.reduce == STX_MEAN && inc->k > 0) scale = 1.0f / (float)((int64_t)inc->b * inc->k);
+    Launch L = row_launch(c->out_dim);
+    STX_DISPATCH_ROW(L, forward_go, c, inc, p, scores, loss, scale, true, c->out_dim);
     return hip_ok(hipGetLastError());
 }
 

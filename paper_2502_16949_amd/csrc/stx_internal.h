@@ -14,6 +14,9 @@ constexpr int kSortTile = kThreads * kSortItems;
 constexpr int kSegTile = 256;          // sorted entries per workgroup in the transposed product
 constexpr int kSelfScanTiles = 128;   // up to this many sort tiles, scatter workgroups scan the histograms themselves
 constexpr int kMaxDim = 1024;
+constexpr int kMaxProjDim = 256;        // TransR: dim and rel_dim are multiples of 32 up to this
+constexpr int kProjRows = 64;           // sorted relation entries per workgroup in the projection products
+constexpr int kProjRowsDm = 256;        // ... and in the product that forms dL/dM_r
 
 // Slots of the control block at the start of the workspace (int32 each).
 enum { CTRL_BAD_INDEX = 0, CTRL_WORDS = 64 };
@@ -78,6 +81,11 @@ struct SgdTables {
 };
 stx_status launch_sgd_rows(stx_ctx *, const stx_incidence *, const SgdTables &, const float *grad_rows,
                            const float *w_rows, float lr);
+stx_status launch_forward_from_y(stx_ctx *, const stx_incidence *, const stx_params *, float *scores, float *loss);
+// stx_transr.hip
+stx_status launch_transr_project(stx_ctx *, const stx_incidence *, const stx_params *);
+stx_status launch_transr_backward(stx_ctx *, const stx_incidence *, const stx_params *, stx_grads *);
+stx_status launch_transr_sgd_proj(stx_ctx *, const stx_incidence *, stx_params *, const stx_grads *, float lr);
 // stx_transh.hip
 stx_status launch_forward_transh(stx_ctx *, const stx_incidence *, const stx_params *, float *scores, float *loss);
 stx_status launch_finish_loss(stx_ctx *, int n_partials, float scale, float *loss);

@@ -1,0 +1,137 @@
+"""GPU parity for the TransR step (per-relation projection on the matrix cores, bfloat16 operands and
+fp32 accumulation) against the oracle in its bfloat16-emulating mode and in its exact-input mode."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import stxo
+from paper_2502_16949_amd import binding as B
+from paper_2502_16949_amd import workloads as W
+from tests import gpu_util as G
+from tests.util import oracle_batch, oracle_config, oracle_tables
+
+pytestmark = pytest.mark.gpu
+
+BF16_TOL = 1e-2          # bar for quantities that pass through a bfloat16 rounding of a computed value
+
+
+def _bulk_and_bar(got, ref, scale, what, bulk_tol=2e-5, bulk_frac=0.995):
+    """Elementwise: everything within BF16_TOL * scale (a computed dL/dy that lands on the other side
+    of a bfloat16 rounding boundary moves one product by 2^-8 of itself), and nearly everything within
+    the fp32 bar."""
+    err = np.abs(got.astype(np.float64) - ref)
+    assert np.all(err <= BF16_TOL * scale + 1e-30), (what, float((err / (scale + 1e-30)).max()))
+    ok = err <= bulk_tol * scale + 1e-30
+    assert ok.mean() >= bulk_frac, (what, float(ok.mean()))
+
+
+def check_transr_step(wl, tabs, bt, reduce, lr=0.01):
+    cfg_b = oracle_config(wl, reduce=reduce, bf16=True)
+    cfg_x = oracle_config(wl, reduce=reduce, bf16=False)
+    m = G.GpuModel(wl, tabs, reduce=reduce, flags=B.STX_FLAG_BF16_PROJ)
+    m.build(bt)
+    m.forward()
+    scores, loss = m.scores_numpy()
+    fw = stxo.forward(cfg_b, oracle_tables(tabs), bt, want_x=False)
+    G.check_scores_and_loss(scores, loss, fw, reduce == B.STX_MEAN)           # 1e-5 against the same roundings
+    fx = stxo.forward(cfg_x, oracle_tables(tabs), bt, want_x=False)
+    np.testing.assert_allclose(scores, fx.scores, rtol=BF16_TOL)              # 1e-2 against exact inputs
+    active = G.resolve_active(scores, fw, bt, wl.margin)
+    g = stxo.backward(cfg_b, oracle_tables(tabs), bt, active=active)
+    m.backward()
+    torch.cuda.synchronize()
+    u = int(m.inc.n_touched.item())
+    cols = m.inc.at_touched_cols[:u].cpu().numpy()
+    rows = m.grads.rows[:u].cpu().numpy()
+    is_ent = cols < wl.n_ent
+    ec, rc = cols[is_ent], cols[~is_ent] - wl.n_ent
+    amb = g.ambiguous.astype(bool)                                           # only L1 kinds can set it
+    assert amb.mean() <= 0.1
+    hh = np.concatenate([bt.h, bt.nh]); tt = np.concatenate([bt.t, bt.nt]); rr = np.concatenate([bt.r, np.repeat(bt.r, bt.k)])
+    loose_ent = np.zeros(wl.n_ent, bool); loose_ent[hh[amb]] = True; loose_ent[tt[amb]] = True
+    loose_rel = np.zeros(wl.n_rel, bool); loose_rel[rr[amb]] = True
+    ke, kr = ~loose_ent[ec], ~loose_rel[rc]
+    _bulk_and_bar(rows[is_ent][ke][:, :wl.dim], g.ent[ec[ke]], g.ent_abs[ec[ke]], "dE")
+    # dL/dr is a plain fp32 sum of dL/dy: the fp32 bar applies
+    G.check_grad_rows(rc[kr], rows[~is_ent][kr], g.rel, g.rel_abs, wl.rel_dim, what="dr", all_cols=rc)
+    proj = m.grads.proj.cpu().numpy()
+    sel = rc[kr]
+    _bulk_and_bar(proj[sel], g.proj[sel], g.proj_abs[sel], "dM")
+    # relations absent from the batch got no gradient in the oracle either
+    absent = np.ones(wl.n_rel, bool); absent[rc] = False
+    assert not np.any(g.proj_abs[absent])
+    # update
+    tb = oracle_tables(tabs)
+    m_ent, m_rel = stxo.touched_masks(cfg_b, bt)
+    stxo.sgd(tb.ent, g.ent, m_ent, lr, 0)
+    stxo.sgd(tb.rel, g.rel, m_rel, lr, 0)
+    stxo.sgd(tb.proj, g.proj, m_rel, lr, 0)
+    m.sgd(lr)
+    torch.cuda.synchronize()
+    for name, new, ref, old, gabs, mask, loose in (
+            ("ent", m.params.ent, tb.ent, tabs["ent"], g.ent_abs, m_ent, loose_ent),
+            ("rel", m.params.rel, tb.rel, tabs["rel"], g.rel_abs, m_rel, loose_rel),
+            ("proj", m.params.proj, tb.proj, tabs["proj"], g.proj_abs, m_rel, loose_rel)):
+        new = new.cpu().numpy()
+        assert np.array_equal(new[mask == 0], old[mask == 0]), name
+        keep = ~loose
+        diff = np.abs(new.astype(np.float64) - ref)[keep]
+        tol = G.REL_TOL if name == "rel" else BF16_TOL
+        assert np.all(diff <= tol * lr * gabs[keep] + np.abs(old[keep]) * 2.0**-22 + 2.0**-23), (name, diff.max())
+
+
+CASES = [
+    # dist, n_ent, n_rel, b, k, dim, rel_dim, zipf
+    ("l2", 1000, 20, 1024, 1, 128, 128, 1.1),
+    ("l2", 400, 40, 900, 2, 128, 128, 1.3),       # many small relations: chunks spanning several of them
+    ("l1", 300, 3, 777, 1, 128, 128, 0.0),        # three large relations: runs crossing many chunks
+    ("l2", 300, 5, 300, 1, 64, 32, 0.0),
+    ("l2", 300, 5, 333, 2, 32, 64, 0.0),
+    ("l2", 200, 7, 500, 1, 256, 128, 1.1),
+    ("l1", 200, 7, 260, 1, 128, 256, 1.1),
+]
+
+
+@pytest.mark.parametrize("reduce", [B.STX_SUM, B.STX_MEAN])
+@pytest.mark.parametrize("dist,n_ent,n_rel,b,k,dim,rel_dim,zipf", CASES)
+def test_transr_step_matches_oracle(dist, n_ent, n_rel, b, k, dim, rel_dim, zipf, reduce):
+    wl = W.Workload("case", 7, "transr", dist, n_ent, n_rel, b, dim, rel_dim, b, k, 1.0, 0.01, 1, zipf, zipf, True)
+    seed = dim + b
+    h, r, t = W.make_graph(wl.scaled(index=seed))
+    tabs = W.make_tables(wl.scaled(index=seed))
+    bt = oracle_batch(wl, h, r, t, 0, b, seed=seed)
+    check_transr_step(wl, tabs, bt, reduce)
+
+
+@pytest.mark.parametrize("which", ["first", "last_partial"])
+def test_transr_config_full_batch(which):
+    wl = W.WORKLOADS["transr"]
+    h, r, t = W.make_graph(wl)
+    tabs = W.make_tables(wl)
+    lo, hi = W.batch_slices(wl)[0 if which == "first" else -1]
+    check_transr_step(wl, tabs, oracle_batch(wl, h, r, t, lo, hi), B.STX_SUM, lr=wl.lr)
+
+
+def test_transr_identity_projection_is_transe():
+    """M_r = I (exact in bfloat16): scores equal TransE's on [E; r] up to the rounding of h - t."""
+    wl = W.Workload("case", 7, "transr", "l2", 300, 6, 512, 128, 128, 512, 1, 1.0, 0.01, 1, 0.0, 0.0, True)
+    h, r, t = W.make_graph(wl)
+    tabs = W.make_tables(wl)
+    tabs["proj"] = np.tile(np.eye(128, dtype=np.float32), (6, 1, 1))
+    bt = oracle_batch(wl, h, r, t, 0, 512)
+    mr = G.GpuModel(wl, tabs, flags=B.STX_FLAG_BF16_PROJ)
+    mr.build(bt); mr.forward()
+    me = G.GpuModel(wl.scaled(model="transe"), {"ent": np.concatenate([tabs["ent"], tabs["rel"]])})
+    me.build(bt); me.forward()
+    sr, _ = mr.scores_numpy()
+    se, _ = me.scores_numpy()
+    np.testing.assert_allclose(sr, se, rtol=5e-3)                          # h - t is rounded to bfloat16
+
+
+def test_transr_needs_the_bf16_flag_and_32_wide_dims():
+    for kw in (dict(flags=0), dict(dim=48, flags=B.STX_FLAG_BF16_PROJ), dict(rel_dim=288, flags=B.STX_FLAG_BF16_PROJ)):
+        base = dict(model="transr", dist="l2", n_ent=100, n_rel=5, dim=64, max_batch=64, max_neg=1, rel_dim=64)
+        base.update(kw)
+        with pytest.raises(B.StxError) as ei:
+            B.stx_workspace_bytes(B.make_config(**base))
+        assert ei.value.status == B.STX_ERR_UNSUPPORTED
