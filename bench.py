@@ -2,11 +2,13 @@
 """Benchmark of the sparse-incidence KGE training step on one MI355X.
 
 A step is one pass of the whole hot path over one batch of synthetic triplets that already sit in
-HBM: negative sampling, incidence build (A and sorted A^T), forward (gather product + distance +
-margin-ranking loss), backward (transposed product) and the sparse SGD update.  Steps walk the
-workload's batches in stored order, epoch after epoch (the last batch of an epoch is partial).
+HBM: negative sampling, incidence build (A and sorted A^T), forward (gather product + model projection
++ distance + margin-ranking loss), backward (transposed products) and the sparse SGD update.  Steps
+walk the workload's batches in stored order, epoch after epoch (the last batch of an epoch is
+partial).  Default workload: "mid" = TransE, d = 128, fp32, the configuration the headline metric is
+quoted on.
 
-Prints ONE JSON line; see DESIGN.md for the byte model behind "roofline".
+Prints ONE JSON line; DESIGN.md derives the byte model behind "roofline".
 """
 from __future__ import annotations
 
@@ -21,6 +23,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+# The kernel whose roofline is reported: the one with the largest share of GPU time in the
+# rocprofv3 kernel trace of the same command (profiles/).
+DOMINANT = {"transe": "k_seg_reduce", "toruse": "k_seg_reduce", "transh": "k_seg_reduce", "transr": "k_transr_dm"}
 
 
 def parse():
@@ -28,22 +35,37 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--config", default="mid", help="workload name: tiny | mid | toruse (and later transh, transr)")
+    ap.add_argument("--config", default="mid", help="workload: tiny | mid | transh | transr | toruse")
+    ap.add_argument("--kernel", default=None, help="kernel to time for the roofline entry (default: the dominant one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=0, help="oracle steps to time (0 = pick for ~10-20 s)")
     return ap.parse_args()
 
 
-def algorithmic_bytes(wl, rows, touched):
-    """Bytes the method itself moves per call for a stacked (TransE/TorusE) step:
-    forward  = rows * (3 gathered table rows + 12 B of column ids + 1 dL/dx row written + 4 B score)
-    backward = rows * (3 dL/dx rows read, one per entry of A^T, + 3 * 4 B packed entries) + touched * (row + 8 B)
-    sgd      = touched * (table row read + gradient row read + table row written)"""
+def kernel_work(wl, kernel, rows, touched):
+    """Algorithmic work of ONE launch of `kernel` on a full batch: (amount, unit, bound, peak).
+    row = 4*dim bytes.  rows = b*(1+k) matrix rows, nnz = 3*rows, touched = distinct columns."""
     row = 4 * wl.dim
-    fwd = rows * (3 * row + 12 + row + 4)
-    bwd = rows * (3 * row + 12) + touched * (row + 8)
-    sgd = touched * 3 * row
-    return fwd, bwd, sgd
+    nnz = 3 * rows
+    if kernel == "k_forward_stacked" and wl.model in ("transe", "toruse"):
+        # 3 gathered table rows + 12 B of column ids per row in; dL/dx row + score out
+        return rows * (3 * row + 12 + row + 4), "GB/s", "hbm", HBM_PEAK_GBS
+    if kernel == "k_forward_stacked":   # TransR: y row in, dL/dy row out, score out
+        return rows * (2 * 4 * wl.rel_dim + 4), "GB/s", "hbm", HBM_PEAK_GBS
+    if kernel == "k_forward_transh":
+        # 2 entity rows + w_r + d_r (+ w_r again for the gradients) in; gx, gy, gw rows + score out
+        return rows * (5 * row + 12 + 3 * row + 4), "GB/s", "hbm", HBM_PEAK_GBS
+    if kernel == "k_seg_reduce":
+        # first launch of the backward call: one source row + 4 B packed entry per sorted entry in, one row per column out
+        n = nnz if wl.model != "transr" else 2 * rows
+        return n * (row + 4) + touched * row, "GB/s", "hbm", HBM_PEAK_GBS
+    if kernel == "k_sgd_rows":
+        return touched * 3 * row, "GB/s", "hbm", HBM_PEAK_GBS
+    if kernel == "k_scatter":
+        return nnz * 16, "GB/s", "hbm", HBM_PEAK_GBS      # key + payload in, key + payload out
+    if kernel in ("k_transr_project", "k_transr_gx", "k_transr_dm"):
+        return 2.0 * rows * wl.dim * wl.rel_dim, "TFLOP/s", "mfma", MFMA_BF16_PEAK_TFLOPS
+    raise ValueError(kernel)
 
 
 def cpu_baseline(wl, h, r, t, tabs, n_steps):
@@ -53,9 +75,8 @@ def cpu_baseline(wl, h, r, t, tabs, n_steps):
     cfg = oracle_config(wl)
     tb = oracle_tables(tabs)
     slices = [(s, min(s + wl.batch, wl.n_triplets)) for s in range(0, wl.n_triplets, wl.batch)]
-    rows = 0
+    rows = done = 0
     t0 = time.perf_counter()
-    done = 0
     for i in range(n_steps):
         lo, hi = slices[i % len(slices)]
         bt = oracle_batch(wl, h, r, t, lo, hi)
@@ -85,16 +106,17 @@ def main():
         sys.exit(2)
     dev = "cuda:0"
     wl = W.WORKLOADS[args.config]
-    if wl.model not in ("transe", "toruse"):
-        print(f"bench.py: workload {wl.name} is not benchmarked yet", file=sys.stderr)
-        sys.exit(2)
+    kernel = args.kernel or DOMINANT[wl.model]
 
     h, r, t = W.make_graph(wl)
     tabs = W.make_tables(wl)
     hd, rd, td = (torch.from_numpy(a).to(dev) for a in (h, r, t))
-    cfg = B.make_config(wl.model, wl.dist, wl.n_ent, wl.n_rel, wl.dim, wl.batch, wl.n_neg, margin=wl.margin)
+    flags = {"transh": B.STX_FLAG_RENORM_W, "transr": B.STX_FLAG_BF16_PROJ}.get(wl.model, 0)
+    cfg = B.make_config(wl.model, wl.dist, wl.n_ent, wl.n_rel, wl.dim, wl.batch, wl.n_neg, rel_dim=wl.rel_dim,
+                        margin=wl.margin, flags=flags)
     ctx = B.Context(cfg, dev)
-    params = B.Params(torch.from_numpy(tabs["ent"]).to(dev))
+    params = B.Params(*(None if tabs.get(k) is None else torch.from_numpy(tabs[k]).to(dev)
+                        for k in ("ent", "rel", "w", "proj")))
     inc = B.Incidence(ctx)
     grads = B.Grads(ctx)
     scores = torch.empty(ctx.rows_max, dtype=torch.float32, device=dev)
@@ -124,7 +146,9 @@ def main():
         step(i)
     torch.cuda.synchronize()
 
-    # ---- timed region: exactly --steps steps, events on the stream the kernels run on --------------
+    # ---- timed region: exactly --steps steps; the library brackets the launches of `kernel` with HIP
+    # events on its own stream, bench.py brackets the five calls with events on the same stream ----------
+    B.stx_profile_kernel(ctx, kernel, 8 * args.steps)
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
     rows_done = 0
     torch.cuda.synchronize()
@@ -133,33 +157,40 @@ def main():
         rows_done += step(args.warmup + i, events[i])
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    kernel_us, kernel_n = B.stx_profile_read(ctx)
+    B.stx_profile_kernel(ctx, None, 0)
 
     phase = np.zeros(5)
-    fwd_full = []
-    for i, ev in enumerate(events):
+    for ev in events:
         for p in range(5):
             phase[p] += ev[p].elapsed_time(ev[p + 1])
-        lo, hi = slices[(args.warmup + i) % len(slices)]
-        if hi - lo == wl.batch:
-            fwd_full.append(ev[2].elapsed_time(ev[3]))
     phase_us = phase / args.steps * 1e3
     loss_last = float(loss.item())
     u_last = int(inc.n_touched.item())
 
-    # ---- roofline of the dominant kernel: the fused forward, one launch per full batch --------------
-    fwd_bytes, bwd_bytes, sgd_bytes = algorithmic_bytes(wl, wl.rows_per_batch, u_last)
-    fwd_ms = float(np.mean(fwd_full)) if fwd_full else float("nan")
-    achieved = fwd_bytes / (fwd_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "k_forward_stacked", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                "bytes_per_launch": fwd_bytes, "avg_launch_us": round(fwd_ms * 1e3, 2)}
+    # ---- roofline of the dominant kernel.  The mean launch time covers every batch of the timed region
+    # (the partial last batch of an epoch included), so the work figure is averaged the same way. ----------
+    mean_rows = rows_done / args.steps
+    work, unit, bound, peak = kernel_work(wl, kernel, mean_rows, u_last * mean_rows / wl.rows_per_batch)
+    if kernel == "k_seg_reduce" and wl.model in ("transh", "transr"):
+        kernel_note = "first of the call's launches of this kernel is modelled; the mean is over all of them"
+    else:
+        kernel_note = ""
+    per_launch = kernel_n / args.steps if args.steps else 0
+    achieved = (work / (kernel_us * 1e-6)) / (1e9 if unit == "GB/s" else 1e12) if kernel_us > 0 else 0.0
+    roofline = {"bound": bound, "kernel": kernel, "achieved": round(achieved, 1), "peak": peak, "unit": unit,
+                "frac": round(achieved / peak, 4), "traffic": None, "work_per_launch": int(work),
+                "avg_launch_us": round(kernel_us, 2), "launches_per_step": round(per_launch, 2)}
+    if kernel_note:
+        roofline["note"] = kernel_note
 
     out = {
         "metric": "training triplets/sec (pos+neg) TransE d=128 fp32" if wl.name == "mid"
                   else f"training triplets/sec (pos+neg) {wl.model} d={wl.dim} fp32",
         "value": round(rows_done / dt, 1), "unit": "triplets/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 4), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32" if wl.model != "transr" else "f32 (bf16 MFMA operands)",
+        "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.model} {wl.dist}, {wl.n_ent} entities, {wl.n_rel} relations, "
                                f"{wl.n_triplets} triplets (Zipf {wl.zipf_ent}/{wl.zipf_rel}), dim {wl.dim}, "
                                f"batch {wl.batch}, {wl.n_neg} negative(s) per positive, margin {wl.margin}, "
@@ -167,7 +198,7 @@ def main():
                    "rows_per_full_batch": wl.rows_per_batch, "batches_per_epoch": len(slices),
                    "step": "sample negatives + build incidence + forward + backward + sgd"},
         "phase_us": {k: round(float(v), 2) for k, v in zip(("sample", "build", "forward", "backward", "sgd"), phase_us)},
-        "algorithmic_bytes": {"forward": fwd_bytes, "backward": bwd_bytes, "sgd": sgd_bytes, "touched_rows": u_last},
+        "touched_rows_last_step": u_last,
         "loss_last_step": loss_last,
         "roofline": roofline,
     }
@@ -175,7 +206,7 @@ def main():
     if not args.no_cpu_baseline:
         n = args.cpu_steps
         if n <= 0:
-            v1, _, dt1 = cpu_baseline(wl, h, r, t, tabs, 1)
+            _, _, dt1 = cpu_baseline(wl, h, r, t, tabs, 1)
             n = max(2, min(60, int(15.0 / max(dt1, 1e-3))))
         v, done, cdt = cpu_baseline(wl, h, r, t, tabs, n)
         out["cpu_baseline"] = {"value": round(v, 1), "unit": "triplets/s", "cores": 1, "kind": "oracle",

@@ -180,6 +180,15 @@ stx_status stx_backward(stx_ctx *ctx, const stx_incidence *inc, const stx_params
 stx_status stx_sgd_step(stx_ctx *ctx, stx_params *p, const stx_incidence *inc, const stx_grads *g,
                         float lr);
 
+/* Live timing of one kernel, for benchmarks.  stx_profile_kernel: from now on every launch of the kernel
+ * called `kernel_name` (e.g. "k_forward_stacked", "k_seg_reduce", "k_sgd_rows", "k_scatter") on this
+ * context is bracketed by a pair of HIP events on the context's stream, for at most max_records
+ * launches; a null name or max_records == 0 switches timing off.  stx_profile_read: waits for the
+ * stream, then *avg_us (host) = mean bracketed time in microseconds and *n (host) = launches recorded;
+ * recording restarts from zero.  Not to be used while the stream is being captured into a graph.     */
+stx_status stx_profile_kernel(stx_ctx *ctx, const char *kernel_name /* host */, int32_t max_records);
+stx_status stx_profile_read(stx_ctx *ctx, double *avg_us, int32_t *n);
+
 const char *stx_status_string(stx_status s);
 
 #ifdef __cplusplus

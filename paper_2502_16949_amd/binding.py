@@ -25,7 +25,8 @@ MODELS = {"transe": STX_TRANSE, "transh": STX_TRANSH, "transr": STX_TRANSR, "tor
 DISTS = {"l1": STX_L1, "l2": STX_L2, "torus_l1": STX_TORUS_L1, "torus_l2": STX_TORUS_L2}
 
 EXPORTS = ["stx_workspace_bytes", "stx_create", "stx_destroy", "stx_sample_negatives", "stx_build_incidence",
-           "stx_check_indices", "stx_spmm", "stx_forward", "stx_backward", "stx_sgd_step", "stx_status_string"]
+           "stx_check_indices", "stx_spmm", "stx_forward", "stx_backward", "stx_sgd_step", "stx_profile_kernel",
+           "stx_profile_read", "stx_status_string"]
 
 
 class StxError(RuntimeError):
@@ -79,6 +80,8 @@ def lib():
         L.stx_backward.argtypes = [vp, C.POINTER(stx_incidence), C.POINTER(stx_params), C.POINTER(stx_grads)]
         L.stx_sgd_step.argtypes = [vp, C.POINTER(stx_params), C.POINTER(stx_incidence), C.POINTER(stx_grads),
                                    C.c_float]
+        L.stx_profile_kernel.argtypes = [vp, C.c_char_p, i32]
+        L.stx_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32)]
         L.stx_status_string.argtypes = [C.c_int]
         L.stx_status_string.restype = C.c_char_p
         for name in EXPORTS[:-1]:
@@ -249,3 +252,15 @@ def stx_backward(ctx: Context, inc: Incidence, p: Params, g: Grads):
 
 def stx_sgd_step(ctx: Context, p: Params, inc: Incidence, g: Grads, lr: float):
     _check("stx_sgd_step", lib().stx_sgd_step(ctx.handle, C.byref(p.c), C.byref(inc.c), C.byref(g.c), lr))
+
+
+def stx_profile_kernel(ctx: Context, kernel_name, max_records: int):
+    name = None if kernel_name is None else kernel_name.encode()
+    _check("stx_profile_kernel", lib().stx_profile_kernel(ctx.handle, name, max_records))
+
+
+def stx_profile_read(ctx: Context):
+    """(mean microseconds per bracketed launch, number of launches recorded)."""
+    avg, n = C.c_double(0), C.c_int32(0)
+    _check("stx_profile_read", lib().stx_profile_read(ctx.handle, C.byref(avg), C.byref(n)))
+    return avg.value, n.value

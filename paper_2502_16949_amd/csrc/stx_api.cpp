@@ -11,7 +11,7 @@ namespace {
 inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 struct Layout {
-    size_t ctrl, keys[2], pay[2], table, tile_heads, loss_partials, partials, gbuf[4], total;
+    size_t ctrl, keys[2], pay[2], table, super, tile_heads, loss_partials, partials, gbuf[4], total;
     int64_t rows_max, nnz_max, cols_max;
     int ld, out_dim, ntiles_max, fwd_blocks_max, n_gbuf;
     int sort_bits, sort_passes, digit_bits;
@@ -63,6 +63,7 @@ Layout make_layout(const stx_config *c)
     for (int i = 0; i < 2; ++i) L.keys[i] = take((size_t)L.nnz_max * 4);
     for (int i = 0; i < 2; ++i) L.pay[i] = take((size_t)L.nnz_max * 4);
     L.table = take((size_t)256 * L.ntiles_max * 4);
+    L.super = take((size_t)256 * (L.ntiles_max / kSuperTile + 1) * 4);
     L.tile_heads = take((size_t)(L.ntiles_max + 1) * 4);
     L.loss_partials = take((size_t)(L.fwd_blocks_max + 1) * 4);
     L.partials = take((size_t)(L.nnz_max / kSegTile + 2) * 2 * L.ld * 4);
@@ -148,22 +149,79 @@ stx_status stx_create(const stx_config *cfg, void *workspace, size_t workspace_b
         c->pay[i] = (int32_t *)(base + L.pay[i]);
     }
     c->table = (int32_t *)(base + L.table);
+    c->super = (int32_t *)(base + L.super);
     c->tile_heads = (int32_t *)(base + L.tile_heads);
     c->loss_partials = (float *)(base + L.loss_partials);
     c->partials = (float *)(base + L.partials);
     for (int i = 0; i < 4; ++i) c->gbuf[i] = i < L.n_gbuf ? (float *)(base + L.gbuf[i]) : nullptr;
     c->fwd_inc = nullptr;
     c->fwd_rows = 0;
+    c->prof_ev = nullptr;
+    c->prof_cap = c->prof_n = 0;
+    c->prof_name[0] = 0;
     s = launch_clear_ctrl(c);
     if (s != STX_OK) { delete c; return s; }
     *out = c;
     return STX_OK;
 }
 
+static void prof_release(stx_ctx *ctx)
+{
+    if (ctx->prof_ev) {
+        for (int i = 0; i < 2 * ctx->prof_cap; ++i) (void)hipEventDestroy(ctx->prof_ev[i]);
+        delete[] ctx->prof_ev;
+    }
+    ctx->prof_ev = nullptr;
+    ctx->prof_cap = ctx->prof_n = 0;
+    ctx->prof_name[0] = 0;
+}
+
 stx_status stx_destroy(stx_ctx *ctx)
 {
     if (!ctx) return STX_ERR_NULL;
+    prof_release(ctx);
     delete ctx;
+    return STX_OK;
+}
+
+stx_status stx_profile_kernel(stx_ctx *ctx, const char *kernel_name, int32_t max_records)
+{
+    if (!ctx) return STX_ERR_NULL;
+    if (max_records < 0 || max_records > (1 << 20)) return STX_ERR_BAD_ARG;
+    prof_release(ctx);
+    if (!kernel_name || max_records == 0) return STX_OK;
+    size_t len = __builtin_strlen(kernel_name);
+    if (len == 0 || len >= sizeof(ctx->prof_name)) return STX_ERR_BAD_ARG;
+    ctx->prof_ev = new (std::nothrow) hipEvent_t[2 * (size_t)max_records];
+    if (!ctx->prof_ev) return STX_ERR_BAD_ARG;
+    for (int i = 0; i < 2 * max_records; ++i)
+        if (hipEventCreate(&ctx->prof_ev[i]) != hipSuccess) {
+            for (int j = 0; j < i; ++j) (void)hipEventDestroy(ctx->prof_ev[j]);
+            delete[] ctx->prof_ev;
+            ctx->prof_ev = nullptr;
+            return STX_ERR_HIP;
+        }
+    ctx->prof_cap = max_records;
+    __builtin_memcpy(ctx->prof_name, kernel_name, len + 1);
+    return STX_OK;
+}
+
+stx_status stx_profile_read(stx_ctx *ctx, double *avg_us, int32_t *n)
+{
+    if (!ctx || !avg_us || !n) return STX_ERR_NULL;
+    *avg_us = 0.0;
+    *n = 0;
+    if (!ctx->prof_ev) return STX_ERR_STATE;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return STX_ERR_HIP;
+    double total_ms = 0.0;
+    for (int i = 0; i < ctx->prof_n; ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]) != hipSuccess) return STX_ERR_HIP;
+        total_ms += ms;
+    }
+    *n = ctx->prof_n;
+    if (ctx->prof_n) *avg_us = total_ms * 1e3 / ctx->prof_n;
+    ctx->prof_n = 0;
     return STX_OK;
 }
 

@@ -214,10 +214,19 @@ __global__ __launch_bounds__(kThreads) void k_seg_fixup(const int32_t *__restric
     const int lo = min(grp * per, n), hi = min(lo + per, n);
     Acc<ITERS> acc;
     acc.zero();
-    for (int q = lo; q < hi; ++q) {
-        const float *p = partials + ((int64_t)(j0 + q) * 2 + (q == 0 ? 1 : 0)) * ld_out;
+    constexpr int FU = ITERS == 1 ? 8 : 2;
+    int q = lo;
+    for (; q + FU <= hi; q += FU) {   // FU partial rows in flight, added in tile order
+        Acc<ITERS> v[FU];
+#pragma unroll
+        for (int u = 0; u < FU; ++u)
+            load_row<LPR, ITERS>(partials + ((int64_t)(j0 + q + u) * 2 + (q + u == 0 ? 1 : 0)) * ld_out, d4, lig, v[u]);
+#pragma unroll
+        for (int u = 0; u < FU; ++u) acc.add(v[u]);
+    }
+    for (; q < hi; ++q) {
         Acc<ITERS> v;
-        load_row<LPR, ITERS>(p, d4, lig, v);
+        load_row<LPR, ITERS>(partials + ((int64_t)(j0 + q) * 2 + (q == 0 ? 1 : 0)) * ld_out, d4, lig, v);
         acc.add(v);
     }
 #pragma unroll
@@ -308,9 +317,12 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
                    const float *src_b, int32_t split, int ld_src, int width, float *out_rows, int ld_out)
 {
     const int ntiles = (e_end - e_begin + kSegTile - 1) / kSegTile;
+    {
+    ProfScope prof(c, "k_seg_reduce");
     hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS>), dim3(ntiles), dim3(kThreads), 0, c->stream, inc->at_packed,
                        inc->at_seg_id, e_begin, e_end, src_a, src_b, split, ld_src, width / 4, out_rows, ld_out,
                        c->partials);
+    }
     if (ntiles > 1)
         hipLaunchKernelGGL((k_seg_fixup<LPR, ITERS>), dim3(ntiles - 1), dim3(kThreads), 0, c->stream,
                            inc->at_packed, inc->at_seg_id, inc->at_seg_ptr, e_begin, e_end, width / 4, out_rows,
@@ -326,6 +338,7 @@ static void sgd_go(stx_ctx *c, const stx_incidence *inc, const SgdTables &T, con
     int64_t blocks = (cap + GROUPS - 1) / GROUPS;
     if (blocks > 8192) blocks = 8192;   // grid-stride beyond this
     if (blocks < 1) blocks = 1;
+    ProfScope prof(c, "k_sgd_rows");
     hipLaunchKernelGGL((k_sgd_rows<LPR, ITERS>), dim3((unsigned)blocks), dim3(kThreads), 0, c->stream,
                        inc->at_touched_cols, inc->n_touched, T.table_a, T.width_a / 4, T.mode_a, (int32_t)T.n_split,
                        T.table_b, T.width_b / 4, T.table_w, T.mode_w, grad_rows, w_rows, c->ld, lr);

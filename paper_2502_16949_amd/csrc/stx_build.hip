@@ -14,7 +14,7 @@
 //   k_seg_write       touched_cols, seg_ptr, row_idx, sign, seg_id, packed, U
 // The tile histograms (tile-major table[tile][digit]) must become global offsets before a scatter.
 // With few tiles every scatter workgroup derives its own offsets from the raw table (a few coalesced
-// reads per thread); with many tiles a one-workgroup k_scan_table does it once in between.
+// reads per thread); with many tiles a small k_super_sums first adds the histograms up in groups of tiles.
 #include "stx_device.h"
 #include "stx_internal.h"
 
@@ -122,21 +122,18 @@ __global__ __launch_bounds__(kThreads) void k_hist(const int32_t *__restrict__ k
     if (tid < radix) table[blockIdx.x * radix + tid] = s_hist[tid];
 }
 
-// One workgroup: table[tile][digit] counts -> number of keys that sort before the first key of that
-// (digit, tile): all keys of smaller digits, plus the same digit in earlier tiles.
-__global__ __launch_bounds__(kThreads) void k_scan_table(int32_t *__restrict__ table, int radix, int ntiles)
+// With many tiles the scatter workgroups cannot each read the whole table.  This kernel adds the tile
+// histograms up in groups of kSuperTile tiles: super[g][digit] = sum over the tiles of group g.  A
+// scatter workgroup then needs its group's earlier tiles plus one row per group.
+__global__ __launch_bounds__(kThreads) void k_super_sums(const int32_t *__restrict__ table, int radix, int ntiles,
+                                                         int32_t *__restrict__ super)
 {
-    const int tid = threadIdx.x;
-    int32_t total = 0;
-    if (tid < radix)
-        for (int t = 0; t < ntiles; ++t) total += table[t * radix + tid];
-    int32_t run = block_exclusive_scan(total, nullptr);
-    if (tid < radix)
-        for (int t = 0; t < ntiles; ++t) {
-            int32_t v = table[t * radix + tid];
-            table[t * radix + tid] = run;
-            run += v;
-        }
+    const int tid = threadIdx.x, t0 = blockIdx.x * kSuperTile, t1 = min(t0 + kSuperTile, ntiles);
+    if (tid >= radix) return;
+    int32_t a = 0;
+#pragma unroll 8
+    for (int t = t0; t < t1; ++t) a += table[t * radix + tid];
+    super[blockIdx.x * radix + tid] = a;
 }
 
 // Stable scatter of one tile by the digit at `shift`.  Element order inside a tile is
@@ -145,20 +142,43 @@ __global__ __launch_bounds__(kThreads) void k_scan_table(int32_t *__restrict__ t
 //   (count in earlier wavefronts) + (count in earlier iterations of this wavefront) + (equal lanes below),
 // the last term from a ballot match over the digit's bits.  The base offset of a (digit, tile) is the
 // number of keys with a smaller digit anywhere plus those with the same digit in earlier tiles: read
-// from `table` when SELF_SCAN is false (k_scan_table ran), else derived here from the raw counts.
-template <bool FIRST, bool SELF_SCAN>
+// derived here from the raw tile counts: directly when there are few tiles (TWO_LEVEL false), through
+// the group sums of k_super_sums otherwise.
+template <bool FIRST, bool TWO_LEVEL>
 __global__ __launch_bounds__(kThreads) void k_scatter(const int32_t *__restrict__ keys_in,
                                                       const int32_t *__restrict__ pay_in,
                                                       int32_t *__restrict__ keys_out,
                                                       int32_t *__restrict__ pay_out, int32_t nnz, int shift,
-                                                      int bits, int ntiles, const int32_t *__restrict__ table)
+                                                      int bits, int ntiles, const int32_t *__restrict__ table,
+                                                      const int32_t *__restrict__ super)
 {
     __shared__ int32_t s_goff[256];
     __shared__ int32_t s_hist[4][256];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int radix = 1 << bits;
     for (int i = tid; i < 4 * 256; i += kThreads) (&s_hist[0][0])[i] = 0;
-    if (SELF_SCAN) {
+    if (TWO_LEVEL) {
+        int32_t below = 0, total = 0;
+        if (tid < radix) {
+            const int me = (int)blockIdx.x, g_me = me / kSuperTile, ngroups = (ntiles + kSuperTile - 1) / kSuperTile;
+            int g = 0;
+            for (; g + 3 < ngroups; g += 4) {
+                int32_t v0 = super[g * radix + tid], v1 = super[(g + 1) * radix + tid];
+                int32_t v2 = super[(g + 2) * radix + tid], v3 = super[(g + 3) * radix + tid];
+                total += (v0 + v1) + (v2 + v3);
+                below += (g < g_me ? v0 : 0) + (g + 1 < g_me ? v1 : 0) + (g + 2 < g_me ? v2 : 0) + (g + 3 < g_me ? v3 : 0);
+            }
+            for (; g < ngroups; ++g) {
+                int32_t v = super[g * radix + tid];
+                total += v;
+                below += g < g_me ? v : 0;
+            }
+#pragma unroll 8
+            for (int t = g_me * kSuperTile; t < me; ++t) below += table[t * radix + tid];
+        }
+        int32_t base = block_exclusive_scan(total, nullptr);
+        s_goff[tid] = base + below;
+    } else {
         // all 256 threads share the table: thread (digit d, part q) sums tiles q, q+parts, ...
         __shared__ int32_t s_tot[256], s_bel[256];
         const int parts = kThreads >> bits, d = tid & (radix - 1), q = tid >> bits;
@@ -189,8 +209,6 @@ __global__ __launch_bounds__(kThreads) void k_scatter(const int32_t *__restrict_
             }
         int32_t base = block_exclusive_scan(total, nullptr);
         s_goff[tid] = base + below;
-    } else if (tid < radix) {
-        s_goff[tid] = table[blockIdx.x * radix + tid];
     }
     __syncthreads();
 
@@ -295,23 +313,53 @@ __global__ __launch_bounds__(kThreads) void k_seg_write(const int32_t *__restric
         n_touched[0] = s_base + tile_total;
         seg_ptr[s_base + tile_total] = nnz;
     }
+    int32_t o_seg[kSortItems], o_row[kSortItems], o_pk[kSortItems];
+    int8_t o_sign[kSortItems];
+    const bool whole = e0 + kSortItems <= nnz;   // e0 is a multiple of 8: 32-byte vector accesses are aligned
+    int32_t pp[kSortItems];
+    if (whole) {
+        const int4 a = *reinterpret_cast<const int4 *>(pay + e0), b = *reinterpret_cast<const int4 *>(pay + e0 + 4);
+        pp[0] = a.x; pp[1] = a.y; pp[2] = a.z; pp[3] = a.w; pp[4] = b.x; pp[5] = b.y; pp[6] = b.z; pp[7] = b.w;
+    } else {
+#pragma unroll
+        for (int i = 0; i < kSortItems; ++i) pp[i] = e0 + i < nnz ? pay[e0 + i] : 0;
+    }
 #pragma unroll
     for (int i = 0; i < kSortItems; ++i) {
         int32_t e = e0 + i;
-        if (e < nnz) {
-            bool head = kk[i + 1] != kk[i];   // e == 0: kk[0] = -1 differs from every column id
-            if (head) {
-                ++seg;
-                touched_cols[seg] = kk[i + 1];
-                seg_ptr[seg] = e;
-            }
-            int32_t p = pay[e];
-            int32_t row = p / 3;
-            int32_t neg = (p - 3 * row) == 2 ? 1 : 0;
-            seg_id[e] = seg;
-            row_idx[e] = row;
-            sign[e] = neg ? (int8_t)-1 : (int8_t)1;
-            packed[e] = (row << 2) | (head ? 2 : 0) | neg;
+        bool head = e < nnz && kk[i + 1] != kk[i];   // e == 0: kk[0] = -1 differs from every column id
+        if (head) {
+            ++seg;
+            touched_cols[seg] = kk[i + 1];
+            seg_ptr[seg] = e;
+        }
+        int32_t row = pp[i] / 3;
+        int32_t neg = (pp[i] - 3 * row) == 2 ? 1 : 0;
+        o_seg[i] = seg;
+        o_row[i] = row;
+        o_sign[i] = neg ? (int8_t)-1 : (int8_t)1;
+        o_pk[i] = (row << 2) | (head ? 2 : 0) | neg;
+    }
+    if (whole) {
+        static_assert(kSortItems == 8, "vector stores below assume 8 entries per thread");
+        *reinterpret_cast<int4 *>(seg_id + e0) = make_int4(o_seg[0], o_seg[1], o_seg[2], o_seg[3]);
+        *reinterpret_cast<int4 *>(seg_id + e0 + 4) = make_int4(o_seg[4], o_seg[5], o_seg[6], o_seg[7]);
+        *reinterpret_cast<int4 *>(row_idx + e0) = make_int4(o_row[0], o_row[1], o_row[2], o_row[3]);
+        *reinterpret_cast<int4 *>(row_idx + e0 + 4) = make_int4(o_row[4], o_row[5], o_row[6], o_row[7]);
+        *reinterpret_cast<int4 *>(packed + e0) = make_int4(o_pk[0], o_pk[1], o_pk[2], o_pk[3]);
+        *reinterpret_cast<int4 *>(packed + e0 + 4) = make_int4(o_pk[4], o_pk[5], o_pk[6], o_pk[7]);
+        uint32_t s0 = 0, s1 = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            s0 |= (uint32_t)(uint8_t)o_sign[i] << (8 * i);
+            s1 |= (uint32_t)(uint8_t)o_sign[4 + i] << (8 * i);
+        }
+        *reinterpret_cast<uint2 *>(sign + e0) = make_uint2(s0, s1);
+    } else {
+#pragma unroll
+        for (int i = 0; i < kSortItems; ++i) {
+            int32_t e = e0 + i;
+            if (e < nnz) { seg_id[e] = o_seg[i]; row_idx[e] = o_row[i]; sign[e] = o_sign[i]; packed[e] = o_pk[i]; }
         }
     }
 }
@@ -351,7 +399,8 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
     int bits0 = c->sort_bits < c->digit_bits ? c->sort_bits : c->digit_bits;
     hipLaunchKernelGGL(k_emit, dim3(ntiles), dim3(kThreads), 0, s, bp, n_ent, n_rel, nnz, inc->a_rowptr,
                        inc->a_colidx, inc->a_vals, c->keys[0], 1 << bits0, ntiles, c->table, c->ctrl);
-    const bool self_scan = ntiles <= kSelfScanTiles;
+    const bool two_level = ntiles > kSelfScanTiles;
+    const int ngroups = (ntiles + kSuperTile - 1) / kSuperTile;
     int cur = 0;
     for (int p = 0; p < c->sort_passes; ++p) {
         int shift = p * c->digit_bits;
@@ -359,12 +408,17 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
         if (p > 0)
             hipLaunchKernelGGL(k_hist, dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], nnz, shift, 1 << bits,
                                c->table);
-        if (!self_scan) hipLaunchKernelGGL(k_scan_table, dim3(1), dim3(kThreads), 0, s, c->table, 1 << bits, ntiles);
+        if (two_level)
+            hipLaunchKernelGGL(k_super_sums, dim3(ngroups), dim3(kThreads), 0, s, c->table, 1 << bits, ntiles,
+                               c->super);
 #define STX_SCATTER(F, S)                                                                                     \
     hipLaunchKernelGGL((k_scatter<F, S>), dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], c->pay[cur],       \
-                       c->keys[cur ^ 1], c->pay[cur ^ 1], nnz, shift, bits, ntiles, c->table)
-        if (p == 0) { if (self_scan) STX_SCATTER(true, true); else STX_SCATTER(true, false); }
-        else        { if (self_scan) STX_SCATTER(false, true); else STX_SCATTER(false, false); }
+                       c->keys[cur ^ 1], c->pay[cur ^ 1], nnz, shift, bits, ntiles, c->table, c->super)
+        {
+            ProfScope prof(c, "k_scatter");
+            if (p == 0) { if (two_level) STX_SCATTER(true, true); else STX_SCATTER(true, false); }
+            else        { if (two_level) STX_SCATTER(false, true); else STX_SCATTER(false, false); }
+        }
 #undef STX_SCATTER
         cur ^= 1;
     }

@@ -51,7 +51,15 @@ __global__ __launch_bounds__(kThreads) void k_finish_loss(const float *__restric
     __shared__ double s_acc[kThreads];
     const int tid = threadIdx.x;
     double a = 0.0;
-    for (int i = tid; i < n; i += kThreads) a += (double)partials[i];
+    int i = tid;
+    for (; i + 7 * kThreads < n; i += 8 * kThreads) {   // eight loads in flight, added in index order
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = partials[i + u * kThreads];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a += (double)v[u];
+    }
+    for (; i < n; i += kThreads) a += (double)partials[i];
     s_acc[tid] = a;
     __syncthreads();
     for (int off = kThreads / 2; off >= 1; off >>= 1) {
@@ -156,11 +164,14 @@ static void forward_go(stx_ctx *c, const stx_incidence *inc, const stx_params *p
                        inc->a_colidx, p->ent, inc->b, inc->k, width, c->cfg.margin, scale, scores, c->gbuf[0],  \
                        c->loss_partials)
 #define STX_FWD2(D) do { if (from_y) STX_FWD(D, true); else STX_FWD(D, false); } while (0)
+    {
+    ProfScope prof(c, "k_forward_stacked");
     switch (c->cfg.dist) {
     case STX_L1: STX_FWD2(STX_L1); break;
     case STX_L2: STX_FWD2(STX_L2); break;
     case STX_TORUS_L1: STX_FWD2(STX_TORUS_L1); break;
     default: STX_FWD2(STX_TORUS_L2); break;
+    }
     }
 #undef STX_FWD2
 #undef STX_FWD

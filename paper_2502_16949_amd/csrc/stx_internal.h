@@ -12,6 +12,7 @@ constexpr int kThreads = 256;          // every kernel here runs 256-thread work
 constexpr int kSortItems = 8;          // keys per thread in the radix-sort kernels
 constexpr int kSortTile = kThreads * kSortItems;
 constexpr int kSegTile = 256;          // sorted entries per workgroup in the transposed product
+constexpr int kSuperTile = 32;         // sort tiles per group when the histogram table is scanned in two levels
 constexpr int kSelfScanTiles = 128;   // up to this many sort tiles, scatter workgroups scan the histograms themselves
 constexpr int kMaxDim = 1024;
 constexpr int kMaxProjDim = 256;        // TransR: dim and rel_dim are multiples of 32 up to this
@@ -48,10 +49,15 @@ struct stx_ctx {
     int32_t *keys[2];
     int32_t *pay[2];
     int32_t *table;                // [256 * ntiles_max] digit-major tile histograms / offsets
+    int32_t *super;                // [256 * (ntiles_max / kSuperTile + 1)] group sums of the tile histograms
     int32_t *tile_heads;           // [ntiles_max + 1]
     float *loss_partials;          // [fwd_blocks_max]
     float *partials;               // [(nnz_max/kSegTile + 2) * 2 * ld]
     float *gbuf[4];                // per-row buffers, rows_max x ld each (how many depends on the model)
+    // optional live timing of one kernel (stx_profile_kernel): event pairs around its launches
+    char prof_name[48];
+    hipEvent_t *prof_ev;           // 2 * prof_cap events, null when profiling is off
+    int prof_cap, prof_n;
     // host-side call-order state
     const stx_incidence *fwd_inc;  // incidence of the last stx_forward, null if none
     int64_t fwd_rows;
@@ -91,5 +97,26 @@ stx_status launch_forward_transh(stx_ctx *, const stx_incidence *, const stx_par
 stx_status launch_finish_loss(stx_ctx *, int n_partials, float scale, float *loss);
 
 inline stx_status hip_ok(hipError_t e) { return e == hipSuccess ? STX_OK : STX_ERR_HIP; }
+
+// Brackets the launches of the kernel selected with stx_profile_kernel by a pair of events on the
+// context's stream.  Costs one string compare per launch when profiling is off.
+struct ProfScope {
+    stx_ctx *c;
+    bool on;
+    ProfScope(stx_ctx *ctx, const char *kernel) : c(ctx), on(false)
+    {
+        if (c->prof_ev && c->prof_n < c->prof_cap && __builtin_strcmp(kernel, c->prof_name) == 0) {
+            on = true;
+            (void)hipEventRecord(c->prof_ev[2 * c->prof_n], c->stream);
+        }
+    }
+    ~ProfScope()
+    {
+        if (on) {
+            (void)hipEventRecord(c->prof_ev[2 * c->prof_n + 1], c->stream);
+            ++c->prof_n;
+        }
+    }
+};
 
 }  // namespace stx

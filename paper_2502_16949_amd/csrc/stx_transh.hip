@@ -115,11 +115,14 @@ static void transh_go(stx_ctx *c, const stx_incidence *inc, const stx_params *p,
     hipLaunchKernelGGL((k_forward_transh<LPR, ITERS, DD>), grid, dim3(kThreads), 0, c->stream, inc->a_colidx,    \
                        p->ent, p->rel, p->w, (int32_t)c->cfg.n_ent, inc->b, inc->k, c->cfg.dim, c->cfg.margin,   \
                        scale, scores, c->gbuf[0], c->gbuf[1], c->gbuf[2], c->loss_partials)
+    {
+    ProfScope prof(c, "k_forward_transh");
     switch (c->cfg.dist) {
     case STX_L1: STX_FWD(STX_L1); break;
     case STX_L2: STX_FWD(STX_L2); break;
     case STX_TORUS_L1: STX_FWD(STX_TORUS_L1); break;
     default: STX_FWD(STX_TORUS_L2); break;
+    }
     }
 #undef STX_FWD
     launch_finish_loss(c, (int)grid.x, scale, loss);

@@ -221,11 +221,23 @@ __global__ __launch_bounds__(kThreads) void k_transr_dm_fixup(ProjArgs p, float 
     const int32_t j0 = (sb - p.e_begin) / kProjRowsDm;
     const int64_t kd = (int64_t)p.k * p.d;
     float *dst = g_proj + (int64_t)(p.touched_cols[s] - p.n_ent) * kd;
-    for (int64_t idx = threadIdx.x; idx < kd; idx += kThreads) {
-        float a = partials[((int64_t)j0 * 2 + 1) * kd + idx];
-        for (int32_t jj = j0 + 1; jj <= j; ++jj) a += partials[((int64_t)jj * 2) * kd + idx];
-        dst[idx] = a;
+    // blockIdx.y slices the matrix: 4 consecutive elements per thread, 1024 per workgroup
+    const int64_t idx = ((int64_t)blockIdx.y * kThreads + threadIdx.x) * 4;
+    if (idx >= kd) return;
+    float4 a = ld4(partials + ((int64_t)j0 * 2 + 1) * kd + idx);
+    int32_t jj = j0 + 1;
+    for (; jj + 3 <= j; jj += 4) {    // four partial matrices in flight, added in chunk order
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = ld4(partials + ((int64_t)(jj + u) * 2) * kd + idx);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { a.x += v[u].x; a.y += v[u].y; a.z += v[u].z; a.w += v[u].w; }
     }
+    for (; jj <= j; ++jj) {
+        float4 v = ld4(partials + ((int64_t)jj * 2) * kd + idx);
+        a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
+    }
+    st4(dst + idx, a);
 }
 
 // M_r <- M_r - lr * dL/dM_r for every relation present in the batch (one workgroup per relation;
@@ -270,6 +282,7 @@ stx_status launch_transr_project(stx_ctx *c, const stx_incidence *inc, const stx
     if (inc->n_rows == 0) return STX_OK;
     ProjArgs a = proj_args(c, inc, p);
     const int chunks = (int)((inc->n_rows + kProjRows - 1) / kProjRows);
+    ProfScope prof(c, "k_transr_project");
     hipLaunchKernelGGL(k_transr_rows<false>, dim3(chunks), dim3(kThreads), 0, c->stream, a, (const float *)nullptr,
                        c->gbuf[0]);
     return hip_ok(hipGetLastError());
@@ -281,12 +294,19 @@ stx_status launch_transr_backward(stx_ctx *c, const stx_incidence *inc, const st
     ProjArgs a = proj_args(c, inc, p);
     const int chunks = (int)((inc->n_rows + kProjRows - 1) / kProjRows);
     const int chunks_dm = (int)((inc->n_rows + kProjRowsDm - 1) / kProjRowsDm);
-    hipLaunchKernelGGL(k_transr_rows<true>, dim3(chunks), dim3(kThreads), 0, c->stream, a, c->gbuf[0], c->gbuf[1]);
-    hipLaunchKernelGGL(k_transr_dm, dim3(chunks_dm), dim3(kThreads), 0, c->stream, a, c->gbuf[0], g->proj,
-                       c->gbuf[2]);
-    if (chunks_dm > 1)
-        hipLaunchKernelGGL(k_transr_dm_fixup, dim3(chunks_dm - 1), dim3(kThreads), 0, c->stream, a, g->proj,
+    {
+        ProfScope prof(c, "k_transr_gx");
+        hipLaunchKernelGGL(k_transr_rows<true>, dim3(chunks), dim3(kThreads), 0, c->stream, a, c->gbuf[0], c->gbuf[1]);
+    }
+    {
+        ProfScope prof(c, "k_transr_dm");
+        hipLaunchKernelGGL(k_transr_dm, dim3(chunks_dm), dim3(kThreads), 0, c->stream, a, c->gbuf[0], g->proj,
                            c->gbuf[2]);
+    }
+    if (chunks_dm > 1)
+        hipLaunchKernelGGL(k_transr_dm_fixup,
+                           dim3(chunks_dm - 1, (unsigned)(((int64_t)a.k * a.d + 4 * kThreads - 1) / (4 * kThreads))),
+                           dim3(kThreads), 0, c->stream, a, g->proj, c->gbuf[2]);
     return hip_ok(hipGetLastError());
 }
 

@@ -53,7 +53,9 @@ WORKLOADS = {
                     1.1, 1.3),
     "transh": Workload("transh", 3, "transh", "l2", 15_000, 1_350, 480_000, 128, 128, 32_768, 1, 1.0, 0.01,
                        20, 1.1, 1.3),
-    "transr": Workload("transr", 4, "transr", "l2", 14_500, 237, 272_000, 128, 128, 16_384, 1, 1.0, 0.01,
+    # no learning rate is given for this configuration; 0.01 with a summed loss diverges within an epoch
+    # (M_r receives thousands of rank-one terms per step), so the paper's own 0.0004 (Sec. 5.3) is used
+    "transr": Workload("transr", 4, "transr", "l2", 14_500, 237, 272_000, 128, 128, 16_384, 1, 1.0, 0.0004,
                        20, 1.1, 1.3, True),
     "toruse": Workload("toruse", 5, "toruse", "torus_l1", 4_000_000, 1_000, 20_000_000, 128, 128, 262_144,
                        4, 1.0, 0.01, 1, 1.05, 1.2),
