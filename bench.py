@@ -38,6 +38,9 @@ def parse():
     ap.add_argument("--config", default="mid", help="workload: tiny | mid | transh | transr | toruse")
     ap.add_argument("--kernel", default=None, help="kernel to time for the roofline entry (default: the dominant one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="instead of the benchmark, run the library's plain copy kernel 20 times on MIB MiB "
+                         "(for scaling rocprofv3 byte counters) and exit")
     ap.add_argument("--cpu-steps", type=int, default=0, help="oracle steps to time (0 = pick for ~10-20 s)")
     return ap.parse_args()
 
@@ -105,6 +108,16 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     dev = "cuda:0"
+    if args.copy_calibration:
+        n = args.copy_calibration * (1 << 20) // 4
+        cctx = B.Context(B.make_config("transe", "l1", 16, 1, 4, 1, 0), dev)
+        src = torch.ones(n, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(20):
+            B.stx_copy_f32(cctx, dst, src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": 4 * n, "bytes_written": 4 * n, "launches": 20}))
+        return
     wl = W.WORKLOADS[args.config]
     kernel = args.kernel or DOMINANT[wl.model]
 

@@ -189,6 +189,11 @@ stx_status stx_sgd_step(stx_ctx *ctx, stx_params *p, const stx_incidence *inc, c
 stx_status stx_profile_kernel(stx_ctx *ctx, const char *kernel_name /* host */, int32_t max_records);
 stx_status stx_profile_read(stx_ctx *ctx, double *avg_us, int32_t *n);
 
+/* Measurement aid: dst[i] = src[i] for n floats (n % 4 == 0, both 16-byte aligned) by a plain
+ * grid-stride copy kernel ("k_copy_f32") that reads 4n and writes 4n bytes.  Profilers' hardware byte
+ * counters are scaled by what they report for this known traffic.                                     */
+stx_status stx_copy_f32(stx_ctx *ctx, float *dst, const float *src, int64_t n);
+
 const char *stx_status_string(stx_status s);
 
 #ifdef __cplusplus

@@ -367,6 +367,13 @@ stx_status stx_sgd_step(stx_ctx *ctx, stx_params *p, const stx_incidence *inc, c
     return launch_transr_sgd_proj(ctx, inc, p, g, lr);
 }
 
+stx_status stx_copy_f32(stx_ctx *ctx, float *dst, const float *src, int64_t n)
+{
+    if (!ctx || !dst || !src) return STX_ERR_NULL;
+    if (n < 0 || n % 4 != 0 || ((uintptr_t)dst & 15u) || ((uintptr_t)src & 15u)) return STX_ERR_BAD_ARG;
+    return launch_copy_f32(ctx, dst, src, n);
+}
+
 const char *stx_status_string(stx_status s)
 {
     switch (s) {

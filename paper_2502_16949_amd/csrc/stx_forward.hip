@@ -121,6 +121,21 @@ __global__ __launch_bounds__(kThreads) void k_forward_stacked(const int32_t *__r
 
 __global__ void k_zero_loss(float *loss) { loss[0] = 0.f; }
 
+__global__ __launch_bounds__(kThreads) void k_copy_f32(float *__restrict__ dst, const float *__restrict__ src, int64_t n4)
+{
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += (int64_t)gridDim.x * kThreads)
+        st4(dst + 4 * i, ld4(src + 4 * i));
+}
+
+stx_status launch_copy_f32(stx_ctx *c, float *dst, const float *src, int64_t n)
+{
+    if (n == 0) return STX_OK;
+    int64_t n4 = n / 4, blocks = (n4 + kThreads - 1) / kThreads;
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL(k_copy_f32, dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, dst, src, n4);
+    return hip_ok(hipGetLastError());
+}
+
 stx_status launch_finish_loss(stx_ctx *c, int n_partials, float scale, float *loss)
 {
     if (n_partials <= 0) hipLaunchKernelGGL(k_zero_loss, dim3(1), dim3(1), 0, c->stream, loss);

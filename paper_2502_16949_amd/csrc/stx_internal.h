@@ -74,6 +74,7 @@ stx_status launch_clear_ctrl(stx_ctx *);
 // stx_forward.hip
 stx_status launch_spmm(stx_ctx *, const stx_incidence *, const stx_params *, float *c_out);
 stx_status launch_forward_stacked(stx_ctx *, const stx_incidence *, const stx_params *, float *scores, float *loss);
+stx_status launch_copy_f32(stx_ctx *, float *dst, const float *src, int64_t n);
 // stx_backward.hip
 // out_rows[segment] = signed sum of source rows over the sorted entries [e_begin, e_end); entries
 // before `split` read src_a, the others src_b (both with ld_src floats per row, `width` of them used).
