@@ -50,9 +50,11 @@ def kernel_work(wl, kernel, rows, touched):
     row = 4*dim bytes.  rows = b*(1+k) matrix rows, nnz = 3*rows, touched = distinct columns."""
     row = 4 * wl.dim
     nnz = 3 * rows
+    packed = wl.model in ("transe", "toruse") and wl.dist in ("l1", "torus_l1")
+    grow = (wl.dim // 4 + 4) if packed else row     # a stored dL/dx row: sign bytes + coefficient, or dense fp32
     if kernel == "k_forward_stacked" and wl.model in ("transe", "toruse"):
         # 3 gathered table rows + 12 B of column ids per row in; dL/dx row + score out
-        return rows * (3 * row + 12 + row + 4), "GB/s", "hbm", HBM_PEAK_GBS
+        return rows * (3 * row + 12 + grow + 4), "GB/s", "hbm", HBM_PEAK_GBS
     if kernel == "k_forward_stacked":   # TransR: y row in, dL/dy row out, score out
         return rows * (2 * 4 * wl.rel_dim + 4), "GB/s", "hbm", HBM_PEAK_GBS
     if kernel == "k_forward_transh":
@@ -61,7 +63,7 @@ def kernel_work(wl, kernel, rows, touched):
     if kernel == "k_seg_reduce":
         # first launch of the backward call: one source row + 4 B packed entry per sorted entry in, one row per column out
         n = nnz if wl.model != "transr" else 2 * rows
-        return n * (row + 4) + touched * row, "GB/s", "hbm", HBM_PEAK_GBS
+        return n * (grow + 4) + touched * row, "GB/s", "hbm", HBM_PEAK_GBS
     if kernel == "k_sgd_rows":
         return touched * 3 * row, "GB/s", "hbm", HBM_PEAK_GBS
     if kernel == "k_scatter":

@@ -6,7 +6,7 @@
 // make segment lengths wildly uneven (one entity can own >10% of all entries), so work is split by
 // entries, not by segments:
 //
-//   k_seg_reduce   each workgroup owns kSegTile consecutive sorted entries, each of its lane groups a
+//   k_seg_reduce   each workgroup owns a tile of consecutive sorted entries, each of its lane groups a
 //                  chunk of LPR of them.  A group walks its chunk in order, adding signed G rows into
 //                  registers and closing a run whenever an entry is flagged as a segment head.  Runs that
 //                  lie inside the chunk are stored to the output directly.  A chunk's first / last run
@@ -60,7 +60,10 @@ __device__ inline void store_row(float *__restrict__ p, int d4, int lig, const A
     }
 }
 
-template <int LPR, int ITERS>
+// PACKED: the source rows are sign bytes (src_a, dim/4 bytes per row) times a coefficient per row
+// (src_b), as the forward pass of an L1-kind distance stores them; values and summation order are the
+// same as with dense rows, so both forms give the same bits.
+template <int LPR, int ITERS, bool PACKED, int CHUNK>
 __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restrict__ packed,
                                                          const int32_t *__restrict__ seg_id, int32_t e_begin,
                                                          int32_t e_end, const float *__restrict__ src_a,
@@ -69,22 +72,26 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
                                                          int ld_out, float *__restrict__ partials)
 {
     constexpr int GROUPS = kThreads / LPR;
-    constexpr int UNROLL = ITERS == 1 ? 8 : (ITERS == 2 ? 4 : 2);
+    // rows in flight per lane: dense rows cost 4*ITERS registers each; packed rows are a byte and a float,
+    // so a whole chunk is fetched at once and the kernel pays one memory latency per chunk
+    constexpr int UNROLL = PACKED ? CHUNK / (ITERS > 2 ? 2 : 1) : (ITERS == 1 ? 8 : (ITERS == 2 ? 4 : 2));
+    constexpr int TILE = GROUPS * CHUNK;    // sorted entries per workgroup
+    static_assert(CHUNK <= LPR && CHUNK % UNROLL == 0, "one entry per lane per chunk");
+    constexpr int VROWS = PACKED ? 1 : UNROLL;
     constexpr int ROWF = ITERS * LPR * 4;   // floats per staged row in LDS
     __shared__ float s_part[GROUPS][2][ROWF];
     __shared__ int s_info[GROUPS];
     __shared__ int32_t s_seg_first[GROUPS], s_seg_last[GROUPS];
 
     const int lig = threadIdx.x % LPR, grp = threadIdx.x / LPR;
-    const int32_t tile0 = e_begin + (int32_t)blockIdx.x * kSegTile;
-    const int32_t ec0 = tile0 + grp * (kSegTile / GROUPS);
-    const int32_t ec1 = min(ec0 + kSegTile / GROUPS, e_end);
-    static_assert(kSegTile / GROUPS == LPR, "one entry per lane per chunk");
+    const int32_t tile0 = e_begin + (int32_t)blockIdx.x * TILE;
+    const int32_t ec0 = tile0 + grp * CHUNK;
+    const int32_t ec1 = min(ec0 + CHUNK, e_end);
 
     int info = 0;
     if (ec0 < e_end) {
         const int n = ec1 - ec0;
-        const int32_t meta = (ec0 + lig < ec1) ? packed[ec0 + lig] : 0;
+        const int32_t meta = (lig < CHUNK && ec0 + lig < ec1) ? packed[ec0 + lig] : 0;   // 0: row 0, a safe address
         const int32_t meta0 = __shfl(meta, 0, LPR);
         const bool first_open = (ec0 > e_begin) && !(meta0 & 2);
         const bool right_open = (ec1 < e_end) && !(packed[ec1] & 2);
@@ -115,15 +122,28 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
         };
 
         for (int j0 = 0; j0 < n; j0 += UNROLL) {
-            Acc<ITERS> v[UNROLL];
+            Acc<ITERS> v[VROWS];
             int32_t mu[UNROLL];
+            uint8_t sb[UNROLL][ITERS];
+            float cf[UNROLL];
+            // every lane learns the batch's entries first (shuffles back to back, one wait), then all row
+            // loads go out unconditionally: entries past the end of the chunk carry meta 0, i.e. row 0
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) mu[u] = __shfl(meta, (j0 + u) & (LPR - 1), LPR);
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
-                const int jj = j0 + u;
-                mu[u] = __shfl(meta, jj < LPR ? jj : LPR - 1, LPR);
-                if (jj < n)   // entries before `split` read src_a, the rest src_b (entity vs relation columns)
-                    load_row<LPR, ITERS>((ec0 + jj < split ? src_a : src_b) + (int64_t)(mu[u] >> 2) * ld_src, d4,
-                                         lig, v[u]);
+                const int64_t row = mu[u] >> 2;
+                if constexpr (PACKED) {
+                    const uint8_t *pb = reinterpret_cast<const uint8_t *>(src_a) + row * d4;
+#pragma unroll
+                    for (int it = 0; it < ITERS; ++it) {
+                        const int j = lig + it * LPR;
+                        sb[u][it] = j < d4 ? pb[j] : (uint8_t)0;
+                    }
+                    cf[u] = src_b[row];
+                } else {   // entries before `split` read src_a, the rest src_b (entity vs relation columns)
+                    load_row<LPR, ITERS>((ec0 + j0 + u < split ? src_a : src_b) + row * ld_src, d4, lig, v[u]);
+                }
             }
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
@@ -134,14 +154,25 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
                         ++cur_seg;
                         acc.zero();
                     }
+                    constexpr int VI = PACKED ? 0 : 1;
+                    Acc<ITERS> &vu = v[u * VI];
+                    if constexpr (PACKED) {   // expand to the dense row the forward pass would have stored: +c, -c or 0
+                        const float c = cf[u];
+#pragma unroll
+                        for (int it = 0; it < ITERS; ++it) {
+                            const unsigned b = sb[u][it];
+                            vu.v[it] = make_float4((b & 1u) ? c : ((b & 16u) ? -c : 0.f), (b & 2u) ? c : ((b & 32u) ? -c : 0.f),
+                                                   (b & 4u) ? c : ((b & 64u) ? -c : 0.f), (b & 8u) ? c : ((b & 128u) ? -c : 0.f));
+                        }
+                    }
                     if (mu[u] & 1) {
 #pragma unroll
                         for (int it = 0; it < ITERS; ++it) {
-                            acc.v[it].x -= v[u].v[it].x; acc.v[it].y -= v[u].v[it].y;
-                            acc.v[it].z -= v[u].v[it].z; acc.v[it].w -= v[u].v[it].w;
+                            acc.v[it].x -= vu.v[it].x; acc.v[it].y -= vu.v[it].y;
+                            acc.v[it].z -= vu.v[it].z; acc.v[it].w -= vu.v[it].w;
                         }
                     } else {
-                        acc.add(v[u]);
+                        acc.add(vu);
                     }
                 }
             }
@@ -185,7 +216,7 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
     }
 }
 
-template <int LPR, int ITERS>
+template <int LPR, int ITERS, int CHUNK>
 __global__ __launch_bounds__(kThreads) void k_seg_fixup(const int32_t *__restrict__ packed,
                                                         const int32_t *__restrict__ seg_id,
                                                         const int32_t *__restrict__ seg_ptr, int32_t e_begin,
@@ -194,12 +225,14 @@ __global__ __launch_bounds__(kThreads) void k_seg_fixup(const int32_t *__restric
 {
     constexpr int GROUPS = kThreads / LPR;
     constexpr int ROWF = ITERS * LPR * 4;
+    constexpr int TILE = GROUPS * CHUNK;
+    static_assert(TILE <= kThreads, "one thread per entry of the tile in the head search");
     __shared__ float s_sum[GROUPS][ROWF];
     const int32_t j = (int32_t)blockIdx.x + 1;                  // tile 0 never ends a crossing run
-    const int32_t tile0 = e_begin + j * kSegTile;
+    const int32_t tile0 = e_begin + j * TILE;
     if (tile0 >= e_end) return;
     if (packed[tile0] & 2) return;                              // the tile starts a new segment: nothing crosses in
-    const int32_t tile1 = min(tile0 + kSegTile, e_end);
+    const int32_t tile1 = min(tile0 + TILE, e_end);
     const int32_t e = tile0 + (int32_t)threadIdx.x;
     int head_inside = (e > tile0 && e < tile1) ? ((packed[e] >> 1) & 1) : 0;
     const int any_head = __syncthreads_or(head_inside);
@@ -207,7 +240,7 @@ __global__ __launch_bounds__(kThreads) void k_seg_fixup(const int32_t *__restric
     if (!closes) return;                                        // the run goes on; a later tile finishes it
 
     const int32_t seg = seg_id[tile0];
-    const int32_t j0 = (seg_ptr[seg] - e_begin) / kSegTile;     // tile in which the run began
+    const int32_t j0 = (seg_ptr[seg] - e_begin) / TILE;         // tile in which the run began
     const int n = j - j0 + 1;                                   // partial rows: (j0, slot 1), (j0+1 .. j, slot 0)
     const int lig = threadIdx.x % LPR, grp = threadIdx.x / LPR;
     const int per = (n + GROUPS - 1) / GROUPS;
@@ -314,19 +347,32 @@ __global__ __launch_bounds__(kThreads) void k_sgd_rows(const int32_t *__restrict
 // ---- dispatch --------------------------------------------------------------------------------------
 template <int LPR, int ITERS>
 static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_t e_end, const float *src_a,
-                   const float *src_b, int32_t split, int ld_src, int width, float *out_rows, int ld_out)
+                   const float *src_b, int32_t split, int ld_src, int width, float *out_rows, int ld_out,
+                   bool packed_src)
 {
-    const int ntiles = (e_end - e_begin + kSegTile - 1) / kSegTile;
-    {
-    ProfScope prof(c, "k_seg_reduce");
-    hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS>), dim3(ntiles), dim3(kThreads), 0, c->stream, inc->at_packed,
-                       inc->at_seg_id, e_begin, e_end, src_a, src_b, split, ld_src, width / 4, out_rows, ld_out,
-                       c->partials);
-    }
-    if (ntiles > 1)
-        hipLaunchKernelGGL((k_seg_fixup<LPR, ITERS>), dim3(ntiles - 1), dim3(kThreads), 0, c->stream,
-                           inc->at_packed, inc->at_seg_id, inc->at_seg_ptr, e_begin, e_end, width / 4, out_rows,
-                           ld_out, c->partials);
+    // Entries per lane group: short chunks shorten every group's serial walk when the whole product is
+    // small (latency bound); long ones mean fewer partial rows when it is large (bandwidth bound).
+    constexpr int CH_LONG = LPR < 32 ? LPR : 32, CH_SHORT = LPR < 16 ? LPR : 16;
+    constexpr int GROUPS = kThreads / LPR;
+    const bool small = (e_end - e_begin) <= (1 << 20);
+    const int tile = GROUPS * (small ? CH_SHORT : CH_LONG);
+    const int ntiles = (e_end - e_begin + tile - 1) / tile;
+#define STX_SEG(P, CH)                                                                                          \
+    do {                                                                                                        \
+        {                                                                                                       \
+            ProfScope prof(c, "k_seg_reduce");                                                                  \
+            hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH>), dim3(ntiles), dim3(kThreads), 0, c->stream,   \
+                               inc->at_packed, inc->at_seg_id, e_begin, e_end, src_a, src_b, split, ld_src,     \
+                               width / 4, out_rows, ld_out, c->partials);                                       \
+        }                                                                                                       \
+        if (ntiles > 1)                                                                                         \
+            hipLaunchKernelGGL((k_seg_fixup<LPR, ITERS, CH>), dim3(ntiles - 1), dim3(kThreads), 0, c->stream,   \
+                               inc->at_packed, inc->at_seg_id, inc->at_seg_ptr, e_begin, e_end, width / 4,      \
+                               out_rows, ld_out, c->partials);                                                  \
+    } while (0)
+    if (packed_src) { if (small) STX_SEG(true, CH_SHORT); else STX_SEG(true, CH_LONG); }
+    else            { if (small) STX_SEG(false, CH_SHORT); else STX_SEG(false, CH_LONG); }
+#undef STX_SEG
 }
 
 template <int LPR, int ITERS>
@@ -346,12 +392,12 @@ static void sgd_go(stx_ctx *c, const stx_incidence *inc, const SgdTables &T, con
 
 stx_status launch_seg_reduce(stx_ctx *c, const stx_incidence *inc, int64_t e_begin, int64_t e_end,
                              const float *src_a, const float *src_b, int64_t split, int ld_src, int width,
-                             float *out_rows, int ld_out)
+                             float *out_rows, int ld_out, bool packed_src)
 {
     if (e_end <= e_begin) return STX_OK;
     Launch L = row_launch(width);
     STX_DISPATCH_ROW(L, seg_go, c, inc, (int32_t)e_begin, (int32_t)e_end, src_a, src_b, (int32_t)split, ld_src, width,
-                     out_rows, ld_out);
+                     out_rows, ld_out, packed_src);
     return hip_ok(hipGetLastError());
 }
 

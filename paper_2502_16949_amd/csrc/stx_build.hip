@@ -179,34 +179,44 @@ __global__ __launch_bounds__(kThreads) void k_scatter(const int32_t *__restrict_
         int32_t base = block_exclusive_scan(total, nullptr);
         s_goff[tid] = base + below;
     } else {
-        // all 256 threads share the table: thread (digit d, part q) sums tiles q, q+parts, ...
-        __shared__ int32_t s_tot[256], s_bel[256];
-        const int parts = kThreads >> bits, d = tid & (radix - 1), q = tid >> bits;
+        // All 256 threads share the table: a thread owns four neighbouring digits (one 16-byte load per
+        // tile row) and every `parts`-th tile; up to 16 loads are in flight per thread.
+        __shared__ int32_t s_tot[1024], s_bel[1024];
         const int me = (int)blockIdx.x;
         int32_t below = 0, total = 0;
-        int t = q;
-        for (; t + 3 * parts < ntiles; t += 4 * parts) {   // four independent loads in flight
-            int32_t v0 = table[t * radix + d], v1 = table[(t + parts) * radix + d];
-            int32_t v2 = table[(t + 2 * parts) * radix + d], v3 = table[(t + 3 * parts) * radix + d];
-            total += (v0 + v1) + (v2 + v3);
-            below += (t < me ? v0 : 0) + (t + parts < me ? v1 : 0) + (t + 2 * parts < me ? v2 : 0) +
-                     (t + 3 * parts < me ? v3 : 0);
-        }
-        for (; t < ntiles; t += parts) {
-            int32_t v = table[t * radix + d];
-            total += v;
-            below += t < me ? v : 0;
-        }
-        s_tot[tid] = total;
-        s_bel[tid] = below;
-        __syncthreads();
-        total = 0;
-        below = 0;
-        if (tid < radix)
-            for (int qq = 0; qq < parts; ++qq) {
-                total += s_tot[qq * radix + tid];
-                below += s_bel[qq * radix + tid];
+        if (radix >= 4) {
+            const int r4 = radix >> 2, parts = kThreads / r4, d4 = tid % r4, q = tid / r4;
+            int4 tot = make_int4(0, 0, 0, 0), bel = make_int4(0, 0, 0, 0);
+            for (int t0 = q; t0 < ntiles; t0 += 16 * parts) {
+                int4 v[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    const int t = t0 + u * parts;
+                    v[u] = t < ntiles ? *reinterpret_cast<const int4 *>(table + t * radix + 4 * d4)
+                                      : make_int4(0, 0, 0, 0);
+                }
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    const int t = t0 + u * parts;
+                    tot.x += v[u].x; tot.y += v[u].y; tot.z += v[u].z; tot.w += v[u].w;
+                    if (t < me) { bel.x += v[u].x; bel.y += v[u].y; bel.z += v[u].z; bel.w += v[u].w; }
+                }
             }
+            *reinterpret_cast<int4 *>(&s_tot[q * radix + 4 * d4]) = tot;
+            *reinterpret_cast<int4 *>(&s_bel[q * radix + 4 * d4]) = bel;
+            __syncthreads();
+            if (tid < radix)
+                for (int qq = 0; qq < parts; ++qq) {
+                    total += s_tot[qq * radix + tid];
+                    below += s_bel[qq * radix + tid];
+                }
+        } else if (tid < radix) {   // two bins only
+            for (int t = 0; t < ntiles; ++t) {
+                const int32_t v = table[t * radix + tid];
+                total += v;
+                below += t < me ? v : 0;
+            }
+        }
         int32_t base = block_exclusive_scan(total, nullptr);
         s_goff[tid] = base + below;
     }
@@ -264,10 +274,10 @@ __global__ __launch_bounds__(kThreads) void k_seg_count(const int32_t *__restric
     const int tid = threadIdx.x;
     if (tid == 0) s_cnt = 0;
     __syncthreads();
-    const int32_t base = blockIdx.x * kSortTile;
+    const int32_t base = blockIdx.x * kSegWTile;
     int32_t c = 0;
 #pragma unroll
-    for (int it = 0; it < kSortItems; ++it) {
+    for (int it = 0; it < kSegWItems; ++it) {
         int32_t e = base + it * kThreads + tid;
         if (e < nnz) c += (e == 0 || keys[e] != keys[e - 1]) ? 1 : 0;
     }
@@ -296,16 +306,20 @@ __global__ __launch_bounds__(kThreads) void k_seg_write(const int32_t *__restric
         for (int t = tid; t < (int)blockIdx.x; t += kThreads) a += tile_heads[t];
         if (a) atomicAdd(&s_base, a);
     }
-    const int32_t e0 = blockIdx.x * kSortTile + tid * kSortItems;
-    int32_t kk[kSortItems + 1];
+    const int32_t e0 = blockIdx.x * kSegWTile + tid * kSegWItems;
+    int32_t kk[kSegWItems + 1];
     kk[0] = (e0 > 0 && e0 - 1 < nnz) ? keys[e0 - 1] : -1;
+    if (e0 + kSegWItems <= nnz) {
+        const int4 a = *reinterpret_cast<const int4 *>(keys + e0), b = *reinterpret_cast<const int4 *>(keys + e0 + 4);
+        kk[1] = a.x; kk[2] = a.y; kk[3] = a.z; kk[4] = a.w; kk[5] = b.x; kk[6] = b.y; kk[7] = b.z; kk[8] = b.w;
+    } else {
+#pragma unroll
+        for (int i = 0; i < kSegWItems; ++i) kk[i + 1] = e0 + i < nnz ? keys[e0 + i] : -1;
+    }
     int32_t cnt = 0;
 #pragma unroll
-    for (int i = 0; i < kSortItems; ++i) {
-        int32_t e = e0 + i;
-        kk[i + 1] = e < nnz ? keys[e] : -1;
-        if (e < nnz && kk[i + 1] != kk[i]) ++cnt;
-    }
+    for (int i = 0; i < kSegWItems; ++i)
+        if (e0 + i < nnz && kk[i + 1] != kk[i]) ++cnt;
     int32_t tile_total;
     const int32_t before = block_exclusive_scan(cnt, &tile_total);   // its barriers also publish s_base
     int32_t seg = s_base + before - 1;                               // segment of the entry before e0
@@ -313,19 +327,19 @@ __global__ __launch_bounds__(kThreads) void k_seg_write(const int32_t *__restric
         n_touched[0] = s_base + tile_total;
         seg_ptr[s_base + tile_total] = nnz;
     }
-    int32_t o_seg[kSortItems], o_row[kSortItems], o_pk[kSortItems];
-    int8_t o_sign[kSortItems];
-    const bool whole = e0 + kSortItems <= nnz;   // e0 is a multiple of 8: 32-byte vector accesses are aligned
-    int32_t pp[kSortItems];
+    int32_t o_seg[kSegWItems], o_row[kSegWItems], o_pk[kSegWItems];
+    int8_t o_sign[kSegWItems];
+    const bool whole = e0 + kSegWItems <= nnz;   // e0 is a multiple of 8: 32-byte vector accesses are aligned
+    int32_t pp[kSegWItems];
     if (whole) {
         const int4 a = *reinterpret_cast<const int4 *>(pay + e0), b = *reinterpret_cast<const int4 *>(pay + e0 + 4);
         pp[0] = a.x; pp[1] = a.y; pp[2] = a.z; pp[3] = a.w; pp[4] = b.x; pp[5] = b.y; pp[6] = b.z; pp[7] = b.w;
     } else {
 #pragma unroll
-        for (int i = 0; i < kSortItems; ++i) pp[i] = e0 + i < nnz ? pay[e0 + i] : 0;
+        for (int i = 0; i < kSegWItems; ++i) pp[i] = e0 + i < nnz ? pay[e0 + i] : 0;
     }
 #pragma unroll
-    for (int i = 0; i < kSortItems; ++i) {
+    for (int i = 0; i < kSegWItems; ++i) {
         int32_t e = e0 + i;
         bool head = e < nnz && kk[i + 1] != kk[i];   // e == 0: kk[0] = -1 differs from every column id
         if (head) {
@@ -341,7 +355,7 @@ __global__ __launch_bounds__(kThreads) void k_seg_write(const int32_t *__restric
         o_pk[i] = (row << 2) | (head ? 2 : 0) | neg;
     }
     if (whole) {
-        static_assert(kSortItems == 8, "vector stores below assume 8 entries per thread");
+        static_assert(kSegWItems == 8, "vector stores below assume 8 entries per thread");
         *reinterpret_cast<int4 *>(seg_id + e0) = make_int4(o_seg[0], o_seg[1], o_seg[2], o_seg[3]);
         *reinterpret_cast<int4 *>(seg_id + e0 + 4) = make_int4(o_seg[4], o_seg[5], o_seg[6], o_seg[7]);
         *reinterpret_cast<int4 *>(row_idx + e0) = make_int4(o_row[0], o_row[1], o_row[2], o_row[3]);
@@ -357,7 +371,7 @@ __global__ __launch_bounds__(kThreads) void k_seg_write(const int32_t *__restric
         *reinterpret_cast<uint2 *>(sign + e0) = make_uint2(s0, s1);
     } else {
 #pragma unroll
-        for (int i = 0; i < kSortItems; ++i) {
+        for (int i = 0; i < kSegWItems; ++i) {
             int32_t e = e0 + i;
             if (e < nnz) { seg_id[e] = o_seg[i]; row_idx[e] = o_row[i]; sign[e] = o_sign[i]; packed[e] = o_pk[i]; }
         }
@@ -422,8 +436,9 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
 #undef STX_SCATTER
         cur ^= 1;
     }
-    hipLaunchKernelGGL(k_seg_count, dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], nnz, c->tile_heads);
-    hipLaunchKernelGGL(k_seg_write, dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], c->pay[cur], nnz,
+    const int nseg = (nnz + kSegWTile - 1) / kSegWTile;
+    hipLaunchKernelGGL(k_seg_count, dim3(nseg), dim3(kThreads), 0, s, c->keys[cur], nnz, c->tile_heads);
+    hipLaunchKernelGGL(k_seg_write, dim3(nseg), dim3(kThreads), 0, s, c->keys[cur], c->pay[cur], nnz,
                        c->tile_heads, inc->n_touched, inc->at_touched_cols, inc->at_seg_ptr, inc->at_row_idx,
                        inc->at_sign, inc->at_seg_id, inc->at_packed);
     return hip_ok(hipGetLastError());

@@ -9,11 +9,13 @@
 namespace stx {
 
 constexpr int kThreads = 256;          // every kernel here runs 256-thread workgroups (4 wavefronts)
-constexpr int kSortItems = 8;          // keys per thread in the radix-sort kernels
+constexpr int kSortItems = 4;          // keys per thread in the radix-sort kernels
 constexpr int kSortTile = kThreads * kSortItems;
-constexpr int kSegTile = 256;          // sorted entries per workgroup in the transposed product
+constexpr int kSegWItems = 8;          // sorted entries per thread in the kernels that derive the segments
+constexpr int kSegWTile = kThreads * kSegWItems;
+constexpr int kSegTileMin = 64;        // fewest sorted entries a workgroup of the transposed product may own
 constexpr int kSuperTile = 32;         // sort tiles per group when the histogram table is scanned in two levels
-constexpr int kSelfScanTiles = 128;   // up to this many sort tiles, scatter workgroups scan the histograms themselves
+constexpr int kSelfScanTiles = 256;   // up to this many sort tiles, scatter workgroups scan the histograms themselves
 constexpr int kMaxDim = 1024;
 constexpr int kMaxProjDim = 256;        // TransR: dim and rel_dim are multiples of 32 up to this
 constexpr int kProjRows = 64;           // sorted relation entries per workgroup in the projection products
@@ -52,7 +54,7 @@ struct stx_ctx {
     int32_t *super;                // [256 * (ntiles_max / kSuperTile + 1)] group sums of the tile histograms
     int32_t *tile_heads;           // [ntiles_max + 1]
     float *loss_partials;          // [fwd_blocks_max]
-    float *partials;               // [(nnz_max/kSegTile + 2) * 2 * ld]
+    float *partials;               // [(nnz_max/kSegTileMin + 2) * 2 * ld]
     float *gbuf[4];                // per-row buffers, rows_max x ld each (how many depends on the model)
     // optional live timing of one kernel (stx_profile_kernel): event pairs around its launches
     char prof_name[48];
@@ -78,8 +80,10 @@ stx_status launch_copy_f32(stx_ctx *, float *dst, const float *src, int64_t n);
 // stx_backward.hip
 // out_rows[segment] = signed sum of source rows over the sorted entries [e_begin, e_end); entries
 // before `split` read src_a, the others src_b (both with ld_src floats per row, `width` of them used).
+// packed_src: src_a is the sign-byte array and src_b the per-row coefficients of packed L1-kind rows.
 stx_status launch_seg_reduce(stx_ctx *, const stx_incidence *, int64_t e_begin, int64_t e_end, const float *src_a,
-                             const float *src_b, int64_t split, int ld_src, int width, float *out_rows, int ld_out);
+                             const float *src_b, int64_t split, int ld_src, int width, float *out_rows, int ld_out,
+                             bool packed_src = false);
 struct SgdTables {
     float *table_a; int width_a; int mode_a;   // columns [0, n_split)
     int64_t n_split;
@@ -96,6 +100,19 @@ stx_status launch_transr_sgd_proj(stx_ctx *, const stx_incidence *, stx_params *
 // stx_transh.hip
 stx_status launch_forward_transh(stx_ctx *, const stx_incidence *, const stx_params *, float *scores, float *loss);
 stx_status launch_finish_loss(stx_ctx *, int n_partials, float scale, float *loss);
+
+// TransE / TorusE with an L1-kind distance keep dL/dx packed inside gbuf[0]: rows_max * dim/4 sign
+// bytes first, then (256-byte aligned) rows_max coefficients.
+inline bool packed_grad(const stx_ctx *c)
+{
+    return (c->cfg.model == STX_TRANSE || c->cfg.model == STX_TORUSE) &&
+           (c->cfg.dist == STX_L1 || c->cfg.dist == STX_TORUS_L1);
+}
+inline float *packed_coef(const stx_ctx *c)
+{
+    size_t off = ((size_t)c->rows_max * (c->cfg.dim / 4) + 255) / 256 * 256;
+    return reinterpret_cast<float *>(reinterpret_cast<char *>(c->gbuf[0]) + off);
+}
 
 inline stx_status hip_ok(hipError_t e) { return e == hipSuccess ? STX_OK : STX_ERR_HIP; }
 
