@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--config", default="mid", help="workload: tiny | mid | transh | transr | toruse")
     ap.add_argument("--kernel", default=None, help="kernel to time for the roofline entry (default: the dominant one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--all-kernels", action="store_true",
+                    help="extra untimed pass that brackets every kernel with events and adds 'kernels_us' to the output")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run the library's plain copy kernel 20 times on MIB MiB "
                          "(for scaling rocprofv3 byte counters) and exit")
@@ -242,6 +244,13 @@ def main():
         "loss_last_step": loss_last,
         "roofline": roofline,
     }
+
+    if args.all_kernels:
+        B.stx_profile_kernel(ctx, "*", 40 * n_ph)
+        for i in range(n_ph):
+            step(args.warmup + args.steps + n_ph + i)
+        out["kernels_us"] = {k: [round(v[0], 2), round(v[1] / n_ph, 2)] for k, v in B.stx_profile_dump(ctx).items()}
+        B.stx_profile_kernel(ctx, None, 0)
 
     if not args.no_cpu_baseline:
         n = args.cpu_steps

@@ -185,9 +185,14 @@ stx_status stx_sgd_step(stx_ctx *ctx, stx_params *p, const stx_incidence *inc, c
  * context is bracketed by a pair of HIP events on the context's stream, for at most max_records
  * launches; a null name or max_records == 0 switches timing off.  stx_profile_read: waits for the
  * stream, then *avg_us (host) = mean bracketed time in microseconds and *n (host) = launches recorded;
- * recording restarts from zero.  Not to be used while the stream is being captured into a graph.     */
+ * recording restarts from zero.  The name "*" brackets every kernel that has a bracket (all but a few
+ * one-workgroup helpers); stx_profile_dump then writes one line "name mean_us launches" per kernel into
+ * text (host, text_bytes long, NUL-terminated) and restarts recording.  Bracketing every kernel adds
+ * event work to the stream: use it to see where time goes, not to time a whole step.  Not to be used
+ * while the stream is being captured into a graph.                                                     */
 stx_status stx_profile_kernel(stx_ctx *ctx, const char *kernel_name /* host */, int32_t max_records);
 stx_status stx_profile_read(stx_ctx *ctx, double *avg_us, int32_t *n);
+stx_status stx_profile_dump(stx_ctx *ctx, char *text, size_t text_bytes);
 
 /* Measurement aid: dst[i] = src[i] for n floats (n % 4 == 0, both 16-byte aligned) by a plain
  * grid-stride copy kernel ("k_copy_f32") that reads 4n and writes 4n bytes.  Profilers' hardware byte

@@ -26,7 +26,7 @@ DISTS = {"l1": STX_L1, "l2": STX_L2, "torus_l1": STX_TORUS_L1, "torus_l2": STX_T
 
 EXPORTS = ["stx_workspace_bytes", "stx_create", "stx_destroy", "stx_sample_negatives", "stx_build_incidence",
            "stx_check_indices", "stx_spmm", "stx_forward", "stx_backward", "stx_sgd_step", "stx_profile_kernel",
-           "stx_profile_read", "stx_copy_f32", "stx_status_string"]
+           "stx_profile_read", "stx_profile_dump", "stx_copy_f32", "stx_status_string"]
 
 
 class StxError(RuntimeError):
@@ -82,6 +82,7 @@ def lib():
                                    C.c_float]
         L.stx_profile_kernel.argtypes = [vp, C.c_char_p, i32]
         L.stx_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32)]
+        L.stx_profile_dump.argtypes = [vp, C.c_char_p, C.c_size_t]
         L.stx_copy_f32.argtypes = [vp, vp, vp, i64]
         L.stx_status_string.argtypes = [C.c_int]
         L.stx_status_string.restype = C.c_char_p
@@ -270,3 +271,14 @@ def stx_profile_read(ctx: Context):
 def stx_copy_f32(ctx: Context, dst, src):
     assert dst.numel() == src.numel() and dst.dtype == src.dtype == torch.float32
     _check("stx_copy_f32", lib().stx_copy_f32(ctx.handle, dst.data_ptr(), src.data_ptr(), src.numel()))
+
+
+def stx_profile_dump(ctx: Context) -> dict:
+    """{kernel name: (mean microseconds, launches)} of everything recorded since the last read."""
+    buf = C.create_string_buffer(8192)
+    _check("stx_profile_dump", lib().stx_profile_dump(ctx.handle, buf, len(buf)))
+    out = {}
+    for ln in buf.value.decode().splitlines():
+        name, us, n = ln.split()
+        out[name] = (float(us), int(n))
+    return out

@@ -1,5 +1,6 @@
 // C-ABI entry points of libstx: argument checks, workspace layout, call-order state, and dispatch to
 // the kernel launchers.  No arithmetic of the method happens here.
+#include <cstdio>
 #include <new>
 
 #include "stx_internal.h"
@@ -157,6 +158,7 @@ stx_status stx_create(const stx_config *cfg, void *workspace, size_t workspace_b
     c->fwd_inc = nullptr;
     c->fwd_rows = 0;
     c->prof_ev = nullptr;
+    c->prof_tag = nullptr;
     c->prof_cap = c->prof_n = 0;
     c->prof_name[0] = 0;
     s = launch_clear_ctrl(c);
@@ -170,8 +172,10 @@ static void prof_release(stx_ctx *ctx)
     if (ctx->prof_ev) {
         for (int i = 0; i < 2 * ctx->prof_cap; ++i) (void)hipEventDestroy(ctx->prof_ev[i]);
         delete[] ctx->prof_ev;
+        delete[] ctx->prof_tag;
     }
     ctx->prof_ev = nullptr;
+    ctx->prof_tag = nullptr;
     ctx->prof_cap = ctx->prof_n = 0;
     ctx->prof_name[0] = 0;
 }
@@ -193,16 +197,61 @@ stx_status stx_profile_kernel(stx_ctx *ctx, const char *kernel_name, int32_t max
     size_t len = __builtin_strlen(kernel_name);
     if (len == 0 || len >= sizeof(ctx->prof_name)) return STX_ERR_BAD_ARG;
     ctx->prof_ev = new (std::nothrow) hipEvent_t[2 * (size_t)max_records];
-    if (!ctx->prof_ev) return STX_ERR_BAD_ARG;
+    ctx->prof_tag = new (std::nothrow) const char *[(size_t)max_records];
+    if (!ctx->prof_ev || !ctx->prof_tag) {
+        delete[] ctx->prof_ev;
+        delete[] ctx->prof_tag;
+        ctx->prof_ev = nullptr;
+        ctx->prof_tag = nullptr;
+        return STX_ERR_BAD_ARG;
+    }
     for (int i = 0; i < 2 * max_records; ++i)
         if (hipEventCreate(&ctx->prof_ev[i]) != hipSuccess) {
             for (int j = 0; j < i; ++j) (void)hipEventDestroy(ctx->prof_ev[j]);
             delete[] ctx->prof_ev;
+            delete[] ctx->prof_tag;
             ctx->prof_ev = nullptr;
+            ctx->prof_tag = nullptr;
             return STX_ERR_HIP;
         }
     ctx->prof_cap = max_records;
     __builtin_memcpy(ctx->prof_name, kernel_name, len + 1);
+    return STX_OK;
+}
+
+stx_status stx_profile_dump(stx_ctx *ctx, char *text, size_t text_bytes)
+{
+    if (!ctx || !text) return STX_ERR_NULL;
+    if (text_bytes == 0) return STX_ERR_BAD_ARG;
+    text[0] = 0;
+    if (!ctx->prof_ev) return STX_ERR_STATE;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return STX_ERR_HIP;
+    const int kMaxNames = 64;
+    const char *names[kMaxNames];
+    double total_ms[kMaxNames];
+    int count[kMaxNames], n_names = 0;
+    for (int i = 0; i < ctx->prof_n; ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]) != hipSuccess) return STX_ERR_HIP;
+        int j = 0;
+        while (j < n_names && __builtin_strcmp(names[j], ctx->prof_tag[i]) != 0) ++j;
+        if (j == n_names) {
+            if (n_names == kMaxNames) continue;
+            names[n_names] = ctx->prof_tag[i];
+            total_ms[n_names] = 0.0;
+            count[n_names] = 0;
+            ++n_names;
+        }
+        total_ms[j] += ms;
+        ++count[j];
+    }
+    size_t used = 0;
+    for (int j = 0; j < n_names; ++j) {
+        int w = snprintf(text + used, text_bytes - used, "%s %.3f %d\n", names[j], total_ms[j] * 1e3 / count[j], count[j]);
+        if (w < 0 || (size_t)w >= text_bytes - used) break;
+        used += (size_t)w;
+    }
+    ctx->prof_n = 0;
     return STX_OK;
 }
 

@@ -74,7 +74,7 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
     constexpr int GROUPS = kThreads / LPR;
     // rows in flight per lane: dense rows cost 4*ITERS registers each; packed rows are a byte and a float,
     // so a whole chunk is fetched at once and the kernel pays one memory latency per chunk
-    constexpr int UNROLL = PACKED ? CHUNK / (ITERS > 2 ? 2 : 1) : (ITERS == 1 ? 8 : (ITERS == 2 ? 4 : 2));
+    constexpr int UNROLL = PACKED ? (CHUNK < 8 ? CHUNK : 8) : (ITERS == 1 ? 8 : (ITERS == 2 ? 4 : 2));
     constexpr int TILE = GROUPS * CHUNK;    // sorted entries per workgroup
     static_assert(CHUNK <= LPR && CHUNK % UNROLL == 0, "one entry per lane per chunk");
     constexpr int VROWS = PACKED ? 1 : UNROLL;
@@ -231,15 +231,18 @@ __global__ __launch_bounds__(kThreads) void k_seg_fixup(const int32_t *__restric
     const int32_t j = (int32_t)blockIdx.x + 1;                  // tile 0 never ends a crossing run
     const int32_t tile0 = e_begin + j * TILE;
     if (tile0 >= e_end) return;
-    if (packed[tile0] & 2) return;                              // the tile starts a new segment: nothing crosses in
     const int32_t tile1 = min(tile0 + TILE, e_end);
     const int32_t e = tile0 + (int32_t)threadIdx.x;
-    int head_inside = (e > tile0 && e < tile1) ? ((packed[e] >> 1) & 1) : 0;
-    const int any_head = __syncthreads_or(head_inside);
-    const bool closes = any_head || tile1 >= e_end || (packed[tile1] & 2);
+    // everything the decision needs is fetched in one round trip
+    const int32_t m_first = packed[tile0];
+    const int32_t m_mine = (e > tile0 && e < tile1) ? packed[e] : 0;
+    const int32_t m_next = tile1 < e_end ? packed[tile1] : 2;
+    const int32_t seg = seg_id[tile0];
+    if (m_first & 2) return;                                    // the tile starts a new segment: nothing crosses in
+    const int any_head = __syncthreads_or((m_mine >> 1) & 1);
+    const bool closes = any_head || (m_next & 2);
     if (!closes) return;                                        // the run goes on; a later tile finishes it
 
-    const int32_t seg = seg_id[tile0];
     const int32_t j0 = (seg_ptr[seg] - e_begin) / TILE;         // tile in which the run began
     const int n = j - j0 + 1;                                   // partial rows: (j0, slot 1), (j0+1 .. j, slot 0)
     const int lig = threadIdx.x % LPR, grp = threadIdx.x / LPR;
@@ -365,10 +368,12 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
                                inc->at_packed, inc->at_seg_id, e_begin, e_end, src_a, src_b, split, ld_src,     \
                                width / 4, out_rows, ld_out, c->partials);                                       \
         }                                                                                                       \
-        if (ntiles > 1)                                                                                         \
+        if (ntiles > 1) {                                                                                       \
+            ProfScope prof(c, "k_seg_fixup");                                                                   \
             hipLaunchKernelGGL((k_seg_fixup<LPR, ITERS, CH>), dim3(ntiles - 1), dim3(kThreads), 0, c->stream,   \
                                inc->at_packed, inc->at_seg_id, inc->at_seg_ptr, e_begin, e_end, width / 4,      \
                                out_rows, ld_out, c->partials);                                                  \
+        }                                                                                                       \
     } while (0)
     if (packed_src) { if (small) STX_SEG(true, CH_SHORT); else STX_SEG(true, CH_LONG); }
     else            { if (small) STX_SEG(false, CH_SHORT); else STX_SEG(false, CH_LONG); }
@@ -382,7 +387,7 @@ static void sgd_go(stx_ctx *c, const stx_incidence *inc, const SgdTables &T, con
     constexpr int GROUPS = kThreads / LPR;
     int64_t cap = inc->nnz < c->cfg.n_ent + c->cfg.n_rel ? inc->nnz : c->cfg.n_ent + c->cfg.n_rel;
     int64_t blocks = (cap + GROUPS - 1) / GROUPS;
-    if (blocks > 8192) blocks = 8192;   // grid-stride beyond this
+    if (blocks > 8192) blocks = 8192;   // grid-stride beyond this (measured faster than one segment per group)
     if (blocks < 1) blocks = 1;
     ProfScope prof(c, "k_sgd_rows");
     hipLaunchKernelGGL((k_sgd_rows<LPR, ITERS>), dim3((unsigned)blocks), dim3(kThreads), 0, c->stream,

@@ -63,6 +63,7 @@ struct BatchPtrs {
 
 // One thread per entry e = 3*row + slot of A.  Writes the CSR arrays and the sort keys (= column ids),
 // and the histogram of the first digit for this tile.
+template <int ITEMS>
 __global__ __launch_bounds__(kThreads) void k_emit(BatchPtrs bp, int32_t n_ent, int32_t n_rel, int32_t nnz,
                                                    int32_t *__restrict__ rowptr, int32_t *__restrict__ colidx,
                                                    float *__restrict__ vals, int32_t *__restrict__ keys,
@@ -73,9 +74,9 @@ __global__ __launch_bounds__(kThreads) void k_emit(BatchPtrs bp, int32_t n_ent, 
     const int tid = threadIdx.x;
     s_hist[tid] = 0;
     __syncthreads();
-    const int32_t base = blockIdx.x * kSortTile;
+    const int32_t base = blockIdx.x * (kThreads * ITEMS);
 #pragma unroll
-    for (int it = 0; it < kSortItems; ++it) {
+    for (int it = 0; it < ITEMS; ++it) {
         int32_t e = base + it * kThreads + tid;
         if (e < nnz) {
             int32_t row = e / 3, slot = e - 3 * row;
@@ -105,6 +106,7 @@ __global__ __launch_bounds__(kThreads) void k_emit(BatchPtrs bp, int32_t n_ent, 
 }
 
 // Tile histograms of the digit at `shift` for the later passes.
+template <int ITEMS>
 __global__ __launch_bounds__(kThreads) void k_hist(const int32_t *__restrict__ keys, int32_t nnz, int shift,
                                                    int radix, int32_t *__restrict__ table)
 {
@@ -112,9 +114,9 @@ __global__ __launch_bounds__(kThreads) void k_hist(const int32_t *__restrict__ k
     const int tid = threadIdx.x;
     s_hist[tid] = 0;
     __syncthreads();
-    const int32_t base = blockIdx.x * kSortTile;
+    const int32_t base = blockIdx.x * (kThreads * ITEMS);
 #pragma unroll
-    for (int it = 0; it < kSortItems; ++it) {
+    for (int it = 0; it < ITEMS; ++it) {
         int32_t e = base + it * kThreads + tid;
         if (e < nnz) atomicAdd(&s_hist[(keys[e] >> shift) & (radix - 1)], 1);
     }
@@ -144,7 +146,7 @@ __global__ __launch_bounds__(kThreads) void k_super_sums(const int32_t *__restri
 // number of keys with a smaller digit anywhere plus those with the same digit in earlier tiles: read
 // derived here from the raw tile counts: directly when there are few tiles (TWO_LEVEL false), through
 // the group sums of k_super_sums otherwise.
-template <bool FIRST, bool TWO_LEVEL>
+template <bool FIRST, bool TWO_LEVEL, int ITEMS>
 __global__ __launch_bounds__(kThreads) void k_scatter(const int32_t *__restrict__ keys_in,
                                                       const int32_t *__restrict__ pay_in,
                                                       int32_t *__restrict__ keys_out,
@@ -222,11 +224,11 @@ __global__ __launch_bounds__(kThreads) void k_scatter(const int32_t *__restrict_
     }
     __syncthreads();
 
-    int32_t key[kSortItems], pay[kSortItems], rank[kSortItems];
-    const int32_t wave_base = blockIdx.x * kSortTile + w * (64 * kSortItems);
+    int32_t key[ITEMS], pay[ITEMS], rank[ITEMS];
+    const int32_t wave_base = blockIdx.x * (kThreads * ITEMS) + w * (64 * ITEMS);
     const uint64_t below = (1ull << lane) - 1ull;
 #pragma unroll
-    for (int it = 0; it < kSortItems; ++it) {
+    for (int it = 0; it < ITEMS; ++it) {
         int32_t e = wave_base + it * 64 + lane;
         bool valid = e < nnz;
         key[it] = valid ? keys_in[e] : 0;
@@ -255,7 +257,7 @@ __global__ __launch_bounds__(kThreads) void k_scatter(const int32_t *__restrict_
     }
     __syncthreads();
 #pragma unroll
-    for (int it = 0; it < kSortItems; ++it) {
+    for (int it = 0; it < ITEMS; ++it) {
         int32_t e = wave_base + it * 64 + lane;
         if (e < nnz) {
             int dgt = (key[it] >> shift) & (radix - 1);
@@ -391,6 +393,7 @@ stx_status launch_sample(stx_ctx *c, const int32_t *h, const int32_t *t, int64_t
     int64_t total = m * k;
     if (total == 0) return STX_OK;
     int64_t blocks = (total + kThreads - 1) / kThreads;
+    ProfScope prof(c, "k_sample");
     hipLaunchKernelGGL(k_sample, dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, h, t, total, k,
                        (uint64_t)c->cfg.n_ent, seed, base_ctr, nh, nt);
     return hip_ok(hipGetLastError());
@@ -406,38 +409,62 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
         return hip_ok(hipGetLastError());
     }
     const int32_t nnz = (int32_t)inc->nnz;
-    const int ntiles = (nnz + kSortTile - 1) / kSortTile;
+    // keys per thread: few when the sort is small (more workgroups, shorter serial ranking per workgroup),
+    // more when it is large (fewer tiles, smaller histogram table)
+    const int items = nnz <= (1 << 19) ? kSortItems : 2 * kSortItems;
+    const int ntiles = (nnz + kThreads * items - 1) / (kThreads * items);
     const int n_ent = (int)c->cfg.n_ent, n_rel = (int)c->cfg.n_rel;
     BatchPtrs bp{h, r, t, nh, nt, b, k > 0 ? k : 1};
 
     int bits0 = c->sort_bits < c->digit_bits ? c->sort_bits : c->digit_bits;
-    hipLaunchKernelGGL(k_emit, dim3(ntiles), dim3(kThreads), 0, s, bp, n_ent, n_rel, nnz, inc->a_rowptr,
-                       inc->a_colidx, inc->a_vals, c->keys[0], 1 << bits0, ntiles, c->table, c->ctrl);
+    {
+    ProfScope prof(c, "k_emit");
+    if (items == kSortItems)
+        hipLaunchKernelGGL(k_emit<kSortItems>, dim3(ntiles), dim3(kThreads), 0, s, bp, n_ent, n_rel, nnz, inc->a_rowptr,
+                           inc->a_colidx, inc->a_vals, c->keys[0], 1 << bits0, ntiles, c->table, c->ctrl);
+    else
+        hipLaunchKernelGGL(k_emit<2 * kSortItems>, dim3(ntiles), dim3(kThreads), 0, s, bp, n_ent, n_rel, nnz,
+                           inc->a_rowptr, inc->a_colidx, inc->a_vals, c->keys[0], 1 << bits0, ntiles, c->table, c->ctrl);
+    }
     const bool two_level = ntiles > kSelfScanTiles;
     const int ngroups = (ntiles + kSuperTile - 1) / kSuperTile;
     int cur = 0;
     for (int p = 0; p < c->sort_passes; ++p) {
         int shift = p * c->digit_bits;
         int bits = c->sort_bits - shift < c->digit_bits ? c->sort_bits - shift : c->digit_bits;
-        if (p > 0)
-            hipLaunchKernelGGL(k_hist, dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], nnz, shift, 1 << bits,
-                               c->table);
-        if (two_level)
+        if (p > 0) {
+            ProfScope prof(c, "k_hist");
+            if (items == kSortItems)
+                hipLaunchKernelGGL(k_hist<kSortItems>, dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], nnz, shift,
+                                   1 << bits, c->table);
+            else
+                hipLaunchKernelGGL(k_hist<2 * kSortItems>, dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], nnz, shift,
+                                   1 << bits, c->table);
+        }
+        if (two_level) {
+            ProfScope prof(c, "k_super_sums");
             hipLaunchKernelGGL(k_super_sums, dim3(ngroups), dim3(kThreads), 0, s, c->table, 1 << bits, ntiles,
                                c->super);
-#define STX_SCATTER(F, S)                                                                                     \
-    hipLaunchKernelGGL((k_scatter<F, S>), dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], c->pay[cur],       \
+        }
+#define STX_SCATTER(F, S, I)                                                                                  \
+    hipLaunchKernelGGL((k_scatter<F, S, I>), dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], c->pay[cur],    \
                        c->keys[cur ^ 1], c->pay[cur ^ 1], nnz, shift, bits, ntiles, c->table, c->super)
+#define STX_SCATTER2(F, S) do { if (items == kSortItems) STX_SCATTER(F, S, kSortItems); else STX_SCATTER(F, S, 2 * kSortItems); } while (0)
         {
             ProfScope prof(c, "k_scatter");
-            if (p == 0) { if (two_level) STX_SCATTER(true, true); else STX_SCATTER(true, false); }
-            else        { if (two_level) STX_SCATTER(false, true); else STX_SCATTER(false, false); }
+            if (p == 0) { if (two_level) STX_SCATTER2(true, true); else STX_SCATTER2(true, false); }
+            else        { if (two_level) STX_SCATTER2(false, true); else STX_SCATTER2(false, false); }
         }
+#undef STX_SCATTER2
 #undef STX_SCATTER
         cur ^= 1;
     }
     const int nseg = (nnz + kSegWTile - 1) / kSegWTile;
-    hipLaunchKernelGGL(k_seg_count, dim3(nseg), dim3(kThreads), 0, s, c->keys[cur], nnz, c->tile_heads);
+    {
+        ProfScope prof(c, "k_seg_count");
+        hipLaunchKernelGGL(k_seg_count, dim3(nseg), dim3(kThreads), 0, s, c->keys[cur], nnz, c->tile_heads);
+    }
+    ProfScope prof(c, "k_seg_write");
     hipLaunchKernelGGL(k_seg_write, dim3(nseg), dim3(kThreads), 0, s, c->keys[cur], c->pay[cur], nnz,
                        c->tile_heads, inc->n_touched, inc->at_touched_cols, inc->at_seg_ptr, inc->at_row_idx,
                        inc->at_sign, inc->at_seg_id, inc->at_packed);

@@ -104,28 +104,57 @@ __global__ __launch_bounds__(kThreads) void k_forward_stacked(const int32_t *__r
     const int d4 = dim / 4;
     float hinge_sum = 0.f;
     if (i < b) {   // uniform within the group; shuffles below stay inside the group
+        // Negatives are taken NB at a time so that the kernel pays two memory round trips per batch (all
+        // column ids, then all table rows) instead of two per row; the positive rides with the first batch.
+        constexpr int NB = ITERS <= 2 ? 4 : 2;
         RowVec<ITERS> xp;
-        if (FROM_Y) load_vec<LPR, ITERS>(G + i * dim, d4, lig, xp);
-        else gather_row<LPR, ITERS, true>(X, dim, d4, lig, colidx[3 * i], colidx[3 * i + 1], colidx[3 * i + 2], xp);
-        const float dpos = row_distance<LPR, ITERS, DIST>(xp);
-        if (lig == 0) scores[i] = dpos;
+        float dpos = 0.f;
         int n_active = 0;
-        for (int kk = 0; kk < k; ++kk) {
-            const int64_t row = (int64_t)b + i * k + kk;
-            RowVec<ITERS> xn;
-            if (FROM_Y) load_vec<LPR, ITERS>(G + row * dim, d4, lig, xn);
-            else gather_row<LPR, ITERS, true>(X, dim, d4, lig, colidx[3 * row], colidx[3 * row + 1],
-                                              colidx[3 * row + 2], xn);
-            const float dneg = row_distance<LPR, ITERS, DIST>(xn);
-            const float arg = (margin + dpos) - dneg;
-            const bool active = arg > 0.f;
-            if (lig == 0) scores[row] = dneg;
-            if (active) { hinge_sum += arg; ++n_active; }
-            if (PACKED)
-                write_grad_row_packed<LPR, ITERS, DIST>(reinterpret_cast<uint8_t *>(G), gcoef, row, d4, lig, xn,
-                                                        active ? -scale : 0.f);
-            else
-                write_grad_row<LPR, ITERS, DIST>(G + row * dim, d4, lig, xn, active ? -scale : 0.f, dneg);
+        int32_t cp[3] = {0, 0, 0};
+        if (!FROM_Y) { cp[0] = colidx[3 * i]; cp[1] = colidx[3 * i + 1]; cp[2] = colidx[3 * i + 2]; }
+        for (int kk0 = 0; kk0 < k || kk0 == 0; kk0 += NB) {
+            const int nb = min(NB, k - kk0);
+            const int64_t row0 = (int64_t)b + i * k + kk0;
+            int32_t cn[NB][3];
+            RowVec<ITERS> xn[NB];
+            if (!FROM_Y) {
+#pragma unroll
+                for (int q = 0; q < NB; ++q) {
+                    const int64_t rr = q < nb ? row0 + q : i;   // past the end: re-read the positive's ids
+                    cn[q][0] = colidx[3 * rr]; cn[q][1] = colidx[3 * rr + 1]; cn[q][2] = colidx[3 * rr + 2];
+                }
+            }
+            if (kk0 == 0) {
+                if (FROM_Y) load_vec<LPR, ITERS>(G + i * dim, d4, lig, xp);
+                else gather_row<LPR, ITERS, true>(X, dim, d4, lig, cp[0], cp[1], cp[2], xp);
+            }
+#pragma unroll
+            for (int q = 0; q < NB; ++q) {
+                if (q < nb) {
+                    if (FROM_Y) load_vec<LPR, ITERS>(G + (row0 + q) * dim, d4, lig, xn[q]);
+                    else gather_row<LPR, ITERS, true>(X, dim, d4, lig, cn[q][0], cn[q][1], cn[q][2], xn[q]);
+                }
+            }
+            if (kk0 == 0) {
+                dpos = row_distance<LPR, ITERS, DIST>(xp);
+                if (lig == 0) scores[i] = dpos;
+            }
+#pragma unroll
+            for (int q = 0; q < NB; ++q) {
+                if (q < nb) {
+                    const int64_t row = row0 + q;
+                    const float dneg = row_distance<LPR, ITERS, DIST>(xn[q]);
+                    const float arg = (margin + dpos) - dneg;
+                    const bool active = arg > 0.f;
+                    if (lig == 0) scores[row] = dneg;
+                    if (active) { hinge_sum += arg; ++n_active; }
+                    if (PACKED)
+                        write_grad_row_packed<LPR, ITERS, DIST>(reinterpret_cast<uint8_t *>(G), gcoef, row, d4, lig,
+                                                                xn[q], active ? -scale : 0.f);
+                    else
+                        write_grad_row<LPR, ITERS, DIST>(G + row * dim, d4, lig, xn[q], active ? -scale : 0.f, dneg);
+                }
+            }
         }
         if (PACKED)
             write_grad_row_packed<LPR, ITERS, DIST>(reinterpret_cast<uint8_t *>(G), gcoef, i, d4, lig, xp,
@@ -163,9 +192,11 @@ stx_status launch_copy_f32(stx_ctx *c, float *dst, const float *src, int64_t n)
 stx_status launch_finish_loss(stx_ctx *c, int n_partials, float scale, float *loss)
 {
     if (n_partials <= 0) hipLaunchKernelGGL(k_zero_loss, dim3(1), dim3(1), 0, c->stream, loss);
-    else
+    else {
+        ProfScope prof(c, "k_finish_loss");
         hipLaunchKernelGGL(k_finish_loss, dim3(1), dim3(kThreads), 0, c->stream, c->loss_partials, n_partials, scale,
                            loss);
+    }
     return hip_ok(hipGetLastError());
 }
 

@@ -59,6 +59,7 @@ struct stx_ctx {
     // optional live timing of one kernel (stx_profile_kernel): event pairs around its launches
     char prof_name[48];
     hipEvent_t *prof_ev;           // 2 * prof_cap events, null when profiling is off
+    const char **prof_tag;         // kernel name of each recorded pair (string literals of the launch sites)
     int prof_cap, prof_n;
     // host-side call-order state
     const stx_incidence *fwd_inc;  // incidence of the last stx_forward, null if none
@@ -123,8 +124,10 @@ struct ProfScope {
     bool on;
     ProfScope(stx_ctx *ctx, const char *kernel) : c(ctx), on(false)
     {
-        if (c->prof_ev && c->prof_n < c->prof_cap && __builtin_strcmp(kernel, c->prof_name) == 0) {
+        if (c->prof_ev && c->prof_n < c->prof_cap &&
+            (c->prof_name[0] == '*' || __builtin_strcmp(kernel, c->prof_name) == 0)) {
             on = true;
+            c->prof_tag[c->prof_n] = kernel;
             (void)hipEventRecord(c->prof_ev[2 * c->prof_n], c->stream);
         }
     }

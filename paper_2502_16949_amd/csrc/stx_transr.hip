@@ -303,16 +303,19 @@ stx_status launch_transr_backward(stx_ctx *c, const stx_incidence *inc, const st
         hipLaunchKernelGGL(k_transr_dm, dim3(chunks_dm), dim3(kThreads), 0, c->stream, a, c->gbuf[0], g->proj,
                            c->gbuf[2]);
     }
-    if (chunks_dm > 1)
+    if (chunks_dm > 1) {
+        ProfScope prof(c, "k_transr_dm_fixup");
         hipLaunchKernelGGL(k_transr_dm_fixup,
                            dim3(chunks_dm - 1, (unsigned)(((int64_t)a.k * a.d + 4 * kThreads - 1) / (4 * kThreads))),
                            dim3(kThreads), 0, c->stream, a, g->proj, c->gbuf[2]);
+    }
     return hip_ok(hipGetLastError());
 }
 
 stx_status launch_transr_sgd_proj(stx_ctx *c, const stx_incidence *inc, stx_params *p, const stx_grads *g, float lr)
 {
     if (inc->n_rows == 0) return STX_OK;
+    ProfScope prof(c, "k_sgd_proj");
     hipLaunchKernelGGL(k_sgd_proj, dim3((unsigned)c->cfg.n_rel), dim3(kThreads), 0, c->stream, inc->at_touched_cols,
                        inc->n_touched, (int32_t)c->cfg.n_ent, (int64_t)c->cfg.rel_dim * c->cfg.dim, p->proj, g->proj,
                        lr);
