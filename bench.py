@@ -27,7 +27,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 # The kernel whose roofline is reported: the one with the largest share of GPU time in the
 # rocprofv3 kernel trace of the same command (profiles/).
-DOMINANT = {"transe": "k_seg_reduce", "toruse": "k_seg_reduce", "transh": "k_seg_reduce", "transr": "k_transr_dm"}
+DOMINANT = {"transe": "k_forward_stacked", "toruse": "k_sgd_rows", "transh": "k_seg_reduce", "transr": "k_transr_dm"}
 
 
 def parse():
@@ -53,7 +53,7 @@ def kernel_work(wl, kernel, rows, touched):
     row = 4 * wl.dim
     nnz = 3 * rows
     packed = wl.model in ("transe", "toruse") and wl.dist in ("l1", "torus_l1")
-    grow = (wl.dim // 4 + 4) if packed else row     # a stored dL/dx row: sign bytes + coefficient, or dense fp32
+    grow = (wl.dim // 4 + 4) if packed else row     # a stored dL/dx row: coefficient + sign bytes, or dense fp32
     if kernel == "k_forward_stacked" and wl.model in ("transe", "toruse"):
         # 3 gathered table rows + 12 B of column ids per row in; dL/dx row + score out
         return rows * (3 * row + 12 + grow + 4), "GB/s", "hbm", HBM_PEAK_GBS
@@ -63,9 +63,15 @@ def kernel_work(wl, kernel, rows, touched):
         # 2 entity rows + w_r + d_r (+ w_r again for the gradients) in; gx, gy, gw rows + score out
         return rows * (5 * row + 12 + 3 * row + 4), "GB/s", "hbm", HBM_PEAK_GBS
     if kernel == "k_seg_reduce":
-        # first launch of the backward call: one source row + 4 B packed entry per sorted entry in, one row per column out
-        n = nnz if wl.model != "transr" else 2 * rows
-        return n * (grow + 4) + touched * row, "GB/s", "hbm", HBM_PEAK_GBS
+        # one source row + 4 B packed entry per sorted entry in, one row per column out.  TransE/TorusE launch it
+        # once over all 3*rows entries.  TransH launches it twice (all entries -> dE and d(d_r); the relation
+        # entries again -> dw_r) and TransR twice (entity entries -> dE; relation entries -> dr): the figure is the
+        # mean of the two launches, like the measured time.  The relation columns touched are few (<= n_rel).
+        if wl.model == "transh":
+            return (nnz * (row + 4) + touched * row + rows * (row + 4) + min(wl.n_rel, rows) * row) / 2, "GB/s", "hbm", HBM_PEAK_GBS
+        if wl.model == "transr":
+            return (nnz * (row + 4) + touched * row) / 2, "GB/s", "hbm", HBM_PEAK_GBS
+        return nnz * (grow + 4) + touched * row, "GB/s", "hbm", HBM_PEAK_GBS
     if kernel == "k_sgd_rows":
         return touched * 3 * row, "GB/s", "hbm", HBM_PEAK_GBS
     if kernel == "k_scatter":
@@ -213,10 +219,8 @@ def main():
     # (the partial last batch of an epoch included), so the work figure is averaged the same way. ----------
     mean_rows = rows_done / args.steps
     work, unit, bound, peak = kernel_work(wl, kernel, mean_rows, u_last * mean_rows / wl.rows_per_batch)
-    if kernel == "k_seg_reduce" and wl.model in ("transh", "transr"):
-        kernel_note = "first of the call's launches of this kernel is modelled; the mean is over all of them"
-    else:
-        kernel_note = ""
+    kernel_note = ("two launches per step with different work: work and time are both means over the two"
+                   if kernel == "k_seg_reduce" and wl.model in ("transh", "transr") else "")
     per_launch = kernel_n / args.steps if args.steps else 0
     achieved = (work / (kernel_us * 1e-6)) / (1e9 if unit == "GB/s" else 1e12) if kernel_us > 0 else 0.0
     roofline = {"bound": bound, "kernel": kernel, "achieved": round(achieved, 1), "peak": peak, "unit": unit,

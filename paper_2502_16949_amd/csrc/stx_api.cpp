@@ -69,7 +69,9 @@ Layout make_layout(const stx_config *c)
     L.loss_partials = take((size_t)(L.fwd_blocks_max + 1) * 4);
     L.partials = take((size_t)(L.nnz_max / kSegTileMin + 2) * 2 * L.ld * 4);
     for (int i = 0; i < 4; ++i) {
-        size_t bytes = (size_t)L.rows_max * L.ld * 4 + 512;   // slack: the packed layout aligns its second part
+        size_t bytes = (size_t)L.rows_max * L.ld * 4;
+        if (i == 0 && bytes < (size_t)L.rows_max * packed_stride(c->dim))   // packed dL/dx records (tiny dims only)
+            bytes = (size_t)L.rows_max * packed_stride(c->dim);
         if (c->model == STX_TRANSR && i == 2)   // partial dL/dM_r matrices: two per chunk of the dM product
             bytes = (size_t)(L.rows_max / kProjRowsDm + 2) * 2 * (size_t)c->rel_dim * c->dim * 4;
         L.gbuf[i] = i < L.n_gbuf ? take(bytes) : 0;
@@ -370,8 +372,8 @@ stx_status stx_backward(stx_ctx *ctx, const stx_incidence *inc, const stx_params
     const int64_t ent_end = 2 * inc->n_rows;   // sorted entries of entity columns come first, then relation columns
     if (stacked(ctx)) {   // dL/dX = A^T G over all columns of X = [E;R] (Appendix G)
         if (packed_grad(ctx))
-            return launch_seg_reduce(ctx, inc, 0, inc->nnz, ctx->gbuf[0], packed_coef(ctx), inc->nnz, dim, dim,
-                                     g->rows, ctx->ld, true);
+            return launch_seg_reduce(ctx, inc, 0, inc->nnz, ctx->gbuf[0], ctx->gbuf[0], inc->nnz, packed_stride(dim),
+                                     dim, g->rows, ctx->ld, true);
         return launch_seg_reduce(ctx, inc, 0, inc->nnz, ctx->gbuf[0], ctx->gbuf[0], inc->nnz, dim, dim, g->rows,
                                  ctx->ld);
     }

@@ -51,6 +51,15 @@ __device__ inline void load_row(const float *__restrict__ p, int d4, int lig, Ac
     }
 }
 template <int LPR, int ITERS>
+__device__ inline void store_row_stream(float *__restrict__ p, int d4, int lig, const Acc<ITERS> &a)
+{
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        int j = lig + it * LPR;
+        if (j < d4) st4_stream(p + 4 * j, a.v[it]);
+    }
+}
+template <int LPR, int ITERS>
 __device__ inline void store_row(float *__restrict__ p, int d4, int lig, const Acc<ITERS> &a)
 {
 #pragma unroll
@@ -60,9 +69,9 @@ __device__ inline void store_row(float *__restrict__ p, int d4, int lig, const A
     }
 }
 
-// PACKED: the source rows are sign bytes (src_a, dim/4 bytes per row) times a coefficient per row
-// (src_b), as the forward pass of an L1-kind distance stores them; values and summation order are the
-// same as with dense rows, so both forms give the same bits.
+// PACKED: the source rows are records of ld_src bytes at src_a (coefficient, then dim/4 sign bytes), as
+// the forward pass of an L1-kind distance stores them; values and summation order are the same as with
+// dense rows, so both forms give the same bits.
 template <int LPR, int ITERS, bool PACKED, int CHUNK>
 __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restrict__ packed,
                                                          const int32_t *__restrict__ seg_id, int32_t e_begin,
@@ -104,7 +113,7 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
             const bool open_left = (nflush == 0) && first_open;
             const bool open_right = last_run && right_open;
             if (!open_left && !open_right) {
-                store_row<LPR, ITERS>(out_rows + (int64_t)cur_seg * ld_out, d4, lig, acc);
+                store_row_stream<LPR, ITERS>(out_rows + (int64_t)cur_seg * ld_out, d4, lig, acc);
             } else {
                 const int slot = open_left ? 0 : 1;
 #pragma unroll
@@ -134,13 +143,14 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
             for (int u = 0; u < UNROLL; ++u) {
                 const int64_t row = mu[u] >> 2;
                 if constexpr (PACKED) {
-                    const uint8_t *pb = reinterpret_cast<const uint8_t *>(src_a) + row * d4;
+                    const uint8_t *rec = reinterpret_cast<const uint8_t *>(src_a) + row * ld_src;
+                    const uint8_t *pb = rec + 4;
 #pragma unroll
                     for (int it = 0; it < ITERS; ++it) {
                         const int j = lig + it * LPR;
                         sb[u][it] = j < d4 ? pb[j] : (uint8_t)0;
                     }
-                    cf[u] = src_b[row];
+                    cf[u] = *reinterpret_cast<const float *>(rec);
                 } else {   // entries before `split` read src_a, the rest src_b (entity vs relation columns)
                     load_row<LPR, ITERS>((ec0 + j0 + u < split ? src_a : src_b) + row * ld_src, d4, lig, v[u]);
                 }
@@ -335,6 +345,54 @@ __global__ __launch_bounds__(kThreads) void k_sgd_rows(const int32_t *__restrict
     constexpr int GROUPS = kThreads / LPR;
     const int lig = threadIdx.x % LPR, grp = threadIdx.x / LPR;
     const int32_t U = n_touched[0];
+    if (!table_b && !table_w) {
+        // One table (TransE / TorusE): a group takes four consecutive segments per turn so that the four
+        // column ids, then the eight rows (table + gradient), are in flight together.
+        constexpr int UB = ITERS <= 2 ? 4 : 2;
+        for (int64_t s0 = ((int64_t)blockIdx.x * GROUPS + grp) * UB; s0 < U; s0 += (int64_t)gridDim.x * GROUPS * UB) {
+            int32_t col[UB];
+#pragma unroll
+            for (int u = 0; u < UB; ++u) col[u] = touched_cols[min(s0 + u, (int64_t)U - 1)];
+            Acc<ITERS> x[UB], g[UB];
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                load_row<LPR, ITERS>(table_a + (int64_t)col[u] * d4_a * 4, d4_a, lig, x[u]);
+                const float *pg = grad_rows + min(s0 + u, (int64_t)U - 1) * ld;
+#pragma unroll
+                for (int it = 0; it < ITERS; ++it) {
+                    const int j = lig + it * LPR;
+                    g[u].v[it] = j < d4_a ? ld4_stream(pg + 4 * j) : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                if (s0 + u < U && col[u] < n_split) {
+#pragma unroll
+                    for (int it = 0; it < ITERS; ++it) {
+                        float *xv = &x[u].v[it].x;
+                        const float *gv = &g[u].v[it].x;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            float step = lr * gv[q];
+                            float nv = xv[q] - step;
+                            if (mode_a == 1) {
+                                nv = nv - floorf(nv);
+                                if (nv >= 1.0f) nv = 0.0f;
+                            }
+                            xv[q] = nv;
+                        }
+                    }
+                    float *pr = table_a + (int64_t)col[u] * d4_a * 4;
+#pragma unroll
+                    for (int it = 0; it < ITERS; ++it) {
+                        const int j = lig + it * LPR;
+                        if (j < d4_a) st4_stream(pr + 4 * j, x[u].v[it]);
+                    }
+                }
+            }
+        }
+        return;
+    }
     for (int64_t s = (int64_t)blockIdx.x * GROUPS + grp; s < U; s += (int64_t)gridDim.x * GROUPS) {
         const int32_t col = touched_cols[s];
         if (col < n_split) {
@@ -387,6 +445,7 @@ static void sgd_go(stx_ctx *c, const stx_incidence *inc, const SgdTables &T, con
     constexpr int GROUPS = kThreads / LPR;
     int64_t cap = inc->nnz < c->cfg.n_ent + c->cfg.n_rel ? inc->nnz : c->cfg.n_ent + c->cfg.n_rel;
     int64_t blocks = (cap + GROUPS - 1) / GROUPS;
+    if (!T.table_b && !T.table_w) blocks = (blocks + 3) / 4;   // that path takes four segments per group and turn
     if (blocks > 8192) blocks = 8192;   // grid-stride beyond this (measured faster than one segment per group)
     if (blocks < 1) blocks = 1;
     ProfScope prof(c, "k_sgd_rows");

@@ -40,6 +40,18 @@ __device__ inline float group_sum(float v)
     return v;
 }
 
+// Streaming variants: data that is read or written once and not needed in cache afterwards.
+typedef float stx_f4 __attribute__((ext_vector_type(4)));
+__device__ inline float4 ld4_stream(const float *p)
+{
+    stx_f4 t = __builtin_nontemporal_load(reinterpret_cast<const stx_f4 *>(p));
+    return make_float4(t.x, t.y, t.z, t.w);
+}
+__device__ inline void st4_stream(float *p, float4 v)
+{
+    stx_f4 t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<stx_f4 *>(p));
+}
 __device__ inline float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
 __device__ inline void st4(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
 

@@ -30,17 +30,18 @@ __global__ __launch_bounds__(kThreads) void k_spmm(const int32_t *__restrict__ c
     }
 }
 
-// Packed dL/dy row of an L1-kind distance: sign bytes to gs[row], the coefficient to gc[row].
+// Packed dL/dy row of an L1-kind distance: record `row` of gs = coefficient (fp32), then the sign bytes.
 template <int LPR, int ITERS, int DIST>
-__device__ inline void write_grad_row_packed(uint8_t *__restrict__ gs, float *__restrict__ gc, int64_t row, int d4,
-                                             int lig, const RowVec<ITERS> &x, float coef)
+__device__ inline void write_grad_row_packed(uint8_t *__restrict__ gs, int gstride, int64_t row, int d4, int lig,
+                                             const RowVec<ITERS> &x, float coef)
 {
+    uint8_t *rec = gs + row * gstride;
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
         int j = lig + it * LPR;
-        if (j < d4) gs[row * d4 + j] = (uint8_t)sign_bits<DIST>(x.v[it]);
+        if (j < d4) rec[4 + j] = (uint8_t)sign_bits<DIST>(x.v[it]);
     }
-    if (lig == 0) gc[row] = coef;
+    if (lig == 0) *reinterpret_cast<float *>(rec) = coef;
 }
 
 template <int LPR, int ITERS, int DIST>
@@ -87,13 +88,13 @@ __global__ __launch_bounds__(kThreads) void k_finish_loss(const float *__restric
 // FROM_Y = true : it is row `row` of the dense buffer G (TransR: y = M_r (h - t) + r was put there by
 //                 the projection kernel), and dL/dy overwrites it in place; every row is read and then
 //                 written by one group only.
-// PACKED (L1 kinds, gathered rows only): dL/dx is written as sign bytes (at G) + coefficients (at gcoef).
+// PACKED (L1 kinds, gathered rows only): dL/dx is written as records of gstride bytes at G (coefficient + sign bytes).
 template <int LPR, int ITERS, int DIST, bool FROM_Y, bool PACKED>
 __global__ __launch_bounds__(kThreads) void k_forward_stacked(const int32_t *__restrict__ colidx,
                                                               const float *__restrict__ X, int32_t b, int32_t k,
                                                               int dim, float margin, float scale,
                                                               float *__restrict__ scores, float *G,
-                                                              float *__restrict__ gcoef,
+                                                              int gstride,
                                                               float *__restrict__ loss_partials)
 {
     static_assert(!PACKED || (is_sign_kind(DIST) && !FROM_Y), "packed rows need an L1-kind distance");
@@ -149,7 +150,7 @@ __global__ __launch_bounds__(kThreads) void k_forward_stacked(const int32_t *__r
                     if (lig == 0) scores[row] = dneg;
                     if (active) { hinge_sum += arg; ++n_active; }
                     if (PACKED)
-                        write_grad_row_packed<LPR, ITERS, DIST>(reinterpret_cast<uint8_t *>(G), gcoef, row, d4, lig,
+                        write_grad_row_packed<LPR, ITERS, DIST>(reinterpret_cast<uint8_t *>(G), gstride, row, d4, lig,
                                                                 xn[q], active ? -scale : 0.f);
                     else
                         write_grad_row<LPR, ITERS, DIST>(G + row * dim, d4, lig, xn[q], active ? -scale : 0.f, dneg);
@@ -157,7 +158,7 @@ __global__ __launch_bounds__(kThreads) void k_forward_stacked(const int32_t *__r
             }
         }
         if (PACKED)
-            write_grad_row_packed<LPR, ITERS, DIST>(reinterpret_cast<uint8_t *>(G), gcoef, i, d4, lig, xp,
+            write_grad_row_packed<LPR, ITERS, DIST>(reinterpret_cast<uint8_t *>(G), gstride, i, d4, lig, xp,
                                                     (float)n_active * scale);
         else
             write_grad_row<LPR, ITERS, DIST>(G + i * dim, d4, lig, xp, (float)n_active * scale, dpos);
@@ -232,7 +233,7 @@ static void forward_go(stx_ctx *c, const stx_incidence *inc, const stx_params *p
 #define STX_FWD(D, Y, P)                                                                                        \
     hipLaunchKernelGGL((k_forward_stacked<LPR, ITERS, D, Y, P>), grid, dim3(kThreads), 0, c->stream,            \
                        inc->a_colidx, p->ent, inc->b, inc->k, width, c->cfg.margin, scale, scores, c->gbuf[0],  \
-                       packed_coef(c), c->loss_partials)
+                       packed_stride(c->cfg.dim), c->loss_partials)
 #define STX_FWD2(D)                                                                                             \
     do {                                                                                                        \
         if (from_y) STX_FWD(D, true, false);                                                                    \

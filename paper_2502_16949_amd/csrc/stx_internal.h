@@ -81,10 +81,10 @@ stx_status launch_copy_f32(stx_ctx *, float *dst, const float *src, int64_t n);
 // stx_backward.hip
 // out_rows[segment] = signed sum of source rows over the sorted entries [e_begin, e_end); entries
 // before `split` read src_a, the others src_b (both with ld_src floats per row, `width` of them used).
-// packed_src: src_a is the sign-byte array and src_b the per-row coefficients of packed L1-kind rows.
+// packed_src: src_a holds packed L1-kind records (see packed_stride), ld_src is the record size in bytes.
 stx_status launch_seg_reduce(stx_ctx *, const stx_incidence *, int64_t e_begin, int64_t e_end, const float *src_a,
                              const float *src_b, int64_t split, int ld_src, int width, float *out_rows, int ld_out,
-                             bool packed_src = false);
+                             bool packed_src = false);   // packed: src_a = records, ld_src = record bytes
 struct SgdTables {
     float *table_a; int width_a; int mode_a;   // columns [0, n_split)
     int64_t n_split;
@@ -102,18 +102,15 @@ stx_status launch_transr_sgd_proj(stx_ctx *, const stx_incidence *, stx_params *
 stx_status launch_forward_transh(stx_ctx *, const stx_incidence *, const stx_params *, float *scores, float *loss);
 stx_status launch_finish_loss(stx_ctx *, int n_partials, float scale, float *loss);
 
-// TransE / TorusE with an L1-kind distance keep dL/dx packed inside gbuf[0]: rows_max * dim/4 sign
-// bytes first, then (256-byte aligned) rows_max coefficients.
+// TransE / TorusE with an L1-kind distance keep dL/dx packed inside gbuf[0]: one record per row, the
+// fp32 coefficient first and dim/4 sign bytes after it, padded to a multiple of 64 bytes so that a
+// record never straddles more cache lines than it must (one line at dim 128).
 inline bool packed_grad(const stx_ctx *c)
 {
     return (c->cfg.model == STX_TRANSE || c->cfg.model == STX_TORUSE) &&
            (c->cfg.dist == STX_L1 || c->cfg.dist == STX_TORUS_L1);
 }
-inline float *packed_coef(const stx_ctx *c)
-{
-    size_t off = ((size_t)c->rows_max * (c->cfg.dim / 4) + 255) / 256 * 256;
-    return reinterpret_cast<float *>(reinterpret_cast<char *>(c->gbuf[0]) + off);
-}
+inline int packed_stride(int dim) { return (dim / 4 + 4 + 63) / 64 * 64; }
 
 inline stx_status hip_ok(hipError_t e) { return e == hipSuccess ? STX_OK : STX_ERR_HIP; }
 
