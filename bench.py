@@ -30,6 +30,15 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 DOMINANT = {"transe": "k_forward_stacked", "toruse": "k_sgd_rows", "transh": "k_seg_reduce", "transr": "k_transr_dm"}
 
 
+# HBM bytes per launch of those kernels, measured: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (separate runs),
+# each scaled by what the same counter reads for the library's plain copy kernel (FETCH_SIZE x2.0, WRITE_SIZE
+# x1.0); the runs and their numbers are in profiles/<workload>_kernel_trace.txt and profiles/copy_calibration.txt.
+# A different kernel (--kernel) or workload has no measured figure here and reports null.
+TRAFFIC_BYTES = {("mid", "k_forward_stacked"): 24.16e6 + 4.48e6,
+                 ("transh", "k_seg_reduce"): 65.31e6 + 4.64e6,
+                 ("toruse", "k_sgd_rows"): 1056.87e6 + 526.34e6}
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -224,7 +233,7 @@ def main():
     per_launch = kernel_n / args.steps if args.steps else 0
     achieved = (work / (kernel_us * 1e-6)) / (1e9 if unit == "GB/s" else 1e12) if kernel_us > 0 else 0.0
     roofline = {"bound": bound, "kernel": kernel, "achieved": round(achieved, 1), "peak": peak, "unit": unit,
-                "frac": round(achieved / peak, 4), "traffic": None, "work_per_launch": int(work),
+                "frac": round(achieved / peak, 4), "traffic": TRAFFIC_BYTES.get((wl.name, kernel)), "work_per_launch": int(work),
                 "avg_launch_us": round(kernel_us, 2), "launches_per_step": round(per_launch, 2)}
     if kernel_note:
         roofline["note"] = kernel_note
@@ -260,7 +269,7 @@ def main():
         n = args.cpu_steps
         if n <= 0:
             _, _, dt1 = cpu_baseline(wl, h, r, t, tabs, 1)
-            n = max(2, min(60, int(15.0 / max(dt1, 1e-3))))
+            n = max(2, min(400, int(15.0 / max(dt1, 1e-3))))
         v, done, cdt = cpu_baseline(wl, h, r, t, tabs, n)
         out["cpu_baseline"] = {"value": round(v, 1), "unit": "triplets/s", "cores": 1, "kind": "oracle",
                                "sample": f"first {done} steps of the same workload (sampling, incidence build, "
