@@ -13,6 +13,7 @@ inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 struct Layout {
     size_t ctrl, keys[2], pay[2], table, super, tile_heads, loss_partials, partials, gbuf[4], total;
+    size_t tr_items, tr_dm_items, tr_counts, tr_m16, tr_m16t, tr_xt, tr_gyt;
     int64_t rows_max, nnz_max, cols_max;
     int ld, out_dim, ntiles_max, fwd_blocks_max, n_gbuf;
     int sort_bits, sort_passes, digit_bits;
@@ -75,6 +76,19 @@ Layout make_layout(const stx_config *c)
         if (c->model == STX_TRANSR && i == 2)   // partial dL/dM_r matrices: two per chunk of the dM product
             bytes = (size_t)(L.rows_max / kProjRowsDm + 2) * 2 * (size_t)c->rel_dim * c->dim * 4;
         L.gbuf[i] = i < L.n_gbuf ? take(bytes) : 0;
+    }
+    if (c->model == STX_TRANSR) {
+        // every relation segment adds at most one item that is not full
+        const size_t segs = (size_t)(L.rows_max < c->n_rel ? L.rows_max : c->n_rel);
+        const size_t items = (size_t)L.rows_max / kProjRows + segs, dm_items = (size_t)L.rows_max / kProjRowsDm + segs;
+        const size_t kd = (size_t)c->rel_dim * c->dim;
+        L.tr_items = take((items + 1) * 16);
+        L.tr_dm_items = take((dm_items + 1) * 32);
+        L.tr_counts = take(64 * sizeof(int32_t));
+        L.tr_m16 = take((size_t)c->n_rel * kd * 2);
+        L.tr_m16t = take((size_t)c->n_rel * kd * 2);
+        L.tr_xt = take((items + 1) * kProjRows * c->dim * 2);
+        L.tr_gyt = take((items + 1) * kProjRows * c->rel_dim * 2);
     }
     L.total = off;
     return L;
@@ -157,6 +171,14 @@ stx_status stx_create(const stx_config *cfg, void *workspace, size_t workspace_b
     c->loss_partials = (float *)(base + L.loss_partials);
     c->partials = (float *)(base + L.partials);
     for (int i = 0; i < 4; ++i) c->gbuf[i] = i < L.n_gbuf ? (float *)(base + L.gbuf[i]) : nullptr;
+    const bool tr = cfg->model == STX_TRANSR;
+    c->tr_items = tr ? (int32_t *)(base + L.tr_items) : nullptr;
+    c->tr_dm_items = tr ? (int32_t *)(base + L.tr_dm_items) : nullptr;
+    c->tr_counts = tr ? (int32_t *)(base + L.tr_counts) : nullptr;
+    c->tr_m16 = tr ? (uint16_t *)(base + L.tr_m16) : nullptr;
+    c->tr_m16t = tr ? (uint16_t *)(base + L.tr_m16t) : nullptr;
+    c->tr_xt = tr ? (uint16_t *)(base + L.tr_xt) : nullptr;
+    c->tr_gyt = tr ? (uint16_t *)(base + L.tr_gyt) : nullptr;
     c->fwd_inc = nullptr;
     c->fwd_rows = 0;
     c->prof_ev = nullptr;

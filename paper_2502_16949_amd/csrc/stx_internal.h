@@ -18,8 +18,8 @@ constexpr int kSuperTile = 32;         // sort tiles per group when the histogra
 constexpr int kSelfScanTiles = 256;   // up to this many sort tiles, scatter workgroups scan the histograms themselves
 constexpr int kMaxDim = 1024;
 constexpr int kMaxProjDim = 256;        // TransR: dim and rel_dim are multiples of 32 up to this
-constexpr int kProjRows = 64;           // sorted relation entries per workgroup in the projection products
-constexpr int kProjRowsDm = 256;        // ... and in the product that forms dL/dM_r
+constexpr int kProjRows = 64;           // TransR: entries of one relation per work item of the two row products
+constexpr int kProjRowsDm = 256;        // ... and per work item of the product that forms dL/dM_r
 
 // Slots of the control block at the start of the workspace (int32 each).
 enum { CTRL_BAD_INDEX = 0, CTRL_WORDS = 64 };
@@ -56,6 +56,9 @@ struct stx_ctx {
     float *loss_partials;          // [fwd_blocks_max]
     float *partials;               // [(nnz_max/kSegTileMin + 2) * 2 * ld]
     float *gbuf[4];                // per-row buffers, rows_max x ld each (how many depends on the model)
+    // TransR only: work items, bfloat16 operand copies of the projection matrices, transposed operand tiles
+    int32_t *tr_items, *tr_dm_items, *tr_counts;
+    uint16_t *tr_m16, *tr_m16t, *tr_xt, *tr_gyt;
     // optional live timing of one kernel (stx_profile_kernel): event pairs around its launches
     char prof_name[48];
     hipEvent_t *prof_ev;           // 2 * prof_cap events, null when profiling is off

@@ -5,19 +5,29 @@
 // relation columns of the sorted A^T (stx_build.hip) already list every relation's rows contiguously,
 // so the projections are dense products over runs of that list:
 //
-//   forward   Y_g  = X_g . M_r^T + r        (n_g x d)(d x k)      k_transr_project
-//   backward  GX_g = GY_g . M_r             (n_g x k)(k x d)      k_transr_gx
+//   forward   Y_g  = X_g . M_r^T + r        (n_g x d)(d x k)      k_transr_rows<false>
+//   backward  GX_g = GY_g . M_r             (n_g x k)(k x d)      k_transr_rows<true>
 //             dM_r = GY_g^T . X_g           (k x n_g)(n_g x d)    k_transr_dm (+ k_transr_dm_fixup)
 //
-// Operands are rounded to bfloat16 (round to nearest even) as they are loaded, products accumulate in
-// fp32 in v_mfma_f32_32x32x16_bf16; x = h - t is formed in fp32 first.  Work is cut by entries of the
-// sorted list, not by relation (group sizes are power-law distributed): a workgroup owns a fixed chunk
-// of entries and walks the runs of equal relation inside it, masking rows of other relations, so a
-// chunk inside a big relation is one dense tile and a chunk in the tail costs one tile per relation.
+// Operands are bfloat16 (round to nearest even), products accumulate in fp32 in
+// v_mfma_f32_32x32x16_bf16; x = h - t is formed in fp32 first.
 //
-// MFMA 32x32x16 operand layout (64 lanes): lane l holds, for the A operand, row (l % 32) and the eight
-// consecutive K elements 8*(l / 32) ..; for the B operand, column (l % 32) and the same eight K
-// elements; accumulator register v holds row 8*(v / 4) + 4*(l / 32) + v % 4 of column l % 32.
+// Work items.  Group sizes are power-law distributed, so the list of every relation is cut into
+// items of at most 64 entries (the two row products) and 256 entries (the dM product); an item never
+// spans two relations, so a workgroup loads one M_r and runs dense tiles.  k_transr_prepare builds
+// both item lists with one scan over the relation segments, and the kernels are launched with the
+// largest possible item count; workgroups past the real count leave at once.
+//
+// Operand order.  The 32x32x16 MFMA wants, from lane l of 64, row (l % 32) of its operand and the
+// eight consecutive reduction elements 8*(l / 32) .. of that row, for A and B alike; accumulator
+// register v holds row 8*(v / 4) + 4*(l / 32) + v % 4 of column l % 32.  Every bfloat16 operand that
+// is read from global memory is therefore stored as a sequence of fragments of 32 rows x 16 reduction
+// elements, fragment (reduction step ks, row tile rt) at ((ks * row_tiles + rt) * 64 + lane) * 8
+// elements: a wavefront fetches one fragment as one contiguous kilobyte, 16 bytes per lane.  That
+// holds for the two copies of M_r made by k_transr_prepare (rows = output columns of the forward
+// product, reduction over d; rows = output columns of GX, reduction over k) and for the transposed
+// tiles X^T and GY^T (rows = columns of x / gy, reduction over the 64 entries of an item) which the
+// row kernels leave behind for the dM product while they have the tile in LDS anyway.
 #include "stx_device.h"
 #include "stx_internal.h"
 
@@ -26,20 +36,14 @@ namespace stx {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 
-__device__ inline bf16x8 cvt8(float4 a, float4 b)
+__device__ inline uint32_t bf16_bits(float v) { return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)v); }
+__device__ inline uint32_t pack2(float lo, float hi) { return bf16_bits(lo) | (bf16_bits(hi) << 16); }
+__device__ inline uint4 pack8(float4 a, float4 b)
 {
-    bf16x8 r;
-    r[0] = (__bf16)a.x; r[1] = (__bf16)a.y; r[2] = (__bf16)a.z; r[3] = (__bf16)a.w;
-    r[4] = (__bf16)b.x; r[5] = (__bf16)b.y; r[6] = (__bf16)b.z; r[7] = (__bf16)b.w;
-    return r;
+    return make_uint4(pack2(a.x, a.y), pack2(a.z, a.w), pack2(b.x, b.y), pack2(b.z, b.w));
 }
-__device__ inline bf16x8 zero8()
-{
-    bf16x8 r;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) r[i] = (__bf16)0.0f;
-    return r;
-}
+__device__ inline bf16x8 as_frag(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+__device__ inline uint4 ld16(const uint16_t *p) { return *reinterpret_cast<const uint4 *>(p); }
 __device__ inline float4 sub4(float4 a, float4 b) { return make_float4(a.x - b.x, a.y - b.y, a.z - b.z, a.w - b.w); }
 __device__ inline floatx16 zero16()
 {
@@ -50,194 +54,333 @@ __device__ inline floatx16 zero16()
 }
 
 constexpr int kMaxNT = kMaxProjDim / 32 / 2;   // 32-column tiles per wavefront (two wavefronts share the columns)
+constexpr int kLdsPad = 8;                      // halfwords added to every LDS row: 16-byte reads stay conflict-free
 
-struct ProjArgs {
-    const int32_t *colidx, *packed, *seg_id, *seg_ptr, *touched_cols;
-    const float *E, *M, *Rv;
-    int32_t n_ent, e_begin, e_end;
+struct PrepArgs {
+    const int32_t *touched_cols, *n_touched, *seg_ptr, *seg_id;
+    int32_t n_ent, e_begin;
+    const float *M;
+    uint16_t *m16, *m16t;
+    int4 *items, *dm_items;
+    int32_t *counts;
     int d, k;
 };
 
-// One workgroup per kProjRows sorted relation entries.  Wavefront w: rows 32*(w/2).., column tiles w%2, w%2+2, ..
-// GX = false: Y[row] = bf16(E[h]-E[t]) . bf16(M_r)^T + r_vec       (out width k, reduction over d)
-// GX = true : GX[row] = bf16(GY[row]) . bf16(M_r)                   (out width d, reduction over k)
-template <bool GX>
-__global__ __launch_bounds__(kThreads) void k_transr_rows(ProjArgs p, const float *__restrict__ gy,
-                                                          float *__restrict__ out)
+// Item lists of the relation segments (one workgroup).  Row item: {relation, first sorted entry,
+// entries (<= 64), 0}.  dM item, two int4: {relation, first row item, entries (<= 256), slot} and
+// {first slot of the segment, parts to add if this is the segment's last item else 0, 0, 0}; slot is
+// -1 when the segment has a single dM item, which then writes dL/dM_r itself.
+__device__ inline void transr_plan(const PrepArgs &p)
 {
-    const int l = threadIdx.x & 63, w = threadIdx.x >> 6, wr = w >> 1, wc = w & 1;
-    const int l31 = l & 31, kg = l >> 5;
-    const int n_out = GX ? p.d : p.k, n_red = GX ? p.k : p.d;
-    const int32_t e_first = p.e_begin + (int32_t)blockIdx.x * kProjRows + 32 * wr;
-    if (e_first >= p.e_end) return;                       // no barrier is used below: wavefronts are independent
-    const int32_t e_last = min(e_first + 31, p.e_end - 1);
-    const int32_t e = e_first + l31;
-    const bool valid = e <= e_last;
-    const int32_t row = valid ? (p.packed[e] >> 2) : 0;
-    const int32_t seg = valid ? p.seg_id[e] : -1;
-    const float *pa0, *pa1 = nullptr;
-    if (GX) {
-        pa0 = gy + (int64_t)row * p.k;
-    } else {
-        pa0 = p.E + (int64_t)(valid ? p.colidx[3 * row] : 0) * p.d;
-        pa1 = p.E + (int64_t)(valid ? p.colidx[3 * row + 2] : 0) * p.d;
-    }
-    const int32_t s_first = p.seg_id[e_first], s_last = p.seg_id[e_last];
-    const int ntiles = n_out / 32, ntw = (ntiles - wc + 1) / 2;
-
-    for (int32_t s = s_first; s <= s_last; ++s) {
-        const int32_t r = p.touched_cols[s] - p.n_ent;
-        const float *Mr = p.M + (int64_t)r * p.k * p.d;
-        const bool mine = valid && seg == s;
-        floatx16 acc[kMaxNT];
-#pragma unroll
-        for (int q = 0; q < kMaxNT; ++q) acc[q] = zero16();
-        for (int ks = 0; ks < n_red / 16; ++ks) {
-            const int j0 = 16 * ks + 8 * kg;
-            bf16x8 a = zero8();
-            if (mine) {
-                if (GX) a = cvt8(ld4(pa0 + j0), ld4(pa0 + j0 + 4));
-                else a = cvt8(sub4(ld4(pa0 + j0), ld4(pa1 + j0)), sub4(ld4(pa0 + j0 + 4), ld4(pa1 + j0 + 4)));
-            }
-#pragma unroll
-            for (int q = 0; q < kMaxNT; ++q) {
-                if (q < ntw) {
-                    const int n = (wc + 2 * q) * 32 + l31;
-                    bf16x8 bfrag;
-                    if (GX) {   // B[K = a][N = j] = M_r[a][j]: eight rows of M_r at column n
-                        const float *pm = Mr + (int64_t)j0 * p.d + n;
-#pragma unroll
-                        for (int i = 0; i < 8; ++i) bfrag[i] = (__bf16)pm[(int64_t)i * p.d];
-                    } else {    // B[K = j][N = a] = M_r[a][j]: eight consecutive elements of row n of M_r
-                        const float *pm = Mr + (int64_t)n * p.d + j0;
-                        bfrag = cvt8(ld4(pm), ld4(pm + 4));
-                    }
-                    acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bfrag, acc[q], 0, 0, 0);
-                }
-            }
+    __shared__ int32_t s_o64[kThreads + 1], s_o256[kThreads + 1], s_op[kThreads], s_beg[kThreads], s_len[kThreads],
+        s_rel[kThreads];
+    const int tid = threadIdx.x;
+    const int32_t n_seg = p.n_touched[0];
+    int32_t base64 = 0, base256 = 0, basep = 0;
+    for (int32_t sb = p.seg_id[p.e_begin]; sb < n_seg; sb += kThreads) {
+        const int32_t s = sb + tid;
+        int32_t beg = 0, len = 0, rel = 0;
+        if (s < n_seg) {
+            beg = p.seg_ptr[s];
+            len = p.seg_ptr[s + 1] - beg;
+            rel = p.touched_cols[s] - p.n_ent;
         }
-#pragma unroll
-        for (int q = 0; q < kMaxNT; ++q) {
-            if (q < ntw) {
-                const int n = (wc + 2 * q) * 32 + l31;
-                const float add = GX ? 0.f : p.Rv[(int64_t)r * p.k + n];
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int m = 8 * (v >> 2) + 4 * kg + (v & 3);
-                    const int32_t row_m = __shfl(row, m), seg_m = __shfl(seg, m);
-                    if (seg_m == s) out[(int64_t)row_m * n_out + n] = acc[q][v] + add;
-                }
+        const int32_t n64 = (len + 63) >> 6, n256 = (len + 255) >> 8;
+        int32_t t64, t256, tp;
+        const int32_t o64 = block_exclusive_scan(n64, &t64);
+        const int32_t o256 = block_exclusive_scan(n256, &t256);
+        const int32_t op = block_exclusive_scan(n256 > 1 ? n256 : 0, &tp);
+        s_o64[tid] = o64; s_o256[tid] = o256; s_op[tid] = op;
+        s_beg[tid] = beg; s_len[tid] = len; s_rel[tid] = rel;
+        if (tid == 0) { s_o64[kThreads] = t64; s_o256[kThreads] = t256; }
+        __syncthreads();
+        for (int32_t w = tid; w < t64; w += kThreads) {
+            int lo = 0, hi = kThreads;                     // last segment whose first item is <= w
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (s_o64[mid] <= w) lo = mid; else hi = mid;
             }
+            const int32_t li = w - s_o64[lo];
+            p.items[base64 + w] = make_int4(s_rel[lo], s_beg[lo] + 64 * li, min(64, s_len[lo] - 64 * li), 0);
+        }
+        for (int32_t w = tid; w < t256; w += kThreads) {
+            int lo = 0, hi = kThreads;
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (s_o256[mid] <= w) lo = mid; else hi = mid;
+            }
+            const int32_t li = w - s_o256[lo], parts = (s_len[lo] + 255) >> 8, first = basep + s_op[lo];
+            p.dm_items[2 * (base256 + w)] = make_int4(s_rel[lo], base64 + s_o64[lo] + 4 * li,
+                                                      min(256, s_len[lo] - 256 * li), parts > 1 ? first + li : -1);
+            p.dm_items[2 * (base256 + w) + 1] = make_int4(first, (parts > 1 && li == parts - 1) ? parts : 0, 0, 0);
+        }
+        base64 += t64; base256 += t256; basep += tp;
+        __syncthreads();
+    }
+    if (tid == 0) { p.counts[0] = base64; p.counts[1] = base256; }
+}
+
+// Workgroup 0 builds the item lists; workgroup 1 + r writes the two bfloat16 operand-order copies of
+// M_r if relation r occurs in the batch (it looks its column up in the sorted touched list).
+__global__ __launch_bounds__(kThreads) void k_transr_prepare(PrepArgs p)
+{
+    if (blockIdx.x == 0) { transr_plan(p); return; }
+    const int tid = threadIdx.x;
+    const int32_t r = (int32_t)blockIdx.x - 1, target = p.n_ent + r;
+    const int32_t n_seg = p.n_touched[0];
+    int32_t lo = 0, hi = n_seg;
+    while (lo < hi) {                                     // first position with touched_cols[pos] >= target
+        const int32_t mid = (lo + hi) >> 1;
+        if (p.touched_cols[mid] < target) lo = mid + 1; else hi = mid;
+    }
+    if (lo >= n_seg || p.touched_cols[lo] != target) return;
+    const int64_t kd = (int64_t)p.k * p.d;
+    const float *__restrict__ M = p.M + r * kd;
+    {   // forward operand: row a of M_r, reduction over j
+        uint16_t *__restrict__ dst = p.m16 + r * kd;
+        const int rt = p.k >> 5, pieces = (p.d >> 4) * rt * 64;
+#pragma unroll 4
+        for (int pc = tid; pc < pieces; pc += kThreads) {
+            const int l = pc & 63, blk = pc >> 6, ks = blk / rt, nt = blk - ks * rt;
+            const float *s = M + (int64_t)(32 * nt + (l & 31)) * p.d + 16 * ks + 8 * (l >> 5);
+            *reinterpret_cast<uint4 *>(dst + (int64_t)pc * 8) = pack8(ld4(s), ld4(s + 4));
+        }
+    }
+    {   // GX operand: column j of M_r, reduction over a
+        uint16_t *__restrict__ dst = p.m16t + r * kd;
+        const int rt = p.d >> 5, pieces = (p.k >> 4) * rt * 64;
+#pragma unroll 2
+        for (int pc = tid; pc < pieces; pc += kThreads) {
+            const int l = pc & 63, blk = pc >> 6, ks = blk / rt, nt = blk - ks * rt;
+            const float *s = M + (int64_t)(16 * ks + 8 * (l >> 5)) * p.d + 32 * nt + (l & 31);
+            float v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = s[(int64_t)i * p.d];
+            *reinterpret_cast<uint4 *>(dst + (int64_t)pc * 8) =
+                make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
         }
     }
 }
 
-// dL/dM_r = sum over the rows i of relation r of bf16(gy_i) bf16(x_i)^T, x_i = E[h_i] - E[t_i].
-// One workgroup per kProjRowsDm sorted relation entries; the reduction runs over rows, 16 per MFMA.
-// Wavefront w owns output column tiles w, w+4, ..; for each it walks the row tiles four at a time.
-// A run of a relation that lies inside the chunk is stored to dM_r directly; a run that crosses the
-// chunk's border is stored as a partial matrix (slot 0: it began before the chunk, slot 1: it goes on
-// after it) for k_transr_dm_fixup.
-__global__ __launch_bounds__(kThreads) void k_transr_dm(ProjArgs p, const float *__restrict__ gy,
-                                                        float *__restrict__ g_proj, float *__restrict__ partials)
+struct RowsArgs {
+    const int4 *items;
+    const int32_t *counts;       // [0] = number of row items
+    const int32_t *colidx, *packed;
+    const float *E, *Rv;
+    const uint16_t *Mb;          // operand-order copies of M_r: n_out rows, reduction n_red
+    uint16_t *tiles;             // per item: the 64-entry operand tile transposed, n_red rows in operand order
+    int n_red, n_out;
+};
+
+// One workgroup per row item.  The item's operand rows are staged in LDS as bfloat16 (forward:
+// x = E[h] - E[t]; GX: the rows of dL/dy), stored once more, transposed, for the dM product, and
+// multiplied by M_r's fragments fetched straight from the operand-order copy.
+// Wavefront w: rows 32*(w/2).., column tiles w%2, w%2+2, ..
+// GX = false: Y[row]  = x . M_r^T + r_vec     (out width k, reduction over d)
+// GX = true : GX[row] = gy . M_r              (out width d, reduction over k)
+template <bool GX>
+__global__ __launch_bounds__(kThreads) void k_transr_rows(RowsArgs p, const float *__restrict__ gy,
+                                                          float *__restrict__ out)
 {
-    __shared__ int32_t s_row[kProjRowsDm], s_h[kProjRowsDm], s_t[kProjRowsDm];
-    const int tid = threadIdx.x, l = tid & 63, w = tid >> 6, l31 = l & 31, kg = l >> 5;
-    const int32_t c0 = p.e_begin + (int32_t)blockIdx.x * kProjRowsDm;
-    const int32_t c1 = min(c0 + kProjRowsDm, p.e_end);
-    {
-        const int32_t e = c0 + tid;
-        int32_t row = 0, hh = 0, tt = 0;
-        if (e < c1) {
-            row = p.packed[e] >> 2;
-            hh = p.colidx[3 * row];
-            tt = p.colidx[3 * row + 2];
+    __shared__ __attribute__((aligned(16))) uint16_t s_a[64 * (kMaxProjDim + kLdsPad)];
+    __shared__ int32_t s_row[64], s_h[64], s_t[64];
+    const int tid = threadIdx.x;
+    if ((int32_t)blockIdx.x >= p.counts[0]) return;
+    const int4 item = p.items[blockIdx.x];
+    const int rel = item.x, begin = item.y, count = item.z;
+    if (tid < 64) {
+        int32_t row = -1, hh = 0, tt = 0;
+        if (tid < count) {
+            row = p.packed[begin + tid] >> 2;
+            if (!GX) { hh = p.colidx[3 * row]; tt = p.colidx[3 * row + 2]; }
         }
         s_row[tid] = row; s_h[tid] = hh; s_t[tid] = tt;
     }
     __syncthreads();
-    const int32_t s_first = p.seg_id[c0], s_last = p.seg_id[c1 - 1];
-    const int mtiles = p.k / 32, ntiles = p.d / 32;
-    const int64_t kd = (int64_t)p.k * p.d;
 
-    for (int32_t s = s_first; s <= s_last; ++s) {
-        const int32_t sb = p.seg_ptr[s], se = p.seg_ptr[s + 1];
-        const int32_t q0 = max(sb, c0) - c0, q1 = min(se, c1) - c0;   // positions in the chunk
-        const int32_t r = p.touched_cols[s] - p.n_ent;
-        float *dst = (sb >= c0 && se <= c1) ? g_proj + (int64_t)r * kd
-                                            : partials + ((int64_t)blockIdx.x * 2 + (sb < c0 ? 0 : 1)) * kd;
-        for (int nt = w; nt < ntiles; nt += 4) {
-            const int j = nt * 32 + l31;
-            for (int mt0 = 0; mt0 < mtiles; mt0 += 4) {
-                floatx16 acc[4];
+    // stage the tile: rows past `count` are zero
+    const int stride = p.n_red + kLdsPad, q4 = p.n_red >> 2, total = 64 * q4;
+    for (int g0 = tid; g0 < total; g0 += 8 * kThreads) {
+        float4 v[8];
 #pragma unroll
-                for (int q = 0; q < 4; ++q) acc[q] = zero16();
-                for (int i0 = q0; i0 < q1; i0 += 16) {
-                    bf16x8 bx;                                   // B[K = i][N = j] = x_i[j]
-                    bf16x8 ax[4];                                // A[M = a][K = i] = gy_i[a]
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const int q = i0 + 8 * kg + i;
-                        const bool ok = q < q1;
-                        const int qq = ok ? q : q0;
-                        const float xv = p.E[(int64_t)s_h[qq] * p.d + j] - p.E[(int64_t)s_t[qq] * p.d + j];
-                        bx[i] = (__bf16)(ok ? xv : 0.f);
-                        const float *pg = gy + (int64_t)s_row[qq] * p.k + l31;
-#pragma unroll
-                        for (int m = 0; m < 4; ++m)
-                            ax[m][i] = (__bf16)((ok && mt0 + m < mtiles) ? pg[(mt0 + m) * 32] : 0.f);
-                    }
-#pragma unroll
-                    for (int m = 0; m < 4; ++m)
-                        if (mt0 + m < mtiles) acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ax[m], bx, acc[m], 0, 0, 0);
+        for (int u = 0; u < 8; ++u) {
+            const int g = g0 + u * kThreads;
+            v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (g < total) {
+                const int i = g / q4, c4 = 4 * (g - i * q4);
+                if (i < count) {
+                    if (GX) v[u] = ld4(gy + (int64_t)s_row[i] * p.n_red + c4);
+                    else v[u] = sub4(ld4(p.E + (int64_t)s_h[i] * p.n_red + c4), ld4(p.E + (int64_t)s_t[i] * p.n_red + c4));
                 }
+            }
+        }
 #pragma unroll
-                for (int m = 0; m < 4; ++m) {
-                    if (mt0 + m < mtiles) {
+        for (int u = 0; u < 8; ++u) {
+            const int g = g0 + u * kThreads;
+            if (g < total) {
+                const int i = g / q4, c4 = 4 * (g - i * q4);
+                *reinterpret_cast<uint2 *>(s_a + i * stride + c4) = make_uint2(pack2(v[u].x, v[u].y), pack2(v[u].z, v[u].w));
+            }
+        }
+    }
+    __syncthreads();
+
+    {   // the transposed tile, in operand order, for the dM product (reduction steps past `count` are never read)
+        const int rt = p.n_red >> 5, pieces = ((count + 15) >> 4) * rt * 64;
+        uint16_t *tile = p.tiles + (int64_t)blockIdx.x * 64 * p.n_red;
+        for (int pc = tid; pc < pieces; pc += kThreads) {
+            const int l = pc & 63, blk = pc >> 6, ks = blk / rt, mt = blk - ks * rt;
+            const uint16_t *s = s_a + (16 * ks + 8 * (l >> 5)) * stride + 32 * mt + (l & 31);
+            uint4 o;
+            o.x = (uint32_t)s[0] | (uint32_t)s[stride] << 16;
+            o.y = (uint32_t)s[2 * stride] | (uint32_t)s[3 * stride] << 16;
+            o.z = (uint32_t)s[4 * stride] | (uint32_t)s[5 * stride] << 16;
+            o.w = (uint32_t)s[6 * stride] | (uint32_t)s[7 * stride] << 16;
+            *reinterpret_cast<uint4 *>(tile + (int64_t)pc * 8) = o;
+        }
+    }
+
+    const int l = tid & 63, w = tid >> 6, wr = w >> 1, wc = w & 1, l31 = l & 31, kg = l >> 5;
+    if (32 * wr >= count) return;                          // no barrier below
+    const int ntl = p.n_out >> 5, ntw = (ntl - wc + 1) >> 1, KS = p.n_red >> 4;
+    const uint16_t *Mb = p.Mb + (int64_t)rel * p.n_out * p.n_red;
+    const uint16_t *arow = s_a + (32 * wr + l31) * stride + 8 * kg;
+    floatx16 acc[kMaxNT];
 #pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            const int a = (mt0 + m) * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
-                            dst[(int64_t)a * p.d + j] = acc[m][v];
-                        }
-                    }
+    for (int q = 0; q < kMaxNT; ++q) acc[q] = zero16();
+    for (int ks0 = 0; ks0 < KS; ks0 += 4) {
+        uint4 a[4], b[4][kMaxNT];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (ks0 + u < KS) {
+#pragma unroll
+                for (int q = 0; q < kMaxNT; ++q)
+                    if (q < ntw) b[u][q] = ld16(Mb + ((int64_t)((ks0 + u) * ntl + wc + 2 * q) * 64 + l) * 8);
+                a[u] = *reinterpret_cast<const uint4 *>(arow + 16 * (ks0 + u));
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (ks0 + u < KS) {
+#pragma unroll
+                for (int q = 0; q < kMaxNT; ++q)
+                    if (q < ntw)
+                        acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(a[u]), as_frag(b[u][q]), acc[q], 0, 0, 0);
+            }
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < kMaxNT; ++q) {
+        if (q < ntw) {
+            const int n = (wc + 2 * q) * 32 + l31;
+            const float add = GX ? 0.f : p.Rv[(int64_t)rel * p.n_out + n];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int32_t row_m = s_row[32 * wr + 8 * (v >> 2) + 4 * kg + (v & 3)];
+                if (row_m >= 0) out[(int64_t)row_m * p.n_out + n] = acc[q][v] + add;
+            }
+        }
+    }
+}
+
+struct DmArgs {
+    const int4 *dm_items;
+    const int32_t *counts;       // [1] = number of dM items
+    const uint16_t *gyt, *xt;    // operand-order transposed tiles written by the row kernels
+    float *g_proj, *partials;
+    int d, k;
+};
+
+// dL/dM_r = sum over the rows i of relation r of bf16(gy_i) bf16(x_i)^T, x_i = E[h_i] - E[t_i].
+// One workgroup per dM item (up to four 64-entry tiles of one relation) and per 128 x 128 block of
+// the matrix (blockIdx.y); the reduction runs over entries, 16 per MFMA, both operands read in
+// operand order from the transposed tiles.  Wavefront w owns the 64 x 64 quarter (w/2, w%2).
+// A relation with one item gets its matrix written directly; otherwise every item writes a partial
+// matrix into its slot and k_transr_dm_fixup adds the slots in order.
+__global__ __launch_bounds__(kThreads) void k_transr_dm(DmArgs p)
+{
+    if ((int32_t)blockIdx.x >= p.counts[1]) return;
+    const int4 it = p.dm_items[2 * blockIdx.x];
+    const int rel = it.x, tile0 = it.y, entries = it.z, slot = it.w;
+    const int l = threadIdx.x & 63, w = threadIdx.x >> 6, l31 = l & 31, kg = l >> 5;
+    const int mtl = p.k >> 5, ntl = p.d >> 5, dblocks = (p.d + 127) >> 7;
+    const int kb = (int)blockIdx.y / dblocks, db = (int)blockIdx.y - kb * dblocks;
+    const int mt0 = 4 * kb + 2 * (w >> 1), nt0 = 4 * db + 2 * (w & 1);
+    if (mt0 >= mtl || nt0 >= ntl) return;                 // no barrier in this kernel
+    const bool m1 = mt0 + 1 < mtl, n1 = nt0 + 1 < ntl;
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i >> 1][i & 1] = zero16();
+    const int ntile = (entries + 63) >> 6;
+    for (int t = 0; t < ntile; ++t) {
+        const int nks = (min(64, entries - 64 * t) + 15) >> 4;
+        const uint16_t *ga = p.gyt + ((int64_t)(tile0 + t) * 64 * p.k) + (int64_t)l * 8;
+        const uint16_t *xb = p.xt + ((int64_t)(tile0 + t) * 64 * p.d) + (int64_t)l * 8;
+        uint4 fa[4][2], fb[4][2];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            fa[ks][0] = fa[ks][1] = fb[ks][0] = fb[ks][1] = make_uint4(0, 0, 0, 0);
+            if (ks < nks) {
+                fa[ks][0] = ld16(ga + (int64_t)(ks * mtl + mt0) * 512);
+                if (m1) fa[ks][1] = ld16(ga + (int64_t)(ks * mtl + mt0 + 1) * 512);
+                fb[ks][0] = ld16(xb + (int64_t)(ks * ntl + nt0) * 512);
+                if (n1) fb[ks][1] = ld16(xb + (int64_t)(ks * ntl + nt0 + 1) * 512);
+            }
+        }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            if (ks < nks) {
+                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(fa[ks][0]), as_frag(fb[ks][0]), acc[0][0], 0, 0, 0);
+                if (n1) acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(fa[ks][0]), as_frag(fb[ks][1]), acc[0][1], 0, 0, 0);
+                if (m1) acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(fa[ks][1]), as_frag(fb[ks][0]), acc[1][0], 0, 0, 0);
+                if (m1 && n1) acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(fa[ks][1]), as_frag(fb[ks][1]), acc[1][1], 0, 0, 0);
+            }
+        }
+    }
+    const int64_t kd = (int64_t)p.k * p.d;
+    float *dst = slot < 0 ? p.g_proj + rel * kd : p.partials + slot * kd;
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi) {
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) {
+            if ((mi == 0 || m1) && (ni == 0 || n1)) {
+                const int j = 32 * (nt0 + ni) + l31;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int a = 32 * (mt0 + mi) + 8 * (v >> 2) + 4 * kg + (v & 3);
+                    dst[(int64_t)a * p.d + j] = acc[mi][ni][v];
                 }
             }
         }
     }
 }
 
-// The chunk in which a border-crossing run of a relation ends adds up the run's partial matrices in
-// chunk order: (first chunk, slot 1), then slot 0 of every later chunk up to this one.
-__global__ __launch_bounds__(kThreads) void k_transr_dm_fixup(ProjArgs p, float *__restrict__ g_proj,
-                                                              const float *__restrict__ partials)
+// The last dM item of a relation that has several adds up the relation's partial matrices in item order.
+__global__ __launch_bounds__(kThreads) void k_transr_dm_fixup(DmArgs p)
 {
-    const int32_t j = (int32_t)blockIdx.x + 1;
-    const int32_t c0 = p.e_begin + j * kProjRowsDm;
-    if (c0 >= p.e_end) return;
-    const int32_t c1 = min(c0 + kProjRowsDm, p.e_end);
-    const int32_t s = p.seg_id[c0];
-    const int32_t sb = p.seg_ptr[s], se = p.seg_ptr[s + 1];
-    if (sb >= c0 || se > c1) return;                      // starts here, or goes on: not the closing chunk
-    const int32_t j0 = (sb - p.e_begin) / kProjRowsDm;
+    if ((int32_t)blockIdx.x >= p.counts[1]) return;
+    const int4 tail = p.dm_items[2 * blockIdx.x + 1];
+    const int parts = tail.y;
+    if (parts == 0) return;
     const int64_t kd = (int64_t)p.k * p.d;
-    float *dst = g_proj + (int64_t)(p.touched_cols[s] - p.n_ent) * kd;
     // blockIdx.y slices the matrix: 4 consecutive elements per thread, 1024 per workgroup
     const int64_t idx = ((int64_t)blockIdx.y * kThreads + threadIdx.x) * 4;
     if (idx >= kd) return;
-    float4 a = ld4(partials + ((int64_t)j0 * 2 + 1) * kd + idx);
-    int32_t jj = j0 + 1;
-    for (; jj + 3 <= j; jj += 4) {    // four partial matrices in flight, added in chunk order
+    const float *src = p.partials + (int64_t)tail.x * kd + idx;
+    float4 a = ld4(src);
+    int u = 1;
+    for (; u + 3 < parts; u += 4) {   // four partial matrices in flight, added in item order
         float4 v[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = ld4(partials + ((int64_t)(jj + u) * 2) * kd + idx);
+        for (int q = 0; q < 4; ++q) v[q] = ld4(src + (int64_t)(u + q) * kd);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) { a.x += v[u].x; a.y += v[u].y; a.z += v[u].z; a.w += v[u].w; }
+        for (int q = 0; q < 4; ++q) { a.x += v[q].x; a.y += v[q].y; a.z += v[q].z; a.w += v[q].w; }
     }
-    for (; jj <= j; ++jj) {
-        float4 v = ld4(partials + ((int64_t)jj * 2) * kd + idx);
+    for (; u < parts; ++u) {
+        float4 v = ld4(src + (int64_t)u * kd);
         a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
     }
-    st4(dst + idx, a);
+    st4(p.g_proj + (int64_t)p.dm_items[2 * blockIdx.x].x * kd + idx, a);
 }
 
 // M_r <- M_r - lr * dL/dM_r for every relation present in the batch (one workgroup per relation;
@@ -264,50 +407,71 @@ __global__ __launch_bounds__(kThreads) void k_sgd_proj(const int32_t *__restrict
 }
 
 // ---------------------------------------------------------------------------------------------------
-static ProjArgs proj_args(stx_ctx *c, const stx_incidence *inc, const stx_params *p)
+static RowsArgs rows_args(stx_ctx *c, const stx_incidence *inc, const stx_params *p, bool gx)
 {
-    ProjArgs a;
-    a.colidx = inc->a_colidx; a.packed = inc->at_packed; a.seg_id = inc->at_seg_id; a.seg_ptr = inc->at_seg_ptr;
-    a.touched_cols = inc->at_touched_cols;
-    a.E = p->ent; a.M = p->proj; a.Rv = p->rel;
-    a.n_ent = (int32_t)c->cfg.n_ent;
-    a.e_begin = (int32_t)(2 * inc->n_rows);               // relation columns follow the entity columns
-    a.e_end = (int32_t)inc->nnz;
-    a.d = c->cfg.dim; a.k = c->cfg.rel_dim;
+    RowsArgs a;
+    a.items = (const int4 *)c->tr_items;
+    a.counts = c->tr_counts;
+    a.colidx = inc->a_colidx; a.packed = inc->at_packed;
+    a.E = p->ent; a.Rv = p->rel;
+    a.Mb = gx ? c->tr_m16t : c->tr_m16;
+    a.tiles = gx ? c->tr_gyt : c->tr_xt;
+    a.n_red = gx ? c->cfg.rel_dim : c->cfg.dim;
+    a.n_out = gx ? c->cfg.dim : c->cfg.rel_dim;
     return a;
 }
+
+// Most row items / dM items a batch of `rows` rows can have: every relation segment adds at most one
+// item that is not full.
+static int64_t max_segments(const stx_ctx *c, int64_t rows) { return rows < c->cfg.n_rel ? rows : c->cfg.n_rel; }
+static unsigned row_items_max(const stx_ctx *c, int64_t rows) { return (unsigned)(rows / 64 + max_segments(c, rows)); }
+static unsigned dm_items_max(const stx_ctx *c, int64_t rows) { return (unsigned)(rows / 256 + max_segments(c, rows)); }
 
 stx_status launch_transr_project(stx_ctx *c, const stx_incidence *inc, const stx_params *p)
 {
     if (inc->n_rows == 0) return STX_OK;
-    ProjArgs a = proj_args(c, inc, p);
-    const int chunks = (int)((inc->n_rows + kProjRows - 1) / kProjRows);
+    {
+        PrepArgs a;
+        a.touched_cols = inc->at_touched_cols; a.n_touched = inc->n_touched;
+        a.seg_ptr = inc->at_seg_ptr; a.seg_id = inc->at_seg_id;
+        a.n_ent = (int32_t)c->cfg.n_ent;
+        a.e_begin = (int32_t)(2 * inc->n_rows);           // relation columns follow the entity columns
+        a.M = p->proj; a.m16 = c->tr_m16; a.m16t = c->tr_m16t;
+        a.items = (int4 *)c->tr_items; a.dm_items = (int4 *)c->tr_dm_items; a.counts = c->tr_counts;
+        a.d = c->cfg.dim; a.k = c->cfg.rel_dim;
+        ProfScope prof(c, "k_transr_prepare");
+        hipLaunchKernelGGL(k_transr_prepare, dim3((unsigned)c->cfg.n_rel + 1), dim3(kThreads), 0, c->stream, a);
+    }
     ProfScope prof(c, "k_transr_project");
-    hipLaunchKernelGGL(k_transr_rows<false>, dim3(chunks), dim3(kThreads), 0, c->stream, a, (const float *)nullptr,
-                       c->gbuf[0]);
+    hipLaunchKernelGGL(k_transr_rows<false>, dim3(row_items_max(c, inc->n_rows)), dim3(kThreads), 0, c->stream,
+                       rows_args(c, inc, p, false), (const float *)nullptr, c->gbuf[0]);
     return hip_ok(hipGetLastError());
 }
 
 stx_status launch_transr_backward(stx_ctx *c, const stx_incidence *inc, const stx_params *p, stx_grads *g)
 {
     if (inc->n_rows == 0) return STX_OK;
-    ProjArgs a = proj_args(c, inc, p);
-    const int chunks = (int)((inc->n_rows + kProjRows - 1) / kProjRows);
-    const int chunks_dm = (int)((inc->n_rows + kProjRowsDm - 1) / kProjRowsDm);
     {
         ProfScope prof(c, "k_transr_gx");
-        hipLaunchKernelGGL(k_transr_rows<true>, dim3(chunks), dim3(kThreads), 0, c->stream, a, c->gbuf[0], c->gbuf[1]);
+        hipLaunchKernelGGL(k_transr_rows<true>, dim3(row_items_max(c, inc->n_rows)), dim3(kThreads), 0, c->stream,
+                           rows_args(c, inc, p, true), c->gbuf[0], c->gbuf[1]);
     }
+    DmArgs a;
+    a.dm_items = (const int4 *)c->tr_dm_items; a.counts = c->tr_counts;
+    a.gyt = c->tr_gyt; a.xt = c->tr_xt;
+    a.g_proj = g->proj; a.partials = c->gbuf[2];
+    a.d = c->cfg.dim; a.k = c->cfg.rel_dim;
+    const unsigned items = dm_items_max(c, inc->n_rows);
     {
         ProfScope prof(c, "k_transr_dm");
-        hipLaunchKernelGGL(k_transr_dm, dim3(chunks_dm), dim3(kThreads), 0, c->stream, a, c->gbuf[0], g->proj,
-                           c->gbuf[2]);
+        hipLaunchKernelGGL(k_transr_dm, dim3(items, (unsigned)(((a.k + 127) / 128) * ((a.d + 127) / 128))),
+                           dim3(kThreads), 0, c->stream, a);
     }
-    if (chunks_dm > 1) {
+    if (inc->n_rows > kProjRowsDm) {                      // otherwise no relation can have two items
         ProfScope prof(c, "k_transr_dm_fixup");
         hipLaunchKernelGGL(k_transr_dm_fixup,
-                           dim3(chunks_dm - 1, (unsigned)(((int64_t)a.k * a.d + 4 * kThreads - 1) / (4 * kThreads))),
-                           dim3(kThreads), 0, c->stream, a, g->proj, c->gbuf[2]);
+                           dim3(items, (unsigned)(((int64_t)a.k * a.d + 4 * kThreads - 1) / (4 * kThreads))),
+                           dim3(kThreads), 0, c->stream, a);
     }
     return hip_ok(hipGetLastError());
 }

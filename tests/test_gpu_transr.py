@@ -89,6 +89,10 @@ CASES = [
     ("l2", 300, 5, 333, 2, 32, 64, 0.0),
     ("l2", 200, 7, 500, 1, 256, 128, 1.1),
     ("l1", 200, 7, 260, 1, 128, 256, 1.1),
+    ("l2", 150, 4, 200, 1, 256, 256, 0.0),        # four 128 x 128 blocks of dL/dM_r
+    ("l2", 150, 6, 130, 1, 96, 160, 0.0),         # tile counts that are not powers of two
+    ("l2", 50, 1, 40, 1, 32, 32, 0.0),            # one relation, one partly filled item
+    ("l2", 500, 300, 100, 1, 64, 64, 0.0),        # more relations than rows: every item nearly empty
 ]
 
 
