@@ -27,7 +27,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 # The kernel whose roofline is reported: the one with the largest share of GPU time in the
 # rocprofv3 kernel trace of the same command (profiles/).
-DOMINANT = {"transe": "k_forward_stacked", "toruse": "k_sgd_rows", "transh": "k_seg_reduce", "transr": "k_transr_dm"}
+DOMINANT = {"transe": "k_forward_stacked", "toruse": "k_sgd_rows", "transh": "k_seg_reduce", "transr": "k_transr_project"}
 
 
 # HBM bytes per launch of those kernels, measured: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (separate runs),
@@ -85,8 +85,16 @@ def kernel_work(wl, kernel, rows, touched):
         return touched * 3 * row, "GB/s", "hbm", HBM_PEAK_GBS
     if kernel == "k_scatter":
         return nnz * 16, "GB/s", "hbm", HBM_PEAK_GBS      # key + payload in, key + payload out
-    if kernel in ("k_transr_project", "k_transr_gx", "k_transr_dm"):
-        return 2.0 * rows * wl.dim * wl.rel_dim, "TFLOP/s", "mfma", MFMA_BF16_PEAK_TFLOPS
+    # TransR's three products: 2*d*k flop per row against ~2 KB of row traffic is ~20 flop per byte, far left of
+    # the ridge (2.5 PFLOP/s / 8 TB/s = 312 flop per byte): their roofline is the memory one.  Bytes: the gathered
+    # fp32 rows, the fp32 rows written, the bf16 transposed tiles, and the bf16 copy of M_r once per relation.
+    nrel = min(wl.n_rel, rows)
+    if kernel == "k_transr_project":   # h and t rows, 12 B of ids, y row out, x tile out
+        return rows * (2 * row + 12 + 4 * wl.rel_dim + 2 * wl.dim) + nrel * 2 * wl.dim * wl.rel_dim, "GB/s", "hbm", HBM_PEAK_GBS
+    if kernel == "k_transr_gx":        # dL/dy row in, dL/dx row out, dL/dy tile out
+        return rows * (4 + 4 * wl.rel_dim + row + 2 * wl.rel_dim) + nrel * 2 * wl.dim * wl.rel_dim, "GB/s", "hbm", HBM_PEAK_GBS
+    if kernel == "k_transr_dm":        # both tiles in, dL/dM_r out
+        return rows * (2 * wl.rel_dim + 2 * wl.dim) + nrel * 4 * wl.dim * wl.rel_dim, "GB/s", "hbm", HBM_PEAK_GBS
     raise ValueError(kernel)
 
 
@@ -237,6 +245,11 @@ def main():
                 "avg_launch_us": round(kernel_us, 2), "launches_per_step": round(per_launch, 2)}
     if kernel_note:
         roofline["note"] = kernel_note
+    if kernel in ("k_transr_project", "k_transr_gx", "k_transr_dm") and kernel_us > 0:
+        # the same launch priced as a contraction, against the dense bf16 matrix-core peak
+        tf = 2.0 * mean_rows * wl.dim * wl.rel_dim / (kernel_us * 1e-6) / 1e12
+        roofline["mfma"] = {"achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                            "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4)}
 
     out = {
         "metric": "training triplets/sec (pos+neg) TransE d=128 fp32" if wl.name == "mid"

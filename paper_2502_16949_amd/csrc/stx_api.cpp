@@ -410,6 +410,8 @@ stx_status stx_backward(stx_ctx *ctx, const stx_incidence *inc, const stx_params
     // and relation columns sum gy (width rel_dim)
     s = launch_transr_backward(ctx, inc, p, g);
     if (s != STX_OK) return s;
+    if (dim == ctx->cfg.rel_dim)   // rows of equal width: one product over all columns, as for TransH
+        return launch_seg_reduce(ctx, inc, 0, inc->nnz, ctx->gbuf[1], ctx->gbuf[0], ent_end, dim, dim, g->rows, ctx->ld);
     s = launch_seg_reduce(ctx, inc, 0, ent_end, ctx->gbuf[1], ctx->gbuf[1], ent_end, dim, dim, g->rows, ctx->ld);
     if (s != STX_OK) return s;
     return launch_seg_reduce(ctx, inc, ent_end, inc->nnz, ctx->gbuf[0], ctx->gbuf[0], inc->nnz, ctx->cfg.rel_dim,

@@ -73,7 +73,7 @@ struct PrepArgs {
 __device__ inline void transr_plan(const PrepArgs &p)
 {
     __shared__ int32_t s_o64[kThreads + 1], s_o256[kThreads + 1], s_op[kThreads], s_beg[kThreads], s_len[kThreads],
-        s_rel[kThreads];
+        s_rel[kThreads], s_wave[kThreads / 64][3];
     const int tid = threadIdx.x;
     const int32_t n_seg = p.n_touched[0];
     int32_t base64 = 0, base256 = 0, basep = 0;
@@ -86,10 +86,30 @@ __device__ inline void transr_plan(const PrepArgs &p)
             rel = p.touched_cols[s] - p.n_ent;
         }
         const int32_t n64 = (len + 63) >> 6, n256 = (len + 255) >> 8;
-        int32_t t64, t256, tp;
-        const int32_t o64 = block_exclusive_scan(n64, &t64);
-        const int32_t o256 = block_exclusive_scan(n256, &t256);
-        const int32_t op = block_exclusive_scan(n256 > 1 ? n256 : 0, &tp);
+        // three exclusive scans across the workgroup at once: shuffles inside a wavefront, LDS across the four
+        int32_t inc3[3] = {n64, n256, n256 > 1 ? n256 : 0};
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+#pragma unroll
+            for (int q = 0; q < 3; ++q) {
+                const int32_t up = __shfl_up(inc3[q], off);
+                if ((tid & 63) >= off) inc3[q] += up;
+            }
+        }
+        if ((tid & 63) == 63) { s_wave[tid >> 6][0] = inc3[0]; s_wave[tid >> 6][1] = inc3[1]; s_wave[tid >> 6][2] = inc3[2]; }
+        __syncthreads();
+        int32_t before[3] = {0, 0, 0}, tot[3] = {0, 0, 0};
+#pragma unroll
+        for (int ww = 0; ww < kThreads / 64; ++ww) {
+#pragma unroll
+            for (int q = 0; q < 3; ++q) {
+                if (ww < (tid >> 6)) before[q] += s_wave[ww][q];
+                tot[q] += s_wave[ww][q];
+            }
+        }
+        const int32_t o64 = before[0] + inc3[0] - n64, o256 = before[1] + inc3[1] - n256,
+                      op = before[2] + inc3[2] - (n256 > 1 ? n256 : 0);
+        const int32_t t64 = tot[0], t256 = tot[1], tp = tot[2];
         s_o64[tid] = o64; s_o256[tid] = o256; s_op[tid] = op;
         s_beg[tid] = beg; s_len[tid] = len; s_rel[tid] = rel;
         if (tid == 0) { s_o64[kThreads] = t64; s_o256[kThreads] = t256; }
@@ -128,7 +148,7 @@ __global__ __launch_bounds__(kThreads) void k_transr_prepare(PrepArgs p)
     const int tid = threadIdx.x;
     const int32_t r = (int32_t)blockIdx.x - 1, target = p.n_ent + r;
     const int32_t n_seg = p.n_touched[0];
-    int32_t lo = 0, hi = n_seg;
+    int32_t lo = p.seg_id[p.e_begin], hi = n_seg;         // relation columns sort after all entity columns
     while (lo < hi) {                                     // first position with touched_cols[pos] >= target
         const int32_t mid = (lo + hi) >> 1;
         if (p.touched_cols[mid] < target) lo = mid + 1; else hi = mid;
@@ -185,8 +205,8 @@ __global__ __launch_bounds__(kThreads) void k_transr_rows(RowsArgs p, const floa
     __shared__ __attribute__((aligned(16))) uint16_t s_a[64 * (kMaxProjDim + kLdsPad)];
     __shared__ int32_t s_row[64], s_h[64], s_t[64];
     const int tid = threadIdx.x;
+    const int4 item = p.items[blockIdx.x];                // the list is allocated for the launch bound: any index is readable
     if ((int32_t)blockIdx.x >= p.counts[0]) return;
-    const int4 item = p.items[blockIdx.x];
     const int rel = item.x, begin = item.y, count = item.z;
     if (tid < 64) {
         int32_t row = -1, hh = 0, tt = 0;
@@ -299,8 +319,8 @@ struct DmArgs {
 // matrix into its slot and k_transr_dm_fixup adds the slots in order.
 __global__ __launch_bounds__(kThreads) void k_transr_dm(DmArgs p)
 {
+    const int4 it = p.dm_items[2 * blockIdx.x];           // readable for every workgroup of the launch bound
     if ((int32_t)blockIdx.x >= p.counts[1]) return;
-    const int4 it = p.dm_items[2 * blockIdx.x];
     const int rel = it.x, tile0 = it.y, entries = it.z, slot = it.w;
     const int l = threadIdx.x & 63, w = threadIdx.x >> 6, l31 = l & 31, kg = l >> 5;
     const int mtl = p.k >> 5, ntl = p.d >> 5, dblocks = (p.d + 127) >> 7;
@@ -383,15 +403,18 @@ __global__ __launch_bounds__(kThreads) void k_transr_dm_fixup(DmArgs p)
     st4(p.g_proj + (int64_t)p.dm_items[2 * blockIdx.x].x * kd + idx, a);
 }
 
-// M_r <- M_r - lr * dL/dM_r for every relation present in the batch (one workgroup per relation;
-// it looks its column up in the sorted touched list and leaves if absent).
+// M_r <- M_r - lr * dL/dM_r for every relation present in the batch: workgroup (r, y) looks relation r's
+// column up in the sorted touched list, leaves if it is absent, and updates slice y of the matrix
+// (four float4 per thread).
+constexpr int kProjSlice = kThreads * 16;
 __global__ __launch_bounds__(kThreads) void k_sgd_proj(const int32_t *__restrict__ touched_cols,
-                                                       const int32_t *__restrict__ n_touched, int32_t n_ent,
+                                                       const int32_t *__restrict__ n_touched,
+                                                       const int32_t *__restrict__ first_rel_seg, int32_t n_ent,
                                                        int64_t kd, float *__restrict__ M,
                                                        const float *__restrict__ g_proj, float lr)
 {
     const int32_t target = n_ent + (int32_t)blockIdx.x;
-    int32_t lo = 0, hi = n_touched[0];
+    int32_t lo = first_rel_seg[0], hi = n_touched[0];     // relation columns sort after all entity columns
     while (lo < hi) {                                     // first position with touched_cols[pos] >= target
         const int32_t mid = (lo + hi) >> 1;
         if (touched_cols[mid] < target) lo = mid + 1; else hi = mid;
@@ -399,10 +422,20 @@ __global__ __launch_bounds__(kThreads) void k_sgd_proj(const int32_t *__restrict
     if (lo >= n_touched[0] || touched_cols[lo] != target) return;
     float *m = M + (int64_t)blockIdx.x * kd;
     const float *g = g_proj + (int64_t)blockIdx.x * kd;
-    for (int64_t idx = (int64_t)threadIdx.x * 4; idx < kd; idx += kThreads * 4) {
-        float4 x = ld4(m + idx), gg = ld4(g + idx);
-        const float s0 = lr * gg.x, s1 = lr * gg.y, s2 = lr * gg.z, s3 = lr * gg.w;
-        st4(m + idx, make_float4(x.x - s0, x.y - s1, x.z - s2, x.w - s3));
+    const int64_t base = (int64_t)blockIdx.y * kProjSlice + (int64_t)threadIdx.x * 4;
+    float4 x[4], gg[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int64_t idx = base + (int64_t)u * kThreads * 4;
+        if (idx < kd) { x[u] = ld4(m + idx); gg[u] = ld4_stream(g + idx); }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int64_t idx = base + (int64_t)u * kThreads * 4;
+        if (idx < kd) {
+            const float s0 = lr * gg[u].x, s1 = lr * gg[u].y, s2 = lr * gg[u].z, s3 = lr * gg[u].w;
+            st4(m + idx, make_float4(x[u].x - s0, x[u].y - s1, x[u].z - s2, x[u].w - s3));
+        }
     }
 }
 
@@ -480,9 +513,11 @@ stx_status launch_transr_sgd_proj(stx_ctx *c, const stx_incidence *inc, stx_para
 {
     if (inc->n_rows == 0) return STX_OK;
     ProfScope prof(c, "k_sgd_proj");
-    hipLaunchKernelGGL(k_sgd_proj, dim3((unsigned)c->cfg.n_rel), dim3(kThreads), 0, c->stream, inc->at_touched_cols,
-                       inc->n_touched, (int32_t)c->cfg.n_ent, (int64_t)c->cfg.rel_dim * c->cfg.dim, p->proj, g->proj,
-                       lr);
+    const int64_t kd = (int64_t)c->cfg.rel_dim * c->cfg.dim;
+    hipLaunchKernelGGL(k_sgd_proj, dim3((unsigned)c->cfg.n_rel, (unsigned)((kd + kProjSlice - 1) / kProjSlice)),
+                       dim3(kThreads), 0, c->stream, inc->at_touched_cols, inc->n_touched,
+                       inc->at_seg_id + 2 * inc->n_rows, (int32_t)c->cfg.n_ent, kd,
+                       p->proj, g->proj, lr);
     return hip_ok(hipGetLastError());
 }
 
