@@ -27,7 +27,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 # The kernel whose roofline is reported: the one with the largest share of GPU time in the
 # rocprofv3 kernel trace of the same command (profiles/).
-DOMINANT = {"transe": "k_forward_stacked", "toruse": "k_sgd_rows", "transh": "k_seg_reduce", "transr": "k_transr_project"}
+DOMINANT = {"transe": "k_forward_stacked", "toruse": "k_seg_reduce", "transh": "k_seg_reduce", "transr": "k_transr_project"}
 
 
 # HBM bytes per launch of those kernels, measured: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (separate runs),
@@ -47,6 +47,8 @@ def parse():
     ap.add_argument("--config", default="mid", help="workload: tiny | mid | transh | transr | toruse")
     ap.add_argument("--kernel", default=None, help="kernel to time for the roofline entry (default: the dominant one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--unfused", action="store_true",
+                    help="call stx_backward and stx_sgd_step separately instead of stx_backward_sgd")
     ap.add_argument("--all-kernels", action="store_true",
                     help="extra untimed pass that brackets every kernel with events and adds 'kernels_us' to the output")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -56,7 +58,7 @@ def parse():
     return ap.parse_args()
 
 
-def kernel_work(wl, kernel, rows, touched):
+def kernel_work(wl, kernel, rows, touched, fused=False):
     """Algorithmic work of ONE launch of `kernel` on a full batch: (amount, unit, bound, peak).
     row = 4*dim bytes.  rows = b*(1+k) matrix rows, nnz = 3*rows, touched = distinct columns."""
     row = 4 * wl.dim
@@ -80,6 +82,9 @@ def kernel_work(wl, kernel, rows, touched):
             return (nnz * (row + 4) + touched * row + rows * (row + 4) + min(wl.n_rel, rows) * row) / 2, "GB/s", "hbm", HBM_PEAK_GBS
         if wl.model == "transr":
             return (nnz * (row + 4) + touched * row) / 2, "GB/s", "hbm", HBM_PEAK_GBS
+        if fused and wl.model in ("transe", "toruse"):
+            # fused update: the table row is read and written where the gradient row would have been written
+            return nnz * (grow + 4) + touched * 2 * row, "GB/s", "hbm", HBM_PEAK_GBS
         return nnz * (grow + 4) + touched * row, "GB/s", "hbm", HBM_PEAK_GBS
     if kernel == "k_sgd_rows":
         return touched * 3 * row, "GB/s", "hbm", HBM_PEAK_GBS
@@ -166,7 +171,9 @@ def main():
     slices = W.batch_slices(wl)
     seed = W.negative_seed(wl)
 
-    # Argument lists are marshalled once per batch; the timed loop makes only the five C calls.
+    # Argument lists are marshalled once per batch; the timed loop makes only the C calls: sample, build,
+    # forward and the fused backward + update (stx_backward_sgd), or backward and update separately (--unfused).
+    fused = not args.unfused
     L = B.lib()
     import ctypes as C
     byref = C.byref
@@ -179,11 +186,12 @@ def main():
                 (ctx.handle, byref(inc.c), byref(params.c), scores.data_ptr(), loss.data_ptr()),
                 (ctx.handle, byref(inc.c), byref(params.c), byref(grads.c)),
                 (ctx.handle, byref(params.c), byref(inc.c), byref(grads.c), wl.lr),
+                (ctx.handle, byref(inc.c), byref(params.c), byref(grads.c), wl.lr),
                 b * (1 + wl.n_neg))
     calls = [marshal(lo, hi) for lo, hi in slices]
 
     def step(i, ev=None):
-        a_s, a_b, a_f, a_g, a_u, rows = calls[i % len(calls)]
+        a_s, a_b, a_f, a_g, a_u, a_bu, rows = calls[i % len(calls)]
         if ev: ev[0].record()
         st = L.stx_sample_negatives(*a_s)
         if ev: ev[1].record()
@@ -191,9 +199,13 @@ def main():
         if ev: ev[2].record()
         st |= L.stx_forward(*a_f)
         if ev: ev[3].record()
-        st |= L.stx_backward(*a_g)
-        if ev: ev[4].record()
-        st |= L.stx_sgd_step(*a_u)
+        if fused:
+            st |= L.stx_backward_sgd(*a_bu)
+            if ev: ev[4].record()
+        else:
+            st |= L.stx_backward(*a_g)
+            if ev: ev[4].record()
+            st |= L.stx_sgd_step(*a_u)
         if ev: ev[5].record()
         if st:
             raise RuntimeError(f"a library call failed in step {i} (or-ed status {st})")
@@ -235,7 +247,7 @@ def main():
     # ---- roofline of the dominant kernel.  The mean launch time covers every batch of the timed region
     # (the partial last batch of an epoch included), so the work figure is averaged the same way. ----------
     mean_rows = rows_done / args.steps
-    work, unit, bound, peak = kernel_work(wl, kernel, mean_rows, u_last * mean_rows / wl.rows_per_batch)
+    work, unit, bound, peak = kernel_work(wl, kernel, mean_rows, u_last * mean_rows / wl.rows_per_batch, fused)
     kernel_note = ("two launches per step with different work: work and time are both means over the two"
                    if kernel == "k_seg_reduce" and wl.model in ("transh", "transr") else "")
     per_launch = kernel_n / args.steps if args.steps else 0
@@ -263,8 +275,10 @@ def main():
                                f"batch {wl.batch}, {wl.n_neg} negative(s) per positive, margin {wl.margin}, "
                                f"SGD lr {wl.lr}",
                    "rows_per_full_batch": wl.rows_per_batch, "batches_per_epoch": len(slices),
-                   "step": "sample negatives + build incidence + forward + backward + sgd"},
-        "phase_us": {k: round(float(v), 2) for k, v in zip(("sample", "build", "forward", "backward", "sgd"), phase_us)},
+                   "step": "sample negatives + build incidence + forward + " +
+                           ("backward with fused sgd (stx_backward_sgd)" if fused else "backward + sgd")},
+        "phase_us": {k: round(float(v), 2) for k, v in
+                     zip(("sample", "build", "forward", "backward_sgd" if fused else "backward", "sgd"), phase_us)},
         "host_enqueue_us_per_step": round(t_enq / args.steps * 1e6, 2),
         "touched_rows_last_step": u_last,
         "loss_last_step": loss_last,

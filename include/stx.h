@@ -180,6 +180,14 @@ stx_status stx_backward(stx_ctx *ctx, const stx_incidence *inc, const stx_params
 stx_status stx_sgd_step(stx_ctx *ctx, stx_params *p, const stx_incidence *inc, const stx_grads *g,
                         float lr);
 
+/* stx_backward and stx_sgd_step in one call, with the same results in the tables (the paper counts the
+ * optimiser step as part of the training loop, Table 1; fusing it with Appendix G's transposed product is
+ * this library's choice).  TransE / TorusE: the update is applied where the transposed product would
+ * store a gradient row, so the gradient rows are never written: g may be null and, if given, is left
+ * untouched.  TransH / TransR: the two calls are made one after the other and g (required) receives
+ * the gradients.  Needs the stx_forward of the same incidence immediately before it.                  */
+stx_status stx_backward_sgd(stx_ctx *ctx, const stx_incidence *inc, stx_params *p, stx_grads *g, float lr);
+
 /* Live timing of one kernel, for benchmarks.  stx_profile_kernel: from now on every launch of the kernel
  * called `kernel_name` (e.g. "k_forward_stacked", "k_seg_reduce", "k_sgd_rows", "k_scatter") on this
  * context is bracketed by a pair of HIP events on the context's stream, for at most max_records

@@ -25,7 +25,7 @@ MODELS = {"transe": STX_TRANSE, "transh": STX_TRANSH, "transr": STX_TRANSR, "tor
 DISTS = {"l1": STX_L1, "l2": STX_L2, "torus_l1": STX_TORUS_L1, "torus_l2": STX_TORUS_L2}
 
 EXPORTS = ["stx_workspace_bytes", "stx_create", "stx_destroy", "stx_sample_negatives", "stx_build_incidence",
-           "stx_check_indices", "stx_spmm", "stx_forward", "stx_backward", "stx_sgd_step", "stx_profile_kernel",
+           "stx_check_indices", "stx_spmm", "stx_forward", "stx_backward", "stx_sgd_step", "stx_backward_sgd", "stx_profile_kernel",
            "stx_profile_read", "stx_profile_dump", "stx_copy_f32", "stx_status_string"]
 
 
@@ -80,6 +80,8 @@ def lib():
         L.stx_backward.argtypes = [vp, C.POINTER(stx_incidence), C.POINTER(stx_params), C.POINTER(stx_grads)]
         L.stx_sgd_step.argtypes = [vp, C.POINTER(stx_params), C.POINTER(stx_incidence), C.POINTER(stx_grads),
                                    C.c_float]
+        L.stx_backward_sgd.argtypes = [vp, C.POINTER(stx_incidence), C.POINTER(stx_params), C.POINTER(stx_grads),
+                                       C.c_float]
         L.stx_profile_kernel.argtypes = [vp, C.c_char_p, i32]
         L.stx_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32)]
         L.stx_profile_dump.argtypes = [vp, C.c_char_p, C.c_size_t]
@@ -254,6 +256,12 @@ def stx_backward(ctx: Context, inc: Incidence, p: Params, g: Grads):
 
 def stx_sgd_step(ctx: Context, p: Params, inc: Incidence, g: Grads, lr: float):
     _check("stx_sgd_step", lib().stx_sgd_step(ctx.handle, C.byref(p.c), C.byref(inc.c), C.byref(g.c), lr))
+
+
+def stx_backward_sgd(ctx: Context, inc: Incidence, p: Params, g, lr: float):
+    """g may be None for TransE / TorusE (no gradient rows are written)."""
+    gp = C.byref(g.c) if g is not None else None
+    _check("stx_backward_sgd", lib().stx_backward_sgd(ctx.handle, C.byref(inc.c), C.byref(p.c), gp, lr))
 
 
 def stx_profile_kernel(ctx: Context, kernel_name, max_records: int):

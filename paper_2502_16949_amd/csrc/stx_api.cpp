@@ -181,6 +181,8 @@ stx_status stx_create(const stx_config *cfg, void *workspace, size_t workspace_b
     c->tr_gyt = tr ? (uint16_t *)(base + L.tr_gyt) : nullptr;
     c->fwd_inc = nullptr;
     c->fwd_rows = 0;
+    c->sorted_inc = nullptr;
+    c->sorted_keys = nullptr;
     c->prof_ev = nullptr;
     c->prof_tag = nullptr;
     c->prof_cap = c->prof_n = 0;
@@ -444,6 +446,27 @@ stx_status stx_sgd_step(stx_ctx *ctx, stx_params *p, const stx_incidence *inc, c
     s = launch_sgd_rows(ctx, inc, T, g->rows, nullptr, lr);
     if (s != STX_OK) return s;
     return launch_transr_sgd_proj(ctx, inc, p, g, lr);
+}
+
+stx_status stx_backward_sgd(stx_ctx *ctx, const stx_incidence *inc, stx_params *p, stx_grads *g, float lr)
+{
+    if (!ctx) return STX_ERR_NULL;
+    if (!stacked(ctx)) {
+        stx_status s = stx_backward(ctx, inc, p, g);
+        if (s != STX_OK) return s;
+        return stx_sgd_step(ctx, p, inc, g, lr);
+    }
+    stx_status s = check_built(ctx, inc);
+    if (s != STX_OK) return s;
+    s = check_params(ctx, p);
+    if (s != STX_OK) return s;
+    if (!(lr == lr)) return STX_ERR_BAD_ARG;
+    if (ctx->fwd_inc != inc || ctx->fwd_rows != inc->n_rows) return STX_ERR_STATE;
+    ctx->fwd_inc = nullptr;   // the tables change: a stored forward no longer matches them
+    const int dim = ctx->cfg.dim;
+    const bool pk = packed_grad(ctx);
+    return launch_seg_reduce(ctx, inc, 0, inc->nnz, ctx->gbuf[0], ctx->gbuf[0], inc->nnz, pk ? packed_stride(dim) : dim,
+                             dim, nullptr, ctx->ld, pk, p->ent, lr, ctx->cfg.model == STX_TORUSE ? 1 : 0);
 }
 
 stx_status stx_copy_f32(stx_ctx *ctx, float *dst, const float *src, int64_t n)

@@ -18,6 +18,12 @@
 //
 // Every output row is written exactly once and every sum has a fixed association order, so results are
 // bitwise reproducible from run to run.
+//
+// FUSED variants of both kernels apply the SGD update in place of the store: wherever a gradient row
+// would be written they write table[column] - lr * gradient (and wrap it for TorusE) instead, with the
+// same two roundings as k_sgd_rows, so the gradient rows never travel to memory and back.  The table
+// row of a run is fetched together with the run's first source row, so closing a run costs no extra
+// memory round trip.
 #include "stx_rowops.h"
 
 namespace stx {
@@ -69,21 +75,53 @@ __device__ inline void store_row(float *__restrict__ p, int d4, int lig, const A
     }
 }
 
+struct FusedArgs {             // the update that replaces the store of a gradient row (FUSED kernels)
+    float *table;              // rows of 4*d4 floats, indexed by column
+    const int32_t *touched_cols;
+    const int32_t *cols_sorted;  // column of every sorted entry, or null: then it is looked up through the segment
+    float lr;
+    int mode;                  // 0 plain, 1 keep the fractional part (TorusE, Sec. 4.6)
+};
+
+// table row <- x - lr * g, each product and difference rounded once, as in k_sgd_rows.
+template <int LPR, int ITERS>
+__device__ inline void apply_update(float *__restrict__ row, int d4, int lig, const Acc<ITERS> &x, const Acc<ITERS> &g,
+                                    float lr, int mode)
+{
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const int j = lig + it * LPR;
+        const float *xv = &x.v[it].x, *gv = &g.v[it].x;
+        float o[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float step = lr * gv[q];
+            float nv = xv[q] - step;
+            if (mode == 1) {
+                nv = nv - floorf(nv);
+                if (nv >= 1.0f) nv = 0.0f;
+            }
+            o[q] = nv;
+        }
+        if (j < d4) st4_stream(row + 4 * j, make_float4(o[0], o[1], o[2], o[3]));
+    }
+}
+
 // PACKED: the source rows are records of ld_src bytes at src_a (coefficient, then dim/4 sign bytes), as
 // the forward pass of an L1-kind distance stores them; values and summation order are the same as with
 // dense rows, so both forms give the same bits.
-template <int LPR, int ITERS, bool PACKED, int CHUNK>
+template <int LPR, int ITERS, bool PACKED, int CHUNK, bool FUSED>
 __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restrict__ packed,
                                                          const int32_t *__restrict__ seg_id, int32_t e_begin,
                                                          int32_t e_end, const float *__restrict__ src_a,
                                                          const float *__restrict__ src_b, int32_t split,
                                                          int ld_src, int d4, float *__restrict__ out_rows,
-                                                         int ld_out, float *__restrict__ partials)
+                                                         int ld_out, float *__restrict__ partials, FusedArgs fu)
 {
     constexpr int GROUPS = kThreads / LPR;
     // rows in flight per lane: dense rows cost 4*ITERS registers each; packed rows are a byte and a float,
     // so a whole chunk is fetched at once and the kernel pays one memory latency per chunk
-    constexpr int UNROLL = PACKED ? (CHUNK < 8 ? CHUNK : 8) : (ITERS == 1 ? 8 : (ITERS == 2 ? 4 : 2));
+    constexpr int UNROLL = PACKED ? (FUSED ? 4 : (CHUNK < 8 ? CHUNK : 8)) : (ITERS == 1 ? (FUSED ? 4 : 8) : (ITERS == 2 ? 4 : 2));
     constexpr int TILE = GROUPS * CHUNK;    // sorted entries per workgroup
     static_assert(CHUNK <= LPR && CHUNK % UNROLL == 0, "one entry per lane per chunk");
     constexpr int VROWS = PACKED ? 1 : UNROLL;
@@ -91,6 +129,10 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
     __shared__ float s_part[GROUPS][2][ROWF];
     __shared__ int s_info[GROUPS];
     __shared__ int32_t s_seg_first[GROUPS], s_seg_last[GROUPS];
+    // FUSED: table row and column of the run that leaves each chunk to the right; which chunk's they are for
+    // the stitched run that closes in a chunk (-1: none closes there)
+    __shared__ float s_x[FUSED ? GROUPS : 1][FUSED ? ROWF : 4];
+    __shared__ int32_t s_col_last[GROUPS], s_fin_src[GROUPS];
 
     const int lig = threadIdx.x % LPR, grp = threadIdx.x / LPR;
     const int32_t tile0 = e_begin + (int32_t)blockIdx.x * TILE;
@@ -101,6 +143,12 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
     if (ec0 < e_end) {
         const int n = ec1 - ec0;
         const int32_t meta = (lig < CHUNK && ec0 + lig < ec1) ? packed[ec0 + lig] : 0;   // 0: row 0, a safe address
+        int32_t colv = 0;                                  // FUSED: the column of this lane's entry
+        if (FUSED && lig < CHUNK && ec0 + lig < ec1)
+            colv = fu.cols_sorted ? fu.cols_sorted[ec0 + lig] : fu.touched_cols[seg_id[ec0 + lig]];
+        Acc<ITERS> xcur;                                   // FUSED: table row of the run that is being summed
+        int32_t colcur = 0;
+        xcur.zero();
         const int32_t meta0 = __shfl(meta, 0, LPR);
         const bool first_open = (ec0 > e_begin) && !(meta0 & 2);
         const bool right_open = (ec1 < e_end) && !(packed[ec1] & 2);
@@ -113,7 +161,10 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
             const bool open_left = (nflush == 0) && first_open;
             const bool open_right = last_run && right_open;
             if (!open_left && !open_right) {
-                store_row_stream<LPR, ITERS>(out_rows + (int64_t)cur_seg * ld_out, d4, lig, acc);
+                if constexpr (FUSED)
+                    apply_update<LPR, ITERS>(fu.table + (int64_t)colcur * d4 * 4, d4, lig, xcur, acc, fu.lr, fu.mode);
+                else
+                    store_row_stream<LPR, ITERS>(out_rows + (int64_t)cur_seg * ld_out, d4, lig, acc);
             } else {
                 const int slot = open_left ? 0 : 1;
 #pragma unroll
@@ -125,6 +176,11 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
                 } else {
                     info |= HAS_LAST;
                     if (lig == 0) s_seg_last[grp] = cur_seg;
+                    if constexpr (FUSED) {   // the run began in this chunk: its table row is already here
+#pragma unroll
+                        for (int it = 0; it < ITERS; ++it) st4(&s_x[grp][(lig + it * LPR) * 4], xcur.v[it]);
+                        if (lig == 0) s_col_last[grp] = colcur;
+                    }
                 }
             }
             ++nflush;
@@ -132,16 +188,24 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
 
         for (int j0 = 0; j0 < n; j0 += UNROLL) {
             Acc<ITERS> v[VROWS];
-            int32_t mu[UNROLL];
+            Acc<ITERS> xr[FUSED ? UNROLL : 1];
+            int32_t mu[UNROLL], cu[UNROLL];
             uint8_t sb[UNROLL][ITERS];
             float cf[UNROLL];
             // every lane learns the batch's entries first (shuffles back to back, one wait), then all row
             // loads go out unconditionally: entries past the end of the chunk carry meta 0, i.e. row 0
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) mu[u] = __shfl(meta, (j0 + u) & (LPR - 1), LPR);
+            if constexpr (FUSED) {
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) cu[u] = __shfl(colv, (j0 + u) & (LPR - 1), LPR);
+            }
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const int64_t row = mu[u] >> 2;
+                if constexpr (FUSED) {   // a run begins here: its table row comes along with its first source row
+                    if (mu[u] & 2) load_row<LPR, ITERS>(fu.table + (int64_t)cu[u] * d4 * 4, d4, lig, xr[u]);
+                }
                 if constexpr (PACKED) {
                     const uint8_t *rec = reinterpret_cast<const uint8_t *>(src_a) + row * ld_src;
                     const uint8_t *pb = rec + 4;
@@ -159,10 +223,13 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
             for (int u = 0; u < UNROLL; ++u) {
                 const int jj = j0 + u;
                 if (jj < n) {
-                    if ((mu[u] & 2) && jj > 0) {
-                        flush(false);
-                        ++cur_seg;
-                        acc.zero();
+                    if (mu[u] & 2) {
+                        if (jj > 0) {
+                            flush(false);
+                            ++cur_seg;
+                            acc.zero();
+                        }
+                        if constexpr (FUSED) { xcur = xr[u]; colcur = cu[u]; }
                     }
                     constexpr int VI = PACKED ? 0 : 1;
                     Acc<ITERS> &vu = v[u * VI];
@@ -189,13 +256,14 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
         }
         flush(true);
     }
-    if (lig == 0) s_info[grp] = info;
+    if (lig == 0) { s_info[grp] = info; s_fin_src[grp] = -1; }
     __syncthreads();
 
     // Stitch the chunk-crossing runs in chunk order (group 0 only; lanes keep their float4 slices).
     if (grp == 0) {
         bool have = false, started_in = false;
         int32_t cur_seg = 0;
+        int cur_src = 0;                                   // chunk in which the current run began
         Acc<ITERS> cur;
         cur.zero();
         float *my_part = partials + (int64_t)blockIdx.x * 2 * ld_out;
@@ -211,27 +279,47 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
                     cur.add(p);
                 }
                 if (!(inf & FIRST_CONT)) {   // the run ends inside chunk g
-                    if (started_in) store_row<LPR, ITERS>(out_rows + (int64_t)cur_seg * ld_out, d4, lig, cur);
-                    else store_row<LPR, ITERS>(my_part, d4, lig, cur);   // began in an earlier workgroup
+                    if (!started_in) {
+                        store_row<LPR, ITERS>(my_part, d4, lig, cur);   // began in an earlier workgroup
+                    } else if constexpr (FUSED) {   // left in chunk g's consumed slot; group g applies it below
+#pragma unroll
+                        for (int it = 0; it < ITERS; ++it) st4(&s_part[g][0][(lig + it * LPR) * 4], cur.v[it]);
+                        if (lig == 0) s_fin_src[g] = cur_src;
+                    } else {
+                        store_row<LPR, ITERS>(out_rows + (int64_t)cur_seg * ld_out, d4, lig, cur);
+                    }
                     have = false;
                 }
             }
             if (inf & HAS_LAST) {
-                have = true; started_in = true; cur_seg = s_seg_last[g];
+                have = true; started_in = true; cur_seg = s_seg_last[g]; cur_src = g;
 #pragma unroll
                 for (int it = 0; it < ITERS; ++it) cur.v[it] = ld4(&s_part[g][1][(lig + it * LPR) * 4]);
             }
         }
         if (have) store_row<LPR, ITERS>(my_part + (started_in ? ld_out : 0), d4, lig, cur);   // runs on into the next tile
     }
+    if constexpr (FUSED) {   // the stitched runs that closed inside the tile: one per group at most, applied in parallel
+        __syncthreads();
+        const int src = s_fin_src[grp];
+        if (src >= 0) {
+            Acc<ITERS> x, g;
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) {
+                x.v[it] = ld4(&s_x[src][(lig + it * LPR) * 4]);
+                g.v[it] = ld4(&s_part[grp][0][(lig + it * LPR) * 4]);
+            }
+            apply_update<LPR, ITERS>(fu.table + (int64_t)s_col_last[src] * d4 * 4, d4, lig, x, g, fu.lr, fu.mode);
+        }
+    }
 }
 
-template <int LPR, int ITERS, int CHUNK>
+template <int LPR, int ITERS, int CHUNK, bool FUSED>
 __global__ __launch_bounds__(kThreads) void k_seg_fixup(const int32_t *__restrict__ packed,
                                                         const int32_t *__restrict__ seg_id,
                                                         const int32_t *__restrict__ seg_ptr, int32_t e_begin,
                                                         int32_t e_end, int d4, float *__restrict__ out_rows,
-                                                        int ld_out, const float *__restrict__ partials)
+                                                        int ld_out, const float *__restrict__ partials, FusedArgs fu)
 {
     constexpr int GROUPS = kThreads / LPR;
     constexpr int ROWF = ITERS * LPR * 4;
@@ -253,9 +341,13 @@ __global__ __launch_bounds__(kThreads) void k_seg_fixup(const int32_t *__restric
     const bool closes = any_head || (m_next & 2);
     if (!closes) return;                                        // the run goes on; a later tile finishes it
 
+    const int lig = threadIdx.x % LPR, grp = threadIdx.x / LPR;
+    const int32_t col = FUSED ? fu.touched_cols[seg] : 0;
     const int32_t j0 = (seg_ptr[seg] - e_begin) / TILE;         // tile in which the run began
     const int n = j - j0 + 1;                                   // partial rows: (j0, slot 1), (j0+1 .. j, slot 0)
-    const int lig = threadIdx.x % LPR, grp = threadIdx.x / LPR;
+    Acc<ITERS> xrow;                                            // FUSED: the table row, fetched beside the partial rows
+    xrow.zero();
+    if (FUSED && grp == 0) load_row<LPR, ITERS>(fu.table + (int64_t)col * d4 * 4, d4, lig, xrow);
     const int per = (n + GROUPS - 1) / GROUPS;
     const int lo = min(grp * per, n), hi = min(lo + per, n);
     Acc<ITERS> acc;
@@ -286,7 +378,8 @@ __global__ __launch_bounds__(kThreads) void k_seg_fixup(const int32_t *__restric
             for (int it = 0; it < ITERS; ++it) v.v[it] = ld4(&s_sum[g][(lig + it * LPR) * 4]);
             acc.add(v);
         }
-        store_row<LPR, ITERS>(out_rows + (int64_t)seg * ld_out, d4, lig, acc);
+        if constexpr (FUSED) apply_update<LPR, ITERS>(fu.table + (int64_t)col * d4 * 4, d4, lig, xrow, acc, fu.lr, fu.mode);
+        else store_row<LPR, ITERS>(out_rows + (int64_t)seg * ld_out, d4, lig, acc);
     }
 }
 
@@ -409,7 +502,7 @@ __global__ __launch_bounds__(kThreads) void k_sgd_rows(const int32_t *__restrict
 template <int LPR, int ITERS>
 static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_t e_end, const float *src_a,
                    const float *src_b, int32_t split, int ld_src, int width, float *out_rows, int ld_out,
-                   bool packed_src)
+                   bool packed_src, const FusedArgs *fused)
 {
     // Entries per lane group: short chunks shorten every group's serial walk when the whole product is
     // small (latency bound); long ones mean fewer partial rows when it is large (bandwidth bound).
@@ -418,23 +511,26 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
     const bool small = (e_end - e_begin) <= (1 << 20);
     const int tile = GROUPS * (small ? CH_SHORT : CH_LONG);
     const int ntiles = (e_end - e_begin + tile - 1) / tile;
-#define STX_SEG(P, CH)                                                                                          \
+    const FusedArgs fu = fused ? *fused : FusedArgs{nullptr, nullptr, nullptr, 0.f, 0};
+#define STX_SEG(P, CH, F)                                                                                       \
     do {                                                                                                        \
         {                                                                                                       \
             ProfScope prof(c, "k_seg_reduce");                                                                  \
-            hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH>), dim3(ntiles), dim3(kThreads), 0, c->stream,   \
-                               inc->at_packed, inc->at_seg_id, e_begin, e_end, src_a, src_b, split, ld_src,     \
-                               width / 4, out_rows, ld_out, c->partials);                                       \
+            hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH, F>), dim3(ntiles), dim3(kThreads), 0,           \
+                               c->stream, inc->at_packed, inc->at_seg_id, e_begin, e_end, src_a, src_b, split,  \
+                               ld_src, width / 4, out_rows, ld_out, c->partials, fu);                           \
         }                                                                                                       \
         if (ntiles > 1) {                                                                                       \
             ProfScope prof(c, "k_seg_fixup");                                                                   \
-            hipLaunchKernelGGL((k_seg_fixup<LPR, ITERS, CH>), dim3(ntiles - 1), dim3(kThreads), 0, c->stream,   \
-                               inc->at_packed, inc->at_seg_id, inc->at_seg_ptr, e_begin, e_end, width / 4,      \
-                               out_rows, ld_out, c->partials);                                                  \
+            hipLaunchKernelGGL((k_seg_fixup<LPR, ITERS, CH, F>), dim3(ntiles - 1), dim3(kThreads), 0,           \
+                               c->stream, inc->at_packed, inc->at_seg_id, inc->at_seg_ptr, e_begin, e_end,      \
+                               width / 4, out_rows, ld_out, c->partials, fu);                                   \
         }                                                                                                       \
     } while (0)
-    if (packed_src) { if (small) STX_SEG(true, CH_SHORT); else STX_SEG(true, CH_LONG); }
-    else            { if (small) STX_SEG(false, CH_SHORT); else STX_SEG(false, CH_LONG); }
+#define STX_SEG2(P, CH) do { if (fused) STX_SEG(P, CH, true); else STX_SEG(P, CH, false); } while (0)
+    if (packed_src) { if (small) STX_SEG2(true, CH_SHORT); else STX_SEG2(true, CH_LONG); }
+    else            { if (small) STX_SEG2(false, CH_SHORT); else STX_SEG2(false, CH_LONG); }
+#undef STX_SEG2
 #undef STX_SEG
 }
 
@@ -456,12 +552,17 @@ static void sgd_go(stx_ctx *c, const stx_incidence *inc, const SgdTables &T, con
 
 stx_status launch_seg_reduce(stx_ctx *c, const stx_incidence *inc, int64_t e_begin, int64_t e_end,
                              const float *src_a, const float *src_b, int64_t split, int ld_src, int width,
-                             float *out_rows, int ld_out, bool packed_src)
+                             float *out_rows, int ld_out, bool packed_src, float *fused_table, float fused_lr,
+                             int fused_mode)
 {
     if (e_end <= e_begin) return STX_OK;
     Launch L = row_launch(width);
+    // the sorted keys of the last build on this context are the columns of the sorted entries
+    const FusedArgs fu{fused_table, inc->at_touched_cols, c->sorted_inc == inc ? c->sorted_keys : nullptr, fused_lr,
+                       fused_mode};
+    const FusedArgs *fused = fused_table ? &fu : nullptr;
     STX_DISPATCH_ROW(L, seg_go, c, inc, (int32_t)e_begin, (int32_t)e_end, src_a, src_b, (int32_t)split, ld_src, width,
-                     out_rows, ld_out, packed_src);
+                     out_rows, ld_out, packed_src, fused);
     return hip_ok(hipGetLastError());
 }
 

@@ -403,6 +403,8 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
                         const int32_t *nt, int32_t b, int32_t k, stx_incidence *inc)
 {
     hipStream_t s = c->stream;
+    c->sorted_inc = nullptr;
+    c->sorted_keys = nullptr;
     if (b == 0) {
         hipLaunchKernelGGL(k_empty_incidence, dim3(1), dim3(64), 0, s, inc->a_rowptr, inc->at_seg_ptr,
                            inc->n_touched);
@@ -468,6 +470,8 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
     hipLaunchKernelGGL(k_seg_write, dim3(nseg), dim3(kThreads), 0, s, c->keys[cur], c->pay[cur], nnz,
                        c->tile_heads, inc->n_touched, inc->at_touched_cols, inc->at_seg_ptr, inc->at_row_idx,
                        inc->at_sign, inc->at_seg_id, inc->at_packed);
+    c->sorted_inc = inc;
+    c->sorted_keys = c->keys[cur];
     return hip_ok(hipGetLastError());
 }
 

@@ -65,6 +65,8 @@ struct stx_ctx {
     const char **prof_tag;         // kernel name of each recorded pair (string literals of the launch sites)
     int prof_cap, prof_n;
     // host-side call-order state
+    const stx_incidence *sorted_inc;   // incidence of the last build, whose sorted keys are still in keys[]
+    const int32_t *sorted_keys;
     const stx_incidence *fwd_inc;  // incidence of the last stx_forward, null if none
     int64_t fwd_rows;
 };
@@ -85,9 +87,12 @@ stx_status launch_copy_f32(stx_ctx *, float *dst, const float *src, int64_t n);
 // out_rows[segment] = signed sum of source rows over the sorted entries [e_begin, e_end); entries
 // before `split` read src_a, the others src_b (both with ld_src floats per row, `width` of them used).
 // packed_src: src_a holds packed L1-kind records (see packed_stride), ld_src is the record size in bytes.
+// fused_table: if not null, no gradient row is written; row `column` of that table (rows of `width` floats)
+// becomes row - fused_lr * gradient instead (fused_mode 1: then its fractional part).
 stx_status launch_seg_reduce(stx_ctx *, const stx_incidence *, int64_t e_begin, int64_t e_end, const float *src_a,
                              const float *src_b, int64_t split, int ld_src, int width, float *out_rows, int ld_out,
-                             bool packed_src = false);   // packed: src_a = records, ld_src = record bytes
+                             bool packed_src = false, float *fused_table = nullptr, float fused_lr = 0.f,
+                             int fused_mode = 0);
 struct SgdTables {
     float *table_a; int width_a; int mode_a;   // columns [0, n_split)
     int64_t n_split;

@@ -51,6 +51,9 @@ class GpuModel:
     def sgd(self, lr):
         B.stx_sgd_step(self.ctx, self.params, self.inc, self.grads, lr)
 
+    def backward_sgd(self, lr, with_grads=True):
+        B.stx_backward_sgd(self.ctx, self.inc, self.params, self.grads if with_grads else None, lr)
+
     # -- results as numpy -------------------------------------------------------------------------
     def incidence_numpy(self):
         torch.cuda.synchronize()

@@ -51,6 +51,13 @@ def test_mid_full_batch(which):
     diff = np.abs(new.astype(np.float64) - tb.ent)
     assert np.all(diff <= G.REL_TOL * (wl.lr * g.ent_abs + np.abs(tabs["ent"]) * 2.0**-23) + 2.0**-23)
     assert np.array_equal(new[touched == 0], tabs["ent"][touched == 0])
+    # the fused backward + update, as bench.py runs it: same bits as the two separate calls just checked
+    m2 = G.GpuModel(wl, tabs)
+    B.stx_build_incidence(m2.ctx, hd[lo:hi], rd[lo:hi], td[lo:hi], nh, nt, wl.n_neg, m2.inc)
+    m2.forward()
+    m2.backward_sgd(wl.lr, with_grads=False)
+    torch.cuda.synchronize()
+    assert np.array_equal(m2.params.ent.cpu().numpy(), new)
 
 
 def test_toruse_large_full_batch_sampled():
@@ -95,3 +102,12 @@ def test_toruse_large_full_batch_sampled():
     sl = slice(1_000_000, 1_200_000)
     same = m.params.ent[sl].cpu().numpy() == tabs["ent"][sl]
     assert np.all(same[~touched[sl]])
+    # the fused backward + update, as bench.py runs it: the whole 2 GB table has the same bits as after the
+    # two separate calls, whose sampled rows were checked against the oracle above
+    ent_after = m.params.ent
+    m2 = G.GpuModel(wl, tabs)
+    m2.build(bt)
+    m2.forward()
+    m2.backward_sgd(wl.lr, with_grads=False)
+    torch.cuda.synchronize()
+    assert torch.equal(m2.params.ent, ent_after)

@@ -161,6 +161,35 @@ def test_training_step_matches_oracle(model, dist, n_ent, n_rel, b, k, dim, zipf
         diff = np.minimum(diff, 1.0 - diff)                              # distance on the circle
         assert new.min() >= 0.0 and new.max() < 1.0
     assert np.all(diff <= G.REL_TOL * step_scale + 2.0**-23), float(diff.max())
+    # the fused call (update applied inside the transposed product) against the same oracle table, and
+    # against the two separate calls: same sums, same roundings, so the same bits
+    m2 = G.GpuModel(wl, tabs, reduce=reduce)
+    m2.build(bt)
+    m2.forward()
+    m2.backward_sgd(lr, with_grads=False)
+    torch.cuda.synchronize()
+    new2 = m2.params.ent.cpu().numpy()
+    diff2 = np.abs(new2.astype(np.float64) - tb.ent)
+    if model == "toruse":
+        diff2 = np.minimum(diff2, 1.0 - diff2)
+    assert np.all(diff2 <= G.REL_TOL * step_scale + 2.0**-23), float(diff2.max())
+    assert np.array_equal(new2[untouched], tabs["ent"][untouched])
+    assert np.array_equal(new2, new)
+
+
+def test_fused_update_needs_forward_and_invalidates_it():
+    wl, tabs, bt = _problem("transe", "l1", 64, 4, 3000, 2, 128, seed=5, zipf=1.1)
+    m = G.GpuModel(wl, tabs)
+    m.build(bt)
+    with pytest.raises(B.StxError) as ei:
+        m.backward_sgd(0.01, with_grads=False)
+    assert ei.value.status == B.STX_ERR_STATE
+    m.forward()
+    m.backward_sgd(0.01, with_grads=False)
+    with pytest.raises(B.StxError):                                      # tables changed: forward again first
+        m.backward_sgd(0.01, with_grads=False)
+    with pytest.raises(B.StxError):
+        m.backward()
 
 
 def test_backward_is_bitwise_reproducible_and_needs_forward():
