@@ -27,16 +27,24 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 # The kernel whose roofline is reported: the one with the largest share of GPU time in the
 # rocprofv3 kernel trace of the same command (profiles/).
-DOMINANT = {"transe": "k_forward_stacked", "toruse": "k_seg_reduce", "transh": "k_seg_reduce", "transr": "k_transr_project"}
+DOMINANT = {"transe": "k_seg_reduce", "toruse": "k_seg_reduce", "transh": "k_seg_reduce", "transr": "k_transr_project"}
 
 
 # HBM bytes per launch of those kernels, measured: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (separate runs),
 # each scaled by what the same counter reads for the library's plain copy kernel (FETCH_SIZE x2.0, WRITE_SIZE
 # x1.0); the runs and their numbers are in profiles/<workload>_kernel_trace.txt and profiles/copy_calibration.txt.
 # A different kernel (--kernel) or workload has no measured figure here and reports null.
-TRAFFIC_BYTES = {("mid", "k_forward_stacked"): 24.16e6 + 4.48e6,
-                 ("transh", "k_seg_reduce"): 65.31e6 + 4.64e6,
-                 ("toruse", "k_sgd_rows"): 1056.87e6 + 526.34e6}
+# Keys: (workload, kernel, fused step or not).
+TRAFFIC_BYTES = {("mid", "k_forward_stacked", True): 24.16e6 + 4.48e6,
+                 ("mid", "k_forward_stacked", False): 24.16e6 + 4.48e6,
+                 ("mid", "k_seg_reduce", True): 28.08e6 + 8.47e6,
+                 ("transh", "k_seg_reduce", True): 65.32e6 + 4.64e6,
+                 ("transh", "k_seg_reduce", False): 65.32e6 + 4.64e6,
+                 ("transr", "k_transr_project", True): 28.29e6 + 25.01e6,
+                 ("transr", "k_transr_project", False): 28.29e6 + 25.01e6,
+                 ("toruse", "k_seg_reduce", True): 973.02e6 + 532.15e6,
+                 ("toruse", "k_forward_stacked", True): 704.01e6 + 90.19e6,
+                 ("toruse", "k_forward_stacked", False): 704.01e6 + 90.19e6}
 
 
 def parse():
@@ -253,7 +261,7 @@ def main():
     per_launch = kernel_n / args.steps if args.steps else 0
     achieved = (work / (kernel_us * 1e-6)) / (1e9 if unit == "GB/s" else 1e12) if kernel_us > 0 else 0.0
     roofline = {"bound": bound, "kernel": kernel, "achieved": round(achieved, 1), "peak": peak, "unit": unit,
-                "frac": round(achieved / peak, 4), "traffic": TRAFFIC_BYTES.get((wl.name, kernel)), "work_per_launch": int(work),
+                "frac": round(achieved / peak, 4), "traffic": TRAFFIC_BYTES.get((wl.name, kernel, fused)), "work_per_launch": int(work),
                 "avg_launch_us": round(kernel_us, 2), "launches_per_step": round(per_launch, 2)}
     if kernel_note:
         roofline["note"] = kernel_note

@@ -188,6 +188,25 @@ stx_status stx_sgd_step(stx_ctx *ctx, stx_params *p, const stx_incidence *inc, c
  * the gradients.  Needs the stx_forward of the same incidence immediately before it.                  */
 stx_status stx_backward_sgd(stx_ctx *ctx, const stx_incidence *inc, stx_params *p, stx_grads *g, float lr);
 
+/* One training step in one call.  The batch's positives plus what stx_sample_negatives needs to draw its
+ * negatives; neg_h / neg_t ([b*k], device, out) receive the negatives drawn (not needed when k == 0).  */
+typedef struct {
+    const int32_t *h, *r, *t; /* [b], device */
+    int32_t b, k;
+    uint64_t seed, epoch;
+    int64_t m_total, global_offset;
+    int32_t *neg_h, *neg_t;
+} stx_batch;
+
+/* stx_sample_negatives, stx_build_incidence, stx_forward and stx_backward_sgd on one batch, with the same
+ * results bit for bit (negatives, incidence arrays, scores, loss, updated tables), in fewer and fatter
+ * kernel launches: the negatives are drawn while A is written, and where the sizes allow independent
+ * kernels share a launch (the forward pass runs beside the first pass of the sort of A^T, the final sum
+ * of the loss beside a later one).  g as for stx_backward_sgd.  Afterwards inc holds this batch's
+ * incidence; a stored forward is consumed (stx_backward needs a new stx_forward).                      */
+stx_status stx_train_step(stx_ctx *ctx, const stx_batch *batch, stx_incidence *inc, stx_params *p, stx_grads *g,
+                          float lr, float *scores, float *loss);
+
 /* Live timing of one kernel, for benchmarks.  stx_profile_kernel: from now on every launch of the kernel
  * called `kernel_name` (e.g. "k_forward_stacked", "k_seg_reduce", "k_sgd_rows", "k_scatter") on this
  * context is bracketed by a pair of HIP events on the context's stream, for at most max_records

@@ -25,7 +25,7 @@ MODELS = {"transe": STX_TRANSE, "transh": STX_TRANSH, "transr": STX_TRANSR, "tor
 DISTS = {"l1": STX_L1, "l2": STX_L2, "torus_l1": STX_TORUS_L1, "torus_l2": STX_TORUS_L2}
 
 EXPORTS = ["stx_workspace_bytes", "stx_create", "stx_destroy", "stx_sample_negatives", "stx_build_incidence",
-           "stx_check_indices", "stx_spmm", "stx_forward", "stx_backward", "stx_sgd_step", "stx_backward_sgd", "stx_profile_kernel",
+           "stx_check_indices", "stx_spmm", "stx_forward", "stx_backward", "stx_sgd_step", "stx_backward_sgd", "stx_train_step", "stx_profile_kernel",
            "stx_profile_read", "stx_profile_dump", "stx_copy_f32", "stx_status_string"]
 
 
@@ -57,6 +57,12 @@ class stx_grads(C.Structure):
     _fields_ = [("rows", C.c_void_p), ("w_rows", C.c_void_p), ("proj", C.c_void_p)]
 
 
+class stx_batch(C.Structure):
+    _fields_ = [("h", C.c_void_p), ("r", C.c_void_p), ("t", C.c_void_p), ("b", C.c_int32), ("k", C.c_int32),
+                ("seed", C.c_uint64), ("epoch", C.c_uint64), ("m_total", C.c_int64), ("global_offset", C.c_int64),
+                ("neg_h", C.c_void_p), ("neg_t", C.c_void_p)]
+
+
 _lib = None
 
 
@@ -82,6 +88,8 @@ def lib():
                                    C.c_float]
         L.stx_backward_sgd.argtypes = [vp, C.POINTER(stx_incidence), C.POINTER(stx_params), C.POINTER(stx_grads),
                                        C.c_float]
+        L.stx_train_step.argtypes = [vp, C.POINTER(stx_batch), C.POINTER(stx_incidence), C.POINTER(stx_params),
+                                     C.POINTER(stx_grads), C.c_float, vp, vp]
         L.stx_profile_kernel.argtypes = [vp, C.c_char_p, i32]
         L.stx_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32)]
         L.stx_profile_dump.argtypes = [vp, C.c_char_p, C.c_size_t]
@@ -262,6 +270,23 @@ def stx_backward_sgd(ctx: Context, inc: Incidence, p: Params, g, lr: float):
     """g may be None for TransE / TorusE (no gradient rows are written)."""
     gp = C.byref(g.c) if g is not None else None
     _check("stx_backward_sgd", lib().stx_backward_sgd(ctx.handle, C.byref(inc.c), C.byref(p.c), gp, lr))
+
+
+def make_batch(h, r, t, k, seed, epoch, m_total, global_offset, neg_h, neg_t) -> "stx_batch":
+    """Argument block of stx_train_step; the tensors must stay alive while it is in use."""
+    b = h.numel()
+    assert r.numel() == b and t.numel() == b
+    assert k == 0 or (neg_h.numel() >= b * k and neg_t.numel() >= b * k)
+    return stx_batch(_i32dev(h), _i32dev(r), _i32dev(t), b, k, seed, epoch, m_total, global_offset,
+                     _i32dev(neg_h) if k else None, _i32dev(neg_t) if k else None)
+
+
+def stx_train_step(ctx: Context, batch, inc: Incidence, p: Params, g, lr: float, scores, loss):
+    assert scores.is_cuda and scores.dtype == torch.float32 and scores.numel() >= batch.b * (1 + batch.k)
+    assert loss.is_cuda and loss.dtype == torch.float32 and loss.numel() >= 1
+    gp = C.byref(g.c) if g is not None else None
+    _check("stx_train_step", lib().stx_train_step(ctx.handle, C.byref(batch), C.byref(inc.c), C.byref(p.c), gp, lr,
+                                                  scores.data_ptr(), loss.data_ptr()))
 
 
 def stx_profile_kernel(ctx: Context, kernel_name, max_records: int):

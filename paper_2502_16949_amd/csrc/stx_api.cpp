@@ -14,6 +14,8 @@ inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 struct Layout {
     size_t ctrl, keys[2], pay[2], table, super, tile_heads, loss_partials, partials, gbuf[4], total;
     size_t tr_items, tr_dm_items, tr_counts, tr_m16, tr_m16t, tr_xt, tr_gyt;
+    size_t colmap;
+    int map_words;
     int64_t rows_max, nnz_max, cols_max;
     int ld, out_dim, ntiles_max, fwd_blocks_max, n_gbuf;
     int sort_bits, sort_passes, digit_bits;
@@ -76,6 +78,11 @@ Layout make_layout(const stx_config *c)
         if (c->model == STX_TRANSR && i == 2)   // partial dL/dM_r matrices: two per chunk of the dM product
             bytes = (size_t)(L.rows_max / kProjRowsDm + 2) * 2 * (size_t)c->rel_dim * c->dim * 4;
         L.gbuf[i] = i < L.n_gbuf ? take(bytes) : 0;
+    }
+    {
+        const int64_t words = (c->n_ent + c->n_rel + 31) / 32;
+        L.map_words = words <= kMapMaxWords ? (int)words : 0;
+        L.colmap = take((size_t)2 * L.map_words * 4 + 4);
     }
     if (c->model == STX_TRANSR) {
         // every relation segment adds at most one item that is not full
@@ -187,7 +194,12 @@ stx_status stx_create(const stx_config *cfg, void *workspace, size_t workspace_b
     c->prof_tag = nullptr;
     c->prof_cap = c->prof_n = 0;
     c->prof_name[0] = 0;
+    c->map_words = L.map_words;
+    c->map_cur = 0;
+    c->colmap[0] = L.map_words ? (uint32_t *)(base + L.colmap) : nullptr;
+    c->colmap[1] = L.map_words ? c->colmap[0] + L.map_words : nullptr;
     s = launch_clear_ctrl(c);
+    if (s == STX_OK) s = launch_clear_maps(c);
     if (s != STX_OK) { delete c; return s; }
     *out = c;
     return STX_OK;
@@ -467,6 +479,36 @@ stx_status stx_backward_sgd(stx_ctx *ctx, const stx_incidence *inc, stx_params *
     const bool pk = packed_grad(ctx);
     return launch_seg_reduce(ctx, inc, 0, inc->nnz, ctx->gbuf[0], ctx->gbuf[0], inc->nnz, pk ? packed_stride(dim) : dim,
                              dim, nullptr, ctx->ld, pk, p->ent, lr, ctx->cfg.model == STX_TORUSE ? 1 : 0);
+}
+
+stx_status stx_train_step(stx_ctx *ctx, const stx_batch *bt, stx_incidence *inc, stx_params *p, stx_grads *g, float lr,
+                          float *scores, float *loss)
+{
+    if (!ctx || !bt) return STX_ERR_NULL;
+    stx_status s = check_incidence_arrays(inc);
+    if (s != STX_OK) return s;
+    const int32_t b = bt->b, k = bt->k;
+    if (b < 0 || k < 0 || b > ctx->cfg.max_batch || k > ctx->cfg.max_neg) return STX_ERR_BAD_ARG;
+    if (bt->m_total < 0 || bt->global_offset < 0) return STX_ERR_BAD_ARG;
+    if (b > 0 && (!bt->h || !bt->r || !bt->t)) return STX_ERR_NULL;
+    if (b > 0 && k > 0 && (!bt->neg_h || !bt->neg_t)) return STX_ERR_NULL;
+    s = check_params(ctx, p);
+    if (s != STX_OK) return s;
+    if (!scores || !loss) return STX_ERR_NULL;
+    if (!stacked(ctx) && (!g || !g->rows)) return STX_ERR_NULL;
+    if (!(lr == lr)) return STX_ERR_BAD_ARG;
+    inc->b = b;
+    inc->k = k;
+    inc->n_rows = (int64_t)b * (1 + k);
+    inc->nnz = 3 * inc->n_rows;
+    ctx->fwd_inc = nullptr;
+    SampleArgs sa{bt->neg_h, bt->neg_t, bt->seed,
+                  (bt->epoch * (uint64_t)bt->m_total + (uint64_t)bt->global_offset) * (uint64_t)k};
+    s = launch_build(ctx, bt->h, bt->r, bt->t, nullptr, nullptr, b, k, inc, &sa);
+    if (s != STX_OK) return s;
+    s = stx_forward(ctx, inc, p, scores, loss);
+    if (s != STX_OK) return s;
+    return stx_backward_sgd(ctx, inc, p, g, lr);
 }
 
 stx_status stx_copy_f32(stx_ctx *ctx, float *dst, const float *src, int64_t n)

@@ -50,6 +50,11 @@ __global__ void k_clear_ctrl(int32_t *ctrl)
     if (threadIdx.x < CTRL_WORDS) ctrl[threadIdx.x] = 0;
 }
 
+__global__ __launch_bounds__(kThreads) void k_clear_words(uint32_t *p, int n)
+{
+    for (int i = (int)blockIdx.x * kThreads + threadIdx.x; i < n; i += (int)gridDim.x * kThreads) p[i] = 0u;
+}
+
 // Empty batch: A has no rows and A^T no segments.
 __global__ void k_empty_incidence(int32_t *rowptr, int32_t *seg_ptr, int32_t *n_touched)
 {
@@ -59,20 +64,37 @@ __global__ void k_empty_incidence(int32_t *rowptr, int32_t *seg_ptr, int32_t *n_
 struct BatchPtrs {
     const int32_t *h, *r, *t, *nh, *nt;
     int32_t b, k;
+    // SAMPLE: the negatives are drawn here (as k_sample draws them) and also written to nh_out / nt_out
+    int32_t *nh_out, *nt_out;
+    uint64_t seed, base_ctr;
+};
+
+// Presence bitmap of the batch's columns (one bit per column of [E;R]), kept when the table has few
+// enough columns for a workgroup to scan the whole map: the segment of a column is then its rank among
+// the set bits, and k_seg_write needs no count of segment heads per tile from a kernel before it.
+// Two maps alternate: a build sets bits in one and clears the other, which the build before it used.
+struct ColMap {
+    uint32_t *cur, *other;
+    int words;
 };
 
 // One thread per entry e = 3*row + slot of A.  Writes the CSR arrays and the sort keys (= column ids),
 // and the histogram of the first digit for this tile.
-template <int ITEMS>
+template <int ITEMS, bool MAP, bool SAMPLE>
 __global__ __launch_bounds__(kThreads) void k_emit(BatchPtrs bp, int32_t n_ent, int32_t n_rel, int32_t nnz,
                                                    int32_t *__restrict__ rowptr, int32_t *__restrict__ colidx,
                                                    float *__restrict__ vals, int32_t *__restrict__ keys,
                                                    int radix, int ntiles, int32_t *__restrict__ table,
-                                                   int32_t *__restrict__ ctrl)
+                                                   int32_t *__restrict__ ctrl, ColMap map)
 {
     __shared__ int32_t s_hist[256];
+    __shared__ uint32_t s_map[MAP ? kMapMaxWords : 1];
     const int tid = threadIdx.x;
     s_hist[tid] = 0;
+    if (MAP) {
+        for (int w = tid; w < map.words; w += kThreads) s_map[w] = 0u;
+        for (int w = (int)blockIdx.x * kThreads + tid; w < map.words; w += (int)gridDim.x * kThreads) map.other[w] = 0u;
+    }
     __syncthreads();
     const int32_t base = blockIdx.x * (kThreads * ITEMS);
 #pragma unroll
@@ -83,6 +105,17 @@ __global__ __launch_bounds__(kThreads) void k_emit(BatchPtrs bp, int32_t n_ent, 
             int32_t idx;
             if (row < bp.b) {
                 idx = slot == 0 ? bp.h[row] : (slot == 1 ? bp.r[row] : bp.t[row]);
+            } else if (SAMPLE) {
+                const int32_t j = row - bp.b, i = j / bp.k;
+                if (slot == 1) {
+                    idx = bp.r[i];
+                } else {   // the three threads of a row draw the same number; slots 0 and 2 store their side
+                    const uint64_t u = splitmix64_at(bp.seed, bp.base_ctr + (uint64_t)j);
+                    const int32_t ent = (int32_t)(((u & 0xFFFFFFFFull) * (uint64_t)n_ent) >> 32);
+                    const bool head = (u >> 63) != 0;
+                    if (slot == 0) { idx = head ? ent : bp.h[i]; bp.nh_out[j] = idx; }
+                    else           { idx = head ? bp.t[i] : ent; bp.nt_out[j] = idx; }
+                }
             } else {
                 int32_t j = row - bp.b;
                 idx = slot == 0 ? bp.nh[j] : (slot == 1 ? bp.r[j / bp.k] : bp.nt[j]);
@@ -99,10 +132,17 @@ __global__ __launch_bounds__(kThreads) void k_emit(BatchPtrs bp, int32_t n_ent, 
             if (e == nnz - 1) rowptr[row + 1] = nnz;
             keys[e] = col;
             atomicAdd(&s_hist[col & (radix - 1)], 1);
+            if (MAP) atomicOr(&s_map[col >> 5], 1u << (col & 31));
         }
     }
     __syncthreads();
     if (tid < radix) table[blockIdx.x * radix + tid] = s_hist[tid];
+    if (MAP) {
+        for (int w = tid; w < map.words; w += kThreads) {
+            const uint32_t v = s_map[w];
+            if (v) atomicOr(&map.cur[w], v);
+        }
+    }
 }
 
 // Tile histograms of the digit at `shift` for the later passes.
@@ -290,6 +330,9 @@ __global__ __launch_bounds__(kThreads) void k_seg_count(const int32_t *__restric
 
 // Per sorted entry: its segment, row, sign and packed form; per segment: its column and first entry.
 // Thread t of a tile owns the 8 consecutive entries base + 8t .. base + 8t + 7.
+// MAP: the segment of an entry is the rank of its column in the presence bitmap (every workgroup scans
+// the map itself); otherwise it is counted from the heads of the earlier tiles (k_seg_count).
+template <bool MAP>
 __global__ __launch_bounds__(kThreads) void k_seg_write(const int32_t *__restrict__ keys,
                                                         const int32_t *__restrict__ pay, int32_t nnz,
                                                         const int32_t *__restrict__ tile_heads,
@@ -297,13 +340,34 @@ __global__ __launch_bounds__(kThreads) void k_seg_write(const int32_t *__restric
                                                         int32_t *__restrict__ touched_cols,
                                                         int32_t *__restrict__ seg_ptr, int32_t *__restrict__ row_idx,
                                                         int8_t *__restrict__ sign, int32_t *__restrict__ seg_id,
-                                                        int32_t *__restrict__ packed)
+                                                        int32_t *__restrict__ packed, ColMap map)
 {
     __shared__ int32_t s_base;
+    __shared__ uint32_t s_word[MAP ? kMapMaxWords : 1];
+    __shared__ int32_t s_pref[MAP ? kMapMaxWords : 1];
     const int tid = threadIdx.x;
     if (tid == 0) s_base = 0;
     __syncthreads();
-    {   // segments that start in earlier tiles
+    int32_t map_total = 0;
+    if (MAP) {   // thread t owns words [t*wpt, (t+1)*wpt): set bits below each word
+        constexpr int WPT = kMapMaxWords / kThreads;
+        const int wpt = (map.words + kThreads - 1) / kThreads;
+        uint32_t wv[WPT];
+        int32_t mine = 0;
+#pragma unroll
+        for (int q = 0; q < WPT; ++q) {
+            const int w = tid * wpt + q;
+            wv[q] = (q < wpt && w < map.words) ? map.cur[w] : 0u;
+            mine += __popc(wv[q]);
+        }
+        int32_t run = block_exclusive_scan(mine, &map_total);
+#pragma unroll
+        for (int q = 0; q < WPT; ++q) {
+            const int w = tid * wpt + q;
+            if (q < wpt && w < map.words) { s_word[w] = wv[q]; s_pref[w] = run; run += __popc(wv[q]); }
+        }
+        __syncthreads();
+    } else {   // segments that start in earlier tiles
         int32_t a = 0;
         for (int t = tid; t < (int)blockIdx.x; t += kThreads) a += tile_heads[t];
         if (a) atomicAdd(&s_base, a);
@@ -322,12 +386,22 @@ __global__ __launch_bounds__(kThreads) void k_seg_write(const int32_t *__restric
 #pragma unroll
     for (int i = 0; i < kSegWItems; ++i)
         if (e0 + i < nnz && kk[i + 1] != kk[i]) ++cnt;
-    int32_t tile_total;
-    const int32_t before = block_exclusive_scan(cnt, &tile_total);   // its barriers also publish s_base
-    int32_t seg = s_base + before - 1;                               // segment of the entry before e0
-    if (blockIdx.x == gridDim.x - 1 && tid == 0) {
-        n_touched[0] = s_base + tile_total;
-        seg_ptr[s_base + tile_total] = nnz;
+    int32_t seg;
+    if (MAP) {
+        const int32_t c0 = kk[0];                                        // column of the entry before e0 (-1: none)
+        seg = c0 < 0 ? -1 : s_pref[c0 >> 5] + __popc(s_word[c0 >> 5] & ((1u << (c0 & 31)) - 1u));
+        if (blockIdx.x == gridDim.x - 1 && tid == 0) {
+            n_touched[0] = map_total;
+            seg_ptr[map_total] = nnz;
+        }
+    } else {
+        int32_t tile_total;
+        const int32_t before = block_exclusive_scan(cnt, &tile_total);   // its barriers also publish s_base
+        seg = s_base + before - 1;                                       // segment of the entry before e0
+        if (blockIdx.x == gridDim.x - 1 && tid == 0) {
+            n_touched[0] = s_base + tile_total;
+            seg_ptr[s_base + tile_total] = nnz;
+        }
     }
     int32_t o_seg[kSegWItems], o_row[kSegWItems], o_pk[kSegWItems];
     int8_t o_sign[kSegWItems];
@@ -387,6 +461,15 @@ stx_status launch_clear_ctrl(stx_ctx *c)
     return hip_ok(hipGetLastError());
 }
 
+stx_status launch_clear_maps(stx_ctx *c)
+{
+    if (c->map_words == 0) return STX_OK;
+    // the two maps are adjacent in the workspace
+    hipLaunchKernelGGL(k_clear_words, dim3(8), dim3(kThreads), 0, c->stream, c->colmap[0], 2 * c->map_words);
+    c->map_cur = 0;
+    return hip_ok(hipGetLastError());
+}
+
 stx_status launch_sample(stx_ctx *c, const int32_t *h, const int32_t *t, int64_t m, int32_t k, uint64_t seed,
                          uint64_t base_ctr, int32_t *nh, int32_t *nt)
 {
@@ -400,7 +483,7 @@ stx_status launch_sample(stx_ctx *c, const int32_t *h, const int32_t *t, int64_t
 }
 
 stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const int32_t *t, const int32_t *nh,
-                        const int32_t *nt, int32_t b, int32_t k, stx_incidence *inc)
+                        const int32_t *nt, int32_t b, int32_t k, stx_incidence *inc, const SampleArgs *sample)
 {
     hipStream_t s = c->stream;
     c->sorted_inc = nullptr;
@@ -416,17 +499,26 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
     const int items = nnz <= (1 << 19) ? kSortItems : 2 * kSortItems;
     const int ntiles = (nnz + kThreads * items - 1) / (kThreads * items);
     const int n_ent = (int)c->cfg.n_ent, n_rel = (int)c->cfg.n_rel;
-    BatchPtrs bp{h, r, t, nh, nt, b, k > 0 ? k : 1};
+    BatchPtrs bp{h, r, t, nh, nt, b, k > 0 ? k : 1, nullptr, nullptr, 0, 0};
+    if (sample) { bp.nh_out = sample->neg_h; bp.nt_out = sample->neg_t; bp.seed = sample->seed; bp.base_ctr = sample->base_ctr; }
+    const bool use_map = c->map_words > 0;
+    ColMap map{nullptr, nullptr, 0};
+    if (use_map) {
+        map = ColMap{c->colmap[c->map_cur], c->colmap[c->map_cur ^ 1], c->map_words};
+        c->map_cur ^= 1;
+    }
 
     int bits0 = c->sort_bits < c->digit_bits ? c->sort_bits : c->digit_bits;
     {
     ProfScope prof(c, "k_emit");
-    if (items == kSortItems)
-        hipLaunchKernelGGL(k_emit<kSortItems>, dim3(ntiles), dim3(kThreads), 0, s, bp, n_ent, n_rel, nnz, inc->a_rowptr,
-                           inc->a_colidx, inc->a_vals, c->keys[0], 1 << bits0, ntiles, c->table, c->ctrl);
-    else
-        hipLaunchKernelGGL(k_emit<2 * kSortItems>, dim3(ntiles), dim3(kThreads), 0, s, bp, n_ent, n_rel, nnz,
-                           inc->a_rowptr, inc->a_colidx, inc->a_vals, c->keys[0], 1 << bits0, ntiles, c->table, c->ctrl);
+#define STX_EMIT(I, M, S)                                                                                       \
+    hipLaunchKernelGGL((k_emit<I, M, S>), dim3(ntiles), dim3(kThreads), 0, s, bp, n_ent, n_rel, nnz, inc->a_rowptr, \
+                       inc->a_colidx, inc->a_vals, c->keys[0], 1 << bits0, ntiles, c->table, c->ctrl, map)
+#define STX_EMIT2(I, M) do { if (sample) STX_EMIT(I, M, true); else STX_EMIT(I, M, false); } while (0)
+    if (items == kSortItems) { if (use_map) STX_EMIT2(kSortItems, true); else STX_EMIT2(kSortItems, false); }
+    else                     { if (use_map) STX_EMIT2(2 * kSortItems, true); else STX_EMIT2(2 * kSortItems, false); }
+#undef STX_EMIT2
+#undef STX_EMIT
     }
     const bool two_level = ntiles > kSelfScanTiles;
     const int ngroups = (ntiles + kSuperTile - 1) / kSuperTile;
@@ -462,14 +554,19 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
         cur ^= 1;
     }
     const int nseg = (nnz + kSegWTile - 1) / kSegWTile;
-    {
+    if (!use_map) {
         ProfScope prof(c, "k_seg_count");
         hipLaunchKernelGGL(k_seg_count, dim3(nseg), dim3(kThreads), 0, s, c->keys[cur], nnz, c->tile_heads);
     }
     ProfScope prof(c, "k_seg_write");
-    hipLaunchKernelGGL(k_seg_write, dim3(nseg), dim3(kThreads), 0, s, c->keys[cur], c->pay[cur], nnz,
-                       c->tile_heads, inc->n_touched, inc->at_touched_cols, inc->at_seg_ptr, inc->at_row_idx,
-                       inc->at_sign, inc->at_seg_id, inc->at_packed);
+    if (use_map)
+        hipLaunchKernelGGL(k_seg_write<true>, dim3(nseg), dim3(kThreads), 0, s, c->keys[cur], c->pay[cur], nnz,
+                           c->tile_heads, inc->n_touched, inc->at_touched_cols, inc->at_seg_ptr, inc->at_row_idx,
+                           inc->at_sign, inc->at_seg_id, inc->at_packed, map);
+    else
+        hipLaunchKernelGGL(k_seg_write<false>, dim3(nseg), dim3(kThreads), 0, s, c->keys[cur], c->pay[cur], nnz,
+                           c->tile_heads, inc->n_touched, inc->at_touched_cols, inc->at_seg_ptr, inc->at_row_idx,
+                           inc->at_sign, inc->at_seg_id, inc->at_packed, map);
     c->sorted_inc = inc;
     c->sorted_keys = c->keys[cur];
     return hip_ok(hipGetLastError());

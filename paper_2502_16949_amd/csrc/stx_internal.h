@@ -16,6 +16,7 @@ constexpr int kSegWTile = kThreads * kSegWItems;
 constexpr int kSegTileMin = 64;        // fewest sorted entries a workgroup of the transposed product may own
 constexpr int kSuperTile = 32;         // sort tiles per group when the histogram table is scanned in two levels
 constexpr int kSelfScanTiles = 256;   // up to this many sort tiles, scatter workgroups scan the histograms themselves
+constexpr int kMapMaxWords = 2048;     // presence bitmap of the columns: kept when n_ent + n_rel <= 32 * this
 constexpr int kMaxDim = 1024;
 constexpr int kMaxProjDim = 256;        // TransR: dim and rel_dim are multiples of 32 up to this
 constexpr int kProjRows = 64;           // TransR: entries of one relation per work item of the two row products
@@ -56,6 +57,8 @@ struct stx_ctx {
     float *loss_partials;          // [fwd_blocks_max]
     float *partials;               // [(nnz_max/kSegTileMin + 2) * 2 * ld]
     float *gbuf[4];                // per-row buffers, rows_max x ld each (how many depends on the model)
+    uint32_t *colmap[2];           // presence bitmaps of the columns (adjacent), or null when the table is too wide
+    int map_words, map_cur;        // words per map (0: not kept); which map the next build fills
     // TransR only: work items, bfloat16 operand copies of the projection matrices, transposed operand tiles
     int32_t *tr_items, *tr_dm_items, *tr_counts;
     uint16_t *tr_m16, *tr_m16t, *tr_xt, *tr_gyt;
@@ -76,9 +79,15 @@ namespace stx {
 // stx_build.hip
 stx_status launch_sample(stx_ctx *, const int32_t *h, const int32_t *t, int64_t m, int32_t k, uint64_t seed,
                          uint64_t base_ctr, int32_t *nh, int32_t *nt);
+struct SampleArgs {            // negatives drawn inside the build (same numbers as launch_sample) and stored here
+    int32_t *neg_h, *neg_t;
+    uint64_t seed, base_ctr;
+};
 stx_status launch_build(stx_ctx *, const int32_t *h, const int32_t *r, const int32_t *t, const int32_t *nh,
-                        const int32_t *nt, int32_t b, int32_t k, stx_incidence *inc);
+                        const int32_t *nt, int32_t b, int32_t k, stx_incidence *inc,
+                        const SampleArgs *sample = nullptr);
 stx_status launch_clear_ctrl(stx_ctx *);
+stx_status launch_clear_maps(stx_ctx *);
 // stx_forward.hip
 stx_status launch_spmm(stx_ctx *, const stx_incidence *, const stx_params *, float *c_out);
 stx_status launch_forward_stacked(stx_ctx *, const stx_incidence *, const stx_params *, float *scores, float *loss);
