@@ -55,8 +55,9 @@ def parse():
     ap.add_argument("--config", default="mid", help="workload: tiny | mid | transh | transr | toruse")
     ap.add_argument("--kernel", default=None, help="kernel to time for the roofline entry (default: the dominant one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--unfused", action="store_true",
-                    help="call stx_backward and stx_sgd_step separately instead of stx_backward_sgd")
+    ap.add_argument("--api", default="step", choices=["step", "fused", "separate"],
+                    help="step: one stx_train_step call per step (default); fused: sample, build, forward, "
+                         "stx_backward_sgd; separate: sample, build, forward, backward, sgd_step")
     ap.add_argument("--all-kernels", action="store_true",
                     help="extra untimed pass that brackets every kernel with events and adds 'kernels_us' to the output")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -181,7 +182,8 @@ def main():
 
     # Argument lists are marshalled once per batch; the timed loop makes only the C calls: sample, build,
     # forward and the fused backward + update (stx_backward_sgd), or backward and update separately (--unfused).
-    fused = not args.unfused
+    fused = args.api != "separate"
+    one_call = args.api == "step"
     L = B.lib()
     import ctypes as C
     byref = C.byref
@@ -195,11 +197,18 @@ def main():
                 (ctx.handle, byref(inc.c), byref(params.c), byref(grads.c)),
                 (ctx.handle, byref(params.c), byref(inc.c), byref(grads.c), wl.lr),
                 (ctx.handle, byref(inc.c), byref(params.c), byref(grads.c), wl.lr),
+                (ctx.handle, byref(B.make_batch(hd[lo:hi], rd[lo:hi], td[lo:hi], wl.n_neg, seed, 0, wl.n_triplets, lo,
+                                                nh, nt)),
+                 byref(inc.c), byref(params.c), byref(grads.c), wl.lr, scores.data_ptr(), loss.data_ptr()),
                 b * (1 + wl.n_neg))
     calls = [marshal(lo, hi) for lo, hi in slices]
 
     def step(i, ev=None):
-        a_s, a_b, a_f, a_g, a_u, a_bu, rows = calls[i % len(calls)]
+        a_s, a_b, a_f, a_g, a_u, a_bu, a_step, rows = calls[i % len(calls)]
+        if one_call and not ev:
+            if L.stx_train_step(*a_step):
+                raise RuntimeError(f"stx_train_step failed in step {i}")
+            return rows
         if ev: ev[0].record()
         st = L.stx_sample_negatives(*a_s)
         if ev: ev[1].record()
@@ -283,8 +292,11 @@ def main():
                                f"batch {wl.batch}, {wl.n_neg} negative(s) per positive, margin {wl.margin}, "
                                f"SGD lr {wl.lr}",
                    "rows_per_full_batch": wl.rows_per_batch, "batches_per_epoch": len(slices),
-                   "step": "sample negatives + build incidence + forward + " +
-                           ("backward with fused sgd (stx_backward_sgd)" if fused else "backward + sgd")},
+                   "step": ("stx_train_step: sample negatives + build incidence + forward + backward with fused sgd, one call"
+                            if one_call else "sample negatives + build incidence + forward + " +
+                            ("backward with fused sgd (stx_backward_sgd)" if fused else "backward + sgd")),
+                   "api": args.api},
+        "phase_us_note": "an extra, untimed pass through the separate calls" if one_call else "",
         "phase_us": {k: round(float(v), 2) for k, v in
                      zip(("sample", "build", "forward", "backward_sgd" if fused else "backward", "sgd"), phase_us)},
         "host_enqueue_us_per_step": round(t_enq / args.steps * 1e6, 2),

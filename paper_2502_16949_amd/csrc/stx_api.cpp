@@ -504,9 +504,16 @@ stx_status stx_train_step(stx_ctx *ctx, const stx_batch *bt, stx_incidence *inc,
     ctx->fwd_inc = nullptr;
     SampleArgs sa{bt->neg_h, bt->neg_t, bt->seed,
                   (bt->epoch * (uint64_t)bt->m_total + (uint64_t)bt->global_offset) * (uint64_t)k};
-    s = launch_build(ctx, bt->h, bt->r, bt->t, nullptr, nullptr, b, k, inc, &sa);
+    StepFusion fusion{p, scores, loss, false, false, 0, 1.0f};
+    s = launch_build(ctx, bt->h, bt->r, bt->t, nullptr, nullptr, b, k, inc, &sa, &fusion);
     if (s != STX_OK) return s;
-    s = stx_forward(ctx, inc, p, scores, loss);
+    if (!fusion.forward_done) {
+        s = stx_forward(ctx, inc, p, scores, loss);
+    } else {   // the forward pass shared a launch with the sort; the sum of the loss may still be missing
+        if (!fusion.finish_done) s = launch_finish_loss(ctx, fusion.n_partials, fusion.scale, loss);
+        ctx->fwd_inc = inc;
+        ctx->fwd_rows = inc->n_rows;
+    }
     if (s != STX_OK) return s;
     return stx_backward_sgd(ctx, inc, p, g, lr);
 }

@@ -15,8 +15,7 @@
 // The tile histograms (tile-major table[tile][digit]) must become global offsets before a scatter.
 // With few tiles every scatter workgroup derives its own offsets from the raw table (a few coalesced
 // reads per thread); with many tiles a small k_super_sums first adds the histograms up in groups of tiles.
-#include "stx_device.h"
-#include "stx_internal.h"
+#include "stx_sort_body.h"
 
 namespace stx {
 
@@ -145,23 +144,11 @@ __global__ __launch_bounds__(kThreads) void k_emit(BatchPtrs bp, int32_t n_ent, 
     }
 }
 
-// Tile histograms of the digit at `shift` for the later passes.
 template <int ITEMS>
 __global__ __launch_bounds__(kThreads) void k_hist(const int32_t *__restrict__ keys, int32_t nnz, int shift,
                                                    int radix, int32_t *__restrict__ table)
 {
-    __shared__ int32_t s_hist[256];
-    const int tid = threadIdx.x;
-    s_hist[tid] = 0;
-    __syncthreads();
-    const int32_t base = blockIdx.x * (kThreads * ITEMS);
-#pragma unroll
-    for (int it = 0; it < ITEMS; ++it) {
-        int32_t e = base + it * kThreads + tid;
-        if (e < nnz) atomicAdd(&s_hist[(keys[e] >> shift) & (radix - 1)], 1);
-    }
-    __syncthreads();
-    if (tid < radix) table[blockIdx.x * radix + tid] = s_hist[tid];
+    hist_body<ITEMS>((int)blockIdx.x, keys, nnz, shift, radix, table);
 }
 
 // With many tiles the scatter workgroups cannot each read the whole table.  This kernel adds the tile
@@ -178,134 +165,10 @@ __global__ __launch_bounds__(kThreads) void k_super_sums(const int32_t *__restri
     super[blockIdx.x * radix + tid] = a;
 }
 
-// Stable scatter of one tile by the digit at `shift`.  Element order inside a tile is
-// (wavefront, iteration, lane): wavefront w owns the contiguous span [w*512, (w+1)*512) of the tile.
-// The rank of a key among equal digits is
-//   (count in earlier wavefronts) + (count in earlier iterations of this wavefront) + (equal lanes below),
-// the last term from a ballot match over the digit's bits.  The base offset of a (digit, tile) is the
-// number of keys with a smaller digit anywhere plus those with the same digit in earlier tiles: read
-// derived here from the raw tile counts: directly when there are few tiles (TWO_LEVEL false), through
-// the group sums of k_super_sums otherwise.
 template <bool FIRST, bool TWO_LEVEL, int ITEMS>
-__global__ __launch_bounds__(kThreads) void k_scatter(const int32_t *__restrict__ keys_in,
-                                                      const int32_t *__restrict__ pay_in,
-                                                      int32_t *__restrict__ keys_out,
-                                                      int32_t *__restrict__ pay_out, int32_t nnz, int shift,
-                                                      int bits, int ntiles, const int32_t *__restrict__ table,
-                                                      const int32_t *__restrict__ super)
+__global__ __launch_bounds__(kThreads) void k_scatter(ScatterArgs a)
 {
-    __shared__ int32_t s_goff[256];
-    __shared__ int32_t s_hist[4][256];
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int radix = 1 << bits;
-    for (int i = tid; i < 4 * 256; i += kThreads) (&s_hist[0][0])[i] = 0;
-    if (TWO_LEVEL) {
-        int32_t below = 0, total = 0;
-        if (tid < radix) {
-            const int me = (int)blockIdx.x, g_me = me / kSuperTile, ngroups = (ntiles + kSuperTile - 1) / kSuperTile;
-            int g = 0;
-            for (; g + 3 < ngroups; g += 4) {
-                int32_t v0 = super[g * radix + tid], v1 = super[(g + 1) * radix + tid];
-                int32_t v2 = super[(g + 2) * radix + tid], v3 = super[(g + 3) * radix + tid];
-                total += (v0 + v1) + (v2 + v3);
-                below += (g < g_me ? v0 : 0) + (g + 1 < g_me ? v1 : 0) + (g + 2 < g_me ? v2 : 0) + (g + 3 < g_me ? v3 : 0);
-            }
-            for (; g < ngroups; ++g) {
-                int32_t v = super[g * radix + tid];
-                total += v;
-                below += g < g_me ? v : 0;
-            }
-#pragma unroll 8
-            for (int t = g_me * kSuperTile; t < me; ++t) below += table[t * radix + tid];
-        }
-        int32_t base = block_exclusive_scan(total, nullptr);
-        s_goff[tid] = base + below;
-    } else {
-        // All 256 threads share the table: a thread owns four neighbouring digits (one 16-byte load per
-        // tile row) and every `parts`-th tile; up to 16 loads are in flight per thread.
-        __shared__ int32_t s_tot[1024], s_bel[1024];
-        const int me = (int)blockIdx.x;
-        int32_t below = 0, total = 0;
-        if (radix >= 4) {
-            const int r4 = radix >> 2, parts = kThreads / r4, d4 = tid % r4, q = tid / r4;
-            int4 tot = make_int4(0, 0, 0, 0), bel = make_int4(0, 0, 0, 0);
-            for (int t0 = q; t0 < ntiles; t0 += 16 * parts) {
-                int4 v[16];
-#pragma unroll
-                for (int u = 0; u < 16; ++u) {
-                    const int t = t0 + u * parts;
-                    v[u] = t < ntiles ? *reinterpret_cast<const int4 *>(table + t * radix + 4 * d4)
-                                      : make_int4(0, 0, 0, 0);
-                }
-#pragma unroll
-                for (int u = 0; u < 16; ++u) {
-                    const int t = t0 + u * parts;
-                    tot.x += v[u].x; tot.y += v[u].y; tot.z += v[u].z; tot.w += v[u].w;
-                    if (t < me) { bel.x += v[u].x; bel.y += v[u].y; bel.z += v[u].z; bel.w += v[u].w; }
-                }
-            }
-            *reinterpret_cast<int4 *>(&s_tot[q * radix + 4 * d4]) = tot;
-            *reinterpret_cast<int4 *>(&s_bel[q * radix + 4 * d4]) = bel;
-            __syncthreads();
-            if (tid < radix)
-                for (int qq = 0; qq < parts; ++qq) {
-                    total += s_tot[qq * radix + tid];
-                    below += s_bel[qq * radix + tid];
-                }
-        } else if (tid < radix) {   // two bins only
-            for (int t = 0; t < ntiles; ++t) {
-                const int32_t v = table[t * radix + tid];
-                total += v;
-                below += t < me ? v : 0;
-            }
-        }
-        int32_t base = block_exclusive_scan(total, nullptr);
-        s_goff[tid] = base + below;
-    }
-    __syncthreads();
-
-    int32_t key[ITEMS], pay[ITEMS], rank[ITEMS];
-    const int32_t wave_base = blockIdx.x * (kThreads * ITEMS) + w * (64 * ITEMS);
-    const uint64_t below = (1ull << lane) - 1ull;
-#pragma unroll
-    for (int it = 0; it < ITEMS; ++it) {
-        int32_t e = wave_base + it * 64 + lane;
-        bool valid = e < nnz;
-        key[it] = valid ? keys_in[e] : 0;
-        pay[it] = FIRST ? e : (valid ? pay_in[e] : 0);
-        int dgt = (key[it] >> shift) & (radix - 1);
-        uint64_t m = __ballot(valid);
-        for (int bit = 0; bit < bits; ++bit) {
-            bool one = (dgt >> bit) & 1;
-            uint64_t bm = __ballot(one);
-            m &= one ? bm : ~bm;
-        }
-        int32_t prior = s_hist[w][dgt];
-        rank[it] = prior + __popcll(m & below);
-        bool leader = valid && ((m >> lane) >> 1) == 0;   // highest lane of its digit class
-        if (leader) s_hist[w][dgt] = prior + __popcll(m);
-    }
-    __syncthreads();
-    if (tid < radix) {
-        int32_t a = 0;
-#pragma unroll
-        for (int w2 = 0; w2 < 4; ++w2) {
-            int32_t c = s_hist[w2][tid];
-            s_hist[w2][tid] = a;
-            a += c;
-        }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int it = 0; it < ITEMS; ++it) {
-        int32_t e = wave_base + it * 64 + lane;
-        if (e < nnz) {
-            int dgt = (key[it] >> shift) & (radix - 1);
-            int32_t pos = s_goff[dgt] + s_hist[w][dgt] + rank[it];
-            keys_out[pos] = key[it];
-            pay_out[pos] = pay[it];
-        }
-    }
+    scatter_body<FIRST, TWO_LEVEL, ITEMS>((int)blockIdx.x, a);
 }
 
 // Number of segment heads (first entry of a column's run) in each tile of the sorted keys.
@@ -483,7 +346,8 @@ stx_status launch_sample(stx_ctx *c, const int32_t *h, const int32_t *t, int64_t
 }
 
 stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const int32_t *t, const int32_t *nh,
-                        const int32_t *nt, int32_t b, int32_t k, stx_incidence *inc, const SampleArgs *sample)
+                        const int32_t *nt, int32_t b, int32_t k, stx_incidence *inc, const SampleArgs *sample,
+                        StepFusion *fusion)
 {
     hipStream_t s = c->stream;
     c->sorted_inc = nullptr;
@@ -526,7 +390,9 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
     for (int p = 0; p < c->sort_passes; ++p) {
         int shift = p * c->digit_bits;
         int bits = c->sort_bits - shift < c->digit_bits ? c->sort_bits - shift : c->digit_bits;
-        if (p > 0) {
+        if (p > 0 && fusion && fusion->forward_done && !fusion->finish_done && items == kSortItems) {
+            launch_hist_finish(c, fusion, c->keys[cur], nnz, shift, 1 << bits, ntiles);
+        } else if (p > 0) {
             ProfScope prof(c, "k_hist");
             if (items == kSortItems)
                 hipLaunchKernelGGL(k_hist<kSortItems>, dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], nnz, shift,
@@ -540,11 +406,14 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
             hipLaunchKernelGGL(k_super_sums, dim3(ngroups), dim3(kThreads), 0, s, c->table, 1 << bits, ntiles,
                                c->super);
         }
+        const ScatterArgs sa{c->keys[cur], c->pay[cur], c->keys[cur ^ 1], c->pay[cur ^ 1], nnz, shift, bits, ntiles,
+                             c->table, c->super};
 #define STX_SCATTER(F, S, I)                                                                                  \
-    hipLaunchKernelGGL((k_scatter<F, S, I>), dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], c->pay[cur],    \
-                       c->keys[cur ^ 1], c->pay[cur ^ 1], nnz, shift, bits, ntiles, c->table, c->super)
+    hipLaunchKernelGGL((k_scatter<F, S, I>), dim3(ntiles), dim3(kThreads), 0, s, sa)
 #define STX_SCATTER2(F, S) do { if (items == kSortItems) STX_SCATTER(F, S, kSortItems); else STX_SCATTER(F, S, 2 * kSortItems); } while (0)
-        {
+        if (p == 0 && fusion && !two_level && items == kSortItems && launch_fwd_scatter(c, inc, fusion, sa)) {
+            // the forward pass ran in the same launch
+        } else {
             ProfScope prof(c, "k_scatter");
             if (p == 0) { if (two_level) STX_SCATTER2(true, true); else STX_SCATTER2(true, false); }
             else        { if (two_level) STX_SCATTER2(false, true); else STX_SCATTER2(false, false); }

@@ -8,7 +8,7 @@
 // The fused forward kernel gives one group a positive row and its k negatives: it computes the
 // distances (Sec. 4.3, 4.6), the margin-ranking hinge (Sec. 5.3) and writes dL/dx of each of those
 // rows straight away, so x itself never goes to memory.
-#include "stx_rowops.h"
+#include "stx_forward_body.h"
 
 namespace stx {
 
@@ -30,147 +30,16 @@ __global__ __launch_bounds__(kThreads) void k_spmm(const int32_t *__restrict__ c
     }
 }
 
-// Packed dL/dy row of an L1-kind distance: record `row` of gs = coefficient (fp32), then the sign bytes.
-template <int LPR, int ITERS, int DIST>
-__device__ inline void write_grad_row_packed(uint8_t *__restrict__ gs, int gstride, int64_t row, int d4, int lig,
-                                             const RowVec<ITERS> &x, float coef)
-{
-    uint8_t *rec = gs + row * gstride;
-#pragma unroll
-    for (int it = 0; it < ITERS; ++it) {
-        int j = lig + it * LPR;
-        if (j < d4) rec[4 + j] = (uint8_t)sign_bits<DIST>(x.v[it]);
-    }
-    if (lig == 0) *reinterpret_cast<float *>(rec) = coef;
-}
-
-template <int LPR, int ITERS, int DIST>
-__device__ inline void write_grad_row(float *__restrict__ g, int d4, int lig, const RowVec<ITERS> &x, float coef,
-                                      float dist)
-{
-    const float cs = coef_scale<DIST>(coef, dist);
-#pragma unroll
-    for (int it = 0; it < ITERS; ++it) {
-        int j = lig + it * LPR;
-        if (j < d4)
-            st4(g + 4 * j, make_float4(dterm<DIST>(x.v[it].x, cs), dterm<DIST>(x.v[it].y, cs),
-                                       dterm<DIST>(x.v[it].z, cs), dterm<DIST>(x.v[it].w, cs)));
-    }
-}
-
-// Sum of the per-workgroup loss partials in a fixed order (one workgroup, launched after the forward).
 __global__ __launch_bounds__(kThreads) void k_finish_loss(const float *__restrict__ partials, int n, float scale,
                                                           float *__restrict__ loss)
 {
-    __shared__ double s_acc[kThreads];
-    const int tid = threadIdx.x;
-    double a = 0.0;
-    int i = tid;
-    for (; i + 7 * kThreads < n; i += 8 * kThreads) {   // eight loads in flight, added in index order
-        float v[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = partials[i + u * kThreads];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) a += (double)v[u];
-    }
-    for (; i < n; i += kThreads) a += (double)partials[i];
-    s_acc[tid] = a;
-    __syncthreads();
-    for (int off = kThreads / 2; off >= 1; off >>= 1) {
-        if (tid < off) s_acc[tid] += s_acc[tid + off];
-        __syncthreads();
-    }
-    if (tid == 0) loss[0] = (float)(s_acc[0] * (double)scale);
+    finish_loss_body(partials, n, scale, loss);
 }
 
-// One group per positive i: rows i and b + i*k + kk (kk < k).
-// FROM_Y = false: the translated vector of a row is gathered from the stacked table X (TransE/TorusE).
-// FROM_Y = true : it is row `row` of the dense buffer G (TransR: y = M_r (h - t) + r was put there by
-//                 the projection kernel), and dL/dy overwrites it in place; every row is read and then
-//                 written by one group only.
-// PACKED (L1 kinds, gathered rows only): dL/dx is written as records of gstride bytes at G (coefficient + sign bytes).
 template <int LPR, int ITERS, int DIST, bool FROM_Y, bool PACKED>
-__global__ __launch_bounds__(kThreads) void k_forward_stacked(const int32_t *__restrict__ colidx,
-                                                              const float *__restrict__ X, int32_t b, int32_t k,
-                                                              int dim, float margin, float scale,
-                                                              float *__restrict__ scores, float *G,
-                                                              int gstride,
-                                                              float *__restrict__ loss_partials)
+__global__ __launch_bounds__(kThreads) void k_forward_stacked(ForwardArgs a)
 {
-    static_assert(!PACKED || (is_sign_kind(DIST) && !FROM_Y), "packed rows need an L1-kind distance");
-    constexpr int GROUPS = kThreads / LPR;
-    __shared__ float s_loss[GROUPS];
-    const int lig = threadIdx.x % LPR, grp = threadIdx.x / LPR;
-    const int64_t i = (int64_t)blockIdx.x * GROUPS + grp;
-    const int d4 = dim / 4;
-    float hinge_sum = 0.f;
-    if (i < b) {   // uniform within the group; shuffles below stay inside the group
-        // Negatives are taken NB at a time so that the kernel pays two memory round trips per batch (all
-        // column ids, then all table rows) instead of two per row; the positive rides with the first batch.
-        constexpr int NB = ITERS <= 2 ? 4 : 2;
-        RowVec<ITERS> xp;
-        float dpos = 0.f;
-        int n_active = 0;
-        int32_t cp[3] = {0, 0, 0};
-        if (!FROM_Y) { cp[0] = colidx[3 * i]; cp[1] = colidx[3 * i + 1]; cp[2] = colidx[3 * i + 2]; }
-        for (int kk0 = 0; kk0 < k || kk0 == 0; kk0 += NB) {
-            const int nb = min(NB, k - kk0);
-            const int64_t row0 = (int64_t)b + i * k + kk0;
-            int32_t cn[NB][3];
-            RowVec<ITERS> xn[NB];
-            if (!FROM_Y) {
-#pragma unroll
-                for (int q = 0; q < NB; ++q) {
-                    const int64_t rr = q < nb ? row0 + q : i;   // past the end: re-read the positive's ids
-                    cn[q][0] = colidx[3 * rr]; cn[q][1] = colidx[3 * rr + 1]; cn[q][2] = colidx[3 * rr + 2];
-                }
-            }
-            if (kk0 == 0) {
-                if (FROM_Y) load_vec<LPR, ITERS>(G + i * dim, d4, lig, xp);
-                else gather_row<LPR, ITERS, true>(X, dim, d4, lig, cp[0], cp[1], cp[2], xp);
-            }
-#pragma unroll
-            for (int q = 0; q < NB; ++q) {
-                if (q < nb) {
-                    if (FROM_Y) load_vec<LPR, ITERS>(G + (row0 + q) * dim, d4, lig, xn[q]);
-                    else gather_row<LPR, ITERS, true>(X, dim, d4, lig, cn[q][0], cn[q][1], cn[q][2], xn[q]);
-                }
-            }
-            if (kk0 == 0) {
-                dpos = row_distance<LPR, ITERS, DIST>(xp);
-                if (lig == 0) scores[i] = dpos;
-            }
-#pragma unroll
-            for (int q = 0; q < NB; ++q) {
-                if (q < nb) {
-                    const int64_t row = row0 + q;
-                    const float dneg = row_distance<LPR, ITERS, DIST>(xn[q]);
-                    const float arg = (margin + dpos) - dneg;
-                    const bool active = arg > 0.f;
-                    if (lig == 0) scores[row] = dneg;
-                    if (active) { hinge_sum += arg; ++n_active; }
-                    if (PACKED)
-                        write_grad_row_packed<LPR, ITERS, DIST>(reinterpret_cast<uint8_t *>(G), gstride, row, d4, lig,
-                                                                xn[q], active ? -scale : 0.f);
-                    else
-                        write_grad_row<LPR, ITERS, DIST>(G + row * dim, d4, lig, xn[q], active ? -scale : 0.f, dneg);
-                }
-            }
-        }
-        if (PACKED)
-            write_grad_row_packed<LPR, ITERS, DIST>(reinterpret_cast<uint8_t *>(G), gstride, i, d4, lig, xp,
-                                                    (float)n_active * scale);
-        else
-            write_grad_row<LPR, ITERS, DIST>(G + i * dim, d4, lig, xp, (float)n_active * scale, dpos);
-    }
-    if (lig == 0) s_loss[grp] = hinge_sum;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        float a = 0.f;
-#pragma unroll
-        for (int g = 0; g < GROUPS; ++g) a += s_loss[g];
-        loss_partials[blockIdx.x] = a;
-    }
+    forward_stacked_body<LPR, ITERS, DIST, FROM_Y, PACKED>((int)blockIdx.x, a);
 }
 
 __global__ void k_zero_loss(float *loss) { loss[0] = 0.f; }
@@ -230,10 +99,10 @@ static void forward_go(stx_ctx *c, const stx_incidence *inc, const stx_params *p
 {
     constexpr int GROUPS = kThreads / LPR;
     dim3 grid((unsigned)((inc->b + GROUPS - 1) / GROUPS));
+    const ForwardArgs fa{inc->a_colidx, p->ent, inc->b, inc->k, width, c->cfg.margin, scale, scores, c->gbuf[0],
+                         packed_stride(c->cfg.dim), c->loss_partials};
 #define STX_FWD(D, Y, P)                                                                                        \
-    hipLaunchKernelGGL((k_forward_stacked<LPR, ITERS, D, Y, P>), grid, dim3(kThreads), 0, c->stream,            \
-                       inc->a_colidx, p->ent, inc->b, inc->k, width, c->cfg.margin, scale, scores, c->gbuf[0],  \
-                       packed_stride(c->cfg.dim), c->loss_partials)
+    hipLaunchKernelGGL((k_forward_stacked<LPR, ITERS, D, Y, P>), grid, dim3(kThreads), 0, c->stream, fa)
 #define STX_FWD2(D)                                                                                             \
     do {                                                                                                        \
         if (from_y) STX_FWD(D, true, false);                                                                    \

@@ -76,6 +76,36 @@ struct stx_ctx {
 
 namespace stx {
 
+// Arguments of the forward-step body and of a scatter pass of the sort (by value into their kernels).
+struct ForwardArgs {
+    const int32_t *colidx;
+    const float *X;
+    int32_t b, k;
+    int dim;
+    float margin, scale;
+    float *scores, *G;
+    int gstride;
+    float *loss_partials;
+};
+
+struct ScatterArgs {
+    const int32_t *keys_in, *pay_in;
+    int32_t *keys_out, *pay_out;
+    int32_t nnz;
+    int shift, bits, ntiles;
+    const int32_t *table, *super;
+};
+
+// stx_train_step: forward-pass work that may share launches with the sort of A^T.  launch_build fills
+// in what it has done; the caller launches the rest.
+struct StepFusion {
+    const stx_params *p;
+    float *scores, *loss;
+    bool forward_done, finish_done;
+    int n_partials;            // loss partials the forward pass wrote
+    float scale;               // of the loss (1, or 1 / pairs for the mean)
+};
+
 // stx_build.hip
 stx_status launch_sample(stx_ctx *, const int32_t *h, const int32_t *t, int64_t m, int32_t k, uint64_t seed,
                          uint64_t base_ctr, int32_t *nh, int32_t *nt);
@@ -85,7 +115,10 @@ struct SampleArgs {            // negatives drawn inside the build (same numbers
 };
 stx_status launch_build(stx_ctx *, const int32_t *h, const int32_t *r, const int32_t *t, const int32_t *nh,
                         const int32_t *nt, int32_t b, int32_t k, stx_incidence *inc,
-                        const SampleArgs *sample = nullptr);
+                        const SampleArgs *sample = nullptr, StepFusion *fusion = nullptr);
+// stx_step.hip
+bool launch_fwd_scatter(stx_ctx *, const stx_incidence *, StepFusion *, const ScatterArgs &);   // false: shape not covered
+void launch_hist_finish(stx_ctx *, StepFusion *, const int32_t *keys, int32_t nnz, int shift, int radix, int ntiles);
 stx_status launch_clear_ctrl(stx_ctx *);
 stx_status launch_clear_maps(stx_ctx *);
 // stx_forward.hip

@@ -1,0 +1,164 @@
+// Device-side bodies of the radix-sort passes over the column ids of A (see stx_build.hip), shared by the
+// kernels that run them alone and by the launches that run them beside another, independent piece of
+// work (stx_step.hip).
+#pragma once
+
+#include "stx_device.h"
+#include "stx_internal.h"
+
+namespace stx {
+
+// Tile histograms of the digit at `shift` for the later passes.
+template <int ITEMS>
+__device__ inline void hist_body(const int block, const int32_t *__restrict__ keys, int32_t nnz, int shift,
+                                 int radix, int32_t *__restrict__ table)
+{
+    __shared__ int32_t s_hist[256];
+    const int tid = threadIdx.x;
+    s_hist[tid] = 0;
+    __syncthreads();
+    const int32_t base = block * (kThreads * ITEMS);
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+        int32_t e = base + it * kThreads + tid;
+        if (e < nnz) atomicAdd(&s_hist[(keys[e] >> shift) & (radix - 1)], 1);
+    }
+    __syncthreads();
+    if (tid < radix) table[block * radix + tid] = s_hist[tid];
+}
+
+// Stable scatter of one tile by the digit at `shift`.  Element order inside a tile is
+// (wavefront, iteration, lane): wavefront w owns the contiguous span [w*512, (w+1)*512) of the tile.
+// The rank of a key among equal digits is
+//   (count in earlier wavefronts) + (count in earlier iterations of this wavefront) + (equal lanes below),
+// the last term from a ballot match over the digit's bits.  The base offset of a (digit, tile) is the
+// number of keys with a smaller digit anywhere plus those with the same digit in earlier tiles: read
+// derived here from the raw tile counts: directly when there are few tiles (TWO_LEVEL false), through
+// the group sums of k_super_sums otherwise.
+// `block` is the tile (the index of the workgroup among those of the scatter; the launch may hold others).
+template <bool FIRST, bool TWO_LEVEL, int ITEMS>
+__device__ inline void scatter_body(const int block, const ScatterArgs &a)
+{
+    const int32_t *__restrict__ keys_in = a.keys_in;
+    const int32_t *__restrict__ pay_in = a.pay_in;
+    int32_t *__restrict__ keys_out = a.keys_out;
+    int32_t *__restrict__ pay_out = a.pay_out;
+    const int32_t nnz = a.nnz;
+    const int shift = a.shift, bits = a.bits, ntiles = a.ntiles;
+    const int32_t *__restrict__ table = a.table;
+    const int32_t *__restrict__ super = a.super;
+    __shared__ int32_t s_goff[256];
+    __shared__ int32_t s_hist[4][256];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int radix = 1 << bits;
+    for (int i = tid; i < 4 * 256; i += kThreads) (&s_hist[0][0])[i] = 0;
+    if (TWO_LEVEL) {
+        int32_t below = 0, total = 0;
+        if (tid < radix) {
+            const int me = block, g_me = me / kSuperTile, ngroups = (ntiles + kSuperTile - 1) / kSuperTile;
+            int g = 0;
+            for (; g + 3 < ngroups; g += 4) {
+                int32_t v0 = super[g * radix + tid], v1 = super[(g + 1) * radix + tid];
+                int32_t v2 = super[(g + 2) * radix + tid], v3 = super[(g + 3) * radix + tid];
+                total += (v0 + v1) + (v2 + v3);
+                below += (g < g_me ? v0 : 0) + (g + 1 < g_me ? v1 : 0) + (g + 2 < g_me ? v2 : 0) + (g + 3 < g_me ? v3 : 0);
+            }
+            for (; g < ngroups; ++g) {
+                int32_t v = super[g * radix + tid];
+                total += v;
+                below += g < g_me ? v : 0;
+            }
+#pragma unroll 8
+            for (int t = g_me * kSuperTile; t < me; ++t) below += table[t * radix + tid];
+        }
+        int32_t base = block_exclusive_scan(total, nullptr);
+        s_goff[tid] = base + below;
+    } else {
+        // All 256 threads share the table: a thread owns four neighbouring digits (one 16-byte load per
+        // tile row) and every `parts`-th tile; up to 16 loads are in flight per thread.
+        __shared__ int32_t s_tot[1024], s_bel[1024];
+        const int me = block;
+        int32_t below = 0, total = 0;
+        if (radix >= 4) {
+            const int r4 = radix >> 2, parts = kThreads / r4, d4 = tid % r4, q = tid / r4;
+            int4 tot = make_int4(0, 0, 0, 0), bel = make_int4(0, 0, 0, 0);
+            for (int t0 = q; t0 < ntiles; t0 += 16 * parts) {
+                int4 v[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    const int t = t0 + u * parts;
+                    v[u] = t < ntiles ? *reinterpret_cast<const int4 *>(table + t * radix + 4 * d4)
+                                      : make_int4(0, 0, 0, 0);
+                }
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    const int t = t0 + u * parts;
+                    tot.x += v[u].x; tot.y += v[u].y; tot.z += v[u].z; tot.w += v[u].w;
+                    if (t < me) { bel.x += v[u].x; bel.y += v[u].y; bel.z += v[u].z; bel.w += v[u].w; }
+                }
+            }
+            *reinterpret_cast<int4 *>(&s_tot[q * radix + 4 * d4]) = tot;
+            *reinterpret_cast<int4 *>(&s_bel[q * radix + 4 * d4]) = bel;
+            __syncthreads();
+            if (tid < radix)
+                for (int qq = 0; qq < parts; ++qq) {
+                    total += s_tot[qq * radix + tid];
+                    below += s_bel[qq * radix + tid];
+                }
+        } else if (tid < radix) {   // two bins only
+            for (int t = 0; t < ntiles; ++t) {
+                const int32_t v = table[t * radix + tid];
+                total += v;
+                below += t < me ? v : 0;
+            }
+        }
+        int32_t base = block_exclusive_scan(total, nullptr);
+        s_goff[tid] = base + below;
+    }
+    __syncthreads();
+
+    int32_t key[ITEMS], pay[ITEMS], rank[ITEMS];
+    const int32_t wave_base = block * (kThreads * ITEMS) + w * (64 * ITEMS);
+    const uint64_t below = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+        int32_t e = wave_base + it * 64 + lane;
+        bool valid = e < nnz;
+        key[it] = valid ? keys_in[e] : 0;
+        pay[it] = FIRST ? e : (valid ? pay_in[e] : 0);
+        int dgt = (key[it] >> shift) & (radix - 1);
+        uint64_t m = __ballot(valid);
+        for (int bit = 0; bit < bits; ++bit) {
+            bool one = (dgt >> bit) & 1;
+            uint64_t bm = __ballot(one);
+            m &= one ? bm : ~bm;
+        }
+        int32_t prior = s_hist[w][dgt];
+        rank[it] = prior + __popcll(m & below);
+        bool leader = valid && ((m >> lane) >> 1) == 0;   // highest lane of its digit class
+        if (leader) s_hist[w][dgt] = prior + __popcll(m);
+    }
+    __syncthreads();
+    if (tid < radix) {
+        int32_t a = 0;
+#pragma unroll
+        for (int w2 = 0; w2 < 4; ++w2) {
+            int32_t c = s_hist[w2][tid];
+            s_hist[w2][tid] = a;
+            a += c;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+        int32_t e = wave_base + it * 64 + lane;
+        if (e < nnz) {
+            int dgt = (key[it] >> shift) & (radix - 1);
+            int32_t pos = s_goff[dgt] + s_hist[w][dgt] + rank[it];
+            keys_out[pos] = key[it];
+            pay_out[pos] = pay[it];
+        }
+    }
+}
+
+}  // namespace stx

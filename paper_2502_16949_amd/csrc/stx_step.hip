@@ -1,0 +1,76 @@
+// Launches in which two independent pieces of one training step share the GPU.
+//
+// At the batch sizes of the paper's benchmarks (Sec. 5.3: 32,768 positives) every kernel of a step is
+// short and the step is a chain of dependent launches, so its duration is the sum of their latencies.
+// Two links of that chain do not depend on each other: the forward pass (SparseTransX Sec. 4.3) needs
+// only A, which the first kernel of the build writes, while the sort that produces A^T for the
+// backward pass (Appendix G) goes on for several more launches; and the final sum of the loss needs
+// only the forward pass.  stx_train_step therefore runs the forward pass in the launch of the sort's
+// first scatter pass, and the loss sum in the launch of the next histogram pass.  The sort's
+// workgroups take the low block indices so that they start first: they are few and long, the forward
+// workgroups many and short.
+#include "stx_forward_body.h"
+#include "stx_sort_body.h"
+
+namespace stx {
+
+template <int LPR, int ITERS, int DIST, bool PACKED>
+__global__ __launch_bounds__(kThreads) void k_fwd_scatter(ForwardArgs fa, ScatterArgs sa)
+{
+    if ((int)blockIdx.x < sa.ntiles) scatter_body<true, false, kSortItems>((int)blockIdx.x, sa);
+    else forward_stacked_body<LPR, ITERS, DIST, false, PACKED>((int)blockIdx.x - sa.ntiles, fa);
+}
+
+__global__ __launch_bounds__(kThreads) void k_hist_finish(const int32_t *__restrict__ keys, int32_t nnz, int shift,
+                                                          int radix, int32_t *__restrict__ table,
+                                                          const float *__restrict__ partials, int n_partials,
+                                                          float scale, float *__restrict__ loss)
+{
+    if (blockIdx.x == 0) finish_loss_body(partials, n_partials, scale, loss);
+    else hist_body<kSortItems>((int)blockIdx.x - 1, keys, nnz, shift, radix, table);
+}
+
+template <int LPR, int ITERS>
+static void fwd_scatter_go(stx_ctx *c, const ForwardArgs &fa, const ScatterArgs &sa, unsigned blocks)
+{
+#define STX_FS(D, P)                                                                                            \
+    hipLaunchKernelGGL((k_fwd_scatter<LPR, ITERS, D, P>), dim3(blocks), dim3(kThreads), 0, c->stream, fa, sa)
+    switch (c->cfg.dist) {
+    case STX_L1: STX_FS(STX_L1, true); break;
+    case STX_L2: STX_FS(STX_L2, false); break;
+    case STX_TORUS_L1: STX_FS(STX_TORUS_L1, true); break;
+    default: STX_FS(STX_TORUS_L2, false); break;
+    }
+#undef STX_FS
+}
+
+bool launch_fwd_scatter(stx_ctx *c, const stx_incidence *inc, StepFusion *f, const ScatterArgs &sa)
+{
+    const bool stacked = c->cfg.model == STX_TRANSE || c->cfg.model == STX_TORUSE;
+    const Launch L = row_launch(c->cfg.dim);
+    if (!stacked || L.iters != 1 || inc->n_rows == 0) return false;
+    f->scale = 1.0f;
+    if (c->cfg.reduce == STX_MEAN && inc->k > 0) f->scale = 1.0f / (float)((int64_t)inc->b * inc->k);
+    const int groups = kThreads / L.lpr;
+    f->n_partials = (inc->b + groups - 1) / groups;
+    const ForwardArgs fa{inc->a_colidx, f->p->ent, inc->b, inc->k, c->cfg.dim, c->cfg.margin, f->scale, f->scores,
+                         c->gbuf[0], packed_stride(c->cfg.dim), c->loss_partials};
+    const unsigned blocks = (unsigned)(sa.ntiles + f->n_partials);
+    ProfScope prof(c, "k_fwd_scatter");
+    if (L.lpr == 8) fwd_scatter_go<8, 1>(c, fa, sa, blocks);
+    else if (L.lpr == 16) fwd_scatter_go<16, 1>(c, fa, sa, blocks);
+    else if (L.lpr == 32) fwd_scatter_go<32, 1>(c, fa, sa, blocks);
+    else fwd_scatter_go<64, 1>(c, fa, sa, blocks);
+    f->forward_done = true;
+    return true;
+}
+
+void launch_hist_finish(stx_ctx *c, StepFusion *f, const int32_t *keys, int32_t nnz, int shift, int radix, int ntiles)
+{
+    ProfScope prof(c, "k_hist_finish");
+    hipLaunchKernelGGL(k_hist_finish, dim3((unsigned)ntiles + 1), dim3(kThreads), 0, c->stream, keys, nnz, shift, radix,
+                       c->table, c->loss_partials, f->n_partials, f->scale, f->loss);
+    f->finish_done = true;
+}
+
+}  // namespace stx
