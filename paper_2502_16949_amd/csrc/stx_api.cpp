@@ -70,7 +70,9 @@ Layout make_layout(const stx_config *c)
     L.super = take((size_t)256 * (L.ntiles_max / kSuperTile + 1) * 4);
     L.tile_heads = take((size_t)(L.ntiles_max + 1) * 4);
     L.loss_partials = take((size_t)(L.fwd_blocks_max + 1) * 4);
-    L.partials = take((size_t)(L.nnz_max / kSegTileMin + 2) * 2 * L.ld * 4);
+    // two partial rows per tile of the transposed product; TransH runs a second product over the relation
+    // entries in the same launch
+    L.partials = take((size_t)(L.nnz_max / kSegTileMin + L.rows_max / kSegTileMin + 4) * 2 * L.ld * 4);
     for (int i = 0; i < 4; ++i) {
         size_t bytes = (size_t)L.rows_max * L.ld * 4;
         if (i == 0 && bytes < (size_t)L.rows_max * packed_stride(c->dim))   // packed dL/dx records (tiny dims only)
@@ -415,10 +417,10 @@ stx_status stx_backward(stx_ctx *ctx, const stx_incidence *inc, const stx_params
     }
     if (ctx->cfg.model == STX_TRANSH) {
         // entity columns: signed sums of gx; relation columns: sums of gy (-> d_r) and of gw (-> w_r)
-        s = launch_seg_reduce(ctx, inc, 0, inc->nnz, ctx->gbuf[0], ctx->gbuf[1], ent_end, dim, dim, g->rows, ctx->ld);
-        if (s != STX_OK) return s;
-        return launch_seg_reduce(ctx, inc, ent_end, inc->nnz, ctx->gbuf[2], ctx->gbuf[2], inc->nnz, dim, dim,
-                                 g->w_rows, ctx->ld);
+        // (both products in the same pair of launches)
+        const SegSecondHost second{(int32_t)ent_end, (int32_t)inc->nnz, ctx->gbuf[2], g->w_rows};
+        return launch_seg_reduce(ctx, inc, 0, inc->nnz, ctx->gbuf[0], ctx->gbuf[1], ent_end, dim, dim, g->rows, ctx->ld,
+                                 false, nullptr, 0.f, 0, &second);
     }
     // TransR: gx = M_r^T gy and dL/dM_r on the matrix cores, then entity columns sum gx (signed, width dim)
     // and relation columns sum gy (width rel_dim)

@@ -83,6 +83,16 @@ struct FusedArgs {             // the update that replaces the store of a gradie
     int mode;                  // 0 plain, 1 keep the fractional part (TorusE, Sec. 4.6)
 };
 
+// A second, independent transposed product that shares the launch (TransH: the sums of gw over the
+// relation columns beside the sums of gx / gy over all columns).  Workgroups from `first_block` on work
+// on it; all of its entries read `src`.
+struct SegSecond {
+    int first_block;           // INT_MAX: no second product
+    int32_t e_begin, e_end;
+    const float *src;
+    float *out_rows, *partials;
+};
+
 // table row <- x - lr * g, each product and difference rounded once, as in k_sgd_rows.
 template <int LPR, int ITERS>
 __device__ inline void apply_update(float *__restrict__ row, int d4, int lig, const Acc<ITERS> &x, const Acc<ITERS> &g,
@@ -116,8 +126,16 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
                                                          int32_t e_end, const float *__restrict__ src_a,
                                                          const float *__restrict__ src_b, int32_t split,
                                                          int ld_src, int d4, float *__restrict__ out_rows,
-                                                         int ld_out, float *__restrict__ partials, FusedArgs fu)
+                                                         int ld_out, float *__restrict__ partials, FusedArgs fu,
+                                                         SegSecond sec)
 {
+    int block = (int)blockIdx.x;
+    if (block >= sec.first_block) {   // uniform in the workgroup
+        block -= sec.first_block;
+        e_begin = sec.e_begin; e_end = sec.e_end;
+        src_a = src_b = sec.src; split = sec.e_end;
+        out_rows = sec.out_rows; partials = sec.partials;
+    }
     constexpr int GROUPS = kThreads / LPR;
     // rows in flight per lane: dense rows cost 4*ITERS registers each; packed rows are a byte and a float,
     // so a whole chunk is fetched at once and the kernel pays one memory latency per chunk
@@ -135,7 +153,7 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
     __shared__ int32_t s_col_last[GROUPS], s_fin_src[GROUPS];
 
     const int lig = threadIdx.x % LPR, grp = threadIdx.x / LPR;
-    const int32_t tile0 = e_begin + (int32_t)blockIdx.x * TILE;
+    const int32_t tile0 = e_begin + block * TILE;
     const int32_t ec0 = tile0 + grp * CHUNK;
     const int32_t ec1 = min(ec0 + CHUNK, e_end);
 
@@ -266,7 +284,7 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
         int cur_src = 0;                                   // chunk in which the current run began
         Acc<ITERS> cur;
         cur.zero();
-        float *my_part = partials + (int64_t)blockIdx.x * 2 * ld_out;
+        float *my_part = partials + (int64_t)block * 2 * ld_out;
         for (int g = 0; g < GROUPS; ++g) {
             const int inf = s_info[g];
             if (inf & HAS_FIRST) {
@@ -319,14 +337,22 @@ __global__ __launch_bounds__(kThreads) void k_seg_fixup(const int32_t *__restric
                                                         const int32_t *__restrict__ seg_id,
                                                         const int32_t *__restrict__ seg_ptr, int32_t e_begin,
                                                         int32_t e_end, int d4, float *__restrict__ out_rows,
-                                                        int ld_out, const float *__restrict__ partials, FusedArgs fu)
+                                                        int ld_out, const float *__restrict__ partials, FusedArgs fu,
+                                                        SegSecond sec)
 {
+    int block = (int)blockIdx.x;
+    if (block >= sec.first_block) {   // uniform in the workgroup
+        block -= sec.first_block;
+        e_begin = sec.e_begin; e_end = sec.e_end;
+        out_rows = sec.out_rows; partials = sec.partials;
+    }
     constexpr int GROUPS = kThreads / LPR;
     constexpr int ROWF = ITERS * LPR * 4;
     constexpr int TILE = GROUPS * CHUNK;
     static_assert(TILE <= kThreads, "one thread per entry of the tile in the head search");
     __shared__ float s_sum[GROUPS][ROWF];
-    const int32_t j = (int32_t)blockIdx.x + 1;                  // tile 0 never ends a crossing run
+    const int32_t j = block;
+    if (j == 0) return;                                         // tile 0 never ends a crossing run
     const int32_t tile0 = e_begin + j * TILE;
     if (tile0 >= e_end) return;
     const int32_t tile1 = min(tile0 + TILE, e_end);
@@ -502,7 +528,7 @@ __global__ __launch_bounds__(kThreads) void k_sgd_rows(const int32_t *__restrict
 template <int LPR, int ITERS>
 static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_t e_end, const float *src_a,
                    const float *src_b, int32_t split, int ld_src, int width, float *out_rows, int ld_out,
-                   bool packed_src, const FusedArgs *fused)
+                   bool packed_src, const FusedArgs *fused, const SegSecondHost *second)
 {
     // Entries per lane group: short chunks shorten every group's serial walk when the whole product is
     // small (latency bound); long ones mean fewer partial rows when it is large (bandwidth bound).
@@ -510,7 +536,14 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
     constexpr int GROUPS = kThreads / LPR;
     const bool small = (e_end - e_begin) <= (1 << 20);
     const int tile = GROUPS * (small ? CH_SHORT : CH_LONG);
-    const int ntiles = (e_end - e_begin + tile - 1) / tile;
+    const int ntiles1 = (e_end - e_begin + tile - 1) / tile;
+    SegSecond sec{0x7fffffff, 0, 0, nullptr, nullptr, nullptr};
+    int ntiles = ntiles1;
+    if (second && second->e_end > second->e_begin) {
+        sec = SegSecond{ntiles1, second->e_begin, second->e_end, second->src, second->out_rows,
+                        c->partials + (int64_t)ntiles1 * 2 * ld_out};
+        ntiles += (second->e_end - second->e_begin + tile - 1) / tile;
+    }
     const FusedArgs fu = fused ? *fused : FusedArgs{nullptr, nullptr, nullptr, 0.f, 0};
 #define STX_SEG(P, CH, F)                                                                                       \
     do {                                                                                                        \
@@ -518,13 +551,13 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
             ProfScope prof(c, "k_seg_reduce");                                                                  \
             hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH, F>), dim3(ntiles), dim3(kThreads), 0,           \
                                c->stream, inc->at_packed, inc->at_seg_id, e_begin, e_end, src_a, src_b, split,  \
-                               ld_src, width / 4, out_rows, ld_out, c->partials, fu);                           \
+                               ld_src, width / 4, out_rows, ld_out, c->partials, fu, sec);                      \
         }                                                                                                       \
         if (ntiles > 1) {                                                                                       \
             ProfScope prof(c, "k_seg_fixup");                                                                   \
-            hipLaunchKernelGGL((k_seg_fixup<LPR, ITERS, CH, F>), dim3(ntiles - 1), dim3(kThreads), 0,           \
+            hipLaunchKernelGGL((k_seg_fixup<LPR, ITERS, CH, F>), dim3(ntiles), dim3(kThreads), 0,               \
                                c->stream, inc->at_packed, inc->at_seg_id, inc->at_seg_ptr, e_begin, e_end,      \
-                               width / 4, out_rows, ld_out, c->partials, fu);                                   \
+                               width / 4, out_rows, ld_out, c->partials, fu, sec);                              \
         }                                                                                                       \
     } while (0)
 #define STX_SEG2(P, CH) do { if (fused) STX_SEG(P, CH, true); else STX_SEG(P, CH, false); } while (0)
@@ -553,7 +586,7 @@ static void sgd_go(stx_ctx *c, const stx_incidence *inc, const SgdTables &T, con
 stx_status launch_seg_reduce(stx_ctx *c, const stx_incidence *inc, int64_t e_begin, int64_t e_end,
                              const float *src_a, const float *src_b, int64_t split, int ld_src, int width,
                              float *out_rows, int ld_out, bool packed_src, float *fused_table, float fused_lr,
-                             int fused_mode)
+                             int fused_mode, const SegSecondHost *second)
 {
     if (e_end <= e_begin) return STX_OK;
     Launch L = row_launch(width);
@@ -562,7 +595,7 @@ stx_status launch_seg_reduce(stx_ctx *c, const stx_incidence *inc, int64_t e_beg
                        fused_mode};
     const FusedArgs *fused = fused_table ? &fu : nullptr;
     STX_DISPATCH_ROW(L, seg_go, c, inc, (int32_t)e_begin, (int32_t)e_end, src_a, src_b, (int32_t)split, ld_src, width,
-                     out_rows, ld_out, packed_src, fused);
+                     out_rows, ld_out, packed_src, fused, second);
     return hip_ok(hipGetLastError());
 }
 

@@ -131,10 +131,17 @@ stx_status launch_copy_f32(stx_ctx *, float *dst, const float *src, int64_t n);
 // packed_src: src_a holds packed L1-kind records (see packed_stride), ld_src is the record size in bytes.
 // fused_table: if not null, no gradient row is written; row `column` of that table (rows of `width` floats)
 // becomes row - fused_lr * gradient instead (fused_mode 1: then its fractional part).
+// second: another product of the same row width over the entries [e_begin, e_end), all reading `src`, that
+// runs in the same two launches (its workgroups follow the first product's).
+struct SegSecondHost {
+    int32_t e_begin, e_end;
+    const float *src;
+    float *out_rows;
+};
 stx_status launch_seg_reduce(stx_ctx *, const stx_incidence *, int64_t e_begin, int64_t e_end, const float *src_a,
                              const float *src_b, int64_t split, int ld_src, int width, float *out_rows, int ld_out,
                              bool packed_src = false, float *fused_table = nullptr, float fused_lr = 0.f,
-                             int fused_mode = 0);
+                             int fused_mode = 0, const SegSecondHost *second = nullptr);
 struct SgdTables {
     float *table_a; int width_a; int mode_a;   // columns [0, n_split)
     int64_t n_split;

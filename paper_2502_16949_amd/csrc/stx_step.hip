@@ -11,6 +11,7 @@
 // workgroups many and short.
 #include "stx_forward_body.h"
 #include "stx_sort_body.h"
+#include "stx_transh_body.h"
 
 namespace stx {
 
@@ -19,6 +20,13 @@ __global__ __launch_bounds__(kThreads) void k_fwd_scatter(ForwardArgs fa, Scatte
 {
     if ((int)blockIdx.x < sa.ntiles) scatter_body<true, false, kSortItems>((int)blockIdx.x, sa);
     else forward_stacked_body<LPR, ITERS, DIST, false, PACKED>((int)blockIdx.x - sa.ntiles, fa);
+}
+
+template <int LPR, int ITERS, int DIST>
+__global__ __launch_bounds__(kThreads) void k_fwdh_scatter(TranshArgs ta, ScatterArgs sa)
+{
+    if ((int)blockIdx.x < sa.ntiles) scatter_body<true, false, kSortItems>((int)blockIdx.x, sa);
+    else forward_transh_body<LPR, ITERS, DIST>((int)blockIdx.x - sa.ntiles, ta);
 }
 
 __global__ __launch_bounds__(kThreads) void k_hist_finish(const int32_t *__restrict__ keys, int32_t nnz, int shift,
@@ -44,15 +52,43 @@ static void fwd_scatter_go(stx_ctx *c, const ForwardArgs &fa, const ScatterArgs 
 #undef STX_FS
 }
 
+template <int LPR, int ITERS>
+static void fwdh_scatter_go(stx_ctx *c, const TranshArgs &ta, const ScatterArgs &sa, unsigned blocks)
+{
+#define STX_FS(D)                                                                                               \
+    hipLaunchKernelGGL((k_fwdh_scatter<LPR, ITERS, D>), dim3(blocks), dim3(kThreads), 0, c->stream, ta, sa)
+    switch (c->cfg.dist) {
+    case STX_L1: STX_FS(STX_L1); break;
+    case STX_L2: STX_FS(STX_L2); break;
+    case STX_TORUS_L1: STX_FS(STX_TORUS_L1); break;
+    default: STX_FS(STX_TORUS_L2); break;
+    }
+#undef STX_FS
+}
+
 bool launch_fwd_scatter(stx_ctx *c, const stx_incidence *inc, StepFusion *f, const ScatterArgs &sa)
 {
     const bool stacked = c->cfg.model == STX_TRANSE || c->cfg.model == STX_TORUSE;
+    const bool transh = c->cfg.model == STX_TRANSH;
     const Launch L = row_launch(c->cfg.dim);
-    if (!stacked || L.iters != 1 || inc->n_rows == 0) return false;
+    if (!(stacked || transh) || L.iters != 1 || inc->n_rows == 0) return false;
     f->scale = 1.0f;
     if (c->cfg.reduce == STX_MEAN && inc->k > 0) f->scale = 1.0f / (float)((int64_t)inc->b * inc->k);
     const int groups = kThreads / L.lpr;
     f->n_partials = (inc->b + groups - 1) / groups;
+    if (transh) {
+        const TranshArgs ta{inc->a_colidx, f->p->ent, f->p->rel, f->p->w, (int32_t)c->cfg.n_ent, inc->b, inc->k,
+                            c->cfg.dim, c->cfg.margin, f->scale, f->scores, c->gbuf[0], c->gbuf[1], c->gbuf[2],
+                            c->loss_partials};
+        const unsigned blocks = (unsigned)(sa.ntiles + f->n_partials);
+        ProfScope prof(c, "k_fwdh_scatter");
+        if (L.lpr == 8) fwdh_scatter_go<8, 1>(c, ta, sa, blocks);
+        else if (L.lpr == 16) fwdh_scatter_go<16, 1>(c, ta, sa, blocks);
+        else if (L.lpr == 32) fwdh_scatter_go<32, 1>(c, ta, sa, blocks);
+        else fwdh_scatter_go<64, 1>(c, ta, sa, blocks);
+        f->forward_done = true;
+        return true;
+    }
     const ForwardArgs fa{inc->a_colidx, f->p->ent, inc->b, inc->k, c->cfg.dim, c->cfg.margin, f->scale, f->scores,
                          c->gbuf[0], packed_stride(c->cfg.dim), c->loss_partials};
     const unsigned blocks = (unsigned)(sa.ntiles + f->n_partials);

@@ -192,52 +192,6 @@ def test_fused_update_needs_forward_and_invalidates_it():
         m.backward()
 
 
-@pytest.mark.parametrize("model,dist,n_ent,n_rel,b,k,dim,zipf", [
-    ("transe", "l1", 1000, 20, 1000, 1, 128, 1.1),
-    ("transe", "l2", 400, 9, 777, 3, 128, 1.1),
-    ("transe", "l1", 64, 4, 2500, 2, 100, 0.0),
-    ("transe", "l2", 70000, 5, 3000, 1, 32, 1.1),        # too many columns for the presence bitmap
-    ("toruse", "torus_l1", 1000, 20, 1024, 4, 128, 1.05),
-    ("toruse", "torus_l2", 500, 7, 600, 2, 64, 1.05),
-    ("transe", "l2", 100, 3, 50, 0, 64, 0.0),             # no negatives at all
-])
-def test_train_step_equals_the_separate_calls(model, dist, n_ent, n_rel, b, k, dim, zipf):
-    """stx_train_step against stx_sample_negatives + stx_build_incidence + stx_forward + stx_backward +
-    stx_sgd_step (each checked against the oracle elsewhere in this file), over three consecutive batches
-    so that the alternating presence bitmaps are exercised: every output must have the same bits."""
-    wl, tabs, _ = _problem(model, dist, n_ent, n_rel, b, k, dim, seed=11, zipf=zipf)
-    rng = np.random.default_rng(5)
-    m_total = 3 * b
-    h = rng.integers(0, n_ent, m_total).astype(np.int32)
-    r = rng.integers(0, n_rel, m_total).astype(np.int32)
-    t = rng.integers(0, n_ent, m_total).astype(np.int32)
-    hd, rd, td = G.dev_i32(h), G.dev_i32(r), G.dev_i32(t)
-    ma, mb = G.GpuModel(wl, tabs), G.GpuModel(wl, tabs)
-    nk = max(1, b * k)
-    nha, nta, nhb, ntb = (torch.zeros(nk, dtype=torch.int32, device=G.DEV) for _ in range(4))
-    for step, (lo, hi) in enumerate([(0, b), (b, 2 * b), (2 * b, 3 * b - 7)]):
-        bb = hi - lo
-        # separate calls
-        if k:
-            B.stx_sample_negatives(ma.ctx, hd[lo:hi], rd[lo:hi], td[lo:hi], k, 99, 2, m_total, lo, nha, nta)
-        B.stx_build_incidence(ma.ctx, hd[lo:hi], rd[lo:hi], td[lo:hi], nha if k else None, nta if k else None, k, ma.inc)
-        ma.forward()
-        ma.backward()
-        ma.sgd(0.01)
-        # one call
-        batch = B.make_batch(hd[lo:hi], rd[lo:hi], td[lo:hi], k, 99, 2, m_total, lo, nhb, ntb)
-        B.stx_train_step(mb.ctx, batch, mb.inc, mb.params, None, 0.01, mb.scores, mb.loss)
-        torch.cuda.synchronize()
-        assert torch.equal(nha[:bb * k], nhb[:bb * k]) and torch.equal(nta[:bb * k], ntb[:bb * k])
-        ia, ib = ma.incidence_numpy(), mb.incidence_numpy()
-        for name in ia:
-            assert np.array_equal(ia[name], ib[name]), (step, name)
-        sa, la = ma.scores_numpy()
-        sb, lb = mb.scores_numpy()
-        assert np.array_equal(sa, sb) and la == lb
-        assert torch.equal(ma.params.ent, mb.params.ent), step
-
-
 def test_backward_is_bitwise_reproducible_and_needs_forward():
     wl, tabs, bt = _problem("transe", "l2", 64, 4, 3000, 2, 128, seed=3, zipf=1.1)
     m = G.GpuModel(wl, tabs)

@@ -1,0 +1,85 @@
+"""stx_train_step (one call per training step, with launches shared between independent kernels) against
+the separate calls stx_sample_negatives + stx_build_incidence + stx_forward + stx_backward + stx_sgd_step.
+The separate calls are checked against the oracle in the other GPU test files; the one-call step does
+the same arithmetic in the same order, so every output must have the same bits.  The full-size checks
+of the step against the oracle itself are in test_gpu_fullsize.py."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_16949_amd import binding as B
+from paper_2502_16949_amd import workloads as W
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # model, dist, n_ent, n_rel, b, k, dim, rel_dim, flags
+    ("transe", "l1", 1000, 20, 1000, 1, 128, 128, 0),
+    ("transe", "l2", 400, 9, 777, 3, 128, 128, 0),
+    ("transe", "l1", 64, 4, 2500, 2, 100, 100, 0),                # one sort pass only
+    ("transe", "l2", 70000, 5, 3000, 1, 32, 32, 0),               # too many columns for the presence bitmap
+    ("transe", "l2", 300, 5, 200, 1, 512, 512, 0),                # rows wider than the shared-launch forward covers
+    ("toruse", "torus_l1", 1000, 20, 1024, 4, 128, 128, 0),
+    ("toruse", "torus_l2", 500, 7, 600, 2, 64, 64, 0),
+    ("transe", "l2", 100, 3, 50, 0, 64, 64, 0),                   # no negatives at all
+    ("transh", "l2", 1000, 20, 1024, 1, 128, 128, B.STX_FLAG_RENORM_W),
+    ("transh", "l1", 400, 9, 777, 3, 64, 64, 0),
+    ("transh", "l2", 200, 5, 200, 1, 1024, 1024, 0),
+    ("transr", "l2", 1000, 20, 1024, 1, 128, 128, B.STX_FLAG_BF16_PROJ),
+    ("transr", "l1", 300, 40, 500, 2, 64, 32, B.STX_FLAG_BF16_PROJ),
+]
+
+
+@pytest.mark.parametrize("model,dist,n_ent,n_rel,b,k,dim,rel_dim,flags", CASES)
+def test_train_step_equals_the_separate_calls(model, dist, n_ent, n_rel, b, k, dim, rel_dim, flags):
+    """Three consecutive batches (the last one shorter), so that the alternating presence bitmaps and the
+    state left by the previous step are exercised."""
+    wl = W.Workload("case", 11, model, dist, n_ent, n_rel, 3 * b, dim, rel_dim, b, k, 1.0, 0.01, 1, 1.1, 1.1,
+                    bool(flags & B.STX_FLAG_BF16_PROJ))
+    tabs = W.make_tables(wl)
+    rng = np.random.default_rng(5)
+    m_total = 3 * b
+    hd = G.dev_i32(rng.integers(0, n_ent, m_total))
+    rd = G.dev_i32(rng.integers(0, n_rel, m_total))
+    td = G.dev_i32(rng.integers(0, n_ent, m_total))
+    ma, mb = G.GpuModel(wl, tabs, flags=flags), G.GpuModel(wl, tabs, flags=flags)
+    nk = max(1, b * k)
+    nha, nta, nhb, ntb = (torch.zeros(nk, dtype=torch.int32, device=G.DEV) for _ in range(4))
+    for step, (lo, hi) in enumerate([(0, b), (b, 2 * b), (2 * b, 3 * b - 7)]):
+        bb = hi - lo
+        if k:
+            B.stx_sample_negatives(ma.ctx, hd[lo:hi], rd[lo:hi], td[lo:hi], k, 99, 2, m_total, lo, nha, nta)
+        B.stx_build_incidence(ma.ctx, hd[lo:hi], rd[lo:hi], td[lo:hi], nha if k else None, nta if k else None, k, ma.inc)
+        ma.forward()
+        ma.backward()
+        ma.sgd(0.01)
+        batch = B.make_batch(hd[lo:hi], rd[lo:hi], td[lo:hi], k, 99, 2, m_total, lo, nhb, ntb)
+        B.stx_train_step(mb.ctx, batch, mb.inc, mb.params, mb.grads, 0.01, mb.scores, mb.loss)
+        torch.cuda.synchronize()
+        assert torch.equal(nha[:bb * k], nhb[:bb * k]) and torch.equal(nta[:bb * k], ntb[:bb * k])
+        ia, ib = ma.incidence_numpy(), mb.incidence_numpy()
+        for name in ia:
+            assert np.array_equal(ia[name], ib[name]), (step, name)
+        sa, la = ma.scores_numpy()
+        sb, lb = mb.scores_numpy()
+        assert np.array_equal(sa, sb) and la == lb, step
+        for name in ("ent", "rel", "w", "proj"):
+            ta, tb = getattr(ma.params, name), getattr(mb.params, name)
+            assert (ta is None and tb is None) or torch.equal(ta, tb), (step, name)
+
+
+def test_train_step_without_gradient_storage_for_stacked_models():
+    wl = W.Workload("case", 3, "transe", "l1", 500, 10, 600, 128, 128, 600, 1, 1.0, 0.01, 1, 1.1, 1.1)
+    tabs = W.make_tables(wl)
+    h, r, t = W.make_graph(wl)
+    hd, rd, td = G.dev_i32(h), G.dev_i32(r), G.dev_i32(t)
+    m = G.GpuModel(wl, tabs)
+    nh, nt = (torch.zeros(600, dtype=torch.int32, device=G.DEV) for _ in range(2))
+    batch = B.make_batch(hd, rd, td, 1, 7, 0, 600, 0, nh, nt)
+    before = m.params.ent.clone()
+    B.stx_train_step(m.ctx, batch, m.inc, m.params, None, 0.01, m.scores, m.loss)
+    torch.cuda.synchronize()
+    assert not torch.equal(before, m.params.ent) and float(m.loss.item()) > 0.0
+    with pytest.raises(B.StxError):                                      # the step consumed its forward pass
+        m.backward()
