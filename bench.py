@@ -27,7 +27,11 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 # The kernel whose roofline is reported: the one with the largest share of GPU time in the
 # rocprofv3 kernel trace of the same command (profiles/).
-DOMINANT = {"transe": "k_seg_reduce", "toruse": "k_seg_reduce", "transh": "k_seg_reduce", "transr": "k_transr_project"}
+DOMINANT = {"mid": "k_fwd_scatter", "tiny": "k_fwd_scatter", "toruse": "k_seg_reduce", "transh": "k_fwdh_scatter",
+            "transr": "k_transr_project"}
+# ... and when the step is made of the separate calls (--api fused | separate)
+DOMINANT_CALLS = {"mid": "k_seg_reduce", "tiny": "k_seg_reduce", "toruse": "k_seg_reduce", "transh": "k_forward_transh",
+                  "transr": "k_transr_project"}
 
 
 # HBM bytes per launch of those kernels, measured: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (separate runs),
@@ -77,20 +81,21 @@ def kernel_work(wl, kernel, rows, touched, fused=False):
     if kernel == "k_forward_stacked" and wl.model in ("transe", "toruse"):
         # 3 gathered table rows + 12 B of column ids per row in; dL/dx row + score out
         return rows * (3 * row + 12 + grow + 4), "GB/s", "hbm", HBM_PEAK_GBS
+    if kernel == "k_fwd_scatter":      # the same forward pass and one scatter pass of the sort in one launch
+        return rows * (3 * row + 12 + grow + 4) + nnz * 16, "GB/s", "hbm", HBM_PEAK_GBS
+    if kernel == "k_fwdh_scatter":     # TransH forward (below) and one scatter pass
+        return rows * (2 * row + 2 * row / (1 + wl.n_neg) + 12 + 3 * row + 4) + nnz * 16, "GB/s", "hbm", HBM_PEAK_GBS
     if kernel == "k_forward_stacked":   # TransR: y row in, dL/dy row out, score out
         return rows * (2 * 4 * wl.rel_dim + 4), "GB/s", "hbm", HBM_PEAK_GBS
     if kernel == "k_forward_transh":
-        # 2 entity rows + w_r + d_r (+ w_r again for the gradients) in; gx, gy, gw rows + score out
-        return rows * (5 * row + 12 + 3 * row + 4), "GB/s", "hbm", HBM_PEAK_GBS
+        # 2 entity rows per row, w_r and d_r once per positive, 12 B of ids in; gx, gy, gw rows + score out
+        return rows * (2 * row + 2 * row / (1 + wl.n_neg) + 12 + 3 * row + 4), "GB/s", "hbm", HBM_PEAK_GBS
     if kernel == "k_seg_reduce":
-        # one source row + 4 B packed entry per sorted entry in, one row per column out.  TransE/TorusE launch it
-        # once over all 3*rows entries.  TransH launches it twice (all entries -> dE and d(d_r); the relation
-        # entries again -> dw_r) and TransR twice (entity entries -> dE; relation entries -> dr): the figure is the
-        # mean of the two launches, like the measured time.  The relation columns touched are few (<= n_rel).
-        if wl.model == "transh":
-            return (nnz * (row + 4) + touched * row + rows * (row + 4) + min(wl.n_rel, rows) * row) / 2, "GB/s", "hbm", HBM_PEAK_GBS
-        if wl.model == "transr":
-            return (nnz * (row + 4) + touched * row) / 2, "GB/s", "hbm", HBM_PEAK_GBS
+        # one source row + 4 B packed entry per sorted entry in, one row per column out, over all 3*rows entries
+        if wl.model == "transh":   # both products (all entries -> dE, d(d_r); relation entries -> dw_r) in one launch
+            return nnz * (row + 4) + touched * row + rows * (row + 4) + min(wl.n_rel, rows) * row, "GB/s", "hbm", HBM_PEAK_GBS
+        if wl.model == "transr":   # one launch when dim == rel_dim
+            return nnz * (row + 4) + touched * row, "GB/s", "hbm", HBM_PEAK_GBS
         if fused and wl.model in ("transe", "toruse"):
             # fused update: the table row is read and written where the gradient row would have been written
             return nnz * (grow + 4) + touched * 2 * row, "GB/s", "hbm", HBM_PEAK_GBS
@@ -160,7 +165,7 @@ def main():
         print(json.dumps({"copy_calibration_bytes_read": 4 * n, "bytes_written": 4 * n, "launches": 20}))
         return
     wl = W.WORKLOADS[args.config]
-    kernel = args.kernel or DOMINANT[wl.model]
+    kernel = args.kernel or (DOMINANT if args.api == "step" else DOMINANT_CALLS)[wl.name]
 
     h, r, t = W.make_graph(wl)
     tabs = W.make_tables(wl)
@@ -265,8 +270,7 @@ def main():
     # (the partial last batch of an epoch included), so the work figure is averaged the same way. ----------
     mean_rows = rows_done / args.steps
     work, unit, bound, peak = kernel_work(wl, kernel, mean_rows, u_last * mean_rows / wl.rows_per_batch, fused)
-    kernel_note = ("two launches per step with different work: work and time are both means over the two"
-                   if kernel == "k_seg_reduce" and wl.model in ("transh", "transr") else "")
+    kernel_note = ""
     per_launch = kernel_n / args.steps if args.steps else 0
     achieved = (work / (kernel_us * 1e-6)) / (1e9 if unit == "GB/s" else 1e12) if kernel_us > 0 else 0.0
     roofline = {"bound": bound, "kernel": kernel, "achieved": round(achieved, 1), "peak": peak, "unit": unit,
