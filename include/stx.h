@@ -182,10 +182,9 @@ stx_status stx_sgd_step(stx_ctx *ctx, stx_params *p, const stx_incidence *inc, c
 
 /* stx_backward and stx_sgd_step in one call, with the same results in the tables (the paper counts the
  * optimiser step as part of the training loop, Table 1; fusing it with Appendix G's transposed product is
- * this library's choice).  TransE / TorusE: the update is applied where the transposed product would
- * store a gradient row, so the gradient rows are never written: g may be null and, if given, is left
- * untouched.  TransH / TransR: the two calls are made one after the other and g (required) receives
- * the gradients.  Needs the stx_forward of the same incidence immediately before it.                  */
+ * this library's choice).  The update is applied where the transposed products (and TransR's product for
+ * dL/dM_r) would store a gradient, so no gradient is written: g may be null and, if given, is left
+ * untouched.  Needs the stx_forward of the same incidence immediately before it.                       */
 stx_status stx_backward_sgd(stx_ctx *ctx, const stx_incidence *inc, stx_params *p, stx_grads *g, float lr);
 
 /* One training step in one call.  The batch's positives plus what stx_sample_negatives needs to draw its

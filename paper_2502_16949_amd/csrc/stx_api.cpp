@@ -395,6 +395,43 @@ stx_status stx_forward(stx_ctx *ctx, const stx_incidence *inc, const stx_params 
     return s;
 }
 
+// The backward pass.  lr == nullptr: gradients go to g.  Otherwise the update is applied where a
+// gradient would be stored and g is not touched (it may be null).
+static stx_status run_backward(stx_ctx *ctx, const stx_incidence *inc, const stx_params *p, stx_grads *g,
+                               const float *lr)
+{
+    const int dim = ctx->cfg.dim;
+    const int64_t ent_end = 2 * inc->n_rows;   // sorted entries of entity columns come first, then relation columns
+    float *rows = lr ? nullptr : g->rows;
+    if (stacked(ctx)) {   // dL/dX = A^T G over all columns of X = [E;R] (Appendix G)
+        const bool pk = packed_grad(ctx);
+        const SegFusedHost fh{p->ent, nullptr, 0x7fffffff, lr ? *lr : 0.f, ctx->cfg.model == STX_TORUSE ? 1 : 0};
+        return launch_seg_reduce(ctx, inc, 0, inc->nnz, ctx->gbuf[0], ctx->gbuf[0], inc->nnz,
+                                 pk ? packed_stride(dim) : dim, dim, rows, ctx->ld, pk, lr ? &fh : nullptr);
+    }
+    const SegFusedHost fh{p->ent, p->rel, (int32_t)ctx->cfg.n_ent, lr ? *lr : 0.f, 0};
+    if (ctx->cfg.model == STX_TRANSH) {
+        // entity columns: signed sums of gx; relation columns: sums of gy (-> d_r) and of gw (-> w_r)
+        // (both products in the same pair of launches)
+        const SegSecondHost second{(int32_t)ent_end, (int32_t)inc->nnz, ctx->gbuf[2], lr ? nullptr : g->w_rows, p->w,
+                                   (ctx->cfg.flags & STX_FLAG_RENORM_W) ? 2 : 0};
+        return launch_seg_reduce(ctx, inc, 0, inc->nnz, ctx->gbuf[0], ctx->gbuf[1], ent_end, dim, dim, rows, ctx->ld,
+                                 false, lr ? &fh : nullptr, &second);
+    }
+    // TransR: gx = M_r^T gy and dL/dM_r on the matrix cores, then entity columns sum gx (signed, width dim)
+    // and relation columns sum gy (width rel_dim)
+    stx_status s = launch_transr_backward(ctx, inc, p, g, lr);
+    if (s != STX_OK) return s;
+    if (dim == ctx->cfg.rel_dim)   // rows of equal width: one product over all columns, as for TransH
+        return launch_seg_reduce(ctx, inc, 0, inc->nnz, ctx->gbuf[1], ctx->gbuf[0], ent_end, dim, dim, rows, ctx->ld,
+                                 false, lr ? &fh : nullptr);
+    s = launch_seg_reduce(ctx, inc, 0, ent_end, ctx->gbuf[1], ctx->gbuf[1], ent_end, dim, dim, rows, ctx->ld, false,
+                          lr ? &fh : nullptr);
+    if (s != STX_OK) return s;
+    return launch_seg_reduce(ctx, inc, ent_end, inc->nnz, ctx->gbuf[0], ctx->gbuf[0], inc->nnz, ctx->cfg.rel_dim,
+                             ctx->cfg.rel_dim, rows, ctx->ld, false, lr ? &fh : nullptr);
+}
+
 stx_status stx_backward(stx_ctx *ctx, const stx_incidence *inc, const stx_params *p, stx_grads *g)
 {
     if (!ctx) return STX_ERR_NULL;
@@ -406,32 +443,7 @@ stx_status stx_backward(stx_ctx *ctx, const stx_incidence *inc, const stx_params
     if (ctx->cfg.model == STX_TRANSH && !g->w_rows) return STX_ERR_NULL;
     if (ctx->cfg.model == STX_TRANSR && !g->proj) return STX_ERR_NULL;
     if (ctx->fwd_inc != inc || ctx->fwd_rows != inc->n_rows) return STX_ERR_STATE;
-    const int dim = ctx->cfg.dim;
-    const int64_t ent_end = 2 * inc->n_rows;   // sorted entries of entity columns come first, then relation columns
-    if (stacked(ctx)) {   // dL/dX = A^T G over all columns of X = [E;R] (Appendix G)
-        if (packed_grad(ctx))
-            return launch_seg_reduce(ctx, inc, 0, inc->nnz, ctx->gbuf[0], ctx->gbuf[0], inc->nnz, packed_stride(dim),
-                                     dim, g->rows, ctx->ld, true);
-        return launch_seg_reduce(ctx, inc, 0, inc->nnz, ctx->gbuf[0], ctx->gbuf[0], inc->nnz, dim, dim, g->rows,
-                                 ctx->ld);
-    }
-    if (ctx->cfg.model == STX_TRANSH) {
-        // entity columns: signed sums of gx; relation columns: sums of gy (-> d_r) and of gw (-> w_r)
-        // (both products in the same pair of launches)
-        const SegSecondHost second{(int32_t)ent_end, (int32_t)inc->nnz, ctx->gbuf[2], g->w_rows};
-        return launch_seg_reduce(ctx, inc, 0, inc->nnz, ctx->gbuf[0], ctx->gbuf[1], ent_end, dim, dim, g->rows, ctx->ld,
-                                 false, nullptr, 0.f, 0, &second);
-    }
-    // TransR: gx = M_r^T gy and dL/dM_r on the matrix cores, then entity columns sum gx (signed, width dim)
-    // and relation columns sum gy (width rel_dim)
-    s = launch_transr_backward(ctx, inc, p, g);
-    if (s != STX_OK) return s;
-    if (dim == ctx->cfg.rel_dim)   // rows of equal width: one product over all columns, as for TransH
-        return launch_seg_reduce(ctx, inc, 0, inc->nnz, ctx->gbuf[1], ctx->gbuf[0], ent_end, dim, dim, g->rows, ctx->ld);
-    s = launch_seg_reduce(ctx, inc, 0, ent_end, ctx->gbuf[1], ctx->gbuf[1], ent_end, dim, dim, g->rows, ctx->ld);
-    if (s != STX_OK) return s;
-    return launch_seg_reduce(ctx, inc, ent_end, inc->nnz, ctx->gbuf[0], ctx->gbuf[0], inc->nnz, ctx->cfg.rel_dim,
-                             ctx->cfg.rel_dim, g->rows, ctx->ld);
+    return run_backward(ctx, inc, p, g, nullptr);
 }
 
 stx_status stx_sgd_step(stx_ctx *ctx, stx_params *p, const stx_incidence *inc, const stx_grads *g, float lr)
@@ -465,11 +477,6 @@ stx_status stx_sgd_step(stx_ctx *ctx, stx_params *p, const stx_incidence *inc, c
 stx_status stx_backward_sgd(stx_ctx *ctx, const stx_incidence *inc, stx_params *p, stx_grads *g, float lr)
 {
     if (!ctx) return STX_ERR_NULL;
-    if (!stacked(ctx)) {
-        stx_status s = stx_backward(ctx, inc, p, g);
-        if (s != STX_OK) return s;
-        return stx_sgd_step(ctx, p, inc, g, lr);
-    }
     stx_status s = check_built(ctx, inc);
     if (s != STX_OK) return s;
     s = check_params(ctx, p);
@@ -477,10 +484,7 @@ stx_status stx_backward_sgd(stx_ctx *ctx, const stx_incidence *inc, stx_params *
     if (!(lr == lr)) return STX_ERR_BAD_ARG;
     if (ctx->fwd_inc != inc || ctx->fwd_rows != inc->n_rows) return STX_ERR_STATE;
     ctx->fwd_inc = nullptr;   // the tables change: a stored forward no longer matches them
-    const int dim = ctx->cfg.dim;
-    const bool pk = packed_grad(ctx);
-    return launch_seg_reduce(ctx, inc, 0, inc->nnz, ctx->gbuf[0], ctx->gbuf[0], inc->nnz, pk ? packed_stride(dim) : dim,
-                             dim, nullptr, ctx->ld, pk, p->ent, lr, ctx->cfg.model == STX_TORUSE ? 1 : 0);
+    return run_backward(ctx, inc, p, g, &lr);
 }
 
 stx_status stx_train_step(stx_ctx *ctx, const stx_batch *bt, stx_incidence *inc, stx_params *p, stx_grads *g, float lr,
@@ -497,7 +501,6 @@ stx_status stx_train_step(stx_ctx *ctx, const stx_batch *bt, stx_incidence *inc,
     s = check_params(ctx, p);
     if (s != STX_OK) return s;
     if (!scores || !loss) return STX_ERR_NULL;
-    if (!stacked(ctx) && (!g || !g->rows)) return STX_ERR_NULL;
     if (!(lr == lr)) return STX_ERR_BAD_ARG;
     inc->b = b;
     inc->k = k;

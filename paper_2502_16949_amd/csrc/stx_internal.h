@@ -129,19 +129,29 @@ stx_status launch_copy_f32(stx_ctx *, float *dst, const float *src, int64_t n);
 // out_rows[segment] = signed sum of source rows over the sorted entries [e_begin, e_end); entries
 // before `split` read src_a, the others src_b (both with ld_src floats per row, `width` of them used).
 // packed_src: src_a holds packed L1-kind records (see packed_stride), ld_src is the record size in bytes.
-// fused_table: if not null, no gradient row is written; row `column` of that table (rows of `width` floats)
-// becomes row - fused_lr * gradient instead (fused_mode 1: then its fractional part).
 // second: another product of the same row width over the entries [e_begin, e_end), all reading `src`, that
 // runs in the same two launches (its workgroups follow the first product's).
+// fused: no gradient row is written; the table row of the column (rows of `width` floats; `table` for
+// columns below n_split, row column - n_split of `table_b` for the others) becomes row - lr * gradient
+// instead (mode 1: then its fractional part; mode 2: then rescaled to unit length).  The second
+// product's columns all lie at or above n_split and update its own table in its own mode.
 struct SegSecondHost {
     int32_t e_begin, e_end;
     const float *src;
     float *out_rows;
+    float *fused_table;
+    int fused_mode;
+};
+struct SegFusedHost {
+    float *table, *table_b;
+    int32_t n_split;
+    float lr;
+    int mode;
 };
 stx_status launch_seg_reduce(stx_ctx *, const stx_incidence *, int64_t e_begin, int64_t e_end, const float *src_a,
                              const float *src_b, int64_t split, int ld_src, int width, float *out_rows, int ld_out,
-                             bool packed_src = false, float *fused_table = nullptr, float fused_lr = 0.f,
-                             int fused_mode = 0, const SegSecondHost *second = nullptr);
+                             bool packed_src = false, const SegFusedHost *fused = nullptr,
+                             const SegSecondHost *second = nullptr);
 struct SgdTables {
     float *table_a; int width_a; int mode_a;   // columns [0, n_split)
     int64_t n_split;
@@ -153,7 +163,9 @@ stx_status launch_sgd_rows(stx_ctx *, const stx_incidence *, const SgdTables &, 
 stx_status launch_forward_from_y(stx_ctx *, const stx_incidence *, const stx_params *, float *scores, float *loss);
 // stx_transr.hip
 stx_status launch_transr_project(stx_ctx *, const stx_incidence *, const stx_params *);
-stx_status launch_transr_backward(stx_ctx *, const stx_incidence *, const stx_params *, stx_grads *);
+// fused_lr: if not null, M_r <- M_r - lr * dL/dM_r is applied in place of the store of dL/dM_r (g may be null)
+stx_status launch_transr_backward(stx_ctx *, const stx_incidence *, const stx_params *, stx_grads *,
+                                  const float *fused_lr = nullptr);
 stx_status launch_transr_sgd_proj(stx_ctx *, const stx_incidence *, stx_params *, const stx_grads *, float lr);
 // stx_transh.hip
 stx_status launch_forward_transh(stx_ctx *, const stx_incidence *, const stx_params *, float *scores, float *loss);

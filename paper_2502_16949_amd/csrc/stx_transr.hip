@@ -309,6 +309,9 @@ struct DmArgs {
     const uint16_t *gyt, *xt;    // operand-order transposed tiles written by the row kernels
     float *g_proj, *partials;
     int d, k;
+    float *M;                    // fused update: M_r <- M_r - lr * dL/dM_r replaces the store of dL/dM_r
+    float lr;
+    int fused;
 };
 
 // dL/dM_r = sum over the rows i of relation r of bf16(gy_i) bf16(x_i)^T, x_i = E[h_i] - E[t_i].
@@ -358,17 +361,26 @@ __global__ __launch_bounds__(kThreads) void k_transr_dm(DmArgs p)
         }
     }
     const int64_t kd = (int64_t)p.k * p.d;
-    float *dst = slot < 0 ? p.g_proj + rel * kd : p.partials + slot * kd;
+    const bool update = slot < 0 && p.fused;             // the relation's only item: apply the step right here
+    float *dst = slot >= 0 ? p.partials + slot * kd : (update ? p.M + rel * kd : p.g_proj + rel * kd);
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi) {
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni) {
             if ((mi == 0 || m1) && (ni == 0 || n1)) {
                 const int j = 32 * (nt0 + ni) + l31;
+                float old[16];
+                if (update) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        old[v] = dst[(int64_t)(32 * (mt0 + mi) + 8 * (v >> 2) + 4 * kg + (v & 3)) * p.d + j];
+                }
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int a = 32 * (mt0 + mi) + 8 * (v >> 2) + 4 * kg + (v & 3);
-                    dst[(int64_t)a * p.d + j] = acc[mi][ni][v];
+                    float val = acc[mi][ni][v];
+                    if (update) { const float step = p.lr * val; val = old[v] - step; }
+                    dst[(int64_t)a * p.d + j] = val;
                 }
             }
         }
@@ -400,7 +412,14 @@ __global__ __launch_bounds__(kThreads) void k_transr_dm_fixup(DmArgs p)
         float4 v = ld4(src + (int64_t)u * kd);
         a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
     }
-    st4(p.g_proj + (int64_t)p.dm_items[2 * blockIdx.x].x * kd + idx, a);
+    const int64_t off = (int64_t)p.dm_items[2 * blockIdx.x].x * kd + idx;
+    if (p.fused) {
+        const float4 m = ld4(p.M + off);
+        const float s0 = p.lr * a.x, s1 = p.lr * a.y, s2 = p.lr * a.z, s3 = p.lr * a.w;
+        st4(p.M + off, make_float4(m.x - s0, m.y - s1, m.z - s2, m.w - s3));
+    } else {
+        st4(p.g_proj + off, a);
+    }
 }
 
 // M_r <- M_r - lr * dL/dM_r for every relation present in the batch: workgroup (r, y) looks relation r's
@@ -481,7 +500,8 @@ stx_status launch_transr_project(stx_ctx *c, const stx_incidence *inc, const stx
     return hip_ok(hipGetLastError());
 }
 
-stx_status launch_transr_backward(stx_ctx *c, const stx_incidence *inc, const stx_params *p, stx_grads *g)
+stx_status launch_transr_backward(stx_ctx *c, const stx_incidence *inc, const stx_params *p, stx_grads *g,
+                                  const float *fused_lr)
 {
     if (inc->n_rows == 0) return STX_OK;
     {
@@ -492,8 +512,9 @@ stx_status launch_transr_backward(stx_ctx *c, const stx_incidence *inc, const st
     DmArgs a;
     a.dm_items = (const int4 *)c->tr_dm_items; a.counts = c->tr_counts;
     a.gyt = c->tr_gyt; a.xt = c->tr_xt;
-    a.g_proj = g->proj; a.partials = c->gbuf[2];
+    a.g_proj = fused_lr ? nullptr : g->proj; a.partials = c->gbuf[2];
     a.d = c->cfg.dim; a.k = c->cfg.rel_dim;
+    a.M = p->proj; a.lr = fused_lr ? *fused_lr : 0.f; a.fused = fused_lr ? 1 : 0;
     const unsigned items = dm_items_max(c, inc->n_rows);
     {
         ProfScope prof(c, "k_transr_dm");
