@@ -198,7 +198,9 @@ struct RowsArgs {
 // Wavefront w: rows 32*(w/2).., column tiles w%2, w%2+2, ..
 // GX = false: Y[row]  = x . M_r^T + r_vec     (out width k, reduction over d)
 // GX = true : GX[row] = gy . M_r              (out width d, reduction over k)
-template <bool GX>
+// SMALL (both widths <= 128): all of the wavefront's M_r fragments are requested before the operand rows
+// are staged, so that their latency is hidden behind the gather instead of following it.
+template <bool GX, bool SMALL>
 __global__ __launch_bounds__(kThreads) void k_transr_rows(RowsArgs p, const float *__restrict__ gy,
                                                           float *__restrict__ out)
 {
@@ -208,6 +210,18 @@ __global__ __launch_bounds__(kThreads) void k_transr_rows(RowsArgs p, const floa
     const int4 item = p.items[blockIdx.x];                // the list is allocated for the launch bound: any index is readable
     if ((int32_t)blockIdx.x >= p.counts[0]) return;
     const int rel = item.x, begin = item.y, count = item.z;
+    const int l = tid & 63, w = tid >> 6, wr = w >> 1, wc = w & 1, l31 = l & 31, kg = l >> 5;
+    const int ntl = p.n_out >> 5, ntw = (ntl - wc + 1) >> 1, KS = p.n_red >> 4;
+    const uint16_t *Mb = p.Mb + (int64_t)rel * p.n_out * p.n_red;
+    uint4 bpre[SMALL ? 8 : 1][SMALL ? 2 : 1];
+    if (SMALL && 32 * wr < count) {
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+                if (ks < KS && q < ntw) bpre[ks][q] = ld16(Mb + ((int64_t)(ks * ntl + wc + 2 * q) * 64 + l) * 8);
+        }
+    }
     if (tid < 64) {
         int32_t row = -1, hh = 0, tt = 0;
         if (tid < count) {
@@ -260,14 +274,23 @@ __global__ __launch_bounds__(kThreads) void k_transr_rows(RowsArgs p, const floa
         }
     }
 
-    const int l = tid & 63, w = tid >> 6, wr = w >> 1, wc = w & 1, l31 = l & 31, kg = l >> 5;
     if (32 * wr >= count) return;                          // no barrier below
-    const int ntl = p.n_out >> 5, ntw = (ntl - wc + 1) >> 1, KS = p.n_red >> 4;
-    const uint16_t *Mb = p.Mb + (int64_t)rel * p.n_out * p.n_red;
     const uint16_t *arow = s_a + (32 * wr + l31) * stride + 8 * kg;
     floatx16 acc[kMaxNT];
 #pragma unroll
     for (int q = 0; q < kMaxNT; ++q) acc[q] = zero16();
+    if constexpr (SMALL) {
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            if (ks < KS) {
+                const uint4 a = *reinterpret_cast<const uint4 *>(arow + 16 * ks);
+#pragma unroll
+                for (int q = 0; q < 2; ++q)
+                    if (q < ntw)
+                        acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(a), as_frag(bpre[ks][q]), acc[q], 0, 0, 0);
+            }
+        }
+    } else
     for (int ks0 = 0; ks0 < KS; ks0 += 4) {
         uint4 a[4], b[4][kMaxNT];
 #pragma unroll
@@ -495,8 +518,12 @@ stx_status launch_transr_project(stx_ctx *c, const stx_incidence *inc, const stx
         hipLaunchKernelGGL(k_transr_prepare, dim3((unsigned)c->cfg.n_rel + 1), dim3(kThreads), 0, c->stream, a);
     }
     ProfScope prof(c, "k_transr_project");
-    hipLaunchKernelGGL(k_transr_rows<false>, dim3(row_items_max(c, inc->n_rows)), dim3(kThreads), 0, c->stream,
-                       rows_args(c, inc, p, false), (const float *)nullptr, c->gbuf[0]);
+    if (c->cfg.dim <= 128 && c->cfg.rel_dim <= 128)
+        hipLaunchKernelGGL((k_transr_rows<false, true>), dim3(row_items_max(c, inc->n_rows)), dim3(kThreads), 0,
+                           c->stream, rows_args(c, inc, p, false), (const float *)nullptr, c->gbuf[0]);
+    else
+        hipLaunchKernelGGL((k_transr_rows<false, false>), dim3(row_items_max(c, inc->n_rows)), dim3(kThreads), 0,
+                           c->stream, rows_args(c, inc, p, false), (const float *)nullptr, c->gbuf[0]);
     return hip_ok(hipGetLastError());
 }
 
@@ -506,8 +533,12 @@ stx_status launch_transr_backward(stx_ctx *c, const stx_incidence *inc, const st
     if (inc->n_rows == 0) return STX_OK;
     {
         ProfScope prof(c, "k_transr_gx");
-        hipLaunchKernelGGL(k_transr_rows<true>, dim3(row_items_max(c, inc->n_rows)), dim3(kThreads), 0, c->stream,
-                           rows_args(c, inc, p, true), c->gbuf[0], c->gbuf[1]);
+        if (c->cfg.dim <= 128 && c->cfg.rel_dim <= 128)
+            hipLaunchKernelGGL((k_transr_rows<true, true>), dim3(row_items_max(c, inc->n_rows)), dim3(kThreads), 0,
+                               c->stream, rows_args(c, inc, p, true), c->gbuf[0], c->gbuf[1]);
+        else
+            hipLaunchKernelGGL((k_transr_rows<true, false>), dim3(row_items_max(c, inc->n_rows)), dim3(kThreads), 0,
+                               c->stream, rows_args(c, inc, p, true), c->gbuf[0], c->gbuf[1]);
     }
     DmArgs a;
     a.dm_items = (const int4 *)c->tr_dm_items; a.counts = c->tr_counts;
