@@ -27,7 +27,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 # The kernel whose roofline is reported: the one with the largest share of GPU time in the
 # rocprofv3 kernel trace of the same command (profiles/).
-DOMINANT = {"mid": "k_fwd_scatter", "tiny": "k_fwd_scatter", "toruse": "k_seg_reduce", "transh": "k_fwdh_scatter",
+DOMINANT = {"mid": "k_seg_reduce", "tiny": "k_seg_reduce", "toruse": "k_seg_reduce", "transh": "k_fwdh_scatter",
             "transr": "k_transr_project"}
 # ... and when the step is made of the separate calls (--api fused | separate)
 DOMINANT_CALLS = {"mid": "k_seg_reduce", "tiny": "k_seg_reduce", "toruse": "k_seg_reduce", "transh": "k_forward_transh",
@@ -256,15 +256,17 @@ def main():
     # ---- untimed extra pass: where the time goes, call by call (events on the context's stream) ----
 
     n_ph = min(args.steps, 60)
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(n_ph)]
-    for i in range(n_ph):
-        step(args.warmup + args.steps + i, events[i])
-    torch.cuda.synchronize()
-    phase = np.zeros(5)
-    for ev in events:
-        for p in range(5):
-            phase[p] += ev[p].elapsed_time(ev[p + 1])
-    phase_us = phase / n_ph * 1e3
+    phase_us = None
+    if not one_call:   # the one-call step has no phases to separate: its per-kernel times are listed instead
+        events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(n_ph)]
+        for i in range(n_ph):
+            step(args.warmup + args.steps + i, events[i])
+        torch.cuda.synchronize()
+        phase = np.zeros(5)
+        for ev in events:
+            for p in range(5):
+                phase[p] += ev[p].elapsed_time(ev[p + 1])
+        phase_us = phase / n_ph * 1e3
 
     # ---- roofline of the dominant kernel.  The mean launch time covers every batch of the timed region
     # (the partial last batch of an epoch included), so the work figure is averaged the same way. ----------
@@ -300,16 +302,18 @@ def main():
                             if one_call else "sample negatives + build incidence + forward + " +
                             ("backward with fused sgd (stx_backward_sgd)" if fused else "backward + sgd")),
                    "api": args.api},
-        "phase_us_note": "an extra, untimed pass through the separate calls" if one_call else "",
-        "phase_us": {k: round(float(v), 2) for k, v in
-                     zip(("sample", "build", "forward", "backward_sgd" if fused else "backward", "sgd"), phase_us)},
         "host_enqueue_us_per_step": round(t_enq / args.steps * 1e6, 2),
         "touched_rows_last_step": u_last,
         "loss_last_step": loss_last,
         "roofline": roofline,
     }
 
-    if args.all_kernels:
+    if phase_us is not None:
+        out["phase_us"] = {k: round(float(v), 2) for k, v in
+                           zip(("sample", "build", "forward", "backward_sgd" if fused else "backward", "sgd"), phase_us)}
+    if args.all_kernels or one_call:
+        # an extra, untimed pass with every kernel bracketed by events: [mean microseconds, launches per step]
+        # (each bracket adds about 2 us to what the kernel trace in profiles/ shows for the same kernel)
         B.stx_profile_kernel(ctx, "*", 40 * n_ph)
         for i in range(n_ph):
             step(args.warmup + args.steps + n_ph + i)
