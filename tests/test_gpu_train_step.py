@@ -55,7 +55,8 @@ def test_train_step_equals_the_separate_calls(model, dist, n_ent, n_rel, b, k, d
         ma.backward()
         ma.sgd(0.01)
         batch = B.make_batch(hd[lo:hi], rd[lo:hi], td[lo:hi], k, 99, 2, m_total, lo, nhb, ntb)
-        B.stx_train_step(mb.ctx, batch, mb.inc, mb.params, mb.grads, 0.01, mb.scores, mb.loss)
+        # no model needs gradient storage for the one-call step: given on the first batch only
+        B.stx_train_step(mb.ctx, batch, mb.inc, mb.params, mb.grads if step == 0 else None, 0.01, mb.scores, mb.loss)
         torch.cuda.synchronize()
         assert torch.equal(nha[:bb * k], nhb[:bb * k]) and torch.equal(nta[:bb * k], ntb[:bb * k])
         ia, ib = ma.incidence_numpy(), mb.incidence_numpy()
@@ -83,3 +84,35 @@ def test_train_step_without_gradient_storage_for_stacked_models():
     assert not torch.equal(before, m.params.ent) and float(m.loss.item()) > 0.0
     with pytest.raises(B.StxError):                                      # the step consumed its forward pass
         m.backward()
+
+
+@pytest.mark.parametrize("model,flags", [("transe", 0), ("transh", 0), ("transr", B.STX_FLAG_BF16_PROJ)])
+def test_train_step_empty_batch_changes_nothing(model, flags):
+    wl = W.Workload("case", 4, model, "l2", 200, 6, 100, 64, 64, 100, 1, 1.0, 0.01, 1, 0.0, 0.0, bool(flags))
+    tabs = W.make_tables(wl)
+    m = G.GpuModel(wl, tabs, flags=flags)
+    empty = torch.zeros(0, dtype=torch.int32, device=G.DEV)
+    neg = torch.zeros(1, dtype=torch.int32, device=G.DEV)
+    batch = B.make_batch(empty, empty, empty, 1, 7, 0, 100, 0, neg, neg)
+    m.loss.fill_(123.0)
+    B.stx_train_step(m.ctx, batch, m.inc, m.params, None, 0.01, m.scores, m.loss)
+    torch.cuda.synchronize()
+    assert float(m.loss.item()) == 0.0 and int(m.inc.n_touched.item()) == 0
+    for name in ("ent", "rel", "w", "proj"):
+        t = getattr(m.params, name)
+        assert t is None or np.array_equal(t.cpu().numpy(), tabs[name])
+
+
+def test_train_step_rejects_bad_arguments():
+    wl = W.Workload("case", 4, "transe", "l2", 200, 6, 100, 64, 64, 100, 1, 1.0, 0.01, 1, 0.0, 0.0)
+    m = G.GpuModel(wl, W.make_tables(wl))
+    h = torch.zeros(101, dtype=torch.int32, device=G.DEV)           # more positives than max_batch
+    neg = torch.zeros(101, dtype=torch.int32, device=G.DEV)
+    scores = torch.zeros(300, dtype=torch.float32, device=G.DEV)
+    with pytest.raises(B.StxError) as ei:
+        B.stx_train_step(m.ctx, B.make_batch(h, h, h, 1, 7, 0, 101, 0, neg, neg), m.inc, m.params, None, 0.01,
+                         scores, m.loss)
+    assert ei.value.status == B.STX_ERR_BAD_ARG
+    with pytest.raises(B.StxError):                                   # lr is NaN
+        B.stx_train_step(m.ctx, B.make_batch(h[:10], h[:10], h[:10], 1, 7, 0, 10, 0, neg, neg), m.inc, m.params, None,
+                         float("nan"), m.scores, m.loss)
