@@ -51,13 +51,25 @@ def test_mid_full_batch(which):
     diff = np.abs(new.astype(np.float64) - tb.ent)
     assert np.all(diff <= G.REL_TOL * (wl.lr * g.ent_abs + np.abs(tabs["ent"]) * 2.0**-23) + 2.0**-23)
     assert np.array_equal(new[touched == 0], tabs["ent"][touched == 0])
-    # the fused backward + update, as bench.py runs it: same bits as the two separate calls just checked
+    # the fused backward + update: same bits as the two separate calls just checked
     m2 = G.GpuModel(wl, tabs)
     B.stx_build_incidence(m2.ctx, hd[lo:hi], rd[lo:hi], td[lo:hi], nh, nt, wl.n_neg, m2.inc)
     m2.forward()
     m2.backward_sgd(wl.lr, with_grads=False)
     torch.cuda.synchronize()
     assert np.array_equal(m2.params.ent.cpu().numpy(), new)
+    # the one-call step, as bench.py runs it: negatives, incidence, scores, loss and table, all the same bits
+    m3 = G.GpuModel(wl, tabs)
+    nh3, nt3 = torch.empty_like(nh), torch.empty_like(nt)
+    batch = B.make_batch(hd[lo:hi], rd[lo:hi], td[lo:hi], wl.n_neg, W.negative_seed(wl), 0, wl.n_triplets, lo, nh3, nt3)
+    B.stx_train_step(m3.ctx, batch, m3.inc, m3.params, None, wl.lr, m3.scores, m3.loss)
+    torch.cuda.synchronize()
+    n = (hi - lo) * wl.n_neg
+    assert torch.equal(nh3[:n], nh[:n]) and torch.equal(nt3[:n], nt[:n])
+    G.check_incidence(m3.incidence_numpy(), stxo.build_incidence(bt, wl.n_ent, wl.n_rel))
+    s3, l3 = m3.scores_numpy()
+    assert np.array_equal(s3, scores) and l3 == loss
+    assert np.array_equal(m3.params.ent.cpu().numpy(), new)
 
 
 def test_toruse_large_full_batch_sampled():
@@ -102,12 +114,17 @@ def test_toruse_large_full_batch_sampled():
     sl = slice(1_000_000, 1_200_000)
     same = m.params.ent[sl].cpu().numpy() == tabs["ent"][sl]
     assert np.all(same[~touched[sl]])
-    # the fused backward + update, as bench.py runs it: the whole 2 GB table has the same bits as after the
-    # two separate calls, whose sampled rows were checked against the oracle above
+    # the one-call step, as bench.py runs it: negatives, scores, loss and the whole 2 GB table have the same
+    # bits as after the separate calls, whose results were checked against the oracle above
     ent_after = m.params.ent
     m2 = G.GpuModel(wl, tabs)
-    m2.build(bt)
-    m2.forward()
-    m2.backward_sgd(wl.lr, with_grads=False)
+    hd, rd, td = G.dev_i32(h[lo:hi]), G.dev_i32(r[lo:hi]), G.dev_i32(t[lo:hi])
+    nh2 = torch.empty((hi - lo) * wl.n_neg, dtype=torch.int32, device=G.DEV)
+    nt2 = torch.empty_like(nh2)
+    batch = B.make_batch(hd, rd, td, wl.n_neg, W.negative_seed(wl), 0, wl.n_triplets, lo, nh2, nt2)
+    B.stx_train_step(m2.ctx, batch, m2.inc, m2.params, None, wl.lr, m2.scores, m2.loss)
     torch.cuda.synchronize()
+    assert np.array_equal(nh2.cpu().numpy(), bt.nh) and np.array_equal(nt2.cpu().numpy(), bt.nt)
+    s2, l2 = m2.scores_numpy()
+    assert np.array_equal(s2, scores) and l2 == loss
     assert torch.equal(m2.params.ent, ent_after)
