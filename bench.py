@@ -8,7 +8,7 @@ walk the workload's batches in stored order, epoch after epoch (the last batch o
 partial).  Default workload: "mid" = TransE, d = 128, fp32, the configuration the headline metric is
 quoted on.
 
-Prints ONE JSON line; DESIGN.md derives the byte model behind "roofline".
+Prints ONE JSON line; kernel_work() below holds the byte model behind "roofline".
 """
 from __future__ import annotations
 
