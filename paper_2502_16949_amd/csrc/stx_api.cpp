@@ -14,7 +14,7 @@ inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 struct Layout {
     size_t ctrl, keys[2], pay[2], table, super, tile_heads, loss_partials, partials, gbuf[4], total;
     size_t tr_items, tr_dm_items, tr_counts, tr_m16, tr_m16t, tr_xt, tr_gyt;
-    size_t colmap;
+    size_t colmap, rel_cnt;
     int map_words;
     int64_t rows_max, nnz_max, cols_max;
     int ld, out_dim, ntiles_max, fwd_blocks_max, n_gbuf;
@@ -98,6 +98,7 @@ Layout make_layout(const stx_config *c)
         L.tr_m16t = take((size_t)c->n_rel * kd * 2);
         L.tr_xt = take((items + 1) * kProjRows * c->dim * 2);
         L.tr_gyt = take((items + 1) * kProjRows * c->rel_dim * 2);
+        L.rel_cnt = take((size_t)2 * c->n_rel * 4);
     }
     L.total = off;
     return L;
@@ -188,6 +189,13 @@ stx_status stx_create(const stx_config *cfg, void *workspace, size_t workspace_b
     c->tr_m16t = tr ? (uint16_t *)(base + L.tr_m16t) : nullptr;
     c->tr_xt = tr ? (uint16_t *)(base + L.tr_xt) : nullptr;
     c->tr_gyt = tr ? (uint16_t *)(base + L.tr_gyt) : nullptr;
+    const bool rc = tr && cfg->n_rel <= kRelCntMax;
+    c->rel_cnt[0] = rc ? (int32_t *)(base + L.rel_cnt) : nullptr;
+    c->rel_cnt[1] = rc ? c->rel_cnt[0] + cfg->n_rel : nullptr;
+    c->cnt_cur = 0;
+    c->cnt_ptr = nullptr;
+    c->cnt_inc = nullptr;
+    c->prep_inc = nullptr;
     c->fwd_inc = nullptr;
     c->fwd_rows = 0;
     c->sorted_inc = nullptr;
@@ -202,6 +210,7 @@ stx_status stx_create(const stx_config *cfg, void *workspace, size_t workspace_b
     c->colmap[1] = L.map_words ? c->colmap[0] + L.map_words : nullptr;
     s = launch_clear_ctrl(c);
     if (s == STX_OK) s = launch_clear_maps(c);
+    if (s == STX_OK) s = launch_clear_rel_counts(c);
     if (s != STX_OK) { delete c; return s; }
     *out = c;
     return STX_OK;

@@ -77,19 +77,31 @@ struct ColMap {
     int words;
 };
 
+// TransR: rows per relation of the batch, for the work-item lists of the projection products.  Two
+// buffers alternate like the bitmaps: a build adds into one and clears the other.
+struct RelCnt {
+    int32_t *cur, *other;
+    int n_rel;
+};
+
 // One thread per entry e = 3*row + slot of A.  Writes the CSR arrays and the sort keys (= column ids),
 // and the histogram of the first digit for this tile.
-template <int ITEMS, bool MAP, bool SAMPLE>
+template <int ITEMS, bool MAP, bool SAMPLE, bool RC>
 __global__ __launch_bounds__(kThreads) void k_emit(BatchPtrs bp, int32_t n_ent, int32_t n_rel, int32_t nnz,
                                                    int32_t *__restrict__ rowptr, int32_t *__restrict__ colidx,
                                                    float *__restrict__ vals, int32_t *__restrict__ keys,
                                                    int radix, int ntiles, int32_t *__restrict__ table,
-                                                   int32_t *__restrict__ ctrl, ColMap map)
+                                                   int32_t *__restrict__ ctrl, ColMap map, RelCnt rc)
 {
     __shared__ int32_t s_hist[256];
     __shared__ uint32_t s_map[MAP ? kMapMaxWords : 1];
+    __shared__ int32_t s_rc[RC ? kRelCntMax : 1];
     const int tid = threadIdx.x;
     s_hist[tid] = 0;
+    if (RC) {
+        for (int r = tid; r < rc.n_rel; r += kThreads) s_rc[r] = 0;
+        for (int r = (int)blockIdx.x * kThreads + tid; r < rc.n_rel; r += (int)gridDim.x * kThreads) rc.other[r] = 0;
+    }
     if (MAP) {
         for (int w = tid; w < map.words; w += kThreads) s_map[w] = 0u;
         for (int w = (int)blockIdx.x * kThreads + tid; w < map.words; w += (int)gridDim.x * kThreads) map.other[w] = 0u;
@@ -132,6 +144,7 @@ __global__ __launch_bounds__(kThreads) void k_emit(BatchPtrs bp, int32_t n_ent, 
             keys[e] = col;
             atomicAdd(&s_hist[col & (radix - 1)], 1);
             if (MAP) atomicOr(&s_map[col >> 5], 1u << (col & 31));
+            if (RC && slot == 1) atomicAdd(&s_rc[idx], 1);
         }
     }
     __syncthreads();
@@ -140,6 +153,12 @@ __global__ __launch_bounds__(kThreads) void k_emit(BatchPtrs bp, int32_t n_ent, 
         for (int w = tid; w < map.words; w += kThreads) {
             const uint32_t v = s_map[w];
             if (v) atomicOr(&map.cur[w], v);
+        }
+    }
+    if (RC) {
+        for (int r = tid; r < rc.n_rel; r += kThreads) {
+            const int32_t v = s_rc[r];
+            if (v) atomicAdd(&rc.cur[r], v);
         }
     }
 }
@@ -333,6 +352,15 @@ stx_status launch_clear_maps(stx_ctx *c)
     return hip_ok(hipGetLastError());
 }
 
+stx_status launch_clear_rel_counts(stx_ctx *c)
+{
+    if (!c->rel_cnt[0]) return STX_OK;
+    hipLaunchKernelGGL(k_clear_words, dim3(8), dim3(kThreads), 0, c->stream, (uint32_t *)c->rel_cnt[0],
+                       (int)(2 * c->cfg.n_rel));
+    c->cnt_cur = 0;
+    return hip_ok(hipGetLastError());
+}
+
 stx_status launch_sample(stx_ctx *c, const int32_t *h, const int32_t *t, int64_t m, int32_t k, uint64_t seed,
                          uint64_t base_ctr, int32_t *nh, int32_t *nt)
 {
@@ -352,6 +380,9 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
     hipStream_t s = c->stream;
     c->sorted_inc = nullptr;
     c->sorted_keys = nullptr;
+    c->cnt_inc = nullptr;
+    c->cnt_ptr = nullptr;
+    c->prep_inc = nullptr;
     if (b == 0) {
         hipLaunchKernelGGL(k_empty_incidence, dim3(1), dim3(64), 0, s, inc->a_rowptr, inc->at_seg_ptr,
                            inc->n_touched);
@@ -373,15 +404,26 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
     }
 
     int bits0 = c->sort_bits < c->digit_bits ? c->sort_bits : c->digit_bits;
+    const bool use_rc = c->rel_cnt[0] != nullptr;
+    RelCnt rc{nullptr, nullptr, 0};
+    if (use_rc) {
+        rc = RelCnt{c->rel_cnt[c->cnt_cur], c->rel_cnt[c->cnt_cur ^ 1], n_rel};
+        c->cnt_ptr = rc.cur;
+        c->cnt_inc = inc;
+        c->cnt_cur ^= 1;
+    }
     {
     ProfScope prof(c, "k_emit");
-#define STX_EMIT(I, M, S)                                                                                       \
-    hipLaunchKernelGGL((k_emit<I, M, S>), dim3(ntiles), dim3(kThreads), 0, s, bp, n_ent, n_rel, nnz, inc->a_rowptr, \
-                       inc->a_colidx, inc->a_vals, c->keys[0], 1 << bits0, ntiles, c->table, c->ctrl, map)
-#define STX_EMIT2(I, M) do { if (sample) STX_EMIT(I, M, true); else STX_EMIT(I, M, false); } while (0)
+#define STX_EMIT(I, M, S, R)                                                                                    \
+    hipLaunchKernelGGL((k_emit<I, M, S, R>), dim3(ntiles), dim3(kThreads), 0, s, bp, n_ent, n_rel, nnz,         \
+                       inc->a_rowptr, inc->a_colidx, inc->a_vals, c->keys[0], 1 << bits0, ntiles, c->table,     \
+                       c->ctrl, map, rc)
+#define STX_EMIT3(I, M, S) do { if (use_rc) STX_EMIT(I, M, S, true); else STX_EMIT(I, M, S, false); } while (0)
+#define STX_EMIT2(I, M) do { if (sample) STX_EMIT3(I, M, true); else STX_EMIT3(I, M, false); } while (0)
     if (items == kSortItems) { if (use_map) STX_EMIT2(kSortItems, true); else STX_EMIT2(kSortItems, false); }
     else                     { if (use_map) STX_EMIT2(2 * kSortItems, true); else STX_EMIT2(2 * kSortItems, false); }
 #undef STX_EMIT2
+#undef STX_EMIT3
 #undef STX_EMIT
     }
     const bool two_level = ntiles > kSelfScanTiles;
@@ -413,6 +455,8 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
 #define STX_SCATTER2(F, S) do { if (items == kSortItems) STX_SCATTER(F, S, kSortItems); else STX_SCATTER(F, S, 2 * kSortItems); } while (0)
         if (p == 0 && fusion && !two_level && items == kSortItems && launch_fwd_scatter(c, inc, fusion, sa)) {
             // the forward pass ran in the same launch
+        } else if (p == 0 && fusion && !two_level && items == kSortItems && launch_prep_scatter(c, inc, fusion->p, sa)) {
+            // TransR: the item lists and the bf16 copies of M_r were made in the same launch
         } else {
             ProfScope prof(c, "k_scatter");
             if (p == 0) { if (two_level) STX_SCATTER2(true, true); else STX_SCATTER2(true, false); }

@@ -17,6 +17,7 @@ constexpr int kSegTileMin = 64;        // fewest sorted entries a workgroup of t
 constexpr int kSuperTile = 32;         // sort tiles per group when the histogram table is scanned in two levels
 constexpr int kSelfScanTiles = 256;   // up to this many sort tiles, scatter workgroups scan the histograms themselves
 constexpr int kMapMaxWords = 2048;     // presence bitmap of the columns: kept when n_ent + n_rel <= 32 * this
+constexpr int kRelCntMax = 4096;       // TransR: rows per relation are counted while A is written when n_rel <= this
 constexpr int kMaxDim = 1024;
 constexpr int kMaxProjDim = 256;        // TransR: dim and rel_dim are multiples of 32 up to this
 constexpr int kProjRows = 64;           // TransR: entries of one relation per work item of the two row products
@@ -62,6 +63,11 @@ struct stx_ctx {
     // TransR only: work items, bfloat16 operand copies of the projection matrices, transposed operand tiles
     int32_t *tr_items, *tr_dm_items, *tr_counts;
     uint16_t *tr_m16, *tr_m16t, *tr_xt, *tr_gyt;
+    int32_t *rel_cnt[2];           // rows per relation of a batch (two buffers alternate, like the bitmaps), or null
+    int cnt_cur;
+    const int32_t *cnt_ptr;        // counts of the last build ...
+    const stx_incidence *cnt_inc;  // ... which was of this incidence
+    const stx_incidence *prep_inc; // incidence whose TransR preparation already ran beside its sort
     // optional live timing of one kernel (stx_profile_kernel): event pairs around its launches
     char prof_name[48];
     hipEvent_t *prof_ev;           // 2 * prof_cap events, null when profiling is off
@@ -116,11 +122,14 @@ struct SampleArgs {            // negatives drawn inside the build (same numbers
 stx_status launch_build(stx_ctx *, const int32_t *h, const int32_t *r, const int32_t *t, const int32_t *nh,
                         const int32_t *nt, int32_t b, int32_t k, stx_incidence *inc,
                         const SampleArgs *sample = nullptr, StepFusion *fusion = nullptr);
+// stx_transr.hip: item lists and bf16 copies of M_r in the launch of the first scatter pass; false: not possible
+bool launch_prep_scatter(stx_ctx *, const stx_incidence *, const stx_params *, const ScatterArgs &);
 // stx_step.hip
 bool launch_fwd_scatter(stx_ctx *, const stx_incidence *, StepFusion *, const ScatterArgs &);   // false: shape not covered
 void launch_hist_finish(stx_ctx *, StepFusion *, const int32_t *keys, int32_t nnz, int shift, int radix, int ntiles);
 stx_status launch_clear_ctrl(stx_ctx *);
 stx_status launch_clear_maps(stx_ctx *);
+stx_status launch_clear_rel_counts(stx_ctx *);
 // stx_forward.hip
 stx_status launch_spmm(stx_ctx *, const stx_incidence *, const stx_params *, float *c_out);
 stx_status launch_forward_stacked(stx_ctx *, const stx_incidence *, const stx_params *, float *scores, float *loss);

@@ -28,8 +28,7 @@
 // product, reduction over d; rows = output columns of GX, reduction over k) and for the transposed
 // tiles X^T and GY^T (rows = columns of x / gy, reduction over the 64 entries of an item) which the
 // row kernels leave behind for the dM product while they have the tile in LDS anyway.
-#include "stx_device.h"
-#include "stx_internal.h"
+#include "stx_sort_body.h"
 
 namespace stx {
 
@@ -64,45 +63,61 @@ struct PrepArgs {
     int4 *items, *dm_items;
     int32_t *counts;
     int d, k;
+    // Rows per relation in the batch, counted while A was written (null: not available).  With them
+    // neither the item lists nor the choice of the M_r to convert need the sorted A^T, so the whole
+    // preparation can run beside the sort instead of after it.
+    const int32_t *rel_cnt;
+    int32_t n_rel;
 };
 
 // Item lists of the relation segments (one workgroup).  Row item: {relation, first sorted entry,
 // entries (<= 64), 0}.  dM item, two int4: {relation, first row item, entries (<= 256), slot} and
 // {first slot of the segment, parts to add if this is the segment's last item else 0, 0, 0}; slot is
 // -1 when the segment has a single dM item, which then writes dL/dM_r itself.
+template <bool FROM_COUNTS>
 __device__ inline void transr_plan(const PrepArgs &p)
 {
     __shared__ int32_t s_o64[kThreads + 1], s_o256[kThreads + 1], s_op[kThreads], s_beg[kThreads], s_len[kThreads],
-        s_rel[kThreads], s_wave[kThreads / 64][3];
+        s_rel[kThreads], s_wave[kThreads / 64][4];
     const int tid = threadIdx.x;
-    const int32_t n_seg = p.n_touched[0];
-    int32_t base64 = 0, base256 = 0, basep = 0;
-    for (int32_t sb = p.seg_id[p.e_begin]; sb < n_seg; sb += kThreads) {
+    // the relations' lists, in the order of the sorted A^T: by touched segment, or by relation id with the
+    // counted rows (an absent relation has no rows and gets no item)
+    const int32_t first = FROM_COUNTS ? 0 : p.seg_id[p.e_begin], last = FROM_COUNTS ? p.n_rel : p.n_touched[0];
+    int32_t base64 = 0, base256 = 0, basep = 0, base_len = 0;
+    for (int32_t sb = first; sb < last; sb += kThreads) {
         const int32_t s = sb + tid;
         int32_t beg = 0, len = 0, rel = 0;
-        if (s < n_seg) {
-            beg = p.seg_ptr[s];
-            len = p.seg_ptr[s + 1] - beg;
-            rel = p.touched_cols[s] - p.n_ent;
+        if (s < last) {
+            if (FROM_COUNTS) {
+                len = p.rel_cnt[s];
+                rel = s;
+            } else {
+                beg = p.seg_ptr[s];
+                len = p.seg_ptr[s + 1] - beg;
+                rel = p.touched_cols[s] - p.n_ent;
+            }
         }
         const int32_t n64 = (len + 63) >> 6, n256 = (len + 255) >> 8;
-        // three exclusive scans across the workgroup at once: shuffles inside a wavefront, LDS across the four
-        int32_t inc3[3] = {n64, n256, n256 > 1 ? n256 : 0};
+        // four exclusive scans across the workgroup at once: shuffles inside a wavefront, LDS across the four
+        int32_t inc3[4] = {n64, n256, n256 > 1 ? n256 : 0, len};
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
 #pragma unroll
-            for (int q = 0; q < 3; ++q) {
+            for (int q = 0; q < 4; ++q) {
                 const int32_t up = __shfl_up(inc3[q], off);
                 if ((tid & 63) >= off) inc3[q] += up;
             }
         }
-        if ((tid & 63) == 63) { s_wave[tid >> 6][0] = inc3[0]; s_wave[tid >> 6][1] = inc3[1]; s_wave[tid >> 6][2] = inc3[2]; }
+        if ((tid & 63) == 63) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) s_wave[tid >> 6][q] = inc3[q];
+        }
         __syncthreads();
-        int32_t before[3] = {0, 0, 0}, tot[3] = {0, 0, 0};
+        int32_t before[4] = {0, 0, 0, 0}, tot[4] = {0, 0, 0, 0};
 #pragma unroll
         for (int ww = 0; ww < kThreads / 64; ++ww) {
 #pragma unroll
-            for (int q = 0; q < 3; ++q) {
+            for (int q = 0; q < 4; ++q) {
                 if (ww < (tid >> 6)) before[q] += s_wave[ww][q];
                 tot[q] += s_wave[ww][q];
             }
@@ -110,6 +125,7 @@ __device__ inline void transr_plan(const PrepArgs &p)
         const int32_t o64 = before[0] + inc3[0] - n64, o256 = before[1] + inc3[1] - n256,
                       op = before[2] + inc3[2] - (n256 > 1 ? n256 : 0);
         const int32_t t64 = tot[0], t256 = tot[1], tp = tot[2];
+        if (FROM_COUNTS) beg = p.e_begin + base_len + before[3] + inc3[3] - len;   // relation lists follow each other
         s_o64[tid] = o64; s_o256[tid] = o256; s_op[tid] = op;
         s_beg[tid] = beg; s_len[tid] = len; s_rel[tid] = rel;
         if (tid == 0) { s_o64[kThreads] = t64; s_o256[kThreads] = t256; }
@@ -134,26 +150,33 @@ __device__ inline void transr_plan(const PrepArgs &p)
                                                       min(256, s_len[lo] - 256 * li), parts > 1 ? first + li : -1);
             p.dm_items[2 * (base256 + w) + 1] = make_int4(first, (parts > 1 && li == parts - 1) ? parts : 0, 0, 0);
         }
-        base64 += t64; base256 += t256; basep += tp;
+        base64 += t64; base256 += t256; basep += tp; base_len += tot[3];
         __syncthreads();
     }
     if (tid == 0) { p.counts[0] = base64; p.counts[1] = base256; }
 }
 
 // Workgroup 0 builds the item lists; workgroup 1 + r writes the two bfloat16 operand-order copies of
-// M_r if relation r occurs in the batch (it looks its column up in the sorted touched list).
-__global__ __launch_bounds__(kThreads) void k_transr_prepare(PrepArgs p)
+// M_r if relation r occurs in the batch (known from the counted rows, else it looks its column up in
+// the sorted touched list).
+template <bool FROM_COUNTS>
+__device__ inline void transr_prepare_body(const int block, const PrepArgs &p)
 {
-    if (blockIdx.x == 0) { transr_plan(p); return; }
+    if (block == 0) { transr_plan<FROM_COUNTS>(p); return; }
     const int tid = threadIdx.x;
-    const int32_t r = (int32_t)blockIdx.x - 1, target = p.n_ent + r;
-    const int32_t n_seg = p.n_touched[0];
-    int32_t lo = p.seg_id[p.e_begin], hi = n_seg;         // relation columns sort after all entity columns
-    while (lo < hi) {                                     // first position with touched_cols[pos] >= target
-        const int32_t mid = (lo + hi) >> 1;
-        if (p.touched_cols[mid] < target) lo = mid + 1; else hi = mid;
+    const int32_t r = block - 1;
+    if (FROM_COUNTS) {
+        if (p.rel_cnt[r] == 0) return;
+    } else {
+        const int32_t target = p.n_ent + r;
+        const int32_t n_seg = p.n_touched[0];
+        int32_t lo = p.seg_id[p.e_begin], hi = n_seg;     // relation columns sort after all entity columns
+        while (lo < hi) {                                 // first position with touched_cols[pos] >= target
+            const int32_t mid = (lo + hi) >> 1;
+            if (p.touched_cols[mid] < target) lo = mid + 1; else hi = mid;
+        }
+        if (lo >= n_seg || p.touched_cols[lo] != target) return;
     }
-    if (lo >= n_seg || p.touched_cols[lo] != target) return;
     const int64_t kd = (int64_t)p.k * p.d;
     const float *__restrict__ M = p.M + r * kd;
     {   // forward operand: row a of M_r, reduction over j
@@ -180,6 +203,20 @@ __global__ __launch_bounds__(kThreads) void k_transr_prepare(PrepArgs p)
                 make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
         }
     }
+}
+
+template <bool FROM_COUNTS>
+__global__ __launch_bounds__(kThreads) void k_transr_prepare(PrepArgs p)
+{
+    transr_prepare_body<FROM_COUNTS>((int)blockIdx.x, p);
+}
+
+// stx_train_step: with the rows per relation counted while A was written, the preparation depends on
+// nothing the sort produces and shares the launch of its first scatter pass (whose workgroups come first).
+__global__ __launch_bounds__(kThreads) void k_prep_scatter(PrepArgs p, ScatterArgs sa)
+{
+    if ((int)blockIdx.x < sa.ntiles) scatter_body<true, false, kSortItems>((int)blockIdx.x, sa);
+    else transr_prepare_body<true>((int)blockIdx.x - sa.ntiles, p);
 }
 
 struct RowsArgs {
@@ -502,21 +539,45 @@ static int64_t max_segments(const stx_ctx *c, int64_t rows) { return rows < c->c
 static unsigned row_items_max(const stx_ctx *c, int64_t rows) { return (unsigned)(rows / 64 + max_segments(c, rows)); }
 static unsigned dm_items_max(const stx_ctx *c, int64_t rows) { return (unsigned)(rows / 256 + max_segments(c, rows)); }
 
+static PrepArgs prep_args(stx_ctx *c, const stx_incidence *inc, const stx_params *p)
+{
+    PrepArgs a;
+    a.touched_cols = inc->at_touched_cols; a.n_touched = inc->n_touched;
+    a.seg_ptr = inc->at_seg_ptr; a.seg_id = inc->at_seg_id;
+    a.n_ent = (int32_t)c->cfg.n_ent;
+    a.e_begin = (int32_t)(2 * inc->n_rows);               // relation columns follow the entity columns
+    a.M = p->proj; a.m16 = c->tr_m16; a.m16t = c->tr_m16t;
+    a.items = (int4 *)c->tr_items; a.dm_items = (int4 *)c->tr_dm_items; a.counts = c->tr_counts;
+    a.d = c->cfg.dim; a.k = c->cfg.rel_dim;
+    a.rel_cnt = c->cnt_inc == inc ? c->cnt_ptr : nullptr;  // the counts of the last build, if that was this incidence
+    a.n_rel = (int32_t)c->cfg.n_rel;
+    return a;
+}
+
+bool launch_prep_scatter(stx_ctx *c, const stx_incidence *inc, const stx_params *p, const ScatterArgs &sa)
+{
+    if (c->cfg.model != STX_TRANSR || inc->n_rows == 0) return false;
+    const PrepArgs a = prep_args(c, inc, p);
+    if (!a.rel_cnt) return false;
+    ProfScope prof(c, "k_prep_scatter");
+    hipLaunchKernelGGL(k_prep_scatter, dim3((unsigned)(sa.ntiles + c->cfg.n_rel + 1)), dim3(kThreads), 0, c->stream, a,
+                       sa);
+    c->prep_inc = inc;
+    return true;
+}
+
 stx_status launch_transr_project(stx_ctx *c, const stx_incidence *inc, const stx_params *p)
 {
     if (inc->n_rows == 0) return STX_OK;
-    {
-        PrepArgs a;
-        a.touched_cols = inc->at_touched_cols; a.n_touched = inc->n_touched;
-        a.seg_ptr = inc->at_seg_ptr; a.seg_id = inc->at_seg_id;
-        a.n_ent = (int32_t)c->cfg.n_ent;
-        a.e_begin = (int32_t)(2 * inc->n_rows);           // relation columns follow the entity columns
-        a.M = p->proj; a.m16 = c->tr_m16; a.m16t = c->tr_m16t;
-        a.items = (int4 *)c->tr_items; a.dm_items = (int4 *)c->tr_dm_items; a.counts = c->tr_counts;
-        a.d = c->cfg.dim; a.k = c->cfg.rel_dim;
+    if (c->prep_inc != inc) {   // not yet prepared beside the sort
+        const PrepArgs a = prep_args(c, inc, p);
         ProfScope prof(c, "k_transr_prepare");
-        hipLaunchKernelGGL(k_transr_prepare, dim3((unsigned)c->cfg.n_rel + 1), dim3(kThreads), 0, c->stream, a);
+        if (a.rel_cnt)
+            hipLaunchKernelGGL(k_transr_prepare<true>, dim3((unsigned)c->cfg.n_rel + 1), dim3(kThreads), 0, c->stream, a);
+        else
+            hipLaunchKernelGGL(k_transr_prepare<false>, dim3((unsigned)c->cfg.n_rel + 1), dim3(kThreads), 0, c->stream, a);
     }
+    c->prep_inc = nullptr;      // the copies of M_r are good for this forward pass only: the update changes M_r
     ProfScope prof(c, "k_transr_project");
     if (c->cfg.dim <= 128 && c->cfg.rel_dim <= 128)
         hipLaunchKernelGGL((k_transr_rows<false, true>), dim3(row_items_max(c, inc->n_rows)), dim3(kThreads), 0,
