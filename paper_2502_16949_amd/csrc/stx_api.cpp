@@ -196,6 +196,10 @@ stx_status stx_create(const stx_config *cfg, void *workspace, size_t workspace_b
     c->cnt_ptr = nullptr;
     c->cnt_inc = nullptr;
     c->prep_inc = nullptr;
+    c->defer_finish = false;
+    c->fin_n = 0;
+    c->fin_scale = 1.0f;
+    c->fin_loss = nullptr;
     c->fwd_inc = nullptr;
     c->fwd_rows = 0;
     c->sorted_inc = nullptr;
@@ -522,14 +526,22 @@ stx_status stx_train_step(stx_ctx *ctx, const stx_batch *bt, stx_incidence *inc,
     s = launch_build(ctx, bt->h, bt->r, bt->t, nullptr, nullptr, b, k, inc, &sa, &fusion);
     if (s != STX_OK) return s;
     if (!fusion.forward_done) {
+        ctx->defer_finish = ctx->cfg.model == STX_TRANSR;   // its loss sum rides in the backward pass's first launch
         s = stx_forward(ctx, inc, p, scores, loss);
+        ctx->defer_finish = false;
     } else {   // the forward pass shared a launch with the sort; the sum of the loss may still be missing
         if (!fusion.finish_done) s = launch_finish_loss(ctx, fusion.n_partials, fusion.scale, loss);
         ctx->fwd_inc = inc;
         ctx->fwd_rows = inc->n_rows;
     }
     if (s != STX_OK) return s;
-    return stx_backward_sgd(ctx, inc, p, g, lr);
+    s = stx_backward_sgd(ctx, inc, p, g, lr);
+    if (ctx->fin_n > 0) {   // nothing took the deferred loss sum along (or the backward pass failed)
+        const stx_status s2 = launch_finish_loss(ctx, ctx->fin_n, ctx->fin_scale, ctx->fin_loss);
+        ctx->fin_n = 0;
+        if (s == STX_OK) s = s2;
+    }
+    return s;
 }
 
 stx_status stx_copy_f32(stx_ctx *ctx, float *dst, const float *src, int64_t n)

@@ -120,7 +120,8 @@ static void forward_go(stx_ctx *c, const stx_incidence *inc, const stx_params *p
     }
 #undef STX_FWD2
 #undef STX_FWD
-    launch_finish_loss(c, (int)grid.x, scale, loss);
+    if (from_y && c->defer_finish) { c->fin_n = (int)grid.x; c->fin_scale = scale; c->fin_loss = loss; }
+    else launch_finish_loss(c, (int)grid.x, scale, loss);
 }
 
 stx_status launch_forward_stacked(stx_ctx *c, const stx_incidence *inc, const stx_params *p, float *scores,

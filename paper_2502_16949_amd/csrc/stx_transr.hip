@@ -28,6 +28,7 @@
 // product, reduction over d; rows = output columns of GX, reduction over k) and for the transposed
 // tiles X^T and GY^T (rows = columns of x / gy, reduction over the 64 entries of an item) which the
 // row kernels leave behind for the dM product while they have the tile in LDS anyway.
+#include "stx_forward_body.h"
 #include "stx_sort_body.h"
 
 namespace stx {
@@ -227,6 +228,11 @@ struct RowsArgs {
     const uint16_t *Mb;          // operand-order copies of M_r: n_out rows, reduction n_red
     uint16_t *tiles;             // per item: the 64-entry operand tile transposed, n_red rows in operand order
     int n_red, n_out;
+    // a deferred final sum of the loss that the launch's last workgroup takes along (fin_n == 0: none)
+    const float *fin_partials;
+    int fin_n;
+    float fin_scale;
+    float *fin_loss;
 };
 
 // One workgroup per row item.  The item's operand rows are staged in LDS as bfloat16 (forward:
@@ -244,6 +250,10 @@ __global__ __launch_bounds__(kThreads) void k_transr_rows(RowsArgs p, const floa
     __shared__ __attribute__((aligned(16))) uint16_t s_a[64 * (kMaxProjDim + kLdsPad)];
     __shared__ int32_t s_row[64], s_h[64], s_t[64];
     const int tid = threadIdx.x;
+    if (p.fin_n > 0 && blockIdx.x == gridDim.x - 1) {     // the extra workgroup of the launch
+        finish_loss_body(p.fin_partials, p.fin_n, p.fin_scale, p.fin_loss);
+        return;
+    }
     const int4 item = p.items[blockIdx.x];                // the list is allocated for the launch bound: any index is readable
     if ((int32_t)blockIdx.x >= p.counts[0]) return;
     const int rel = item.x, begin = item.y, count = item.z;
@@ -530,6 +540,7 @@ static RowsArgs rows_args(stx_ctx *c, const stx_incidence *inc, const stx_params
     a.tiles = gx ? c->tr_gyt : c->tr_xt;
     a.n_red = gx ? c->cfg.rel_dim : c->cfg.dim;
     a.n_out = gx ? c->cfg.dim : c->cfg.rel_dim;
+    a.fin_partials = nullptr; a.fin_n = 0; a.fin_scale = 1.0f; a.fin_loss = nullptr;
     return a;
 }
 
@@ -593,13 +604,20 @@ stx_status launch_transr_backward(stx_ctx *c, const stx_incidence *inc, const st
 {
     if (inc->n_rows == 0) return STX_OK;
     {
+        RowsArgs ra = rows_args(c, inc, p, true);
+        unsigned blocks = row_items_max(c, inc->n_rows);
+        if (c->fin_n > 0) {
+            ra.fin_partials = c->loss_partials; ra.fin_n = c->fin_n; ra.fin_scale = c->fin_scale; ra.fin_loss = c->fin_loss;
+            c->fin_n = 0;
+            ++blocks;
+        }
         ProfScope prof(c, "k_transr_gx");
         if (c->cfg.dim <= 128 && c->cfg.rel_dim <= 128)
-            hipLaunchKernelGGL((k_transr_rows<true, true>), dim3(row_items_max(c, inc->n_rows)), dim3(kThreads), 0,
-                               c->stream, rows_args(c, inc, p, true), c->gbuf[0], c->gbuf[1]);
+            hipLaunchKernelGGL((k_transr_rows<true, true>), dim3(blocks), dim3(kThreads), 0, c->stream, ra, c->gbuf[0],
+                               c->gbuf[1]);
         else
-            hipLaunchKernelGGL((k_transr_rows<true, false>), dim3(row_items_max(c, inc->n_rows)), dim3(kThreads), 0,
-                               c->stream, rows_args(c, inc, p, true), c->gbuf[0], c->gbuf[1]);
+            hipLaunchKernelGGL((k_transr_rows<true, false>), dim3(blocks), dim3(kThreads), 0, c->stream, ra, c->gbuf[0],
+                               c->gbuf[1]);
     }
     DmArgs a;
     a.dm_items = (const int4 *)c->tr_dm_items; a.counts = c->tr_counts;
