@@ -108,28 +108,40 @@ __global__ __launch_bounds__(kThreads) void k_emit(BatchPtrs bp, int32_t n_ent, 
     }
     __syncthreads();
     const int32_t base = blockIdx.x * (kThreads * ITEMS);
+    // First every index of the thread's entries is fetched (the loads of all items are in flight together:
+    // a store in between would order them one after the other), then the entries are written.
+    int32_t raw[ITEMS];
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+        const int32_t e = base + it * kThreads + tid;
+        raw[it] = 0;
+        if (e < nnz) {
+            const int32_t row = e / 3, slot = e - 3 * row;
+            if (row < bp.b) {
+                raw[it] = slot == 0 ? bp.h[row] : (slot == 1 ? bp.r[row] : bp.t[row]);
+            } else if (SAMPLE) {   // the positive's side that a negative may keep; the draw decides below
+                const int32_t i = (row - bp.b) / bp.k;
+                raw[it] = slot == 0 ? bp.h[i] : (slot == 1 ? bp.r[i] : bp.t[i]);
+            } else {
+                const int32_t j = row - bp.b;
+                raw[it] = slot == 0 ? bp.nh[j] : (slot == 1 ? bp.r[j / bp.k] : bp.nt[j]);
+            }
+        }
+    }
 #pragma unroll
     for (int it = 0; it < ITEMS; ++it) {
         int32_t e = base + it * kThreads + tid;
         if (e < nnz) {
             int32_t row = e / 3, slot = e - 3 * row;
-            int32_t idx;
-            if (row < bp.b) {
-                idx = slot == 0 ? bp.h[row] : (slot == 1 ? bp.r[row] : bp.t[row]);
-            } else if (SAMPLE) {
-                const int32_t j = row - bp.b, i = j / bp.k;
-                if (slot == 1) {
-                    idx = bp.r[i];
-                } else {   // the three threads of a row draw the same number; slots 0 and 2 store their side
-                    const uint64_t u = splitmix64_at(bp.seed, bp.base_ctr + (uint64_t)j);
-                    const int32_t ent = (int32_t)(((u & 0xFFFFFFFFull) * (uint64_t)n_ent) >> 32);
-                    const bool head = (u >> 63) != 0;
-                    if (slot == 0) { idx = head ? ent : bp.h[i]; bp.nh_out[j] = idx; }
-                    else           { idx = head ? bp.t[i] : ent; bp.nt_out[j] = idx; }
-                }
-            } else {
-                int32_t j = row - bp.b;
-                idx = slot == 0 ? bp.nh[j] : (slot == 1 ? bp.r[j / bp.k] : bp.nt[j]);
+            int32_t idx = raw[it];
+            if (SAMPLE && row >= bp.b && slot != 1) {
+                // the three threads of a row draw the same number; slots 0 and 2 store their side
+                const int32_t j = row - bp.b;
+                const uint64_t u = splitmix64_at(bp.seed, bp.base_ctr + (uint64_t)j);
+                const int32_t ent = (int32_t)(((u & 0xFFFFFFFFull) * (uint64_t)n_ent) >> 32);
+                const bool head = (u >> 63) != 0;
+                if (slot == 0) { idx = head ? ent : idx; bp.nh_out[j] = idx; }
+                else           { idx = head ? idx : ent; bp.nt_out[j] = idx; }
             }
             int32_t lim = slot == 1 ? n_rel : n_ent;
             if (idx < 0 || idx >= lim) {           // clamp so nothing downstream reads outside a table

@@ -18,10 +18,16 @@ __device__ inline void hist_body(const int block, const int32_t *__restrict__ ke
     s_hist[tid] = 0;
     __syncthreads();
     const int32_t base = block * (kThreads * ITEMS);
+    int32_t kv[ITEMS];                                   // all loads first, so that they are in flight together
 #pragma unroll
     for (int it = 0; it < ITEMS; ++it) {
-        int32_t e = base + it * kThreads + tid;
-        if (e < nnz) atomicAdd(&s_hist[(keys[e] >> shift) & (radix - 1)], 1);
+        const int32_t e = base + it * kThreads + tid;
+        kv[it] = e < nnz ? keys[e] : 0;
+    }
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+        const int32_t e = base + it * kThreads + tid;
+        if (e < nnz) atomicAdd(&s_hist[(kv[it] >> shift) & (radix - 1)], 1);
     }
     __syncthreads();
     if (tid < radix) table[block * radix + tid] = s_hist[tid];
@@ -121,11 +127,16 @@ __device__ inline void scatter_body(const int block, const ScatterArgs &a)
     const int32_t wave_base = block * (kThreads * ITEMS) + w * (64 * ITEMS);
     const uint64_t below = (1ull << lane) - 1ull;
 #pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {                 // all loads first, so that they are in flight together
+        const int32_t e = wave_base + it * 64 + lane;
+        const bool valid = e < nnz;
+        key[it] = valid ? keys_in[e] : 0;
+        pay[it] = FIRST ? e : (valid ? pay_in[e] : 0);
+    }
+#pragma unroll
     for (int it = 0; it < ITEMS; ++it) {
         int32_t e = wave_base + it * 64 + lane;
         bool valid = e < nnz;
-        key[it] = valid ? keys_in[e] : 0;
-        pay[it] = FIRST ? e : (valid ? pay_in[e] : 0);
         int dgt = (key[it] >> shift) & (radix - 1);
         uint64_t m = __ballot(valid);
         for (int bit = 0; bit < bits; ++bit) {
