@@ -368,7 +368,7 @@ stx_status stx_check_indices(stx_ctx *ctx, int64_t *n_bad)
     if (hipStreamSynchronize(ctx->stream) != hipSuccess) return STX_ERR_HIP;
     if (n_bad) *n_bad = bad;
     if (bad) {
-        stx_status s = launch_clear_ctrl(ctx);   // tickets are zero between calls, so clearing all words is safe
+        stx_status s = launch_clear_ctrl(ctx);   // the block holds nothing but this counter
         if (s != STX_OK) return s;
         return STX_ERR_INDEX_RANGE;
     }

@@ -7,11 +7,15 @@
 // contiguous and in a unique order, which is what lets the backward product run without atomics.
 //
 // Launch sequence for one batch (P = number of digit passes, 1..4):
-//   k_emit            keys + CSR arrays + tile histograms of digit 0
+//   k_emit            keys + CSR arrays + tile histograms of digit 0 (+ the negatives, when they are drawn
+//                     here; + a presence bitmap of the columns when the table has few enough of them;
+//                     + rows per relation for TransR)
 //   k_scatter  x P    stable scatter by digit p
 //   k_hist     x P-1  tile histograms of digit p (between scatters)
-//   k_seg_count       segment heads per tile
+//   k_seg_count       segment heads per tile (only without the presence bitmap)
 //   k_seg_write       touched_cols, seg_ptr, row_idx, sign, seg_id, packed, U
+// stx_train_step lets independent work of the step share the launches of the first scatter pass and of
+// the following histogram pass (stx_step.hip, stx_transr.hip).
 // The tile histograms (tile-major table[tile][digit]) must become global offsets before a scatter.
 // With few tiles every scatter workgroup derives its own offsets from the raw table (a few coalesced
 // reads per thread); with many tiles a small k_super_sums first adds the histograms up in groups of tiles.
