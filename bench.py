@@ -28,10 +28,12 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # The kernel whose roofline is reported: the one with the largest share of GPU time in the
 # rocprofv3 kernel trace of the same command (profiles/).
 DOMINANT = {"mid": "k_seg_reduce", "tiny": "k_seg_reduce", "toruse": "k_seg_reduce", "transh": "k_fwdh_scatter",
-            "transr": "k_transr_project"}
+            "transr": "k_transr_project", "paper_transe": "k_seg_reduce", "paper_toruse": "k_seg_reduce",
+            "paper_transr": "k_transr_project"}
 # ... and when the step is made of the separate calls (--api fused | separate)
 DOMINANT_CALLS = {"mid": "k_seg_reduce", "tiny": "k_seg_reduce", "toruse": "k_seg_reduce", "transh": "k_forward_transh",
-                  "transr": "k_transr_project"}
+                  "transr": "k_transr_project", "paper_transe": "k_seg_reduce", "paper_toruse": "k_seg_reduce",
+                  "paper_transr": "k_transr_project"}
 
 
 # HBM bytes per launch of those kernels, measured: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (separate runs),
@@ -56,7 +58,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--config", default="mid", help="workload: tiny | mid | transh | transr | toruse")
+    ap.add_argument("--config", default="mid", help="workload: tiny | mid | transh | transr | toruse | paper_transe | paper_toruse | paper_transr")
     ap.add_argument("--kernel", default=None, help="kernel to time for the roofline entry (default: the dominant one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--api", default="step", choices=["step", "fused", "separate"],

@@ -59,6 +59,15 @@ WORKLOADS = {
                        20, 1.1, 1.3, True),
     "toruse": Workload("toruse", 5, "toruse", "torus_l1", 4_000_000, 1_000, 20_000_000, 128, 128, 262_144,
                        4, 1.0, 0.01, 1, 1.05, 1.2),
+    # The paper's own training shapes (Sec. 5.3: embedding 1024 and batch 12 x 32,768 for TransE / TorusE, 128 and
+    # 2 x 32,768 for TransR; L2 or L2-torus dissimilarity, margin 0.5, learning rate 0.0004, one pre-generated
+    # negative per positive) on a graph with the sizes of FB15k's training split (Table 3).
+    "paper_transe": Workload("paper_transe", 6, "transe", "l2", 14_951, 1_345, 483_142, 1_024, 1_024, 393_216, 1,
+                             0.5, 0.0004, 1, 1.1, 1.3),
+    "paper_toruse": Workload("paper_toruse", 7, "toruse", "torus_l2", 14_951, 1_345, 483_142, 1_024, 1_024, 393_216,
+                             1, 0.5, 0.0004, 1, 1.1, 1.3),
+    "paper_transr": Workload("paper_transr", 8, "transr", "l2", 14_951, 1_345, 483_142, 128, 128, 65_536, 1, 0.5,
+                             0.0004, 1, 1.1, 1.3, True),
 }
 
 

@@ -14,9 +14,12 @@ from tests.util import oracle_batch, oracle_config, oracle_tables
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("which", ["first", "last_partial"])
-def test_mid_full_batch(which):
-    wl = W.WORKLOADS["mid"]
+@pytest.mark.parametrize("name,which", [("mid", "first"), ("mid", "last_partial"), ("paper_transe", "first"),
+                                        ("paper_toruse", "last_partial")])
+def test_stacked_config_full_batch(name, which):
+    """"mid", and the paper's own training shape (d = 1024, 393,216 positives per batch): every score, every
+    gradient row and the whole updated table against the oracle."""
+    wl = W.WORKLOADS[name]
     h, r, t = W.make_graph(wl)
     tabs = W.make_tables(wl)
     lo, hi = W.batch_slices(wl)[0 if which == "first" else -1]
@@ -44,11 +47,14 @@ def test_mid_full_batch(which):
     G.check_grad_rows(cols, rows, g.ent, g.ent_abs, wl.dim)
     tb = oracle_tables(tabs)
     touched, _ = stxo.touched_masks(cfg, bt)
-    stxo.sgd(tb.ent, g.ent, touched, wl.lr, 0)
+    stxo.sgd(tb.ent, g.ent, touched, wl.lr, 1 if wl.model == "toruse" else 0)
     m.sgd(wl.lr)
     torch.cuda.synchronize()
     new = m.params.ent.cpu().numpy()
     diff = np.abs(new.astype(np.float64) - tb.ent)
+    if wl.model == "toruse":
+        diff = np.minimum(diff, 1.0 - diff)                              # distance on the circle
+        assert new.min() >= 0.0 and new.max() < 1.0
     assert np.all(diff <= G.REL_TOL * (wl.lr * g.ent_abs + np.abs(tabs["ent"]) * 2.0**-23) + 2.0**-23)
     assert np.array_equal(new[touched == 0], tabs["ent"][touched == 0])
     # the fused backward + update: same bits as the two separate calls just checked

@@ -107,9 +107,9 @@ def test_transr_step_matches_oracle(dist, n_ent, n_rel, b, k, dim, rel_dim, zipf
     check_transr_step(wl, tabs, bt, reduce)
 
 
-@pytest.mark.parametrize("which", ["first", "last_partial"])
-def test_transr_config_full_batch(which):
-    wl = W.WORKLOADS["transr"]
+@pytest.mark.parametrize("name,which", [("transr", "first"), ("transr", "last_partial"), ("paper_transr", "first")])
+def test_transr_config_full_batch(name, which):
+    wl = W.WORKLOADS[name]
     h, r, t = W.make_graph(wl)
     tabs = W.make_tables(wl)
     lo, hi = W.batch_slices(wl)[0 if which == "first" else -1]
