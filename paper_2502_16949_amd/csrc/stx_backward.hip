@@ -85,9 +85,9 @@ struct FusedArgs {             // the update that replaces the store of a gradie
     int mode;                  // 0 plain, 1 keep the fractional part (TorusE, Sec. 4.6), 2 rescale to unit length
     int stream;                // tables far larger than the caches: updated rows bypass them on the way out
 };
-__device__ inline float *fused_row(const FusedArgs &fu, int32_t col, int d4)
+__device__ inline float *fused_row(const FusedArgs &fu, int32_t col, int ld_tab)
 {
-    return col < fu.n_split ? fu.table + (int64_t)col * d4 * 4 : fu.table_b + (int64_t)(col - fu.n_split) * d4 * 4;
+    return col < fu.n_split ? fu.table + (int64_t)col * ld_tab : fu.table_b + (int64_t)(col - fu.n_split) * ld_tab;
 }
 
 // A second, independent transposed product that shares the launch (TransH: the sums of gw over the
@@ -165,6 +165,20 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
         out_rows = sec.out_rows; partials = sec.partials;
         fu.table_b = sec.fused_table; fu.mode = sec.fused_mode;
     }
+    // A row wider than the lanes of a group cover at once can be cut into slices of LPR float4, one per
+    // blockIdx.y: every pointer moves to the slice's first column and the width shrinks to the slice.
+    const int ld_tab = d4 * 4;                             // floats per table row (fused update)
+    int pk_off = 0;                                        // packed records: sign byte of the slice's first float4
+    if (gridDim.y > 1) {
+        const int c4 = (int)blockIdx.y * LPR;
+        d4 = min(LPR, d4 - c4);
+        if (PACKED) pk_off = c4;
+        else { src_a += 4 * c4; src_b += 4 * c4; }
+        if (out_rows) out_rows += 4 * c4;
+        partials += 4 * c4;
+        if (fu.table) fu.table += 4 * c4;
+        if (fu.table_b) fu.table_b += 4 * c4;
+    }
     constexpr int GROUPS = kThreads / LPR;
     // rows in flight per lane: dense rows cost 4*ITERS registers each; packed rows are a byte and a float,
     // so a whole chunk is fetched at once and the kernel pays one memory latency per chunk
@@ -209,7 +223,7 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
             const bool open_right = last_run && right_open;
             if (!open_left && !open_right) {
                 if constexpr (FUSED)
-                    apply_update<LPR, ITERS>(fused_row(fu, colcur, d4), d4, lig, xcur, acc, fu.lr, fu.mode, fu.stream);
+                    apply_update<LPR, ITERS>(fused_row(fu, colcur, ld_tab), d4, lig, xcur, acc, fu.lr, fu.mode, fu.stream);
                 else
                     store_row_stream<LPR, ITERS>(out_rows + (int64_t)cur_seg * ld_out, d4, lig, acc);
             } else {
@@ -251,11 +265,11 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
             for (int u = 0; u < UNROLL; ++u) {
                 const int64_t row = mu[u] >> 2;
                 if constexpr (FUSED) {   // a run begins here: its table row comes along with its first source row
-                    if (mu[u] & 2) load_row<LPR, ITERS>(fused_row(fu, cu[u], d4), d4, lig, xr[u]);
+                    if (mu[u] & 2) load_row<LPR, ITERS>(fused_row(fu, cu[u], ld_tab), d4, lig, xr[u]);
                 }
                 if constexpr (PACKED) {
                     const uint8_t *rec = reinterpret_cast<const uint8_t *>(src_a) + row * ld_src;
-                    const uint8_t *pb = rec + 4;
+                    const uint8_t *pb = rec + 4 + pk_off;
 #pragma unroll
                     for (int it = 0; it < ITERS; ++it) {
                         const int j = lig + it * LPR;
@@ -356,7 +370,7 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
                 x.v[it] = ld4(&s_x[src][(lig + it * LPR) * 4]);
                 g.v[it] = ld4(&s_part[grp][0][(lig + it * LPR) * 4]);
             }
-            apply_update<LPR, ITERS>(fused_row(fu, s_col_last[src], d4), d4, lig, x, g, fu.lr, fu.mode, fu.stream);
+            apply_update<LPR, ITERS>(fused_row(fu, s_col_last[src], ld_tab), d4, lig, x, g, fu.lr, fu.mode, fu.stream);
         }
     }
 }
@@ -375,6 +389,15 @@ __global__ __launch_bounds__(kThreads) void k_seg_fixup(const int32_t *__restric
         e_begin = sec.e_begin; e_end = sec.e_end;
         out_rows = sec.out_rows; partials = sec.partials;
         fu.table_b = sec.fused_table; fu.mode = sec.fused_mode;
+    }
+    const int ld_tab = d4 * 4;
+    if (gridDim.y > 1) {                                   // column slices, as in k_seg_reduce
+        const int c4 = (int)blockIdx.y * LPR;
+        d4 = min(LPR, d4 - c4);
+        if (out_rows) out_rows += 4 * c4;
+        partials += 4 * c4;
+        if (fu.table) fu.table += 4 * c4;
+        if (fu.table_b) fu.table_b += 4 * c4;
     }
     constexpr int GROUPS = kThreads / LPR;
     constexpr int ROWF = ITERS * LPR * 4;
@@ -403,7 +426,7 @@ __global__ __launch_bounds__(kThreads) void k_seg_fixup(const int32_t *__restric
     const int n = j - j0 + 1;                                   // partial rows: (j0, slot 1), (j0+1 .. j, slot 0)
     Acc<ITERS> xrow;                                            // FUSED: the table row, fetched beside the partial rows
     xrow.zero();
-    if (FUSED && grp == 0) load_row<LPR, ITERS>(fused_row(fu, col, d4), d4, lig, xrow);
+    if (FUSED && grp == 0) load_row<LPR, ITERS>(fused_row(fu, col, ld_tab), d4, lig, xrow);
     const int per = (n + GROUPS - 1) / GROUPS;
     const int lo = min(grp * per, n), hi = min(lo + per, n);
     Acc<ITERS> acc;
@@ -434,7 +457,7 @@ __global__ __launch_bounds__(kThreads) void k_seg_fixup(const int32_t *__restric
             for (int it = 0; it < ITERS; ++it) v.v[it] = ld4(&s_sum[g][(lig + it * LPR) * 4]);
             acc.add(v);
         }
-        if constexpr (FUSED) apply_update<LPR, ITERS>(fused_row(fu, col, d4), d4, lig, xrow, acc, fu.lr, fu.mode, fu.stream);
+        if constexpr (FUSED) apply_update<LPR, ITERS>(fused_row(fu, col, ld_tab), d4, lig, xrow, acc, fu.lr, fu.mode, fu.stream);
         else store_row<LPR, ITERS>(out_rows + (int64_t)seg * ld_out, d4, lig, acc);
     }
 }
@@ -586,6 +609,33 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
         ntiles += (second->e_end - second->e_begin + tile - 1) / tile;
     }
     const FusedArgs fu = fused ? *fused : FusedArgs{nullptr, nullptr, 0, nullptr, nullptr, 0.f, 0, 0};
+    // Wide rows (more than one float4 per lane) run as column slices of the one-float4 kernels: more rows in
+    // flight per lane and ITERS times the workgroups.  The unit-length rescale needs whole rows.
+    const bool whole_rows = fused && (fu.mode == 2 || sec.fused_mode == 2);
+    if (ITERS > 1 && !whole_rows) {
+        const dim3 grid((unsigned)ntiles, (unsigned)ITERS);
+#define STX_SLICED(P, CH, F)                                                                                    \
+    do {                                                                                                        \
+        {                                                                                                       \
+            ProfScope prof(c, "k_seg_reduce");                                                                  \
+            hipLaunchKernelGGL((k_seg_reduce<LPR, 1, P, CH, F>), grid, dim3(kThreads), 0, c->stream,            \
+                               inc->at_packed, inc->at_seg_id, e_begin, e_end, src_a, src_b, split, ld_src,     \
+                               width / 4, out_rows, ld_out, c->partials, fu, sec);                              \
+        }                                                                                                       \
+        if (ntiles > 1) {                                                                                       \
+            ProfScope prof(c, "k_seg_fixup");                                                                   \
+            hipLaunchKernelGGL((k_seg_fixup<LPR, 1, CH, F>), grid, dim3(kThreads), 0, c->stream,                \
+                               inc->at_packed, inc->at_seg_id, inc->at_seg_ptr, e_begin, e_end, width / 4,      \
+                               out_rows, ld_out, c->partials, fu, sec);                                         \
+        }                                                                                                       \
+    } while (0)
+#define STX_SLICED2(P, CH) do { if (fused) STX_SLICED(P, CH, true); else STX_SLICED(P, CH, false); } while (0)
+        if (packed_src) { if (small) STX_SLICED2(true, CH_SHORT); else STX_SLICED2(true, CH_LONG); }
+        else            { if (small) STX_SLICED2(false, CH_SHORT); else STX_SLICED2(false, CH_LONG); }
+#undef STX_SLICED2
+#undef STX_SLICED
+        return;
+    }
 #define STX_SEG(P, CH, F)                                                                                       \
     do {                                                                                                        \
         {                                                                                                       \

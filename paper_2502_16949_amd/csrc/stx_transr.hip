@@ -69,14 +69,17 @@ struct PrepArgs {
     // preparation can run beside the sort instead of after it.
     const int32_t *rel_cnt;
     int32_t n_rel;
+    int nplan;                   // workgroups that build the item lists (the others convert one M_r each)
 };
 
 // Item lists of the relation segments (one workgroup).  Row item: {relation, first sorted entry,
 // entries (<= 64), 0}.  dM item, two int4: {relation, first row item, entries (<= 256), slot} and
 // {first slot of the segment, parts to add if this is the segment's last item else 0, 0, 0}; slot is
 // -1 when the segment has a single dM item, which then writes dL/dM_r itself.
+// Workgroup `block` of the planners handles relations (or touched segments) 256*block .. and first adds
+// up what the lists before them need, so the planners do not wait for each other.
 template <bool FROM_COUNTS>
-__device__ inline void transr_plan(const PrepArgs &p)
+__device__ inline void transr_plan(const int block, const PrepArgs &p)
 {
     __shared__ int32_t s_o64[kThreads + 1], s_o256[kThreads + 1], s_op[kThreads], s_beg[kThreads], s_len[kThreads],
         s_rel[kThreads], s_wave[kThreads / 64][4];
@@ -84,8 +87,33 @@ __device__ inline void transr_plan(const PrepArgs &p)
     // the relations' lists, in the order of the sorted A^T: by touched segment, or by relation id with the
     // counted rows (an absent relation has no rows and gets no item)
     const int32_t first = FROM_COUNTS ? 0 : p.seg_id[p.e_begin], last = FROM_COUNTS ? p.n_rel : p.n_touched[0];
+    const int32_t sb = first + block * kThreads;
+    if (sb >= last) return;
     int32_t base64 = 0, base256 = 0, basep = 0, base_len = 0;
-    for (int32_t sb = first; sb < last; sb += kThreads) {
+    {   // items, slots and entries of the lists before this workgroup's
+        int32_t pre[4] = {0, 0, 0, 0};
+        for (int32_t s = first + tid; s < sb; s += kThreads) {
+            const int32_t len = FROM_COUNTS ? p.rel_cnt[s] : p.seg_ptr[s + 1] - p.seg_ptr[s];
+            const int32_t n256 = (len + 255) >> 8;
+            pre[0] += (len + 63) >> 6; pre[1] += n256; pre[2] += n256 > 1 ? n256 : 0; pre[3] += len;
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) pre[q] += __shfl_xor(pre[q], off);
+        }
+        if ((tid & 63) == 0) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) s_wave[tid >> 6][q] = pre[q];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int ww = 0; ww < kThreads / 64; ++ww) {
+            base64 += s_wave[ww][0]; base256 += s_wave[ww][1]; basep += s_wave[ww][2]; base_len += s_wave[ww][3];
+        }
+        __syncthreads();
+    }
+    {
         const int32_t s = sb + tid;
         int32_t beg = 0, len = 0, rel = 0;
         if (s < last) {
@@ -151,10 +179,10 @@ __device__ inline void transr_plan(const PrepArgs &p)
                                                       min(256, s_len[lo] - 256 * li), parts > 1 ? first + li : -1);
             p.dm_items[2 * (base256 + w) + 1] = make_int4(first, (parts > 1 && li == parts - 1) ? parts : 0, 0, 0);
         }
-        base64 += t64; base256 += t256; basep += tp; base_len += tot[3];
-        __syncthreads();
+        // the planner of the last lists knows the totals
+        if (sb + kThreads >= last && tid == 0) { p.counts[0] = base64 + t64; p.counts[1] = base256 + t256; }
+        (void)tp;
     }
-    if (tid == 0) { p.counts[0] = base64; p.counts[1] = base256; }
 }
 
 // Workgroup 0 builds the item lists; workgroup 1 + r writes the two bfloat16 operand-order copies of
@@ -163,9 +191,9 @@ __device__ inline void transr_plan(const PrepArgs &p)
 template <bool FROM_COUNTS>
 __device__ inline void transr_prepare_body(const int block, const PrepArgs &p)
 {
-    if (block == 0) { transr_plan<FROM_COUNTS>(p); return; }
+    if (block < p.nplan) { transr_plan<FROM_COUNTS>(block, p); return; }
     const int tid = threadIdx.x;
-    const int32_t r = block - 1;
+    const int32_t r = block - p.nplan;
     if (FROM_COUNTS) {
         if (p.rel_cnt[r] == 0) return;
     } else {
@@ -178,31 +206,57 @@ __device__ inline void transr_prepare_body(const int block, const PrepArgs &p)
         }
         if (lo >= n_seg || p.touched_cols[lo] != target) return;
     }
+    // 64 rows of M_r at a time go through LDS as bfloat16: the fp32 rows are read with whole-row float4
+    // accesses, and both operand-order copies are written 16 bytes per thread, contiguous across threads.
+    __shared__ __attribute__((aligned(16))) uint16_t s_m[64 * (kMaxProjDim + kLdsPad)];
     const int64_t kd = (int64_t)p.k * p.d;
     const float *__restrict__ M = p.M + r * kd;
-    {   // forward operand: row a of M_r, reduction over j
-        uint16_t *__restrict__ dst = p.m16 + r * kd;
-        const int rt = p.k >> 5, pieces = (p.d >> 4) * rt * 64;
-#pragma unroll 4
-        for (int pc = tid; pc < pieces; pc += kThreads) {
-            const int l = pc & 63, blk = pc >> 6, ks = blk / rt, nt = blk - ks * rt;
-            const float *s = M + (int64_t)(32 * nt + (l & 31)) * p.d + 16 * ks + 8 * (l >> 5);
-            *reinterpret_cast<uint4 *>(dst + (int64_t)pc * 8) = pack8(ld4(s), ld4(s + 4));
-        }
-    }
-    {   // GX operand: column j of M_r, reduction over a
-        uint16_t *__restrict__ dst = p.m16t + r * kd;
-        const int rt = p.d >> 5, pieces = (p.k >> 4) * rt * 64;
-#pragma unroll 2
-        for (int pc = tid; pc < pieces; pc += kThreads) {
-            const int l = pc & 63, blk = pc >> 6, ks = blk / rt, nt = blk - ks * rt;
-            const float *s = M + (int64_t)(16 * ks + 8 * (l >> 5)) * p.d + 32 * nt + (l & 31);
-            float v[8];
+    uint16_t *__restrict__ fwd = p.m16 + r * kd;          // rows a, reduction over j
+    uint16_t *__restrict__ gx = p.m16t + r * kd;          // rows j, reduction over a
+    const int stride = p.d + kLdsPad, q4 = p.d >> 2;
+    const int rt_f = p.k >> 5, rt_g = p.d >> 5, ks_d = p.d >> 4;
+    for (int a0 = 0; a0 < p.k; a0 += 64) {
+        const int rows = min(64, p.k - a0);               // 32 or 64
+        for (int g0 = tid; g0 < rows * q4; g0 += 8 * kThreads) {
+            float4 v[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) v[i] = s[(int64_t)i * p.d];
-            *reinterpret_cast<uint4 *>(dst + (int64_t)pc * 8) =
-                make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
+            for (int u = 0; u < 8; ++u) {
+                const int g = g0 + u * kThreads;
+                v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (g < rows * q4) { const int i = g / q4; v[u] = ld4(M + (int64_t)(a0 + i) * p.d + 4 * (g - i * q4)); }
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int g = g0 + u * kThreads;
+                if (g < rows * q4) {
+                    const int i = g / q4, c4 = 4 * (g - i * q4);
+                    *reinterpret_cast<uint2 *>(s_m + i * stride + c4) = make_uint2(pack2(v[u].x, v[u].y), pack2(v[u].z, v[u].w));
+                }
+            }
         }
+        __syncthreads();
+        {   // forward operand: the row tiles of these rows, every reduction step over j
+            const int nt_n = rows >> 5, pieces = ks_d * nt_n * 64;
+            for (int pc = tid; pc < pieces; pc += kThreads) {
+                const int l = pc & 63, blk = pc >> 6, ks = blk / nt_n, ntl = blk - ks * nt_n;
+                const uint4 o = *reinterpret_cast<const uint4 *>(s_m + (32 * ntl + (l & 31)) * stride + 16 * ks + 8 * (l >> 5));
+                *reinterpret_cast<uint4 *>(fwd + ((int64_t)(ks * rt_f + (a0 >> 5) + ntl) * 64 + l) * 8) = o;
+            }
+        }
+        {   // GX operand: every row tile over j, the reduction steps that these rows of M_r cover
+            const int ks_n = rows >> 4, pieces = ks_n * rt_g * 64;
+            for (int pc = tid; pc < pieces; pc += kThreads) {
+                const int l = pc & 63, blk = pc >> 6, ksl = blk / rt_g, nt = blk - ksl * rt_g;
+                const uint16_t *src = s_m + (16 * ksl + 8 * (l >> 5)) * stride + 32 * nt + (l & 31);
+                uint4 o;
+                o.x = (uint32_t)src[0] | (uint32_t)src[stride] << 16;
+                o.y = (uint32_t)src[2 * stride] | (uint32_t)src[3 * stride] << 16;
+                o.z = (uint32_t)src[4 * stride] | (uint32_t)src[5 * stride] << 16;
+                o.w = (uint32_t)src[6 * stride] | (uint32_t)src[7 * stride] << 16;
+                *reinterpret_cast<uint4 *>(gx + ((int64_t)(((a0 >> 4) + ksl) * rt_g + nt) * 64 + l) * 8) = o;
+            }
+        }
+        __syncthreads();
     }
 }
 
@@ -562,6 +616,8 @@ static PrepArgs prep_args(stx_ctx *c, const stx_incidence *inc, const stx_params
     a.d = c->cfg.dim; a.k = c->cfg.rel_dim;
     a.rel_cnt = c->cnt_inc == inc ? c->cnt_ptr : nullptr;  // the counts of the last build, if that was this incidence
     a.n_rel = (int32_t)c->cfg.n_rel;
+    const int64_t lists = inc->n_rows < c->cfg.n_rel ? inc->n_rows : c->cfg.n_rel;   // most touched relations
+    a.nplan = (int)(((a.rel_cnt ? c->cfg.n_rel : lists) + kThreads - 1) / kThreads);
     return a;
 }
 
@@ -571,8 +627,8 @@ bool launch_prep_scatter(stx_ctx *c, const stx_incidence *inc, const stx_params 
     const PrepArgs a = prep_args(c, inc, p);
     if (!a.rel_cnt) return false;
     ProfScope prof(c, "k_prep_scatter");
-    hipLaunchKernelGGL(k_prep_scatter, dim3((unsigned)(sa.ntiles + c->cfg.n_rel + 1)), dim3(kThreads), 0, c->stream, a,
-                       sa);
+    hipLaunchKernelGGL(k_prep_scatter, dim3((unsigned)(sa.ntiles + c->cfg.n_rel + a.nplan)), dim3(kThreads), 0,
+                       c->stream, a, sa);
     c->prep_inc = inc;
     return true;
 }
@@ -584,9 +640,9 @@ stx_status launch_transr_project(stx_ctx *c, const stx_incidence *inc, const stx
         const PrepArgs a = prep_args(c, inc, p);
         ProfScope prof(c, "k_transr_prepare");
         if (a.rel_cnt)
-            hipLaunchKernelGGL(k_transr_prepare<true>, dim3((unsigned)c->cfg.n_rel + 1), dim3(kThreads), 0, c->stream, a);
+            hipLaunchKernelGGL(k_transr_prepare<true>, dim3((unsigned)(c->cfg.n_rel + a.nplan)), dim3(kThreads), 0, c->stream, a);
         else
-            hipLaunchKernelGGL(k_transr_prepare<false>, dim3((unsigned)c->cfg.n_rel + 1), dim3(kThreads), 0, c->stream, a);
+            hipLaunchKernelGGL(k_transr_prepare<false>, dim3((unsigned)(c->cfg.n_rel + a.nplan)), dim3(kThreads), 0, c->stream, a);
     }
     c->prep_inc = nullptr;      // the copies of M_r are good for this forward pass only: the update changes M_r
     ProfScope prof(c, "k_transr_project");
