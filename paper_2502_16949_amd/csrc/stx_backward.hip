@@ -596,7 +596,7 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
 {
     // Entries per lane group: short chunks shorten every group's serial walk when the whole product is
     // small (latency bound); long ones mean fewer partial rows when it is large (bandwidth bound).
-    constexpr int CH_LONG = LPR < 32 ? LPR : 32, CH_SHORT = LPR < 16 ? LPR : 16;
+    constexpr int CH_LONG = LPR == 64 ? 64 : (LPR < 32 ? LPR : 32), CH_SHORT = LPR < 16 ? LPR : 16;
     constexpr int GROUPS = kThreads / LPR;
     const bool small = (e_end - e_begin) <= (1 << 20);
     const int tile = GROUPS * (small ? CH_SHORT : CH_LONG);
