@@ -38,7 +38,7 @@
 #include <string.h>
 
 enum { STXO_TRANSE = 0, STXO_TRANSH = 1, STXO_TRANSR = 2, STXO_TORUSE = 3 };
-enum { STXO_L1 = 0, STXO_L2 = 1, STXO_TORUS_L1 = 2, STXO_TORUS_L2 = 3 };
+enum { STXO_L1 = 0, STXO_L2 = 1, STXO_TORUS_L1 = 2, STXO_TORUS_L2 = 3, STXO_L2_SQ = 4 };
 enum { STXO_SUM = 0, STXO_MEAN = 1 };
 
 typedef struct {
@@ -273,15 +273,17 @@ static void row_y(const stxo_cfg *c, const stxo_tables *tb, int32_t rr, const fl
     }
 }
 
-/* Distance of Table 2's norm: L1, L2 (unsquared), or the torus versions on f = y - floor(y):
- * torus-L1 = sum min(f,1-f); torus-L2 = sqrt(sum min(f,1-f)^2).  For the torus the fractional part
- * is taken in fp32 (y is the fp32 x there), the sum in double.                                */
+/* Distance of Table 2's norm: L1, L2 (unsquared), the squared L2 norm of the TransC row of that
+ * table, or the torus versions on f = y - floor(y): torus-L1 = sum min(f,1-f); torus-L2 =
+ * sqrt(sum min(f,1-f)^2).  For the torus the fractional part is taken in fp32 (y is the fp32 x
+ * there), the sum in double.                                                                  */
 static double row_dist(const stxo_cfg *c, const double *y, int32_t n)
 {
     double acc = 0.0;
     switch (c->dist) {
     case STXO_L1: for (int32_t j = 0; j < n; ++j) acc += fabs(y[j]); return acc;
     case STXO_L2: for (int32_t j = 0; j < n; ++j) acc += y[j] * y[j]; return sqrt(acc);
+    case STXO_L2_SQ: for (int32_t j = 0; j < n; ++j) acc += y[j] * y[j]; return acc;
     default:
         for (int32_t j = 0; j < n; ++j) {
             float yf = (float)y[j];
@@ -301,6 +303,7 @@ static void row_ddist(const stxo_cfg *c, const double *y, int32_t n, double dist
         switch (c->dist) {
         case STXO_L1: g[j] = (y[j] > 0) - (y[j] < 0); break;
         case STXO_L2: g[j] = dist > 0 ? y[j] / dist : 0.0; break;
+        case STXO_L2_SQ: g[j] = 2.0 * y[j]; break;
         default: {
             float yf = (float)y[j];
             float f = yf - floorf(yf);
@@ -361,7 +364,8 @@ int stxo_forward(const stxo_cfg *c, const stxo_tables *tb, const stxo_batch *bt,
  *   g_w   : TransH n_rel x dim
  *   g_proj: TransR n_rel x rel_dim x dim
  * For TransH and TransR, y itself is a computed quantity, so the scale of dL/dy_j used in those sums
- * is max(|dL/dy_j|, |coef|/dist * sum|terms of y_j|) for the L2 kinds.
+ * is max(|dL/dy_j|, |coef|/dist * sum|terms of y_j|) for the L2 kinds (2 |coef| * sum|terms of y_j|
+ * for the squared L2 norm).
  * gy_out (optional, rows x out_dim doubles): dL/dy of every row.
  * ambiguous (optional, rows bytes): set to 1 for rows of TransH/TransR with an L1-kind distance in
  * which some y_j lies within 1e-5 * sum|terms of y_j| of a point where the subgradient jumps (0, or
@@ -417,6 +421,9 @@ int stxo_backward(const stxo_cfg *c, const stxo_tables *tb, const stxo_batch *bt
                 if (is_stacked(c)) continue;            /* there y is the exact fp32 x */
                 if (l2kind) {
                     double alt = dist[i] > 0 ? fabs(coef[i]) / dist[i] * yabs[j] : 0.0;
+                    if (alt > ug[j]) ug[j] = alt;
+                } else if (c->dist == STXO_L2_SQ) {
+                    double alt = 2.0 * fabs(coef[i]) * yabs[j];
                     if (alt > ug[j]) ug[j] = alt;
                 } else if (c->dist == STXO_L1) {
                     if (fabs(y[j]) <= STXO_TIE_WIDTH * yabs[j]) amb = 1;

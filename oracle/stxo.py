@@ -18,7 +18,7 @@ _SRC = os.path.join(_HERE, "stxo.c")
 _LIB = os.path.join(_HERE, "libstxo.so")
 
 TRANSE, TRANSH, TRANSR, TORUSE = 0, 1, 2, 3
-L1, L2, TORUS_L1, TORUS_L2 = 0, 1, 2, 3
+L1, L2, TORUS_L1, TORUS_L2, L2_SQ = 0, 1, 2, 3, 4
 SUM, MEAN = 0, 1
 
 

@@ -19,7 +19,7 @@ def _one(h, r, t, nh=E0, nt=E0):
 def test_hand_computed_distances():
     # X = [E;R] with 3 entities and 1 relation, dim 2: h=(3,0), t=(0,0), r=(0,-4) -> y=(3,-4)
     X = np.array([[3, 0], [0, 0], [9, 9], [0, -4]], np.float32)
-    for dist, want in ((stxo.L1, 7.0), (stxo.L2, 5.0)):
+    for dist, want in ((stxo.L1, 7.0), (stxo.L2, 5.0), (stxo.L2_SQ, 25.0)):     # the last: TransC's row of Table 2
         cfg = stxo.Config(stxo.TRANSE, dist, 3, 1, 2)
         fw = stxo.forward(cfg, stxo.Tables(X), _one(0, 0, 1))
         assert fw.scores[0] == want and np.array_equal(fw.x[0], [3, -4])
@@ -142,7 +142,8 @@ def _loss_of(cfg, tabs, bt):
 
 
 CASES = [("transe", "l1"), ("transe", "l2"), ("toruse", "torus_l1"), ("toruse", "torus_l2"),
-         ("transh", "l2"), ("transh", "l1"), ("transr", "l2"), ("transr", "l1")]
+         ("transh", "l2"), ("transh", "l1"), ("transr", "l2"), ("transr", "l1"),
+         ("transe", "l2_sq"), ("transh", "l2_sq"), ("transr", "l2_sq")]
 
 
 @pytest.mark.parametrize("model,dist", CASES)
@@ -154,7 +155,7 @@ def test_gradients_by_central_differences(model, dist, reduce):
     cfg = oracle_config(wl, reduce=reduce, bf16=False)
     g = stxo.backward(cfg, oracle_tables(tabs), bt)
     eps = 2.0 ** -9
-    smooth = dist in ("l2", "torus_l2") or model in ("transh", "transr")
+    smooth = dist in ("l2", "torus_l2", "l2_sq") or model in ("transh", "transr")
     for name, grad in (("ent", g.ent), ("rel", g.rel), ("w", g.w), ("proj", g.proj)):
         if grad is None:
             continue
@@ -190,6 +191,8 @@ def _torch_loss(model, dist, reduce, margin, tabs, bt, n_ent):
         s = y.abs().sum(1)
     elif dist == "l2":
         s = (y * y).sum(1).sqrt()
+    elif dist == "l2_sq":
+        s = (y * y).sum(1)
     else:
         f = y - torch.floor(y)
         m = torch.minimum(f, 1 - f)

@@ -7,7 +7,7 @@ from oracle import stxo
 from paper_2502_16949_amd import workloads as W
 
 MODEL = {"transe": stxo.TRANSE, "transh": stxo.TRANSH, "transr": stxo.TRANSR, "toruse": stxo.TORUSE}
-DIST = {"l1": stxo.L1, "l2": stxo.L2, "torus_l1": stxo.TORUS_L1, "torus_l2": stxo.TORUS_L2}
+DIST = {"l1": stxo.L1, "l2": stxo.L2, "torus_l1": stxo.TORUS_L1, "torus_l2": stxo.TORUS_L2, "l2_sq": stxo.L2_SQ}
 
 
 def oracle_config(wl: W.Workload, reduce=stxo.SUM, bf16=None) -> stxo.Config:
