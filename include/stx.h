@@ -45,7 +45,7 @@ typedef enum {
 enum { STX_TRANSE = 0, STX_TRANSH = 1, STX_TRANSR = 2, STX_TORUSE = 3 };
 /* Norm applied to the translated vector (Sec. 4.3, 4.6): L1, unsquared L2, or their torus
  * versions, taken on the fractional part f = y - floor(y) as sum / root-sum-square of min(f, 1-f). */
-enum { STX_L1 = 0, STX_L2 = 1, STX_TORUS_L1 = 2, STX_TORUS_L2 = 3 };
+enum { STX_L1 = 0, STX_L2 = 1, STX_TORUS_L1 = 2, STX_TORUS_L2 = 3, STX_L2_SQ = 4 /* sum y^2: Table 2, TransC */ };
 /* Reduction of the margin-ranking loss over the b*k (positive, negative) pairs. */
 enum { STX_SUM = 0, STX_MEAN = 1 };
 

@@ -17,12 +17,12 @@ STX_OK = 0
 STX_ERR_NULL, STX_ERR_BAD_ARG, STX_ERR_INDEX_RANGE, STX_ERR_WORKSPACE = 1, 2, 3, 4
 STX_ERR_STATE, STX_ERR_UNSUPPORTED, STX_ERR_HIP = 5, 6, 7
 STX_TRANSE, STX_TRANSH, STX_TRANSR, STX_TORUSE = 0, 1, 2, 3
-STX_L1, STX_L2, STX_TORUS_L1, STX_TORUS_L2 = 0, 1, 2, 3
+STX_L1, STX_L2, STX_TORUS_L1, STX_TORUS_L2, STX_L2_SQ = 0, 1, 2, 3, 4
 STX_SUM, STX_MEAN = 0, 1
 STX_FLAG_RENORM_W, STX_FLAG_BF16_PROJ = 1, 2
 
 MODELS = {"transe": STX_TRANSE, "transh": STX_TRANSH, "transr": STX_TRANSR, "toruse": STX_TORUSE}
-DISTS = {"l1": STX_L1, "l2": STX_L2, "torus_l1": STX_TORUS_L1, "torus_l2": STX_TORUS_L2}
+DISTS = {"l1": STX_L1, "l2": STX_L2, "torus_l1": STX_TORUS_L1, "torus_l2": STX_TORUS_L2, "l2_sq": STX_L2_SQ}
 
 EXPORTS = ["stx_workspace_bytes", "stx_create", "stx_destroy", "stx_sample_negatives", "stx_build_incidence",
            "stx_check_indices", "stx_spmm", "stx_forward", "stx_backward", "stx_sgd_step", "stx_backward_sgd", "stx_train_step", "stx_profile_kernel",

@@ -25,7 +25,7 @@ stx_status check_config(const stx_config *c)
 {
     if (!c) return STX_ERR_NULL;
     if (c->model < STX_TRANSE || c->model > STX_TORUSE) return STX_ERR_BAD_ARG;
-    if (c->dist < STX_L1 || c->dist > STX_TORUS_L2) return STX_ERR_BAD_ARG;
+    if (c->dist < STX_L1 || c->dist > STX_L2_SQ) return STX_ERR_BAD_ARG;
     if (c->reduce != STX_SUM && c->reduce != STX_MEAN) return STX_ERR_BAD_ARG;
     if (c->dim <= 0 || c->dim % 4 != 0 || c->dim > kMaxDim) return STX_ERR_BAD_ARG;
     if (c->model == STX_TRANSR && (c->rel_dim <= 0 || c->rel_dim % 4 != 0 || c->rel_dim > kMaxDim))

@@ -115,6 +115,7 @@ static void forward_go(stx_ctx *c, const stx_incidence *inc, const stx_params *p
     case STX_L1: STX_FWD2(STX_L1); break;
     case STX_L2: STX_FWD2(STX_L2); break;
     case STX_TORUS_L1: STX_FWD2(STX_TORUS_L1); break;
+    case STX_L2_SQ: STX_FWD2(STX_L2_SQ); break;
     default: STX_FWD2(STX_TORUS_L2); break;
     }
     }

@@ -59,7 +59,7 @@ template <int DIST>
 __device__ inline float term(float y)
 {
     if (DIST == STX_L1) return fabsf(y);
-    if (DIST == STX_L2) return y * y;
+    if (DIST == STX_L2 || DIST == STX_L2_SQ) return y * y;
     float f = y - floorf(y);
     float m = fminf(f, 1.0f - f);
     return DIST == STX_TORUS_L1 ? m : m * m;
@@ -69,12 +69,13 @@ __device__ inline float finish(float acc)
 {
     return (DIST == STX_L2 || DIST == STX_TORUS_L2) ? sqrtf(acc) : acc;
 }
-// d(dist)/dy times coef.  cs = coef for the L1 kinds, coef / dist (0 if dist == 0) for the L2 kinds.
+// d(dist)/dy times coef.  cs = coef for the L1 kinds, coef / dist (0 if dist == 0) for the L2 kinds,
+// 2 coef for the squared L2 norm.
 template <int DIST>
 __device__ inline float dterm(float y, float cs)
 {
     if (DIST == STX_L1) return y > 0.f ? cs : (y < 0.f ? -cs : 0.f);
-    if (DIST == STX_L2) return y * cs;
+    if (DIST == STX_L2 || DIST == STX_L2_SQ) return y * cs;
     float f = y - floorf(y);
     float sg = (f > 0.f && f < 0.5f) ? 1.f : (f > 0.5f ? -1.f : 0.f);
     if (DIST == STX_TORUS_L1) return sg * cs;
@@ -102,6 +103,7 @@ template <int DIST>
 __device__ inline float coef_scale(float coef, float dist)
 {
     if (DIST == STX_L2 || DIST == STX_TORUS_L2) return dist > 0.f ? coef / dist : 0.f;
+    if (DIST == STX_L2_SQ) return 2.0f * coef;
     return coef;
 }
 

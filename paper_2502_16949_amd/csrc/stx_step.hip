@@ -47,6 +47,7 @@ static void fwd_scatter_go(stx_ctx *c, const ForwardArgs &fa, const ScatterArgs 
     case STX_L1: STX_FS(STX_L1, true); break;
     case STX_L2: STX_FS(STX_L2, false); break;
     case STX_TORUS_L1: STX_FS(STX_TORUS_L1, true); break;
+    case STX_L2_SQ: STX_FS(STX_L2_SQ, false); break;
     default: STX_FS(STX_TORUS_L2, false); break;
     }
 #undef STX_FS
@@ -61,6 +62,7 @@ static void fwdh_scatter_go(stx_ctx *c, const TranshArgs &ta, const ScatterArgs 
     case STX_L1: STX_FS(STX_L1); break;
     case STX_L2: STX_FS(STX_L2); break;
     case STX_TORUS_L1: STX_FS(STX_TORUS_L1); break;
+    case STX_L2_SQ: STX_FS(STX_L2_SQ); break;
     default: STX_FS(STX_TORUS_L2); break;
     }
 #undef STX_FS

@@ -33,6 +33,7 @@ static void transh_go(stx_ctx *c, const stx_incidence *inc, const stx_params *p,
     case STX_L1: STX_FWD(STX_L1); break;
     case STX_L2: STX_FWD(STX_L2); break;
     case STX_TORUS_L1: STX_FWD(STX_TORUS_L1); break;
+    case STX_L2_SQ: STX_FWD(STX_L2_SQ); break;
     default: STX_FWD(STX_TORUS_L2); break;
     }
     }

@@ -126,6 +126,8 @@ STEP_CASES = [
     ("transe", "l2", 200, 5, 200, 1, 1024, 0.0),
     ("toruse", "torus_l1", 1000, 20, 1024, 4, 128, 1.05),
     ("toruse", "torus_l2", 500, 7, 600, 2, 64, 1.05),
+    ("transe", "l2_sq", 400, 9, 777, 3, 128, 1.1),     # squared L2 norm (Table 2, TransC row)
+    ("transe", "l2_sq", 200, 5, 200, 1, 1024, 0.0),
 ]
 
 

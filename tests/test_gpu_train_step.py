@@ -23,6 +23,8 @@ CASES = [
     ("toruse", "torus_l1", 1000, 20, 1024, 4, 128, 128, 0),
     ("toruse", "torus_l2", 500, 7, 600, 2, 64, 64, 0),
     ("transe", "l2", 100, 3, 50, 0, 64, 64, 0),                   # no negatives at all
+    ("transe", "l2_sq", 400, 9, 777, 3, 128, 128, 0),
+    ("transh", "l2_sq", 400, 9, 777, 2, 64, 64, 0),
     ("transh", "l2", 1000, 20, 1024, 1, 128, 128, B.STX_FLAG_RENORM_W),
     ("transh", "l1", 400, 9, 777, 3, 64, 64, 0),
     ("transh", "l2", 200, 5, 200, 1, 1024, 1024, 0),

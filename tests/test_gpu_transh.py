@@ -80,6 +80,7 @@ CASES = [
     ("l1", 300, 5, 300, 2, 256, 0.0),
     ("l2", 200, 5, 200, 1, 1024, 0.0),
     ("torus_l2", 300, 6, 400, 2, 64, 1.1),
+    ("l2_sq", 400, 9, 777, 3, 128, 1.1),
 ]
 
 

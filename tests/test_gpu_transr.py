@@ -93,6 +93,7 @@ CASES = [
     ("l2", 150, 6, 130, 1, 96, 160, 0.0),         # tile counts that are not powers of two
     ("l2", 50, 1, 40, 1, 32, 32, 0.0),            # one relation, one partly filled item
     ("l2", 500, 300, 100, 1, 64, 64, 0.0),        # more relations than rows: every item nearly empty
+    ("l2_sq", 400, 40, 900, 2, 128, 128, 1.3),
 ]
 
 
