@@ -54,7 +54,13 @@ typedef struct {
  * TransR: ent = E (n_ent x dim), rel = r (n_rel x rel_dim), proj = M_r (n_rel x rel_dim x dim, row-major). */
 typedef struct {
     const float *ent, *rel, *w, *proj;
+    /* Optional (NULL: every weight is 1): a fixed positive weight per relation that multiplies the
+     * distance of every triplet of that relation, as in the TransM row of Table 2, w_r ||h + r - t||.
+     * It is a constant of the model, not a trained parameter: no gradient is formed for it. */
+    const float *rel_weight;
 } stxo_tables;
+
+static double rel_w(const stxo_tables *tb, int32_t rr) { return tb->rel_weight ? (double)tb->rel_weight[rr] : 1.0; }
 
 /* One batch: b positives (h,r,t) and b*k negatives (nh,nt); the negative (i,kk) keeps r[i].
  * Row order of the incidence matrix: positives 0..b-1, then negative (i,kk) at b + i*k + kk. */
@@ -336,7 +342,7 @@ int stxo_forward(const stxo_cfg *c, const stxo_tables *tb, const stxo_batch *bt,
         row_x(c, tb, hh, rr, tt, x);
         if (x_out) memcpy(x_out + i * d, x, sizeof(float) * (size_t)d);
         row_y(c, tb, rr, x, y, NULL, NULL);
-        scores[i] = row_dist(c, y, n);
+        scores[i] = rel_w(tb, rr) * row_dist(c, y, n);
     }
     double total = 0.0;
     for (int64_t i = 0; i < bt->b; ++i)
@@ -387,9 +393,10 @@ int stxo_backward(const stxo_cfg *c, const stxo_tables *tb, const stxo_batch *bt
     double *ax = (double *)malloc(sizeof(double) * (size_t)d); /* sum of |products| that make up gx */
     double *yabs = (double *)malloc(sizeof(double) * (size_t)n);
     double *ug = (double *)malloc(sizeof(double) * (size_t)n);  /* scale of each dL/dy_j */
-    double *dist = (double *)malloc(sizeof(double) * (size_t)rows);
+    double *dist = (double *)malloc(sizeof(double) * (size_t)rows);   /* the norm itself ... */
+    double *wrow = (double *)malloc(sizeof(double) * (size_t)rows);   /* ... and the row's relation weight */
     double *coef = (double *)calloc((size_t)rows, sizeof(double));
-    if (!x || !y || !gd || !gx || !ax || !yabs || !ug || !dist || !coef) return 2;
+    if (!x || !y || !gd || !gx || !ax || !yabs || !ug || !dist || !wrow || !coef) return 2;
 
     for (int64_t i = 0; i < rows; ++i) {
         int32_t hh, rr, tt;
@@ -397,14 +404,16 @@ int stxo_backward(const stxo_cfg *c, const stxo_tables *tb, const stxo_batch *bt
         row_x(c, tb, hh, rr, tt, x);
         row_y(c, tb, rr, x, y, NULL, NULL);
         dist[i] = row_dist(c, y, n);
+        wrow[i] = rel_w(tb, rr);
     }
     for (int64_t i = 0; i < b; ++i)
         for (int32_t kk = 0; kk < k; ++kk) {
             int64_t p = i * k + kk;
             int act = active_override ? (active_override[p] != 0)
-                                      : ((double)c->margin + dist[i] - dist[b + p] > 0);
+                                      : ((double)c->margin + wrow[i] * dist[i] - wrow[b + p] * dist[b + p] > 0);
             if (act) { coef[i] += scale; coef[b + p] -= scale; }
         }
+    for (int64_t i = 0; i < rows; ++i) coef[i] *= wrow[i];   /* score = weight * norm */
     for (int64_t i = 0; i < rows; ++i) {
         int32_t hh, rr, tt;
         double s = 0.0;
@@ -480,7 +489,7 @@ int stxo_backward(const stxo_cfg *c, const stxo_tables *tb, const stxo_batch *bt
         for (int32_t j = 0; j < d; ++j) { gh[j] += gx[j]; ah[j] += ax[j]; }
         for (int32_t j = 0; j < d; ++j) { gt[j] -= gx[j]; at[j] += ax[j]; }
     }
-    free(x); free(y); free(gd); free(gx); free(ax); free(yabs); free(ug); free(dist); free(coef);
+    free(x); free(y); free(gd); free(gx); free(ax); free(yabs); free(ug); free(dist); free(wrow); free(coef);
     return 0;
 }
 
@@ -549,6 +558,7 @@ int stxo_grad_column_stacked(const stxo_cfg *c, const stxo_tables *tb, const stx
         double coef = 0.0;
         if (i < b) { for (int32_t kk = 0; kk < k; ++kk) if (active[i * k + kk]) coef += scale; }
         else if (active[i - b]) coef = -scale;
+        coef *= rel_w(tb, rr);
         row_x(c, tb, hh, rr, tt, x);
         row_y(c, tb, rr, x, y, NULL, NULL);
         double dist = row_dist(c, y, d);

@@ -39,7 +39,8 @@ class _Cfg(C.Structure):
 
 
 class _Tables(C.Structure):
-    _fields_ = [("ent", C.c_void_p), ("rel", C.c_void_p), ("w", C.c_void_p), ("proj", C.c_void_p)]
+    _fields_ = [("ent", C.c_void_p), ("rel", C.c_void_p), ("w", C.c_void_p), ("proj", C.c_void_p),
+                ("rel_weight", C.c_void_p)]
 
 
 class _Batch(C.Structure):
@@ -138,15 +139,16 @@ class Batch:
 
 
 class Tables:
-    def __init__(self, ent, rel=None, w=None, proj=None):
+    def __init__(self, ent, rel=None, w=None, proj=None, rel_weight=None):
         self.ent, self.rel, self.w, self.proj = _f32(ent), _f32(rel), _f32(w), _f32(proj)
+        self.rel_weight = _f32(rel_weight)      # fixed per-relation weight of the distance (TransM), or None
 
     def c(self) -> _Tables:
-        return _Tables(_p(self.ent), _p(self.rel), _p(self.w), _p(self.proj))
+        return _Tables(_p(self.ent), _p(self.rel), _p(self.w), _p(self.proj), _p(self.rel_weight))
 
     def copy(self) -> "Tables":
         cp = lambda a: None if a is None else a.copy()
-        return Tables(cp(self.ent), cp(self.rel), cp(self.w), cp(self.proj))
+        return Tables(cp(self.ent), cp(self.rel), cp(self.w), cp(self.proj), cp(self.rel_weight))
 
 
 def rng_u64(seed: int, counter: int) -> int:

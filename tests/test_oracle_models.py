@@ -25,6 +25,15 @@ def test_hand_computed_distances():
         assert fw.scores[0] == want and np.array_equal(fw.x[0], [3, -4])
 
 
+def test_hand_computed_relation_weight():
+    # the TransM row of Table 2: the same y = (3,-4) with relation weight 2
+    X = np.array([[3, 0], [0, 0], [9, 9], [0, -4]], np.float32)
+    for dist, want in ((stxo.L1, 14.0), (stxo.L2, 10.0), (stxo.L2_SQ, 50.0)):
+        cfg = stxo.Config(stxo.TRANSE, dist, 3, 1, 2)
+        fw = stxo.forward(cfg, stxo.Tables(X, rel_weight=np.array([2.0], np.float32)), _one(0, 0, 1))
+        assert fw.scores[0] == want
+
+
 def test_hand_computed_torus():
     # y = (0.25, 0.75, 0.5, 0, -0.25, 1.25): min(f,1-f) = .25 .25 .5 0 .25 .25
     y = np.array([0.25, 0.75, 0.5, 0.0, -0.25, 1.25], np.float32)
@@ -170,9 +179,9 @@ def test_gradients_by_central_differences(model, dist, reduce):
             assert abs(fd - grad.reshape(-1)[idx]) <= tol, (name, idx, fd, grad.reshape(-1)[idx])
 
 
-def _torch_loss(model, dist, reduce, margin, tabs, bt, n_ent):
+def _torch_loss(model, dist, reduce, margin, tabs, bt, n_ent, rel_weight=None):
     """The gather formulation with library ops only (index_select + autograd), float64."""
-    T = {k: torch.tensor(v, dtype=torch.float64, requires_grad=True) for k, v in tabs.items()}
+    T = {k: torch.tensor(v, dtype=torch.float64, requires_grad=True) for k, v in tabs.items() if k != "rel_weight"}
     hh = torch.tensor(np.concatenate([bt.h, bt.nh]), dtype=torch.long)
     tt = torch.tensor(np.concatenate([bt.t, bt.nt]), dtype=torch.long)
     rr = torch.tensor(np.concatenate([bt.r, np.repeat(bt.r, bt.k)]), dtype=torch.long)
@@ -197,6 +206,8 @@ def _torch_loss(model, dist, reduce, margin, tabs, bt, n_ent):
         f = y - torch.floor(y)
         m = torch.minimum(f, 1 - f)
         s = m.sum(1) if dist == "torus_l1" else (m * m).sum(1).sqrt()
+    if rel_weight is not None:
+        s = s * torch.tensor(rel_weight, dtype=torch.float64).index_select(0, rr)
     b, k = bt.b, bt.k
     arg = margin + s[:b].unsqueeze(1) - s[b:].reshape(b, k)
     loss = torch.clamp(arg, min=0).sum()
@@ -219,6 +230,37 @@ def test_gradients_against_library_autograd(model, dist, reduce):
     for name, mine in (("ent", g.ent), ("rel", g.rel), ("w", g.w), ("proj", g.proj)):
         if mine is not None:
             np.testing.assert_allclose(mine, tg[name], rtol=1e-9, atol=1e-11, err_msg=name)
+
+
+@pytest.mark.parametrize("model,dist", [("transe", "l1"), ("transe", "l2"), ("transe", "l2_sq"), ("toruse", "torus_l2"),
+                                        ("transh", "l2")])
+def test_relation_weight_against_library_autograd(model, dist):
+    wl, tabs, bt = small_problem(model, dist, n_ent=40, n_rel=5, b=64, k=2, dim=16, seed=23, grid=12)
+    wts = np.array([0.5, 2.0, 1.0, 1.75, 0.25], np.float32)
+    cfg = oracle_config(wl, bf16=False)
+    tb = oracle_tables(tabs)
+    plain_fw = stxo.forward(cfg, tb, bt)
+    tb.rel_weight = wts
+    fw = stxo.forward(cfg, tb, bt)
+    g = stxo.backward(cfg, tb, bt)
+    loss, tg = _torch_loss(model, dist, stxo.SUM, wl.margin, tabs, bt, wl.n_ent, rel_weight=wts)
+    assert fw.loss == pytest.approx(loss, rel=1e-12) and fw.loss != plain_fw.loss
+    rr = np.concatenate([bt.r, np.repeat(bt.r, bt.k)])
+    np.testing.assert_allclose(fw.scores, plain_fw.scores * wts[rr].astype(np.float64), rtol=1e-15)
+    for name, mine in (("ent", g.ent), ("rel", g.rel), ("w", g.w)):
+        if mine is not None:
+            np.testing.assert_allclose(mine, tg[name], rtol=1e-9, atol=1e-11, err_msg=name)
+    # weights of one change nothing, bit for bit
+    tb.rel_weight = np.ones(5, np.float32)
+    g1, g0 = stxo.backward(cfg, tb, bt), stxo.backward(cfg, oracle_tables(tabs), bt)
+    assert np.array_equal(g1.ent, g0.ent)
+    # the column-wise gradient used for spot checks at large sizes sees the weights too
+    if cfg.stacked:
+        tb.rel_weight = wts
+        active = (fw.hinge_arg > 0).astype(np.uint8)
+        for col in (0, 7, wl.n_ent + 1):
+            want, _ = stxo.grad_column_stacked(cfg, tb, bt, active, col)
+            np.testing.assert_allclose(want, g.ent[col], rtol=1e-12, atol=1e-14)
 
 
 def test_transe_gradient_is_transposed_spmm():

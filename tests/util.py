@@ -17,7 +17,7 @@ def oracle_config(wl: W.Workload, reduce=stxo.SUM, bf16=None) -> stxo.Config:
 
 def oracle_tables(tabs: dict) -> stxo.Tables:
     return stxo.Tables(tabs["ent"].copy(), *(None if tabs.get(k) is None else tabs[k].copy()
-                                             for k in ("rel", "w", "proj")))
+                                             for k in ("rel", "w", "proj", "rel_weight")))
 
 
 def oracle_batch(wl: W.Workload, h, r, t, lo, hi, seed=None, epoch=0) -> stxo.Batch:
