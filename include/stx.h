@@ -69,7 +69,9 @@ typedef struct {
 
 /* Parameter tables (device, fp32, row-major), updated in place by stx_sgd_step.
  *   TransE / TorusE : ent = X = [E;R], (n_ent + n_rel) x dim, relation r in row n_ent + r (Sec. 4.2.2);
- *                     rel, w, proj unused.
+ *                     rel, w, proj unused.  rel_weight (optional, n_rel floats, read only): a fixed weight
+ *                     per relation that multiplies the distance of its triplets, the TransM row of
+ *                     Table 2; null = all ones.  The other models reject a non-null rel_weight.
  *   TransH          : ent = E (n_ent x dim), rel = d_r (n_rel x dim), w = w_r (n_rel x dim)  (Sec. 4.5).
  *   TransR          : ent = E (n_ent x dim), rel = r (n_rel x rel_dim),
  *                     proj = M_r (n_rel x rel_dim x dim, each matrix row-major)               (Sec. 4.4). */
@@ -78,6 +80,7 @@ typedef struct {
     float *rel;
     float *w;
     float *proj;
+    const float *rel_weight;
 } stx_params;
 
 /* One batch as a sparse incidence matrix and its transpose (Sec. 4.2; Appendix G).

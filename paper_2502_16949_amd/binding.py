@@ -42,7 +42,8 @@ class stx_config(C.Structure):
 
 
 class stx_params(C.Structure):
-    _fields_ = [("ent", C.c_void_p), ("rel", C.c_void_p), ("w", C.c_void_p), ("proj", C.c_void_p)]
+    _fields_ = [("ent", C.c_void_p), ("rel", C.c_void_p), ("w", C.c_void_p), ("proj", C.c_void_p),
+                ("rel_weight", C.c_void_p)]
 
 
 class stx_incidence(C.Structure):
@@ -208,11 +209,11 @@ class Grads:
 
 
 class Params:
-    def __init__(self, ent, rel=None, w=None, proj=None):
-        self.ent, self.rel, self.w, self.proj = ent, rel, w, proj
-        for t in (ent, rel, w, proj):
+    def __init__(self, ent, rel=None, w=None, proj=None, rel_weight=None):
+        self.ent, self.rel, self.w, self.proj, self.rel_weight = ent, rel, w, proj, rel_weight
+        for t in (ent, rel, w, proj, rel_weight):
             assert t is None or (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous())
-        self.c = stx_params(_ptr(ent), _ptr(rel), _ptr(w), _ptr(proj))
+        self.c = stx_params(_ptr(ent), _ptr(rel), _ptr(w), _ptr(proj), _ptr(rel_weight))
 
 
 def _i32dev(t):

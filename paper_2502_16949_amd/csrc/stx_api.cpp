@@ -127,6 +127,7 @@ stx_status check_params(const stx_ctx *ctx, const stx_params *p)
     if (!p || !p->ent) return STX_ERR_NULL;
     if (ctx->cfg.model == STX_TRANSH && (!p->rel || !p->w)) return STX_ERR_NULL;
     if (ctx->cfg.model == STX_TRANSR && (!p->rel || !p->proj)) return STX_ERR_NULL;
+    if (p->rel_weight && ctx->cfg.model != STX_TRANSE && ctx->cfg.model != STX_TORUSE) return STX_ERR_UNSUPPORTED;
     return STX_OK;
 }
 

@@ -100,7 +100,8 @@ static void forward_go(stx_ctx *c, const stx_incidence *inc, const stx_params *p
     constexpr int GROUPS = kThreads / LPR;
     dim3 grid((unsigned)((inc->b + GROUPS - 1) / GROUPS));
     const ForwardArgs fa{inc->a_colidx, p->ent, inc->b, inc->k, width, c->cfg.margin, scale, scores, c->gbuf[0],
-                         packed_stride(c->cfg.dim), c->loss_partials};
+                         packed_stride(c->cfg.dim), c->loss_partials, from_y ? nullptr : p->rel_weight,
+                         (int32_t)c->cfg.n_ent};
 #define STX_FWD(D, Y, P)                                                                                        \
     hipLaunchKernelGGL((k_forward_stacked<LPR, ITERS, D, Y, P>), grid, dim3(kThreads), 0, c->stream, fa)
 #define STX_FWD2(D)                                                                                             \

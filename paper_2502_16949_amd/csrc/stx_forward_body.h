@@ -90,10 +90,13 @@ __device__ inline void forward_stacked_body(const int block, const ForwardArgs &
         // column ids, then all table rows) instead of two per row; the positive rides with the first batch.
         constexpr int NB = ITERS <= 2 ? 4 : 2;
         RowVec<ITERS> xp;
-        float dpos = 0.f;
+        float dpos = 0.f, npos = 0.f;   // the positive's score and its norm (they differ by the relation's weight)
         int n_active = 0;
         int32_t cp[3] = {0, 0, 0};
         if (!FROM_Y) { cp[0] = colidx[3 * i]; cp[1] = colidx[3 * i + 1]; cp[2] = colidx[3 * i + 2]; }
+        // Table 2, TransM row: a fixed weight per relation multiplies the norm (1 when there is none; the
+        // negatives of a positive keep its relation).  Multiplying by 1 changes no bit.
+        const float wr = (!FROM_Y && a.rel_weight) ? a.rel_weight[cp[1] - a.n_ent] : 1.0f;
         for (int kk0 = 0; kk0 < k || kk0 == 0; kk0 += NB) {
             const int nb = min(NB, k - kk0);
             const int64_t row0 = (int64_t)b + i * k + kk0;
@@ -118,31 +121,34 @@ __device__ inline void forward_stacked_body(const int block, const ForwardArgs &
                 }
             }
             if (kk0 == 0) {
-                dpos = row_distance<LPR, ITERS, DIST>(xp);
+                npos = row_distance<LPR, ITERS, DIST>(xp);
+                dpos = wr * npos;
                 if (lig == 0) scores[i] = dpos;
             }
 #pragma unroll
             for (int q = 0; q < NB; ++q) {
                 if (q < nb) {
                     const int64_t row = row0 + q;
-                    const float dneg = row_distance<LPR, ITERS, DIST>(xn[q]);
+                    const float nneg = row_distance<LPR, ITERS, DIST>(xn[q]);
+                    const float dneg = wr * nneg;
                     const float arg = (margin + dpos) - dneg;
                     const bool active = arg > 0.f;
                     if (lig == 0) scores[row] = dneg;
                     if (active) { hinge_sum += arg; ++n_active; }
                     if (PACKED)
                         write_grad_row_packed<LPR, ITERS, DIST>(reinterpret_cast<uint8_t *>(G), gstride, row, d4, lig,
-                                                                xn[q], active ? -scale : 0.f);
+                                                                xn[q], active ? -scale * wr : 0.f);
                     else
-                        write_grad_row<LPR, ITERS, DIST>(G + row * dim, d4, lig, xn[q], active ? -scale : 0.f, dneg);
+                        write_grad_row<LPR, ITERS, DIST>(G + row * dim, d4, lig, xn[q], active ? -scale * wr : 0.f,
+                                                         nneg);
                 }
             }
         }
         if (PACKED)
             write_grad_row_packed<LPR, ITERS, DIST>(reinterpret_cast<uint8_t *>(G), gstride, i, d4, lig, xp,
-                                                    (float)n_active * scale);
+                                                    (float)n_active * scale * wr);
         else
-            write_grad_row<LPR, ITERS, DIST>(G + i * dim, d4, lig, xp, (float)n_active * scale, dpos);
+            write_grad_row<LPR, ITERS, DIST>(G + i * dim, d4, lig, xp, (float)n_active * scale * wr, npos);
     }
     if (lig == 0) s_loss[grp] = hinge_sum;
     __syncthreads();

@@ -98,6 +98,8 @@ struct ForwardArgs {
     float *scores, *G;
     int gstride;
     float *loss_partials;
+    const float *rel_weight;   // fixed weight of every relation's distance, or null (gathered rows only)
+    int32_t n_ent;
 };
 
 struct ScatterArgs {

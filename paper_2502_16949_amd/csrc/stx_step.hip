@@ -92,7 +92,8 @@ bool launch_fwd_scatter(stx_ctx *c, const stx_incidence *inc, StepFusion *f, con
         return true;
     }
     const ForwardArgs fa{inc->a_colidx, f->p->ent, inc->b, inc->k, c->cfg.dim, c->cfg.margin, f->scale, f->scores,
-                         c->gbuf[0], packed_stride(c->cfg.dim), c->loss_partials};
+                         c->gbuf[0], packed_stride(c->cfg.dim), c->loss_partials, f->p->rel_weight,
+                         (int32_t)c->cfg.n_ent};
     const unsigned blocks = (unsigned)(sa.ntiles + f->n_partials);
     ProfScope prof(c, "k_fwd_scatter");
     if (L.lpr == 8) fwd_scatter_go<8, 1>(c, fa, sa, blocks);

@@ -30,7 +30,7 @@ class GpuModel:
                                  reduce=reduce, flags=flags)
         self.ctx = B.Context(self.cfg, DEV)
         self.params = B.Params(*(None if tabs.get(k) is None else dev_f32(tabs[k])
-                                 for k in ("ent", "rel", "w", "proj")))
+                                 for k in ("ent", "rel", "w", "proj", "rel_weight")))
         self.inc = B.Incidence(self.ctx)
         self.grads = B.Grads(self.ctx)
         self.scores = torch.empty(self.ctx.rows_max, dtype=torch.float32, device=DEV)

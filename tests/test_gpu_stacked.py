@@ -135,6 +135,31 @@ STEP_CASES = [
 @pytest.mark.parametrize("model,dist,n_ent,n_rel,b,k,dim,zipf", STEP_CASES)
 def test_training_step_matches_oracle(model, dist, n_ent, n_rel, b, k, dim, zipf, reduce):
     wl, tabs, bt = _problem(model, dist, n_ent, n_rel, b, k, dim, seed=dim + b, zipf=zipf)
+    _check_step(wl, tabs, bt, model, dim, reduce)
+
+
+@pytest.mark.parametrize("model,dist,dim", [("transe", "l1", 128), ("transe", "l2", 128), ("transe", "l2_sq", 64),
+                                            ("toruse", "torus_l2", 128), ("toruse", "torus_l1", 256)])
+def test_relation_weights_match_oracle(model, dist, dim):
+    """Table 2, TransM row: a fixed weight per relation multiplies the distance."""
+    wl, tabs, bt = _problem(model, dist, 400, 9, 777, 3, dim, seed=31, zipf=1.1)
+    tabs["rel_weight"] = np.random.default_rng(4).uniform(0.25, 2.0, 9).astype(np.float32)
+    _check_step(wl, tabs, bt, model, dim, B.STX_SUM)
+
+
+def test_relation_weights_are_rejected_where_unsupported():
+    wl = W.Workload("case", 7, "transh", "l2", 100, 5, 64, 64, 64, 64, 1, 1.0, 0.01, 1, 0.0, 0.0)
+    tabs = W.make_tables(wl)
+    tabs["rel_weight"] = np.ones(5, np.float32)
+    h, r, t = W.make_graph(wl)
+    m = G.GpuModel(wl, tabs)
+    m.build(oracle_batch(wl, h, r, t, 0, 64))
+    with pytest.raises(B.StxError) as ei:
+        m.forward()
+    assert ei.value.status == B.STX_ERR_UNSUPPORTED
+
+
+def _check_step(wl, tabs, bt, model, dim, reduce):
     lr = 0.01
     cfg = oracle_config(wl, reduce=reduce)
     m = G.GpuModel(wl, tabs, reduce=reduce)
