@@ -27,7 +27,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 # The kernel whose roofline is reported: the one with the largest share of GPU time in the
 # rocprofv3 kernel trace of the same command (profiles/).
-DOMINANT = {"mid": "k_seg_reduce", "tiny": "k_seg_reduce", "toruse": "k_seg_reduce", "transh": "k_fwdh_scatter",
+DOMINANT = {"mid": "k_fwd_scatter", "tiny": "k_fwd_scatter", "toruse": "k_seg_reduce", "transh": "k_seg_reduce",
             "transr": "k_transr_project", "paper_transe": "k_seg_reduce", "paper_toruse": "k_seg_reduce",
             "paper_transr": "k_transr_project"}
 # ... and when the step is made of the separate calls (--api fused | separate)
@@ -41,16 +41,17 @@ DOMINANT_CALLS = {"mid": "k_seg_reduce", "tiny": "k_seg_reduce", "toruse": "k_se
 # x1.0); the runs and their numbers are in profiles/<workload>_kernel_trace.txt and profiles/copy_calibration.txt.
 # A different kernel (--kernel) or workload has no measured figure here and reports null.
 # Keys: (workload, kernel, fused step or not).
-TRAFFIC_BYTES = {("mid", "k_forward_stacked", True): 24.16e6 + 4.48e6,
-                 ("mid", "k_forward_stacked", False): 24.16e6 + 4.48e6,
-                 ("mid", "k_seg_reduce", True): 28.08e6 + 8.47e6,
-                 ("transh", "k_seg_reduce", True): 65.32e6 + 4.64e6,
-                 ("transh", "k_seg_reduce", False): 65.32e6 + 4.64e6,
-                 ("transr", "k_transr_project", True): 28.29e6 + 25.01e6,
-                 ("transr", "k_transr_project", False): 28.29e6 + 25.01e6,
-                 ("toruse", "k_seg_reduce", True): 973.02e6 + 532.15e6,
+TRAFFIC_BYTES = {("mid", "k_fwd_scatter", True): 26.10e6 + 7.33e6,
+                 ("mid", "k_seg_reduce", True): 28.19e6 + 8.47e6,
+                 ("transh", "k_seg_reduce", True): 140.49e6 + 9.29e6,
+                 ("transh", "k_fwdh_scatter", True): 32.45e6 + 101.56e6,
+                 ("transr", "k_transr_project", True): 28.28e6 + 25.11e6,
+                 ("transr", "k_transr_project", False): 28.28e6 + 25.11e6,
+                 ("toruse", "k_seg_reduce", True): 972.93e6 + 532.22e6,
                  ("toruse", "k_forward_stacked", True): 704.01e6 + 90.19e6,
-                 ("toruse", "k_forward_stacked", False): 704.01e6 + 90.19e6}
+                 ("toruse", "k_forward_stacked", False): 704.01e6 + 90.19e6,
+                 # mean of the two batches of an epoch (393,216 and 89,926 positives), like the timed mean
+                 ("paper_transe", "k_seg_reduce", True): (9761.85e6 + 104.19e6 + 2281.04e6 + 99.90e6) / 2}
 
 
 def parse():
@@ -95,9 +96,10 @@ def kernel_work(wl, kernel, rows, touched, fused=False):
     if kernel == "k_seg_reduce":
         # one source row + 4 B packed entry per sorted entry in, one row per column out, over all 3*rows entries
         if wl.model == "transh":   # both products (all entries -> dE, d(d_r); relation entries -> dw_r) in one launch
-            return nnz * (row + 4) + touched * row + rows * (row + 4) + min(wl.n_rel, rows) * row, "GB/s", "hbm", HBM_PEAK_GBS
+            out_rows = (touched + min(wl.n_rel, rows)) * row * (2 if fused else 1)   # fused: table row in, table row out
+            return nnz * (row + 4) + rows * (row + 4) + out_rows, "GB/s", "hbm", HBM_PEAK_GBS
         if wl.model == "transr":   # one launch when dim == rel_dim
-            return nnz * (row + 4) + touched * row, "GB/s", "hbm", HBM_PEAK_GBS
+            return nnz * (row + 4) + touched * row * (2 if fused else 1), "GB/s", "hbm", HBM_PEAK_GBS
         if fused and wl.model in ("transe", "toruse"):
             # fused update: the table row is read and written where the gradient row would have been written
             return nnz * (grow + 4) + touched * 2 * row, "GB/s", "hbm", HBM_PEAK_GBS
