@@ -201,6 +201,44 @@ void stxo_spmm_csr(int64_t nrows, const int32_t *rowptr, const int32_t *colidx, 
     }
 }
 
+/* The semiring products of Appendix D over rows with three stored entries (head, relation, tail
+ * columns, in that order, as in the hrt incidence matrix): the model's multiplication takes the
+ * place of the sum over the row's entries.  fp32, every real product and sum rounded once.
+ *   kind 0, DistMult: z_j = (h_j r_j) t_j
+ *   kind 1, ComplEx : rows are d/2 complex numbers stored (re, im); z = (h r) conj(t)
+ *   kind 2, RotatE  : the same storage; z = h r - t
+ * with the complex product (a+bi)(c+di) = (ac - bd) + (ad + bc)i.                              */
+static void cmul(float a, float b, float c, float d, float *re, float *im)
+{
+    volatile float ac = a * c, bd = b * d, ad = a * d, bc = b * c;
+    *re = ac - bd;
+    *im = ad + bc;
+}
+
+int stxo_spmm_semiring(int64_t nrows, const int32_t *colidx, const float *X, int32_t d, int32_t kind, float *Z)
+{
+    if (kind < 0 || kind > 2 || (kind != 0 && d % 2 != 0)) return 1;
+    for (int64_t i = 0; i < nrows; ++i) {
+        const float *h = X + (int64_t)colidx[3 * i] * d, *r = X + (int64_t)colidx[3 * i + 1] * d;
+        const float *t = X + (int64_t)colidx[3 * i + 2] * d;
+        float *z = Z + i * d;
+        if (kind == 0) {
+            for (int32_t j = 0; j < d; ++j) {
+                volatile float hr = h[j] * r[j];
+                z[j] = hr * t[j];
+            }
+        } else {
+            for (int32_t j = 0; j < d; j += 2) {
+                float re, im;
+                cmul(h[j], h[j + 1], r[j], r[j + 1], &re, &im);
+                if (kind == 1) cmul(re, im, t[j], -t[j + 1], &z[j], &z[j + 1]);
+                else { z[j] = re - t[j]; z[j + 1] = im - t[j + 1]; }
+            }
+        }
+    }
+    return 0;
+}
+
 /* out (ncols x d, double, caller-zeroed) += A^T G, looping over the rows of A.                 */
 void stxo_spmm_csr_t(int64_t nrows, const int32_t *rowptr, const int32_t *colidx, const float *vals,
                      const float *G, int32_t d, double *out)

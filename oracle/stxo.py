@@ -67,6 +67,8 @@ def lib():
         _lib.stxo_build_incidence.argtypes = [C.c_void_p, C.c_int64, C.c_int64] + [C.c_void_p] * 9
         _lib.stxo_spmm_csr.restype = None
         _lib.stxo_spmm_csr.argtypes = [C.c_int64] + [C.c_void_p] * 4 + [C.c_int32, C.c_void_p]
+        _lib.stxo_spmm_semiring.restype = C.c_int
+        _lib.stxo_spmm_semiring.argtypes = [C.c_int64, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
         _lib.stxo_spmm_csr_t.restype = None
         _lib.stxo_spmm_csr_t.argtypes = [C.c_int64] + [C.c_void_p] * 4 + [C.c_int32, C.c_void_p]
         _lib.stxo_forward.restype = C.c_int
@@ -212,6 +214,20 @@ def spmm_csr(rowptr, colidx, vals, X, nrows=None):
     d = X.shape[1]
     out = np.empty((nrows, d), np.float32)
     lib().stxo_spmm_csr(nrows, _p(_i32(rowptr)), _p(_i32(colidx)), _p(_f32(vals)), _p(X), d, _p(out))
+    return out
+
+
+DISTMULT, COMPLEX, ROTATE = 0, 1, 2
+
+
+def spmm_semiring(colidx, X, kind: int):
+    """The semiring products of the paper's Appendix D over rows of three columns (head, relation, tail)."""
+    X = _f32(X)
+    colidx = _i32(colidx)
+    nrows, d = colidx.shape[0] // 3, X.shape[1]
+    out = np.empty((nrows, d), np.float32)
+    if lib().stxo_spmm_semiring(nrows, _p(colidx), _p(X), d, kind, _p(out)) != 0:
+        raise ValueError("stxo_spmm_semiring: bad kind or odd width for a complex kind")
     return out
 
 

@@ -243,3 +243,38 @@ def test_appendix_two_by_two_expansion():
     out = stxo.spmm_csr_t(rowptr, colidx, vals, G, 2)
     want = np.array([[a1 * dc1 + a3 * dc3, a1 * dc2 + a3 * dc4], [a2 * dc1 + a4 * dc3, a2 * dc2 + a4 * dc4]])
     assert np.array_equal(out, want)
+
+
+# ----------------------------------------------------------------------------- Appendix D semirings
+def test_semiring_products_hand_computed():
+    # one row (h, r, t) = columns (0, 1, 2) of a table of width 2 = one complex number per row
+    X = np.array([[1, 2], [3, 4], [5, -6]], np.float32)                  # h = 1+2i, r = 3+4i, t = 5-6i
+    col = np.array([0, 1, 2], np.int32)
+    assert np.array_equal(stxo.spmm_semiring(col, X, stxo.DISTMULT)[0], [15, -48])   # 1*3*5, 2*4*(-6)
+    # (1+2i)(3+4i) = -5+10i;  times conj(t) = 5+6i:  (-5+10i)(5+6i) = -25-60 + (-30+50)i = -85+20i
+    assert np.array_equal(stxo.spmm_semiring(col, X, stxo.COMPLEX)[0], [-85, 20])
+    # RotatE: h r - t = -5+10i - (5-6i) = -10+16i
+    assert np.array_equal(stxo.spmm_semiring(col, X, stxo.ROTATE)[0], [-10, 16])
+    with pytest.raises(ValueError):
+        stxo.spmm_semiring(col, np.ones((3, 3), np.float32), stxo.COMPLEX)             # odd width
+
+
+def test_semiring_products_against_library_complex_arithmetic():
+    rng = np.random.default_rng(3)
+    n, d, rows = 40, 16, 200
+    X = rng.uniform(-1, 1, (n, d)).astype(np.float32)
+    col = rng.integers(0, n, 3 * rows).astype(np.int32)
+    h, r, t = (X[col[s::3]].astype(np.float64) for s in range(3))
+    np.testing.assert_allclose(stxo.spmm_semiring(col, X, stxo.DISTMULT), h * r * t, rtol=3e-7, atol=1e-7)
+    cx = lambda a: a[:, 0::2] + 1j * a[:, 1::2]
+    for kind, want in ((stxo.COMPLEX, cx(h) * cx(r) * np.conj(cx(t))), (stxo.ROTATE, cx(h) * cx(r) - cx(t))):
+        got = stxo.spmm_semiring(col, X, kind).astype(np.float64)
+        np.testing.assert_allclose(got[:, 0::2], want.real, rtol=0, atol=1e-6)
+        np.testing.assert_allclose(got[:, 1::2], want.imag, rtol=0, atol=1e-6)
+    # a unit relation leaves DistMult / ComplEx as h t / h conj(t), and a rotation by r = 1 gives h - t
+    X[1] = np.tile([1, 0], d // 2)
+    col2 = np.array([0, 1, 2], np.int32)
+    np.testing.assert_array_equal(stxo.spmm_semiring(col2, X, stxo.ROTATE)[0], X[0] - X[2])
+    z = stxo.spmm_semiring(col2, X, stxo.COMPLEX)[0].astype(np.float64)
+    want = cx(X[0:1].astype(np.float64)) * np.conj(cx(X[2:3].astype(np.float64)))
+    np.testing.assert_allclose(z[0::2], want.real[0], atol=1e-6)
