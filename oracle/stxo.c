@@ -32,6 +32,7 @@
  *
  * Build: gcc -O2 -std=c99 -ffp-contract=off -fno-fast-math -shared -fPIC stxo.c -o libstxo.so -lm
  */
+#include <complex.h>
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
@@ -234,6 +235,65 @@ int stxo_spmm_semiring(int64_t nrows, const int32_t *colidx, const float *X, int
                 if (kind == 1) cmul(re, im, t[j], -t[j + 1], &z[j], &z[j + 1]);
                 else { z[j] = re - t[j]; z[j + 1] = im - t[j + 1]; }
             }
+        }
+    }
+    return 0;
+}
+
+/* Backward of the semiring products for a real-valued loss L (Appendix D names the products only;
+ * Appendix G's rule "the gradient flows back along the entries of the row" carries over, with the
+ * model's product in place of the sign).  G = dL/dZ, rows of d floats; for the complex kinds a pair
+ * holds (dL/dRe z, dL/dIm z).  With g the complex number made of such a pair, the chain rule gives
+ * dL/dv = g conj(dz/dv) for a factor v the product is holomorphic in, and dL/dv = conj(g) (dz/dconj(v))
+ * for ComplEx's tail, which enters conjugated:
+ *   DistMult  dL/dh = g r t         dL/dr = g h t         dL/dt = g h r       (real numbers)
+ *   ComplEx   dL/dh = g conj(r) t   dL/dr = g conj(h) t   dL/dt = conj(g) h r
+ *   RotatE    dL/dh = g conj(r)     dL/dr = g conj(h)     dL/dt = -g
+ * out (ncols x d, double, caller-zeroed) += these rows at the row's head, relation and tail columns,
+ * looping over the rows in ascending order; scale (same shape) += a bound on the magnitudes of the real
+ * products behind each element (the products of the factors' |re| + |im|), the error scale that a
+ * comparison in single precision needs.                                                              */
+static double l1mod(double complex v) { return fabs(creal(v)) + fabs(cimag(v)); }
+
+int stxo_spmm_semiring_t(int64_t nrows, const int32_t *colidx, const float *X, int32_t d, int32_t kind,
+                         const float *G, double *out, double *scale)
+{
+    if (kind < 0 || kind > 2 || (kind != 0 && d % 2 != 0)) return 1;
+    for (int64_t i = 0; i < nrows; ++i) {
+        const int64_t ch = colidx[3 * i], cr = colidx[3 * i + 1], ct = colidx[3 * i + 2];
+        const float *h = X + ch * d, *r = X + cr * d, *t = X + ct * d, *g = G + i * d;
+        if (kind == 0) {
+            for (int32_t j = 0; j < d; ++j) {
+                const double gj = g[j], hj = h[j], rj = r[j], tj = t[j];
+                out[ch * d + j] += gj * rj * tj;
+                out[cr * d + j] += gj * hj * tj;
+                out[ct * d + j] += gj * hj * rj;
+                scale[ch * d + j] += fabs(gj * rj * tj);
+                scale[cr * d + j] += fabs(gj * hj * tj);
+                scale[ct * d + j] += fabs(gj * hj * rj);
+            }
+            continue;
+        }
+        for (int32_t j = 0; j < d; j += 2) {
+            const double complex gz = g[j] + I * (double)g[j + 1], hz = h[j] + I * (double)h[j + 1];
+            const double complex rz = r[j] + I * (double)r[j + 1], tz = t[j] + I * (double)t[j + 1];
+            double complex dh, dr, dt;
+            double sh, sr, st;
+            if (kind == 1) {
+                dh = gz * conj(rz) * tz;  sh = l1mod(gz) * l1mod(rz) * l1mod(tz);
+                dr = gz * conj(hz) * tz;  sr = l1mod(gz) * l1mod(hz) * l1mod(tz);
+                dt = conj(gz) * hz * rz;  st = l1mod(gz) * l1mod(hz) * l1mod(rz);
+            } else {
+                dh = gz * conj(rz);       sh = l1mod(gz) * l1mod(rz);
+                dr = gz * conj(hz);       sr = l1mod(gz) * l1mod(hz);
+                dt = -gz;                 st = l1mod(gz);
+            }
+            out[ch * d + j] += creal(dh); out[ch * d + j + 1] += cimag(dh);
+            out[cr * d + j] += creal(dr); out[cr * d + j + 1] += cimag(dr);
+            out[ct * d + j] += creal(dt); out[ct * d + j + 1] += cimag(dt);
+            scale[ch * d + j] += sh; scale[ch * d + j + 1] += sh;
+            scale[cr * d + j] += sr; scale[cr * d + j + 1] += sr;
+            scale[ct * d + j] += st; scale[ct * d + j + 1] += st;
         }
     }
     return 0;

@@ -69,6 +69,8 @@ def lib():
         _lib.stxo_spmm_csr.argtypes = [C.c_int64] + [C.c_void_p] * 4 + [C.c_int32, C.c_void_p]
         _lib.stxo_spmm_semiring.restype = C.c_int
         _lib.stxo_spmm_semiring.argtypes = [C.c_int64, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+        _lib.stxo_spmm_semiring_t.restype = C.c_int
+        _lib.stxo_spmm_semiring_t.argtypes = [C.c_int64, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32] + [C.c_void_p] * 3
         _lib.stxo_spmm_csr_t.restype = None
         _lib.stxo_spmm_csr_t.argtypes = [C.c_int64] + [C.c_void_p] * 4 + [C.c_int32, C.c_void_p]
         _lib.stxo_forward.restype = C.c_int
@@ -229,6 +231,19 @@ def spmm_semiring(colidx, X, kind: int):
     if lib().stxo_spmm_semiring(nrows, _p(colidx), _p(X), d, kind, _p(out)) != 0:
         raise ValueError("stxo_spmm_semiring: bad kind or odd width for a complex kind")
     return out
+
+
+def spmm_semiring_t(colidx, X, kind: int, G):
+    """Gradient of a real loss with respect to X through the semiring product, given G = dL/dZ: (gradient,
+    error scale), both (rows of X) x d in float64."""
+    X, G = _f32(X), _f32(G)
+    colidx = _i32(colidx)
+    out = np.zeros(X.shape, np.float64)
+    scale = np.zeros(X.shape, np.float64)
+    if lib().stxo_spmm_semiring_t(colidx.shape[0] // 3, _p(colidx), _p(X), X.shape[1], kind, _p(G), _p(out),
+                                  _p(scale)) != 0:
+        raise ValueError("stxo_spmm_semiring_t: bad kind or odd width for a complex kind")
+    return out, scale
 
 
 def spmm_csr_t(rowptr, colidx, vals, G, ncols):

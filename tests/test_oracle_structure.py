@@ -278,3 +278,70 @@ def test_semiring_products_against_library_complex_arithmetic():
     z = stxo.spmm_semiring(col2, X, stxo.COMPLEX)[0].astype(np.float64)
     want = cx(X[0:1].astype(np.float64)) * np.conj(cx(X[2:3].astype(np.float64)))
     np.testing.assert_allclose(z[0::2], want.real[0], atol=1e-6)
+
+
+def test_semiring_backward_hand_computed():
+    # one row over columns (0, 1, 2), one complex number per table row, dL/dz = g = 1 + i
+    X = np.array([[1, 2], [3, 4], [5, -6]], np.float32)                  # h = 1+2i, r = 3+4i, t = 5-6i
+    col = np.array([0, 1, 2], np.int32)
+    G = np.array([[1, 1]], np.float32)
+    # DistMult, element by element: dh = g r t = (15, -24), dr = g h t = (5, -12), dt = g h r = (3, 8)
+    out, scale = stxo.spmm_semiring_t(col, X, stxo.DISTMULT, G)
+    assert np.array_equal(out, [[15, -24], [5, -12], [3, 8]])
+    assert np.array_equal(scale, np.abs(out))
+    # ComplEx: dh = g conj(r) t = (1+i)(3-4i)(5-6i) = (7-i)(5-6i) = 29-47i
+    #          dr = g conj(h) t = (1+i)(1-2i)(5-6i) = (3-i)(5-6i) = 9-23i
+    #          dt = conj(g) h r = (1-i)(-5+10i) = 5+15i
+    out, _ = stxo.spmm_semiring_t(col, X, stxo.COMPLEX, G)
+    assert np.array_equal(out, [[29, -47], [9, -23], [5, 15]])
+    # RotatE: dh = g conj(r) = (1+i)(3-4i) = 7-i, dr = g conj(h) = (1+i)(1-2i) = 3-i, dt = -g
+    out, scale = stxo.spmm_semiring_t(col, X, stxo.ROTATE, G)
+    assert np.array_equal(out, [[7, -1], [3, -1], [-1, -1]])
+    assert np.array_equal(scale, [[14, 14], [6, 6], [2, 2]])             # (1+1)(3+4), (1+1)(1+2), 1+1
+
+
+def test_semiring_backward_against_library_autograd():
+    # the library differentiates L = sum(G * Z) through its own complex arithmetic; repeated columns inside a
+    # row (h = t, h = r) and across rows exercise the accumulation
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(5)
+    n, d, rows = 12, 8, 60
+    X = rng.uniform(-1, 1, (n, d)).astype(np.float32)
+    col = rng.integers(0, n, 3 * rows).astype(np.int32)
+    col[0:3] = [4, 4, 4]
+    col[3:6] = [2, 7, 2]
+    G = rng.uniform(-1, 1, (rows, d)).astype(np.float32)
+    idx = [torch.from_numpy(col[s::3].astype(np.int64)) for s in range(3)]
+    Gt = torch.from_numpy(G.astype(np.float64))
+    for kind in (stxo.DISTMULT, stxo.COMPLEX, stxo.ROTATE):
+        Xt = torch.from_numpy(X.astype(np.float64)).requires_grad_(True)
+        if kind == stxo.DISTMULT:
+            z = Xt[idx[0]] * Xt[idx[1]] * Xt[idx[2]]
+            loss = (Gt * z).sum()
+        else:
+            Xc = torch.view_as_complex(Xt.reshape(n, d // 2, 2))
+            h, r, t = Xc[idx[0]], Xc[idx[1]], Xc[idx[2]]
+            z = h * r * t.conj() if kind == stxo.COMPLEX else h * r - t
+            loss = (Gt * torch.view_as_real(z).reshape(rows, d)).sum()
+        loss.backward()
+        out, scale = stxo.spmm_semiring_t(col, X, kind, G)
+        np.testing.assert_allclose(out, Xt.grad.numpy(), rtol=0, atol=1e-12)
+        assert np.all(scale >= np.abs(out) - 1e-12)
+
+
+def test_semiring_backward_is_the_directional_derivative():
+    # Z is linear in every table row that a matrix row names once: <G, Z(X + eps D) - Z(X - eps D)> / (2 eps)
+    # equals <dL/dX, D> up to the cubic term, with Z from the forward oracle
+    rng = np.random.default_rng(6)
+    n, d, rows = 30, 8, 50
+    X = rng.uniform(-1, 1, (n, d)).astype(np.float32)
+    col = rng.integers(0, n, 3 * rows).astype(np.int32)
+    G = rng.uniform(-1, 1, (rows, d)).astype(np.float32)
+    D = rng.uniform(-1, 1, (n, d)).astype(np.float32)
+    eps = np.float32(2.0**-6)                                            # X +- eps D is exact enough in fp32
+    for kind in (stxo.DISTMULT, stxo.COMPLEX, stxo.ROTATE):
+        zp = stxo.spmm_semiring(col, X + eps * D, kind).astype(np.float64)
+        zm = stxo.spmm_semiring(col, X - eps * D, kind).astype(np.float64)
+        fd = np.sum(G * (zp - zm)) / (2.0 * float(eps))
+        out, _ = stxo.spmm_semiring_t(col, X, kind, G)
+        assert abs(fd - np.sum(out * D)) <= 2e-3 * max(1.0, abs(fd))
