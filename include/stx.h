@@ -163,6 +163,27 @@ stx_status stx_check_indices(stx_ctx *ctx, int64_t *n_bad);
  * E[h] - E[t] for TransH/TransR, each operation rounded once, in that order.                          */
 stx_status stx_spmm(stx_ctx *ctx, const stx_incidence *inc, const stx_params *p, float *c_out);
 
+/* The same three-entry product under the semirings of Appendix D, for the models it names: the entries
+ * of a row are multiplied instead of added.  TransE / TorusE contexts only (X = [E;R] stacked in p->ent,
+ * columns as in a_colidx; the values of A play no part), else STX_ERR_UNSUPPORTED.
+ *   STX_DISTMULT : z = (h r) t elementwise over the dim floats of a row;
+ *   STX_COMPLEX  : a row is dim/2 complex numbers stored (re, im); z = (h r) conj(t);
+ *   STX_ROTATE   : the same storage; z = h r - t;
+ * with (a + bi)(c + di) = (ac - bd) + (ad + bc)i and every real product and sum rounded once.
+ * z_out: n_rows x dim floats (device, out).                                                           */
+enum { STX_DISTMULT = 0, STX_COMPLEX = 1, STX_ROTATE = 2 };
+stx_status stx_spmm_semiring(stx_ctx *ctx, const stx_incidence *inc, const stx_params *p, int32_t kind,
+                             float *z_out);
+
+/* Backward of stx_spmm_semiring for a real loss (Appendix G's transposed product with Appendix D's
+ * operators).  gz: dL/dZ, n_rows x dim (device, in; complex kinds: (dL/dRe z, dL/dIm z) pairs).
+ * g->rows[s] = sum over the entries of segment s of gz[row] times the conjugated product of the row's
+ * other two factors (head entry: conj(r) t | conj(r); relation entry: conj(h) t | conj(h); tail entry:
+ * ComplEx conj(gz) h r, RotatE -gz; DistMult: the plain products), summed in the fixed order of
+ * stx_backward.  work: 3 * n_rows * dim floats of device scratch owned by the caller (the per-row terms). */
+stx_status stx_spmm_semiring_t(stx_ctx *ctx, const stx_incidence *inc, const stx_params *p, int32_t kind,
+                               const float *gz, float *work, stx_grads *g);
+
 /* Forward (Sec. 4.3-4.6, 5.3): scores[i] = distance of row i (n_rows, fp32); *loss (device, fp32) =
  * sum (or mean) over pairs of max(0, margin + score[i] - score[b + i*k + kk]).  Also stores dL/dy of
  * every row in the workspace for stx_backward: the pair is active when margin + d_pos - d_neg > 0

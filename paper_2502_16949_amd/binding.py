@@ -20,12 +20,13 @@ STX_TRANSE, STX_TRANSH, STX_TRANSR, STX_TORUSE = 0, 1, 2, 3
 STX_L1, STX_L2, STX_TORUS_L1, STX_TORUS_L2, STX_L2_SQ = 0, 1, 2, 3, 4
 STX_SUM, STX_MEAN = 0, 1
 STX_FLAG_RENORM_W, STX_FLAG_BF16_PROJ = 1, 2
+STX_DISTMULT, STX_COMPLEX, STX_ROTATE = 0, 1, 2
 
 MODELS = {"transe": STX_TRANSE, "transh": STX_TRANSH, "transr": STX_TRANSR, "toruse": STX_TORUSE}
 DISTS = {"l1": STX_L1, "l2": STX_L2, "torus_l1": STX_TORUS_L1, "torus_l2": STX_TORUS_L2, "l2_sq": STX_L2_SQ}
 
 EXPORTS = ["stx_workspace_bytes", "stx_create", "stx_destroy", "stx_sample_negatives", "stx_build_incidence",
-           "stx_check_indices", "stx_spmm", "stx_forward", "stx_backward", "stx_sgd_step", "stx_backward_sgd", "stx_train_step", "stx_profile_kernel",
+           "stx_check_indices", "stx_spmm", "stx_spmm_semiring", "stx_spmm_semiring_t", "stx_forward", "stx_backward", "stx_sgd_step", "stx_backward_sgd", "stx_train_step", "stx_profile_kernel",
            "stx_profile_read", "stx_profile_dump", "stx_copy_f32", "stx_status_string"]
 
 
@@ -83,6 +84,9 @@ def lib():
         L.stx_build_incidence.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, C.POINTER(stx_incidence)]
         L.stx_check_indices.argtypes = [vp, C.POINTER(i64)]
         L.stx_spmm.argtypes = [vp, C.POINTER(stx_incidence), C.POINTER(stx_params), vp]
+        L.stx_spmm_semiring.argtypes = [vp, C.POINTER(stx_incidence), C.POINTER(stx_params), i32, vp]
+        L.stx_spmm_semiring_t.argtypes = [vp, C.POINTER(stx_incidence), C.POINTER(stx_params), i32, vp, vp,
+                                          C.POINTER(stx_grads)]
         L.stx_forward.argtypes = [vp, C.POINTER(stx_incidence), C.POINTER(stx_params), vp, vp]
         L.stx_backward.argtypes = [vp, C.POINTER(stx_incidence), C.POINTER(stx_params), C.POINTER(stx_grads)]
         L.stx_sgd_step.argtypes = [vp, C.POINTER(stx_params), C.POINTER(stx_incidence), C.POINTER(stx_grads),
@@ -250,6 +254,21 @@ def stx_spmm(ctx: Context, inc: Incidence, p: Params, c_out):
     assert c_out.is_cuda and c_out.dtype == torch.float32 and c_out.is_contiguous()
     assert c_out.numel() >= inc.n_rows * ctx.cfg.dim
     _check("stx_spmm", lib().stx_spmm(ctx.handle, C.byref(inc.c), C.byref(p.c), c_out.data_ptr()))
+
+
+def stx_spmm_semiring(ctx: Context, inc: Incidence, p: Params, kind: int, z_out):
+    assert z_out.is_cuda and z_out.dtype == torch.float32 and z_out.is_contiguous()
+    assert z_out.numel() >= inc.n_rows * ctx.cfg.dim
+    _check("stx_spmm_semiring", lib().stx_spmm_semiring(ctx.handle, C.byref(inc.c), C.byref(p.c), kind,
+                                                        z_out.data_ptr()))
+
+
+def stx_spmm_semiring_t(ctx: Context, inc: Incidence, p: Params, kind: int, gz, work, g: Grads):
+    for t in (gz, work):
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
+    assert gz.numel() >= inc.n_rows * ctx.cfg.dim and work.numel() >= 3 * inc.n_rows * ctx.cfg.dim
+    _check("stx_spmm_semiring_t", lib().stx_spmm_semiring_t(ctx.handle, C.byref(inc.c), C.byref(p.c), kind,
+                                                            gz.data_ptr(), work.data_ptr(), C.byref(g.c)))
 
 
 def stx_forward(ctx: Context, inc: Incidence, p: Params, scores, loss):

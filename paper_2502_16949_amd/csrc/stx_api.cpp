@@ -385,6 +385,30 @@ stx_status stx_spmm(stx_ctx *ctx, const stx_incidence *inc, const stx_params *p,
     return launch_spmm(ctx, inc, p, c_out);
 }
 
+stx_status stx_spmm_semiring(stx_ctx *ctx, const stx_incidence *inc, const stx_params *p, int32_t kind, float *z_out)
+{
+    if (!ctx) return STX_ERR_NULL;
+    stx_status s = check_built(ctx, inc);
+    if (s != STX_OK) return s;
+    if (!p || !p->ent || !z_out) return STX_ERR_NULL;
+    if (kind < STX_DISTMULT || kind > STX_ROTATE) return STX_ERR_BAD_ARG;
+    if (!stacked(ctx)) return STX_ERR_UNSUPPORTED;
+    return launch_semiring(ctx, inc, p, kind, z_out);
+}
+
+stx_status stx_spmm_semiring_t(stx_ctx *ctx, const stx_incidence *inc, const stx_params *p, int32_t kind,
+                               const float *gz, float *work, stx_grads *g)
+{
+    if (!ctx) return STX_ERR_NULL;
+    stx_status s = check_built(ctx, inc);
+    if (s != STX_OK) return s;
+    if (!p || !p->ent || !gz || !work || !g || !g->rows) return STX_ERR_NULL;
+    if (kind < STX_DISTMULT || kind > STX_ROTATE) return STX_ERR_BAD_ARG;
+    if (((uintptr_t)gz & 15u) || ((uintptr_t)work & 15u)) return STX_ERR_BAD_ARG;
+    if (!stacked(ctx)) return STX_ERR_UNSUPPORTED;
+    return launch_semiring_t(ctx, inc, p, kind, gz, work, g->rows);
+}
+
 stx_status stx_forward(stx_ctx *ctx, const stx_incidence *inc, const stx_params *p, float *scores, float *loss)
 {
     if (!ctx) return STX_ERR_NULL;

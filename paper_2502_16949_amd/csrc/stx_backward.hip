@@ -153,7 +153,7 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
                                                          const int32_t *__restrict__ seg_id, int32_t e_begin,
                                                          int32_t e_end, const float *__restrict__ src_a,
                                                          const float *__restrict__ src_b, int32_t split,
-                                                         int ld_src, int d4, float *__restrict__ out_rows,
+                                                         int ld_src, int tail_off, int d4, float *__restrict__ out_rows,
                                                          int ld_out, float *__restrict__ partials, FusedArgs fu,
                                                          SegSecond sec)
 {
@@ -277,7 +277,9 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
                     }
                     cf[u] = *reinterpret_cast<const float *>(rec);
                 } else {   // entries before `split` read src_a, the rest src_b (entity vs relation columns)
-                    load_row<LPR, ITERS>((ec0 + j0 + u < split ? src_a : src_b) + row * ld_src, d4, lig, v[u]);
+                    // (tail_off: where the rows that tail entries read sit, relative to the head entries' rows)
+                    load_row<LPR, ITERS>((ec0 + j0 + u < split ? src_a : src_b) + row * ld_src + ((mu[u] & 1) ? tail_off : 0),
+                                         d4, lig, v[u]);
                 }
             }
 #pragma unroll
@@ -592,7 +594,7 @@ static int big_tables(const stx_ctx *c)
 template <int LPR, int ITERS>
 static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_t e_end, const float *src_a,
                    const float *src_b, int32_t split, int ld_src, int width, float *out_rows, int ld_out,
-                   bool packed_src, const FusedArgs *fused, const SegSecondHost *second)
+                   bool packed_src, const FusedArgs *fused, const SegSecondHost *second, int tail_off)
 {
     // Entries per lane group: short chunks shorten every group's serial walk when the whole product is
     // small (latency bound); long ones mean fewer partial rows when it is large (bandwidth bound).
@@ -620,7 +622,7 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
             ProfScope prof(c, "k_seg_reduce");                                                                  \
             hipLaunchKernelGGL((k_seg_reduce<LPR, 1, P, CH, F>), grid, dim3(kThreads), 0, c->stream,            \
                                inc->at_packed, inc->at_seg_id, e_begin, e_end, src_a, src_b, split, ld_src,     \
-                               width / 4, out_rows, ld_out, c->partials, fu, sec);                              \
+                               tail_off, width / 4, out_rows, ld_out, c->partials, fu, sec);                    \
         }                                                                                                       \
         if (ntiles > 1) {                                                                                       \
             ProfScope prof(c, "k_seg_fixup");                                                                   \
@@ -642,7 +644,7 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
             ProfScope prof(c, "k_seg_reduce");                                                                  \
             hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH, F>), dim3(ntiles), dim3(kThreads), 0,           \
                                c->stream, inc->at_packed, inc->at_seg_id, e_begin, e_end, src_a, src_b, split,  \
-                               ld_src, width / 4, out_rows, ld_out, c->partials, fu, sec);                      \
+                               ld_src, tail_off, width / 4, out_rows, ld_out, c->partials, fu, sec);            \
         }                                                                                                       \
         if (ntiles > 1) {                                                                                       \
             ProfScope prof(c, "k_seg_fixup");                                                                   \
@@ -677,7 +679,7 @@ static void sgd_go(stx_ctx *c, const stx_incidence *inc, const SgdTables &T, con
 stx_status launch_seg_reduce(stx_ctx *c, const stx_incidence *inc, int64_t e_begin, int64_t e_end,
                              const float *src_a, const float *src_b, int64_t split, int ld_src, int width,
                              float *out_rows, int ld_out, bool packed_src, const SegFusedHost *fh,
-                             const SegSecondHost *second)
+                             const SegSecondHost *second, int tail_off)
 {
     if (e_end <= e_begin) return STX_OK;
     Launch L = row_launch(width);
@@ -687,7 +689,7 @@ stx_status launch_seg_reduce(stx_ctx *c, const stx_incidence *inc, int64_t e_beg
     if (fh) { fu.table = fh->table; fu.table_b = fh->table_b; fu.n_split = fh->n_split; fu.lr = fh->lr; fu.mode = fh->mode; }
     const FusedArgs *fused = fh ? &fu : nullptr;
     STX_DISPATCH_ROW(L, seg_go, c, inc, (int32_t)e_begin, (int32_t)e_end, src_a, src_b, (int32_t)split, ld_src, width,
-                     out_rows, ld_out, packed_src, fused, second);
+                     out_rows, ld_out, packed_src, fused, second, packed_src ? 0 : tail_off);
     return hip_ok(hipGetLastError());
 }
 

@@ -148,6 +148,7 @@ stx_status launch_copy_f32(stx_ctx *, float *dst, const float *src, int64_t n);
 // packed_src: src_a holds packed L1-kind records (see packed_stride), ld_src is the record size in bytes.
 // second: another product of the same row width over the entries [e_begin, e_end), all reading `src`, that
 // runs in the same two launches (its workgroups follow the first product's).
+// tail_off (dense source rows only): entries with value -1 read their row tail_off floats further on.
 // fused: no gradient row is written; the table row of the column (rows of `width` floats; `table` for
 // columns below n_split, row column - n_split of `table_b` for the others) becomes row - lr * gradient
 // instead (mode 1: then its fractional part; mode 2: then rescaled to unit length).  The second
@@ -168,7 +169,7 @@ struct SegFusedHost {
 stx_status launch_seg_reduce(stx_ctx *, const stx_incidence *, int64_t e_begin, int64_t e_end, const float *src_a,
                              const float *src_b, int64_t split, int ld_src, int width, float *out_rows, int ld_out,
                              bool packed_src = false, const SegFusedHost *fused = nullptr,
-                             const SegSecondHost *second = nullptr);
+                             const SegSecondHost *second = nullptr, int tail_off = 0);
 struct SgdTables {
     float *table_a; int width_a; int mode_a;   // columns [0, n_split)
     int64_t n_split;
@@ -178,6 +179,10 @@ struct SgdTables {
 stx_status launch_sgd_rows(stx_ctx *, const stx_incidence *, const SgdTables &, const float *grad_rows,
                            const float *w_rows, float lr);
 stx_status launch_forward_from_y(stx_ctx *, const stx_incidence *, const stx_params *, float *scores, float *loss);
+// stx_semiring.hip
+stx_status launch_semiring(stx_ctx *, const stx_incidence *, const stx_params *, int kind, float *z_out);
+stx_status launch_semiring_t(stx_ctx *, const stx_incidence *, const stx_params *, int kind, const float *gz,
+                             float *work, float *out_rows);
 // stx_transr.hip
 stx_status launch_transr_project(stx_ctx *, const stx_incidence *, const stx_params *);
 // fused_lr: if not null, M_r <- M_r - lr * dL/dM_r is applied in place of the store of dL/dM_r (g may be null)
