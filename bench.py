@@ -71,6 +71,9 @@ def parse():
                     help="instead of the benchmark, run the library's plain copy kernel 20 times on MIB MiB "
                          "(for scaling rocprofv3 byte counters) and exit")
     ap.add_argument("--cpu-steps", type=int, default=0, help="oracle steps to time (0 = pick for ~10-20 s)")
+    ap.add_argument("--semiring", default=None, choices=["distmult", "complex", "rotate"],
+                    help="instead of the training step, time the semiring product of that model and its backward "
+                         "(stx_spmm_semiring + stx_spmm_semiring_t) on the first batch of the workload's graph")
     return ap.parse_args()
 
 
@@ -106,6 +109,12 @@ def kernel_work(wl, kernel, rows, touched, fused=False):
         return nnz * (grow + 4) + touched * row, "GB/s", "hbm", HBM_PEAK_GBS
     if kernel == "k_sgd_rows":
         return touched * 3 * row, "GB/s", "hbm", HBM_PEAK_GBS
+    if kernel == "k_semiring":          # three gathered rows + ids in, the product row out
+        return rows * (3 * row + 12 + row), "GB/s", "hbm", HBM_PEAK_GBS
+    if kernel == "k_semiring_terms":    # three gathered rows, the dL/dZ row and ids in, three term rows out
+        return rows * (4 * row + 12 + 3 * row), "GB/s", "hbm", HBM_PEAK_GBS
+    if kernel == "k_seg_reduce_terms":  # the transposed product over the term rows: one row per entry in, one per column out
+        return nnz * (row + 4) + touched * row, "GB/s", "hbm", HBM_PEAK_GBS
     if kernel == "k_scatter":
         return nnz * 16, "GB/s", "hbm", HBM_PEAK_GBS      # key + payload in, key + payload out
     # TransR's three products: 2*d*k flop per row against ~2 KB of row traffic is ~20 flop per byte, far left of
@@ -141,6 +150,81 @@ def cpu_baseline(wl, h, r, t, tabs, n_steps):
     return rows / dt, done, dt
 
 
+def bench_semiring(args, wl, dev):
+    """Forward and backward of one semiring product (Appendix D) over the rows of one batch."""
+    import numpy as np
+    import torch
+
+    from paper_2502_16949_amd import binding as B
+    from paper_2502_16949_amd import workloads as W
+    kind = {"distmult": B.STX_DISTMULT, "complex": B.STX_COMPLEX, "rotate": B.STX_ROTATE}[args.semiring]
+    h, r, t = W.make_graph(wl)
+    tabs = W.make_tables(wl)
+    b = min(wl.batch, wl.n_triplets)
+    hd, rd, td = (torch.from_numpy(a[:b].copy()).to(dev) for a in (h, r, t))
+    cfg = B.make_config("transe", "l2", wl.n_ent, wl.n_rel, wl.dim, b, wl.n_neg, margin=wl.margin)
+    ctx = B.Context(cfg, dev)
+    ent = tabs["ent"] if tabs["ent"].shape[0] == wl.n_ent + wl.n_rel else np.concatenate([tabs["ent"], tabs["rel"]])
+    params = B.Params(torch.from_numpy(np.ascontiguousarray(ent[:, :wl.dim])).to(dev))
+    inc, grads = B.Incidence(ctx), B.Grads(ctx)
+    nh = torch.empty(b * wl.n_neg, dtype=torch.int32, device=dev)
+    nt = torch.empty_like(nh)
+    B.stx_sample_negatives(ctx, hd, rd, td, wl.n_neg, W.negative_seed(wl), 0, wl.n_triplets, 0, nh, nt)
+    B.stx_build_incidence(ctx, hd, rd, td, nh, nt, wl.n_neg, inc)
+    rows = inc.n_rows
+    z = torch.empty(rows, wl.dim, dtype=torch.float32, device=dev)
+    gz = torch.rand(rows, wl.dim, dtype=torch.float32, device=dev) - 0.5
+    work = torch.empty(3 * rows * wl.dim, dtype=torch.float32, device=dev)
+    kernel = args.kernel or "k_semiring_terms"
+    for _ in range(args.warmup):
+        B.stx_spmm_semiring(ctx, inc, params, kind, z)
+        B.stx_spmm_semiring_t(ctx, inc, params, kind, gz, work, grads)
+    torch.cuda.synchronize()
+    B.stx_profile_kernel(ctx, kernel, 4 * args.steps)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        B.stx_spmm_semiring(ctx, inc, params, kind, z)
+        B.stx_spmm_semiring_t(ctx, inc, params, kind, gz, work, grads)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kernel_us, kernel_n = B.stx_profile_read(ctx)
+    u = int(inc.n_touched.item())
+    work_b, unit, bound, peak = kernel_work(wl, "k_seg_reduce_terms" if kernel == "k_seg_reduce" else kernel, rows, u)
+    achieved = work_b / (kernel_us * 1e-6) / 1e9 if kernel_us > 0 else 0.0
+    n_ph = min(args.steps, 40)
+    B.stx_profile_kernel(ctx, "*", 8 * n_ph)
+    for _ in range(n_ph):
+        B.stx_spmm_semiring(ctx, inc, params, kind, z)
+        B.stx_spmm_semiring_t(ctx, inc, params, kind, gz, work, grads)
+    kernels_us = {k: [round(v[0], 2), round(v[1] / n_ph, 2)] for k, v in B.stx_profile_dump(ctx).items()}
+    out = {"metric": f"semiring product rows/sec ({args.semiring}: forward + backward) d={wl.dim} fp32",
+           "value": round(rows * args.steps / dt, 1), "unit": "rows/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 4), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"{wl.name} graph, first batch: {rows} rows, {u} touched columns, dim {wl.dim}",
+                      "step": "stx_spmm_semiring + stx_spmm_semiring_t"},
+           "roofline": {"bound": bound, "kernel": kernel, "achieved": round(achieved, 1), "peak": peak, "unit": unit,
+                        "frac": round(achieved / peak, 4), "traffic": None, "work_per_launch": int(work_b),
+                        "avg_launch_us": round(kernel_us, 2), "launches_per_step": round(kernel_n / args.steps, 2)},
+           "kernels_us": kernels_us}
+    if not args.no_cpu_baseline:
+        from oracle import stxo
+        from tests.util import oracle_batch
+        bt = oracle_batch(wl, h, r, t, 0, b)
+        oinc = stxo.build_incidence(bt, wl.n_ent, wl.n_rel)
+        okind = {"distmult": stxo.DISTMULT, "complex": stxo.COMPLEX, "rotate": stxo.ROTATE}[args.semiring]
+        gzn = gz.cpu().numpy()
+        n, t0 = 0, time.perf_counter()
+        while time.perf_counter() - t0 < 10.0:
+            stxo.spmm_semiring(oinc.colidx, ent, okind)
+            stxo.spmm_semiring_t(oinc.colidx, ent, okind, gzn)
+            n += 1
+        cdt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(rows * n / cdt, 1), "unit": "rows/s", "cores": 1, "kind": "oracle",
+                               "sample": f"{n} forward + backward passes over the same batch, {cdt:.1f} s, single thread"}
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -169,6 +253,9 @@ def main():
         print(json.dumps({"copy_calibration_bytes_read": 4 * n, "bytes_written": 4 * n, "launches": 20}))
         return
     wl = W.WORKLOADS[args.config]
+    if args.semiring:
+        bench_semiring(args, wl, dev)
+        return
     kernel = args.kernel or (DOMINANT if args.api == "step" else DOMINANT_CALLS)[wl.name]
 
     h, r, t = W.make_graph(wl)
