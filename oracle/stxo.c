@@ -17,6 +17,8 @@
  *   - loss: margin ranking, one pre-generated negative set ... Sec. 5.3
  *   - backward of C=AX is A^T dL/dC ........ Appendix G
  *   - three nonzeros per row, cost O(3 m n) . Appendices B, C
+ *   - semiring products and their backward . Appendix D
+ *   - link prediction by exhaustive scoring . Sec. 4.7, Sec. 6.1 (Hits@10)
  *
  * The method reaches exactly the result of the gather/scatter definition (Sec. 6, "Model
  * Accuracies": the sparse form does not change the computational steps), so every model function
@@ -453,6 +455,57 @@ int stxo_forward(const stxo_cfg *c, const stxo_tables *tb, const stxo_batch *bt,
     if (c->reduce == STXO_MEAN) total /= (double)((int64_t)bt->b * bt->k);
     *loss = total;
     free(x); free(y);
+    return 0;
+}
+
+/* Link prediction by exhaustive scoring (the "predicting links" facility of Sec. 4.7; Hits@10, the
+ * accuracy measure of Sec. 6.1, is the share of test triplets whose true entity ranks among the ten
+ * best).  TransE / TorusE only.  The paper fixes no protocol; the reading taken here is the usual raw
+ * (unfiltered) one: for a test triplet (h, r, t) every entity e of the table is a candidate,
+ *   side 0, tail prediction: query point q = h + r, score of e = distance(q - e), true entity t;
+ *   side 1, head prediction: query point q = t - r, score of e = distance(e - q), true entity h;
+ * q and the difference are each rounded once to fp32 (for the tail side that is the x of the training
+ * score, bit for bit), the distance is the model's (row_dist above, summed in double), smaller is
+ * better, and a relation weight (Table 2, TransM) would scale all candidates of a query alike and
+ * plays no part.  Outputs per query:
+ *   true_score : the true entity's score;
+ *   n_less     : candidates scoring strictly below the true entity and outside the band below;
+ *   n_band     : candidates with |score - true| <= tol * (score + true), the true entity among them.
+ * With tol = 0 the band holds the exact ties, the best rank the true entity can claim is 1 + n_less
+ * and the worst n_less + n_band.  With tol > 0 the band holds every candidate whose order against
+ * the true entity a single-precision evaluation may decide either way.                          */
+int stxo_rank(const stxo_cfg *c, const float *X, const int32_t *h, const int32_t *r, const int32_t *t,
+              int64_t nq, int32_t side, double tol, double *true_score, int64_t *n_less, int64_t *n_band)
+{
+    if (!is_stacked(c) || side < 0 || side > 1) return 1;
+    const int32_t d = c->dim;
+    float *q = (float *)malloc(sizeof(float) * (size_t)d);
+    double *y = (double *)malloc(sizeof(double) * (size_t)d);
+    double *score = (double *)malloc(sizeof(double) * (size_t)c->n_ent);
+    if (!q || !y || !score) return 2;
+    for (int64_t i = 0; i < nq; ++i) {
+        const float *eh = X + (int64_t)h[i] * d, *et = X + (int64_t)t[i] * d;
+        const float *er = X + (c->n_ent + r[i]) * (int64_t)d;
+        for (int32_t j = 0; j < d; ++j) q[j] = side == 0 ? eh[j] + er[j] : et[j] - er[j];
+        for (int64_t e = 0; e < c->n_ent; ++e) {
+            const float *ee = X + e * d;
+            for (int32_t j = 0; j < d; ++j) {
+                const float diff = side == 0 ? q[j] - ee[j] : ee[j] - q[j];
+                y[j] = (double)diff;
+            }
+            score[e] = row_dist(c, y, d);
+        }
+        const double st = score[side == 0 ? t[i] : h[i]];
+        int64_t less = 0, band = 0;
+        for (int64_t e = 0; e < c->n_ent; ++e) {
+            if (fabs(score[e] - st) <= tol * (score[e] + st)) ++band;
+            else if (score[e] < st) ++less;
+        }
+        true_score[i] = st;
+        n_less[i] = less;
+        n_band[i] = band;
+    }
+    free(q); free(y); free(score);
     return 0;
 }
 

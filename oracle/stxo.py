@@ -71,6 +71,8 @@ def lib():
         _lib.stxo_spmm_semiring.argtypes = [C.c_int64, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
         _lib.stxo_spmm_semiring_t.restype = C.c_int
         _lib.stxo_spmm_semiring_t.argtypes = [C.c_int64, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32] + [C.c_void_p] * 3
+        _lib.stxo_rank.restype = C.c_int
+        _lib.stxo_rank.argtypes = [C.c_void_p] * 5 + [C.c_int64, C.c_int32, C.c_double] + [C.c_void_p] * 3
         _lib.stxo_spmm_csr_t.restype = None
         _lib.stxo_spmm_csr_t.argtypes = [C.c_int64] + [C.c_void_p] * 4 + [C.c_int32, C.c_void_p]
         _lib.stxo_forward.restype = C.c_int
@@ -244,6 +246,24 @@ def spmm_semiring_t(colidx, X, kind: int, G):
                                   _p(scale)) != 0:
         raise ValueError("stxo_spmm_semiring_t: bad kind or odd width for a complex kind")
     return out, scale
+
+
+TAIL, HEAD = 0, 1
+
+
+def rank(cfg: "Config", X, h, r, t, side: int, tol: float = 0.0):
+    """Raw link-prediction counts of every test triplet against all entities: (true_score float64,
+    n_less int64, n_band int64); see stxo_rank in stxo.c."""
+    X = _f32(X)
+    h, r, t = _i32(h), _i32(r), _i32(t)
+    nq = h.shape[0]
+    ts = np.empty(nq, np.float64)
+    less = np.empty(nq, np.int64)
+    band = np.empty(nq, np.int64)
+    cc = cfg.c()
+    if lib().stxo_rank(C.addressof(cc), _p(X), _p(h), _p(r), _p(t), nq, side, tol, _p(ts), _p(less), _p(band)) != 0:
+        raise ValueError("stxo_rank: TransE / TorusE only, side 0 (tail) or 1 (head)")
+    return ts, less, band
 
 
 def spmm_csr_t(rowptr, colidx, vals, G, ncols):

@@ -1,0 +1,115 @@
+"""Pins of the oracle's link-prediction counts (oracle/stxo.c: stxo_rank) that need no GPU: hand-computed
+cases, brute force through a library distance routine on exactly representable tables, agreement of the true
+entity's score with the training forward pass, and the meaning of the ambiguity band."""
+import numpy as np
+import pytest
+from scipy.spatial.distance import cdist
+
+from oracle import stxo
+from tests.util import oracle_config, oracle_tables, small_problem
+
+
+def _cfg(dist, n_ent, n_rel, dim, model=stxo.TRANSE):
+    return stxo.Config(model, dist, n_ent, n_rel, dim)
+
+
+def test_rank_hand_computed():
+    # four entities in the plane, one relation r = (1, 0) stored after them (row n_ent + 0)
+    X = np.array([[0, 0], [1, 0], [3, 0], [0, 5], [1, 0]], np.float32)
+    h, r = np.array([0, 0, 3], np.int32), np.zeros(3, np.int32)
+    t = np.array([1, 2, 2], np.int32)
+    # tail side, L1: q = h + r.  (0,r,1): q = (1,0), scores 1,0,2,6 -> true 0, nothing below
+    #                            (0,r,2): true 2; entities 1 (0) and 0 (1) are closer
+    #                            (3,r,2): q = (1,5), scores 6,5,7,1 -> true 7, all three others closer
+    ts, less, band = stxo.rank(_cfg(stxo.L1, 4, 1, 2), X, h, r, t, stxo.TAIL)
+    assert ts.tolist() == [0, 2, 7] and less.tolist() == [0, 2, 3] and band.tolist() == [1, 1, 1]
+    # head side, L1: q = t - r.  (0,r,1): q = (0,0), scores 0,1,3,5 -> true entity 0 scores 0
+    #                            (0,r,2): q = (2,0), scores 2,1,1,7 -> true 2, two closer
+    #                            (3,r,2): q = (2,0) -> true entity 3 scores 7, three closer
+    ts, less, band = stxo.rank(_cfg(stxo.L1, 4, 1, 2), X, h, r, t, stxo.HEAD)
+    assert ts.tolist() == [0, 2, 7] and less.tolist() == [0, 2, 3] and band.tolist() == [1, 1, 1]
+    # L2 and its square order the candidates alike; (3,r,2), tail: (1,5)-(3,0) -> sqrt(29)
+    ts, less, _ = stxo.rank(_cfg(stxo.L2, 4, 1, 2), X, h, r, t, stxo.TAIL)
+    assert ts[2] == pytest.approx(np.sqrt(29.0), rel=1e-15) and less.tolist() == [0, 2, 3]
+    ts, less, _ = stxo.rank(_cfg(stxo.L2_SQ, 4, 1, 2), X, h, r, t, stxo.TAIL)
+    assert ts.tolist() == [0, 4, 29] and less.tolist() == [0, 2, 3]
+
+
+def test_rank_exact_ties_are_counted_in_the_band():
+    # entities 1 and 2 coincide; entity 3 is as far from q on the other side
+    X = np.array([[0, 0], [2, 0], [2, 0], [0, 0], [1, 0]], np.float32)   # last row: r = (1, 0); q = h + r = (1, 0)
+    ts, less, band = stxo.rank(_cfg(stxo.L1, 4, 1, 2), X, [0], [0], [1], stxo.TAIL)
+    assert ts[0] == 1 and less[0] == 0 and band[0] == 4                  # all four entities are at distance 1
+    with pytest.raises(ValueError):
+        stxo.rank(stxo.Config(stxo.TRANSH, stxo.L1, 4, 1, 2), X, [0], [0], [1], stxo.TAIL)
+    with pytest.raises(ValueError):
+        stxo.rank(_cfg(stxo.L1, 4, 1, 2), X, [0], [0], [1], 2)
+
+
+@pytest.mark.parametrize("dist,metric", [(stxo.L1, "cityblock"), (stxo.L2, "sqeuclidean"), (stxo.L2_SQ, "sqeuclidean")])
+@pytest.mark.parametrize("side", [stxo.TAIL, stxo.HEAD])
+def test_rank_against_library_distance_matrix(dist, metric, side):
+    # entries are multiples of 1/2 in [-3, 3): sums, differences and squares are exact in both precisions,
+    # so the counts must agree exactly, ties included (a coarse grid makes many)
+    rng = np.random.default_rng(11 + dist + side)
+    n_ent, n_rel, dim, nq = 200, 5, 4, 80
+    X = (rng.integers(-6, 6, (n_ent + n_rel, dim)) / 2.0).astype(np.float32)
+    h, t = rng.integers(0, n_ent, nq).astype(np.int32), rng.integers(0, n_ent, nq).astype(np.int32)
+    r = rng.integers(0, n_rel, nq).astype(np.int32)
+    E, R = X[:n_ent].astype(np.float64), X[n_ent:].astype(np.float64)
+    Q = E[h] + R[r] if side == stxo.TAIL else E[t] - R[r]
+    D = cdist(Q, E, metric)
+    true = D[np.arange(nq), t if side == stxo.TAIL else h]
+    ts, less, band = stxo.rank(_cfg(dist, n_ent, n_rel, dim), X, h, r, t, side)
+    assert np.array_equal(less, (D < true[:, None]).sum(1))
+    assert np.array_equal(band, (D == true[:, None]).sum(1))
+    assert band.max() > 1                                                # the case does contain ties
+    np.testing.assert_allclose(ts, np.sqrt(true) if dist == stxo.L2 else true, rtol=1e-15)
+
+
+@pytest.mark.parametrize("dist", [stxo.TORUS_L1, stxo.TORUS_L2])
+def test_rank_on_the_torus_brute_force(dist):
+    # multiples of 1/64 in [0, 1): fractional parts and their sums are exact
+    rng = np.random.default_rng(21 + dist)
+    n_ent, n_rel, dim, nq = 150, 4, 5, 60
+    X = (rng.integers(0, 64, (n_ent + n_rel, dim)) / 64.0).astype(np.float32)
+    h, t = rng.integers(0, n_ent, nq).astype(np.int32), rng.integers(0, n_ent, nq).astype(np.int32)
+    r = rng.integers(0, n_rel, nq).astype(np.int32)
+    E, R = X[:n_ent].astype(np.float64), X[n_ent:].astype(np.float64)
+    for side in (stxo.TAIL, stxo.HEAD):
+        Q = E[h] + R[r] if side == stxo.TAIL else E[t] - R[r]
+        Y = Q[:, None, :] - E[None, :, :]
+        F = Y - np.floor(Y)                                              # the torus distance is even in y
+        Mn = np.minimum(F, 1.0 - F)
+        D = Mn.sum(2) if dist == stxo.TORUS_L1 else (Mn * Mn).sum(2)
+        true = D[np.arange(nq), t if side == stxo.TAIL else h]
+        ts, less, band = stxo.rank(_cfg(dist, n_ent, n_rel, dim, stxo.TORUSE), X, h, r, t, side)
+        assert np.array_equal(less, (D < true[:, None]).sum(1))
+        assert np.array_equal(band, (D == true[:, None]).sum(1))
+
+
+def test_rank_true_score_is_the_training_score():
+    # tail side: the same x = (h + r) - t and the same distance as the forward pass, bit for bit;
+    # head side: e - (t - r) differs from it by roundings only
+    for model, dist in (("transe", "l1"), ("transe", "l2"), ("toruse", "torus_l1"), ("toruse", "torus_l2")):
+        wl, tabs, bt = small_problem(model, dist, n_ent=40, n_rel=5, b=25, k=0, dim=16, seed=3)
+        cfg = oracle_config(wl)
+        fw = stxo.forward(cfg, oracle_tables(tabs), bt, want_x=False)
+        ts, less, band = stxo.rank(cfg, tabs["ent"], bt.h, bt.r, bt.t, stxo.TAIL)
+        assert np.array_equal(ts, fw.scores[:25])
+        ts_h, _, _ = stxo.rank(cfg, tabs["ent"], bt.h, bt.r, bt.t, stxo.HEAD)
+        np.testing.assert_allclose(ts_h, fw.scores[:25], rtol=2e-6)
+        assert np.all(band >= 1) and np.all(less + band <= 40)
+
+
+def test_rank_band_holds_what_single_precision_cannot_order():
+    # one dimension, five entities and the relation r = 1 in the last row.  Query (h = 0, r, t = 0): q = 1,
+    # the true entity (0) is at distance 1, the others at 1 + 2^-19, 1 - 2^-19, 0.5 and 3
+    X = np.array([[0.0], [2.0 + 2.0**-19], [2.0 - 2.0**-19], [1.5], [4.0], [1.0]], np.float32)
+    ts, less, band = stxo.rank(_cfg(stxo.L1, 5, 1, 1), X, [0], [0], [0], stxo.TAIL, tol=0.0)
+    assert ts[0] == 1.0 and less[0] == 2 and band[0] == 1               # 0.5 and 1 - 2^-19 are closer
+    ts, less, band = stxo.rank(_cfg(stxo.L1, 5, 1, 1), X, [0], [0], [0], stxo.TAIL, tol=1e-5)
+    assert less[0] == 1 and band[0] == 3                                 # only 0.5 is surely closer
+    # the band is symmetric in the two scores and scales with them
+    ts, less, band = stxo.rank(_cfg(stxo.L1, 5, 1, 1), X, [0], [0], [0], stxo.TAIL, tol=0.6)
+    assert less[0] == 0 and band[0] == 5                                 # |3 - 1| <= 0.6 * 4, |0.5 - 1| <= 0.6 * 1.5
