@@ -230,6 +230,24 @@ typedef struct {
 stx_status stx_train_step(stx_ctx *ctx, const stx_batch *batch, stx_incidence *inc, stx_params *p, stx_grads *g,
                           float lr, float *scores, float *loss);
 
+/* Link prediction by exhaustive scoring (Sec. 4.7 lists it among the framework's functions; Hits@10,
+ * Sec. 6.1, is the share of test triplets whose true entity is among the ten best candidates).  Raw,
+ * unfiltered counts; TransE / TorusE contexts only (else STX_ERR_UNSUPPORTED); a relation weight scales
+ * all candidates of a query alike and is ignored.  For test triplet i = (h, r, t) every entity e of the
+ * table is a candidate:
+ *   STX_TAIL : q = X[h] + X[n_ent + r],  y = q - X[e],  the true entity is t;
+ *   STX_HEAD : q = X[t] - X[n_ent + r],  y = X[e] - q,  the true entity is h;
+ * q and y rounded once each, score(e) = the context's distance of y, summed over the row in index order
+ * (the L2 kinds with a fused multiply-add, and compared before the square root).
+ *   true_score[i] : score of the true entity;
+ *   n_less[i]     : candidates scoring strictly below it (the best rank it can claim is 1 + n_less);
+ *   n_equal[i]    : candidates scoring exactly like it, itself included (the worst is n_less + n_equal).
+ * h, r, t: [nq] device, in; the three outputs: [nq] device.  Out-of-range indices are clamped and
+ * counted as in stx_build_incidence.  Cost: nq * n_ent * dim steps of vector arithmetic.               */
+enum { STX_TAIL = 0, STX_HEAD = 1 };
+stx_status stx_rank(stx_ctx *ctx, const stx_params *p, const int32_t *h, const int32_t *r, const int32_t *t,
+                    int64_t nq, int32_t side, float *true_score, int32_t *n_less, int32_t *n_equal);
+
 /* Live timing of one kernel, for benchmarks.  stx_profile_kernel: from now on every launch of the kernel
  * called `kernel_name` (e.g. "k_forward_stacked", "k_seg_reduce", "k_sgd_rows", "k_scatter") on this
  * context is bracketed by a pair of HIP events on the context's stream, for at most max_records

@@ -21,12 +21,13 @@ STX_L1, STX_L2, STX_TORUS_L1, STX_TORUS_L2, STX_L2_SQ = 0, 1, 2, 3, 4
 STX_SUM, STX_MEAN = 0, 1
 STX_FLAG_RENORM_W, STX_FLAG_BF16_PROJ = 1, 2
 STX_DISTMULT, STX_COMPLEX, STX_ROTATE = 0, 1, 2
+STX_TAIL, STX_HEAD = 0, 1
 
 MODELS = {"transe": STX_TRANSE, "transh": STX_TRANSH, "transr": STX_TRANSR, "toruse": STX_TORUSE}
 DISTS = {"l1": STX_L1, "l2": STX_L2, "torus_l1": STX_TORUS_L1, "torus_l2": STX_TORUS_L2, "l2_sq": STX_L2_SQ}
 
 EXPORTS = ["stx_workspace_bytes", "stx_create", "stx_destroy", "stx_sample_negatives", "stx_build_incidence",
-           "stx_check_indices", "stx_spmm", "stx_spmm_semiring", "stx_spmm_semiring_t", "stx_forward", "stx_backward", "stx_sgd_step", "stx_backward_sgd", "stx_train_step", "stx_profile_kernel",
+           "stx_check_indices", "stx_spmm", "stx_spmm_semiring", "stx_spmm_semiring_t", "stx_rank", "stx_forward", "stx_backward", "stx_sgd_step", "stx_backward_sgd", "stx_train_step", "stx_profile_kernel",
            "stx_profile_read", "stx_profile_dump", "stx_copy_f32", "stx_status_string"]
 
 
@@ -87,6 +88,7 @@ def lib():
         L.stx_spmm_semiring.argtypes = [vp, C.POINTER(stx_incidence), C.POINTER(stx_params), i32, vp]
         L.stx_spmm_semiring_t.argtypes = [vp, C.POINTER(stx_incidence), C.POINTER(stx_params), i32, vp, vp,
                                           C.POINTER(stx_grads)]
+        L.stx_rank.argtypes = [vp, C.POINTER(stx_params), vp, vp, vp, i64, i32, vp, vp, vp]
         L.stx_forward.argtypes = [vp, C.POINTER(stx_incidence), C.POINTER(stx_params), vp, vp]
         L.stx_backward.argtypes = [vp, C.POINTER(stx_incidence), C.POINTER(stx_params), C.POINTER(stx_grads)]
         L.stx_sgd_step.argtypes = [vp, C.POINTER(stx_params), C.POINTER(stx_incidence), C.POINTER(stx_grads),
@@ -269,6 +271,16 @@ def stx_spmm_semiring_t(ctx: Context, inc: Incidence, p: Params, kind: int, gz, 
     assert gz.numel() >= inc.n_rows * ctx.cfg.dim and work.numel() >= 3 * inc.n_rows * ctx.cfg.dim
     _check("stx_spmm_semiring_t", lib().stx_spmm_semiring_t(ctx.handle, C.byref(inc.c), C.byref(p.c), kind,
                                                             gz.data_ptr(), work.data_ptr(), C.byref(g.c)))
+
+
+def stx_rank(ctx: Context, p: Params, h, r, t, side: int, true_score, n_less, n_equal):
+    nq = h.numel()
+    assert r.numel() == nq and t.numel() == nq
+    assert true_score.is_cuda and true_score.dtype == torch.float32 and true_score.numel() >= nq
+    for c in (n_less, n_equal):
+        assert c.is_cuda and c.dtype == torch.int32 and c.is_contiguous() and c.numel() >= nq
+    _check("stx_rank", lib().stx_rank(ctx.handle, C.byref(p.c), _i32dev(h), _i32dev(r), _i32dev(t), nq, side,
+                                      true_score.data_ptr(), n_less.data_ptr(), n_equal.data_ptr()))
 
 
 def stx_forward(ctx: Context, inc: Incidence, p: Params, scores, loss):

@@ -409,6 +409,18 @@ stx_status stx_spmm_semiring_t(stx_ctx *ctx, const stx_incidence *inc, const stx
     return launch_semiring_t(ctx, inc, p, kind, gz, work, g->rows);
 }
 
+stx_status stx_rank(stx_ctx *ctx, const stx_params *p, const int32_t *h, const int32_t *r, const int32_t *t,
+                    int64_t nq, int32_t side, float *true_score, int32_t *n_less, int32_t *n_equal)
+{
+    if (!ctx) return STX_ERR_NULL;
+    if (!p || !p->ent) return STX_ERR_NULL;
+    if (nq < 0 || nq > ((int64_t)1 << 31) - 256 || (side != STX_TAIL && side != STX_HEAD)) return STX_ERR_BAD_ARG;
+    if (!stacked(ctx)) return STX_ERR_UNSUPPORTED;
+    if (nq == 0) return STX_OK;
+    if (!h || !r || !t || !true_score || !n_less || !n_equal) return STX_ERR_NULL;
+    return launch_rank(ctx, p, h, r, t, nq, side, true_score, n_less, n_equal);
+}
+
 stx_status stx_forward(stx_ctx *ctx, const stx_incidence *inc, const stx_params *p, float *scores, float *loss)
 {
     if (!ctx) return STX_ERR_NULL;

@@ -179,6 +179,9 @@ struct SgdTables {
 stx_status launch_sgd_rows(stx_ctx *, const stx_incidence *, const SgdTables &, const float *grad_rows,
                            const float *w_rows, float lr);
 stx_status launch_forward_from_y(stx_ctx *, const stx_incidence *, const stx_params *, float *scores, float *loss);
+// stx_rank.hip
+stx_status launch_rank(stx_ctx *, const stx_params *, const int32_t *h, const int32_t *r, const int32_t *t, int64_t nq,
+                       int side, float *true_score, int32_t *n_less, int32_t *n_equal);
 // stx_semiring.hip
 stx_status launch_semiring(stx_ctx *, const stx_incidence *, const stx_params *, int kind, float *z_out);
 stx_status launch_semiring_t(stx_ctx *, const stx_incidence *, const stx_params *, int kind, const float *gz,

@@ -100,6 +100,23 @@ def make_graph(wl: Workload):
     return h, r, t
 
 
+# Test triplets for link prediction: 59,071 is the size of FB15k's test split (the paper's dataset table).
+N_TEST_FB15K = 59_071
+
+
+def make_test_triplets(wl: Workload, n: int = N_TEST_FB15K):
+    """(h, r, t) of n held-out triplets drawn from the same degree laws and id permutations as the training
+    graph, with their own seed (4000 + index)."""
+    rng0 = np.random.Generator(np.random.PCG64(1000 + wl.index))          # the graph's permutations, redrawn
+    perm_e = rng0.permutation(wl.n_ent) if wl.zipf_ent else None
+    perm_r = rng0.permutation(wl.n_rel) if wl.zipf_rel else None
+    rng = np.random.Generator(np.random.PCG64(4000 + wl.index))
+    h = _zipf_draw(rng, wl.n_ent, wl.zipf_ent, n, perm_e)
+    t = _zipf_draw(rng, wl.n_ent, wl.zipf_ent, n, perm_e)
+    r = _zipf_draw(rng, wl.n_rel, wl.zipf_rel, n, perm_r)
+    return h, r, t
+
+
 def make_tables(wl: Workload):
     """Initial parameter tables as a dict of fp32 arrays.  Seed = 2000 + index.
 
