@@ -71,6 +71,10 @@ def parse():
                     help="instead of the benchmark, run the library's plain copy kernel 20 times on MIB MiB "
                          "(for scaling rocprofv3 byte counters) and exit")
     ap.add_argument("--cpu-steps", type=int, default=0, help="oracle steps to time (0 = pick for ~10-20 s)")
+    ap.add_argument("--rank", action="store_true",
+                    help="instead of the training step, time link prediction (stx_rank, tail and head side) of "
+                         "--rank-queries test triplets against all entities of the workload's table")
+    ap.add_argument("--rank-queries", type=int, default=59_071, help="test triplets (default: FB15k's test split size)")
     ap.add_argument("--semiring", default=None, choices=["distmult", "complex", "rotate"],
                     help="instead of the training step, time the semiring product of that model and its backward "
                          "(stx_spmm_semiring + stx_spmm_semiring_t) on the first batch of the workload's graph")
@@ -148,6 +152,84 @@ def cpu_baseline(wl, h, r, t, tabs, n_steps):
         done += 1
     dt = time.perf_counter() - t0
     return rows / dt, done, dt
+
+
+# Vector-ALU peak in operations: 256 compute units x 128 fp32 lanes x 2.4 GHz = 78.6 T operations per second; the
+# published 157.3 TFLOP/s counts every one of them as a fused multiply-add, i.e. two flops.  A sum of absolute
+# differences has no product to fuse, so its flop peak is the operation peak.
+VALU_OPS_PEAK_T = 256 * 128 * 2.4e9 / 1e12
+# vector operations per (query, candidate, row element) in k_rank, and flops they stand for
+RANK_OPS = {"l1": (2, 2), "l2": (2, 3), "l2_sq": (2, 3), "torus_l1": (5, 5), "torus_l2": (5, 6)}
+
+
+def bench_rank(args, wl, dev):
+    """One evaluation pass: tail and head ranking of every test triplet against all entities."""
+    import numpy as np
+    import torch
+
+    from paper_2502_16949_amd import binding as B
+    from paper_2502_16949_amd import workloads as W
+    nq = args.rank_queries
+    h, r, t = W.make_test_triplets(wl, nq)
+    tabs = W.make_tables(wl)
+    cfg = B.make_config(wl.model, wl.dist, wl.n_ent, wl.n_rel, wl.dim, 8, 1, margin=wl.margin)
+    ctx = B.Context(cfg, dev)
+    params = B.Params(torch.from_numpy(tabs["ent"]).to(dev))
+    hd, rd, td = (torch.from_numpy(a).to(dev) for a in (h, r, t))
+    ts = torch.empty(2, nq, dtype=torch.float32, device=dev)
+    less = torch.empty(2, nq, dtype=torch.int32, device=dev)
+    equal = torch.empty(2, nq, dtype=torch.int32, device=dev)
+
+    def step():
+        B.stx_rank(ctx, params, hd, rd, td, B.STX_TAIL, ts[0], less[0], equal[0])
+        B.stx_rank(ctx, params, hd, rd, td, B.STX_HEAD, ts[1], less[1], equal[1])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.stx_profile_kernel(ctx, "k_rank", 2 * args.steps)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kernel_us, kernel_n = B.stx_profile_read(ctx)
+    ops, flops = RANK_OPS[wl.dist]
+    elems = float(nq) * wl.n_ent * wl.dim                     # per launch (one side)
+    achieved = elems * flops / (kernel_us * 1e-6) / 1e12 if kernel_us > 0 else 0.0
+    peak = VALU_OPS_PEAK_T * flops / ops
+    best = 1 + less.cpu().numpy().astype(np.int64)
+    out = {"metric": f"link prediction, test triplets ranked/sec (tail and head, all {wl.n_ent} entities) {wl.model} "
+                     f"{wl.dist} d={wl.dim} fp32",
+           "value": round(nq * args.steps / dt, 1), "unit": "triplets/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 4), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"{wl.name} tables ({wl.n_ent} entities, {wl.n_rel} relations, dim {wl.dim}, {wl.dist}), "
+                                  f"{nq} test triplets (the size of FB15k's test split) from the graph's degree laws",
+                      "step": "stx_rank tail side + stx_rank head side over all test triplets"},
+           "hits_at_10_raw": round(float((best <= 10).mean()), 4),
+           "roofline": {"bound": "alu", "kernel": "k_rank", "achieved": round(achieved, 2), "peak": round(peak, 1),
+                        "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None,
+                        "work_per_launch": int(elems * flops), "avg_launch_us": round(kernel_us, 2),
+                        "launches_per_step": round(kernel_n / args.steps, 2),
+                        "note": f"{ops} vector operations ({flops} flops) per query x candidate x element; peak = 256 CUs x "
+                                "128 lanes x 2.4 GHz operations per second"}}
+    if not args.no_cpu_baseline:
+        from oracle import stxo
+        from tests.util import oracle_config
+        ocfg = oracle_config(wl)
+        n = 8
+        while True:
+            t0 = time.perf_counter()
+            stxo.rank(ocfg, tabs["ent"], h[:n], r[:n], t[:n], stxo.TAIL)
+            stxo.rank(ocfg, tabs["ent"], h[:n], r[:n], t[:n], stxo.HEAD)
+            cdt = time.perf_counter() - t0
+            if cdt >= 8.0 or n >= nq:
+                break
+            n = min(nq, max(n * 2, int(n * 12.0 / max(cdt, 1e-3))))
+        out["cpu_baseline"] = {"value": round(n / cdt, 2), "unit": "triplets/s", "cores": 1, "kind": "oracle",
+                               "sample": f"first {n} test triplets, both sides, {cdt:.1f} s, single thread"}
+    print(json.dumps(out))
 
 
 def bench_semiring(args, wl, dev):
@@ -255,6 +337,9 @@ def main():
     wl = W.WORKLOADS[args.config]
     if args.semiring:
         bench_semiring(args, wl, dev)
+        return
+    if args.rank:
+        bench_rank(args, wl, dev)
         return
     kernel = args.kernel or (DOMINANT if args.api == "step" else DOMINANT_CALLS)[wl.name]
 

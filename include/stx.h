@@ -238,7 +238,8 @@ stx_status stx_train_step(stx_ctx *ctx, const stx_batch *batch, stx_incidence *i
  *   STX_TAIL : q = X[h] + X[n_ent + r],  y = q - X[e],  the true entity is t;
  *   STX_HEAD : q = X[t] - X[n_ent + r],  y = X[e] - q,  the true entity is h;
  * q and y rounded once each, score(e) = the context's distance of y, summed over the row in index order
- * (the L2 kinds with a fused multiply-add, and compared before the square root).
+ * (the L2 kinds with a fused multiply-add, and compared before the square root; the torus kinds on the
+ * fractional part of y as the hardware forms it, which stays below 1 where y - floor(y) would round to 1).
  *   true_score[i] : score of the true entity;
  *   n_less[i]     : candidates scoring strictly below it (the best rank it can claim is 1 + n_less);
  *   n_equal[i]    : candidates scoring exactly like it, itself included (the worst is n_less + n_equal).

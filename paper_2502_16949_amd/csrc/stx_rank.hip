@@ -28,7 +28,7 @@ __device__ inline float rank_step(float acc, float y)
 {
     if (DIST == STX_L1) return acc + fabsf(y);
     if (DIST == STX_L2 || DIST == STX_L2_SQ) return __builtin_fmaf(y, y, acc);
-    const float f = y - floorf(y);
+    const float f = __builtin_amdgcn_fractf(y);            // fractional part, always below 1
     const float m = fminf(f, 1.0f - f);
     return DIST == STX_TORUS_L1 ? acc + m : __builtin_fmaf(m, m, acc);
 }
@@ -40,65 +40,80 @@ struct RankArgs {
     int32_t n_ent, n_rel;
     int dim;
     int32_t slice;                     // candidates per blockIdx.y, a multiple of kRankE
-    float *true_score;                 // [nq]
-    int32_t *n_less, *n_equal;         // [nq], zeroed before the launch
+    float *true_score;                 // [nq]: the true entity's sum until k_rank_finish
+    int32_t *n_less, *n_equal;         // [nq], cleared by k_rank_true
     int32_t *bad;                      // counter of out-of-range indices
 };
 
-__global__ __launch_bounds__(kThreads) void k_rank_clear(int32_t *a, int32_t *b, int64_t n)
+// Clamped table rows of one query: q = h + r (tail side) or t - r (head side); the true entity is t or h.
+struct RankRows {
+    const float *pa, *pr, *ptrue;
+    bool bad;
+};
+template <bool HEAD>
+__device__ inline RankRows rank_rows(const RankArgs &a, int64_t qi)
 {
-    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i < n) { a[i] = 0; b[i] = 0; }
+    int32_t ih = a.h[qi], ir = a.r[qi], it = a.t[qi];
+    const bool bad = ih < 0 || ih >= a.n_ent || it < 0 || it >= a.n_ent || ir < 0 || ir >= a.n_rel;
+    ih = min(max(ih, 0), a.n_ent - 1);
+    it = min(max(it, 0), a.n_ent - 1);
+    ir = min(max(ir, 0), a.n_rel - 1);
+    return {a.X + (int64_t)(HEAD ? it : ih) * a.dim, a.X + ((int64_t)a.n_ent + ir) * a.dim,
+            a.X + (int64_t)(HEAD ? ih : it) * a.dim, bad};
 }
 
+// One thread per query: the true entity's sum, formed step by step in index order exactly as the sweep forms
+// every candidate's, so that the true entity ties with itself there.  Also clears the query's counters.
 template <int DIST, bool HEAD>
-__global__ __launch_bounds__(kThreads) void k_rank(RankArgs a)
+__global__ __launch_bounds__(kThreads) void k_rank_true(RankArgs a)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= a.nq) return;
+    const RankRows rw = rank_rows<HEAD>(a, i);
+    if (rw.bad) atomicAdd(a.bad, 1);
+    float acc = 0.f;
+    for (int j = 0; j < a.dim; j += 4) {
+        const float4 va = ld4(rw.pa + j), vr = ld4(rw.pr + j), ve = ld4(rw.ptrue + j);
+        const float av[4] = {va.x, va.y, va.z, va.w}, rv[4] = {vr.x, vr.y, vr.z, vr.w};
+        const float ev[4] = {ve.x, ve.y, ve.z, ve.w};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float q = HEAD ? av[u] - rv[u] : av[u] + rv[u];
+            acc = rank_step<DIST>(acc, HEAD ? ev[u] - q : q - ev[u]);
+        }
+    }
+    a.true_score[i] = acc;        // the sum; k_rank_finish turns it into the distance after the sweep
+    a.n_less[i] = 0;
+    a.n_equal[i] = 0;
+}
+
+template <int DIST>
+__global__ __launch_bounds__(kThreads) void k_rank_finish(float *true_score, int64_t nq)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i < nq) true_score[i] = finish<DIST>(true_score[i]);
+}
+
+// (three waves per SIMD: the register budget that lets three workgroups share a compute unit)
+template <int DIST, bool HEAD>
+__global__ __launch_bounds__(kThreads, 3) void k_rank(RankArgs a)
 {
     __shared__ __attribute__((aligned(16))) float s_q[kRankJ][kRankLd];
     __shared__ __attribute__((aligned(16))) float s_e[kRankJ][kRankLd];
-    __shared__ float s_true[kRankQ];
 
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;               // candidate / query position of the 8 x 8 block
     const int64_t q0 = (int64_t)blockIdx.x * kRankQ;
     const int dim = a.dim;
 
-    // The query this thread stages (and, in the first half of the workgroup, scores against its true entity).
-    // Past the end the last query is repeated; its counts are not stored.
+    // The query this thread stages; past the end the last query is repeated and its counts are not stored.
     const int sc = tid & (kRankQ - 1);                    // staged query / candidate of this thread
     const int sj = (tid >> 7) * 4;                        // first float of its float4 inside a chunk (then + 8 i)
-    const int64_t qi = min(q0 + sc, a.nq - 1);
-    int32_t ih = a.h[qi], ir = a.r[qi], it = a.t[qi];
-    if (blockIdx.y == 0 && tid < kRankQ && q0 + sc < a.nq &&
-        (ih < 0 || ih >= a.n_ent || it < 0 || it >= a.n_ent || ir < 0 || ir >= a.n_rel))
-        atomicAdd(a.bad, 1);
-    ih = min(max(ih, 0), a.n_ent - 1);
-    it = min(max(it, 0), a.n_ent - 1);
-    ir = min(max(ir, 0), a.n_rel - 1);
-    // q = h + r (tail side) or t - r (head side); the true entity is t or h
-    const float *pa = a.X + (int64_t)(HEAD ? it : ih) * dim;
-    const float *pr = a.X + ((int64_t)a.n_ent + ir) * dim;
-    const float *ptrue = a.X + (int64_t)(HEAD ? ih : it) * dim;
-
-    if (tid < kRankQ) {
-        float acc = 0.f;
-        for (int j = 0; j < dim; j += 4) {
-            const float4 va = ld4(pa + j), vr = ld4(pr + j), ve = ld4(ptrue + j);
-            const float av[4] = {va.x, va.y, va.z, va.w}, rv[4] = {vr.x, vr.y, vr.z, vr.w};
-            const float ev[4] = {ve.x, ve.y, ve.z, ve.w};
+    const RankRows rw = rank_rows<HEAD>(a, min(q0 + sc, a.nq - 1));
+    const float *pa = rw.pa, *pr = rw.pr;
+    float tr[8];                                          // the true entities' sums (k_rank_true)
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const float q = HEAD ? av[u] - rv[u] : av[u] + rv[u];
-                acc = rank_step<DIST>(acc, HEAD ? ev[u] - q : q - ev[u]);
-            }
-        }
-        s_true[tid] = acc;
-        if (blockIdx.y == 0 && q0 + tid < a.nq) a.true_score[q0 + tid] = finish<DIST>(acc);
-    }
-    __syncthreads();
-    float tr[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) tr[u] = s_true[(u < 4 ? 0 : 64) + ty * 4 + (u & 3)];
+    for (int u = 0; u < 8; ++u) tr[u] = a.true_score[min(q0 + (u < 4 ? 0 : 64) + ty * 4 + (u & 3), a.nq - 1)];
 
     int32_t less[8], equal[8];
 #pragma unroll
@@ -114,29 +129,42 @@ __global__ __launch_bounds__(kThreads) void k_rank(RankArgs a)
             for (int v = 0; v < 8; ++v) acc[u][v] = 0.f;
         const float *pe = a.X + (int64_t)min(e0 + sc, a.n_ent - 1) * dim;   // past the end: repeated, not counted
         for (int j0 = 0; j0 < dim; j0 += kRankJ) {
+            // all twelve loads of the chunk go out together (addresses past the row's end are pulled back
+            // inside it and their values replaced by zeros, which add nothing to a sum)
+            float4 va[4], vr[4], ve[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int j = min(j0 + sj + 8 * i, dim - 4);
+                va[i] = ld4(pa + j); vr[i] = ld4(pr + j); ve[i] = ld4(pe + j);
+            }
             __syncthreads();                              // the previous chunk has been consumed
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int jj = sj + 8 * i, j = j0 + jj;
-                float4 q4 = make_float4(0.f, 0.f, 0.f, 0.f), e4 = q4;   // past the row's end: zeros add nothing
-                if (j < dim) {
-                    const float4 va = ld4(pa + j), vr = ld4(pr + j);
-                    q4 = HEAD ? make_float4(va.x - vr.x, va.y - vr.y, va.z - vr.z, va.w - vr.w)
-                              : make_float4(va.x + vr.x, va.y + vr.y, va.z + vr.z, va.w + vr.w);
-                    e4 = ld4(pe + j);
-                }
+                const int jj = sj + 8 * i;
+                float4 q4 = HEAD ? make_float4(va[i].x - vr[i].x, va[i].y - vr[i].y, va[i].z - vr[i].z, va[i].w - vr[i].w)
+                                 : make_float4(va[i].x + vr[i].x, va[i].y + vr[i].y, va[i].z + vr[i].z, va[i].w + vr[i].w);
+                float4 e4 = ve[i];
+                if (j0 + jj >= dim) q4 = e4 = make_float4(0.f, 0.f, 0.f, 0.f);
                 s_q[jj][sc] = q4.x; s_q[jj + 1][sc] = q4.y; s_q[jj + 2][sc] = q4.z; s_q[jj + 3][sc] = q4.w;
                 s_e[jj][sc] = e4.x; s_e[jj + 1][sc] = e4.y; s_e[jj + 2][sc] = e4.z; s_e[jj + 3][sc] = e4.w;
             }
             __syncthreads();
+            // the operands of step jj + 1 are requested before step jj is computed, so the LDS round trip hides
+            // behind 128 vector operations
+            float4 qa = *reinterpret_cast<const float4 *>(&s_q[0][ty * 4]);
+            float4 qb = *reinterpret_cast<const float4 *>(&s_q[0][64 + ty * 4]);
+            float4 ea = *reinterpret_cast<const float4 *>(&s_e[0][tx * 4]);
+            float4 eb = *reinterpret_cast<const float4 *>(&s_e[0][64 + tx * 4]);
 #pragma unroll 4
             for (int jj = 0; jj < kRankJ; ++jj) {
-                const float4 qa = *reinterpret_cast<const float4 *>(&s_q[jj][ty * 4]);
-                const float4 qb = *reinterpret_cast<const float4 *>(&s_q[jj][64 + ty * 4]);
-                const float4 ea = *reinterpret_cast<const float4 *>(&s_e[jj][tx * 4]);
-                const float4 eb = *reinterpret_cast<const float4 *>(&s_e[jj][64 + tx * 4]);
                 const float qv[8] = {qa.x, qa.y, qa.z, qa.w, qb.x, qb.y, qb.z, qb.w};
                 const float ev[8] = {ea.x, ea.y, ea.z, ea.w, eb.x, eb.y, eb.z, eb.w};
+                const int jn = min(jj + 1, kRankJ - 1);
+                qa = *reinterpret_cast<const float4 *>(&s_q[jn][ty * 4]);
+                qb = *reinterpret_cast<const float4 *>(&s_q[jn][64 + ty * 4]);
+                ea = *reinterpret_cast<const float4 *>(&s_e[jn][tx * 4]);
+                eb = *reinterpret_cast<const float4 *>(&s_e[jn][64 + tx * 4]);
+                __builtin_amdgcn_sched_barrier(0);        // keep the requests ahead of the arithmetic
 #pragma unroll
                 for (int u = 0; u < 8; ++u)
 #pragma unroll
@@ -176,23 +204,28 @@ stx_status launch_rank(stx_ctx *c, const stx_params *p, const int32_t *h, const 
     if (nq == 0) return STX_OK;
     const int32_t n_ent = (int32_t)c->cfg.n_ent;
     const int64_t qblocks = (nq + kRankQ - 1) / kRankQ;
-    // Candidate slices: enough workgroups to fill the chip several times over, but whole tiles per slice.
+    // Candidate slices: enough workgroups that the last, partly filled round of them is a small share of the
+    // run (768 fit the chip at once), but whole tiles per slice.
     const int64_t tiles = ((int64_t)n_ent + kRankE - 1) / kRankE;
-    int64_t slices = (4096 + qblocks - 1) / qblocks;
-    if (slices > tiles) slices = tiles;
+    int64_t slices = (32768 + qblocks - 1) / qblocks;
+    if (slices > (tiles + 1) / 2) slices = (tiles + 1) / 2;   // at least two tiles per workgroup
     if (slices > 65535) slices = 65535;
     const int32_t slice = (int32_t)((tiles + slices - 1) / slices) * kRankE;
     slices = ((int64_t)n_ent + slice - 1) / slice;
-    hipLaunchKernelGGL(k_rank_clear, dim3((unsigned)((nq + kThreads - 1) / kThreads)), dim3(kThreads), 0, c->stream,
-                       n_less, n_equal, nq);
     const RankArgs a{p->ent, h, r, t, nq, n_ent, (int32_t)c->cfg.n_rel, c->cfg.dim, slice, true_score, n_less, n_equal,
                      c->ctrl + CTRL_BAD_INDEX};
-    const dim3 grid((unsigned)qblocks, (unsigned)slices);
+    const dim3 grid((unsigned)qblocks, (unsigned)slices), qgrid((unsigned)((nq + kThreads - 1) / kThreads));
 #define STX_RANK(D)                                                                                             \
     do {                                                                                                        \
-        ProfScope prof(c, "k_rank");                                                                            \
-        if (side) hipLaunchKernelGGL((k_rank<D, true>), grid, dim3(kThreads), 0, c->stream, a);                 \
-        else hipLaunchKernelGGL((k_rank<D, false>), grid, dim3(kThreads), 0, c->stream, a);                     \
+        if (side) hipLaunchKernelGGL((k_rank_true<D, true>), qgrid, dim3(kThreads), 0, c->stream, a);           \
+        else hipLaunchKernelGGL((k_rank_true<D, false>), qgrid, dim3(kThreads), 0, c->stream, a);               \
+        {                                                                                                       \
+            ProfScope prof(c, "k_rank");                                                                        \
+            if (side) hipLaunchKernelGGL((k_rank<D, true>), grid, dim3(kThreads), 0, c->stream, a);             \
+            else hipLaunchKernelGGL((k_rank<D, false>), grid, dim3(kThreads), 0, c->stream, a);                 \
+        }                                                                                                       \
+        if (D == STX_L2 || D == STX_TORUS_L2)                                                                   \
+            hipLaunchKernelGGL((k_rank_finish<D>), qgrid, dim3(kThreads), 0, c->stream, true_score, nq);        \
     } while (0)
     switch (c->cfg.dist) {
     case STX_L1: STX_RANK(STX_L1); break;

@@ -150,3 +150,29 @@ def test_rank_true_score_matches_the_forward_pass():
     m.forward()
     scores, _ = m.scores_numpy()
     np.testing.assert_allclose(ts, scores, rtol=1e-5)
+
+
+@pytest.mark.parametrize("name,nq,n_sample", [("mid", W.N_TEST_FB15K, 256), ("paper_transe", 4096, 32),
+                                              ("toruse", 256, 3)])
+def test_rank_full_size(name, nq, n_sample):
+    """The launch configuration bench.py times ("mid": FB15k-sized test split against 15,000 entities), the
+    paper's own width (d = 1024) and the 4M-entity torus table: properties that hold for every query, and the
+    oracle's band on a seeded sample of queries it scores one by one."""
+    wl = W.WORKLOADS[name]
+    X = W.make_tables(wl)["ent"]
+    h, r, t = W.make_test_triplets(wl, nq)
+    pick = np.sort(np.random.default_rng(5).choice(nq, n_sample, replace=False))
+    tol = band_tol(wl.dim)
+    hits = {}
+    for side, oside in SIDES:
+        _, ts, less, equal = run_rank(wl, X, h, r, t, side)
+        assert np.all(np.isfinite(ts)) and np.all(ts >= 0)
+        assert np.all(equal >= 1) and np.all(less >= 0) and np.all(less.astype(np.int64) + equal <= wl.n_ent)
+        ref = stxo.rank(oracle_config(wl), X, h[pick], r[pick], t[pick], oside, tol=tol)
+        check_counts(ts[pick], less[pick], equal[pick], ref, tol)
+        hits[side] = float((1 + less <= 10).mean())
+    # identical (h, r, t) queries give identical counts wherever they sit in the launch
+    key = h.astype(np.int64) * (wl.n_rel + 1) * (wl.n_ent + 1) + r.astype(np.int64) * (wl.n_ent + 1) + t
+    _, first, inv = np.unique(key, return_index=True, return_inverse=True)
+    assert np.array_equal(less, less[first][inv]) and np.array_equal(equal, equal[first][inv])
+    assert 0.0 <= hits[B.STX_TAIL] <= 1.0 and 0.0 <= hits[B.STX_HEAD] <= 1.0
