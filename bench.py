@@ -51,7 +51,10 @@ TRAFFIC_BYTES = {("mid", "k_fwd_scatter", True): 26.10e6 + 7.33e6,
                  ("toruse", "k_forward_stacked", True): 704.01e6 + 90.19e6,
                  ("toruse", "k_forward_stacked", False): 704.01e6 + 90.19e6,
                  # mean of the two batches of an epoch (393,216 and 89,926 positives), like the timed mean
-                 ("paper_transe", "k_seg_reduce", True): (9761.85e6 + 104.19e6 + 2281.04e6 + 99.90e6) / 2}
+                 ("paper_transe", "k_seg_reduce", True): (9761.85e6 + 104.19e6 + 2281.04e6 + 99.90e6) / 2,
+                 # the other modes (profiles/semiring_complex_*_kernel_trace.txt, profiles/rank_mid_kernel_trace.txt)
+                 ("semiring complex", "mid", "k_semiring_terms"): 66.64e6 + 100.66e6,
+                 ("semiring complex", "toruse", "k_semiring_terms"): 1560.16e6 + 2013.27e6}
 
 
 def parse():
@@ -286,7 +289,9 @@ def bench_semiring(args, wl, dev):
            "config": {"workload": f"{wl.name} graph, first batch: {rows} rows, {u} touched columns, dim {wl.dim}",
                       "step": "stx_spmm_semiring + stx_spmm_semiring_t"},
            "roofline": {"bound": bound, "kernel": kernel, "achieved": round(achieved, 1), "peak": peak, "unit": unit,
-                        "frac": round(achieved / peak, 4), "traffic": None, "work_per_launch": int(work_b),
+                        "frac": round(achieved / peak, 4),
+                        "traffic": TRAFFIC_BYTES.get((f"semiring {args.semiring}", wl.name, kernel)),
+                        "work_per_launch": int(work_b),
                         "avg_launch_us": round(kernel_us, 2), "launches_per_step": round(kernel_n / args.steps, 2)},
            "kernels_us": kernels_us}
     if not args.no_cpu_baseline:

@@ -192,8 +192,8 @@ __global__ __launch_bounds__(kThreads, 3) void k_rank(RankArgs a)
         }
         const int64_t q = q0 + (u < 4 ? 0 : 64) + ty * 4 + (u & 3);
         if (tx == 0 && q < a.nq) {
-            atomicAdd(&a.n_less[q], less[u]);
-            atomicAdd(&a.n_equal[q], equal[u]);
+            if (less[u]) atomicAdd(&a.n_less[q], less[u]);
+            if (equal[u]) atomicAdd(&a.n_equal[q], equal[u]);
         }
     }
 }
