@@ -460,52 +460,73 @@ int stxo_forward(const stxo_cfg *c, const stxo_tables *tb, const stxo_batch *bt,
 
 /* Link prediction by exhaustive scoring (the "predicting links" facility of Sec. 4.7; Hits@10, the
  * accuracy measure of Sec. 6.1, is the share of test triplets whose true entity ranks among the ten
- * best).  TransE / TorusE only.  The paper fixes no protocol; the reading taken here is the usual raw
- * (unfiltered) one: for a test triplet (h, r, t) every entity e of the table is a candidate,
- *   side 0, tail prediction: query point q = h + r, score of e = distance(q - e), true entity t;
- *   side 1, head prediction: query point q = t - r, score of e = distance(e - q), true entity h;
- * q and the difference are each rounded once to fp32 (for the tail side that is the x of the training
- * score, bit for bit), the distance is the model's (row_dist above, summed in double), smaller is
- * better, and a relation weight (Table 2, TransM) would scale all candidates of a query alike and
- * plays no part.  Outputs per query:
+ * best).  TransE, TorusE and TransH.  The paper fixes no protocol; the reading taken here is the usual
+ * raw (unfiltered) one: for a test triplet (h, r, t) every entity e of the table is a candidate,
+ * side 0 (tail prediction) scores the triplets (h, r, e), true entity t; side 1 (head prediction)
+ * scores (e, r, t), true entity h; smaller is better.
+ *   TransE / TorusE: query point q = h + r (tail side) or t - r (head side), score of e =
+ *     distance(q - e) or distance(e - q); q and the difference are each rounded once to fp32 (for the
+ *     tail side that is the x of the training score, bit for bit).  A relation weight (Table 2, TransM)
+ *     would scale all candidates of a query alike and plays no part.
+ *   TransH: the training score of the triplet with e in place of the true entity (Sec. 4.5):
+ *     x = h - e or e - t in fp32, y = x + d_r - (w_r.x) w_r, distance(y), by row_x / row_y above.
+ * The distance is the model's (row_dist, summed in double).  Outputs per query:
  *   true_score : the true entity's score;
  *   n_less     : candidates scoring strictly below the true entity and outside the band below;
- *   n_band     : candidates with |score - true| <= tol * (score + true), the true entity among them.
+ *   n_band     : candidates with |score - true| <= tol * (scale + scale of the true entity), the true
+ *                entity among them, where scale is the distance taken over the sums of magnitudes of
+ *                the terms behind each element of y (the score itself for TransE / TorusE; twice that
+ *                for the squared L2 norm of a computed y): the size against which a single-precision
+ *                evaluation of the score can be off.
  * With tol = 0 the band holds the exact ties, the best rank the true entity can claim is 1 + n_less
  * and the worst n_less + n_band.  With tol > 0 the band holds every candidate whose order against
  * the true entity a single-precision evaluation may decide either way.                          */
-int stxo_rank(const stxo_cfg *c, const float *X, const int32_t *h, const int32_t *r, const int32_t *t,
+int stxo_rank(const stxo_cfg *c, const stxo_tables *tb, const int32_t *h, const int32_t *r, const int32_t *t,
               int64_t nq, int32_t side, double tol, double *true_score, int64_t *n_less, int64_t *n_band)
 {
-    if (!is_stacked(c) || side < 0 || side > 1) return 1;
+    if (c->model == STXO_TRANSR || side < 0 || side > 1) return 1;
     const int32_t d = c->dim;
+    const float *X = tb->ent;
     float *q = (float *)malloc(sizeof(float) * (size_t)d);
+    float *x = (float *)malloc(sizeof(float) * (size_t)d);
     double *y = (double *)malloc(sizeof(double) * (size_t)d);
+    double *ya = (double *)malloc(sizeof(double) * (size_t)d);
     double *score = (double *)malloc(sizeof(double) * (size_t)c->n_ent);
-    if (!q || !y || !score) return 2;
+    double *scale = (double *)malloc(sizeof(double) * (size_t)c->n_ent);
+    if (!q || !x || !y || !ya || !score || !scale) return 2;
     for (int64_t i = 0; i < nq; ++i) {
-        const float *eh = X + (int64_t)h[i] * d, *et = X + (int64_t)t[i] * d;
-        const float *er = X + (c->n_ent + r[i]) * (int64_t)d;
-        for (int32_t j = 0; j < d; ++j) q[j] = side == 0 ? eh[j] + er[j] : et[j] - er[j];
-        for (int64_t e = 0; e < c->n_ent; ++e) {
-            const float *ee = X + e * d;
-            for (int32_t j = 0; j < d; ++j) {
-                const float diff = side == 0 ? q[j] - ee[j] : ee[j] - q[j];
-                y[j] = (double)diff;
-            }
-            score[e] = row_dist(c, y, d);
+        if (is_stacked(c)) {
+            const float *eh = X + (int64_t)h[i] * d, *et = X + (int64_t)t[i] * d;
+            const float *er = X + (c->n_ent + r[i]) * (int64_t)d;
+            for (int32_t j = 0; j < d; ++j) q[j] = side == 0 ? eh[j] + er[j] : et[j] - er[j];
         }
-        const double st = score[side == 0 ? t[i] : h[i]];
+        for (int64_t e = 0; e < c->n_ent; ++e) {
+            if (is_stacked(c)) {
+                const float *ee = X + e * d;
+                for (int32_t j = 0; j < d; ++j) {
+                    const float diff = side == 0 ? q[j] - ee[j] : ee[j] - q[j];
+                    y[j] = (double)diff;
+                }
+                score[e] = scale[e] = row_dist(c, y, d);
+            } else {
+                row_x(c, tb, side == 0 ? h[i] : (int32_t)e, r[i], side == 0 ? (int32_t)e : t[i], x);
+                row_y(c, tb, r[i], x, y, NULL, ya);
+                score[e] = row_dist(c, y, d);
+                scale[e] = (c->dist == STXO_L2_SQ ? 2.0 : 1.0) * row_dist(c, ya, d);
+            }
+        }
+        const int64_t te = side == 0 ? t[i] : h[i];
+        const double st = score[te];
         int64_t less = 0, band = 0;
         for (int64_t e = 0; e < c->n_ent; ++e) {
-            if (fabs(score[e] - st) <= tol * (score[e] + st)) ++band;
+            if (fabs(score[e] - st) <= tol * (scale[e] + scale[te])) ++band;
             else if (score[e] < st) ++less;
         }
         true_score[i] = st;
         n_less[i] = less;
         n_band[i] = band;
     }
-    free(q); free(y); free(score);
+    free(q); free(x); free(y); free(ya); free(score); free(scale);
     return 0;
 }
 

@@ -251,18 +251,22 @@ def spmm_semiring_t(colidx, X, kind: int, G):
 TAIL, HEAD = 0, 1
 
 
-def rank(cfg: "Config", X, h, r, t, side: int, tol: float = 0.0):
+def rank(cfg: "Config", tables, h, r, t, side: int, tol: float = 0.0):
     """Raw link-prediction counts of every test triplet against all entities: (true_score float64,
-    n_less int64, n_band int64); see stxo_rank in stxo.c."""
-    X = _f32(X)
+    n_less int64, n_band int64); see stxo_rank in stxo.c.  tables: a Tables object, or the stacked table
+    X = [E;R] of TransE / TorusE as an array."""
+    if not isinstance(tables, Tables):
+        tables = Tables(_f32(tables))
+    if cfg.model == TRANSH and (tables.rel is None or tables.w is None):
+        raise ValueError("stxo_rank: TransH needs the d_r and w_r tables")
     h, r, t = _i32(h), _i32(r), _i32(t)
     nq = h.shape[0]
     ts = np.empty(nq, np.float64)
     less = np.empty(nq, np.int64)
     band = np.empty(nq, np.int64)
-    cc = cfg.c()
-    if lib().stxo_rank(C.addressof(cc), _p(X), _p(h), _p(r), _p(t), nq, side, tol, _p(ts), _p(less), _p(band)) != 0:
-        raise ValueError("stxo_rank: TransE / TorusE only, side 0 (tail) or 1 (head)")
+    cc, ct = cfg.c(), tables.c()
+    if lib().stxo_rank(C.byref(cc), C.byref(ct), _p(h), _p(r), _p(t), nq, side, tol, _p(ts), _p(less), _p(band)) != 0:
+        raise ValueError("stxo_rank: TransE / TorusE / TransH only, side 0 (tail) or 1 (head)")
     return ts, less, band
 
 

@@ -41,7 +41,7 @@ def test_rank_exact_ties_are_counted_in_the_band():
     ts, less, band = stxo.rank(_cfg(stxo.L1, 4, 1, 2), X, [0], [0], [1], stxo.TAIL)
     assert ts[0] == 1 and less[0] == 0 and band[0] == 4                  # all four entities are at distance 1
     with pytest.raises(ValueError):
-        stxo.rank(stxo.Config(stxo.TRANSH, stxo.L1, 4, 1, 2), X, [0], [0], [1], stxo.TAIL)
+        stxo.rank(stxo.Config(stxo.TRANSR, stxo.L1, 4, 1, 2, 2), X, [0], [0], [1], stxo.TAIL)
     with pytest.raises(ValueError):
         stxo.rank(_cfg(stxo.L1, 4, 1, 2), X, [0], [0], [1], 2)
 
@@ -113,3 +113,81 @@ def test_rank_band_holds_what_single_precision_cannot_order():
     # the band is symmetric in the two scores and scales with them
     ts, less, band = stxo.rank(_cfg(stxo.L1, 5, 1, 1), X, [0], [0], [0], stxo.TAIL, tol=0.6)
     assert less[0] == 0 and band[0] == 5                                 # |3 - 1| <= 0.6 * 4, |0.5 - 1| <= 0.6 * 1.5
+
+
+# ------------------------------------------------------------------------------------------ TransH
+def _transh_grid_problem(seed, n_ent=120, n_rel=5, dim=4, nq=60):
+    """Tables on a coarse grid (multiples of 1/2, normals of small integers): every product and sum of the
+    TransH score is exact in single and double precision alike."""
+    rng = np.random.default_rng(seed)
+    E = (rng.integers(-4, 4, (n_ent, dim)) / 2.0).astype(np.float32)
+    D = (rng.integers(-4, 4, (n_rel, dim)) / 2.0).astype(np.float32)
+    Wn = rng.integers(-1, 2, (n_rel, dim)).astype(np.float32)
+    h, t = rng.integers(0, n_ent, nq).astype(np.int32), rng.integers(0, n_ent, nq).astype(np.int32)
+    r = rng.integers(0, n_rel, nq).astype(np.int32)
+    return E, D, Wn, h, r, t
+
+
+@pytest.mark.parametrize("dist", [stxo.L1, stxo.L2_SQ])
+@pytest.mark.parametrize("side", [stxo.TAIL, stxo.HEAD])
+def test_rank_transh_against_the_projected_form(dist, side):
+    # Sec. 4.5 first writes the score with both entities projected onto the relation's hyperplane,
+    # h_p + d_r - t_p with v_p = v - (w.v) w; the oracle uses the rearranged form on h - t.  Evaluate the
+    # projected form with library array arithmetic for every candidate and count.
+    E, D, Wn, h, r, t = _transh_grid_problem(31 + dist + side)
+    n_ent, dim = E.shape
+    cfg = stxo.Config(stxo.TRANSH, dist, n_ent, D.shape[0], dim)
+    ts, less, band = stxo.rank(cfg, stxo.Tables(E, D, Wn), h, r, t, side)
+    E64, D64, W64 = E.astype(np.float64), D.astype(np.float64), Wn.astype(np.float64)
+    for i in range(len(h)):
+        w, dr = W64[r[i]], D64[r[i]]
+        proj = lambda v: v - (v @ w)[..., None] * w
+        if side == stxo.TAIL:
+            Y = proj(E64[h[i]][None, :]) + dr - proj(E64)               # candidates as tails
+            true = t[i]
+        else:
+            Y = proj(E64) + dr - proj(E64[t[i]][None, :])               # candidates as heads
+            true = h[i]
+        sc = np.abs(Y).sum(1) if dist == stxo.L1 else (Y * Y).sum(1)
+        assert ts[i] == sc[true]
+        assert less[i] == (sc < sc[true]).sum() and band[i] == (sc == sc[true]).sum()
+    assert band.max() > 1
+
+
+def test_rank_transh_true_score_is_the_training_score_and_zero_normals_give_a_translation():
+    wl, tabs, bt = small_problem("transh", "l2", n_ent=40, n_rel=5, b=25, k=0, dim=16, seed=4)
+    cfg = oracle_config(wl)
+    fw = stxo.forward(cfg, oracle_tables(tabs), bt, want_x=False)
+    for side in (stxo.TAIL, stxo.HEAD):
+        ts, less, band = stxo.rank(cfg, oracle_tables(tabs), bt.h, bt.r, bt.t, side)
+        assert np.array_equal(ts, fw.scores[:25])                        # the same triplet, the same functions
+        assert np.all(band >= 1) and np.all(less + band <= 40)
+    # w_r = 0: TransH is a translation by d_r, i.e. TransE on the stacked table [E; D] (exact on a grid)
+    E, D, Wn, h, r, t = _transh_grid_problem(9)
+    n_ent, dim = E.shape
+    cfg_h = stxo.Config(stxo.TRANSH, stxo.L1, n_ent, D.shape[0], dim)
+    cfg_e = stxo.Config(stxo.TRANSE, stxo.L1, n_ent, D.shape[0], dim)
+    for side in (stxo.TAIL, stxo.HEAD):
+        got = stxo.rank(cfg_h, stxo.Tables(E, D, np.zeros_like(Wn)), h, r, t, side)
+        want = stxo.rank(cfg_e, np.concatenate([E, D]), h, r, t, side)
+        for a, b in zip(got, want):
+            assert np.array_equal(a, b)
+    with pytest.raises(ValueError):
+        stxo.rank(stxo.Config(stxo.TRANSR, stxo.L1, n_ent, D.shape[0], dim, dim), stxo.Tables(E, D), h, r, t, 0)
+
+
+def test_rank_transh_band_uses_the_magnitudes_behind_y():
+    # one dimension, w = 1 (so y = d_r whatever the entities are: every candidate ties exactly); with
+    # entities of size ~1000 and d_r = 1 a single-precision evaluation cannot order them, and the band,
+    # scaled by |x| + |d| + |s w| rather than by the score, says so
+    E = np.array([[1000.0], [999.0], [-1000.0]], np.float32)
+    D = np.array([[1.0]], np.float32)
+    Wn = np.array([[1.0]], np.float32)
+    cfg = stxo.Config(stxo.TRANSH, stxo.L1, 3, 1, 1)
+    ts, less, band = stxo.rank(cfg, stxo.Tables(E, D, Wn), [0], [0], [1], stxo.TAIL, tol=0.0)
+    assert ts[0] == 1.0 and less[0] == 0 and band[0] == 3
+    Wn2 = np.array([[1.0 - 2.0**-12]], np.float32)                      # now y = d + x (1 - w^2), x = h - e
+    ts, less, band = stxo.rank(cfg, stxo.Tables(E, D, Wn2), [0], [0], [1], stxo.TAIL, tol=0.0)
+    assert less[0] == 1 and band[0] == 1                                # e = 0 (x = 0) scores exactly 1, below x = 1
+    ts, less, band = stxo.rank(cfg, stxo.Tables(E, D, Wn2), [0], [0], [1], stxo.TAIL, tol=1e-3)
+    assert less[0] == 0 and band[0] >= 2                                # scale ~ 2 |x| + 1: 1e-3 of it covers the gap
