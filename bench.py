@@ -163,6 +163,9 @@ def cpu_baseline(wl, h, r, t, tabs, n_steps):
 VALU_OPS_PEAK_T = 256 * 128 * 2.4e9 / 1e12
 # vector operations per (query, candidate, row element) in k_rank, and flops they stand for
 RANK_OPS = {"l1": (2, 2), "l2": (2, 3), "l2_sq": (2, 3), "torus_l1": (5, 5), "torus_l2": (5, 6)}
+# TransH (k_rank_h): a fused multiply-add for w.e in the first pass over the row, then a difference, a fused
+# multiply-add for the projection and the distance step
+RANK_OPS_H = {"l1": (4, 6), "l2": (4, 7), "l2_sq": (4, 7), "torus_l1": (7, 9), "torus_l2": (7, 10)}
 
 
 def bench_rank(args, wl, dev):
@@ -177,7 +180,12 @@ def bench_rank(args, wl, dev):
     tabs = W.make_tables(wl)
     cfg = B.make_config(wl.model, wl.dist, wl.n_ent, wl.n_rel, wl.dim, 8, 1, margin=wl.margin)
     ctx = B.Context(cfg, dev)
-    params = B.Params(torch.from_numpy(tabs["ent"]).to(dev))
+    transh = wl.model == "transh"
+    if wl.model == "transr":
+        print("bench.py --rank: TransR is not supported by stx_rank", file=sys.stderr)
+        sys.exit(2)
+    params = B.Params(*(torch.from_numpy(tabs[k]).to(dev) for k in (("ent", "rel", "w") if transh else ("ent",))))
+    rank_kernel = "k_rank_h" if transh else "k_rank"
     hd, rd, td = (torch.from_numpy(a).to(dev) for a in (h, r, t))
     ts = torch.empty(2, nq, dtype=torch.float32, device=dev)
     less = torch.empty(2, nq, dtype=torch.int32, device=dev)
@@ -190,14 +198,14 @@ def bench_rank(args, wl, dev):
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    B.stx_profile_kernel(ctx, "k_rank", 2 * args.steps)
+    B.stx_profile_kernel(ctx, rank_kernel, 2 * args.steps)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     kernel_us, kernel_n = B.stx_profile_read(ctx)
-    ops, flops = RANK_OPS[wl.dist]
+    ops, flops = (RANK_OPS_H if transh else RANK_OPS)[wl.dist]
     elems = float(nq) * wl.n_ent * wl.dim                     # per launch (one side)
     achieved = elems * flops / (kernel_us * 1e-6) / 1e12 if kernel_us > 0 else 0.0
     peak = VALU_OPS_PEAK_T * flops / ops
@@ -211,7 +219,7 @@ def bench_rank(args, wl, dev):
                                   f"{nq} test triplets (the size of FB15k's test split) from the graph's degree laws",
                       "step": "stx_rank tail side + stx_rank head side over all test triplets"},
            "hits_at_10_raw": round(float((best <= 10).mean()), 4),
-           "roofline": {"bound": "alu", "kernel": "k_rank", "achieved": round(achieved, 2), "peak": round(peak, 1),
+           "roofline": {"bound": "alu", "kernel": rank_kernel, "achieved": round(achieved, 2), "peak": round(peak, 1),
                         "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None,
                         "work_per_launch": int(elems * flops), "avg_launch_us": round(kernel_us, 2),
                         "launches_per_step": round(kernel_n / args.steps, 2),
@@ -221,11 +229,12 @@ def bench_rank(args, wl, dev):
         from oracle import stxo
         from tests.util import oracle_config
         ocfg = oracle_config(wl)
+        otab = stxo.Tables(tabs["ent"], tabs.get("rel"), tabs.get("w"))
         n = 8
         while True:
             t0 = time.perf_counter()
-            stxo.rank(ocfg, tabs["ent"], h[:n], r[:n], t[:n], stxo.TAIL)
-            stxo.rank(ocfg, tabs["ent"], h[:n], r[:n], t[:n], stxo.HEAD)
+            stxo.rank(ocfg, otab, h[:n], r[:n], t[:n], stxo.TAIL)
+            stxo.rank(ocfg, otab, h[:n], r[:n], t[:n], stxo.HEAD)
             cdt = time.perf_counter() - t0
             if cdt >= 8.0 or n >= nq:
                 break

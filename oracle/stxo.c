@@ -478,11 +478,14 @@ int stxo_forward(const stxo_cfg *c, const stxo_tables *tb, const stxo_batch *bt,
  *                the terms behind each element of y (the score itself for TransE / TorusE; twice that
  *                for the squared L2 norm of a computed y): the size against which a single-precision
  *                evaluation of the score can be off.
+ * abs_tol (optional, one value per query) widens the band by an absolute amount: a caller that knows an
+ * error term of the evaluation it checks which the scales above do not cover passes it here.
  * With tol = 0 the band holds the exact ties, the best rank the true entity can claim is 1 + n_less
  * and the worst n_less + n_band.  With tol > 0 the band holds every candidate whose order against
  * the true entity a single-precision evaluation may decide either way.                          */
 int stxo_rank(const stxo_cfg *c, const stxo_tables *tb, const int32_t *h, const int32_t *r, const int32_t *t,
-              int64_t nq, int32_t side, double tol, double *true_score, int64_t *n_less, int64_t *n_band)
+              int64_t nq, int32_t side, double tol, const double *abs_tol, double *true_score, int64_t *n_less,
+              int64_t *n_band)
 {
     if (c->model == STXO_TRANSR || side < 0 || side > 1) return 1;
     const int32_t d = c->dim;
@@ -519,7 +522,7 @@ int stxo_rank(const stxo_cfg *c, const stxo_tables *tb, const int32_t *h, const 
         const double st = score[te];
         int64_t less = 0, band = 0;
         for (int64_t e = 0; e < c->n_ent; ++e) {
-            if (fabs(score[e] - st) <= tol * (scale[e] + scale[te])) ++band;
+            if (fabs(score[e] - st) <= tol * (scale[e] + scale[te]) + (abs_tol ? abs_tol[i] : 0.0)) ++band;
             else if (score[e] < st) ++less;
         }
         true_score[i] = st;

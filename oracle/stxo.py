@@ -72,7 +72,7 @@ def lib():
         _lib.stxo_spmm_semiring_t.restype = C.c_int
         _lib.stxo_spmm_semiring_t.argtypes = [C.c_int64, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32] + [C.c_void_p] * 3
         _lib.stxo_rank.restype = C.c_int
-        _lib.stxo_rank.argtypes = [C.c_void_p] * 5 + [C.c_int64, C.c_int32, C.c_double] + [C.c_void_p] * 3
+        _lib.stxo_rank.argtypes = [C.c_void_p] * 5 + [C.c_int64, C.c_int32, C.c_double] + [C.c_void_p] * 4
         _lib.stxo_spmm_csr_t.restype = None
         _lib.stxo_spmm_csr_t.argtypes = [C.c_int64] + [C.c_void_p] * 4 + [C.c_int32, C.c_void_p]
         _lib.stxo_forward.restype = C.c_int
@@ -251,7 +251,7 @@ def spmm_semiring_t(colidx, X, kind: int, G):
 TAIL, HEAD = 0, 1
 
 
-def rank(cfg: "Config", tables, h, r, t, side: int, tol: float = 0.0):
+def rank(cfg: "Config", tables, h, r, t, side: int, tol: float = 0.0, abs_tol=None):
     """Raw link-prediction counts of every test triplet against all entities: (true_score float64,
     n_less int64, n_band int64); see stxo_rank in stxo.c.  tables: a Tables object, or the stacked table
     X = [E;R] of TransE / TorusE as an array."""
@@ -265,7 +265,11 @@ def rank(cfg: "Config", tables, h, r, t, side: int, tol: float = 0.0):
     less = np.empty(nq, np.int64)
     band = np.empty(nq, np.int64)
     cc, ct = cfg.c(), tables.c()
-    if lib().stxo_rank(C.byref(cc), C.byref(ct), _p(h), _p(r), _p(t), nq, side, tol, _p(ts), _p(less), _p(band)) != 0:
+    if abs_tol is not None:
+        abs_tol = np.ascontiguousarray(abs_tol, dtype=np.float64)
+        assert abs_tol.shape == (nq,)
+    if lib().stxo_rank(C.byref(cc), C.byref(ct), _p(h), _p(r), _p(t), nq, side, tol, _p(abs_tol), _p(ts), _p(less),
+                       _p(band)) != 0:
         raise ValueError("stxo_rank: TransE / TorusE / TransH only, side 0 (tail) or 1 (head)")
     return ts, less, band
 

@@ -415,7 +415,8 @@ stx_status stx_rank(stx_ctx *ctx, const stx_params *p, const int32_t *h, const i
     if (!ctx) return STX_ERR_NULL;
     if (!p || !p->ent) return STX_ERR_NULL;
     if (nq < 0 || nq > ((int64_t)1 << 31) - 256 || (side != STX_TAIL && side != STX_HEAD)) return STX_ERR_BAD_ARG;
-    if (!stacked(ctx)) return STX_ERR_UNSUPPORTED;
+    if (ctx->cfg.model == STX_TRANSR) return STX_ERR_UNSUPPORTED;
+    if (ctx->cfg.model == STX_TRANSH && (!p->rel || !p->w)) return STX_ERR_NULL;
     if (nq == 0) return STX_OK;
     if (!h || !r || !t || !true_score || !n_less || !n_equal) return STX_ERR_NULL;
     return launch_rank(ctx, p, h, r, t, nq, side, true_score, n_less, n_equal);

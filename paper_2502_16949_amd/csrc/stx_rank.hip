@@ -34,7 +34,8 @@ __device__ inline float rank_step(float acc, float y)
 }
 
 struct RankArgs {
-    const float *X;                    // [E;R], rows of dim floats
+    const float *X;                    // TransE / TorusE: [E;R]; TransH: E.  Rows of dim floats
+    const float *D, *W;                // TransH: d_r and w_r, n_rel rows each
     const int32_t *h, *r, *t;          // [nq]
     int64_t nq;
     int32_t n_ent, n_rel;
@@ -44,6 +45,40 @@ struct RankArgs {
     int32_t *n_less, *n_equal;         // [nq], cleared by k_rank_true
     int32_t *bad;                      // counter of out-of-range indices
 };
+
+// The 8 x 8 block of a thread: query u is block row (u < 4 ? 0 : 64) + 4 ty + (u & 3) of the workgroup's 128,
+// candidate v is (v < 4 ? 0 : 64) + 4 tx + (v & 3) of the tile's 128.
+__device__ inline void rank_count(const float (&acc)[8][8], const float (&tr)[8], int32_t e0, int32_t e_end, int tx,
+                                  int32_t (&less)[8], int32_t (&equal)[8])
+{
+#pragma unroll
+    for (int v = 0; v < 8; ++v) {
+        const bool valid = e0 + (v < 4 ? 0 : 64) + tx * 4 + (v & 3) < e_end;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            less[u] += (valid && acc[u][v] < tr[u]) ? 1 : 0;
+            equal[u] += (valid && acc[u][v] == tr[u]) ? 1 : 0;
+        }
+    }
+}
+
+// Adds a workgroup's counts to the queries' counters.  The 16 threads that share a query sit in consecutive lanes.
+__device__ inline void rank_flush(const RankArgs &a, int64_t q0, int tx, int ty, int32_t (&less)[8], int32_t (&equal)[8])
+{
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+#pragma unroll
+        for (int m = 8; m >= 1; m >>= 1) {
+            less[u] += __shfl_xor(less[u], m, 16);
+            equal[u] += __shfl_xor(equal[u], m, 16);
+        }
+        const int64_t q = q0 + (u < 4 ? 0 : 64) + ty * 4 + (u & 3);
+        if (tx == 0 && q < a.nq) {
+            if (less[u]) atomicAdd(&a.n_less[q], less[u]);
+            if (equal[u]) atomicAdd(&a.n_equal[q], equal[u]);
+        }
+    }
+}
 
 // Clamped table rows of one query: q = h + r (tail side) or t - r (head side); the true entity is t or h.
 struct RankRows {
@@ -172,30 +207,194 @@ __global__ __launch_bounds__(kThreads, 3) void k_rank(RankArgs a)
                         acc[u][v] = rank_step<DIST>(acc[u][v], HEAD ? ev[v] - qv[u] : qv[u] - ev[v]);
             }
         }
+        rank_count(acc, tr, e0, e_end, tx, less, equal);
+    }
+    rank_flush(a, q0, tx, ty, less, equal);
+}
+
+// ---- TransH (Sec. 4.5) -----------------------------------------------------------------------------
+// Candidate e as tail: x = h - e, y = x + d_r - (w_r.x) w_r; as head: x = e - t.  With b = h (tail side) or t
+// (head side) and B = h + d_r or t - d_r, the projection coefficient splits into a part of the query and a
+// part of the pair: s = w.b - w.e (tail) or w.e - w.b (head), and y_j = (B_j - e_j) - s w_j or
+// (e_j - B_j) - s w_j.  The sweep therefore runs over the row twice: first the 8 x 8 dot products w_u.e_v,
+// then the distances, three operations per element (difference, fused multiply-add, accumulate).
+// Every sum runs in index order with fused multiply-adds, in the sweep and in k_rank_true_h alike.
+struct RankRowsH {
+    const float *pb, *pd, *pw, *ptrue;   // b = h or t, d_r, w_r, the true entity's row
+    bool bad;
+};
+template <bool HEAD>
+__device__ inline RankRowsH rank_rows_h(const RankArgs &a, int64_t qi)
+{
+    int32_t ih = a.h[qi], ir = a.r[qi], it = a.t[qi];
+    const bool bad = ih < 0 || ih >= a.n_ent || it < 0 || it >= a.n_ent || ir < 0 || ir >= a.n_rel;
+    ih = min(max(ih, 0), a.n_ent - 1);
+    it = min(max(it, 0), a.n_ent - 1);
+    ir = min(max(ir, 0), a.n_rel - 1);
+    return {a.X + (int64_t)(HEAD ? it : ih) * a.dim, a.D + (int64_t)ir * a.dim, a.W + (int64_t)ir * a.dim,
+            a.X + (int64_t)(HEAD ? ih : it) * a.dim, bad};
+}
+
+// w.v over a row, index order, fused multiply-adds (v = the query's own entity or a candidate).
+__device__ inline float rank_dot_row(const float *__restrict__ pw, const float *__restrict__ pv, int dim)
+{
+    float s = 0.f;
+    for (int j = 0; j < dim; j += 4) {
+        const float4 w4 = ld4(pw + j), v4 = ld4(pv + j);
+        s = __builtin_fmaf(w4.x, v4.x, s); s = __builtin_fmaf(w4.y, v4.y, s);
+        s = __builtin_fmaf(w4.z, v4.z, s); s = __builtin_fmaf(w4.w, v4.w, s);
+    }
+    return s;
+}
+
+template <int DIST, bool HEAD>
+__global__ __launch_bounds__(kThreads) void k_rank_true_h(RankArgs a)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= a.nq) return;
+    const RankRowsH rw = rank_rows_h<HEAD>(a, i);
+    if (rw.bad) atomicAdd(a.bad, 1);
+    const float sb = rank_dot_row(rw.pw, rw.pb, a.dim), se = rank_dot_row(rw.pw, rw.ptrue, a.dim);
+    const float ns = HEAD ? sb - se : se - sb;            // minus the projection coefficient
+    float acc = 0.f;
+    for (int j = 0; j < a.dim; j += 4) {
+        const float4 b4 = ld4(rw.pb + j), d4 = ld4(rw.pd + j), w4 = ld4(rw.pw + j), e4 = ld4(rw.ptrue + j);
+        const float bv[4] = {b4.x, b4.y, b4.z, b4.w}, dv[4] = {d4.x, d4.y, d4.z, d4.w};
+        const float wv[4] = {w4.x, w4.y, w4.z, w4.w}, ev[4] = {e4.x, e4.y, e4.z, e4.w};
 #pragma unroll
-        for (int v = 0; v < 8; ++v) {
-            const bool valid = e0 + (v < 4 ? 0 : 64) + tx * 4 + (v & 3) < e_end;
+        for (int u = 0; u < 4; ++u) {
+            const float B = HEAD ? bv[u] - dv[u] : bv[u] + dv[u];
+            acc = rank_step<DIST>(acc, __builtin_fmaf(ns, wv[u], HEAD ? ev[u] - B : B - ev[u]));
+        }
+    }
+    a.true_score[i] = acc;
+    a.n_less[i] = 0;
+    a.n_equal[i] = 0;
+}
+
+template <int DIST, bool HEAD>
+__global__ __launch_bounds__(kThreads, 2) void k_rank_h(RankArgs a)
+{
+    __shared__ __attribute__((aligned(16))) float s_b[kRankJ][kRankLd];
+    __shared__ __attribute__((aligned(16))) float s_w[kRankJ][kRankLd];
+    __shared__ __attribute__((aligned(16))) float s_e[kRankJ][kRankLd];
+    __shared__ float s_sb[kRankQ];
+
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;
+    const int64_t q0 = (int64_t)blockIdx.x * kRankQ;
+    const int dim = a.dim;
+    const int sc = tid & (kRankQ - 1);
+    const int sj = (tid >> 7) * 4;
+    const RankRowsH rw = rank_rows_h<HEAD>(a, min(q0 + sc, a.nq - 1));
+    if (tid < kRankQ) s_sb[tid] = rank_dot_row(rw.pw, rw.pb, dim);   // w.b of the workgroup's queries
+    float tr[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                less[u] += (valid && acc[u][v] < tr[u]) ? 1 : 0;
-                equal[u] += (valid && acc[u][v] == tr[u]) ? 1 : 0;
+    for (int u = 0; u < 8; ++u) tr[u] = a.true_score[min(q0 + (u < 4 ? 0 : 64) + ty * 4 + (u & 3), a.nq - 1)];
+    __syncthreads();
+    float sb[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) sb[u] = s_sb[(u < 4 ? 0 : 64) + ty * 4 + (u & 3)];
+
+    int32_t less[8], equal[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) less[u] = equal[u] = 0;
+
+    const int32_t e_begin = (int32_t)blockIdx.y * a.slice;
+    const int32_t e_end = min(e_begin + a.slice, a.n_ent);
+    for (int32_t e0 = e_begin; e0 < e_end; e0 += kRankE) {
+        const float *pe = a.X + (int64_t)min(e0 + sc, a.n_ent - 1) * dim;
+        // ---- first pass over the row: dot[u][v] = w_u . e_v --------------------------------------------
+        float ns[8][8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int v = 0; v < 8; ++v) ns[u][v] = 0.f;
+        for (int j0 = 0; j0 < dim; j0 += kRankJ) {
+            float4 vw[4], ve[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int j = min(j0 + sj + 8 * i, dim - 4);
+                vw[i] = ld4(rw.pw + j); ve[i] = ld4(pe + j);
+            }
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int jj = sj + 8 * i;
+                float4 w4 = vw[i], e4 = ve[i];
+                if (j0 + jj >= dim) w4 = e4 = make_float4(0.f, 0.f, 0.f, 0.f);
+                s_w[jj][sc] = w4.x; s_w[jj + 1][sc] = w4.y; s_w[jj + 2][sc] = w4.z; s_w[jj + 3][sc] = w4.w;
+                s_e[jj][sc] = e4.x; s_e[jj + 1][sc] = e4.y; s_e[jj + 2][sc] = e4.z; s_e[jj + 3][sc] = e4.w;
+            }
+            __syncthreads();
+#pragma unroll 4
+            for (int jj = 0; jj < kRankJ; ++jj) {
+                const float4 wa = *reinterpret_cast<const float4 *>(&s_w[jj][ty * 4]);
+                const float4 wb = *reinterpret_cast<const float4 *>(&s_w[jj][64 + ty * 4]);
+                const float4 ea = *reinterpret_cast<const float4 *>(&s_e[jj][tx * 4]);
+                const float4 eb = *reinterpret_cast<const float4 *>(&s_e[jj][64 + tx * 4]);
+                const float wv[8] = {wa.x, wa.y, wa.z, wa.w, wb.x, wb.y, wb.z, wb.w};
+                const float ev[8] = {ea.x, ea.y, ea.z, ea.w, eb.x, eb.y, eb.z, eb.w};
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+#pragma unroll
+                    for (int v = 0; v < 8; ++v) ns[u][v] = __builtin_fmaf(wv[u], ev[v], ns[u][v]);
             }
         }
-    }
-    // the 16 threads that share a query block sit in consecutive lanes
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < 8; ++u)
 #pragma unroll
-        for (int m = 8; m >= 1; m >>= 1) {
-            less[u] += __shfl_xor(less[u], m, 16);
-            equal[u] += __shfl_xor(equal[u], m, 16);
+            for (int v = 0; v < 8; ++v) ns[u][v] = HEAD ? sb[u] - ns[u][v] : ns[u][v] - sb[u];   // minus the coefficient
+        // ---- second pass: the distances ------------------------------------------------------------------
+        float acc[8][8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int v = 0; v < 8; ++v) acc[u][v] = 0.f;
+        for (int j0 = 0; j0 < dim; j0 += kRankJ) {
+            __syncthreads();                              // the previous chunk has been consumed
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {        // two batches of eight loads: fewer registers in flight
+                float4 vb[2], vd[2], vw[2], ve[2];
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int j = min(j0 + sj + 8 * (2 * half + i), dim - 4);
+                    vb[i] = ld4(rw.pb + j); vd[i] = ld4(rw.pd + j); vw[i] = ld4(rw.pw + j); ve[i] = ld4(pe + j);
+                }
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int jj = sj + 8 * (2 * half + i);
+                    float4 B4 = HEAD ? make_float4(vb[i].x - vd[i].x, vb[i].y - vd[i].y, vb[i].z - vd[i].z, vb[i].w - vd[i].w)
+                                     : make_float4(vb[i].x + vd[i].x, vb[i].y + vd[i].y, vb[i].z + vd[i].z, vb[i].w + vd[i].w);
+                    float4 w4 = vw[i], e4 = ve[i];
+                    if (j0 + jj >= dim) B4 = w4 = e4 = make_float4(0.f, 0.f, 0.f, 0.f);
+                    s_b[jj][sc] = B4.x; s_b[jj + 1][sc] = B4.y; s_b[jj + 2][sc] = B4.z; s_b[jj + 3][sc] = B4.w;
+                    s_w[jj][sc] = w4.x; s_w[jj + 1][sc] = w4.y; s_w[jj + 2][sc] = w4.z; s_w[jj + 3][sc] = w4.w;
+                    s_e[jj][sc] = e4.x; s_e[jj + 1][sc] = e4.y; s_e[jj + 2][sc] = e4.z; s_e[jj + 3][sc] = e4.w;
+                }
+            }
+            __syncthreads();
+#pragma unroll 2
+            for (int jj = 0; jj < kRankJ; ++jj) {
+                const float4 ba = *reinterpret_cast<const float4 *>(&s_b[jj][ty * 4]);
+                const float4 bb = *reinterpret_cast<const float4 *>(&s_b[jj][64 + ty * 4]);
+                const float4 wa = *reinterpret_cast<const float4 *>(&s_w[jj][ty * 4]);
+                const float4 wb = *reinterpret_cast<const float4 *>(&s_w[jj][64 + ty * 4]);
+                const float4 ea = *reinterpret_cast<const float4 *>(&s_e[jj][tx * 4]);
+                const float4 eb = *reinterpret_cast<const float4 *>(&s_e[jj][64 + tx * 4]);
+                const float bv[8] = {ba.x, ba.y, ba.z, ba.w, bb.x, bb.y, bb.z, bb.w};
+                const float wv[8] = {wa.x, wa.y, wa.z, wa.w, wb.x, wb.y, wb.z, wb.w};
+                const float ev[8] = {ea.x, ea.y, ea.z, ea.w, eb.x, eb.y, eb.z, eb.w};
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+#pragma unroll
+                    for (int v = 0; v < 8; ++v)
+                        acc[u][v] = rank_step<DIST>(acc[u][v], __builtin_fmaf(ns[u][v], wv[u], HEAD ? ev[v] - bv[u] : bv[u] - ev[v]));
+            }
         }
-        const int64_t q = q0 + (u < 4 ? 0 : 64) + ty * 4 + (u & 3);
-        if (tx == 0 && q < a.nq) {
-            if (less[u]) atomicAdd(&a.n_less[q], less[u]);
-            if (equal[u]) atomicAdd(&a.n_equal[q], equal[u]);
-        }
+        rank_count(acc, tr, e0, e_end, tx, less, equal);
     }
+    rank_flush(a, q0, tx, ty, less, equal);
 }
 
 stx_status launch_rank(stx_ctx *c, const stx_params *p, const int32_t *h, const int32_t *r, const int32_t *t,
@@ -207,23 +406,26 @@ stx_status launch_rank(stx_ctx *c, const stx_params *p, const int32_t *h, const 
     // Candidate slices: enough workgroups that the last, partly filled round of them is a small share of the
     // run (768 fit the chip at once), but whole tiles per slice.
     const int64_t tiles = ((int64_t)n_ent + kRankE - 1) / kRankE;
+    const int64_t min_tiles = c->cfg.model == STX_TRANSH ? 4 : 2;   // TransH workgroups start with a dot product per query
     int64_t slices = (32768 + qblocks - 1) / qblocks;
-    if (slices > (tiles + 1) / 2) slices = (tiles + 1) / 2;   // at least two tiles per workgroup
+    if (slices > (tiles + min_tiles - 1) / min_tiles) slices = (tiles + min_tiles - 1) / min_tiles;
     if (slices > 65535) slices = 65535;
     const int32_t slice = (int32_t)((tiles + slices - 1) / slices) * kRankE;
     slices = ((int64_t)n_ent + slice - 1) / slice;
-    const RankArgs a{p->ent, h, r, t, nq, n_ent, (int32_t)c->cfg.n_rel, c->cfg.dim, slice, true_score, n_less, n_equal,
-                     c->ctrl + CTRL_BAD_INDEX};
+    const bool transh = c->cfg.model == STX_TRANSH;
+    const RankArgs a{p->ent, transh ? p->rel : nullptr, transh ? p->w : nullptr, h, r, t, nq, n_ent, (int32_t)c->cfg.n_rel,
+                     c->cfg.dim, slice, true_score, n_less, n_equal, c->ctrl + CTRL_BAD_INDEX};
     const dim3 grid((unsigned)qblocks, (unsigned)slices), qgrid((unsigned)((nq + kThreads - 1) / kThreads));
+#define STX_RANK_GO(KT, KS, D, H)                                                                               \
+    do {                                                                                                        \
+        hipLaunchKernelGGL((KT<D, H>), qgrid, dim3(kThreads), 0, c->stream, a);                                 \
+        ProfScope prof(c, #KS);                                                                                 \
+        hipLaunchKernelGGL((KS<D, H>), grid, dim3(kThreads), 0, c->stream, a);                                  \
+    } while (0)
 #define STX_RANK(D)                                                                                             \
     do {                                                                                                        \
-        if (side) hipLaunchKernelGGL((k_rank_true<D, true>), qgrid, dim3(kThreads), 0, c->stream, a);           \
-        else hipLaunchKernelGGL((k_rank_true<D, false>), qgrid, dim3(kThreads), 0, c->stream, a);               \
-        {                                                                                                       \
-            ProfScope prof(c, "k_rank");                                                                        \
-            if (side) hipLaunchKernelGGL((k_rank<D, true>), grid, dim3(kThreads), 0, c->stream, a);             \
-            else hipLaunchKernelGGL((k_rank<D, false>), grid, dim3(kThreads), 0, c->stream, a);                 \
-        }                                                                                                       \
+        if (transh) { if (side) STX_RANK_GO(k_rank_true_h, k_rank_h, D, true); else STX_RANK_GO(k_rank_true_h, k_rank_h, D, false); } \
+        else        { if (side) STX_RANK_GO(k_rank_true, k_rank, D, true); else STX_RANK_GO(k_rank_true, k_rank, D, false); }         \
         if (D == STX_L2 || D == STX_TORUS_L2)                                                                   \
             hipLaunchKernelGGL((k_rank_finish<D>), qgrid, dim3(kThreads), 0, c->stream, true_score, nq);        \
     } while (0)
@@ -235,6 +437,7 @@ stx_status launch_rank(stx_ctx *c, const stx_params *p, const int32_t *h, const 
     default: STX_RANK(STX_TORUS_L2); break;
     }
 #undef STX_RANK
+#undef STX_RANK_GO
     return hip_ok(hipGetLastError());
 }
 

@@ -27,9 +27,11 @@ def band_tol(dim):
 
 
 def run_rank(wl, X, h, r, t, side, max_batch=8):
+    """X: the stacked table of TransE / TorusE, or the dict of TransH's tables."""
     cfg = B.make_config(wl.model, wl.dist, wl.n_ent, wl.n_rel, wl.dim, max_batch, 1, margin=wl.margin)
     ctx = B.Context(cfg, G.DEV)
-    p = B.Params(G.dev_f32(X))
+    p = (B.Params(G.dev_f32(X["ent"]), G.dev_f32(X["rel"]), G.dev_f32(X["w"])) if isinstance(X, dict)
+         else B.Params(G.dev_f32(X)))
     nq = len(h)
     ts = torch.full((max(nq, 1),), float("nan"), dtype=torch.float32, device=G.DEV)
     less = torch.full((max(nq, 1),), -7, dtype=torch.int32, device=G.DEV)
@@ -127,11 +129,6 @@ def test_rank_edge_cases():
     with pytest.raises(B.StxError) as err:
         B.stx_rank(ctx, p, G.dev_i32(z), G.dev_i32(z), G.dev_i32(z), 2, out, cnt, cnt.clone())
     assert err.value.status == B.STX_ERR_BAD_ARG
-    wlh = W.Workload("case", 7, "transh", "l2", 50, 3, 8, 8, 8, 8, 1, 1.0, 0.01, 1, 0.0, 0.0)
-    mh = G.GpuModel(wlh, W.make_tables(wlh))
-    with pytest.raises(B.StxError) as err:
-        B.stx_rank(mh.ctx, mh.params, G.dev_i32(z), G.dev_i32(z), G.dev_i32(z), B.STX_TAIL, out, cnt, cnt.clone())
-    assert err.value.status == B.STX_ERR_UNSUPPORTED
 
 
 def test_rank_true_score_matches_the_forward_pass():
@@ -176,3 +173,94 @@ def test_rank_full_size(name, nq, n_sample):
     _, first, inv = np.unique(key, return_index=True, return_inverse=True)
     assert np.array_equal(less, less[first][inv]) and np.array_equal(equal, equal[first][inv])
     assert 0.0 <= hits[B.STX_TAIL] <= 1.0 and 0.0 <= hits[B.STX_HEAD] <= 1.0
+
+
+# ------------------------------------------------------------------------------------------ TransH
+def transh_abs_tol(tabs, h, r, t, side, dim):
+    """What the oracle's band does not cover: the kernel forms the projection coefficient w.x from two separate
+    dot products, w.b - w.e (b = the query's own entity), each an fp32 sum of dim products.  Their rounding
+    error, (dim + 1) 2^-24 times the magnitudes summed, moves every element of y by that much times |w_j|."""
+    E, Wn = np.abs(tabs["ent"].astype(np.float64)), np.abs(tabs["w"].astype(np.float64))
+    b = h if side == B.STX_TAIL else t
+    mag_b = (Wn[r] * E[b]).sum(1)                          # sum |w_j| |b_j| per query
+    mag_e = (E @ Wn.T).max(0)[r]                           # the largest sum |w_j| |e_j| over the candidates
+    return 2.0 * (dim + 1) * 2.0**-24 * (mag_b + mag_e) * Wn[r].sum(1)      # (the L1 norm of w bounds the L2 one)
+
+
+H_CASES = [
+    # dist, n_ent, n_rel, dim, nq
+    ("l1", 10, 2, 8, 1),
+    ("l2", 300, 7, 32, 200),
+    ("l1", 1000, 20, 128, 129),
+    ("l2_sq", 515, 3, 100, 77),
+    ("torus_l1", 257, 4, 36, 130),
+    ("l2", 400, 9, 1024, 64),
+]
+
+
+@pytest.mark.parametrize("dist,n_ent,n_rel,dim,nq", H_CASES)
+@pytest.mark.parametrize("side,oside", SIDES)
+def test_rank_transh_counts_within_the_oracle_band(side, oside, dist, n_ent, n_rel, dim, nq):
+    wl = _wl("transh", dist, n_ent, n_rel, dim)
+    tabs = W.make_tables(wl)
+    rng = np.random.default_rng(n_ent + dim + side + 1)
+    h, t = rng.integers(0, n_ent, nq).astype(np.int32), rng.integers(0, n_ent, nq).astype(np.int32)
+    r = rng.integers(0, n_rel, nq).astype(np.int32)
+    ctx, ts, less, equal = run_rank(wl, tabs, h, r, t, side)
+    tol = max(G.REL_TOL, (dim + 8) * 2.0**-24)
+    extra = transh_abs_tol(tabs, h, r, t, side, dim) * (2.0 * np.abs(tabs["ent"]).max() * 4 if dist == "l2_sq" else 1.0)
+    ot = stxo.Tables(tabs["ent"], tabs["rel"], tabs["w"])
+    ref = stxo.rank(oracle_config(wl), ot, h, r, t, oside, tol=tol, abs_tol=extra)
+    check_counts(ts, less, equal, ref, 4 * tol)
+    assert B.stx_check_indices(ctx) == 0
+    sure = ref[2] == 1
+    if dim <= 128:                                         # (wide rows: worst-case bounds, crowded scores, no empty bands)
+        assert sure.mean() > 0.05                          # the band is not all that makes the test pass
+    assert np.array_equal(less[sure], ref[1][sure]) and np.all(equal[sure] == 1)
+
+
+@pytest.mark.parametrize("dist", ["l1", "l2_sq"])
+@pytest.mark.parametrize("side,oside", SIDES)
+def test_rank_transh_counts_exact_on_exactly_summable_tables(side, oside, dist):
+    n_ent, n_rel, dim, nq = 500, 6, 4, 300
+    wl = _wl("transh", dist, n_ent, n_rel, dim)
+    rng = np.random.default_rng(23 + side)
+    tabs = {"ent": (rng.integers(-4, 4, (n_ent, dim)) / 2.0).astype(np.float32),
+            "rel": (rng.integers(-4, 4, (n_rel, dim)) / 2.0).astype(np.float32),
+            "w": rng.integers(-1, 2, (n_rel, dim)).astype(np.float32)}
+    h, t = rng.integers(0, n_ent, nq).astype(np.int32), rng.integers(0, n_ent, nq).astype(np.int32)
+    r = rng.integers(0, n_rel, nq).astype(np.int32)
+    _, ts, less, equal = run_rank(wl, tabs, h, r, t, side)
+    ref_ts, ref_less, ref_band = stxo.rank(oracle_config(wl), stxo.Tables(tabs["ent"], tabs["rel"], tabs["w"]), h, r, t,
+                                           oside, tol=0.0)
+    assert ref_band.max() > 1
+    assert np.array_equal(less, ref_less) and np.array_equal(equal, ref_band)
+    assert np.array_equal(ts.astype(np.float64), ref_ts)
+
+
+def test_rank_transh_full_size():
+    """The "transh" benchmark tables (15,000 entities, d = 128, L2) against an FB15k-sized test split."""
+    wl = W.WORKLOADS["transh"]
+    tabs = W.make_tables(wl)
+    nq = W.N_TEST_FB15K
+    h, r, t = W.make_test_triplets(wl, nq)
+    pick = np.sort(np.random.default_rng(6).choice(nq, 128, replace=False))
+    tol = max(G.REL_TOL, (wl.dim + 8) * 2.0**-24)
+    ot = stxo.Tables(tabs["ent"], tabs["rel"], tabs["w"])
+    for side, oside in SIDES:
+        _, ts, less, equal = run_rank(wl, tabs, h, r, t, side)
+        assert np.all(np.isfinite(ts)) and np.all(equal >= 1) and np.all(less.astype(np.int64) + equal <= wl.n_ent)
+        extra = transh_abs_tol(tabs, h[pick], r[pick], t[pick], side, wl.dim)
+        ref = stxo.rank(oracle_config(wl), ot, h[pick], r[pick], t[pick], oside, tol=tol, abs_tol=extra)
+        check_counts(ts[pick], less[pick], equal[pick], ref, 4 * tol)
+
+
+def test_rank_transr_is_not_supported():
+    wl = W.Workload("case", 7, "transr", "l2", 50, 3, 8, 32, 32, 8, 1, 1.0, 0.01, 1, 0.0, 0.0, True)
+    m = G.GpuModel(wl, W.make_tables(wl), flags=B.STX_FLAG_BF16_PROJ)
+    z = G.dev_i32(np.zeros(3, np.int32))
+    out = torch.zeros(4, dtype=torch.float32, device=G.DEV)
+    cnt = torch.zeros(4, dtype=torch.int32, device=G.DEV)
+    with pytest.raises(B.StxError) as err:
+        B.stx_rank(m.ctx, m.params, z, z, z, B.STX_TAIL, out, cnt, cnt.clone())
+    assert err.value.status == B.STX_ERR_UNSUPPORTED

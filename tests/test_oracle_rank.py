@@ -191,3 +191,6 @@ def test_rank_transh_band_uses_the_magnitudes_behind_y():
     assert less[0] == 1 and band[0] == 1                                # e = 0 (x = 0) scores exactly 1, below x = 1
     ts, less, band = stxo.rank(cfg, stxo.Tables(E, D, Wn2), [0], [0], [1], stxo.TAIL, tol=1e-3)
     assert less[0] == 0 and band[0] >= 2                                # scale ~ 2 |x| + 1: 1e-3 of it covers the gap
+    # an absolute allowance per query widens the band the same way
+    ts, less, band = stxo.rank(cfg, stxo.Tables(E, D, Wn2), [0], [0], [1], stxo.TAIL, tol=0.0, abs_tol=[0.5])
+    assert less[0] == 0 and band[0] >= 2
