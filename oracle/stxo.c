@@ -460,7 +460,7 @@ int stxo_forward(const stxo_cfg *c, const stxo_tables *tb, const stxo_batch *bt,
 
 /* Link prediction by exhaustive scoring (the "predicting links" facility of Sec. 4.7; Hits@10, the
  * accuracy measure of Sec. 6.1, is the share of test triplets whose true entity ranks among the ten
- * best).  TransE, TorusE and TransH.  The paper fixes no protocol; the reading taken here is the usual
+ * best).  The paper fixes no protocol; the reading taken here is the usual
  * raw (unfiltered) one: for a test triplet (h, r, t) every entity e of the table is a candidate,
  * side 0 (tail prediction) scores the triplets (h, r, e), true entity t; side 1 (head prediction)
  * scores (e, r, t), true entity h; smaller is better.
@@ -470,6 +470,8 @@ int stxo_forward(const stxo_cfg *c, const stxo_tables *tb, const stxo_batch *bt,
  *     would scale all candidates of a query alike and plays no part.
  *   TransH: the training score of the triplet with e in place of the true entity (Sec. 4.5):
  *     x = h - e or e - t in fp32, y = x + d_r - (w_r.x) w_r, distance(y), by row_x / row_y above.
+ *   TransR: likewise (Sec. 4.4): y = M_r x + r on the fp32 operands as they are (rounding the operands to
+ *     bfloat16 is an option of the training configuration; a configuration that sets it is refused here).
  * The distance is the model's (row_dist, summed in double).  Outputs per query:
  *   true_score : the true entity's score;
  *   n_less     : candidates scoring strictly below the true entity and outside the band below;
@@ -487,13 +489,13 @@ int stxo_rank(const stxo_cfg *c, const stxo_tables *tb, const int32_t *h, const 
               int64_t nq, int32_t side, double tol, const double *abs_tol, double *true_score, int64_t *n_less,
               int64_t *n_band)
 {
-    if (c->model == STXO_TRANSR || side < 0 || side > 1) return 1;
-    const int32_t d = c->dim;
+    if ((c->model == STXO_TRANSR && c->bf16_proj) || side < 0 || side > 1) return 1;
+    const int32_t d = c->dim, n = out_dim(c);
     const float *X = tb->ent;
     float *q = (float *)malloc(sizeof(float) * (size_t)d);
     float *x = (float *)malloc(sizeof(float) * (size_t)d);
-    double *y = (double *)malloc(sizeof(double) * (size_t)d);
-    double *ya = (double *)malloc(sizeof(double) * (size_t)d);
+    double *y = (double *)malloc(sizeof(double) * (size_t)(d > n ? d : n));
+    double *ya = (double *)malloc(sizeof(double) * (size_t)(d > n ? d : n));
     double *score = (double *)malloc(sizeof(double) * (size_t)c->n_ent);
     double *scale = (double *)malloc(sizeof(double) * (size_t)c->n_ent);
     if (!q || !x || !y || !ya || !score || !scale) return 2;
@@ -514,8 +516,8 @@ int stxo_rank(const stxo_cfg *c, const stxo_tables *tb, const int32_t *h, const 
             } else {
                 row_x(c, tb, side == 0 ? h[i] : (int32_t)e, r[i], side == 0 ? (int32_t)e : t[i], x);
                 row_y(c, tb, r[i], x, y, NULL, ya);
-                score[e] = row_dist(c, y, d);
-                scale[e] = (c->dist == STXO_L2_SQ ? 2.0 : 1.0) * row_dist(c, ya, d);
+                score[e] = row_dist(c, y, n);
+                scale[e] = (c->dist == STXO_L2_SQ ? 2.0 : 1.0) * row_dist(c, ya, n);
             }
         }
         const int64_t te = side == 0 ? t[i] : h[i];

@@ -259,6 +259,8 @@ def rank(cfg: "Config", tables, h, r, t, side: int, tol: float = 0.0, abs_tol=No
         tables = Tables(_f32(tables))
     if cfg.model == TRANSH and (tables.rel is None or tables.w is None):
         raise ValueError("stxo_rank: TransH needs the d_r and w_r tables")
+    if cfg.model == TRANSR and (tables.rel is None or tables.proj is None):
+        raise ValueError("stxo_rank: TransR needs the r and M_r tables")
     h, r, t = _i32(h), _i32(r), _i32(t)
     nq = h.shape[0]
     ts = np.empty(nq, np.float64)
@@ -270,7 +272,7 @@ def rank(cfg: "Config", tables, h, r, t, side: int, tol: float = 0.0, abs_tol=No
         assert abs_tol.shape == (nq,)
     if lib().stxo_rank(C.byref(cc), C.byref(ct), _p(h), _p(r), _p(t), nq, side, tol, _p(abs_tol), _p(ts), _p(less),
                        _p(band)) != 0:
-        raise ValueError("stxo_rank: TransE / TorusE / TransH only, side 0 (tail) or 1 (head)")
+        raise ValueError("stxo_rank: side 0 (tail) or 1 (head); TransR without bfloat16 operand rounding")
     return ts, less, band
 
 

@@ -41,7 +41,8 @@ def test_rank_exact_ties_are_counted_in_the_band():
     ts, less, band = stxo.rank(_cfg(stxo.L1, 4, 1, 2), X, [0], [0], [1], stxo.TAIL)
     assert ts[0] == 1 and less[0] == 0 and band[0] == 4                  # all four entities are at distance 1
     with pytest.raises(ValueError):
-        stxo.rank(stxo.Config(stxo.TRANSR, stxo.L1, 4, 1, 2, 2), X, [0], [0], [1], stxo.TAIL)
+        stxo.rank(stxo.Config(stxo.TRANSR, stxo.L1, 4, 1, 2, 2, bf16_proj=True), stxo.Tables(X[:4], X[4:], None, X[:4].reshape(1, 2, 4)[:, :, :2].copy()),
+                  [0], [0], [1], stxo.TAIL)
     with pytest.raises(ValueError):
         stxo.rank(_cfg(stxo.L1, 4, 1, 2), X, [0], [0], [1], 2)
 
@@ -173,7 +174,7 @@ def test_rank_transh_true_score_is_the_training_score_and_zero_normals_give_a_tr
         for a, b in zip(got, want):
             assert np.array_equal(a, b)
     with pytest.raises(ValueError):
-        stxo.rank(stxo.Config(stxo.TRANSR, stxo.L1, n_ent, D.shape[0], dim, dim), stxo.Tables(E, D), h, r, t, 0)
+        stxo.rank(stxo.Config(stxo.TRANSR, stxo.L1, n_ent, D.shape[0], dim, dim), stxo.Tables(E, D), h, r, t, 0)   # no M_r
 
 
 def test_rank_transh_band_uses_the_magnitudes_behind_y():
@@ -194,3 +195,54 @@ def test_rank_transh_band_uses_the_magnitudes_behind_y():
     # an absolute allowance per query widens the band the same way
     ts, less, band = stxo.rank(cfg, stxo.Tables(E, D, Wn2), [0], [0], [1], stxo.TAIL, tol=0.0, abs_tol=[0.5])
     assert less[0] == 0 and band[0] >= 2
+
+
+# ------------------------------------------------------------------------------------------ TransR
+def _transr_grid_problem(seed, n_ent=90, n_rel=4, dim=4, rel_dim=3, nq=50):
+    rng = np.random.default_rng(seed)
+    E = (rng.integers(-4, 4, (n_ent, dim)) / 2.0).astype(np.float32)
+    Rv = (rng.integers(-4, 4, (n_rel, rel_dim)) / 2.0).astype(np.float32)
+    M = rng.integers(-2, 3, (n_rel, rel_dim, dim)).astype(np.float32)
+    h, t = rng.integers(0, n_ent, nq).astype(np.int32), rng.integers(0, n_ent, nq).astype(np.int32)
+    r = rng.integers(0, n_rel, nq).astype(np.int32)
+    return E, Rv, M, h, r, t
+
+
+@pytest.mark.parametrize("dist", [stxo.L1, stxo.L2_SQ])
+@pytest.mark.parametrize("side", [stxo.TAIL, stxo.HEAD])
+def test_rank_transr_against_projected_entities(dist, side):
+    # Sec. 4.4 scores M_r h + r - M_r t; the oracle applies M_r to h - t.  Project every entity with the
+    # library's matrix product, form the score from the projected rows, and count (exact on this grid).
+    E, Rv, M, h, r, t = _transr_grid_problem(41 + dist + side)
+    n_ent, dim = E.shape
+    cfg = stxo.Config(stxo.TRANSR, dist, n_ent, Rv.shape[0], dim, M.shape[1])
+    ts, less, band = stxo.rank(cfg, stxo.Tables(E, Rv, None, M), h, r, t, side)
+    for i in range(len(h)):
+        P = E.astype(np.float64) @ M[r[i]].astype(np.float64).T          # n_ent x rel_dim
+        rv = Rv[r[i]].astype(np.float64)
+        Y = (P[h[i]] + rv) - P if side == stxo.TAIL else P + rv - P[t[i]]
+        true = t[i] if side == stxo.TAIL else h[i]
+        sc = np.abs(Y).sum(1) if dist == stxo.L1 else (Y * Y).sum(1)
+        assert ts[i] == sc[true]
+        assert less[i] == (sc < sc[true]).sum() and band[i] == (sc == sc[true]).sum()
+    assert band.max() > 1
+
+
+def test_rank_transr_true_score_is_the_training_score_and_identity_matrices_give_transe():
+    wl, tabs, bt = small_problem("transr", "l2", n_ent=40, n_rel=5, b=25, k=0, dim=8, rel_dim=6, seed=5)
+    cfg = oracle_config(wl, bf16=False)
+    fw = stxo.forward(cfg, oracle_tables(tabs), bt, want_x=False)
+    for side in (stxo.TAIL, stxo.HEAD):
+        ts, less, band = stxo.rank(cfg, oracle_tables(tabs), bt.h, bt.r, bt.t, side)
+        assert np.array_equal(ts, fw.scores[:25])
+    # M_r = I: TransR is TransE on the stacked table [E; R] (Sec. 4.4 with the identity; exact on a grid)
+    E, Rv, M, h, r, t = _transr_grid_problem(12, dim=4, rel_dim=4)
+    M[:] = np.eye(4, dtype=np.float32)
+    n_ent = E.shape[0]
+    cfg_r = stxo.Config(stxo.TRANSR, stxo.L1, n_ent, Rv.shape[0], 4, 4)
+    cfg_e = stxo.Config(stxo.TRANSE, stxo.L1, n_ent, Rv.shape[0], 4)
+    for side in (stxo.TAIL, stxo.HEAD):
+        got = stxo.rank(cfg_r, stxo.Tables(E, Rv, None, M), h, r, t, side)
+        want = stxo.rank(cfg_e, np.concatenate([E, Rv]), h, r, t, side)
+        for a, b in zip(got, want):
+            assert np.array_equal(a, b)
