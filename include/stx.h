@@ -232,22 +232,34 @@ stx_status stx_train_step(stx_ctx *ctx, const stx_batch *batch, stx_incidence *i
 
 /* Link prediction by exhaustive scoring (Sec. 4.7 lists it among the framework's functions; Hits@10,
  * Sec. 6.1, is the share of test triplets whose true entity is among the ten best candidates).  Raw,
- * unfiltered counts; TransE / TorusE contexts only (else STX_ERR_UNSUPPORTED); a relation weight scales
- * all candidates of a query alike and is ignored.  For test triplet i = (h, r, t) every entity e of the
- * table is a candidate:
- *   STX_TAIL : q = X[h] + X[n_ent + r],  y = q - X[e],  the true entity is t;
- *   STX_HEAD : q = X[t] - X[n_ent + r],  y = X[e] - q,  the true entity is h;
- * q and y rounded once each, score(e) = the context's distance of y, summed over the row in index order
- * (the L2 kinds with a fused multiply-add, and compared before the square root; the torus kinds on the
- * fractional part of y as the hardware forms it, which stays below 1 where y - floor(y) would round to 1).
+ * unfiltered counts.  For test triplet i = (h, r, t) every entity e of the table is a candidate; STX_TAIL
+ * scores the triplets (h, r, e) (the true entity is t), STX_HEAD the triplets (e, r, t) (true entity h).
+ *   TransE / TorusE : q = X[h] + X[n_ent + r], y = q - X[e]  |  q = X[t] - X[n_ent + r], y = X[e] - q;
+ *                     q and y rounded once each.  A relation weight scales all candidates of a query
+ *                     alike and is ignored.
+ *   TransH (Sec. 4.5): y = (B - E[e]) - s w_r with B = E[h] + d_r, s = w_r.E[h] - w_r.E[e]  |
+ *                     y = (E[e] - B) - s w_r with B = E[t] - d_r, s = w_r.E[e] - w_r.E[t].
+ *   TransR (Sec. 4.4): with p_v = M_r E[v] in fp32 (no bfloat16 rounding here, whatever the flag),
+ *                     y = (p_h + r) - p_e  |  y = p_e - (p_t - r).
+ * score(e) = the context's distance of y.  Every sum (distances, dot products, projections) runs over the
+ * row in index order; products inside sums are fused multiply-adds; L2 kinds are compared before the
+ * square root; the torus kinds use the fractional part of y as the hardware forms it, which stays below
+ * 1 where y - floor(y) would round to 1.
  *   true_score[i] : score of the true entity;
  *   n_less[i]     : candidates scoring strictly below it (the best rank it can claim is 1 + n_less);
  *   n_equal[i]    : candidates scoring exactly like it, itself included (the worst is n_less + n_equal).
  * h, r, t: [nq] device, in; the three outputs: [nq] device.  Out-of-range indices are clamped and
- * counted as in stx_build_incidence.  Cost: nq * n_ent * dim steps of vector arithmetic.               */
+ * counted as in stx_build_incidence.  work: device scratch of stx_rank_work_bytes(nq) bytes, 256-byte
+ * aligned, owned by the caller; TransE / TorusE / TransH need none (null is fine).  TransR groups the
+ * queries by relation and builds one projected table per relation that occurs; it waits for the stream
+ * once (to learn the group sizes) and launches a few kernels per relation.
+ * Cost: nq * n_ent * dim steps of vector arithmetic (TransH about twice that; TransR rel_dim in place of
+ * dim, plus n_ent * dim * rel_dim per relation that occurs).                                            */
 enum { STX_TAIL = 0, STX_HEAD = 1 };
+stx_status stx_rank_work_bytes(const stx_ctx *ctx, int64_t nq, size_t *bytes /* host, out */);
 stx_status stx_rank(stx_ctx *ctx, const stx_params *p, const int32_t *h, const int32_t *r, const int32_t *t,
-                    int64_t nq, int32_t side, float *true_score, int32_t *n_less, int32_t *n_equal);
+                    int64_t nq, int32_t side, float *true_score, int32_t *n_less, int32_t *n_equal, void *work,
+                    size_t work_bytes);
 
 /* Live timing of one kernel, for benchmarks.  stx_profile_kernel: from now on every launch of the kernel
  * called `kernel_name` (e.g. "k_forward_stacked", "k_seg_reduce", "k_sgd_rows", "k_scatter") on this

@@ -27,7 +27,7 @@ MODELS = {"transe": STX_TRANSE, "transh": STX_TRANSH, "transr": STX_TRANSR, "tor
 DISTS = {"l1": STX_L1, "l2": STX_L2, "torus_l1": STX_TORUS_L1, "torus_l2": STX_TORUS_L2, "l2_sq": STX_L2_SQ}
 
 EXPORTS = ["stx_workspace_bytes", "stx_create", "stx_destroy", "stx_sample_negatives", "stx_build_incidence",
-           "stx_check_indices", "stx_spmm", "stx_spmm_semiring", "stx_spmm_semiring_t", "stx_rank", "stx_forward", "stx_backward", "stx_sgd_step", "stx_backward_sgd", "stx_train_step", "stx_profile_kernel",
+           "stx_check_indices", "stx_spmm", "stx_spmm_semiring", "stx_spmm_semiring_t", "stx_rank", "stx_rank_work_bytes", "stx_forward", "stx_backward", "stx_sgd_step", "stx_backward_sgd", "stx_train_step", "stx_profile_kernel",
            "stx_profile_read", "stx_profile_dump", "stx_copy_f32", "stx_status_string"]
 
 
@@ -88,7 +88,8 @@ def lib():
         L.stx_spmm_semiring.argtypes = [vp, C.POINTER(stx_incidence), C.POINTER(stx_params), i32, vp]
         L.stx_spmm_semiring_t.argtypes = [vp, C.POINTER(stx_incidence), C.POINTER(stx_params), i32, vp, vp,
                                           C.POINTER(stx_grads)]
-        L.stx_rank.argtypes = [vp, C.POINTER(stx_params), vp, vp, vp, i64, i32, vp, vp, vp]
+        L.stx_rank.argtypes = [vp, C.POINTER(stx_params), vp, vp, vp, i64, i32, vp, vp, vp, vp, C.c_size_t]
+        L.stx_rank_work_bytes.argtypes = [vp, i64, C.POINTER(C.c_size_t)]
         L.stx_forward.argtypes = [vp, C.POINTER(stx_incidence), C.POINTER(stx_params), vp, vp]
         L.stx_backward.argtypes = [vp, C.POINTER(stx_incidence), C.POINTER(stx_params), C.POINTER(stx_grads)]
         L.stx_sgd_step.argtypes = [vp, C.POINTER(stx_params), C.POINTER(stx_incidence), C.POINTER(stx_grads),
@@ -273,14 +274,26 @@ def stx_spmm_semiring_t(ctx: Context, inc: Incidence, p: Params, kind: int, gz, 
                                                             gz.data_ptr(), work.data_ptr(), C.byref(g.c)))
 
 
-def stx_rank(ctx: Context, p: Params, h, r, t, side: int, true_score, n_less, n_equal):
+def stx_rank_work_bytes(ctx: Context, nq: int) -> int:
+    n = C.c_size_t(0)
+    _check("stx_rank_work_bytes", lib().stx_rank_work_bytes(ctx.handle, nq, C.byref(n)))
+    return n.value
+
+
+def stx_rank(ctx: Context, p: Params, h, r, t, side: int, true_score, n_less, n_equal, work=None):
+    """work: a uint8 device tensor of at least stx_rank_work_bytes(nq) + 256 bytes (TransR), else None."""
     nq = h.numel()
     assert r.numel() == nq and t.numel() == nq
     assert true_score.is_cuda and true_score.dtype == torch.float32 and true_score.numel() >= nq
     for c in (n_less, n_equal):
         assert c.is_cuda and c.dtype == torch.int32 and c.is_contiguous() and c.numel() >= nq
+    wp, wb = None, 0
+    if work is not None:
+        assert work.is_cuda and work.dtype == torch.uint8 and work.is_contiguous()
+        wp = (work.data_ptr() + 255) // 256 * 256
+        wb = work.numel() - (wp - work.data_ptr())
     _check("stx_rank", lib().stx_rank(ctx.handle, C.byref(p.c), _i32dev(h), _i32dev(r), _i32dev(t), nq, side,
-                                      true_score.data_ptr(), n_less.data_ptr(), n_equal.data_ptr()))
+                                      true_score.data_ptr(), n_less.data_ptr(), n_equal.data_ptr(), wp, wb))
 
 
 def stx_forward(ctx: Context, inc: Incidence, p: Params, scores, loss):

@@ -409,17 +409,29 @@ stx_status stx_spmm_semiring_t(stx_ctx *ctx, const stx_incidence *inc, const stx
     return launch_semiring_t(ctx, inc, p, kind, gz, work, g->rows);
 }
 
+stx_status stx_rank_work_bytes(const stx_ctx *ctx, int64_t nq, size_t *bytes)
+{
+    if (!ctx || !bytes) return STX_ERR_NULL;
+    if (nq < 0 || nq > ((int64_t)1 << 31) - 256) return STX_ERR_BAD_ARG;
+    *bytes = rank_work_bytes(ctx, nq);
+    return STX_OK;
+}
+
 stx_status stx_rank(stx_ctx *ctx, const stx_params *p, const int32_t *h, const int32_t *r, const int32_t *t,
-                    int64_t nq, int32_t side, float *true_score, int32_t *n_less, int32_t *n_equal)
+                    int64_t nq, int32_t side, float *true_score, int32_t *n_less, int32_t *n_equal, void *work,
+                    size_t work_bytes)
 {
     if (!ctx) return STX_ERR_NULL;
     if (!p || !p->ent) return STX_ERR_NULL;
     if (nq < 0 || nq > ((int64_t)1 << 31) - 256 || (side != STX_TAIL && side != STX_HEAD)) return STX_ERR_BAD_ARG;
-    if (ctx->cfg.model == STX_TRANSR) return STX_ERR_UNSUPPORTED;
     if (ctx->cfg.model == STX_TRANSH && (!p->rel || !p->w)) return STX_ERR_NULL;
+    if (ctx->cfg.model == STX_TRANSR && (!p->rel || !p->proj)) return STX_ERR_NULL;
     if (nq == 0) return STX_OK;
     if (!h || !r || !t || !true_score || !n_less || !n_equal) return STX_ERR_NULL;
-    return launch_rank(ctx, p, h, r, t, nq, side, true_score, n_less, n_equal);
+    const size_t need = rank_work_bytes(ctx, nq);
+    if (need > 0 && !work) return STX_ERR_NULL;
+    if (need > 0 && (work_bytes < need || ((uintptr_t)work & 255u))) return STX_ERR_WORKSPACE;
+    return launch_rank(ctx, p, h, r, t, nq, side, true_score, n_less, n_equal, work);
 }
 
 stx_status stx_forward(stx_ctx *ctx, const stx_incidence *inc, const stx_params *p, float *scores, float *loss)

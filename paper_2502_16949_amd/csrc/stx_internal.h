@@ -181,7 +181,8 @@ stx_status launch_sgd_rows(stx_ctx *, const stx_incidence *, const SgdTables &, 
 stx_status launch_forward_from_y(stx_ctx *, const stx_incidence *, const stx_params *, float *scores, float *loss);
 // stx_rank.hip
 stx_status launch_rank(stx_ctx *, const stx_params *, const int32_t *h, const int32_t *r, const int32_t *t, int64_t nq,
-                       int side, float *true_score, int32_t *n_less, int32_t *n_equal);
+                       int side, float *true_score, int32_t *n_less, int32_t *n_equal, void *work);
+size_t rank_work_bytes(const stx_ctx *, int64_t nq);   // scratch launch_rank needs for nq queries (0 unless TransR)
 // stx_semiring.hip
 stx_status launch_semiring(stx_ctx *, const stx_incidence *, const stx_params *, int kind, float *z_out);
 stx_status launch_semiring_t(stx_ctx *, const stx_incidence *, const stx_params *, int kind, const float *gz,

@@ -13,6 +13,8 @@
 // registers, so every value fetched from LDS feeds eight steps.  Sums run over the row in index order in
 // one thread; the true entity's own sum is formed the same way, so it compares equal to itself.
 // Counts are integers: candidate slices of one query block add theirs with atomics, in any order.
+#include <new>
+
 #include "stx_rowops.h"
 
 namespace stx {
@@ -36,7 +38,7 @@ __device__ inline float rank_step(float acc, float y)
 struct RankArgs {
     const float *X;                    // TransE / TorusE: [E;R]; TransH: E.  Rows of dim floats
     const float *D, *W;                // TransH: d_r and w_r, n_rel rows each
-    const int32_t *h, *r, *t;          // [nq]
+    const int32_t *h, *r, *t;          // [nq]; r may be null: every query has relation 0
     int64_t nq;
     int32_t n_ent, n_rel;
     int dim;
@@ -88,7 +90,7 @@ struct RankRows {
 template <bool HEAD>
 __device__ inline RankRows rank_rows(const RankArgs &a, int64_t qi)
 {
-    int32_t ih = a.h[qi], ir = a.r[qi], it = a.t[qi];
+    int32_t ih = a.h[qi], ir = a.r ? a.r[qi] : 0, it = a.t[qi];
     const bool bad = ih < 0 || ih >= a.n_ent || it < 0 || it >= a.n_ent || ir < 0 || ir >= a.n_rel;
     ih = min(max(ih, 0), a.n_ent - 1);
     it = min(max(it, 0), a.n_ent - 1);
@@ -397,25 +399,186 @@ __global__ __launch_bounds__(kThreads, 2) void k_rank_h(RankArgs a)
     rank_flush(a, q0, tx, ty, less, equal);
 }
 
-stx_status launch_rank(stx_ctx *c, const stx_params *p, const int32_t *h, const int32_t *r, const int32_t *t,
-                       int64_t nq, int side, float *true_score, int32_t *n_less, int32_t *n_equal)
+// ---- TransR (Sec. 4.4) -----------------------------------------------------------------------------
+// score = dist(M_r (h - t) + r).  M_r is linear, so for one relation the candidates can be projected once,
+// p_e = M_r e, and the score of e as tail of (h, r, .) is dist((p_h + r) - p_e), as head of (., r, t)
+// dist(p_e - (p_t - r)): the TransE sweep over the table [P_r; r] with a single relation.  Queries are
+// grouped by relation (counting sort), and for every relation that occurs its projected table is built
+// (k_rr_project, a plain fp32 product with sums in index order) and swept by k_rank_true / k_rank.
+struct RankRWork {                      // partitions of the caller's work buffer
+    int32_t *counts, *cursor, *offsets; // [n_rel], [n_rel], [n_rel + 1]
+    int32_t *perm, *gh, *gt;            // [nq]: query at each grouped position, its clamped head and tail
+    float *gts;                         // [nq] grouped outputs
+    int32_t *gless, *gequal;
+    float *table;                       // (n_ent + 1) x rel_dim: P_r, then r
+    size_t total;
+};
+static RankRWork rank_r_work(const stx_config &cfg, int64_t nq, void *base)
 {
-    if (nq == 0) return STX_OK;
-    const int32_t n_ent = (int32_t)c->cfg.n_ent;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = (off + bytes + 255) / 256 * 256; return (char *)base + o; };
+    RankRWork w;
+    w.counts = (int32_t *)take((size_t)cfg.n_rel * 4);
+    w.cursor = (int32_t *)take((size_t)cfg.n_rel * 4);
+    w.offsets = (int32_t *)take((size_t)(cfg.n_rel + 1) * 4);
+    w.perm = (int32_t *)take((size_t)nq * 4);
+    w.gh = (int32_t *)take((size_t)nq * 4);
+    w.gt = (int32_t *)take((size_t)nq * 4);
+    w.gts = (float *)take((size_t)nq * 4);
+    w.gless = (int32_t *)take((size_t)nq * 4);
+    w.gequal = (int32_t *)take((size_t)nq * 4);
+    w.table = (float *)take((size_t)(cfg.n_ent + 1) * cfg.rel_dim * 4);
+    w.total = off;
+    return w;
+}
+size_t rank_work_bytes(const stx_ctx *c, int64_t nq)
+{
+    return c->cfg.model == STX_TRANSR ? rank_r_work(c->cfg, nq, nullptr).total : 0;
+}
+
+__global__ __launch_bounds__(kThreads) void k_rr_clear(int32_t *counts, int32_t *cursor, int n_rel)
+{
+    const int i = (int)blockIdx.x * kThreads + threadIdx.x;
+    if (i < n_rel) { counts[i] = 0; cursor[i] = 0; }
+}
+
+__global__ __launch_bounds__(kThreads) void k_rr_hist(const int32_t *h, const int32_t *r, const int32_t *t, int64_t nq,
+                                                      int32_t n_ent, int32_t n_rel, int32_t *counts, int32_t *bad)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= nq) return;
+    const int32_t ih = h[i], ir = r[i], it = t[i];
+    if (ih < 0 || ih >= n_ent || it < 0 || it >= n_ent || ir < 0 || ir >= n_rel) atomicAdd(bad, 1);
+    atomicAdd(&counts[min(max(ir, 0), n_rel - 1)], 1);
+}
+
+// offsets[i] = counts[0] + ... + counts[i-1], offsets[n_rel] = nq.  One workgroup.
+__global__ __launch_bounds__(kThreads) void k_rr_scan(const int32_t *counts, int32_t *offsets, int n_rel)
+{
+    __shared__ int32_t s_total;
+    int32_t base = 0;
+    for (int i0 = 0; i0 < n_rel; i0 += kThreads) {
+        const int i = i0 + (int)threadIdx.x;
+        const int32_t v = i < n_rel ? counts[i] : 0;
+        const int32_t ex = block_exclusive_scan(v, &s_total);
+        if (i < n_rel) offsets[i] = base + ex;
+        __syncthreads();
+        base += s_total;
+    }
+    if (threadIdx.x == 0) offsets[n_rel] = base;
+}
+
+// Grouped position of every query (any order inside a relation: a query's counts do not depend on it).
+__global__ __launch_bounds__(kThreads) void k_rr_scatter(const int32_t *h, const int32_t *r, const int32_t *t, int64_t nq,
+                                                         int32_t n_ent, int32_t n_rel, const int32_t *offsets,
+                                                         int32_t *cursor, int32_t *perm, int32_t *gh, int32_t *gt)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= nq) return;
+    const int32_t ir = min(max(r[i], 0), n_rel - 1);
+    const int32_t pos = offsets[ir] + atomicAdd(&cursor[ir], 1);
+    perm[pos] = (int32_t)i;
+    gh[pos] = min(max(h[i], 0), n_ent - 1);
+    gt[pos] = min(max(t[i], 0), n_ent - 1);
+}
+
+__global__ __launch_bounds__(kThreads) void k_rr_unpermute(const int32_t *perm, const float *gts, const int32_t *gless,
+                                                           const int32_t *gequal, int64_t nq, float *true_score,
+                                                           int32_t *n_less, int32_t *n_equal)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= nq) return;
+    const int32_t q = perm[i];
+    true_score[q] = gts[i];
+    n_less[q] = gless[i];
+    n_equal[q] = gequal[i];
+}
+
+// T[e][a] = sum_j E[e][j] M[a][j] (index order, fused multiply-adds) for e < n_ent, a < k; T[n_ent][a] = rvec[a].
+// Tiled like the sweep: 128 entities x 128 outputs per workgroup, 8 x 8 per thread.
+__global__ __launch_bounds__(kThreads, 3) void k_rr_project(const float *__restrict__ E, const float *__restrict__ M,
+                                                            const float *__restrict__ rvec, int32_t n_ent, int dim, int k,
+                                                            float *__restrict__ T)
+{
+    __shared__ __attribute__((aligned(16))) float s_m[kRankJ][kRankLd];
+    __shared__ __attribute__((aligned(16))) float s_e[kRankJ][kRankLd];
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const int32_t e0 = (int32_t)blockIdx.x * kRankE;
+    const int a0 = (int)blockIdx.y * kRankQ;
+    const int sc = tid & (kRankQ - 1), sj = (tid >> 7) * 4;
+    const float *pm = M + (int64_t)min(a0 + sc, k - 1) * dim;
+    const float *pe = E + (int64_t)min(e0 + sc, n_ent - 1) * dim;
+    if (blockIdx.x == 0 && tid < kRankQ && a0 + tid < k) T[(int64_t)n_ent * k + a0 + tid] = rvec[a0 + tid];
+    float acc[8][8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int v = 0; v < 8; ++v) acc[u][v] = 0.f;
+    for (int j0 = 0; j0 < dim; j0 += kRankJ) {
+        float4 vm[4], ve[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int j = min(j0 + sj + 8 * i, dim - 4);
+            vm[i] = ld4(pm + j); ve[i] = ld4(pe + j);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int jj = sj + 8 * i;
+            float4 m4 = vm[i], e4 = ve[i];
+            if (j0 + jj >= dim) m4 = e4 = make_float4(0.f, 0.f, 0.f, 0.f);
+            s_m[jj][sc] = m4.x; s_m[jj + 1][sc] = m4.y; s_m[jj + 2][sc] = m4.z; s_m[jj + 3][sc] = m4.w;
+            s_e[jj][sc] = e4.x; s_e[jj + 1][sc] = e4.y; s_e[jj + 2][sc] = e4.z; s_e[jj + 3][sc] = e4.w;
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int jj = 0; jj < kRankJ; ++jj) {
+            const float4 ma = *reinterpret_cast<const float4 *>(&s_m[jj][ty * 4]);
+            const float4 mb = *reinterpret_cast<const float4 *>(&s_m[jj][64 + ty * 4]);
+            const float4 ea = *reinterpret_cast<const float4 *>(&s_e[jj][tx * 4]);
+            const float4 eb = *reinterpret_cast<const float4 *>(&s_e[jj][64 + tx * 4]);
+            const float mv[8] = {ma.x, ma.y, ma.z, ma.w, mb.x, mb.y, mb.z, mb.w};
+            const float ev[8] = {ea.x, ea.y, ea.z, ea.w, eb.x, eb.y, eb.z, eb.w};
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int v = 0; v < 8; ++v) acc[u][v] = __builtin_fmaf(ev[v], mv[u], acc[u][v]);
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < 8; ++v) {
+        const int32_t e = e0 + (v < 4 ? 0 : 64) + tx * 4 + (v & 3);
+        if (e >= n_ent) continue;
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {                     // the thread's outputs: two runs of four consecutive a
+            const int a = a0 + g * 64 + ty * 4;
+            if (a < k) st4(T + (int64_t)e * k + a, make_float4(acc[4 * g][v], acc[4 * g + 1][v], acc[4 * g + 2][v], acc[4 * g + 3][v]));
+        }
+    }
+}
+
+// Launch shape of one sweep: query blocks, and candidate slices of whole tiles such that enough workgroups
+// exist for the last, partly filled round of them to be a small share of the run (768 fit the chip at once).
+struct RankShape {
+    dim3 grid, qgrid;
+    int32_t slice;
+};
+static RankShape rank_shape(int64_t nq, int32_t n_ent, int64_t min_tiles)
+{
     const int64_t qblocks = (nq + kRankQ - 1) / kRankQ;
-    // Candidate slices: enough workgroups that the last, partly filled round of them is a small share of the
-    // run (768 fit the chip at once), but whole tiles per slice.
     const int64_t tiles = ((int64_t)n_ent + kRankE - 1) / kRankE;
-    const int64_t min_tiles = c->cfg.model == STX_TRANSH ? 4 : 2;   // TransH workgroups start with a dot product per query
     int64_t slices = (32768 + qblocks - 1) / qblocks;
     if (slices > (tiles + min_tiles - 1) / min_tiles) slices = (tiles + min_tiles - 1) / min_tiles;
     if (slices > 65535) slices = 65535;
     const int32_t slice = (int32_t)((tiles + slices - 1) / slices) * kRankE;
     slices = ((int64_t)n_ent + slice - 1) / slice;
-    const bool transh = c->cfg.model == STX_TRANSH;
-    const RankArgs a{p->ent, transh ? p->rel : nullptr, transh ? p->w : nullptr, h, r, t, nq, n_ent, (int32_t)c->cfg.n_rel,
-                     c->cfg.dim, slice, true_score, n_less, n_equal, c->ctrl + CTRL_BAD_INDEX};
-    const dim3 grid((unsigned)qblocks, (unsigned)slices), qgrid((unsigned)((nq + kThreads - 1) / kThreads));
+    return {dim3((unsigned)qblocks, (unsigned)slices), dim3((unsigned)((nq + kThreads - 1) / kThreads)), slice};
+}
+
+// k_rank_true, the sweep and (L2 kinds) the square root for one table and one list of queries.
+static void rank_sweep(stx_ctx *c, const RankArgs &a, const RankShape &sh, bool transh, int side)
+{
+    const dim3 grid = sh.grid, qgrid = sh.qgrid;
 #define STX_RANK_GO(KT, KS, D, H)                                                                               \
     do {                                                                                                        \
         hipLaunchKernelGGL((KT<D, H>), qgrid, dim3(kThreads), 0, c->stream, a);                                 \
@@ -427,7 +590,7 @@ stx_status launch_rank(stx_ctx *c, const stx_params *p, const int32_t *h, const 
         if (transh) { if (side) STX_RANK_GO(k_rank_true_h, k_rank_h, D, true); else STX_RANK_GO(k_rank_true_h, k_rank_h, D, false); } \
         else        { if (side) STX_RANK_GO(k_rank_true, k_rank, D, true); else STX_RANK_GO(k_rank_true, k_rank, D, false); }         \
         if (D == STX_L2 || D == STX_TORUS_L2)                                                                   \
-            hipLaunchKernelGGL((k_rank_finish<D>), qgrid, dim3(kThreads), 0, c->stream, true_score, nq);        \
+            hipLaunchKernelGGL((k_rank_finish<D>), qgrid, dim3(kThreads), 0, c->stream, a.true_score, a.nq);    \
     } while (0)
     switch (c->cfg.dist) {
     case STX_L1: STX_RANK(STX_L1); break;
@@ -438,6 +601,58 @@ stx_status launch_rank(stx_ctx *c, const stx_params *p, const int32_t *h, const 
     }
 #undef STX_RANK
 #undef STX_RANK_GO
+}
+
+stx_status launch_rank(stx_ctx *c, const stx_params *p, const int32_t *h, const int32_t *r, const int32_t *t,
+                       int64_t nq, int side, float *true_score, int32_t *n_less, int32_t *n_equal, void *work)
+{
+    if (nq == 0) return STX_OK;
+    const int32_t n_ent = (int32_t)c->cfg.n_ent, n_rel = (int32_t)c->cfg.n_rel;
+    int32_t *bad = c->ctrl + CTRL_BAD_INDEX;
+    if (c->cfg.model != STX_TRANSR) {
+        const bool transh = c->cfg.model == STX_TRANSH;
+        const RankShape sh = rank_shape(nq, n_ent, transh ? 4 : 2);   // TransH workgroups start with a dot product per query
+        const RankArgs a{p->ent, transh ? p->rel : nullptr, transh ? p->w : nullptr, h, r, t, nq, n_ent, n_rel, c->cfg.dim,
+                         sh.slice, true_score, n_less, n_equal, bad};
+        rank_sweep(c, a, sh, transh, side);
+        return hip_ok(hipGetLastError());
+    }
+    // TransR: group the queries by relation, learn the group sizes (the one wait of this call), then one
+    // projected table and one sweep per relation that occurs
+    const RankRWork w = rank_r_work(c->cfg, nq, work);
+    const int dim = c->cfg.dim, k = c->cfg.rel_dim;
+    const dim3 rgrid((unsigned)((n_rel + kThreads - 1) / kThreads)), qgrid((unsigned)((nq + kThreads - 1) / kThreads));
+    hipLaunchKernelGGL(k_rr_clear, rgrid, dim3(kThreads), 0, c->stream, w.counts, w.cursor, n_rel);
+    hipLaunchKernelGGL(k_rr_hist, qgrid, dim3(kThreads), 0, c->stream, h, r, t, nq, n_ent, n_rel, w.counts, bad);
+    hipLaunchKernelGGL(k_rr_scan, dim3(1), dim3(kThreads), 0, c->stream, w.counts, w.offsets, n_rel);
+    hipLaunchKernelGGL(k_rr_scatter, qgrid, dim3(kThreads), 0, c->stream, h, r, t, nq, n_ent, n_rel, w.offsets, w.cursor,
+                       w.perm, w.gh, w.gt);
+    int32_t *counts = new (std::nothrow) int32_t[(size_t)n_rel];
+    if (!counts) return STX_ERR_BAD_ARG;
+    if (hipMemcpyAsync(counts, w.counts, (size_t)n_rel * 4, hipMemcpyDeviceToHost, c->stream) != hipSuccess ||
+        hipStreamSynchronize(c->stream) != hipSuccess) {
+        delete[] counts;
+        return STX_ERR_HIP;
+    }
+    const dim3 pgrid((unsigned)((n_ent + kRankE - 1) / kRankE), (unsigned)((k + kRankQ - 1) / kRankQ));
+    int64_t off = 0;
+    for (int32_t rr = 0; rr < n_rel; ++rr) {
+        const int64_t n = counts[rr];
+        if (n <= 0) continue;
+        {
+            ProfScope prof(c, "k_rr_project");
+            hipLaunchKernelGGL(k_rr_project, pgrid, dim3(kThreads), 0, c->stream, p->ent, p->proj + (int64_t)rr * k * dim,
+                               p->rel + (int64_t)rr * k, n_ent, dim, k, w.table);
+        }
+        const RankShape sh = rank_shape(n, n_ent, 2);
+        const RankArgs a{w.table, nullptr, nullptr, w.gh + off, nullptr, w.gt + off, n, n_ent, 1, k, sh.slice, w.gts + off,
+                         w.gless + off, w.gequal + off, bad};
+        rank_sweep(c, a, sh, false, side);
+        off += n;
+    }
+    delete[] counts;
+    hipLaunchKernelGGL(k_rr_unpermute, qgrid, dim3(kThreads), 0, c->stream, w.perm, w.gts, w.gless, w.gequal, nq,
+                       true_score, n_less, n_equal);
     return hip_ok(hipGetLastError());
 }
 

@@ -28,15 +28,22 @@ def band_tol(dim):
 
 def run_rank(wl, X, h, r, t, side, max_batch=8):
     """X: the stacked table of TransE / TorusE, or the dict of TransH's tables."""
-    cfg = B.make_config(wl.model, wl.dist, wl.n_ent, wl.n_rel, wl.dim, max_batch, 1, margin=wl.margin)
+    flags = B.STX_FLAG_BF16_PROJ if wl.model == "transr" else 0
+    cfg = B.make_config(wl.model, wl.dist, wl.n_ent, wl.n_rel, wl.dim, max_batch, 1, rel_dim=wl.rel_dim, margin=wl.margin,
+                        flags=flags)
     ctx = B.Context(cfg, G.DEV)
-    p = (B.Params(G.dev_f32(X["ent"]), G.dev_f32(X["rel"]), G.dev_f32(X["w"])) if isinstance(X, dict)
-         else B.Params(G.dev_f32(X)))
+    if isinstance(X, dict):
+        p = B.Params(*(None if X.get(k) is None else G.dev_f32(X[k]) for k in ("ent", "rel", "w", "proj")))
+    else:
+        p = B.Params(G.dev_f32(X))
+    need = B.stx_rank_work_bytes(ctx, len(h))
+    assert (need > 0) == (wl.model == "transr")
+    work = torch.empty(need + 256, dtype=torch.uint8, device=G.DEV) if need else None
     nq = len(h)
     ts = torch.full((max(nq, 1),), float("nan"), dtype=torch.float32, device=G.DEV)
     less = torch.full((max(nq, 1),), -7, dtype=torch.int32, device=G.DEV)
     equal = torch.full((max(nq, 1),), -7, dtype=torch.int32, device=G.DEV)
-    B.stx_rank(ctx, p, G.dev_i32(h), G.dev_i32(r), G.dev_i32(t), side, ts, less, equal)
+    B.stx_rank(ctx, p, G.dev_i32(h), G.dev_i32(r), G.dev_i32(t), side, ts, less, equal, work)
     torch.cuda.synchronize()
     return ctx, ts.cpu().numpy()[:nq], less.cpu().numpy()[:nq], equal.cpu().numpy()[:nq]
 
@@ -255,12 +262,106 @@ def test_rank_transh_full_size():
         check_counts(ts[pick], less[pick], equal[pick], ref, 4 * tol)
 
 
-def test_rank_transr_is_not_supported():
-    wl = W.Workload("case", 7, "transr", "l2", 50, 3, 8, 32, 32, 8, 1, 1.0, 0.01, 1, 0.0, 0.0, True)
-    m = G.GpuModel(wl, W.make_tables(wl), flags=B.STX_FLAG_BF16_PROJ)
+# ------------------------------------------------------------------------------------------ TransR
+def transr_abs_tol(tabs, h, r, t, side, dim):
+    """The kernel projects the query's entity and every candidate separately (p_v = M_r v, fp32 sums of dim
+    products) and subtracts; the oracle projects the difference.  The rounding of the two projections,
+    (dim + 1) 2^-24 times the magnitudes summed, is what the oracle's band does not cover."""
+    E = np.abs(tabs["ent"].astype(np.float64))
+    out = np.empty(len(h))
+    cache = {}
+    for i in range(len(h)):
+        if r[i] not in cache:
+            cache[r[i]] = (E @ np.abs(tabs["proj"][r[i]].astype(np.float64)).T).sum(1)    # sum_a sum_j |M_aj| |e_j| per entity
+        mag = cache[r[i]]
+        out[i] = 2.0 * (dim + 1) * 2.0**-24 * (mag[h[i] if side == B.STX_TAIL else t[i]] + mag.max())
+    return out
+
+
+def _wl_r(dist, n_ent, n_rel, dim, rel_dim):
+    return W.Workload("case", 7, "transr", dist, n_ent, n_rel, 1, dim, rel_dim, 1, 1, 1.0, 0.01, 1, 0.0, 0.0, True)
+
+
+R_CASES = [
+    # dist, n_ent, n_rel, dim, rel_dim, nq
+    ("l1", 10, 2, 32, 32, 1),
+    ("l2", 300, 7, 64, 32, 200),                  # several relations, ragged tiles
+    ("l1", 1000, 20, 128, 128, 129),
+    ("l2_sq", 515, 3, 32, 96, 300),               # groups larger than a query block
+    ("l2", 257, 40, 32, 256, 90),                 # two output tiles per projected row; most relations have few queries
+]
+
+
+@pytest.mark.parametrize("dist,n_ent,n_rel,dim,rel_dim,nq", R_CASES)
+@pytest.mark.parametrize("side,oside", SIDES)
+def test_rank_transr_counts_within_the_oracle_band(side, oside, dist, n_ent, n_rel, dim, rel_dim, nq):
+    wl = _wl_r(dist, n_ent, n_rel, dim, rel_dim)
+    tabs = W.make_tables(wl)
+    rng = np.random.default_rng(n_ent + dim + side + 2)
+    h, t = rng.integers(0, n_ent, nq).astype(np.int32), rng.integers(0, n_ent, nq).astype(np.int32)
+    r = rng.integers(0, n_rel, nq).astype(np.int32)
+    ctx, ts, less, equal = run_rank(wl, tabs, h, r, t, side)
+    tol = max(G.REL_TOL, (rel_dim + dim + 8) * 2.0**-24)
+    extra = transr_abs_tol(tabs, h, r, t, side, dim) * (8.0 * np.abs(tabs["ent"]).max() * dim**0.5 if dist == "l2_sq" else 1.0)
+    ot = stxo.Tables(tabs["ent"], tabs["rel"], None, tabs["proj"])
+    ref = stxo.rank(oracle_config(wl, bf16=False), ot, h, r, t, oside, tol=tol, abs_tol=extra)
+    check_counts(ts, less, equal, ref, 4 * tol)
+    assert B.stx_check_indices(ctx) == 0
+
+
+@pytest.mark.parametrize("side,oside", SIDES)
+def test_rank_transr_counts_exact_on_exactly_summable_tables(side, oside):
+    n_ent, n_rel, dim, rel_dim, nq = 400, 5, 32, 32, 300
+    wl = _wl_r("l1", n_ent, n_rel, dim, rel_dim)
+    rng = np.random.default_rng(29 + side)
+    tabs = {"ent": (rng.integers(-2, 3, (n_ent, dim)) / 2.0).astype(np.float32),
+            "rel": (rng.integers(-4, 4, (n_rel, rel_dim)) / 2.0).astype(np.float32),
+            "proj": rng.integers(-1, 2, (n_rel, rel_dim, dim)).astype(np.float32)}
+    tabs["ent"][:, 3:] = 0                                     # few distinct rows: many exact ties
+    tabs["ent"][n_ent // 2:] = tabs["ent"][:n_ent - n_ent // 2]
+    h, t = rng.integers(0, n_ent, nq).astype(np.int32), rng.integers(0, n_ent, nq).astype(np.int32)
+    r = rng.integers(0, n_rel, nq).astype(np.int32)
+    ctx, ts, less, equal = run_rank(wl, tabs, h, r, t, side)
+    ref_ts, ref_less, ref_band = stxo.rank(oracle_config(wl, bf16=False), stxo.Tables(tabs["ent"], tabs["rel"], None, tabs["proj"]),
+                                           h, r, t, oside, tol=0.0)
+    assert ref_band.min() > 1
+    assert np.array_equal(less, ref_less) and np.array_equal(equal, ref_band)
+    assert np.array_equal(ts.astype(np.float64), ref_ts)
+    # the same queries again with out-of-range indices in between: clamped, counted, the rest unchanged
+    h2, r2 = h.copy(), r.copy()
+    h2[7], r2[11] = n_ent + 5, -3
+    ctx, ts2, less2, equal2 = run_rank(wl, tabs, h2, r2, t, side)
+    assert B.stx_check_indices(ctx) == 2
+    keep = np.ones(nq, bool)
+    keep[[7, 11]] = False
+    assert np.array_equal(less2[keep], less[keep]) and np.array_equal(equal2[keep], equal[keep])
+
+
+def test_rank_transr_full_size_and_workspace_errors():
+    """The "transr" benchmark tables (14,500 entities, 237 relations, d = k = 128) against 20,466 test triplets,
+    the size of FB15k-237's test split, which the seeded draw stands in for."""
+    wl = W.WORKLOADS["transr"]
+    tabs = W.make_tables(wl)
+    nq = 20_466
+    h, r, t = W.make_test_triplets(wl, nq)
+    pick = np.sort(np.random.default_rng(7).choice(nq, 6, replace=False))
+    tol = max(G.REL_TOL, (wl.rel_dim + wl.dim + 8) * 2.0**-24)
+    ot = stxo.Tables(tabs["ent"], tabs["rel"], None, tabs["proj"])
+    for side, oside in SIDES:
+        _, ts, less, equal = run_rank(wl, tabs, h, r, t, side)
+        assert np.all(np.isfinite(ts)) and np.all(equal >= 1) and np.all(less.astype(np.int64) + equal <= wl.n_ent)
+        extra = transr_abs_tol(tabs, h[pick], r[pick], t[pick], side, wl.dim)
+        ref = stxo.rank(oracle_config(wl, bf16=False), ot, h[pick], r[pick], t[pick], oside, tol=tol, abs_tol=extra)
+        check_counts(ts[pick], less[pick], equal[pick], ref, 4 * tol)
+    # a missing or short work buffer is refused before anything is launched
+    m = G.GpuModel(_wl_r("l2", 50, 3, 32, 32), W.make_tables(_wl_r("l2", 50, 3, 32, 32)), flags=B.STX_FLAG_BF16_PROJ)
     z = G.dev_i32(np.zeros(3, np.int32))
     out = torch.zeros(4, dtype=torch.float32, device=G.DEV)
     cnt = torch.zeros(4, dtype=torch.int32, device=G.DEV)
     with pytest.raises(B.StxError) as err:
         B.stx_rank(m.ctx, m.params, z, z, z, B.STX_TAIL, out, cnt, cnt.clone())
-    assert err.value.status == B.STX_ERR_UNSUPPORTED
+    assert err.value.status == B.STX_ERR_NULL
+    with pytest.raises(B.StxError) as err:
+        B.stx_rank(m.ctx, m.params, z, z, z, B.STX_TAIL, out, cnt, cnt.clone(),
+                   torch.empty(512, dtype=torch.uint8, device=G.DEV))
+    assert err.value.status == B.STX_ERR_WORKSPACE
