@@ -77,7 +77,8 @@ def parse():
     ap.add_argument("--rank", action="store_true",
                     help="instead of the training step, time link prediction (stx_rank, tail and head side) of "
                          "--rank-queries test triplets against all entities of the workload's table")
-    ap.add_argument("--rank-queries", type=int, default=59_071, help="test triplets (default: FB15k's test split size)")
+    ap.add_argument("--rank-queries", type=int, default=0,
+                    help="test triplets (default: 59,071, the size of FB15k's test split; 20,466, FB15k-237's, for TransR)")
     ap.add_argument("--semiring", default=None, choices=["distmult", "complex", "rotate"],
                     help="instead of the training step, time the semiring product of that model and its backward "
                          "(stx_spmm_semiring + stx_spmm_semiring_t) on the first batch of the workload's graph")
@@ -175,16 +176,16 @@ def bench_rank(args, wl, dev):
 
     from paper_2502_16949_amd import binding as B
     from paper_2502_16949_amd import workloads as W
-    nq = args.rank_queries
+    nq = args.rank_queries or (20_466 if wl.model == "transr" else W.N_TEST_FB15K)
     h, r, t = W.make_test_triplets(wl, nq)
     tabs = W.make_tables(wl)
-    cfg = B.make_config(wl.model, wl.dist, wl.n_ent, wl.n_rel, wl.dim, 8, 1, margin=wl.margin)
+    transh, transr = wl.model == "transh", wl.model == "transr"
+    cfg = B.make_config(wl.model, wl.dist, wl.n_ent, wl.n_rel, wl.dim, 8, 1, rel_dim=wl.rel_dim, margin=wl.margin,
+                        flags=B.STX_FLAG_BF16_PROJ if transr else 0)
     ctx = B.Context(cfg, dev)
-    transh = wl.model == "transh"
-    if wl.model == "transr":
-        print("bench.py --rank: TransR is not supported by stx_rank", file=sys.stderr)
-        sys.exit(2)
-    params = B.Params(*(torch.from_numpy(tabs[k]).to(dev) for k in (("ent", "rel", "w") if transh else ("ent",))))
+    params = B.Params(*(None if tabs.get(k) is None else torch.from_numpy(tabs[k]).to(dev) for k in ("ent", "rel", "w", "proj")))
+    need = B.stx_rank_work_bytes(ctx, nq)
+    work = torch.empty(need + 256, dtype=torch.uint8, device=dev) if need else None
     rank_kernel = "k_rank_h" if transh else "k_rank"
     hd, rd, td = (torch.from_numpy(a).to(dev) for a in (h, r, t))
     ts = torch.empty(2, nq, dtype=torch.float32, device=dev)
@@ -192,13 +193,13 @@ def bench_rank(args, wl, dev):
     equal = torch.empty(2, nq, dtype=torch.int32, device=dev)
 
     def step():
-        B.stx_rank(ctx, params, hd, rd, td, B.STX_TAIL, ts[0], less[0], equal[0])
-        B.stx_rank(ctx, params, hd, rd, td, B.STX_HEAD, ts[1], less[1], equal[1])
+        B.stx_rank(ctx, params, hd, rd, td, B.STX_TAIL, ts[0], less[0], equal[0], work)
+        B.stx_rank(ctx, params, hd, rd, td, B.STX_HEAD, ts[1], less[1], equal[1], work)
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    B.stx_profile_kernel(ctx, rank_kernel, 2 * args.steps)
+    B.stx_profile_kernel(ctx, rank_kernel, 2 * args.steps * (wl.n_rel if transr else 1))
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
@@ -206,8 +207,11 @@ def bench_rank(args, wl, dev):
     dt = time.perf_counter() - t0
     kernel_us, kernel_n = B.stx_profile_read(ctx)
     ops, flops = (RANK_OPS_H if transh else RANK_OPS)[wl.dist]
-    elems = float(nq) * wl.n_ent * wl.dim                     # per launch (one side)
-    achieved = elems * flops / (kernel_us * 1e-6) / 1e12 if kernel_us > 0 else 0.0
+    # per side; TransR sweeps rows of rel_dim projected values in one launch per relation: the launches of a
+    # side are priced together (mean launch time x launches per side)
+    elems = float(nq) * wl.n_ent * (wl.rel_dim if transr else wl.dim)
+    side_us = kernel_us * kernel_n / (2 * args.steps) if args.steps else 0.0
+    achieved = elems * flops / (side_us * 1e-6) / 1e12 if side_us > 0 else 0.0
     peak = VALU_OPS_PEAK_T * flops / ops
     best = 1 + less.cpu().numpy().astype(np.int64)
     out = {"metric": f"link prediction, test triplets ranked/sec (tail and head, all {wl.n_ent} entities) {wl.model} "
@@ -216,7 +220,8 @@ def bench_rank(args, wl, dev):
            "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 4), "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": f"{wl.name} tables ({wl.n_ent} entities, {wl.n_rel} relations, dim {wl.dim}, {wl.dist}), "
-                                  f"{nq} test triplets (the size of FB15k's test split) from the graph's degree laws",
+                                  f"{nq} test triplets (the size of the test split of FB15k{'-237' if transr else ''}) from the "
+                                  "graph's degree laws",
                       "step": "stx_rank tail side + stx_rank head side over all test triplets"},
            "hits_at_10_raw": round(float((best <= 10).mean()), 4),
            "roofline": {"bound": "alu", "kernel": rank_kernel, "achieved": round(achieved, 2), "peak": round(peak, 1),
@@ -229,8 +234,10 @@ def bench_rank(args, wl, dev):
         from oracle import stxo
         from tests.util import oracle_config
         ocfg = oracle_config(wl)
-        otab = stxo.Tables(tabs["ent"], tabs.get("rel"), tabs.get("w"))
-        n = 8
+        otab = stxo.Tables(tabs["ent"], tabs.get("rel"), tabs.get("w"), tabs.get("proj"))
+        if transr:
+            ocfg = oracle_config(wl, bf16=False)
+        n = 2 if transr else 8
         while True:
             t0 = time.perf_counter()
             stxo.rank(ocfg, otab, h[:n], r[:n], t[:n], stxo.TAIL)

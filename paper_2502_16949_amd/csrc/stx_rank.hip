@@ -46,7 +46,28 @@ struct RankArgs {
     float *true_score;                 // [nq]: the true entity's sum until k_rank_finish
     int32_t *n_less, *n_equal;         // [nq], cleared by k_rank_true
     int32_t *bad;                      // counter of out-of-range indices
+    // TransR: blockIdx.z walks the relations grp_first, grp_first + 1, ...; relation g owns the grouped queries
+    // [grp_offsets[g], + grp_counts[g]) (h, t and the outputs are grouped arrays) and table number blockIdx.z.
+    // With several relations per launch, those with more than grp_big queries are left to a launch of their own.
+    const int32_t *grp_counts, *grp_offsets;
+    int32_t grp_first, grp_big;
+    int64_t table_stride;              // floats between the tables of consecutive blockIdx.z
 };
+
+// Narrows the arguments to the relation of this workgroup; false: nothing to do.
+__device__ inline bool rank_group(RankArgs &a)
+{
+    if (!a.grp_counts) return true;
+    const int32_t g = a.grp_first + (int32_t)blockIdx.z;
+    const int32_t n = a.grp_counts[g];
+    if (n == 0 || (gridDim.z > 1 && n > a.grp_big)) return false;
+    const int64_t off = a.grp_offsets[g];
+    a.X += (int64_t)blockIdx.z * a.table_stride;
+    a.h += off; a.t += off;
+    a.true_score += off; a.n_less += off; a.n_equal += off;
+    a.nq = n;
+    return true;
+}
 
 // The 8 x 8 block of a thread: query u is block row (u < 4 ? 0 : 64) + 4 ty + (u & 3) of the workgroup's 128,
 // candidate v is (v < 4 ? 0 : 64) + 4 tx + (v & 3) of the tile's 128.
@@ -104,6 +125,7 @@ __device__ inline RankRows rank_rows(const RankArgs &a, int64_t qi)
 template <int DIST, bool HEAD>
 __global__ __launch_bounds__(kThreads) void k_rank_true(RankArgs a)
 {
+    if (!rank_group(a)) return;
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i >= a.nq) return;
     const RankRows rw = rank_rows<HEAD>(a, i);
@@ -138,9 +160,11 @@ __global__ __launch_bounds__(kThreads, 3) void k_rank(RankArgs a)
     __shared__ __attribute__((aligned(16))) float s_q[kRankJ][kRankLd];
     __shared__ __attribute__((aligned(16))) float s_e[kRankJ][kRankLd];
 
+    if (!rank_group(a)) return;                           // (uniform over the workgroup)
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;               // candidate / query position of the 8 x 8 block
     const int64_t q0 = (int64_t)blockIdx.x * kRankQ;
+    if (q0 >= a.nq) return;
     const int dim = a.dim;
 
     // The query this thread stages; past the end the last query is repeated and its counts are not stored.
@@ -404,15 +428,19 @@ __global__ __launch_bounds__(kThreads, 2) void k_rank_h(RankArgs a)
 // p_e = M_r e, and the score of e as tail of (h, r, .) is dist((p_h + r) - p_e), as head of (., r, t)
 // dist(p_e - (p_t - r)): the TransE sweep over the table [P_r; r] with a single relation.  Queries are
 // grouped by relation (counting sort), and for every relation that occurs its projected table is built
-// (k_rr_project, a plain fp32 product with sums in index order) and swept by k_rank_true / k_rank.
+// (k_rr_project, a plain fp32 product with sums in index order) and swept by k_rank_true / k_rank.  Relations
+// with many queries get launches of their own; the many relations with few queries are taken several per
+// launch (blockIdx.z), each with its own table, so that their small sweeps fill the chip together.
 struct RankRWork {                      // partitions of the caller's work buffer
     int32_t *counts, *cursor, *offsets; // [n_rel], [n_rel], [n_rel + 1]
     int32_t *perm, *gh, *gt;            // [nq]: query at each grouped position, its clamped head and tail
     float *gts;                         // [nq] grouped outputs
     int32_t *gless, *gequal;
-    float *table;                       // (n_ent + 1) x rel_dim: P_r, then r
+    float *table;                       // n_tables tables of (n_ent + 1) x rel_dim: P_r, then r
+    int n_tables;
     size_t total;
 };
+constexpr int kRankBig = 1024;          // relations with more queries than this get a launch of their own
 static RankRWork rank_r_work(const stx_config &cfg, int64_t nq, void *base)
 {
     size_t off = 0;
@@ -427,7 +455,12 @@ static RankRWork rank_r_work(const stx_config &cfg, int64_t nq, void *base)
     w.gts = (float *)take((size_t)nq * 4);
     w.gless = (int32_t *)take((size_t)nq * 4);
     w.gequal = (int32_t *)take((size_t)nq * 4);
-    w.table = (float *)take((size_t)(cfg.n_ent + 1) * cfg.rel_dim * 4);
+    // relations with few queries are swept several per launch, each with a table of its own: up to 32, within 256 MiB
+    const size_t table_bytes = (size_t)(cfg.n_ent + 1) * cfg.rel_dim * 4;
+    const size_t fit = ((size_t)256 << 20) / table_bytes;
+    w.n_tables = (int)(fit < 1 ? 1 : (fit > 32 ? 32 : fit));
+    if (w.n_tables > cfg.n_rel) w.n_tables = (int)cfg.n_rel;
+    w.table = (float *)take(table_bytes * w.n_tables);
     w.total = off;
     return w;
 }
@@ -496,10 +529,19 @@ __global__ __launch_bounds__(kThreads) void k_rr_unpermute(const int32_t *perm, 
 
 // T[e][a] = sum_j E[e][j] M[a][j] (index order, fused multiply-adds) for e < n_ent, a < k; T[n_ent][a] = rvec[a].
 // Tiled like the sweep: 128 entities x 128 outputs per workgroup, 8 x 8 per thread.
+// blockIdx.z walks the relations first, first + 1, ... as in the sweep (M, rvec: the whole tables).
 __global__ __launch_bounds__(kThreads, 3) void k_rr_project(const float *__restrict__ E, const float *__restrict__ M,
                                                             const float *__restrict__ rvec, int32_t n_ent, int dim, int k,
-                                                            float *__restrict__ T)
+                                                            float *__restrict__ T, const int32_t *__restrict__ counts,
+                                                            int32_t first, int32_t big, int64_t table_stride)
 {
+    {
+        const int32_t g = first + (int32_t)blockIdx.z, n = counts[g];
+        if (n == 0 || (gridDim.z > 1 && n > big)) return;
+        M += (int64_t)g * k * dim;
+        rvec += (int64_t)g * k;
+        T += (int64_t)blockIdx.z * table_stride;
+    }
     __shared__ __attribute__((aligned(16))) float s_m[kRankJ][kRankLd];
     __shared__ __attribute__((aligned(16))) float s_e[kRankJ][kRankLd];
     const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
@@ -576,9 +618,10 @@ static RankShape rank_shape(int64_t nq, int32_t n_ent, int64_t min_tiles)
 }
 
 // k_rank_true, the sweep and (L2 kinds) the square root for one table and one list of queries.
-static void rank_sweep(stx_ctx *c, const RankArgs &a, const RankShape &sh, bool transh, int side)
+static void rank_sweep(stx_ctx *c, const RankArgs &a, const RankShape &sh, bool transh, int side, int nz = 1,
+                       bool finish = true)
 {
-    const dim3 grid = sh.grid, qgrid = sh.qgrid;
+    const dim3 grid(sh.grid.x, sh.grid.y, (unsigned)nz), qgrid(sh.qgrid.x, 1, (unsigned)nz);
 #define STX_RANK_GO(KT, KS, D, H)                                                                               \
     do {                                                                                                        \
         hipLaunchKernelGGL((KT<D, H>), qgrid, dim3(kThreads), 0, c->stream, a);                                 \
@@ -589,7 +632,7 @@ static void rank_sweep(stx_ctx *c, const RankArgs &a, const RankShape &sh, bool 
     do {                                                                                                        \
         if (transh) { if (side) STX_RANK_GO(k_rank_true_h, k_rank_h, D, true); else STX_RANK_GO(k_rank_true_h, k_rank_h, D, false); } \
         else        { if (side) STX_RANK_GO(k_rank_true, k_rank, D, true); else STX_RANK_GO(k_rank_true, k_rank, D, false); }         \
-        if (D == STX_L2 || D == STX_TORUS_L2)                                                                   \
+        if (finish && (D == STX_L2 || D == STX_TORUS_L2))                                                       \
             hipLaunchKernelGGL((k_rank_finish<D>), qgrid, dim3(kThreads), 0, c->stream, a.true_score, a.nq);    \
     } while (0)
     switch (c->cfg.dist) {
@@ -613,7 +656,7 @@ stx_status launch_rank(stx_ctx *c, const stx_params *p, const int32_t *h, const 
         const bool transh = c->cfg.model == STX_TRANSH;
         const RankShape sh = rank_shape(nq, n_ent, transh ? 4 : 2);   // TransH workgroups start with a dot product per query
         const RankArgs a{p->ent, transh ? p->rel : nullptr, transh ? p->w : nullptr, h, r, t, nq, n_ent, n_rel, c->cfg.dim,
-                         sh.slice, true_score, n_less, n_equal, bad};
+                         sh.slice, true_score, n_less, n_equal, bad, nullptr, nullptr, 0, 0, 0};
         rank_sweep(c, a, sh, transh, side);
         return hip_ok(hipGetLastError());
     }
@@ -634,22 +677,32 @@ stx_status launch_rank(stx_ctx *c, const stx_params *p, const int32_t *h, const 
         delete[] counts;
         return STX_ERR_HIP;
     }
-    const dim3 pgrid((unsigned)((n_ent + kRankE - 1) / kRankE), (unsigned)((k + kRankQ - 1) / kRankQ));
-    int64_t off = 0;
-    for (int32_t rr = 0; rr < n_rel; ++rr) {
-        const int64_t n = counts[rr];
-        if (n <= 0) continue;
+    const int64_t stride = (int64_t)(n_ent + 1) * k;
+    // relations first, first + 1, ... first + nz - 1 in one set of launches; max_n: the largest group among them
+    auto sweep = [&](int32_t first, int nz, int64_t max_n, int32_t big) {
+        const dim3 pgrid((unsigned)((n_ent + kRankE - 1) / kRankE), (unsigned)((k + kRankQ - 1) / kRankQ), (unsigned)nz);
         {
             ProfScope prof(c, "k_rr_project");
-            hipLaunchKernelGGL(k_rr_project, pgrid, dim3(kThreads), 0, c->stream, p->ent, p->proj + (int64_t)rr * k * dim,
-                               p->rel + (int64_t)rr * k, n_ent, dim, k, w.table);
+            hipLaunchKernelGGL(k_rr_project, pgrid, dim3(kThreads), 0, c->stream, p->ent, p->proj, p->rel, n_ent, dim, k,
+                               w.table, w.counts, first, big, stride);
         }
-        const RankShape sh = rank_shape(n, n_ent, 2);
-        const RankArgs a{w.table, nullptr, nullptr, w.gh + off, nullptr, w.gt + off, n, n_ent, 1, k, sh.slice, w.gts + off,
-                         w.gless + off, w.gequal + off, bad};
-        rank_sweep(c, a, sh, false, side);
-        off += n;
+        const RankShape sh = rank_shape(max_n, n_ent, 2);
+        const RankArgs a{w.table, nullptr, nullptr, w.gh, nullptr, w.gt, max_n, n_ent, 1, k, sh.slice, w.gts, w.gless,
+                         w.gequal, bad, w.counts, w.offsets, first, big, stride};
+        rank_sweep(c, a, sh, false, side, nz, false);
+    };
+    for (int32_t rr = 0; rr < n_rel; ++rr)
+        if (counts[rr] > kRankBig) sweep(rr, 1, counts[rr], 0x7fffffff);
+    for (int32_t r0 = 0; r0 < n_rel; r0 += w.n_tables) {
+        const int nz = n_rel - r0 < w.n_tables ? n_rel - r0 : w.n_tables;
+        int64_t max_n = 0;
+        for (int z = 0; z < nz; ++z)
+            if (counts[r0 + z] <= kRankBig && counts[r0 + z] > max_n) max_n = counts[r0 + z];
+        if (max_n > 0) sweep(r0, nz, max_n, nz > 1 ? kRankBig : 0x7fffffff);
     }
+    if (c->cfg.dist == STX_L2) hipLaunchKernelGGL((k_rank_finish<STX_L2>), qgrid, dim3(kThreads), 0, c->stream, w.gts, nq);
+    if (c->cfg.dist == STX_TORUS_L2)
+        hipLaunchKernelGGL((k_rank_finish<STX_TORUS_L2>), qgrid, dim3(kThreads), 0, c->stream, w.gts, nq);
     delete[] counts;
     hipLaunchKernelGGL(k_rr_unpermute, qgrid, dim3(kThreads), 0, c->stream, w.perm, w.gts, w.gless, w.gequal, nq,
                        true_score, n_less, n_equal);
