@@ -117,6 +117,23 @@ def make_test_triplets(wl: Workload, n: int = N_TEST_FB15K):
     return h, r, t
 
 
+def make_shift_graph(n_ent: int, shifts, seed: int, ring: bool, test_share: float = 0.1):
+    """A graph with structure a translation model can learn: entities are the positions 0..n_ent-1 of a line
+    (or of a ring), relation i joins every position h to h + shifts[i] where that exists (modulo n_ent on the
+    ring).  Returns ((h, r, t) for training, (h, r, t) held out), shuffled with the given seed."""
+    hs, rs, ts = [], [], []
+    for ri, sft in enumerate(shifts):
+        for hh in range(n_ent):
+            tt = (hh + sft) % n_ent if ring else hh + sft
+            if 0 <= tt < n_ent:
+                hs.append(hh); rs.append(ri); ts.append(tt)
+    h, r, t = (np.array(a, np.int32) for a in (hs, rs, ts))
+    p = np.random.Generator(np.random.PCG64(seed)).permutation(len(h))
+    h, r, t = h[p], r[p], t[p]
+    n_test = int(len(h) * test_share)
+    return (h[n_test:], r[n_test:], t[n_test:]), (h[:n_test], r[:n_test], t[:n_test])
+
+
 def make_tables(wl: Workload):
     """Initial parameter tables as a dict of fp32 arrays.  Seed = 2000 + index.
 

@@ -1,0 +1,54 @@
+"""End to end on the GPU: the schedule of tests/test_learns.py through stx_train_step and stx_rank.  The GPU
+run must learn the shift graph as the oracle does (same batches, same negatives; the two trajectories part in
+the last bits and stay statistically alike) and must be bitwise reproducible."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_16949_amd import binding as B
+from paper_2502_16949_amd import workloads as W
+from tests import gpu_util as G
+from tests.test_learns import CASES, hits_at_10, learn_setup, oracle_learn
+
+pytestmark = pytest.mark.gpu
+
+
+def gpu_learn(name):
+    wl, (h, r, t), (th, tr, tt), _ = learn_setup(name)
+    m = G.GpuModel(wl, W.make_tables(wl))
+    hd, rd, td = G.dev_i32(h), G.dev_i32(r), G.dev_i32(t)
+    nh = torch.empty(wl.batch, dtype=torch.int32, device=G.DEV)
+    nt = torch.empty_like(nh)
+    losses = []
+    for ep in range(wl.epochs):
+        total = torch.zeros(1, dtype=torch.float32, device=G.DEV)
+        for lo in range(0, len(h), wl.batch):
+            hi = min(lo + wl.batch, len(h))
+            batch = B.make_batch(hd[lo:hi], rd[lo:hi], td[lo:hi], 1, W.negative_seed(wl), ep, len(h), lo, nh, nt)
+            B.stx_train_step(m.ctx, batch, m.inc, m.params, None, wl.lr, m.scores, m.loss)
+            total += m.loss
+        losses.append(float(total.item()))
+    nq = len(th)
+    ts = torch.empty(nq, dtype=torch.float32, device=G.DEV)
+    less = torch.empty(nq, dtype=torch.int32, device=G.DEV)
+    equal = torch.empty_like(less)
+    hits = []
+    for side in (B.STX_TAIL, B.STX_HEAD):
+        B.stx_rank(m.ctx, m.params, G.dev_i32(th), G.dev_i32(tr), G.dev_i32(tt), side, ts, less, equal)
+        torch.cuda.synchronize()
+        hits.append(hits_at_10(less.cpu().numpy()))
+    return losses, hits, m.params.ent.cpu().numpy()
+
+
+@pytest.mark.parametrize("name", sorted(CASES))
+def test_gpu_training_learns_the_shift_graph(name):
+    losses, hits, table = gpu_learn(name)
+    ref_losses, ref_hits, bar = oracle_learn(name)
+    assert losses[-1] < 0.2 * losses[0]
+    assert min(hits) >= bar, hits
+    assert max(abs(a - b) for a, b in zip(hits, ref_hits)) <= 0.15, (hits, ref_hits)
+    # the first epoch follows the oracle closely (the trajectories have had no time to part)
+    assert abs(losses[0] - ref_losses[0]) <= 1e-4 * ref_losses[0]
+    # the whole run again: same bits
+    losses2, hits2, table2 = gpu_learn(name)
+    assert losses2 == losses and hits2 == hits and np.array_equal(table.view(np.uint32), table2.view(np.uint32))
