@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 
 def gpu_learn(name):
     wl, (h, r, t), (th, tr, tt), _ = learn_setup(name)
-    m = G.GpuModel(wl, W.make_tables(wl))
+    m = G.GpuModel(wl, W.make_tables(wl), flags={"transh": B.STX_FLAG_RENORM_W, "transr": B.STX_FLAG_BF16_PROJ}.get(wl.model, 0))
     hd, rd, td = G.dev_i32(h), G.dev_i32(r), G.dev_i32(t)
     nh = torch.empty(wl.batch, dtype=torch.int32, device=G.DEV)
     nt = torch.empty_like(nh)
@@ -25,7 +25,7 @@ def gpu_learn(name):
         for lo in range(0, len(h), wl.batch):
             hi = min(lo + wl.batch, len(h))
             batch = B.make_batch(hd[lo:hi], rd[lo:hi], td[lo:hi], 1, W.negative_seed(wl), ep, len(h), lo, nh, nt)
-            B.stx_train_step(m.ctx, batch, m.inc, m.params, None, wl.lr, m.scores, m.loss)
+            B.stx_train_step(m.ctx, batch, m.inc, m.params, m.grads, wl.lr, m.scores, m.loss)
             total += m.loss
         losses.append(float(total.item()))
     nq = len(th)
@@ -33,8 +33,10 @@ def gpu_learn(name):
     less = torch.empty(nq, dtype=torch.int32, device=G.DEV)
     equal = torch.empty_like(less)
     hits = []
+    need = B.stx_rank_work_bytes(m.ctx, nq)
+    work = torch.empty(need + 256, dtype=torch.uint8, device=G.DEV) if need else None
     for side in (B.STX_TAIL, B.STX_HEAD):
-        B.stx_rank(m.ctx, m.params, G.dev_i32(th), G.dev_i32(tr), G.dev_i32(tt), side, ts, less, equal)
+        B.stx_rank(m.ctx, m.params, G.dev_i32(th), G.dev_i32(tr), G.dev_i32(tt), side, ts, less, equal, work)
         torch.cuda.synchronize()
         hits.append(hits_at_10(less.cpu().numpy()))
     return losses, hits, m.params.ent.cpu().numpy()
@@ -48,7 +50,7 @@ def test_gpu_training_learns_the_shift_graph(name):
     assert min(hits) >= bar, hits
     assert max(abs(a - b) for a, b in zip(hits, ref_hits)) <= 0.15, (hits, ref_hits)
     # the first epoch follows the oracle closely (the trajectories have had no time to part)
-    assert abs(losses[0] - ref_losses[0]) <= 1e-4 * ref_losses[0]
+    assert abs(losses[0] - ref_losses[0]) <= (1e-2 if name == "transr" else 1e-4) * ref_losses[0]
     # the whole run again: same bits
     losses2, hits2, table2 = gpu_learn(name)
     assert losses2 == losses and hits2 == hits and np.array_equal(table.view(np.uint32), table2.view(np.uint32))
