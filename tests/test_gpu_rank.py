@@ -289,6 +289,7 @@ R_CASES = [
     ("l1", 1000, 20, 128, 128, 129),
     ("l2_sq", 515, 3, 32, 96, 300),               # groups larger than a query block
     ("l2", 257, 40, 32, 256, 90),                 # two output tiles per projected row; most relations have few queries
+    ("l1", 64, 700, 32, 32, 150),                 # more relations than one pass of the offset scan covers; most are empty
 ]
 
 
