@@ -516,6 +516,21 @@ def main():
             step(args.warmup + args.steps + n_ph + i)
         out["kernels_us"] = {k: [round(v[0], 2), round(v[1] / n_ph, 2)] for k, v in B.stx_profile_dump(ctx).items()}
         B.stx_profile_kernel(ctx, None, 0)
+        # the same byte models for the other kernels of the step that have one, from this pass's means: where two
+        # kernels take nearly the same time (forward and transposed product at "mid") both figures are on record
+        others = {}
+        for kname, (us, per_step) in out["kernels_us"].items():
+            if kname == kernel or us <= 0:
+                continue
+            try:
+                w, unit, bound, peak = kernel_work(wl, kname, mean_rows, u_last * mean_rows / wl.rows_per_batch, fused)
+            except ValueError:
+                continue
+            ach = w / (us * 1e-6) / (1e9 if unit == "GB/s" else 1e12)
+            others[kname] = {"bound": bound, "achieved": round(ach, 1), "peak": peak, "unit": unit,
+                             "frac": round(ach / peak, 4), "traffic": TRAFFIC_BYTES.get((wl.name, kname, fused)),
+                             "work_per_launch": int(w), "avg_launch_us": us}
+        out["roofline_other_kernels"] = others
 
     if not args.no_cpu_baseline:
         n = args.cpu_steps

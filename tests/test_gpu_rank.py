@@ -70,6 +70,9 @@ CASES = [
     ("toruse", "torus_l2", 257, 4, 36, 130),
     ("transe", "l1", 20_000, 11, 16, 40),         # many candidate slices per query block
     ("transe", "l2", 400, 9, 1024, 64),           # widest rows
+    ("transe", "l1", 128, 1, 32, 128),            # exactly one tile of each, a single relation
+    ("transe", "l2", 256, 2, 32, 256),            # exactly two
+    ("toruse", "torus_l1", 129, 3, 4, 127),       # one over / one under, the narrowest rows
 ]
 
 
