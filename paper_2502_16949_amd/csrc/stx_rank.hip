@@ -1,5 +1,5 @@
-// Link prediction by exhaustive scoring for TransE / TorusE: how many entities score below (and exactly
-// like) the true entity of each test triplet.
+// Link prediction by exhaustive scoring: how many entities score below (and exactly like) the true entity
+// of each test triplet.  TransE / TorusE first; TransH and TransR, further down, reuse the same sweep.
 //
 // SparseTransX Sec. 4.7 lists link prediction among the framework's functions and Sec. 6.1 measures
 // accuracy as Hits@10, the share of test triplets whose true entity is among the ten best candidates.
