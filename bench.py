@@ -138,6 +138,21 @@ def kernel_work(wl, kernel, rows, touched, fused=False):
     raise ValueError(kernel)
 
 
+def kernel_min_bytes(wl, kernel, rows, touched, fused=False):
+    """Lower bound on the bytes one launch must move: every distinct table row once instead of once per entry
+    that names it, every stored dL/dx row once.  None for kernels without such a bound here."""
+    row = 4 * wl.dim
+    nnz = 3 * rows
+    packed = wl.model in ("transe", "toruse") and wl.dist in ("l1", "torus_l1")
+    grow = (wl.dim // 4 + 4) if packed else row
+    stacked = wl.model in ("transe", "toruse")
+    if kernel in ("k_forward_stacked", "k_fwd_scatter") and stacked:
+        return touched * row + rows * (12 + grow + 4) + (nnz * 16 if kernel == "k_fwd_scatter" else 0)
+    if kernel == "k_seg_reduce" and stacked:
+        return rows * grow + nnz * 4 + touched * row * (2 if fused else 1)
+    return None
+
+
 def cpu_baseline(wl, h, r, t, tabs, n_steps):
     """The CPU oracle as it stands, single thread, on the first batches of the same workload."""
     from oracle import stxo
@@ -475,6 +490,11 @@ def main():
     roofline = {"bound": bound, "kernel": kernel, "achieved": round(achieved, 1), "peak": peak, "unit": unit,
                 "frac": round(achieved / peak, 4), "traffic": TRAFFIC_BYTES.get((wl.name, kernel, fused)), "work_per_launch": int(work),
                 "avg_launch_us": round(kernel_us, 2), "launches_per_step": round(per_launch, 2)}
+    bmin = kernel_min_bytes(wl, kernel, mean_rows, u_last * mean_rows / wl.rows_per_batch, fused)
+    if bmin is not None and kernel_us > 0:
+        # the same launch priced by the fewest bytes it could move (distinct rows once): a second, lower figure
+        roofline["min_bytes_per_launch"] = int(bmin)
+        roofline["achieved_min_bytes"] = round(bmin / (kernel_us * 1e-6) / 1e9, 1)
     if kernel_note:
         roofline["note"] = kernel_note
     if kernel in ("k_transr_project", "k_transr_gx", "k_transr_dm") and kernel_us > 0:
