@@ -12,7 +12,7 @@ namespace {
 inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 struct Layout {
-    size_t ctrl, keys[2], pay[2], table, super, tile_heads, loss_partials, partials, gbuf[4], total;
+    size_t ctrl, keys[3], pay[2], table, super, tile_heads, loss_partials, partials, gbuf[4], total;
     size_t tr_items, tr_dm_items, tr_counts, tr_m16, tr_m16t, tr_xt, tr_gyt;
     size_t colmap, rel_cnt;
     int map_words;
@@ -64,7 +64,7 @@ Layout make_layout(const stx_config *c)
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
     L.ctrl = take(CTRL_WORDS * sizeof(int32_t));
-    for (int i = 0; i < 2; ++i) L.keys[i] = take((size_t)L.nnz_max * 4);
+    for (int i = 0; i < 3; ++i) L.keys[i] = take((size_t)L.nnz_max * 4);
     for (int i = 0; i < 2; ++i) L.pay[i] = take((size_t)L.nnz_max * 4);
     L.table = take((size_t)256 * L.ntiles_max * 4);
     L.super = take((size_t)256 * (L.ntiles_max / kSuperTile + 1) * 4);
@@ -172,10 +172,8 @@ stx_status stx_create(const stx_config *cfg, void *workspace, size_t workspace_b
     c->fwd_blocks_max = L.fwd_blocks_max;
     char *base = (char *)workspace;
     c->ctrl = (int32_t *)(base + L.ctrl);
-    for (int i = 0; i < 2; ++i) {
-        c->keys[i] = (int32_t *)(base + L.keys[i]);
-        c->pay[i] = (int32_t *)(base + L.pay[i]);
-    }
+    for (int i = 0; i < 3; ++i) c->keys[i] = (int32_t *)(base + L.keys[i]);
+    for (int i = 0; i < 2; ++i) c->pay[i] = (int32_t *)(base + L.pay[i]);
     c->table = (int32_t *)(base + L.table);
     c->super = (int32_t *)(base + L.super);
     c->tile_heads = (int32_t *)(base + L.tile_heads);

@@ -19,19 +19,10 @@
 // The tile histograms (tile-major table[tile][digit]) must become global offsets before a scatter.
 // With few tiles every scatter workgroup derives its own offsets from the raw table (a few coalesced
 // reads per thread); with many tiles a small k_super_sums first adds the histograms up in groups of tiles.
+#include "stx_emit_body.h"
 #include "stx_sort_body.h"
 
 namespace stx {
-
-// SplitMix64 (Steele, Lea, Flood, OOPSLA 2014) used as a counter-based generator: output number `ctr`
-// of the sequence started at `seed`.
-__device__ inline uint64_t splitmix64_at(uint64_t seed, uint64_t ctr)
-{
-    uint64_t z = seed + (ctr + 1ull) * 0x9E3779B97F4A7C15ull;
-    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-    return z ^ (z >> 31);
-}
 
 __global__ __launch_bounds__(kThreads) void k_sample(const int32_t *__restrict__ h, const int32_t *__restrict__ t,
                                                      int64_t total, int32_t k, uint64_t n_ent, uint64_t seed,
@@ -64,119 +55,10 @@ __global__ void k_empty_incidence(int32_t *rowptr, int32_t *seg_ptr, int32_t *n_
     if (threadIdx.x == 0) { rowptr[0] = 0; seg_ptr[0] = 0; n_touched[0] = 0; }
 }
 
-struct BatchPtrs {
-    const int32_t *h, *r, *t, *nh, *nt;
-    int32_t b, k;
-    // SAMPLE: the negatives are drawn here (as k_sample draws them) and also written to nh_out / nt_out
-    int32_t *nh_out, *nt_out;
-    uint64_t seed, base_ctr;
-};
-
-// Presence bitmap of the batch's columns (one bit per column of [E;R]), kept when the table has few
-// enough columns for a workgroup to scan the whole map: the segment of a column is then its rank among
-// the set bits, and k_seg_write needs no count of segment heads per tile from a kernel before it.
-// Two maps alternate: a build sets bits in one and clears the other, which the build before it used.
-struct ColMap {
-    uint32_t *cur, *other;
-    int words;
-};
-
-// TransR: rows per relation of the batch, for the work-item lists of the projection products.  Two
-// buffers alternate like the bitmaps: a build adds into one and clears the other.
-struct RelCnt {
-    int32_t *cur, *other;
-    int n_rel;
-};
-
-// One thread per entry e = 3*row + slot of A.  Writes the CSR arrays and the sort keys (= column ids),
-// and the histogram of the first digit for this tile.
 template <int ITEMS, bool MAP, bool SAMPLE, bool RC>
-__global__ __launch_bounds__(kThreads) void k_emit(BatchPtrs bp, int32_t n_ent, int32_t n_rel, int32_t nnz,
-                                                   int32_t *__restrict__ rowptr, int32_t *__restrict__ colidx,
-                                                   float *__restrict__ vals, int32_t *__restrict__ keys,
-                                                   int radix, int ntiles, int32_t *__restrict__ table,
-                                                   int32_t *__restrict__ ctrl, ColMap map, RelCnt rc)
+__global__ __launch_bounds__(kThreads) void k_emit(EmitArgs a)
 {
-    __shared__ int32_t s_hist[256];
-    __shared__ uint32_t s_map[MAP ? kMapMaxWords : 1];
-    __shared__ int32_t s_rc[RC ? kRelCntMax : 1];
-    const int tid = threadIdx.x;
-    s_hist[tid] = 0;
-    if (RC) {
-        for (int r = tid; r < rc.n_rel; r += kThreads) s_rc[r] = 0;
-        for (int r = (int)blockIdx.x * kThreads + tid; r < rc.n_rel; r += (int)gridDim.x * kThreads) rc.other[r] = 0;
-    }
-    if (MAP) {
-        for (int w = tid; w < map.words; w += kThreads) s_map[w] = 0u;
-        for (int w = (int)blockIdx.x * kThreads + tid; w < map.words; w += (int)gridDim.x * kThreads) map.other[w] = 0u;
-    }
-    __syncthreads();
-    const int32_t base = blockIdx.x * (kThreads * ITEMS);
-    // First every index of the thread's entries is fetched (the loads of all items are in flight together:
-    // a store in between would order them one after the other), then the entries are written.
-    int32_t raw[ITEMS];
-#pragma unroll
-    for (int it = 0; it < ITEMS; ++it) {
-        const int32_t e = base + it * kThreads + tid;
-        raw[it] = 0;
-        if (e < nnz) {
-            const int32_t row = e / 3, slot = e - 3 * row;
-            if (row < bp.b) {
-                raw[it] = slot == 0 ? bp.h[row] : (slot == 1 ? bp.r[row] : bp.t[row]);
-            } else if (SAMPLE) {   // the positive's side that a negative may keep; the draw decides below
-                const int32_t i = (row - bp.b) / bp.k;
-                raw[it] = slot == 0 ? bp.h[i] : (slot == 1 ? bp.r[i] : bp.t[i]);
-            } else {
-                const int32_t j = row - bp.b;
-                raw[it] = slot == 0 ? bp.nh[j] : (slot == 1 ? bp.r[j / bp.k] : bp.nt[j]);
-            }
-        }
-    }
-#pragma unroll
-    for (int it = 0; it < ITEMS; ++it) {
-        int32_t e = base + it * kThreads + tid;
-        if (e < nnz) {
-            int32_t row = e / 3, slot = e - 3 * row;
-            int32_t idx = raw[it];
-            if (SAMPLE && row >= bp.b && slot != 1) {
-                // the three threads of a row draw the same number; slots 0 and 2 store their side
-                const int32_t j = row - bp.b;
-                const uint64_t u = splitmix64_at(bp.seed, bp.base_ctr + (uint64_t)j);
-                const int32_t ent = (int32_t)(((u & 0xFFFFFFFFull) * (uint64_t)n_ent) >> 32);
-                const bool head = (u >> 63) != 0;
-                if (slot == 0) { idx = head ? ent : idx; bp.nh_out[j] = idx; }
-                else           { idx = head ? idx : ent; bp.nt_out[j] = idx; }
-            }
-            int32_t lim = slot == 1 ? n_rel : n_ent;
-            if (idx < 0 || idx >= lim) {           // clamp so nothing downstream reads outside a table
-                atomicAdd(&ctrl[CTRL_BAD_INDEX], 1);
-                idx = idx < 0 ? 0 : lim - 1;
-            }
-            int32_t col = slot == 1 ? n_ent + idx : idx;
-            colidx[e] = col;
-            vals[e] = slot == 2 ? -1.0f : 1.0f;
-            if (slot == 0) rowptr[row] = e;
-            if (e == nnz - 1) rowptr[row + 1] = nnz;
-            keys[e] = col;
-            atomicAdd(&s_hist[col & (radix - 1)], 1);
-            if (MAP) atomicOr(&s_map[col >> 5], 1u << (col & 31));
-            if (RC && slot == 1) atomicAdd(&s_rc[idx], 1);
-        }
-    }
-    __syncthreads();
-    if (tid < radix) table[blockIdx.x * radix + tid] = s_hist[tid];
-    if (MAP) {
-        for (int w = tid; w < map.words; w += kThreads) {
-            const uint32_t v = s_map[w];
-            if (v) atomicOr(&map.cur[w], v);
-        }
-    }
-    if (RC) {
-        for (int r = tid; r < rc.n_rel; r += kThreads) {
-            const int32_t v = s_rc[r];
-            if (v) atomicAdd(&rc.cur[r], v);
-        }
-    }
+    emit_body<ITEMS, MAP, SAMPLE, RC>((int)blockIdx.x, (int)gridDim.x, a);
 }
 
 template <int ITEMS>
@@ -428,12 +310,13 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
         c->cnt_inc = inc;
         c->cnt_cur ^= 1;
     }
+    // keys[2] receives the unsorted keys: the sorted keys of the previous batch (in keys[0] or keys[1]) stay
+    // readable while this batch's first kernel runs
+    const EmitArgs ea{bp, n_ent, n_rel, nnz, inc->a_rowptr, inc->a_colidx, inc->a_vals, c->keys[2], 1 << bits0, ntiles,
+                      c->table, c->ctrl, map, rc};
     {
     ProfScope prof(c, "k_emit");
-#define STX_EMIT(I, M, S, R)                                                                                    \
-    hipLaunchKernelGGL((k_emit<I, M, S, R>), dim3(ntiles), dim3(kThreads), 0, s, bp, n_ent, n_rel, nnz,         \
-                       inc->a_rowptr, inc->a_colidx, inc->a_vals, c->keys[0], 1 << bits0, ntiles, c->table,     \
-                       c->ctrl, map, rc)
+#define STX_EMIT(I, M, S, R) hipLaunchKernelGGL((k_emit<I, M, S, R>), dim3(ntiles), dim3(kThreads), 0, s, ea)
 #define STX_EMIT3(I, M, S) do { if (use_rc) STX_EMIT(I, M, S, true); else STX_EMIT(I, M, S, false); } while (0)
 #define STX_EMIT2(I, M) do { if (sample) STX_EMIT3(I, M, true); else STX_EMIT3(I, M, false); } while (0)
     if (items == kSortItems) { if (use_map) STX_EMIT2(kSortItems, true); else STX_EMIT2(kSortItems, false); }
@@ -464,8 +347,8 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
             hipLaunchKernelGGL(k_super_sums, dim3(ngroups), dim3(kThreads), 0, s, c->table, 1 << bits, ntiles,
                                c->super);
         }
-        const ScatterArgs sa{c->keys[cur], c->pay[cur], c->keys[cur ^ 1], c->pay[cur ^ 1], nnz, shift, bits, ntiles,
-                             c->table, c->super};
+        const ScatterArgs sa{p == 0 ? c->keys[2] : c->keys[cur], c->pay[cur], c->keys[cur ^ 1], c->pay[cur ^ 1], nnz, shift,
+                             bits, ntiles, c->table, c->super};
 #define STX_SCATTER(F, S, I)                                                                                  \
     hipLaunchKernelGGL((k_scatter<F, S, I>), dim3(ntiles), dim3(kThreads), 0, s, sa)
 #define STX_SCATTER2(F, S) do { if (items == kSortItems) STX_SCATTER(F, S, kSortItems); else STX_SCATTER(F, S, 2 * kSortItems); } while (0)

@@ -50,7 +50,7 @@ struct stx_ctx {
     int fwd_blocks_max;
     // workspace partitions (device)
     int32_t *ctrl;
-    int32_t *keys[2];
+    int32_t *keys[3];              // [0], [1]: ping-pong of the sort; [2]: the unsorted keys of the batch being built
     int32_t *pay[2];
     int32_t *table;                // [256 * ntiles_max] digit-major tile histograms / offsets
     int32_t *super;                // [256 * (ntiles_max / kSuperTile + 1)] group sums of the tile histograms
