@@ -68,6 +68,9 @@ def parse():
     ap.add_argument("--api", default="step", choices=["step", "fused", "separate"],
                     help="step: one stx_train_step call per step (default); fused: sample, build, forward, "
                          "stx_backward_sgd; separate: sample, build, forward, backward, sgd_step")
+    ap.add_argument("--no-lookahead", action="store_true",
+                    help="--api step: do not tell a step which batch follows (its first build kernel then runs on its own "
+                         "instead of inside the previous step's transposed product)")
     ap.add_argument("--all-kernels", action="store_true",
                     help="extra untimed pass that brackets every kernel with events and adds 'kernels_us' to the output")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -419,6 +422,10 @@ def main():
                  byref(inc.c), byref(params.c), byref(grads.c), wl.lr, scores.data_ptr(), loss.data_ptr()),
                 b * (1 + wl.n_neg))
     calls = [marshal(lo, hi) for lo, hi in slices]
+    if one_call and not args.no_lookahead:
+        # every step names the batch of the step after it (steps walk the batches cyclically)
+        batch_objs = [c[6][1]._obj for c in calls]
+        B.link_batches(batch_objs, cyclic=True)
 
     def step(i, ev=None):
         a_s, a_b, a_f, a_g, a_u, a_bu, a_step, rows = calls[i % len(calls)]
@@ -516,7 +523,7 @@ def main():
                                f"SGD lr {wl.lr}",
                    "rows_per_full_batch": wl.rows_per_batch, "batches_per_epoch": len(slices),
                    "step": ("stx_train_step: sample negatives + build incidence + forward + backward with fused sgd, one call"
-                            if one_call else "sample negatives + build incidence + forward + " +
+                            + ("" if args.no_lookahead else "; each call names the next batch") if one_call else "sample negatives + build incidence + forward + " +
                             ("backward with fused sgd (stx_backward_sgd)" if fused else "backward + sgd")),
                    "api": args.api},
         "host_enqueue_us_per_step": round(t_enq / args.steps * 1e6, 2),

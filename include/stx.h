@@ -212,13 +212,20 @@ stx_status stx_sgd_step(stx_ctx *ctx, stx_params *p, const stx_incidence *inc, c
 stx_status stx_backward_sgd(stx_ctx *ctx, const stx_incidence *inc, stx_params *p, stx_grads *g, float lr);
 
 /* One training step in one call.  The batch's positives plus what stx_sample_negatives needs to draw its
- * negatives; neg_h / neg_t ([b*k], device, out) receive the negatives drawn (not needed when k == 0).  */
-typedef struct {
+ * negatives; neg_h / neg_t ([b*k], device, out) receive the negatives drawn (not needed when k == 0).
+ * next (host, may be null): the batch the NEXT stx_train_step call on this context will be given, with the
+ * same inc.  Nothing in the first kernel of a build depends on the step before it, so it then runs in the
+ * launch of this step's transposed product, and the next call, if it is given exactly that batch, starts
+ * from there; results are the same bit for bit.  With next set, on return the A arrays of inc (a_rowptr,
+ * a_colidx, a_vals) and next's neg_h / neg_t already hold the next batch's, the A^T arrays this batch's.
+ * A next call with another batch, or any other call, simply builds as usual.  next->next is ignored.     */
+typedef struct stx_batch {
     const int32_t *h, *r, *t; /* [b], device */
     int32_t b, k;
     uint64_t seed, epoch;
     int64_t m_total, global_offset;
     int32_t *neg_h, *neg_t;
+    const struct stx_batch *next;
 } stx_batch;
 
 /* stx_sample_negatives, stx_build_incidence, stx_forward and stx_backward_sgd on one batch, with the same

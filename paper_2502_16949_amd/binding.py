@@ -63,7 +63,7 @@ class stx_grads(C.Structure):
 class stx_batch(C.Structure):
     _fields_ = [("h", C.c_void_p), ("r", C.c_void_p), ("t", C.c_void_p), ("b", C.c_int32), ("k", C.c_int32),
                 ("seed", C.c_uint64), ("epoch", C.c_uint64), ("m_total", C.c_int64), ("global_offset", C.c_int64),
-                ("neg_h", C.c_void_p), ("neg_t", C.c_void_p)]
+                ("neg_h", C.c_void_p), ("neg_t", C.c_void_p), ("next", C.c_void_p)]
 
 
 _lib = None
@@ -317,13 +317,23 @@ def stx_backward_sgd(ctx: Context, inc: Incidence, p: Params, g, lr: float):
     _check("stx_backward_sgd", lib().stx_backward_sgd(ctx.handle, C.byref(inc.c), C.byref(p.c), gp, lr))
 
 
-def make_batch(h, r, t, k, seed, epoch, m_total, global_offset, neg_h, neg_t) -> "stx_batch":
-    """Argument block of stx_train_step; the tensors must stay alive while it is in use."""
+def make_batch(h, r, t, k, seed, epoch, m_total, global_offset, neg_h, neg_t, next_batch=None) -> "stx_batch":
+    """Argument block of stx_train_step; the tensors (and next_batch, the block of the call that follows, if
+    given) must stay alive while it is in use.  link_batches() chains a list of them."""
     b = h.numel()
     assert r.numel() == b and t.numel() == b
     assert k == 0 or (neg_h.numel() >= b * k and neg_t.numel() >= b * k)
     return stx_batch(_i32dev(h), _i32dev(r), _i32dev(t), b, k, seed, epoch, m_total, global_offset,
-                     _i32dev(neg_h) if k else None, _i32dev(neg_t) if k else None)
+                     _i32dev(neg_h) if k else None, _i32dev(neg_t) if k else None,
+                     C.addressof(next_batch) if next_batch is not None else None)
+
+
+def link_batches(batches, cyclic=False):
+    """Sets every block's `next` to the block after it (the last one's to the first when cyclic)."""
+    for i, bt in enumerate(batches):
+        nxt = batches[(i + 1) % len(batches)] if (cyclic or i + 1 < len(batches)) else None
+        bt.next = C.addressof(nxt) if nxt is not None else None
+    return batches
 
 
 def stx_train_step(ctx: Context, batch, inc: Incidence, p: Params, g, lr: float, scores, loss):

@@ -201,6 +201,8 @@ stx_status stx_create(const stx_config *cfg, void *workspace, size_t workspace_b
     c->fin_loss = nullptr;
     c->fwd_inc = nullptr;
     c->fwd_rows = 0;
+    c->ahead.armed = c->ahead.done = false;
+    c->ahead.inc = nullptr;
     c->sorted_inc = nullptr;
     c->sorted_keys = nullptr;
     c->prof_ev = nullptr;
@@ -583,7 +585,14 @@ stx_status stx_train_step(stx_ctx *ctx, const stx_batch *bt, stx_incidence *inc,
         ctx->fwd_rows = inc->n_rows;
     }
     if (s != STX_OK) return s;
+    // the next batch's first build kernel may ride in the launch of the transposed product
+    if (bt->next && b > 0) prepare_emit_ahead(ctx, bt->next, inc);
     s = stx_backward_sgd(ctx, inc, p, g, lr);
+    if (!ctx->ahead.done && ctx->ahead.armed) {   // no launch could take it: the maps go back to their roles
+        ctx->ahead.armed = false;
+        ctx->map_cur ^= 1;
+    }
+    ctx->ahead.armed = false;
     if (ctx->fin_n > 0) {   // nothing took the deferred loss sum along (or the backward pass failed)
         const stx_status s2 = launch_finish_loss(ctx, ctx->fin_n, ctx->fin_scale, ctx->fin_loss);
         ctx->fin_n = 0;

@@ -271,6 +271,31 @@ stx_status launch_sample(stx_ctx *c, const int32_t *h, const int32_t *t, int64_t
     return hip_ok(hipGetLastError());
 }
 
+bool prepare_emit_ahead(stx_ctx *c, const stx_batch *next, stx_incidence *inc)
+{
+    c->ahead.armed = c->ahead.done = false;
+    if (!next || next->b <= 0 || next->k < 0 || next->b > c->cfg.max_batch || next->k > c->cfg.max_neg) return false;
+    if (!next->h || !next->r || !next->t || (next->k > 0 && (!next->neg_h || !next->neg_t))) return false;
+    if (next->m_total < 0 || next->global_offset < 0) return false;
+    if (c->map_words <= 0 || c->rel_cnt[0] != nullptr) return false;   // needs the bitmap path, no relation counts
+    const int64_t nnz = 3 * (int64_t)next->b * (1 + next->k);
+    if (nnz > (1 << 19)) return false;                                  // the small-sort shape of the first kernel only
+    const int ntiles = (int)((nnz + kThreads * kSortItems - 1) / (kThreads * kSortItems));
+    const int bits0 = c->sort_bits < c->digit_bits ? c->sort_bits : c->digit_bits;
+    const uint64_t base_ctr = (next->epoch * (uint64_t)next->m_total + (uint64_t)next->global_offset) * (uint64_t)next->k;
+    const BatchPtrs bp{next->h, next->r, next->t, nullptr, nullptr, next->b, next->k > 0 ? next->k : 1,
+                       next->neg_h, next->neg_t, next->seed, base_ctr};
+    const ColMap map{c->colmap[c->map_cur], c->colmap[c->map_cur ^ 1], c->map_words};
+    c->map_cur ^= 1;
+    c->ahead.args = EmitArgs{bp, (int32_t)c->cfg.n_ent, (int32_t)c->cfg.n_rel, (int32_t)nnz, inc->a_rowptr, inc->a_colidx,
+                             inc->a_vals, c->keys[2], 1 << bits0, ntiles, c->table, c->ctrl, map,
+                             RelCnt{nullptr, nullptr, 0}};
+    c->ahead.ntiles = ntiles;
+    c->ahead.inc = inc;
+    c->ahead.armed = true;
+    return true;
+}
+
 stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const int32_t *t, const int32_t *nh,
                         const int32_t *nt, int32_t b, int32_t k, stx_incidence *inc, const SampleArgs *sample,
                         StepFusion *fusion)
@@ -281,6 +306,9 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
     c->cnt_inc = nullptr;
     c->cnt_ptr = nullptr;
     c->prep_inc = nullptr;
+    // the first kernel may already have run, in the launch of the previous step's transposed product
+    const bool ahead_done = c->ahead.done;
+    c->ahead.armed = c->ahead.done = false;
     if (b == 0) {
         hipLaunchKernelGGL(k_empty_incidence, dim3(1), dim3(64), 0, s, inc->a_rowptr, inc->at_seg_ptr,
                            inc->n_touched);
@@ -295,8 +323,15 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
     BatchPtrs bp{h, r, t, nh, nt, b, k > 0 ? k : 1, nullptr, nullptr, 0, 0};
     if (sample) { bp.nh_out = sample->neg_h; bp.nt_out = sample->neg_t; bp.seed = sample->seed; bp.base_ctr = sample->base_ctr; }
     const bool use_map = c->map_words > 0;
+    const EmitArgs &pa = c->ahead.args;
+    const bool emitted = ahead_done && sample && use_map && c->ahead.inc == inc && pa.bp.h == h && pa.bp.r == r &&
+                         pa.bp.t == t && pa.bp.b == b && pa.bp.k == bp.k && pa.nnz == nnz &&
+                         pa.bp.nh_out == bp.nh_out && pa.bp.nt_out == bp.nt_out && pa.bp.seed == bp.seed &&
+                         pa.bp.base_ctr == bp.base_ctr;
     ColMap map{nullptr, nullptr, 0};
-    if (use_map) {
+    if (emitted) {
+        map = pa.map;                    // (the maps changed roles when it was prepared)
+    } else if (use_map) {
         map = ColMap{c->colmap[c->map_cur], c->colmap[c->map_cur ^ 1], c->map_words};
         c->map_cur ^= 1;
     }
@@ -314,7 +349,7 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
     // readable while this batch's first kernel runs
     const EmitArgs ea{bp, n_ent, n_rel, nnz, inc->a_rowptr, inc->a_colidx, inc->a_vals, c->keys[2], 1 << bits0, ntiles,
                       c->table, c->ctrl, map, rc};
-    {
+    if (!emitted) {
     ProfScope prof(c, "k_emit");
 #define STX_EMIT(I, M, S, R) hipLaunchKernelGGL((k_emit<I, M, S, R>), dim3(ntiles), dim3(kThreads), 0, s, ea)
 #define STX_EMIT3(I, M, S) do { if (use_rc) STX_EMIT(I, M, S, true); else STX_EMIT(I, M, S, false); } while (0)

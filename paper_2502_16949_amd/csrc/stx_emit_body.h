@@ -19,45 +19,6 @@ __device__ inline uint64_t splitmix64_at(uint64_t seed, uint64_t ctr)
     return z ^ (z >> 31);
 }
 
-struct BatchPtrs {
-    const int32_t *h, *r, *t, *nh, *nt;
-    int32_t b, k;
-    // SAMPLE: the negatives are drawn here (as k_sample draws them) and also written to nh_out / nt_out
-    int32_t *nh_out, *nt_out;
-    uint64_t seed, base_ctr;
-};
-
-// Presence bitmap of the batch's columns (one bit per column of [E;R]), kept when the table has few
-// enough columns for a workgroup to scan the whole map: the segment of a column is then its rank among
-// the set bits, and k_seg_write needs no count of segment heads per tile from a kernel before it.
-// Two maps alternate: a build sets bits in one and clears the other, which the build before it used.
-struct ColMap {
-    uint32_t *cur, *other;
-    int words;
-};
-
-// TransR: rows per relation of the batch, for the work-item lists of the projection products.  Two
-// buffers alternate like the bitmaps: a build adds into one and clears the other.
-struct RelCnt {
-    int32_t *cur, *other;
-    int n_rel;
-};
-
-// One thread per entry e = 3*row + slot of A.  Writes the CSR arrays and the sort keys (= column ids),
-// and the histogram of the first digit for this tile.
-// Everything k_emit needs, by value, so that the same body can run in a launch shared with another kernel.
-struct EmitArgs {
-    BatchPtrs bp;
-    int32_t n_ent, n_rel, nnz;
-    int32_t *rowptr, *colidx;
-    float *vals;
-    int32_t *keys;
-    int radix, ntiles;
-    int32_t *table, *ctrl;
-    ColMap map;
-    RelCnt rc;
-};
-
 // `block` of `nblocks`: the index of the workgroup among those of the emit (the launch may hold others).
 template <int ITEMS, bool MAP, bool SAMPLE, bool RC>
 __device__ inline void emit_body(const int block, const int nblocks, const EmitArgs &a)

@@ -37,6 +37,58 @@ inline Launch row_launch(int width)
     return {lpr, (q + lpr - 1) / lpr};
 }
 
+
+// What the first kernel of a build (k_emit, stx_emit_body.h) takes; plain data, shared with the host code
+// that prepares a build ahead of time.
+struct BatchPtrs {
+    const int32_t *h, *r, *t, *nh, *nt;
+    int32_t b, k;
+    // SAMPLE: the negatives are drawn here (as k_sample draws them) and also written to nh_out / nt_out
+    int32_t *nh_out, *nt_out;
+    uint64_t seed, base_ctr;
+};
+
+// Presence bitmap of the batch's columns (one bit per column of [E;R]), kept when the table has few
+// enough columns for a workgroup to scan the whole map: the segment of a column is then its rank among
+// the set bits, and k_seg_write needs no count of segment heads per tile from a kernel before it.
+// Two maps alternate: a build sets bits in one and clears the other, which the build before it used.
+struct ColMap {
+    uint32_t *cur, *other;
+    int words;
+};
+
+// TransR: rows per relation of the batch, for the work-item lists of the projection products.  Two
+// buffers alternate like the bitmaps: a build adds into one and clears the other.
+struct RelCnt {
+    int32_t *cur, *other;
+    int n_rel;
+};
+
+// One thread per entry e = 3*row + slot of A.  Writes the CSR arrays and the sort keys (= column ids),
+// and the histogram of the first digit for this tile.
+// Everything k_emit needs, by value, so that the same body can run in a launch shared with another kernel.
+struct EmitArgs {
+    BatchPtrs bp;
+    int32_t n_ent, n_rel, nnz;
+    int32_t *rowptr, *colidx;
+    float *vals;
+    int32_t *keys;
+    int radix, ntiles;
+    int32_t *table, *ctrl;
+    ColMap map;
+    RelCnt rc;
+};
+
+// stx_train_step with a next batch: the first kernel of the next build runs in the launch of this step's
+// transposed product (nothing in it depends on this step).  `armed`: prepared, waiting for that launch;
+// `done`: it ran, the next build may skip its first kernel if it is this very batch.
+struct EmitAheadState {
+    bool armed, done;
+    EmitArgs args;
+    int ntiles;
+    const stx_incidence *inc;
+};
+
 }  // namespace stx
 
 struct stx_ctx {
@@ -84,6 +136,7 @@ struct stx_ctx {
     const int32_t *sorted_keys;
     const stx_incidence *fwd_inc;  // incidence of the last stx_forward, null if none
     int64_t fwd_rows;
+    stx::EmitAheadState ahead;
 };
 
 namespace stx {
@@ -130,6 +183,9 @@ struct SampleArgs {            // negatives drawn inside the build (same numbers
 stx_status launch_build(stx_ctx *, const int32_t *h, const int32_t *r, const int32_t *t, const int32_t *nh,
                         const int32_t *nt, int32_t b, int32_t k, stx_incidence *inc,
                         const SampleArgs *sample = nullptr, StepFusion *fusion = nullptr);
+// Prepares the first kernel of the build of `next` (as stx_train_step would launch it) to run inside the next
+// fused transposed product of this context; false: this configuration or batch does not allow it.
+bool prepare_emit_ahead(stx_ctx *, const stx_batch *next, stx_incidence *inc);
 // stx_transr.hip: item lists and bf16 copies of M_r in the launch of the first scatter pass; false: not possible
 bool launch_prep_scatter(stx_ctx *, const stx_incidence *, const stx_params *, const ScatterArgs &);
 // stx_step.hip

@@ -118,3 +118,73 @@ def test_train_step_rejects_bad_arguments():
     with pytest.raises(B.StxError):                                   # lr is NaN
         B.stx_train_step(m.ctx, B.make_batch(h[:10], h[:10], h[:10], 1, 7, 0, 10, 0, neg, neg), m.inc, m.params, None,
                          float("nan"), m.scores, m.loss)
+
+
+LOOKAHEAD_CASES = [
+    # model, dist, n_ent, n_rel, b, k, dim, flags                 what it exercises
+    ("transe", "l1", 1000, 20, 1000, 1, 128, 0),                 # the benchmark's shape in small: packed dL/dx rows
+    ("transe", "l2", 400, 9, 777, 3, 128, 0),                    # dense rows, several negatives
+    ("toruse", "torus_l1", 1000, 20, 1024, 4, 64, 0),
+    ("transh", "l2", 1000, 20, 1024, 1, 128, B.STX_FLAG_RENORM_W),   # two transposed products in the launch
+    ("transe", "l2", 70000, 5, 3000, 1, 32, 0),                  # no presence bitmap: `next` is ignored
+    ("transe", "l2", 300, 5, 200, 1, 512, 0),                    # wide rows (column slices): `next` is ignored
+    ("transr", "l2", 300, 8, 500, 1, 64, B.STX_FLAG_BF16_PROJ),  # TransR counts rows per relation: `next` is ignored
+]
+
+
+@pytest.mark.parametrize("model,dist,n_ent,n_rel,b,k,dim,flags", LOOKAHEAD_CASES)
+def test_train_step_with_the_next_batch_named_gives_the_same_bits(model, dist, n_ent, n_rel, b, k, dim, flags):
+    """Seven steps over three batches (the last one shorter; the walk wraps around twice), once plain and once with
+    every call naming the batch of the call after it, whose first build kernel then runs inside the launch of this
+    step's transposed product.  After every step: same scores, loss, tables, A^T arrays; and the A arrays and
+    negatives already those of the next batch.  Then a call that is given another batch than the one named."""
+    wl = W.Workload("case", 12, model, dist, n_ent, n_rel, 3 * b, dim, dim, b, k, 1.0, 0.01, 1, 1.1, 1.1,
+                    bool(flags & B.STX_FLAG_BF16_PROJ))
+    tabs = W.make_tables(wl)
+    rng = np.random.default_rng(6)
+    m_total = 3 * b
+    hd = G.dev_i32(rng.integers(0, n_ent, m_total))
+    rd = G.dev_i32(rng.integers(0, n_rel, m_total))
+    td = G.dev_i32(rng.integers(0, n_ent, m_total))
+    slices = [(0, b), (b, 2 * b), (2 * b, 3 * b - 7)]
+    ma, mb = G.GpuModel(wl, tabs, flags=flags), G.GpuModel(wl, tabs, flags=flags)
+    nk = max(1, b * k)
+    neg_a = [tuple(torch.zeros(nk, dtype=torch.int32, device=G.DEV) for _ in range(2)) for _ in slices]
+    neg_b = [tuple(torch.zeros(nk, dtype=torch.int32, device=G.DEV) for _ in range(2)) for _ in slices]
+    mk = lambda neg: [B.make_batch(hd[lo:hi], rd[lo:hi], td[lo:hi], k, 99, 1, m_total, lo, *neg[i])
+                      for i, (lo, hi) in enumerate(slices)]
+    plain, linked = mk(neg_a), B.link_batches(mk(neg_b), cyclic=True)
+    for step in range(7):
+        i = step % 3
+        B.stx_train_step(ma.ctx, plain[i], ma.inc, ma.params, ma.grads, 0.01, ma.scores, ma.loss)
+        B.stx_train_step(mb.ctx, linked[i], mb.inc, mb.params, mb.grads, 0.01, mb.scores, mb.loss)
+        torch.cuda.synchronize()
+        bb = slices[i][1] - slices[i][0]
+        assert torch.equal(neg_a[i][0][:bb * k], neg_b[i][0][:bb * k]) and torch.equal(neg_a[i][1][:bb * k], neg_b[i][1][:bb * k])
+        sa, la = ma.scores_numpy()
+        sb, lb = mb.scores_numpy()
+        assert np.array_equal(sa, sb) and la == lb, step
+        ia, ib = ma.incidence_numpy(), mb.incidence_numpy()
+        for name in ("touched_cols", "seg_ptr", "row_idx", "sign", "seg_id", "packed", "n_touched"):
+            assert np.array_equal(ia[name], ib[name]), (step, name)
+        for name in ("ent", "rel", "w", "proj"):
+            ta, tb = getattr(ma.params, name), getattr(mb.params, name)
+            assert (ta is None and tb is None) or torch.equal(ta, tb), (step, name)
+    # the call after step 6 (batch 0) was announced as batch 1; give batch 2 instead: it must build from scratch
+    B.stx_train_step(ma.ctx, plain[2], ma.inc, ma.params, ma.grads, 0.01, ma.scores, ma.loss)
+    B.stx_train_step(mb.ctx, linked[2], mb.inc, mb.params, mb.grads, 0.01, mb.scores, mb.loss)
+    # ... and then a plain build + forward on the same context (its announced batch 0 is not what comes)
+    for m in (ma, mb):
+        B.stx_build_incidence(m.ctx, hd[:b], rd[:b], td[:b], neg_a[0][0] if k else None, neg_a[0][1] if k else None, k, m.inc)
+        m.forward()
+    torch.cuda.synchronize()
+    ia, ib = ma.incidence_numpy(), mb.incidence_numpy()
+    for name in ia:
+        assert np.array_equal(ia[name], ib[name]), name
+    sa, la = ma.scores_numpy()
+    sb, lb = mb.scores_numpy()
+    assert np.array_equal(sa, sb) and la == lb
+    for name in ("ent", "rel", "w", "proj"):
+        ta, tb = getattr(ma.params, name), getattr(mb.params, name)
+        assert (ta is None and tb is None) or torch.equal(ta, tb), name
+    assert B.stx_check_indices(ma.ctx) == 0 and B.stx_check_indices(mb.ctx) == 0
