@@ -215,7 +215,7 @@ stx_status stx_backward_sgd(stx_ctx *ctx, const stx_incidence *inc, stx_params *
  * negatives; neg_h / neg_t ([b*k], device, out) receive the negatives drawn (not needed when k == 0).
  * next (host, may be null): the batch the NEXT stx_train_step call on this context will be given, with the
  * same inc.  Nothing in the first kernel of a build depends on the step before it, so it then runs in the
- * launch of this step's transposed product, and the next call, if it is given exactly that batch, starts
+ * last launch of this step's transposed product, and the next call, if it is given exactly that batch, starts
  * from there; results are the same bit for bit.  With next set, on return the A arrays of inc (a_rowptr,
  * a_colidx, a_vals) and next's neg_h / neg_t already hold the next batch's, the A^T arrays this batch's.
  * A next call with another batch, or any other call, simply builds as usual.  next->next is ignored.     */

@@ -29,8 +29,8 @@
 
 namespace stx {
 
-// The first kernel of the next batch's build, riding in this launch (EMIT kernels): its workgroups take the
-// low block indices.
+// The first kernel of the next batch's build, riding in the launch of the fix-up kernel (EMIT): its
+// workgroups take the low block indices.
 struct EmitAhead {
     EmitArgs args;
     int ntiles;
@@ -156,23 +156,16 @@ __device__ inline void apply_update(float *__restrict__ row, int d4, int lig, co
 // PACKED: the source rows are records of ld_src bytes at src_a (coefficient, then dim/4 sign bytes), as
 // the forward pass of an L1-kind distance stores them; values and summation order are the same as with
 // dense rows, so both forms give the same bits.
-template <int LPR, int ITERS, bool PACKED, int CHUNK, bool FUSED, bool EMIT>
+template <int LPR, int ITERS, bool PACKED, int CHUNK, bool FUSED>
 __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restrict__ packed,
                                                          const int32_t *__restrict__ seg_id, int32_t e_begin,
                                                          int32_t e_end, const float *__restrict__ src_a,
                                                          const float *__restrict__ src_b, int32_t split,
                                                          int ld_src, int tail_off, int d4, float *__restrict__ out_rows,
                                                          int ld_out, float *__restrict__ partials, FusedArgs fu,
-                                                         SegSecond sec, EmitAhead ea)
+                                                         SegSecond sec)
 {
     int block = (int)blockIdx.x;
-    if constexpr (EMIT) {
-        if (block < ea.ntiles) {      // uniform in the workgroup
-            emit_body<kSortItems, true, true, false>(block, ea.ntiles, ea.args);
-            return;
-        }
-        block -= ea.ntiles;
-    }
     if (block >= sec.first_block) {   // uniform in the workgroup
         block -= sec.first_block;
         e_begin = sec.e_begin; e_end = sec.e_end;
@@ -392,15 +385,22 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
     }
 }
 
-template <int LPR, int ITERS, int CHUNK, bool FUSED>
+template <int LPR, int ITERS, int CHUNK, bool FUSED, bool EMIT>
 __global__ __launch_bounds__(kThreads) void k_seg_fixup(const int32_t *__restrict__ packed,
                                                         const int32_t *__restrict__ seg_id,
                                                         const int32_t *__restrict__ seg_ptr, int32_t e_begin,
                                                         int32_t e_end, int d4, float *__restrict__ out_rows,
                                                         int ld_out, const float *__restrict__ partials, FusedArgs fu,
-                                                        SegSecond sec)
+                                                        SegSecond sec, EmitAhead ea)
 {
     int block = (int)blockIdx.x;
+    if constexpr (EMIT) {
+        if (block < ea.ntiles) {      // uniform in the workgroup
+            emit_body<kSortItems, true, true, false>(block, ea.ntiles, ea.args);
+            return;
+        }
+        block -= ea.ntiles;
+    }
     if (block >= sec.first_block) {   // uniform in the workgroup
         block -= sec.first_block;
         e_begin = sec.e_begin; e_end = sec.e_end;
@@ -626,9 +626,10 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
         ntiles += (second->e_end - second->e_begin + tile - 1) / tile;
     }
     const FusedArgs fu = fused ? *fused : FusedArgs{nullptr, nullptr, 0, nullptr, nullptr, 0.f, 0, 0};
-    // the next batch's first build kernel, if one is waiting, rides in this launch (fused, one float4 per lane)
+    // the next batch's first build kernel, if one is waiting, rides in the launch of the fix-up kernel (fused
+    // products of one float4 per lane that have more than one tile, i.e. a fix-up launch at all)
     const EmitAhead no_emit{};
-    const bool emit_now = fused && ITERS == 1 && c->ahead.armed && !c->ahead.done;
+    const bool emit_now = fused && ITERS == 1 && ntiles > 1 && c->ahead.armed && !c->ahead.done;
     const EmitAhead ahead = emit_now ? EmitAhead{c->ahead.args, c->ahead.ntiles} : no_emit;
     if (emit_now) c->ahead.done = true;
     // Wide rows (more than one float4 per lane) run as column slices of the one-float4 kernels: more rows in
@@ -640,15 +641,15 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
     do {                                                                                                        \
         {                                                                                                       \
             ProfScope prof(c, "k_seg_reduce");                                                                  \
-            hipLaunchKernelGGL((k_seg_reduce<LPR, 1, P, CH, F, false>), grid, dim3(kThreads), 0, c->stream,     \
+            hipLaunchKernelGGL((k_seg_reduce<LPR, 1, P, CH, F>), grid, dim3(kThreads), 0, c->stream,            \
                                inc->at_packed, inc->at_seg_id, e_begin, e_end, src_a, src_b, split, ld_src,     \
-                               tail_off, width / 4, out_rows, ld_out, c->partials, fu, sec, no_emit);           \
+                               tail_off, width / 4, out_rows, ld_out, c->partials, fu, sec);                    \
         }                                                                                                       \
         if (ntiles > 1) {                                                                                       \
             ProfScope prof(c, "k_seg_fixup");                                                                   \
-            hipLaunchKernelGGL((k_seg_fixup<LPR, 1, CH, F>), grid, dim3(kThreads), 0, c->stream,                \
+            hipLaunchKernelGGL((k_seg_fixup<LPR, 1, CH, F, false>), grid, dim3(kThreads), 0, c->stream,         \
                                inc->at_packed, inc->at_seg_id, inc->at_seg_ptr, e_begin, e_end, width / 4,      \
-                               out_rows, ld_out, c->partials, fu, sec);                                         \
+                               out_rows, ld_out, c->partials, fu, sec, no_emit);                                \
         }                                                                                                       \
     } while (0)
 #define STX_SLICED2(P, CH) do { if (fused) STX_SLICED(P, CH, true); else STX_SLICED(P, CH, false); } while (0)
@@ -662,22 +663,21 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
     do {                                                                                                        \
         {                                                                                                       \
             ProfScope prof(c, "k_seg_reduce");                                                                  \
-            if (F && ITERS == 1 && emit_now)                                                                    \
-                hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH, F, F && ITERS == 1>),                       \
-                                   dim3(ntiles + ahead.ntiles), dim3(kThreads), 0, c->stream, inc->at_packed,   \
-                                   inc->at_seg_id, e_begin, e_end, src_a, src_b, split, ld_src, tail_off,       \
-                                   width / 4, out_rows, ld_out, c->partials, fu, sec, ahead);                   \
-            else                                                                                                \
-                hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH, F, false>), dim3(ntiles), dim3(kThreads),   \
-                                   0, c->stream, inc->at_packed, inc->at_seg_id, e_begin, e_end, src_a, src_b,  \
-                                   split, ld_src, tail_off, width / 4, out_rows, ld_out, c->partials, fu, sec,  \
-                                   no_emit);                                                                    \
+            hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH, F>), dim3(ntiles), dim3(kThreads), 0,           \
+                               c->stream, inc->at_packed, inc->at_seg_id, e_begin, e_end, src_a, src_b, split,  \
+                               ld_src, tail_off, width / 4, out_rows, ld_out, c->partials, fu, sec);            \
         }                                                                                                       \
         if (ntiles > 1) {                                                                                       \
             ProfScope prof(c, "k_seg_fixup");                                                                   \
-            hipLaunchKernelGGL((k_seg_fixup<LPR, ITERS, CH, F>), dim3(ntiles), dim3(kThreads), 0,               \
-                               c->stream, inc->at_packed, inc->at_seg_id, inc->at_seg_ptr, e_begin, e_end,      \
-                               width / 4, out_rows, ld_out, c->partials, fu, sec);                              \
+            if (F && ITERS == 1 && emit_now)                                                                    \
+                hipLaunchKernelGGL((k_seg_fixup<LPR, ITERS, CH, F, F && ITERS == 1>),                           \
+                                   dim3(ntiles + ahead.ntiles), dim3(kThreads), 0, c->stream, inc->at_packed,   \
+                                   inc->at_seg_id, inc->at_seg_ptr, e_begin, e_end, width / 4, out_rows,        \
+                                   ld_out, c->partials, fu, sec, ahead);                                        \
+            else                                                                                                \
+                hipLaunchKernelGGL((k_seg_fixup<LPR, ITERS, CH, F, false>), dim3(ntiles), dim3(kThreads), 0,    \
+                                   c->stream, inc->at_packed, inc->at_seg_id, inc->at_seg_ptr, e_begin, e_end,  \
+                                   width / 4, out_rows, ld_out, c->partials, fu, sec, no_emit);                 \
         }                                                                                                       \
     } while (0)
 #define STX_SEG2(P, CH) do { if (fused) STX_SEG(P, CH, true); else STX_SEG(P, CH, false); } while (0)
