@@ -202,6 +202,7 @@ stx_status stx_create(const stx_config *cfg, void *workspace, size_t workspace_b
     c->fwd_inc = nullptr;
     c->fwd_rows = 0;
     c->ahead.armed = c->ahead.done = false;
+    c->ahead.scatter_armed = c->ahead.scatter_done = false;
     c->ahead.inc = nullptr;
     c->sorted_inc = nullptr;
     c->sorted_keys = nullptr;
@@ -592,7 +593,7 @@ stx_status stx_train_step(stx_ctx *ctx, const stx_batch *bt, stx_incidence *inc,
         ctx->ahead.armed = false;
         ctx->map_cur ^= 1;
     }
-    ctx->ahead.armed = false;
+    ctx->ahead.armed = ctx->ahead.scatter_armed = false;
     if (ctx->fin_n > 0) {   // nothing took the deferred loss sum along (or the backward pass failed)
         const stx_status s2 = launch_finish_loss(ctx, ctx->fin_n, ctx->fin_scale, ctx->fin_loss);
         ctx->fin_n = 0;

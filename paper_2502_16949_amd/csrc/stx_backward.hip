@@ -26,13 +26,19 @@
 // memory round trip.
 #include "stx_emit_body.h"
 #include "stx_rowops.h"
+#include "stx_sort_body.h"
 
 namespace stx {
 
-// The first kernel of the next batch's build, riding in the launch of the fix-up kernel (EMIT): its
-// workgroups take the low block indices.
+// The first two kernels of the next batch's build, riding in this step's launches: k_emit's workgroups in the
+// launch of k_seg_reduce (EMIT), those of the sort's first scatter pass in the launch of k_seg_fixup (RIDE).
+// They take the low block indices.
 struct EmitAhead {
     EmitArgs args;
+    int ntiles;
+};
+struct ScatterAhead {
+    ScatterArgs args;
     int ntiles;
 };
 
@@ -156,16 +162,23 @@ __device__ inline void apply_update(float *__restrict__ row, int d4, int lig, co
 // PACKED: the source rows are records of ld_src bytes at src_a (coefficient, then dim/4 sign bytes), as
 // the forward pass of an L1-kind distance stores them; values and summation order are the same as with
 // dense rows, so both forms give the same bits.
-template <int LPR, int ITERS, bool PACKED, int CHUNK, bool FUSED>
+template <int LPR, int ITERS, bool PACKED, int CHUNK, bool FUSED, bool EMIT>
 __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restrict__ packed,
                                                          const int32_t *__restrict__ seg_id, int32_t e_begin,
                                                          int32_t e_end, const float *__restrict__ src_a,
                                                          const float *__restrict__ src_b, int32_t split,
                                                          int ld_src, int tail_off, int d4, float *__restrict__ out_rows,
                                                          int ld_out, float *__restrict__ partials, FusedArgs fu,
-                                                         SegSecond sec)
+                                                         SegSecond sec, EmitAhead ea)
 {
     int block = (int)blockIdx.x;
+    if constexpr (EMIT) {
+        if (block < ea.ntiles) {      // uniform in the workgroup
+            emit_body<kSortItems, true, true, false>(block, ea.ntiles, ea.args);
+            return;
+        }
+        block -= ea.ntiles;
+    }
     if (block >= sec.first_block) {   // uniform in the workgroup
         block -= sec.first_block;
         e_begin = sec.e_begin; e_end = sec.e_end;
@@ -385,21 +398,21 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
     }
 }
 
-template <int LPR, int ITERS, int CHUNK, bool FUSED, bool EMIT>
+template <int LPR, int ITERS, int CHUNK, bool FUSED, bool RIDE>
 __global__ __launch_bounds__(kThreads) void k_seg_fixup(const int32_t *__restrict__ packed,
                                                         const int32_t *__restrict__ seg_id,
                                                         const int32_t *__restrict__ seg_ptr, int32_t e_begin,
                                                         int32_t e_end, int d4, float *__restrict__ out_rows,
                                                         int ld_out, const float *__restrict__ partials, FusedArgs fu,
-                                                        SegSecond sec, EmitAhead ea)
+                                                        SegSecond sec, ScatterAhead sa)
 {
     int block = (int)blockIdx.x;
-    if constexpr (EMIT) {
-        if (block < ea.ntiles) {      // uniform in the workgroup
-            emit_body<kSortItems, true, true, false>(block, ea.ntiles, ea.args);
+    if constexpr (RIDE) {
+        if (block < sa.ntiles) {      // uniform in the workgroup
+            scatter_body<true, false, kSortItems>(block, sa.args);
             return;
         }
-        block -= ea.ntiles;
+        block -= sa.ntiles;
     }
     if (block >= sec.first_block) {   // uniform in the workgroup
         block -= sec.first_block;
@@ -626,12 +639,17 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
         ntiles += (second->e_end - second->e_begin + tile - 1) / tile;
     }
     const FusedArgs fu = fused ? *fused : FusedArgs{nullptr, nullptr, 0, nullptr, nullptr, 0.f, 0, 0};
-    // the next batch's first build kernel, if one is waiting, rides in the launch of the fix-up kernel (fused
-    // products of one float4 per lane that have more than one tile, i.e. a fix-up launch at all)
+    // the next batch's first build kernels, if they are waiting, ride in these launches (fused products of one
+    // float4 per lane): k_emit in that of k_seg_reduce, the first scatter pass in that of k_seg_fixup (which
+    // exists when the product has more than one tile)
     const EmitAhead no_emit{};
-    const bool emit_now = fused && ITERS == 1 && ntiles > 1 && c->ahead.armed && !c->ahead.done;
+    const ScatterAhead no_ride{};
+    const bool emit_now = fused && ITERS == 1 && c->ahead.armed && !c->ahead.done;
+    const bool ride_now = emit_now && ntiles > 1 && c->ahead.scatter_armed && !c->ahead.scatter_done;
     const EmitAhead ahead = emit_now ? EmitAhead{c->ahead.args, c->ahead.ntiles} : no_emit;
+    const ScatterAhead ride = ride_now ? ScatterAhead{c->ahead.sargs, c->ahead.ntiles} : no_ride;
     if (emit_now) c->ahead.done = true;
+    if (ride_now) c->ahead.scatter_done = true;
     // Wide rows (more than one float4 per lane) run as column slices of the one-float4 kernels: more rows in
     // flight per lane and ITERS times the workgroups.  The unit-length rescale needs whole rows.
     const bool whole_rows = fused && (fu.mode == 2 || sec.fused_mode == 2);
@@ -641,15 +659,15 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
     do {                                                                                                        \
         {                                                                                                       \
             ProfScope prof(c, "k_seg_reduce");                                                                  \
-            hipLaunchKernelGGL((k_seg_reduce<LPR, 1, P, CH, F>), grid, dim3(kThreads), 0, c->stream,            \
+            hipLaunchKernelGGL((k_seg_reduce<LPR, 1, P, CH, F, false>), grid, dim3(kThreads), 0, c->stream,     \
                                inc->at_packed, inc->at_seg_id, e_begin, e_end, src_a, src_b, split, ld_src,     \
-                               tail_off, width / 4, out_rows, ld_out, c->partials, fu, sec);                    \
+                               tail_off, width / 4, out_rows, ld_out, c->partials, fu, sec, no_emit);           \
         }                                                                                                       \
         if (ntiles > 1) {                                                                                       \
             ProfScope prof(c, "k_seg_fixup");                                                                   \
             hipLaunchKernelGGL((k_seg_fixup<LPR, 1, CH, F, false>), grid, dim3(kThreads), 0, c->stream,         \
                                inc->at_packed, inc->at_seg_id, inc->at_seg_ptr, e_begin, e_end, width / 4,      \
-                               out_rows, ld_out, c->partials, fu, sec, no_emit);                                \
+                               out_rows, ld_out, c->partials, fu, sec, no_ride);                                \
         }                                                                                                       \
     } while (0)
 #define STX_SLICED2(P, CH) do { if (fused) STX_SLICED(P, CH, true); else STX_SLICED(P, CH, false); } while (0)
@@ -663,21 +681,28 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
     do {                                                                                                        \
         {                                                                                                       \
             ProfScope prof(c, "k_seg_reduce");                                                                  \
-            hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH, F>), dim3(ntiles), dim3(kThreads), 0,           \
-                               c->stream, inc->at_packed, inc->at_seg_id, e_begin, e_end, src_a, src_b, split,  \
-                               ld_src, tail_off, width / 4, out_rows, ld_out, c->partials, fu, sec);            \
+            if (F && ITERS == 1 && emit_now)                                                                    \
+                hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH, F, F && ITERS == 1>),                       \
+                                   dim3(ntiles + ahead.ntiles), dim3(kThreads), 0, c->stream, inc->at_packed,   \
+                                   inc->at_seg_id, e_begin, e_end, src_a, src_b, split, ld_src, tail_off,       \
+                                   width / 4, out_rows, ld_out, c->partials, fu, sec, ahead);                   \
+            else                                                                                                \
+                hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH, F, false>), dim3(ntiles), dim3(kThreads),   \
+                                   0, c->stream, inc->at_packed, inc->at_seg_id, e_begin, e_end, src_a, src_b,  \
+                                   split, ld_src, tail_off, width / 4, out_rows, ld_out, c->partials, fu, sec,  \
+                                   no_emit);                                                                    \
         }                                                                                                       \
         if (ntiles > 1) {                                                                                       \
             ProfScope prof(c, "k_seg_fixup");                                                                   \
-            if (F && ITERS == 1 && emit_now)                                                                    \
+            if (F && ITERS == 1 && ride_now)                                                                    \
                 hipLaunchKernelGGL((k_seg_fixup<LPR, ITERS, CH, F, F && ITERS == 1>),                           \
-                                   dim3(ntiles + ahead.ntiles), dim3(kThreads), 0, c->stream, inc->at_packed,   \
+                                   dim3(ntiles + ride.ntiles), dim3(kThreads), 0, c->stream, inc->at_packed,    \
                                    inc->at_seg_id, inc->at_seg_ptr, e_begin, e_end, width / 4, out_rows,        \
-                                   ld_out, c->partials, fu, sec, ahead);                                        \
+                                   ld_out, c->partials, fu, sec, ride);                                         \
             else                                                                                                \
                 hipLaunchKernelGGL((k_seg_fixup<LPR, ITERS, CH, F, false>), dim3(ntiles), dim3(kThreads), 0,    \
                                    c->stream, inc->at_packed, inc->at_seg_id, inc->at_seg_ptr, e_begin, e_end,  \
-                                   width / 4, out_rows, ld_out, c->partials, fu, sec, no_emit);                 \
+                                   width / 4, out_rows, ld_out, c->partials, fu, sec, no_ride);                 \
         }                                                                                                       \
     } while (0)
 #define STX_SEG2(P, CH) do { if (fused) STX_SEG(P, CH, true); else STX_SEG(P, CH, false); } while (0)

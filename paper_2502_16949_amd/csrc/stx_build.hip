@@ -274,6 +274,7 @@ stx_status launch_sample(stx_ctx *c, const int32_t *h, const int32_t *t, int64_t
 bool prepare_emit_ahead(stx_ctx *c, const stx_batch *next, stx_incidence *inc)
 {
     c->ahead.armed = c->ahead.done = false;
+    c->ahead.scatter_armed = c->ahead.scatter_done = false;
     if (!next || next->b <= 0 || next->k < 0 || next->b > c->cfg.max_batch || next->k > c->cfg.max_neg) return false;
     if (!next->h || !next->r || !next->t || (next->k > 0 && (!next->neg_h || !next->neg_t))) return false;
     if (next->m_total < 0 || next->global_offset < 0) return false;
@@ -293,6 +294,13 @@ bool prepare_emit_ahead(stx_ctx *c, const stx_batch *next, stx_incidence *inc)
     c->ahead.ntiles = ntiles;
     c->ahead.inc = inc;
     c->ahead.armed = true;
+    // the first scatter pass (keys[2] -> keys[1], payload = position) can follow in the next launch when its
+    // workgroups derive their offsets from the raw histograms themselves
+    if (ntiles <= kSelfScanTiles) {
+        c->ahead.sargs = ScatterArgs{c->keys[2], c->pay[0], c->keys[1], c->pay[1], (int32_t)nnz, 0, bits0, ntiles, c->table,
+                                     c->super};
+        c->ahead.scatter_armed = true;
+    }
     return true;
 }
 
@@ -307,8 +315,9 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
     c->cnt_ptr = nullptr;
     c->prep_inc = nullptr;
     // the first kernel may already have run, in the launch of the previous step's transposed product
-    const bool ahead_done = c->ahead.done;
+    const bool ahead_done = c->ahead.done, ahead_scattered = c->ahead.scatter_done;
     c->ahead.armed = c->ahead.done = false;
+    c->ahead.scatter_armed = c->ahead.scatter_done = false;
     if (b == 0) {
         hipLaunchKernelGGL(k_empty_incidence, dim3(1), dim3(64), 0, s, inc->a_rowptr, inc->at_seg_ptr,
                            inc->n_touched);
@@ -328,6 +337,7 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
                          pa.bp.t == t && pa.bp.b == b && pa.bp.k == bp.k && pa.nnz == nnz &&
                          pa.bp.nh_out == bp.nh_out && pa.bp.nt_out == bp.nt_out && pa.bp.seed == bp.seed &&
                          pa.bp.base_ctr == bp.base_ctr;
+    const bool scattered0 = emitted && ahead_scattered;   // ... and the first scatter pass as well
     ColMap map{nullptr, nullptr, 0};
     if (emitted) {
         map = pa.map;                    // (the maps changed roles when it was prepared)
@@ -366,7 +376,14 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
     for (int p = 0; p < c->sort_passes; ++p) {
         int shift = p * c->digit_bits;
         int bits = c->sort_bits - shift < c->digit_bits ? c->sort_bits - shift : c->digit_bits;
-        if (p > 0 && fusion && fusion->forward_done && !fusion->finish_done && items == kSortItems) {
+        if (p == 0 && scattered0) {   // ran in the launch of the previous step's fix-up kernel
+            cur ^= 1;
+            continue;
+        }
+        if (p == 1 && scattered0 && fusion && !fusion->forward_done && !two_level && items == kSortItems &&
+            launch_fwd_hist(c, inc, fusion, c->keys[cur], nnz, shift, 1 << bits, ntiles)) {
+            // the forward pass, which could not share the first scatter pass's launch, shares this histogram's
+        } else if (p > 0 && fusion && fusion->forward_done && !fusion->finish_done && items == kSortItems) {
             launch_hist_finish(c, fusion, c->keys[cur], nnz, shift, 1 << bits, ntiles);
         } else if (p > 0) {
             ProfScope prof(c, "k_hist");
@@ -391,6 +408,9 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
             // the forward pass ran in the same launch
         } else if (p == 0 && fusion && !two_level && items == kSortItems && launch_prep_scatter(c, inc, fusion->p, sa)) {
             // TransR: the item lists and the bf16 copies of M_r were made in the same launch
+        } else if (p > 0 && scattered0 && fusion && fusion->forward_done && !fusion->finish_done && !two_level &&
+                   items == kSortItems) {
+            launch_scatter_finish(c, fusion, sa);   // the sum of the loss rides here
         } else {
             ProfScope prof(c, "k_scatter");
             if (p == 0) { if (two_level) STX_SCATTER2(true, true); else STX_SCATTER2(true, false); }

@@ -79,12 +79,24 @@ struct EmitArgs {
     RelCnt rc;
 };
 
-// stx_train_step with a next batch: the first kernel of the next build runs in the launch of this step's
-// transposed product (nothing in it depends on this step).  `armed`: prepared, waiting for that launch;
-// `done`: it ran, the next build may skip its first kernel if it is this very batch.
+// Arguments of a scatter pass of the sort (by value into its kernel).
+struct ScatterArgs {
+    const int32_t *keys_in, *pay_in;
+    int32_t *keys_out, *pay_out;
+    int32_t nnz;
+    int shift, bits, ntiles;
+    const int32_t *table, *super;
+};
+
+// stx_train_step with a next batch: the first two kernels of the next build (k_emit, then the first scatter
+// pass of the sort) depend on nothing this step computes and run in the two launches of this step's transposed
+// product.  `armed`: prepared, waiting for its launch; `done`: it ran, and the next build may skip it if it is
+// given this very batch.  The scatter pass needs the first kernel's histograms, hence the later launch.
 struct EmitAheadState {
     bool armed, done;
+    bool scatter_armed, scatter_done;
     EmitArgs args;
+    ScatterArgs sargs;
     int ntiles;
     const stx_incidence *inc;
 };
@@ -155,13 +167,6 @@ struct ForwardArgs {
     int32_t n_ent;
 };
 
-struct ScatterArgs {
-    const int32_t *keys_in, *pay_in;
-    int32_t *keys_out, *pay_out;
-    int32_t nnz;
-    int shift, bits, ntiles;
-    const int32_t *table, *super;
-};
 
 // stx_train_step: forward-pass work that may share launches with the sort of A^T.  launch_build fills
 // in what it has done; the caller launches the rest.
@@ -190,6 +195,11 @@ bool prepare_emit_ahead(stx_ctx *, const stx_batch *next, stx_incidence *inc);
 bool launch_prep_scatter(stx_ctx *, const stx_incidence *, const stx_params *, const ScatterArgs &);
 // stx_step.hip
 bool launch_fwd_scatter(stx_ctx *, const stx_incidence *, StepFusion *, const ScatterArgs &);   // false: shape not covered
+// the forward pass beside a histogram pass; a scatter pass beside the sum of the loss (when the first scatter
+// pass already ran ahead of time)
+bool launch_fwd_hist(stx_ctx *, const stx_incidence *, StepFusion *, const int32_t *keys, int32_t nnz, int shift,
+                     int radix, int ntiles);
+void launch_scatter_finish(stx_ctx *, StepFusion *, const ScatterArgs &);
 void launch_hist_finish(stx_ctx *, StepFusion *, const int32_t *keys, int32_t nnz, int shift, int radix, int ntiles);
 stx_status launch_clear_ctrl(stx_ctx *);
 stx_status launch_clear_maps(stx_ctx *);

@@ -38,6 +38,32 @@ __global__ __launch_bounds__(kThreads) void k_hist_finish(const int32_t *__restr
     else hist_body<kSortItems>((int)blockIdx.x - 1, keys, nnz, shift, radix, table);
 }
 
+// When the first scatter pass of a build ran ahead of time (in the previous step's last launch), the forward
+// pass shares the launch of the next histogram pass instead, and the sum of the loss that of the scatter
+// pass after it.
+template <int LPR, int ITERS, int DIST, bool PACKED>
+__global__ __launch_bounds__(kThreads) void k_fwd_hist(ForwardArgs fa, const int32_t *__restrict__ keys, int32_t nnz,
+                                                       int shift, int radix, int32_t *__restrict__ table, int ntiles)
+{
+    if ((int)blockIdx.x < ntiles) hist_body<kSortItems>((int)blockIdx.x, keys, nnz, shift, radix, table);
+    else forward_stacked_body<LPR, ITERS, DIST, false, PACKED>((int)blockIdx.x - ntiles, fa);
+}
+
+template <int LPR, int ITERS, int DIST>
+__global__ __launch_bounds__(kThreads) void k_fwdh_hist(TranshArgs ta, const int32_t *__restrict__ keys, int32_t nnz,
+                                                        int shift, int radix, int32_t *__restrict__ table, int ntiles)
+{
+    if ((int)blockIdx.x < ntiles) hist_body<kSortItems>((int)blockIdx.x, keys, nnz, shift, radix, table);
+    else forward_transh_body<LPR, ITERS, DIST>((int)blockIdx.x - ntiles, ta);
+}
+
+__global__ __launch_bounds__(kThreads) void k_scatter_finish(ScatterArgs sa, const float *__restrict__ partials,
+                                                             int n_partials, float scale, float *__restrict__ loss)
+{
+    if (blockIdx.x == 0) finish_loss_body(partials, n_partials, scale, loss);
+    else scatter_body<false, false, kSortItems>((int)blockIdx.x - 1, sa);
+}
+
 template <int LPR, int ITERS>
 static void fwd_scatter_go(stx_ctx *c, const ForwardArgs &fa, const ScatterArgs &sa, unsigned blocks)
 {
@@ -66,6 +92,84 @@ static void fwdh_scatter_go(stx_ctx *c, const TranshArgs &ta, const ScatterArgs 
     default: STX_FS(STX_TORUS_L2); break;
     }
 #undef STX_FS
+}
+
+template <int LPR>
+static void fwd_hist_go(stx_ctx *c, const ForwardArgs &fa, const int32_t *keys, int32_t nnz, int shift, int radix,
+                        int ntiles, unsigned blocks)
+{
+#define STX_FH(D, P)                                                                                            \
+    hipLaunchKernelGGL((k_fwd_hist<LPR, 1, D, P>), dim3(blocks), dim3(kThreads), 0, c->stream, fa, keys, nnz, shift, \
+                       radix, c->table, ntiles)
+    switch (c->cfg.dist) {
+    case STX_L1: STX_FH(STX_L1, true); break;
+    case STX_L2: STX_FH(STX_L2, false); break;
+    case STX_TORUS_L1: STX_FH(STX_TORUS_L1, true); break;
+    case STX_L2_SQ: STX_FH(STX_L2_SQ, false); break;
+    default: STX_FH(STX_TORUS_L2, false); break;
+    }
+#undef STX_FH
+}
+
+template <int LPR>
+static void fwdh_hist_go(stx_ctx *c, const TranshArgs &ta, const int32_t *keys, int32_t nnz, int shift, int radix,
+                         int ntiles, unsigned blocks)
+{
+#define STX_FH(D)                                                                                               \
+    hipLaunchKernelGGL((k_fwdh_hist<LPR, 1, D>), dim3(blocks), dim3(kThreads), 0, c->stream, ta, keys, nnz, shift,  \
+                       radix, c->table, ntiles)
+    switch (c->cfg.dist) {
+    case STX_L1: STX_FH(STX_L1); break;
+    case STX_L2: STX_FH(STX_L2); break;
+    case STX_TORUS_L1: STX_FH(STX_TORUS_L1); break;
+    case STX_L2_SQ: STX_FH(STX_L2_SQ); break;
+    default: STX_FH(STX_TORUS_L2); break;
+    }
+#undef STX_FH
+}
+
+bool launch_fwd_hist(stx_ctx *c, const stx_incidence *inc, StepFusion *f, const int32_t *keys, int32_t nnz, int shift,
+                     int radix, int ntiles)
+{
+    const bool stacked = c->cfg.model == STX_TRANSE || c->cfg.model == STX_TORUSE;
+    const bool transh = c->cfg.model == STX_TRANSH;
+    const Launch L = row_launch(c->cfg.dim);
+    if (!(stacked || transh) || L.iters != 1 || inc->n_rows == 0) return false;
+    f->scale = 1.0f;
+    if (c->cfg.reduce == STX_MEAN && inc->k > 0) f->scale = 1.0f / (float)((int64_t)inc->b * inc->k);
+    const int groups = kThreads / L.lpr;
+    f->n_partials = (inc->b + groups - 1) / groups;
+    const unsigned blocks = (unsigned)(ntiles + f->n_partials);
+    if (transh) {
+        const TranshArgs ta{inc->a_colidx, f->p->ent, f->p->rel, f->p->w, (int32_t)c->cfg.n_ent, inc->b, inc->k,
+                            c->cfg.dim, c->cfg.margin, f->scale, f->scores, c->gbuf[0], c->gbuf[1], c->gbuf[2],
+                            c->loss_partials};
+        ProfScope prof(c, "k_fwdh_hist");
+        if (L.lpr == 8) fwdh_hist_go<8>(c, ta, keys, nnz, shift, radix, ntiles, blocks);
+        else if (L.lpr == 16) fwdh_hist_go<16>(c, ta, keys, nnz, shift, radix, ntiles, blocks);
+        else if (L.lpr == 32) fwdh_hist_go<32>(c, ta, keys, nnz, shift, radix, ntiles, blocks);
+        else fwdh_hist_go<64>(c, ta, keys, nnz, shift, radix, ntiles, blocks);
+        f->forward_done = true;
+        return true;
+    }
+    const ForwardArgs fa{inc->a_colidx, f->p->ent, inc->b, inc->k, c->cfg.dim, c->cfg.margin, f->scale, f->scores,
+                         c->gbuf[0], packed_stride(c->cfg.dim), c->loss_partials, f->p->rel_weight,
+                         (int32_t)c->cfg.n_ent};
+    ProfScope prof(c, "k_fwd_hist");
+    if (L.lpr == 8) fwd_hist_go<8>(c, fa, keys, nnz, shift, radix, ntiles, blocks);
+    else if (L.lpr == 16) fwd_hist_go<16>(c, fa, keys, nnz, shift, radix, ntiles, blocks);
+    else if (L.lpr == 32) fwd_hist_go<32>(c, fa, keys, nnz, shift, radix, ntiles, blocks);
+    else fwd_hist_go<64>(c, fa, keys, nnz, shift, radix, ntiles, blocks);
+    f->forward_done = true;
+    return true;
+}
+
+void launch_scatter_finish(stx_ctx *c, StepFusion *f, const ScatterArgs &sa)
+{
+    ProfScope prof(c, "k_scatter_finish");
+    hipLaunchKernelGGL(k_scatter_finish, dim3((unsigned)sa.ntiles + 1), dim3(kThreads), 0, c->stream, sa, c->loss_partials,
+                       f->n_partials, f->scale, f->loss);
+    f->finish_done = true;
 }
 
 bool launch_fwd_scatter(stx_ctx *c, const stx_incidence *inc, StepFusion *f, const ScatterArgs &sa)
