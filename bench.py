@@ -27,9 +27,11 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 # The kernel whose roofline is reported: the one with the largest share of GPU time in the
 # rocprofv3 kernel trace of the same command (profiles/).
-DOMINANT = {"mid": "k_fwd_scatter", "tiny": "k_fwd_scatter", "toruse": "k_seg_reduce", "transh": "k_seg_reduce",
+DOMINANT = {"mid": "k_seg_reduce", "tiny": "k_seg_reduce", "toruse": "k_seg_reduce", "transh": "k_seg_reduce",
             "transr": "k_transr_project", "paper_transe": "k_seg_reduce", "paper_toruse": "k_seg_reduce",
             "paper_transr": "k_transr_project"}
+# ... without the look-ahead (--no-lookahead) the forward pass and the first scatter pass share the longest launch
+DOMINANT_PLAIN = dict(DOMINANT, mid="k_fwd_scatter", tiny="k_fwd_scatter")
 # ... and when the step is made of the separate calls (--api fused | separate)
 DOMINANT_CALLS = {"mid": "k_seg_reduce", "tiny": "k_seg_reduce", "toruse": "k_seg_reduce", "transh": "k_forward_transh",
                   "transr": "k_transr_project", "paper_transe": "k_seg_reduce", "paper_toruse": "k_seg_reduce",
@@ -88,11 +90,24 @@ def parse():
     return ap.parse_args()
 
 
-def kernel_work(wl, kernel, rows, touched, fused=False):
+def kernel_work(wl, kernel, rows, touched, fused=False, rides=False):
     """Algorithmic work of ONE launch of `kernel` on a full batch: (amount, unit, bound, peak).
-    row = 4*dim bytes.  rows = b*(1+k) matrix rows, nnz = 3*rows, touched = distinct columns."""
+    row = 4*dim bytes.  rows = b*(1+k) matrix rows, nnz = 3*rows, touched = distinct columns.
+    rides: the launch of k_seg_reduce also runs the next batch's k_emit (about 28 B per entry: indices in, CSR
+    arrays, keys and negatives out), that of k_seg_fixup its first scatter pass (16 B per entry)."""
     row = 4 * wl.dim
     nnz = 3 * rows
+    if kernel == "k_seg_reduce" and rides:
+        w, unit, bound, peak = kernel_work(wl, kernel, rows, touched, fused, False)
+        return w + nnz * 28, unit, bound, peak
+    if kernel == "k_seg_fixup" and rides:
+        return nnz * 16, "GB/s", "hbm", HBM_PEAK_GBS
+    if kernel in ("k_fwd_hist", "k_fwdh_hist"):      # the forward pass and a histogram pass (4 B per key) in one launch
+        w, unit, bound, peak = kernel_work(wl, "k_forward_stacked" if kernel == "k_fwd_hist" else "k_forward_transh", rows,
+                                           touched, fused, False)
+        return w + nnz * 4, unit, bound, peak
+    if kernel == "k_scatter_finish":
+        return nnz * 16, "GB/s", "hbm", HBM_PEAK_GBS
     packed = wl.model in ("transe", "toruse") and wl.dist in ("l1", "torus_l1")
     grow = (wl.dim // 4 + 4) if packed else row     # a stored dL/dx row: coefficient + sign bytes, or dense fp32
     if kernel == "k_forward_stacked" and wl.model in ("transe", "toruse"):
@@ -380,7 +395,11 @@ def main():
     if args.rank:
         bench_rank(args, wl, dev)
         return
-    kernel = args.kernel or (DOMINANT if args.api == "step" else DOMINANT_CALLS)[wl.name]
+    kernel = args.kernel or ((DOMINANT_PLAIN if args.no_lookahead else DOMINANT) if args.api == "step"
+                             else DOMINANT_CALLS)[wl.name]
+    # batches whose first build kernels can run inside the previous step's launches (see stx_batch.next)
+    rides = (args.api == "step" and not args.no_lookahead and wl.model in ("transe", "toruse", "transh")
+             and wl.n_ent + wl.n_rel <= 65536 and 3 * wl.rows_per_batch <= (1 << 18) and wl.dim <= 256)
 
     h, r, t = W.make_graph(wl)
     tabs = W.make_tables(wl)
@@ -490,12 +509,14 @@ def main():
     # ---- roofline of the dominant kernel.  The mean launch time covers every batch of the timed region
     # (the partial last batch of an epoch included), so the work figure is averaged the same way. ----------
     mean_rows = rows_done / args.steps
-    work, unit, bound, peak = kernel_work(wl, kernel, mean_rows, u_last * mean_rows / wl.rows_per_batch, fused)
-    kernel_note = ""
+    work, unit, bound, peak = kernel_work(wl, kernel, mean_rows, u_last * mean_rows / wl.rows_per_batch, fused, rides)
+    kernel_note = ("this launch also runs the first build kernel of the next batch (about 28 B per entry, counted)"
+                   if rides and kernel == "k_seg_reduce" else "")
     per_launch = kernel_n / args.steps if args.steps else 0
     achieved = (work / (kernel_us * 1e-6)) / (1e9 if unit == "GB/s" else 1e12) if kernel_us > 0 else 0.0
     roofline = {"bound": bound, "kernel": kernel, "achieved": round(achieved, 1), "peak": peak, "unit": unit,
-                "frac": round(achieved / peak, 4), "traffic": TRAFFIC_BYTES.get((wl.name, kernel, fused)), "work_per_launch": int(work),
+                "frac": round(achieved / peak, 4),
+                "traffic": TRAFFIC_BYTES.get((wl.name, kernel, "rides" if rides else fused)), "work_per_launch": int(work),
                 "avg_launch_us": round(kernel_us, 2), "launches_per_step": round(per_launch, 2)}
     bmin = kernel_min_bytes(wl, kernel, mean_rows, u_last * mean_rows / wl.rows_per_batch, fused)
     if bmin is not None and kernel_us > 0:
@@ -550,12 +571,13 @@ def main():
             if kname == kernel or us <= 0:
                 continue
             try:
-                w, unit, bound, peak = kernel_work(wl, kname, mean_rows, u_last * mean_rows / wl.rows_per_batch, fused)
+                w, unit, bound, peak = kernel_work(wl, kname, mean_rows, u_last * mean_rows / wl.rows_per_batch, fused, rides)
             except ValueError:
                 continue
             ach = w / (us * 1e-6) / (1e9 if unit == "GB/s" else 1e12)
             others[kname] = {"bound": bound, "achieved": round(ach, 1), "peak": peak, "unit": unit,
-                             "frac": round(ach / peak, 4), "traffic": TRAFFIC_BYTES.get((wl.name, kname, fused)),
+                             "frac": round(ach / peak, 4),
+                             "traffic": TRAFFIC_BYTES.get((wl.name, kname, "rides" if rides else fused)),
                              "work_per_launch": int(w), "avg_launch_us": us}
         out["roofline_other_kernels"] = others
 
