@@ -54,6 +54,11 @@ TRAFFIC_BYTES = {("mid", "k_fwd_scatter", True): 26.10e6 + 7.33e6,
                  ("toruse", "k_forward_stacked", False): 704.01e6 + 90.19e6,
                  # mean of the two batches of an epoch (393,216 and 89,926 positives), like the timed mean
                  ("paper_transe", "k_seg_reduce", True): (9761.85e6 + 104.19e6 + 2281.04e6 + 99.90e6) / 2,
+                 # with the look-ahead (the next batch's first build kernels ride in these launches)
+                 ("mid", "k_seg_reduce", "rides"): 28.77e6 + 11.79e6,
+                 ("mid", "k_fwd_hist", "rides"): 24.93e6 + 4.57e6,
+                 ("transh", "k_seg_reduce", "rides"): 140.63e6 + 12.63e6,
+                 ("transh", "k_fwdh_hist", "rides"): 31.42e6 + 98.76e6,
                  # the other modes (profiles/semiring_complex_*_kernel_trace.txt, profiles/rank_mid_kernel_trace.txt)
                  ("semiring complex", "mid", "k_semiring_terms"): 66.64e6 + 100.66e6,
                  ("semiring complex", "toruse", "k_semiring_terms"): 1560.16e6 + 2013.27e6}
@@ -477,7 +482,11 @@ def main():
 
     # ---- timed region: exactly --steps steps; the library brackets the launches of `kernel` with HIP
     # events on the stream that kernel runs on ---------------------------------------------------------
+    # every eighth launch of the kernel is bracketed: an event pair costs a few microseconds of stream time, and
+    # at 50 us per step bracketing them all would slow the steps that are being timed by a tenth
     B.stx_profile_kernel(ctx, kernel, 8 * args.steps)
+    prof_every = 8 if args.steps >= 64 else 1
+    B.stx_profile_every(ctx, prof_every)
     rows_done = 0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -512,7 +521,7 @@ def main():
     work, unit, bound, peak = kernel_work(wl, kernel, mean_rows, u_last * mean_rows / wl.rows_per_batch, fused, rides)
     kernel_note = ("this launch also runs the first build kernel of the next batch (about 28 B per entry, counted)"
                    if rides and kernel == "k_seg_reduce" else "")
-    per_launch = kernel_n / args.steps if args.steps else 0
+    per_launch = kernel_n * prof_every / args.steps if args.steps else 0
     achieved = (work / (kernel_us * 1e-6)) / (1e9 if unit == "GB/s" else 1e12) if kernel_us > 0 else 0.0
     roofline = {"bound": bound, "kernel": kernel, "achieved": round(achieved, 1), "peak": peak, "unit": unit,
                 "frac": round(achieved / peak, 4),

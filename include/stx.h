@@ -283,6 +283,10 @@ stx_status stx_rank(stx_ctx *ctx, const stx_params *p, const int32_t *h, const i
  * event work to the stream: use it to see where time goes, not to time a whole step.  Not to be used
  * while the stream is being captured into a graph.                                                     */
 stx_status stx_profile_kernel(stx_ctx *ctx, const char *kernel_name /* host */, int32_t max_records);
+/* Bracket only every `every`-th launch that stx_profile_kernel selects (1 = all, the default after every
+ * stx_profile_kernel call).  An event pair costs a few microseconds of stream time: a benchmark that times
+ * whole steps and one kernel together samples the kernel sparsely so that the steps are not slowed.    */
+stx_status stx_profile_every(stx_ctx *ctx, int32_t every);
 stx_status stx_profile_read(stx_ctx *ctx, double *avg_us, int32_t *n);
 stx_status stx_profile_dump(stx_ctx *ctx, char *text, size_t text_bytes);
 

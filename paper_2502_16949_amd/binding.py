@@ -28,7 +28,7 @@ DISTS = {"l1": STX_L1, "l2": STX_L2, "torus_l1": STX_TORUS_L1, "torus_l2": STX_T
 
 EXPORTS = ["stx_workspace_bytes", "stx_create", "stx_destroy", "stx_sample_negatives", "stx_build_incidence",
            "stx_check_indices", "stx_spmm", "stx_spmm_semiring", "stx_spmm_semiring_t", "stx_rank", "stx_rank_work_bytes", "stx_forward", "stx_backward", "stx_sgd_step", "stx_backward_sgd", "stx_train_step", "stx_profile_kernel",
-           "stx_profile_read", "stx_profile_dump", "stx_copy_f32", "stx_status_string"]
+           "stx_profile_every", "stx_profile_read", "stx_profile_dump", "stx_copy_f32", "stx_status_string"]
 
 
 class StxError(RuntimeError):
@@ -99,6 +99,7 @@ def lib():
         L.stx_train_step.argtypes = [vp, C.POINTER(stx_batch), C.POINTER(stx_incidence), C.POINTER(stx_params),
                                      C.POINTER(stx_grads), C.c_float, vp, vp]
         L.stx_profile_kernel.argtypes = [vp, C.c_char_p, i32]
+        L.stx_profile_every.argtypes = [vp, i32]
         L.stx_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32)]
         L.stx_profile_dump.argtypes = [vp, C.c_char_p, C.c_size_t]
         L.stx_copy_f32.argtypes = [vp, vp, vp, i64]
@@ -347,6 +348,10 @@ def stx_train_step(ctx: Context, batch, inc: Incidence, p: Params, g, lr: float,
 def stx_profile_kernel(ctx: Context, kernel_name, max_records: int):
     name = None if kernel_name is None else kernel_name.encode()
     _check("stx_profile_kernel", lib().stx_profile_kernel(ctx.handle, name, max_records))
+
+
+def stx_profile_every(ctx: Context, every: int):
+    _check("stx_profile_every", lib().stx_profile_every(ctx.handle, every))
 
 
 def stx_profile_read(ctx: Context):

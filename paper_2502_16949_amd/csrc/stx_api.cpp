@@ -209,6 +209,8 @@ stx_status stx_create(const stx_config *cfg, void *workspace, size_t workspace_b
     c->prof_ev = nullptr;
     c->prof_tag = nullptr;
     c->prof_cap = c->prof_n = 0;
+    c->prof_every = 1;
+    c->prof_seen = 0;
     c->prof_name[0] = 0;
     c->map_words = L.map_words;
     c->map_cur = 0;
@@ -233,6 +235,8 @@ static void prof_release(stx_ctx *ctx)
     ctx->prof_tag = nullptr;
     ctx->prof_cap = ctx->prof_n = 0;
     ctx->prof_name[0] = 0;
+    ctx->prof_every = 1;
+    ctx->prof_seen = 0;
 }
 
 stx_status stx_destroy(stx_ctx *ctx)
@@ -271,6 +275,15 @@ stx_status stx_profile_kernel(stx_ctx *ctx, const char *kernel_name, int32_t max
         }
     ctx->prof_cap = max_records;
     __builtin_memcpy(ctx->prof_name, kernel_name, len + 1);
+    return STX_OK;
+}
+
+stx_status stx_profile_every(stx_ctx *ctx, int32_t every)
+{
+    if (!ctx) return STX_ERR_NULL;
+    if (every < 1) return STX_ERR_BAD_ARG;
+    ctx->prof_every = every;
+    ctx->prof_seen = 0;
     return STX_OK;
 }
 

@@ -143,6 +143,7 @@ struct stx_ctx {
     hipEvent_t *prof_ev;           // 2 * prof_cap events, null when profiling is off
     const char **prof_tag;         // kernel name of each recorded pair (string literals of the launch sites)
     int prof_cap, prof_n;
+    int prof_every, prof_seen;     // bracket every prof_every-th selected launch
     // host-side call-order state
     const stx_incidence *sorted_inc;   // incidence of the last build, whose sorted keys are still in keys[]
     const int32_t *sorted_keys;
@@ -283,7 +284,8 @@ struct ProfScope {
     ProfScope(stx_ctx *ctx, const char *kernel) : c(ctx), on(false)
     {
         if (c->prof_ev && c->prof_n < c->prof_cap &&
-            (c->prof_name[0] == '*' || __builtin_strcmp(kernel, c->prof_name) == 0)) {
+            (c->prof_name[0] == '*' || __builtin_strcmp(kernel, c->prof_name) == 0) &&
+            (c->prof_every <= 1 || c->prof_seen++ % c->prof_every == 0)) {
             on = true;
             c->prof_tag[c->prof_n] = kernel;
             (void)hipEventRecord(c->prof_ev[2 * c->prof_n], c->stream);
