@@ -315,25 +315,29 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
                         }
                         if constexpr (FUSED) { xcur = xr[u]; colcur = cu[u]; }
                     }
-                    constexpr int VI = PACKED ? 0 : 1;
-                    Acc<ITERS> &vu = v[u * VI];
-                    if constexpr (PACKED) {   // expand to the dense row the forward pass would have stored: +c, -c or 0
-                        const float c = cf[u];
+                    if constexpr (PACKED) {
+                        // the dense row the forward pass would have stored is +c, -c or 0 per element, and a tail
+                        // entry subtracts it: one fused multiply-add per element with the element's sign
+                        const float c = (mu[u] & 1) ? -cf[u] : cf[u];
 #pragma unroll
                         for (int it = 0; it < ITERS; ++it) {
-                            const unsigned b = sb[u][it];
-                            vu.v[it] = make_float4((b & 1u) ? c : ((b & 16u) ? -c : 0.f), (b & 2u) ? c : ((b & 32u) ? -c : 0.f),
-                                                   (b & 4u) ? c : ((b & 64u) ? -c : 0.f), (b & 8u) ? c : ((b & 128u) ? -c : 0.f));
-                        }
-                    }
-                    if (mu[u] & 1) {
-#pragma unroll
-                        for (int it = 0; it < ITERS; ++it) {
-                            acc.v[it].x -= vu.v[it].x; acc.v[it].y -= vu.v[it].y;
-                            acc.v[it].z -= vu.v[it].z; acc.v[it].w -= vu.v[it].w;
+                            const unsigned b = sb[u][it];   // (shift up, arithmetic shift down: sign-extends two bits)
+                            acc.v[it].x = __builtin_fmaf(c, (float)((int)(b << 30) >> 30), acc.v[it].x);
+                            acc.v[it].y = __builtin_fmaf(c, (float)((int)(b << 28) >> 30), acc.v[it].y);
+                            acc.v[it].z = __builtin_fmaf(c, (float)((int)(b << 26) >> 30), acc.v[it].z);
+                            acc.v[it].w = __builtin_fmaf(c, (float)((int)(b << 24) >> 30), acc.v[it].w);
                         }
                     } else {
-                        acc.add(vu);
+                        Acc<ITERS> &vu = v[u];
+                        if (mu[u] & 1) {
+#pragma unroll
+                            for (int it = 0; it < ITERS; ++it) {
+                                acc.v[it].x -= vu.v[it].x; acc.v[it].y -= vu.v[it].y;
+                                acc.v[it].z -= vu.v[it].z; acc.v[it].w -= vu.v[it].w;
+                            }
+                        } else {
+                            acc.add(vu);
+                        }
                     }
                 }
             }
