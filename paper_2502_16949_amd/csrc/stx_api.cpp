@@ -75,8 +75,8 @@ Layout make_layout(const stx_config *c)
     L.partials = take((size_t)(L.nnz_max / kSegTileMin + L.rows_max / kSegTileMin + 4) * 2 * L.ld * 4);
     for (int i = 0; i < 4; ++i) {
         size_t bytes = (size_t)L.rows_max * L.ld * 4;
-        if (i == 0 && bytes < (size_t)L.rows_max * packed_stride(c->dim))   // packed dL/dx records (tiny dims only)
-            bytes = (size_t)L.rows_max * packed_stride(c->dim);
+        const size_t pk_bytes = (size_t)packed_coef_offset(L.rows_max, packed_stride(c->dim)) + (size_t)L.rows_max * 4;
+        if (i == 0 && bytes < pk_bytes) bytes = pk_bytes;   // packed dL/dx records and coefficients (tiny dims only)
         if (c->model == STX_TRANSR && i == 2)   // partial dL/dM_r matrices: two per chunk of the dM product
             bytes = (size_t)(L.rows_max / kProjRowsDm + 2) * 2 * (size_t)c->rel_dim * c->dim * 4;
         L.gbuf[i] = i < L.n_gbuf ? take(bytes) : 0;
@@ -483,8 +483,11 @@ static stx_status run_backward(stx_ctx *ctx, const stx_incidence *inc, const stx
     if (stacked(ctx)) {   // dL/dX = A^T G over all columns of X = [E;R] (Appendix G)
         const bool pk = packed_grad(ctx);
         const SegFusedHost fh{p->ent, nullptr, 0x7fffffff, lr ? *lr : 0.f, ctx->cfg.model == STX_TORUSE ? 1 : 0};
-        return launch_seg_reduce(ctx, inc, 0, inc->nnz, ctx->gbuf[0], ctx->gbuf[0], inc->nnz,
-                                 pk ? packed_stride(dim) : dim, dim, rows, ctx->ld, pk, lr ? &fh : nullptr);
+        const float *coefs = pk ? reinterpret_cast<const float *>(reinterpret_cast<const char *>(ctx->gbuf[0]) +
+                                                                  packed_coef_offset(inc->n_rows, packed_stride(dim)))
+                                : ctx->gbuf[0];
+        return launch_seg_reduce(ctx, inc, 0, inc->nnz, ctx->gbuf[0], coefs, inc->nnz, pk ? packed_stride(dim) : dim, dim,
+                                 rows, ctx->ld, pk, lr ? &fh : nullptr);
     }
     const SegFusedHost fh{p->ent, p->rel, (int32_t)ctx->cfg.n_ent, lr ? *lr : 0.f, 0};
     if (ctx->cfg.model == STX_TRANSH) {

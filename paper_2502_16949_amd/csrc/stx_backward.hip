@@ -159,8 +159,8 @@ __device__ inline void apply_update(float *__restrict__ row, int d4, int lig, co
     }
 }
 
-// PACKED: the source rows are records of ld_src bytes at src_a (coefficient, then dim/4 sign bytes), as
-// the forward pass of an L1-kind distance stores them; values and summation order are the same as with
+// PACKED: the source rows are records of ld_src bytes at src_a (dim/4 sign bytes) with their coefficients in
+// src_b, as the forward pass of an L1-kind distance stores them; values and summation order are the same as with
 // dense rows, so both forms give the same bits.
 template <int LPR, int ITERS, bool PACKED, int CHUNK, bool FUSED, bool EMIT>
 __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restrict__ packed,
@@ -289,14 +289,13 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
                     if (mu[u] & 2) load_row<LPR, ITERS>(fused_row(fu, cu[u], ld_tab), d4, lig, xr[u]);
                 }
                 if constexpr (PACKED) {
-                    const uint8_t *rec = reinterpret_cast<const uint8_t *>(src_a) + row * ld_src;
-                    const uint8_t *pb = rec + 4 + pk_off;
+                    const uint8_t *pb = reinterpret_cast<const uint8_t *>(src_a) + row * ld_src + pk_off;
 #pragma unroll
                     for (int it = 0; it < ITERS; ++it) {
                         const int j = lig + it * LPR;
                         sb[u][it] = j < d4 ? pb[j] : (uint8_t)0;
                     }
-                    cf[u] = *reinterpret_cast<const float *>(rec);
+                    cf[u] = src_b[row];
                 } else {   // entries before `split` read src_a, the rest src_b (entity vs relation columns)
                     // (tail_off: where the rows that tail entries read sit, relative to the head entries' rows)
                     load_row<LPR, ITERS>((ec0 + j0 + u < split ? src_a : src_b) + row * ld_src + ((mu[u] & 1) ? tail_off : 0),

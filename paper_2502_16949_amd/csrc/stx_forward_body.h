@@ -9,16 +9,16 @@ namespace stx {
 
 // Packed dL/dy row of an L1-kind distance: record `row` of gs = coefficient (fp32), then the sign bytes.
 template <int LPR, int ITERS, int DIST>
-__device__ inline void write_grad_row_packed(uint8_t *__restrict__ gs, int gstride, int64_t row, int d4, int lig,
-                                             const RowVec<ITERS> &x, float coef)
+__device__ inline void write_grad_row_packed(uint8_t *__restrict__ gs, int gstride, float *__restrict__ coefs,
+                                             int64_t row, int d4, int lig, const RowVec<ITERS> &x, float coef)
 {
     uint8_t *rec = gs + row * gstride;
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
         int j = lig + it * LPR;
-        if (j < d4) rec[4 + j] = (uint8_t)sign_bits<DIST>(x.v[it]);
+        if (j < d4) rec[j] = (uint8_t)sign_bits<DIST>(x.v[it]);
     }
-    if (lig == 0) *reinterpret_cast<float *>(rec) = coef;
+    if (lig == 0) coefs[row] = coef;
 }
 
 template <int LPR, int ITERS, int DIST>
@@ -65,7 +65,8 @@ __device__ inline void finish_loss_body(const float *__restrict__ partials, int 
 // FROM_Y = true : it is row `row` of the dense buffer G (TransR: y = M_r (h - t) + r was put there by
 //                 the projection kernel), and dL/dy overwrites it in place; every row is read and then
 //                 written by one group only.
-// PACKED (L1 kinds, gathered rows only): dL/dx is written as records of gstride bytes at G (coefficient + sign bytes).
+// PACKED (L1 kinds, gathered rows only): dL/dx is written as records of gstride bytes at G (sign bytes), the
+// rows' coefficients behind the records of the batch.
 // `block` is the index of the workgroup among those of the forward pass (the launch may hold others).
 template <int LPR, int ITERS, int DIST, bool FROM_Y, bool PACKED>
 __device__ inline void forward_stacked_body(const int block, const ForwardArgs &a)
@@ -77,6 +78,9 @@ __device__ inline void forward_stacked_body(const int block, const ForwardArgs &
     const float margin = a.margin, scale = a.scale;
     float *__restrict__ scores = a.scores;
     float *G = a.G;
+    float *gcoef = PACKED ? reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(a.G) +
+                                                      packed_coef_offset((int64_t)b * (1 + k), gstride))
+                          : nullptr;
     float *__restrict__ loss_partials = a.loss_partials;
     static_assert(!PACKED || (is_sign_kind(DIST) && !FROM_Y), "packed rows need an L1-kind distance");
     constexpr int GROUPS = kThreads / LPR;
@@ -136,8 +140,8 @@ __device__ inline void forward_stacked_body(const int block, const ForwardArgs &
                     if (lig == 0) scores[row] = dneg;
                     if (active) { hinge_sum += arg; ++n_active; }
                     if (PACKED)
-                        write_grad_row_packed<LPR, ITERS, DIST>(reinterpret_cast<uint8_t *>(G), gstride, row, d4, lig,
-                                                                xn[q], active ? -scale * wr : 0.f);
+                        write_grad_row_packed<LPR, ITERS, DIST>(reinterpret_cast<uint8_t *>(G), gstride, gcoef, row, d4,
+                                                                lig, xn[q], active ? -scale * wr : 0.f);
                     else
                         write_grad_row<LPR, ITERS, DIST>(G + row * dim, d4, lig, xn[q], active ? -scale * wr : 0.f,
                                                          nneg);
@@ -145,7 +149,7 @@ __device__ inline void forward_stacked_body(const int block, const ForwardArgs &
             }
         }
         if (PACKED)
-            write_grad_row_packed<LPR, ITERS, DIST>(reinterpret_cast<uint8_t *>(G), gstride, i, d4, lig, xp,
+            write_grad_row_packed<LPR, ITERS, DIST>(reinterpret_cast<uint8_t *>(G), gstride, gcoef, i, d4, lig, xp,
                                                     (float)n_active * scale * wr);
         else
             write_grad_row<LPR, ITERS, DIST>(G + i * dim, d4, lig, xp, (float)n_active * scale * wr, npos);

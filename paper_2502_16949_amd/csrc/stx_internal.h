@@ -212,7 +212,8 @@ stx_status launch_copy_f32(stx_ctx *, float *dst, const float *src, int64_t n);
 // stx_backward.hip
 // out_rows[segment] = signed sum of source rows over the sorted entries [e_begin, e_end); entries
 // before `split` read src_a, the others src_b (both with ld_src floats per row, `width` of them used).
-// packed_src: src_a holds packed L1-kind records (see packed_stride), ld_src is the record size in bytes.
+// packed_src: src_a holds packed L1-kind sign records (see packed_stride), ld_src is the record size in bytes,
+// and src_b the rows' coefficients.
 // second: another product of the same row width over the entries [e_begin, e_end), all reading `src`, that
 // runs in the same two launches (its workgroups follow the first product's).
 // tail_off (dense source rows only): entries with value -1 read their row tail_off floats further on.
@@ -264,15 +265,18 @@ stx_status launch_transr_sgd_proj(stx_ctx *, const stx_incidence *, stx_params *
 stx_status launch_forward_transh(stx_ctx *, const stx_incidence *, const stx_params *, float *scores, float *loss);
 stx_status launch_finish_loss(stx_ctx *, int n_partials, float scale, float *loss);
 
-// TransE / TorusE with an L1-kind distance keep dL/dx packed inside gbuf[0]: one record per row, the
-// fp32 coefficient first and dim/4 sign bytes after it, padded to a multiple of 64 bytes so that a
-// record never straddles more cache lines than it must (one line at dim 128).
+// TransE / TorusE with an L1-kind distance keep dL/dx packed inside gbuf[0]: per row a record of dim/4 sign
+// bytes, padded to a multiple of 32 bytes (one 32-byte memory sector at dim 128, which is what a random
+// read of it costs), and, in an array of their own behind the records of the batch, the rows' fp32
+// coefficients (4 bytes a row: 5 MB at 1.3 M rows, read out of the caches).
 inline bool packed_grad(const stx_ctx *c)
 {
     return (c->cfg.model == STX_TRANSE || c->cfg.model == STX_TORUSE) &&
            (c->cfg.dist == STX_L1 || c->cfg.dist == STX_TORUS_L1);
 }
-inline int packed_stride(int dim) { return (dim / 4 + 4 + 63) / 64 * 64; }
+inline int packed_stride(int dim) { return (dim / 4 + 31) / 32 * 32; }
+// byte offset of the coefficient array from the start of the records of a batch of `rows` rows
+__host__ __device__ inline int64_t packed_coef_offset(int64_t rows, int stride) { return (rows * stride + 255) / 256 * 256; }
 
 inline stx_status hip_ok(hipError_t e) { return e == hipSuccess ? STX_OK : STX_ERR_HIP; }
 
