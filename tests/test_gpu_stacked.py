@@ -128,6 +128,7 @@ STEP_CASES = [
     ("toruse", "torus_l2", 500, 7, 600, 2, 64, 1.05),
     ("transe", "l2_sq", 400, 9, 777, 3, 128, 1.1),     # squared L2 norm (Table 2, TransC row)
     ("transe", "l2_sq", 200, 5, 200, 1, 1024, 0.0),
+    ("transe", "l1", 200, 5, 40, 130, 64, 0.0),        # more negatives than a packed row's one-byte count holds
 ]
 
 
