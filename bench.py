@@ -95,16 +95,18 @@ def parse():
     return ap.parse_args()
 
 
-def kernel_work(wl, kernel, rows, touched, fused=False, rides=False):
+def kernel_work(wl, kernel, rows, touched, fused=False, rides=False, segw=False):
     """Algorithmic work of ONE launch of `kernel` on a full batch: (amount, unit, bound, peak).
     row = 4*dim bytes.  rows = b*(1+k) matrix rows, nnz = 3*rows, touched = distinct columns.
     rides: the launch of k_seg_reduce also runs the next batch's k_emit (about 28 B per entry: indices in, CSR
-    arrays, keys and negatives out), that of k_seg_fixup its first scatter pass (16 B per entry)."""
+    arrays, keys and negatives out), that of k_seg_fixup its first scatter pass (16 B per entry).
+    segw: the launch of k_seg_reduce also runs the last kernel of this batch's build (sorted key and payload in,
+    segment, row, packed entry and sign out: 21 B per entry)."""
     row = 4 * wl.dim
     nnz = 3 * rows
-    if kernel == "k_seg_reduce" and rides:
-        w, unit, bound, peak = kernel_work(wl, kernel, rows, touched, fused, False)
-        return w + nnz * 28, unit, bound, peak
+    if kernel == "k_seg_reduce" and (rides or segw):
+        w, unit, bound, peak = kernel_work(wl, kernel, rows, touched, fused, False, False)
+        return w + nnz * ((28 if rides else 0) + (21 if segw else 0)), unit, bound, peak
     if kernel == "k_seg_fixup" and rides:
         return nnz * 16, "GB/s", "hbm", HBM_PEAK_GBS
     if kernel in ("k_fwd_hist", "k_fwdh_hist"):      # the forward pass and a histogram pass (4 B per key) in one launch
@@ -406,6 +408,10 @@ def main():
     rides = (args.api == "step" and not args.no_lookahead and wl.model in ("transe", "toruse", "transh")
              and wl.n_ent + wl.n_rel <= 65536 and 3 * wl.rows_per_batch <= (1 << 18) and wl.dim <= 256)
 
+    # the one-call step leaves the last kernel of the build to the launch of the transposed product (rows of one
+    # float4 per lane, not TransR)
+    segw = args.api == "step" and wl.model != "transr" and wl.dim <= 256
+
     h, r, t = W.make_graph(wl)
     tabs = W.make_tables(wl)
     hd, rd, td = (torch.from_numpy(a).to(dev) for a in (h, r, t))
@@ -522,9 +528,14 @@ def main():
     # ---- roofline of the dominant kernel.  The mean launch time covers every batch of the timed region
     # (the partial last batch of an epoch included), so the work figure is averaged the same way. ----------
     mean_rows = rows_done / args.steps
-    work, unit, bound, peak = kernel_work(wl, kernel, mean_rows, u_last * mean_rows / wl.rows_per_batch, fused, rides)
-    kernel_note = ("this launch also runs the first build kernel of the next batch (about 28 B per entry, counted)"
-                   if rides and kernel == "k_seg_reduce" else "")
+    work, unit, bound, peak = kernel_work(wl, kernel, mean_rows, u_last * mean_rows / wl.rows_per_batch, fused, rides,
+                                          segw)
+    kernel_note = ""
+    if kernel == "k_seg_reduce" and (rides or segw):
+        kernel_note = ("this launch also runs " +
+                       " and ".join((["the last kernel of this batch's build (21 B per entry)"] if segw else []) +
+                                    (["the first build kernel of the next batch (about 28 B per entry)"] if rides else [])) +
+                       ", counted")
     per_launch = kernel_n * prof_every / args.steps if args.steps else 0
     achieved = (work / (kernel_us * 1e-6)) / (1e9 if unit == "GB/s" else 1e12) if kernel_us > 0 else 0.0
     roofline = {"bound": bound, "kernel": kernel, "achieved": round(achieved, 1), "peak": peak, "unit": unit,
@@ -584,7 +595,8 @@ def main():
             if kname == kernel or us <= 0:
                 continue
             try:
-                w, unit, bound, peak = kernel_work(wl, kname, mean_rows, u_last * mean_rows / wl.rows_per_batch, fused, rides)
+                w, unit, bound, peak = kernel_work(wl, kname, mean_rows, u_last * mean_rows / wl.rows_per_batch, fused, rides,
+                                                   segw)
             except ValueError:
                 continue
             ach = w / (us * 1e-6) / (1e9 if unit == "GB/s" else 1e12)

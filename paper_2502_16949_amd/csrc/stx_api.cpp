@@ -84,7 +84,7 @@ Layout make_layout(const stx_config *c)
     {
         const int64_t words = (c->n_ent + c->n_rel + 31) / 32;
         L.map_words = words <= kMapMaxWords ? (int)words : 0;
-        L.colmap = take((size_t)2 * L.map_words * 4 + 4);
+        L.colmap = take((size_t)3 * L.map_words * 4 + 4);
     }
     if (c->model == STX_TRANSR) {
         // every relation segment adds at most one item that is not full
@@ -216,6 +216,8 @@ stx_status stx_create(const stx_config *cfg, void *workspace, size_t workspace_b
     c->map_cur = 0;
     c->colmap[0] = L.map_words ? (uint32_t *)(base + L.colmap) : nullptr;
     c->colmap[1] = L.map_words ? c->colmap[0] + L.map_words : nullptr;
+    c->colmap[2] = L.map_words ? c->colmap[1] + L.map_words : nullptr;
+    c->segw.allowed = c->segw.armed = false;
     s = launch_clear_ctrl(c);
     if (s == STX_OK) s = launch_clear_maps(c);
     if (s == STX_OK) s = launch_clear_rel_counts(c);
@@ -590,8 +592,11 @@ stx_status stx_train_step(stx_ctx *ctx, const stx_batch *bt, stx_incidence *inc,
     SampleArgs sa{bt->neg_h, bt->neg_t, bt->seed,
                   (bt->epoch * (uint64_t)bt->m_total + (uint64_t)bt->global_offset) * (uint64_t)k};
     StepFusion fusion{p, scores, loss, false, false, 0, 1.0f};
+    // the fused transposed product of one float4 per lane can run the build's last kernel in its own launch
+    ctx->segw.allowed = ctx->cfg.model != STX_TRANSR && row_launch(ctx->cfg.dim).iters == 1;
     s = launch_build(ctx, bt->h, bt->r, bt->t, nullptr, nullptr, b, k, inc, &sa, &fusion);
-    if (s != STX_OK) return s;
+    ctx->segw.allowed = false;
+    if (s != STX_OK) { launch_seg_write_late(ctx); return s; }
     if (!fusion.forward_done) {
         ctx->defer_finish = ctx->cfg.model == STX_TRANSR;   // its loss sum rides in the backward pass's first launch
         s = stx_forward(ctx, inc, p, scores, loss);
@@ -601,13 +606,17 @@ stx_status stx_train_step(stx_ctx *ctx, const stx_batch *bt, stx_incidence *inc,
         ctx->fwd_inc = inc;
         ctx->fwd_rows = inc->n_rows;
     }
-    if (s != STX_OK) return s;
+    if (s != STX_OK) { launch_seg_write_late(ctx); return s; }
     // the next batch's first build kernel may ride in the launch of the transposed product
     if (bt->next && b > 0) prepare_emit_ahead(ctx, bt->next, inc);
     s = stx_backward_sgd(ctx, inc, p, g, lr);
     if (!ctx->ahead.done && ctx->ahead.armed) {   // no launch could take it: the maps go back to their roles
         ctx->ahead.armed = false;
-        ctx->map_cur ^= 1;
+        ctx->map_cur = (ctx->map_cur + 2) % 3;
+    }
+    if (ctx->segw.armed) {   // no launch took the build's last kernel along
+        const stx_status s2 = launch_seg_write_late(ctx);
+        if (s == STX_OK) s = s2;
     }
     ctx->ahead.armed = ctx->ahead.scatter_armed = false;
     if (ctx->fin_n > 0) {   // nothing took the deferred loss sum along (or the backward pass failed)

@@ -26,6 +26,7 @@
 // memory round trip.
 #include "stx_emit_body.h"
 #include "stx_rowops.h"
+#include "stx_segw_body.h"
 #include "stx_sort_body.h"
 
 namespace stx {
@@ -40,6 +41,11 @@ struct EmitAhead {
 struct ScatterAhead {
     ScatterArgs args;
     int ntiles;
+};
+struct SegWriteRide {
+    SegWriteArgs args;
+    int ntiles;
+    int use_map;
 };
 
 enum { HAS_FIRST = 1, FIRST_CONT = 2, HAS_LAST = 4 };
@@ -162,16 +168,28 @@ __device__ inline void apply_update(float *__restrict__ row, int d4, int lig, co
 // PACKED: the source rows are records of ld_src bytes at src_a (dim/4 sign bytes) with their coefficients in
 // src_b, as the forward pass of an L1-kind distance stores them; values and summation order are the same as with
 // dense rows, so both forms give the same bits.
-template <int LPR, int ITERS, bool PACKED, int CHUNK, bool FUSED, bool EMIT>
+// RAW: `packed` and `seg_id` are the sorted payloads and keys of the build instead (a lane derives its entry's
+// row, sign, column and whether it heads a segment from them), and the first sw.ntiles workgroups run the
+// build's last kernel, whose arrays nothing reads before the fix-up launch.
+template <int LPR, int ITERS, bool PACKED, int CHUNK, bool FUSED, bool EMIT, bool RAW>
 __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restrict__ packed,
                                                          const int32_t *__restrict__ seg_id, int32_t e_begin,
                                                          int32_t e_end, const float *__restrict__ src_a,
                                                          const float *__restrict__ src_b, int32_t split,
                                                          int ld_src, int tail_off, int d4, float *__restrict__ out_rows,
                                                          int ld_out, float *__restrict__ partials, FusedArgs fu,
-                                                         SegSecond sec, EmitAhead ea)
+                                                         SegSecond sec, EmitAhead ea, SegWriteRide sw)
 {
     int block = (int)blockIdx.x;
+    if constexpr (RAW) {
+        static_assert(FUSED, "the segment of an entry is not known here");
+        if (block < sw.ntiles) {      // uniform in the workgroup
+            if (sw.use_map) seg_write_body<true>(block, sw.ntiles, sw.args);
+            else seg_write_body<false>(block, sw.ntiles, sw.args);
+            return;
+        }
+        block -= sw.ntiles;
+    }
     if constexpr (EMIT) {
         if (block < ea.ntiles) {      // uniform in the workgroup
             emit_body<kSortItems, true, true, false>(block, ea.ntiles, ea.args);
@@ -224,17 +242,31 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
     int info = 0;
     if (ec0 < e_end) {
         const int n = ec1 - ec0;
-        const int32_t meta = (lig < CHUNK && ec0 + lig < ec1) ? packed[ec0 + lig] : 0;   // 0: row 0, a safe address
+        int32_t meta = 0;                                  // 0: row 0, a safe address
         int32_t colv = 0;                                  // FUSED: the column of this lane's entry
-        if (FUSED && lig < CHUNK && ec0 + lig < ec1)
-            colv = fu.cols_sorted ? fu.cols_sorted[ec0 + lig] : fu.touched_cols[seg_id[ec0 + lig]];
+        bool right_head = true;                            // the entry after the chunk heads a segment
+        if constexpr (RAW) {
+            if (lig < CHUNK && ec0 + lig < ec1) {
+                const int32_t e = ec0 + lig;
+                const int32_t pos = packed[e], kc = seg_id[e], kp = e > 0 ? seg_id[e - 1] : -1;
+                const int32_t row = pos / 3;
+                meta = (row << 2) | (kc != kp ? 2 : 0) | (pos - 3 * row == 2 ? 1 : 0);
+                colv = kc;
+            }
+            if (ec1 < e_end) right_head = seg_id[ec1] != seg_id[ec1 - 1];
+        } else {
+            if (lig < CHUNK && ec0 + lig < ec1) meta = packed[ec0 + lig];
+            if (FUSED && lig < CHUNK && ec0 + lig < ec1)
+                colv = fu.cols_sorted ? fu.cols_sorted[ec0 + lig] : fu.touched_cols[seg_id[ec0 + lig]];
+            if (ec1 < e_end) right_head = (packed[ec1] & 2) != 0;
+        }
         Acc<ITERS> xcur;                                   // FUSED: table row of the run that is being summed
         int32_t colcur = 0;
         xcur.zero();
         const int32_t meta0 = __shfl(meta, 0, LPR);
         const bool first_open = (ec0 > e_begin) && !(meta0 & 2);
-        const bool right_open = (ec1 < e_end) && !(packed[ec1] & 2);
-        int32_t cur_seg = seg_id[ec0];
+        const bool right_open = (ec1 < e_end) && !right_head;
+        int32_t cur_seg = RAW ? 0 : seg_id[ec0];
         int nflush = 0;
         Acc<ITERS> acc;
         acc.zero();
@@ -645,6 +677,13 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
     // the next batch's first build kernels, if they are waiting, ride in these launches (fused products of one
     // float4 per lane): k_emit in that of k_seg_reduce, the first scatter pass in that of k_seg_fixup (which
     // exists when the product has more than one tile)
+    // ... and so does the last kernel of this batch's build when it was left waiting (stx_train_step); a
+    // product that cannot take it runs after it
+    const bool raw_now = fused && ITERS == 1 && c->segw.armed && c->sorted_inc == inc;
+    if (c->segw.armed && !raw_now) launch_seg_write_late(c);
+    const SegWriteRide no_segw{};
+    const SegWriteRide segw = raw_now ? SegWriteRide{c->segw.args, c->segw.ntiles, c->segw.use_map ? 1 : 0} : no_segw;
+    if (raw_now) c->segw.armed = false;
     const EmitAhead no_emit{};
     const ScatterAhead no_ride{};
     const bool emit_now = fused && ITERS == 1 && c->ahead.armed && !c->ahead.done;
@@ -662,9 +701,10 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
     do {                                                                                                        \
         {                                                                                                       \
             ProfScope prof(c, "k_seg_reduce");                                                                  \
-            hipLaunchKernelGGL((k_seg_reduce<LPR, 1, P, CH, F, false>), grid, dim3(kThreads), 0, c->stream,     \
-                               inc->at_packed, inc->at_seg_id, e_begin, e_end, src_a, src_b, split, ld_src,     \
-                               tail_off, width / 4, out_rows, ld_out, c->partials, fu, sec, no_emit);           \
+            hipLaunchKernelGGL((k_seg_reduce<LPR, 1, P, CH, F, false, false>), grid, dim3(kThreads), 0,         \
+                               c->stream, inc->at_packed, inc->at_seg_id, e_begin, e_end, src_a, src_b, split,  \
+                               ld_src, tail_off, width / 4, out_rows, ld_out, c->partials, fu, sec, no_emit,    \
+                               no_segw);                                                                        \
         }                                                                                                       \
         if (ntiles > 1) {                                                                                       \
             ProfScope prof(c, "k_seg_fixup");                                                                   \
@@ -684,16 +724,26 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
     do {                                                                                                        \
         {                                                                                                       \
             ProfScope prof(c, "k_seg_reduce");                                                                  \
-            if (F && ITERS == 1 && emit_now)                                                                    \
-                hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH, F, F && ITERS == 1>),                       \
+            if (F && ITERS == 1 && emit_now && raw_now)                                                         \
+                hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH, F, F && ITERS == 1, F && ITERS == 1>),      \
+                                   dim3(ntiles + ahead.ntiles + segw.ntiles), dim3(kThreads), 0, c->stream,     \
+                                   segw.args.pay, segw.args.keys, e_begin, e_end, src_a, src_b, split, ld_src,  \
+                                   tail_off, width / 4, out_rows, ld_out, c->partials, fu, sec, ahead, segw);   \
+            else if (F && ITERS == 1 && raw_now)                                                                \
+                hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH, F, false, F && ITERS == 1>),                \
+                                   dim3(ntiles + segw.ntiles), dim3(kThreads), 0, c->stream, segw.args.pay,     \
+                                   segw.args.keys, e_begin, e_end, src_a, src_b, split, ld_src, tail_off,       \
+                                   width / 4, out_rows, ld_out, c->partials, fu, sec, no_emit, segw);           \
+            else if (F && ITERS == 1 && emit_now)                                                               \
+                hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH, F, F && ITERS == 1, false>),                \
                                    dim3(ntiles + ahead.ntiles), dim3(kThreads), 0, c->stream, inc->at_packed,   \
                                    inc->at_seg_id, e_begin, e_end, src_a, src_b, split, ld_src, tail_off,       \
-                                   width / 4, out_rows, ld_out, c->partials, fu, sec, ahead);                   \
+                                   width / 4, out_rows, ld_out, c->partials, fu, sec, ahead, no_segw);          \
             else                                                                                                \
-                hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH, F, false>), dim3(ntiles), dim3(kThreads),   \
-                                   0, c->stream, inc->at_packed, inc->at_seg_id, e_begin, e_end, src_a, src_b,  \
-                                   split, ld_src, tail_off, width / 4, out_rows, ld_out, c->partials, fu, sec,  \
-                                   no_emit);                                                                    \
+                hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH, F, false, false>), dim3(ntiles),            \
+                                   dim3(kThreads), 0, c->stream, inc->at_packed, inc->at_seg_id, e_begin,       \
+                                   e_end, src_a, src_b, split, ld_src, tail_off, width / 4, out_rows, ld_out,   \
+                                   c->partials, fu, sec, no_emit, no_segw);                                     \
         }                                                                                                       \
         if (ntiles > 1) {                                                                                       \
             ProfScope prof(c, "k_seg_fixup");                                                                   \

@@ -20,6 +20,7 @@
 // With few tiles every scatter workgroup derives its own offsets from the raw table (a few coalesced
 // reads per thread); with many tiles a small k_super_sums first adds the histograms up in groups of tiles.
 #include "stx_emit_body.h"
+#include "stx_segw_body.h"
 #include "stx_sort_body.h"
 
 namespace stx {
@@ -108,130 +109,10 @@ __global__ __launch_bounds__(kThreads) void k_seg_count(const int32_t *__restric
     if (tid == 0) tile_heads[blockIdx.x] = s_cnt;
 }
 
-// Per sorted entry: its segment, row, sign and packed form; per segment: its column and first entry.
-// Thread t of a tile owns the 8 consecutive entries base + 8t .. base + 8t + 7.
-// MAP: the segment of an entry is the rank of its column in the presence bitmap (every workgroup scans
-// the map itself); otherwise it is counted from the heads of the earlier tiles (k_seg_count).
 template <bool MAP>
-__global__ __launch_bounds__(kThreads) void k_seg_write(const int32_t *__restrict__ keys,
-                                                        const int32_t *__restrict__ pay, int32_t nnz,
-                                                        const int32_t *__restrict__ tile_heads,
-                                                        int32_t *__restrict__ n_touched,
-                                                        int32_t *__restrict__ touched_cols,
-                                                        int32_t *__restrict__ seg_ptr, int32_t *__restrict__ row_idx,
-                                                        int8_t *__restrict__ sign, int32_t *__restrict__ seg_id,
-                                                        int32_t *__restrict__ packed, ColMap map)
+__global__ __launch_bounds__(kThreads) void k_seg_write(SegWriteArgs a)
 {
-    __shared__ int32_t s_base;
-    __shared__ uint32_t s_word[MAP ? kMapMaxWords : 1];
-    __shared__ int32_t s_pref[MAP ? kMapMaxWords : 1];
-    const int tid = threadIdx.x;
-    if (tid == 0) s_base = 0;
-    __syncthreads();
-    int32_t map_total = 0;
-    if (MAP) {   // thread t owns words [t*wpt, (t+1)*wpt): set bits below each word
-        constexpr int WPT = kMapMaxWords / kThreads;
-        const int wpt = (map.words + kThreads - 1) / kThreads;
-        uint32_t wv[WPT];
-        int32_t mine = 0;
-#pragma unroll
-        for (int q = 0; q < WPT; ++q) {
-            const int w = tid * wpt + q;
-            wv[q] = (q < wpt && w < map.words) ? map.cur[w] : 0u;
-            mine += __popc(wv[q]);
-        }
-        int32_t run = block_exclusive_scan(mine, &map_total);
-#pragma unroll
-        for (int q = 0; q < WPT; ++q) {
-            const int w = tid * wpt + q;
-            if (q < wpt && w < map.words) { s_word[w] = wv[q]; s_pref[w] = run; run += __popc(wv[q]); }
-        }
-        __syncthreads();
-    } else {   // segments that start in earlier tiles
-        int32_t a = 0;
-        for (int t = tid; t < (int)blockIdx.x; t += kThreads) a += tile_heads[t];
-        if (a) atomicAdd(&s_base, a);
-    }
-    const int32_t e0 = blockIdx.x * kSegWTile + tid * kSegWItems;
-    int32_t kk[kSegWItems + 1];
-    kk[0] = (e0 > 0 && e0 - 1 < nnz) ? keys[e0 - 1] : -1;
-    if (e0 + kSegWItems <= nnz) {
-        const int4 a = *reinterpret_cast<const int4 *>(keys + e0), b = *reinterpret_cast<const int4 *>(keys + e0 + 4);
-        kk[1] = a.x; kk[2] = a.y; kk[3] = a.z; kk[4] = a.w; kk[5] = b.x; kk[6] = b.y; kk[7] = b.z; kk[8] = b.w;
-    } else {
-#pragma unroll
-        for (int i = 0; i < kSegWItems; ++i) kk[i + 1] = e0 + i < nnz ? keys[e0 + i] : -1;
-    }
-    int32_t cnt = 0;
-#pragma unroll
-    for (int i = 0; i < kSegWItems; ++i)
-        if (e0 + i < nnz && kk[i + 1] != kk[i]) ++cnt;
-    int32_t seg;
-    if (MAP) {
-        const int32_t c0 = kk[0];                                        // column of the entry before e0 (-1: none)
-        seg = c0 < 0 ? -1 : s_pref[c0 >> 5] + __popc(s_word[c0 >> 5] & ((1u << (c0 & 31)) - 1u));
-        if (blockIdx.x == gridDim.x - 1 && tid == 0) {
-            n_touched[0] = map_total;
-            seg_ptr[map_total] = nnz;
-        }
-    } else {
-        int32_t tile_total;
-        const int32_t before = block_exclusive_scan(cnt, &tile_total);   // its barriers also publish s_base
-        seg = s_base + before - 1;                                       // segment of the entry before e0
-        if (blockIdx.x == gridDim.x - 1 && tid == 0) {
-            n_touched[0] = s_base + tile_total;
-            seg_ptr[s_base + tile_total] = nnz;
-        }
-    }
-    int32_t o_seg[kSegWItems], o_row[kSegWItems], o_pk[kSegWItems];
-    int8_t o_sign[kSegWItems];
-    const bool whole = e0 + kSegWItems <= nnz;   // e0 is a multiple of 8: 32-byte vector accesses are aligned
-    int32_t pp[kSegWItems];
-    if (whole) {
-        const int4 a = *reinterpret_cast<const int4 *>(pay + e0), b = *reinterpret_cast<const int4 *>(pay + e0 + 4);
-        pp[0] = a.x; pp[1] = a.y; pp[2] = a.z; pp[3] = a.w; pp[4] = b.x; pp[5] = b.y; pp[6] = b.z; pp[7] = b.w;
-    } else {
-#pragma unroll
-        for (int i = 0; i < kSegWItems; ++i) pp[i] = e0 + i < nnz ? pay[e0 + i] : 0;
-    }
-#pragma unroll
-    for (int i = 0; i < kSegWItems; ++i) {
-        int32_t e = e0 + i;
-        bool head = e < nnz && kk[i + 1] != kk[i];   // e == 0: kk[0] = -1 differs from every column id
-        if (head) {
-            ++seg;
-            touched_cols[seg] = kk[i + 1];
-            seg_ptr[seg] = e;
-        }
-        int32_t row = pp[i] / 3;
-        int32_t neg = (pp[i] - 3 * row) == 2 ? 1 : 0;
-        o_seg[i] = seg;
-        o_row[i] = row;
-        o_sign[i] = neg ? (int8_t)-1 : (int8_t)1;
-        o_pk[i] = (row << 2) | (head ? 2 : 0) | neg;
-    }
-    if (whole) {
-        static_assert(kSegWItems == 8, "vector stores below assume 8 entries per thread");
-        *reinterpret_cast<int4 *>(seg_id + e0) = make_int4(o_seg[0], o_seg[1], o_seg[2], o_seg[3]);
-        *reinterpret_cast<int4 *>(seg_id + e0 + 4) = make_int4(o_seg[4], o_seg[5], o_seg[6], o_seg[7]);
-        *reinterpret_cast<int4 *>(row_idx + e0) = make_int4(o_row[0], o_row[1], o_row[2], o_row[3]);
-        *reinterpret_cast<int4 *>(row_idx + e0 + 4) = make_int4(o_row[4], o_row[5], o_row[6], o_row[7]);
-        *reinterpret_cast<int4 *>(packed + e0) = make_int4(o_pk[0], o_pk[1], o_pk[2], o_pk[3]);
-        *reinterpret_cast<int4 *>(packed + e0 + 4) = make_int4(o_pk[4], o_pk[5], o_pk[6], o_pk[7]);
-        uint32_t s0 = 0, s1 = 0;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            s0 |= (uint32_t)(uint8_t)o_sign[i] << (8 * i);
-            s1 |= (uint32_t)(uint8_t)o_sign[4 + i] << (8 * i);
-        }
-        *reinterpret_cast<uint2 *>(sign + e0) = make_uint2(s0, s1);
-    } else {
-#pragma unroll
-        for (int i = 0; i < kSegWItems; ++i) {
-            int32_t e = e0 + i;
-            if (e < nnz) { seg_id[e] = o_seg[i]; row_idx[e] = o_row[i]; sign[e] = o_sign[i]; packed[e] = o_pk[i]; }
-        }
-    }
+    seg_write_body<MAP>((int)blockIdx.x, (int)gridDim.x, a);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -245,7 +126,7 @@ stx_status launch_clear_maps(stx_ctx *c)
 {
     if (c->map_words == 0) return STX_OK;
     // the two maps are adjacent in the workspace
-    hipLaunchKernelGGL(k_clear_words, dim3(8), dim3(kThreads), 0, c->stream, c->colmap[0], 2 * c->map_words);
+    hipLaunchKernelGGL(k_clear_words, dim3(8), dim3(kThreads), 0, c->stream, c->colmap[0], 3 * c->map_words);
     c->map_cur = 0;
     return hip_ok(hipGetLastError());
 }
@@ -286,8 +167,8 @@ bool prepare_emit_ahead(stx_ctx *c, const stx_batch *next, stx_incidence *inc)
     const uint64_t base_ctr = (next->epoch * (uint64_t)next->m_total + (uint64_t)next->global_offset) * (uint64_t)next->k;
     const BatchPtrs bp{next->h, next->r, next->t, nullptr, nullptr, next->b, next->k > 0 ? next->k : 1,
                        next->neg_h, next->neg_t, next->seed, base_ctr};
-    const ColMap map{c->colmap[c->map_cur], c->colmap[c->map_cur ^ 1], c->map_words};
-    c->map_cur ^= 1;
+    const ColMap map{c->colmap[c->map_cur], c->colmap[(c->map_cur + 1) % 3], c->map_words};
+    c->map_cur = (c->map_cur + 1) % 3;
     c->ahead.args = EmitArgs{bp, (int32_t)c->cfg.n_ent, (int32_t)c->cfg.n_rel, (int32_t)nnz, inc->a_rowptr, inc->a_colidx,
                              inc->a_vals, c->keys[2], 1 << bits0, ntiles, c->table, c->ctrl, map,
                              RelCnt{nullptr, nullptr, 0}};
@@ -309,6 +190,7 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
                         StepFusion *fusion)
 {
     hipStream_t s = c->stream;
+    if (c->segw.armed) launch_seg_write_late(c);   // (a build whose last kernel nobody took along)
     c->sorted_inc = nullptr;
     c->sorted_keys = nullptr;
     c->cnt_inc = nullptr;
@@ -342,8 +224,8 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
     if (emitted) {
         map = pa.map;                    // (the maps changed roles when it was prepared)
     } else if (use_map) {
-        map = ColMap{c->colmap[c->map_cur], c->colmap[c->map_cur ^ 1], c->map_words};
-        c->map_cur ^= 1;
+        map = ColMap{c->colmap[c->map_cur], c->colmap[(c->map_cur + 1) % 3], c->map_words};
+        c->map_cur = (c->map_cur + 1) % 3;
     }
 
     int bits0 = c->sort_bits < c->digit_bits ? c->sort_bits : c->digit_bits;
@@ -425,17 +307,27 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
         ProfScope prof(c, "k_seg_count");
         hipLaunchKernelGGL(k_seg_count, dim3(nseg), dim3(kThreads), 0, s, c->keys[cur], nnz, c->tile_heads);
     }
-    ProfScope prof(c, "k_seg_write");
-    if (use_map)
-        hipLaunchKernelGGL(k_seg_write<true>, dim3(nseg), dim3(kThreads), 0, s, c->keys[cur], c->pay[cur], nnz,
-                           c->tile_heads, inc->n_touched, inc->at_touched_cols, inc->at_seg_ptr, inc->at_row_idx,
-                           inc->at_sign, inc->at_seg_id, inc->at_packed, map);
-    else
-        hipLaunchKernelGGL(k_seg_write<false>, dim3(nseg), dim3(kThreads), 0, s, c->keys[cur], c->pay[cur], nnz,
-                           c->tile_heads, inc->n_touched, inc->at_touched_cols, inc->at_seg_ptr, inc->at_row_idx,
-                           inc->at_sign, inc->at_seg_id, inc->at_packed, map);
+    c->segw.args = SegWriteArgs{c->keys[cur], c->pay[cur], nnz, c->tile_heads, inc->n_touched, inc->at_touched_cols,
+                                inc->at_seg_ptr, inc->at_row_idx, inc->at_sign, inc->at_seg_id, inc->at_packed, map};
+    c->segw.ntiles = nseg;
+    c->segw.use_map = use_map;
+    c->segw.armed = true;
     c->sorted_inc = inc;
     c->sorted_keys = c->keys[cur];
+    if (c->segw.allowed) return hip_ok(hipGetLastError());   // the transposed product takes it along
+    return launch_seg_write_late(c);
+}
+
+// The last kernel of the build that is waiting, if one is.
+stx_status launch_seg_write_late(stx_ctx *c)
+{
+    if (!c->segw.armed) return STX_OK;
+    c->segw.armed = false;
+    ProfScope prof(c, "k_seg_write");
+    if (c->segw.use_map)
+        hipLaunchKernelGGL(k_seg_write<true>, dim3(c->segw.ntiles), dim3(kThreads), 0, c->stream, c->segw.args);
+    else
+        hipLaunchKernelGGL(k_seg_write<false>, dim3(c->segw.ntiles), dim3(kThreads), 0, c->stream, c->segw.args);
     return hip_ok(hipGetLastError());
 }
 

@@ -51,7 +51,8 @@ struct BatchPtrs {
 // Presence bitmap of the batch's columns (one bit per column of [E;R]), kept when the table has few
 // enough columns for a workgroup to scan the whole map: the segment of a column is then its rank among
 // the set bits, and k_seg_write needs no count of segment heads per tile from a kernel before it.
-// Two maps alternate: a build sets bits in one and clears the other, which the build before it used.
+// Three maps rotate: a build sets bits in one and clears the next one, which the build two before it used; the
+// map of the build just before it stays intact, because that build's last kernel may run late (SegWriteLate).
 struct ColMap {
     uint32_t *cur, *other;
     int words;
@@ -88,6 +89,27 @@ struct ScatterArgs {
     const int32_t *table, *super;
 };
 
+// Arguments of the last kernel of a build (k_seg_write, stx_segw_body.h), by value.
+struct SegWriteArgs {
+    const int32_t *keys, *pay;     // sorted
+    int32_t nnz;
+    const int32_t *tile_heads;
+    int32_t *n_touched, *touched_cols, *seg_ptr, *row_idx;
+    int8_t *sign;
+    int32_t *seg_id, *packed;
+    ColMap map;
+};
+
+// stx_train_step: the fused transposed product of one float4 per lane reads the sorted keys and payloads
+// itself, so the last kernel of the build need not run before it: it waits here (`armed`) and runs as extra
+// workgroups of that product's launch (the fix-up launch after it is the first reader of its arrays).
+struct SegWriteLate {
+    bool allowed, armed;
+    bool use_map;
+    SegWriteArgs args;
+    int ntiles;
+};
+
 // stx_train_step with a next batch: the first two kernels of the next build (k_emit, then the first scatter
 // pass of the sort) depend on nothing this step computes and run in the two launches of this step's transposed
 // product.  `armed`: prepared, waiting for its launch; `done`: it ran, and the next build may skip it if it is
@@ -122,8 +144,8 @@ struct stx_ctx {
     float *loss_partials;          // [fwd_blocks_max]
     float *partials;               // [(nnz_max/kSegTileMin + 2) * 2 * ld]
     float *gbuf[4];                // per-row buffers, rows_max x ld each (how many depends on the model)
-    uint32_t *colmap[2];           // presence bitmaps of the columns (adjacent), or null when the table is too wide
-    int map_words, map_cur;        // words per map (0: not kept); which map the next build fills
+    uint32_t *colmap[3];           // presence bitmaps of the columns (adjacent), or null when the table is too wide
+    int map_words, map_cur;        // words per map (0: not kept); which map the next build fills (they rotate)
     // TransR only: work items, bfloat16 operand copies of the projection matrices, transposed operand tiles
     int32_t *tr_items, *tr_dm_items, *tr_counts;
     uint16_t *tr_m16, *tr_m16t, *tr_xt, *tr_gyt;
@@ -150,6 +172,7 @@ struct stx_ctx {
     const stx_incidence *fwd_inc;  // incidence of the last stx_forward, null if none
     int64_t fwd_rows;
     stx::EmitAheadState ahead;
+    stx::SegWriteLate segw;
 };
 
 namespace stx {
@@ -192,6 +215,7 @@ stx_status launch_build(stx_ctx *, const int32_t *h, const int32_t *r, const int
 // Prepares the first kernel of the build of `next` (as stx_train_step would launch it) to run inside the next
 // fused transposed product of this context; false: this configuration or batch does not allow it.
 bool prepare_emit_ahead(stx_ctx *, const stx_batch *next, stx_incidence *inc);
+stx_status launch_seg_write_late(stx_ctx *);
 // stx_transr.hip: item lists and bf16 copies of M_r in the launch of the first scatter pass; false: not possible
 bool launch_prep_scatter(stx_ctx *, const stx_incidence *, const stx_params *, const ScatterArgs &);
 // stx_step.hip
