@@ -12,7 +12,7 @@ namespace {
 inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 struct Layout {
-    size_t ctrl, keys[3], pay[2], table, super, tile_heads, loss_partials, partials, gbuf[4], total;
+    size_t ctrl, keys[3], pay[2], cix[2], table, table1, super, tile_heads, loss_partials, partials, gbuf[4], total;
     size_t tr_items, tr_dm_items, tr_counts, tr_m16, tr_m16t, tr_xt, tr_gyt;
     size_t colmap, rel_cnt;
     int map_words;
@@ -66,7 +66,9 @@ Layout make_layout(const stx_config *c)
     L.ctrl = take(CTRL_WORDS * sizeof(int32_t));
     for (int i = 0; i < 3; ++i) L.keys[i] = take((size_t)L.nnz_max * 4);
     for (int i = 0; i < 2; ++i) L.pay[i] = take((size_t)L.nnz_max * 4);
+    for (int i = 0; i < 2; ++i) L.cix[i] = take((size_t)L.nnz_max * 4);
     L.table = take((size_t)256 * L.ntiles_max * 4);
+    L.table1 = take((size_t)256 * L.ntiles_max * 4);
     L.super = take((size_t)256 * (L.ntiles_max / kSuperTile + 1) * 4);
     L.tile_heads = take((size_t)(L.ntiles_max + 1) * 4);
     L.loss_partials = take((size_t)(L.fwd_blocks_max + 1) * 4);
@@ -175,6 +177,9 @@ stx_status stx_create(const stx_config *cfg, void *workspace, size_t workspace_b
     for (int i = 0; i < 3; ++i) c->keys[i] = (int32_t *)(base + L.keys[i]);
     for (int i = 0; i < 2; ++i) c->pay[i] = (int32_t *)(base + L.pay[i]);
     c->table = (int32_t *)(base + L.table);
+    c->table1 = (int32_t *)(base + L.table1);
+    for (int i = 0; i < 2; ++i) c->cix[i] = (int32_t *)(base + L.cix[i]);
+    c->cix_cur = 0;
     c->super = (int32_t *)(base + L.super);
     c->tile_heads = (int32_t *)(base + L.tile_heads);
     c->loss_partials = (float *)(base + L.loss_partials);
@@ -201,8 +206,9 @@ stx_status stx_create(const stx_config *cfg, void *workspace, size_t workspace_b
     c->fin_loss = nullptr;
     c->fwd_inc = nullptr;
     c->fwd_rows = 0;
-    c->ahead.armed = c->ahead.done = false;
-    c->ahead.scatter_armed = c->ahead.scatter_done = false;
+    c->ahead.armed = false;
+    c->ahead.emit_done = c->ahead.scatter_done = c->ahead.hist_done = false;
+    c->ahead.scatter_ok = c->ahead.hist_ok = false;
     c->ahead.inc = nullptr;
     c->sorted_inc = nullptr;
     c->sorted_keys = nullptr;
@@ -591,34 +597,45 @@ stx_status stx_train_step(stx_ctx *ctx, const stx_batch *bt, stx_incidence *inc,
     ctx->fwd_inc = nullptr;
     SampleArgs sa{bt->neg_h, bt->neg_t, bt->seed,
                   (bt->epoch * (uint64_t)bt->m_total + (uint64_t)bt->global_offset) * (uint64_t)k};
-    StepFusion fusion{p, scores, loss, false, false, 0, 1.0f};
+    // (the next batch's first build kernels may ride in this step's launches: the build prepares them)
+    StepFusion fusion{p, scores, loss, false, false, 0, 1.0f, b > 0 ? bt->next : nullptr, nullptr};
     // the fused transposed product of one float4 per lane can run the build's last kernel in its own launch
     ctx->segw.allowed = ctx->cfg.model != STX_TRANSR && row_launch(ctx->cfg.dim).iters == 1;
     s = launch_build(ctx, bt->h, bt->r, bt->t, nullptr, nullptr, b, k, inc, &sa, &fusion);
     ctx->segw.allowed = false;
-    if (s != STX_OK) { launch_seg_write_late(ctx); return s; }
+    // a stage of the next build that no launch took along: the buffers go back to their roles
+    auto unwind_ahead = [&]() {
+        if (ctx->ahead.armed && !ctx->ahead.emit_done) {
+            ctx->ahead.armed = false;
+            ctx->map_cur = (ctx->map_cur + 2) % 3;
+            ctx->cix_cur ^= 1;
+        }
+    };
+    if (s != STX_OK) { launch_seg_write_late(ctx); unwind_ahead(); return s; }
     if (!fusion.forward_done) {
         ctx->defer_finish = ctx->cfg.model == STX_TRANSR;   // its loss sum rides in the backward pass's first launch
         s = stx_forward(ctx, inc, p, scores, loss);
         ctx->defer_finish = false;
     } else {   // the forward pass shared a launch with the sort; the sum of the loss may still be missing
-        if (!fusion.finish_done) s = launch_finish_loss(ctx, fusion.n_partials, fusion.scale, loss);
+        if (!fusion.finish_done) {
+            if (ctx->segw.armed) {   // the launch that takes the build's last kernel along takes this sum as well
+                ctx->fin_n = fusion.n_partials;
+                ctx->fin_scale = fusion.scale;
+                ctx->fin_loss = loss;
+            } else {
+                s = launch_finish_loss(ctx, fusion.n_partials, fusion.scale, loss);
+            }
+        }
         ctx->fwd_inc = inc;
         ctx->fwd_rows = inc->n_rows;
     }
-    if (s != STX_OK) { launch_seg_write_late(ctx); return s; }
-    // the next batch's first build kernel may ride in the launch of the transposed product
-    if (bt->next && b > 0) prepare_emit_ahead(ctx, bt->next, inc);
+    if (s != STX_OK) { launch_seg_write_late(ctx); unwind_ahead(); return s; }
     s = stx_backward_sgd(ctx, inc, p, g, lr);
-    if (!ctx->ahead.done && ctx->ahead.armed) {   // no launch could take it: the maps go back to their roles
-        ctx->ahead.armed = false;
-        ctx->map_cur = (ctx->map_cur + 2) % 3;
-    }
+    unwind_ahead();
     if (ctx->segw.armed) {   // no launch took the build's last kernel along
         const stx_status s2 = launch_seg_write_late(ctx);
         if (s == STX_OK) s = s2;
     }
-    ctx->ahead.armed = ctx->ahead.scatter_armed = false;
     if (ctx->fin_n > 0) {   // nothing took the deferred loss sum along (or the backward pass failed)
         const stx_status s2 = launch_finish_loss(ctx, ctx->fin_n, ctx->fin_scale, ctx->fin_loss);
         ctx->fin_n = 0;

@@ -25,27 +25,25 @@
 // row of a run is fetched together with the run's first source row, so closing a run costs no extra
 // memory round trip.
 #include "stx_emit_body.h"
+#include "stx_forward_body.h"
 #include "stx_rowops.h"
 #include "stx_segw_body.h"
 #include "stx_sort_body.h"
 
 namespace stx {
 
-// The first two kernels of the next batch's build, riding in this step's launches: k_emit's workgroups in the
-// launch of k_seg_reduce (EMIT), those of the sort's first scatter pass in the launch of k_seg_fixup (RIDE).
-// They take the low block indices.
-struct EmitAhead {
-    EmitArgs args;
-    int ntiles;
-};
-struct ScatterAhead {
-    ScatterArgs args;
-    int ntiles;
-};
+// Work that rides in the launches of the transposed product, as workgroups with the low block indices: the last
+// kernel of this batch's build and the sum of the loss (SegWriteRide), and one stage of the next batch's build
+// per launch (EmitAhead, ScatterAhead, HistAhead).
 struct SegWriteRide {
     SegWriteArgs args;
     int ntiles;
     int use_map;
+    // a final sum of the loss that waits for a launch (fin_n > 0: one more workgroup)
+    const float *fin_partials;
+    int fin_n;
+    float fin_scale;
+    float *fin_loss;
 };
 
 enum { HAS_FIRST = 1, FIRST_CONT = 2, HAS_LAST = 4 };
@@ -171,15 +169,19 @@ __device__ inline void apply_update(float *__restrict__ row, int d4, int lig, co
 // RAW: `packed` and `seg_id` are the sorted payloads and keys of the build instead (a lane derives its entry's
 // row, sign, column and whether it heads a segment from them), and the first sw.ntiles workgroups run the
 // build's last kernel, whose arrays nothing reads before the fix-up launch.
-template <int LPR, int ITERS, bool PACKED, int CHUNK, bool FUSED, bool EMIT, bool RAW>
+// RIDE: 0 none of this; 1 RAW; 2 RAW, and the first kernel of the next batch's build comes along; 3 RAW, and the
+// first scatter pass of the next batch's sort comes along.
+template <int LPR, int ITERS, bool PACKED, int CHUNK, bool FUSED, int RIDE>
 __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restrict__ packed,
                                                          const int32_t *__restrict__ seg_id, int32_t e_begin,
                                                          int32_t e_end, const float *__restrict__ src_a,
                                                          const float *__restrict__ src_b, int32_t split,
                                                          int ld_src, int tail_off, int d4, float *__restrict__ out_rows,
                                                          int ld_out, float *__restrict__ partials, FusedArgs fu,
-                                                         SegSecond sec, EmitAhead ea, SegWriteRide sw)
+                                                         SegSecond sec, SegWriteRide sw, EmitAhead ea,
+                                                         ScatterAhead sca)
 {
+    constexpr bool RAW = RIDE != 0;
     int block = (int)blockIdx.x;
     if constexpr (RAW) {
         static_assert(FUSED, "the segment of an entry is not known here");
@@ -189,13 +191,27 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
             return;
         }
         block -= sw.ntiles;
+        if (sw.fin_n > 0) {
+            if (block == 0) {
+                finish_loss_body(sw.fin_partials, sw.fin_n, sw.fin_scale, sw.fin_loss);
+                return;
+            }
+            --block;
+        }
     }
-    if constexpr (EMIT) {
+    if constexpr (RIDE == 2) {
         if (block < ea.ntiles) {      // uniform in the workgroup
             emit_body<kSortItems, true, true, false>(block, ea.ntiles, ea.args);
             return;
         }
         block -= ea.ntiles;
+    }
+    if constexpr (RIDE == 3) {
+        if (block < sca.ntiles) {
+            scatter_body<true, false, kSortItems>(block, sca.args);
+            return;
+        }
+        block -= sca.ntiles;
     }
     if (block >= sec.first_block) {   // uniform in the workgroup
         block -= sec.first_block;
@@ -433,21 +449,29 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
     }
 }
 
-template <int LPR, int ITERS, int CHUNK, bool FUSED, bool RIDE>
+// RIDE: 1 the first scatter pass of the next batch's sort comes along, 2 its histogram pass of the second digit.
+template <int LPR, int ITERS, int CHUNK, bool FUSED, int RIDE>
 __global__ __launch_bounds__(kThreads) void k_seg_fixup(const int32_t *__restrict__ packed,
                                                         const int32_t *__restrict__ seg_id,
                                                         const int32_t *__restrict__ seg_ptr, int32_t e_begin,
                                                         int32_t e_end, int d4, float *__restrict__ out_rows,
                                                         int ld_out, const float *__restrict__ partials, FusedArgs fu,
-                                                        SegSecond sec, ScatterAhead sa)
+                                                        SegSecond sec, ScatterAhead sa, HistAhead ha)
 {
     int block = (int)blockIdx.x;
-    if constexpr (RIDE) {
+    if constexpr (RIDE == 1) {
         if (block < sa.ntiles) {      // uniform in the workgroup
             scatter_body<true, false, kSortItems>(block, sa.args);
             return;
         }
         block -= sa.ntiles;
+    }
+    if constexpr (RIDE == 2) {
+        if (block < ha.ntiles) {
+            hist_body<kSortItems>(block, ha.args.keys, ha.args.nnz, ha.args.shift, ha.args.radix, ha.args.table);
+            return;
+        }
+        block -= ha.ntiles;
     }
     if (block >= sec.first_block) {   // uniform in the workgroup
         block -= sec.first_block;
@@ -674,24 +698,29 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
         ntiles += (second->e_end - second->e_begin + tile - 1) / tile;
     }
     const FusedArgs fu = fused ? *fused : FusedArgs{nullptr, nullptr, 0, nullptr, nullptr, 0.f, 0, 0};
-    // the next batch's first build kernels, if they are waiting, ride in these launches (fused products of one
-    // float4 per lane): k_emit in that of k_seg_reduce, the first scatter pass in that of k_seg_fixup (which
-    // exists when the product has more than one tile)
-    // ... and so does the last kernel of this batch's build when it was left waiting (stx_train_step); a
-    // product that cannot take it runs after it
+    // The last kernel of this batch's build, when it was left waiting (stx_train_step), runs in the launch of a
+    // fused product of one float4 per lane, and so does the sum of the loss; a product that cannot take them runs
+    // after them.  The stages of the next batch's build that are due ride too, one per launch.
     const bool raw_now = fused && ITERS == 1 && c->segw.armed && c->sorted_inc == inc;
     if (c->segw.armed && !raw_now) launch_seg_write_late(c);
     const SegWriteRide no_segw{};
-    const SegWriteRide segw = raw_now ? SegWriteRide{c->segw.args, c->segw.ntiles, c->segw.use_map ? 1 : 0} : no_segw;
-    if (raw_now) c->segw.armed = false;
-    const EmitAhead no_emit{};
-    const ScatterAhead no_ride{};
-    const bool emit_now = fused && ITERS == 1 && c->ahead.armed && !c->ahead.done;
-    const bool ride_now = emit_now && ntiles > 1 && c->ahead.scatter_armed && !c->ahead.scatter_done;
-    const EmitAhead ahead = emit_now ? EmitAhead{c->ahead.args, c->ahead.ntiles} : no_emit;
-    const ScatterAhead ride = ride_now ? ScatterAhead{c->ahead.sargs, c->ahead.ntiles} : no_ride;
-    if (emit_now) c->ahead.done = true;
-    if (ride_now) c->ahead.scatter_done = true;
+    const SegWriteRide segw = raw_now ? SegWriteRide{c->segw.args, c->segw.ntiles, c->segw.use_map ? 1 : 0,
+                                                     c->loss_partials, c->fin_n, c->fin_scale, c->fin_loss}
+                                      : no_segw;
+    const int segw_blocks = segw.ntiles + (segw.fin_n > 0 ? 1 : 0);
+    if (raw_now) { c->segw.armed = false; c->fin_n = 0; }
+    EmitAhead r_emit{};
+    ScatterAhead r_scat{}, f_scat{};
+    HistAhead f_hist{};
+    if (raw_now) {
+        r_scat = take_scatter_ahead(c);
+        if (r_scat.ntiles == 0) r_emit = take_emit_ahead(c);
+        if (ntiles > 1) {   // a fix-up launch follows
+            f_hist = take_hist_ahead(c);
+            if (f_hist.ntiles == 0) f_scat = take_scatter_ahead(c);
+        }
+    }
+    const int r_blocks = r_emit.ntiles + r_scat.ntiles, f_blocks = f_scat.ntiles + f_hist.ntiles;
     // Wide rows (more than one float4 per lane) run as column slices of the one-float4 kernels: more rows in
     // flight per lane and ITERS times the workgroups.  The unit-length rescale needs whole rows.
     const bool whole_rows = fused && (fu.mode == 2 || sec.fused_mode == 2);
@@ -701,16 +730,16 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
     do {                                                                                                        \
         {                                                                                                       \
             ProfScope prof(c, "k_seg_reduce");                                                                  \
-            hipLaunchKernelGGL((k_seg_reduce<LPR, 1, P, CH, F, false, false>), grid, dim3(kThreads), 0,         \
-                               c->stream, inc->at_packed, inc->at_seg_id, e_begin, e_end, src_a, src_b, split,  \
-                               ld_src, tail_off, width / 4, out_rows, ld_out, c->partials, fu, sec, no_emit,    \
-                               no_segw);                                                                        \
+            hipLaunchKernelGGL((k_seg_reduce<LPR, 1, P, CH, F, 0>), grid, dim3(kThreads), 0, c->stream,         \
+                               inc->at_packed, inc->at_seg_id, e_begin, e_end, src_a, src_b, split, ld_src,     \
+                               tail_off, width / 4, out_rows, ld_out, c->partials, fu, sec, no_segw, r_emit,    \
+                               r_scat);                                                                         \
         }                                                                                                       \
         if (ntiles > 1) {                                                                                       \
             ProfScope prof(c, "k_seg_fixup");                                                                   \
-            hipLaunchKernelGGL((k_seg_fixup<LPR, 1, CH, F, false>), grid, dim3(kThreads), 0, c->stream,         \
+            hipLaunchKernelGGL((k_seg_fixup<LPR, 1, CH, F, 0>), grid, dim3(kThreads), 0, c->stream,             \
                                inc->at_packed, inc->at_seg_id, inc->at_seg_ptr, e_begin, e_end, width / 4,      \
-                               out_rows, ld_out, c->partials, fu, sec, no_ride);                                \
+                               out_rows, ld_out, c->partials, fu, sec, f_scat, f_hist);                         \
         }                                                                                                       \
     } while (0)
 #define STX_SLICED2(P, CH) do { if (fused) STX_SLICED(P, CH, true); else STX_SLICED(P, CH, false); } while (0)
@@ -720,42 +749,33 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
 #undef STX_SLICED
         return;
     }
+#define STX_SEG_R(P, CH, F, R)                                                                                  \
+    hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH, F, (F && ITERS == 1) ? R : 0>),                         \
+                       dim3(ntiles + segw_blocks + r_blocks), dim3(kThreads), 0, c->stream, segw.args.pay,      \
+                       segw.args.keys, e_begin, e_end, src_a, src_b, split, ld_src, tail_off, width / 4,        \
+                       out_rows, ld_out, c->partials, fu, sec, segw, r_emit, r_scat)
+#define STX_SEG_F(CH, F, R)                                                                                     \
+    hipLaunchKernelGGL((k_seg_fixup<LPR, ITERS, CH, F, (F && ITERS == 1) ? R : 0>), dim3(ntiles + f_blocks),    \
+                       dim3(kThreads), 0, c->stream, inc->at_packed, inc->at_seg_id, inc->at_seg_ptr, e_begin,  \
+                       e_end, width / 4, out_rows, ld_out, c->partials, fu, sec, f_scat, f_hist)
 #define STX_SEG(P, CH, F)                                                                                       \
     do {                                                                                                        \
         {                                                                                                       \
             ProfScope prof(c, "k_seg_reduce");                                                                  \
-            if (F && ITERS == 1 && emit_now && raw_now)                                                         \
-                hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH, F, F && ITERS == 1, F && ITERS == 1>),      \
-                                   dim3(ntiles + ahead.ntiles + segw.ntiles), dim3(kThreads), 0, c->stream,     \
-                                   segw.args.pay, segw.args.keys, e_begin, e_end, src_a, src_b, split, ld_src,  \
-                                   tail_off, width / 4, out_rows, ld_out, c->partials, fu, sec, ahead, segw);   \
-            else if (F && ITERS == 1 && raw_now)                                                                \
-                hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH, F, false, F && ITERS == 1>),                \
-                                   dim3(ntiles + segw.ntiles), dim3(kThreads), 0, c->stream, segw.args.pay,     \
-                                   segw.args.keys, e_begin, e_end, src_a, src_b, split, ld_src, tail_off,       \
-                                   width / 4, out_rows, ld_out, c->partials, fu, sec, no_emit, segw);           \
-            else if (F && ITERS == 1 && emit_now)                                                               \
-                hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH, F, F && ITERS == 1, false>),                \
-                                   dim3(ntiles + ahead.ntiles), dim3(kThreads), 0, c->stream, inc->at_packed,   \
-                                   inc->at_seg_id, e_begin, e_end, src_a, src_b, split, ld_src, tail_off,       \
-                                   width / 4, out_rows, ld_out, c->partials, fu, sec, ahead, no_segw);          \
+            if (F && ITERS == 1 && raw_now && r_scat.ntiles) STX_SEG_R(P, CH, F, 3);                            \
+            else if (F && ITERS == 1 && raw_now && r_emit.ntiles) STX_SEG_R(P, CH, F, 2);                       \
+            else if (F && ITERS == 1 && raw_now) STX_SEG_R(P, CH, F, 1);                                        \
             else                                                                                                \
-                hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH, F, false, false>), dim3(ntiles),            \
-                                   dim3(kThreads), 0, c->stream, inc->at_packed, inc->at_seg_id, e_begin,       \
-                                   e_end, src_a, src_b, split, ld_src, tail_off, width / 4, out_rows, ld_out,   \
-                                   c->partials, fu, sec, no_emit, no_segw);                                     \
+                hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH, F, 0>), dim3(ntiles), dim3(kThreads), 0,    \
+                                   c->stream, inc->at_packed, inc->at_seg_id, e_begin, e_end, src_a, src_b,     \
+                                   split, ld_src, tail_off, width / 4, out_rows, ld_out, c->partials, fu, sec,  \
+                                   no_segw, r_emit, r_scat);                                                    \
         }                                                                                                       \
         if (ntiles > 1) {                                                                                       \
             ProfScope prof(c, "k_seg_fixup");                                                                   \
-            if (F && ITERS == 1 && ride_now)                                                                    \
-                hipLaunchKernelGGL((k_seg_fixup<LPR, ITERS, CH, F, F && ITERS == 1>),                           \
-                                   dim3(ntiles + ride.ntiles), dim3(kThreads), 0, c->stream, inc->at_packed,    \
-                                   inc->at_seg_id, inc->at_seg_ptr, e_begin, e_end, width / 4, out_rows,        \
-                                   ld_out, c->partials, fu, sec, ride);                                         \
-            else                                                                                                \
-                hipLaunchKernelGGL((k_seg_fixup<LPR, ITERS, CH, F, false>), dim3(ntiles), dim3(kThreads), 0,    \
-                                   c->stream, inc->at_packed, inc->at_seg_id, inc->at_seg_ptr, e_begin, e_end,  \
-                                   width / 4, out_rows, ld_out, c->partials, fu, sec, no_ride);                 \
+            if (F && ITERS == 1 && f_hist.ntiles) STX_SEG_F(CH, F, 2);                                          \
+            else if (F && ITERS == 1 && f_scat.ntiles) STX_SEG_F(CH, F, 1);                                     \
+            else STX_SEG_F(CH, F, 0);                                                                           \
         }                                                                                                       \
     } while (0)
 #define STX_SEG2(P, CH) do { if (fused) STX_SEG(P, CH, true); else STX_SEG(P, CH, false); } while (0)
@@ -763,6 +783,8 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
     else            { if (small) STX_SEG2(false, CH_SHORT); else STX_SEG2(false, CH_LONG); }
 #undef STX_SEG2
 #undef STX_SEG
+#undef STX_SEG_F
+#undef STX_SEG_R
 }
 
 template <int LPR, int ITERS>

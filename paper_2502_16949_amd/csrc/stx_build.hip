@@ -152,10 +152,16 @@ stx_status launch_sample(stx_ctx *c, const int32_t *h, const int32_t *t, int64_t
     return hip_ok(hipGetLastError());
 }
 
+static void clear_ahead(stx_ctx *c)
+{
+    c->ahead.armed = false;
+    c->ahead.emit_done = c->ahead.scatter_done = c->ahead.hist_done = false;
+    c->ahead.scatter_ok = c->ahead.hist_ok = false;
+}
+
 bool prepare_emit_ahead(stx_ctx *c, const stx_batch *next, stx_incidence *inc)
 {
-    c->ahead.armed = c->ahead.done = false;
-    c->ahead.scatter_armed = c->ahead.scatter_done = false;
+    clear_ahead(c);
     if (!next || next->b <= 0 || next->k < 0 || next->b > c->cfg.max_batch || next->k > c->cfg.max_neg) return false;
     if (!next->h || !next->r || !next->t || (next->k > 0 && (!next->neg_h || !next->neg_t))) return false;
     if (next->m_total < 0 || next->global_offset < 0) return false;
@@ -171,18 +177,49 @@ bool prepare_emit_ahead(stx_ctx *c, const stx_batch *next, stx_incidence *inc)
     c->map_cur = (c->map_cur + 1) % 3;
     c->ahead.args = EmitArgs{bp, (int32_t)c->cfg.n_ent, (int32_t)c->cfg.n_rel, (int32_t)nnz, inc->a_rowptr, inc->a_colidx,
                              inc->a_vals, c->keys[2], 1 << bits0, ntiles, c->table, c->ctrl, map,
-                             RelCnt{nullptr, nullptr, 0}};
+                             RelCnt{nullptr, nullptr, 0}, c->cix[c->cix_cur]};
+    c->cix_cur ^= 1;
     c->ahead.ntiles = ntiles;
     c->ahead.inc = inc;
     c->ahead.armed = true;
     // the first scatter pass (keys[2] -> keys[1], payload = position) can follow in the next launch when its
-    // workgroups derive their offsets from the raw histograms themselves
+    // workgroups derive their offsets from the raw histograms themselves, and the histograms of the second
+    // digit in the launch after that
     if (ntiles <= kSelfScanTiles) {
         c->ahead.sargs = ScatterArgs{c->keys[2], c->pay[0], c->keys[1], c->pay[1], (int32_t)nnz, 0, bits0, ntiles, c->table,
                                      c->super};
-        c->ahead.scatter_armed = true;
+        c->ahead.scatter_ok = true;
+        if (c->sort_passes >= 2) {
+            const int left = c->sort_bits - c->digit_bits;
+            c->ahead.hargs = HistArgs{c->keys[1], (int32_t)nnz, c->digit_bits, 1 << (left < c->digit_bits ? left : c->digit_bits),
+                                      c->table1, ntiles};
+            c->ahead.hist_ok = true;
+        }
     }
     return true;
+}
+
+// The stages of the next build in their order; a launch that asks gets the stage that is due, at most one per
+// launch because every stage reads what the whole of the one before it wrote.
+EmitAhead take_emit_ahead(stx_ctx *c)
+{
+    if (!c->ahead.armed || c->ahead.emit_done) return EmitAhead{};
+    c->ahead.emit_done = true;
+    return EmitAhead{c->ahead.args, c->ahead.ntiles};
+}
+
+ScatterAhead take_scatter_ahead(stx_ctx *c)
+{
+    if (!c->ahead.armed || !c->ahead.emit_done || !c->ahead.scatter_ok || c->ahead.scatter_done) return ScatterAhead{};
+    c->ahead.scatter_done = true;
+    return ScatterAhead{c->ahead.sargs, c->ahead.ntiles};
+}
+
+HistAhead take_hist_ahead(stx_ctx *c)
+{
+    if (!c->ahead.armed || !c->ahead.scatter_done || !c->ahead.hist_ok || c->ahead.hist_done) return HistAhead{};
+    c->ahead.hist_done = true;
+    return HistAhead{c->ahead.hargs, c->ahead.ntiles};
 }
 
 stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const int32_t *t, const int32_t *nh,
@@ -196,10 +233,9 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
     c->cnt_inc = nullptr;
     c->cnt_ptr = nullptr;
     c->prep_inc = nullptr;
-    // the first kernel may already have run, in the launch of the previous step's transposed product
-    const bool ahead_done = c->ahead.done, ahead_scattered = c->ahead.scatter_done;
-    c->ahead.armed = c->ahead.done = false;
-    c->ahead.scatter_armed = c->ahead.scatter_done = false;
+    // the first kernels may already have run, in launches of the previous step
+    const EmitAheadState prev = c->ahead;
+    clear_ahead(c);
     if (b == 0) {
         hipLaunchKernelGGL(k_empty_incidence, dim3(1), dim3(64), 0, s, inc->a_rowptr, inc->at_seg_ptr,
                            inc->n_touched);
@@ -214,18 +250,30 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
     BatchPtrs bp{h, r, t, nh, nt, b, k > 0 ? k : 1, nullptr, nullptr, 0, 0};
     if (sample) { bp.nh_out = sample->neg_h; bp.nt_out = sample->neg_t; bp.seed = sample->seed; bp.base_ctr = sample->base_ctr; }
     const bool use_map = c->map_words > 0;
-    const EmitArgs &pa = c->ahead.args;
-    const bool emitted = ahead_done && sample && use_map && c->ahead.inc == inc && pa.bp.h == h && pa.bp.r == r &&
+    const EmitArgs &pa = prev.args;
+    const bool emitted = prev.armed && prev.emit_done && sample && use_map && prev.inc == inc && pa.bp.h == h && pa.bp.r == r &&
                          pa.bp.t == t && pa.bp.b == b && pa.bp.k == bp.k && pa.nnz == nnz &&
                          pa.bp.nh_out == bp.nh_out && pa.bp.nt_out == bp.nt_out && pa.bp.seed == bp.seed &&
                          pa.bp.base_ctr == bp.base_ctr;
-    const bool scattered0 = emitted && ahead_scattered;   // ... and the first scatter pass as well
+    const bool scattered0 = emitted && prev.scatter_done;   // ... and the first scatter pass as well
+    const bool counted1 = scattered0 && prev.hist_done;     // ... and the histograms of the second digit
     ColMap map{nullptr, nullptr, 0};
+    int32_t *colidx2 = nullptr;
     if (emitted) {
         map = pa.map;                    // (the maps changed roles when it was prepared)
-    } else if (use_map) {
-        map = ColMap{c->colmap[c->map_cur], c->colmap[(c->map_cur + 1) % 3], c->map_words};
-        c->map_cur = (c->map_cur + 1) % 3;
+        colidx2 = pa.colidx2;
+    } else {
+        if (use_map) {
+            map = ColMap{c->colmap[c->map_cur], c->colmap[(c->map_cur + 1) % 3], c->map_words};
+            c->map_cur = (c->map_cur + 1) % 3;
+        }
+        if (fusion) { colidx2 = c->cix[c->cix_cur]; c->cix_cur ^= 1; }
+    }
+    if (fusion) {
+        fusion->colidx = colidx2;
+        // this batch has its map and its copy of the column ids: the next batch's first kernels can be prepared,
+        // for the launches below and those of the backward pass to take along
+        if (fusion->next) prepare_emit_ahead(c, fusion->next, inc);
     }
 
     int bits0 = c->sort_bits < c->digit_bits ? c->sort_bits : c->digit_bits;
@@ -240,7 +288,7 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
     // keys[2] receives the unsorted keys: the sorted keys of the previous batch (in keys[0] or keys[1]) stay
     // readable while this batch's first kernel runs
     const EmitArgs ea{bp, n_ent, n_rel, nnz, inc->a_rowptr, inc->a_colidx, inc->a_vals, c->keys[2], 1 << bits0, ntiles,
-                      c->table, c->ctrl, map, rc};
+                      c->table, c->ctrl, map, rc, colidx2};
     if (!emitted) {
     ProfScope prof(c, "k_emit");
 #define STX_EMIT(I, M, S, R) hipLaunchKernelGGL((k_emit<I, M, S, R>), dim3(ntiles), dim3(kThreads), 0, s, ea)
@@ -262,7 +310,10 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
             cur ^= 1;
             continue;
         }
-        if (p == 1 && scattered0 && fusion && !fusion->forward_done && !two_level && items == kSortItems &&
+        // (histograms of the later digits go to the second table: the first one may be receiving the next batch's)
+        if (p == 1 && counted1) {
+            // the histograms of this digit are there already
+        } else if (p == 1 && scattered0 && fusion && !fusion->forward_done && !two_level && items == kSortItems &&
             launch_fwd_hist(c, inc, fusion, c->keys[cur], nnz, shift, 1 << bits, ntiles)) {
             // the forward pass, which could not share the first scatter pass's launch, shares this histogram's
         } else if (p > 0 && fusion && fusion->forward_done && !fusion->finish_done && items == kSortItems) {
@@ -271,23 +322,26 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
             ProfScope prof(c, "k_hist");
             if (items == kSortItems)
                 hipLaunchKernelGGL(k_hist<kSortItems>, dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], nnz, shift,
-                                   1 << bits, c->table);
+                                   1 << bits, c->table1);
             else
                 hipLaunchKernelGGL(k_hist<2 * kSortItems>, dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], nnz, shift,
-                                   1 << bits, c->table);
+                                   1 << bits, c->table1);
         }
         if (two_level) {
             ProfScope prof(c, "k_super_sums");
-            hipLaunchKernelGGL(k_super_sums, dim3(ngroups), dim3(kThreads), 0, s, c->table, 1 << bits, ntiles,
-                               c->super);
+            hipLaunchKernelGGL(k_super_sums, dim3(ngroups), dim3(kThreads), 0, s, p == 0 ? c->table : c->table1, 1 << bits,
+                               ntiles, c->super);
         }
         const ScatterArgs sa{p == 0 ? c->keys[2] : c->keys[cur], c->pay[cur], c->keys[cur ^ 1], c->pay[cur ^ 1], nnz, shift,
-                             bits, ntiles, c->table, c->super};
+                             bits, ntiles, p == 0 ? c->table : c->table1, c->super};
 #define STX_SCATTER(F, S, I)                                                                                  \
     hipLaunchKernelGGL((k_scatter<F, S, I>), dim3(ntiles), dim3(kThreads), 0, s, sa)
 #define STX_SCATTER2(F, S) do { if (items == kSortItems) STX_SCATTER(F, S, kSortItems); else STX_SCATTER(F, S, 2 * kSortItems); } while (0)
-        if (p == 0 && fusion && !two_level && items == kSortItems && launch_fwd_scatter(c, inc, fusion, sa)) {
+        if (p == 0 && fusion && !two_level && items == kSortItems && launch_fwd_scatter(c, inc, fusion, sa, true)) {
             // the forward pass ran in the same launch
+        } else if (p == 1 && counted1 && fusion && !fusion->forward_done && !two_level && items == kSortItems &&
+                   launch_fwd_scatter(c, inc, fusion, sa, false)) {
+            // the forward pass shares the launch of the sort's last pass
         } else if (p == 0 && fusion && !two_level && items == kSortItems && launch_prep_scatter(c, inc, fusion->p, sa)) {
             // TransR: the item lists and the bf16 copies of M_r were made in the same launch
         } else if (p > 0 && scattered0 && fusion && fusion->forward_done && !fusion->finish_done && !two_level &&

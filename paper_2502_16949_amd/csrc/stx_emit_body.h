@@ -91,6 +91,7 @@ __device__ inline void emit_body(const int block, const int nblocks, const EmitA
             }
             int32_t col = slot == 1 ? n_ent + idx : idx;
             colidx[e] = col;
+            if (a.colidx2) a.colidx2[e] = col;
             vals[e] = slot == 2 ? -1.0f : 1.0f;
             if (slot == 0) rowptr[row] = e;
             if (e == nnz - 1) rowptr[row + 1] = nnz;

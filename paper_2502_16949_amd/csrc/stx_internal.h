@@ -78,6 +78,7 @@ struct EmitArgs {
     int32_t *table, *ctrl;
     ColMap map;
     RelCnt rc;
+    int32_t *colidx2;              // a second copy of colidx, kept by the context (see stx_ctx::cix), or null
 };
 
 // Arguments of a scatter pass of the sort (by value into its kernel).
@@ -87,6 +88,15 @@ struct ScatterArgs {
     int32_t nnz;
     int shift, bits, ntiles;
     const int32_t *table, *super;
+};
+
+// Arguments of a histogram pass of the sort (a later digit).
+struct HistArgs {
+    const int32_t *keys;
+    int32_t nnz;
+    int shift, radix;
+    int32_t *table;
+    int ntiles;
 };
 
 // Arguments of the last kernel of a build (k_seg_write, stx_segw_body.h), by value.
@@ -110,15 +120,20 @@ struct SegWriteLate {
     int ntiles;
 };
 
-// stx_train_step with a next batch: the first two kernels of the next build (k_emit, then the first scatter
-// pass of the sort) depend on nothing this step computes and run in the two launches of this step's transposed
-// product.  `armed`: prepared, waiting for its launch; `done`: it ran, and the next build may skip it if it is
-// given this very batch.  The scatter pass needs the first kernel's histograms, hence the later launch.
+// stx_train_step with a next batch: the first kernels of the next build (k_emit, then the first scatter pass
+// of the sort, then the histogram pass of the second digit) depend on nothing this step computes and run as
+// extra workgroups of this step's launches, one stage per launch, because each stage needs all of the one
+// before it: in the forward pass's launch, the transposed product's and its fix-up's when the forward pass
+// runs in a launch that can take a stage along, else in the last two.  `armed`: prepared for the batch that
+// `args` describes; `*_done`: that stage ran, and the next build may skip it if it is given this very batch;
+// `*_ok`: the stage may run ahead at all (shape of the sort).
 struct EmitAheadState {
-    bool armed, done;
-    bool scatter_armed, scatter_done;
+    bool armed;
+    bool emit_done, scatter_done, hist_done;
+    bool scatter_ok, hist_ok;
     EmitArgs args;
     ScatterArgs sargs;
+    HistArgs hargs;
     int ntiles;
     const stx_incidence *inc;
 };
@@ -138,7 +153,10 @@ struct stx_ctx {
     int32_t *ctrl;
     int32_t *keys[3];              // [0], [1]: ping-pong of the sort; [2]: the unsorted keys of the batch being built
     int32_t *pay[2];
-    int32_t *table;                // [256 * ntiles_max] digit-major tile histograms / offsets
+    int32_t *table;                // [256 * ntiles_max] tile histograms of the first digit (written by k_emit)
+    int32_t *table1;               // ... and of the later digits: a next batch's first kernel may run beside them
+    int32_t *cix[2];               // copies of A's column ids that the forward pass of stx_train_step reads: the
+    int cix_cur;                   // next batch's first kernel may overwrite the caller's arrays meanwhile
     int32_t *super;                // [256 * (ntiles_max / kSuperTile + 1)] group sums of the tile histograms
     int32_t *tile_heads;           // [ntiles_max + 1]
     float *loss_partials;          // [fwd_blocks_max]
@@ -200,6 +218,8 @@ struct StepFusion {
     bool forward_done, finish_done;
     int n_partials;            // loss partials the forward pass wrote
     float scale;               // of the loss (1, or 1 / pairs for the mean)
+    const stx_batch *next;     // the batch of the next call, or null
+    const int32_t *colidx;     // A's column ids for the forward pass (the context's copy; filled in by the build)
 };
 
 // stx_build.hip
@@ -215,11 +235,28 @@ stx_status launch_build(stx_ctx *, const int32_t *h, const int32_t *r, const int
 // Prepares the first kernel of the build of `next` (as stx_train_step would launch it) to run inside the next
 // fused transposed product of this context; false: this configuration or batch does not allow it.
 bool prepare_emit_ahead(stx_ctx *, const stx_batch *next, stx_incidence *inc);
+// A launch that can take a stage of the next build along asks for it here (null args / zero tiles: none).
+struct EmitAhead {
+    EmitArgs args;
+    int ntiles;
+};
+struct ScatterAhead {
+    ScatterArgs args;
+    int ntiles;
+};
+struct HistAhead {
+    HistArgs args;
+    int ntiles;
+};
+EmitAhead take_emit_ahead(stx_ctx *);
+ScatterAhead take_scatter_ahead(stx_ctx *);
+HistAhead take_hist_ahead(stx_ctx *);
 stx_status launch_seg_write_late(stx_ctx *);
 // stx_transr.hip: item lists and bf16 copies of M_r in the launch of the first scatter pass; false: not possible
 bool launch_prep_scatter(stx_ctx *, const stx_incidence *, const stx_params *, const ScatterArgs &);
 // stx_step.hip
-bool launch_fwd_scatter(stx_ctx *, const stx_incidence *, StepFusion *, const ScatterArgs &);   // false: shape not covered
+// (first: the sort's first pass, whose payloads are the positions; false: shape not covered)
+bool launch_fwd_scatter(stx_ctx *, const stx_incidence *, StepFusion *, const ScatterArgs &, bool first);
 // the forward pass beside a histogram pass; a scatter pass beside the sum of the loss (when the first scatter
 // pass already ran ahead of time)
 bool launch_fwd_hist(stx_ctx *, const stx_incidence *, StepFusion *, const int32_t *keys, int32_t nnz, int shift,

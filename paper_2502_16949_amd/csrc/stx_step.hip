@@ -9,24 +9,38 @@
 // first scatter pass, and the loss sum in the launch of the next histogram pass.  The sort's
 // workgroups take the low block indices so that they start first: they are few and long, the forward
 // workgroups many and short.
+#include "stx_emit_body.h"
 #include "stx_forward_body.h"
 #include "stx_sort_body.h"
 #include "stx_transh_body.h"
 
 namespace stx {
 
-template <int LPR, int ITERS, int DIST, bool PACKED>
-__global__ __launch_bounds__(kThreads) void k_fwd_scatter(ForwardArgs fa, ScatterArgs sa)
+// (a later pass, FIRST false, can also take the first kernel of the next batch's build along: ea.ntiles > 0)
+template <int LPR, int ITERS, int DIST, bool PACKED, bool FIRST>
+__global__ __launch_bounds__(kThreads) void k_fwd_scatter(ForwardArgs fa, ScatterArgs sa, EmitAhead ea)
 {
-    if ((int)blockIdx.x < sa.ntiles) scatter_body<true, false, kSortItems>((int)blockIdx.x, sa);
-    else forward_stacked_body<LPR, ITERS, DIST, false, PACKED>((int)blockIdx.x - sa.ntiles, fa);
+    int block = (int)blockIdx.x;
+    if (block < sa.ntiles) { scatter_body<FIRST, false, kSortItems>(block, sa); return; }
+    block -= sa.ntiles;
+    if constexpr (!FIRST) {
+        if (block < ea.ntiles) { emit_body<kSortItems, true, true, false>(block, ea.ntiles, ea.args); return; }
+        block -= ea.ntiles;
+    }
+    forward_stacked_body<LPR, ITERS, DIST, false, PACKED>(block, fa);
 }
 
-template <int LPR, int ITERS, int DIST>
-__global__ __launch_bounds__(kThreads) void k_fwdh_scatter(TranshArgs ta, ScatterArgs sa)
+template <int LPR, int ITERS, int DIST, bool FIRST>
+__global__ __launch_bounds__(kThreads) void k_fwdh_scatter(TranshArgs ta, ScatterArgs sa, EmitAhead ea)
 {
-    if ((int)blockIdx.x < sa.ntiles) scatter_body<true, false, kSortItems>((int)blockIdx.x, sa);
-    else forward_transh_body<LPR, ITERS, DIST>((int)blockIdx.x - sa.ntiles, ta);
+    int block = (int)blockIdx.x;
+    if (block < sa.ntiles) { scatter_body<FIRST, false, kSortItems>(block, sa); return; }
+    block -= sa.ntiles;
+    if constexpr (!FIRST) {
+        if (block < ea.ntiles) { emit_body<kSortItems, true, true, false>(block, ea.ntiles, ea.args); return; }
+        block -= ea.ntiles;
+    }
+    forward_transh_body<LPR, ITERS, DIST>(block, ta);
 }
 
 __global__ __launch_bounds__(kThreads) void k_hist_finish(const int32_t *__restrict__ keys, int32_t nnz, int shift,
@@ -38,23 +52,31 @@ __global__ __launch_bounds__(kThreads) void k_hist_finish(const int32_t *__restr
     else hist_body<kSortItems>((int)blockIdx.x - 1, keys, nnz, shift, radix, table);
 }
 
-// When the first scatter pass of a build ran ahead of time (in the previous step's last launch), the forward
+// When the first scatter pass of a build ran ahead of time (in a launch of the previous step), the forward
 // pass shares the launch of the next histogram pass instead, and the sum of the loss that of the scatter
-// pass after it.
+// pass after it.  The first kernel of the next batch's build can come along (ea.ntiles > 0).
 template <int LPR, int ITERS, int DIST, bool PACKED>
 __global__ __launch_bounds__(kThreads) void k_fwd_hist(ForwardArgs fa, const int32_t *__restrict__ keys, int32_t nnz,
-                                                       int shift, int radix, int32_t *__restrict__ table, int ntiles)
+                                                       int shift, int radix, int32_t *__restrict__ table, int ntiles,
+                                                       EmitAhead ea)
 {
-    if ((int)blockIdx.x < ntiles) hist_body<kSortItems>((int)blockIdx.x, keys, nnz, shift, radix, table);
-    else forward_stacked_body<LPR, ITERS, DIST, false, PACKED>((int)blockIdx.x - ntiles, fa);
+    int block = (int)blockIdx.x;
+    if (block < ntiles) { hist_body<kSortItems>(block, keys, nnz, shift, radix, table); return; }
+    block -= ntiles;
+    if (block < ea.ntiles) { emit_body<kSortItems, true, true, false>(block, ea.ntiles, ea.args); return; }
+    forward_stacked_body<LPR, ITERS, DIST, false, PACKED>(block - ea.ntiles, fa);
 }
 
 template <int LPR, int ITERS, int DIST>
 __global__ __launch_bounds__(kThreads) void k_fwdh_hist(TranshArgs ta, const int32_t *__restrict__ keys, int32_t nnz,
-                                                        int shift, int radix, int32_t *__restrict__ table, int ntiles)
+                                                        int shift, int radix, int32_t *__restrict__ table, int ntiles,
+                                                        EmitAhead ea)
 {
-    if ((int)blockIdx.x < ntiles) hist_body<kSortItems>((int)blockIdx.x, keys, nnz, shift, radix, table);
-    else forward_transh_body<LPR, ITERS, DIST>((int)blockIdx.x - ntiles, ta);
+    int block = (int)blockIdx.x;
+    if (block < ntiles) { hist_body<kSortItems>(block, keys, nnz, shift, radix, table); return; }
+    block -= ntiles;
+    if (block < ea.ntiles) { emit_body<kSortItems, true, true, false>(block, ea.ntiles, ea.args); return; }
+    forward_transh_body<LPR, ITERS, DIST>(block - ea.ntiles, ta);
 }
 
 __global__ __launch_bounds__(kThreads) void k_scatter_finish(ScatterArgs sa, const float *__restrict__ partials,
@@ -65,10 +87,18 @@ __global__ __launch_bounds__(kThreads) void k_scatter_finish(ScatterArgs sa, con
 }
 
 template <int LPR, int ITERS>
-static void fwd_scatter_go(stx_ctx *c, const ForwardArgs &fa, const ScatterArgs &sa, unsigned blocks)
+static void fwd_scatter_go(stx_ctx *c, const ForwardArgs &fa, const ScatterArgs &sa, unsigned blocks, bool first,
+                           const EmitAhead &ea)
 {
 #define STX_FS(D, P)                                                                                            \
-    hipLaunchKernelGGL((k_fwd_scatter<LPR, ITERS, D, P>), dim3(blocks), dim3(kThreads), 0, c->stream, fa, sa)
+    do {                                                                                                        \
+        if (first)                                                                                              \
+            hipLaunchKernelGGL((k_fwd_scatter<LPR, ITERS, D, P, true>), dim3(blocks), dim3(kThreads), 0,        \
+                               c->stream, fa, sa, ea);                                                          \
+        else                                                                                                    \
+            hipLaunchKernelGGL((k_fwd_scatter<LPR, ITERS, D, P, false>), dim3(blocks), dim3(kThreads), 0,       \
+                               c->stream, fa, sa, ea);                                                          \
+    } while (0)
     switch (c->cfg.dist) {
     case STX_L1: STX_FS(STX_L1, true); break;
     case STX_L2: STX_FS(STX_L2, false); break;
@@ -80,10 +110,18 @@ static void fwd_scatter_go(stx_ctx *c, const ForwardArgs &fa, const ScatterArgs 
 }
 
 template <int LPR, int ITERS>
-static void fwdh_scatter_go(stx_ctx *c, const TranshArgs &ta, const ScatterArgs &sa, unsigned blocks)
+static void fwdh_scatter_go(stx_ctx *c, const TranshArgs &ta, const ScatterArgs &sa, unsigned blocks, bool first,
+                            const EmitAhead &ea)
 {
 #define STX_FS(D)                                                                                               \
-    hipLaunchKernelGGL((k_fwdh_scatter<LPR, ITERS, D>), dim3(blocks), dim3(kThreads), 0, c->stream, ta, sa)
+    do {                                                                                                        \
+        if (first)                                                                                              \
+            hipLaunchKernelGGL((k_fwdh_scatter<LPR, ITERS, D, true>), dim3(blocks), dim3(kThreads), 0,          \
+                               c->stream, ta, sa, ea);                                                          \
+        else                                                                                                    \
+            hipLaunchKernelGGL((k_fwdh_scatter<LPR, ITERS, D, false>), dim3(blocks), dim3(kThreads), 0,         \
+                               c->stream, ta, sa, ea);                                                          \
+    } while (0)
     switch (c->cfg.dist) {
     case STX_L1: STX_FS(STX_L1); break;
     case STX_L2: STX_FS(STX_L2); break;
@@ -96,11 +134,11 @@ static void fwdh_scatter_go(stx_ctx *c, const TranshArgs &ta, const ScatterArgs 
 
 template <int LPR>
 static void fwd_hist_go(stx_ctx *c, const ForwardArgs &fa, const int32_t *keys, int32_t nnz, int shift, int radix,
-                        int ntiles, unsigned blocks)
+                        int ntiles, unsigned blocks, const EmitAhead &ea)
 {
 #define STX_FH(D, P)                                                                                            \
     hipLaunchKernelGGL((k_fwd_hist<LPR, 1, D, P>), dim3(blocks), dim3(kThreads), 0, c->stream, fa, keys, nnz, shift, \
-                       radix, c->table, ntiles)
+                       radix, c->table1, ntiles, ea)
     switch (c->cfg.dist) {
     case STX_L1: STX_FH(STX_L1, true); break;
     case STX_L2: STX_FH(STX_L2, false); break;
@@ -113,11 +151,11 @@ static void fwd_hist_go(stx_ctx *c, const ForwardArgs &fa, const int32_t *keys, 
 
 template <int LPR>
 static void fwdh_hist_go(stx_ctx *c, const TranshArgs &ta, const int32_t *keys, int32_t nnz, int shift, int radix,
-                         int ntiles, unsigned blocks)
+                         int ntiles, unsigned blocks, const EmitAhead &ea)
 {
 #define STX_FH(D)                                                                                               \
     hipLaunchKernelGGL((k_fwdh_hist<LPR, 1, D>), dim3(blocks), dim3(kThreads), 0, c->stream, ta, keys, nnz, shift,  \
-                       radix, c->table, ntiles)
+                       radix, c->table1, ntiles, ea)
     switch (c->cfg.dist) {
     case STX_L1: STX_FH(STX_L1); break;
     case STX_L2: STX_FH(STX_L2); break;
@@ -139,27 +177,29 @@ bool launch_fwd_hist(stx_ctx *c, const stx_incidence *inc, StepFusion *f, const 
     if (c->cfg.reduce == STX_MEAN && inc->k > 0) f->scale = 1.0f / (float)((int64_t)inc->b * inc->k);
     const int groups = kThreads / L.lpr;
     f->n_partials = (inc->b + groups - 1) / groups;
-    const unsigned blocks = (unsigned)(ntiles + f->n_partials);
+    const int32_t *colidx = f->colidx ? f->colidx : inc->a_colidx;
+    const EmitAhead ea = take_emit_ahead(c);
+    const unsigned blocks = (unsigned)(ntiles + ea.ntiles + f->n_partials);
     if (transh) {
-        const TranshArgs ta{inc->a_colidx, f->p->ent, f->p->rel, f->p->w, (int32_t)c->cfg.n_ent, inc->b, inc->k,
+        const TranshArgs ta{colidx, f->p->ent, f->p->rel, f->p->w, (int32_t)c->cfg.n_ent, inc->b, inc->k,
                             c->cfg.dim, c->cfg.margin, f->scale, f->scores, c->gbuf[0], c->gbuf[1], c->gbuf[2],
                             c->loss_partials};
         ProfScope prof(c, "k_fwdh_hist");
-        if (L.lpr == 8) fwdh_hist_go<8>(c, ta, keys, nnz, shift, radix, ntiles, blocks);
-        else if (L.lpr == 16) fwdh_hist_go<16>(c, ta, keys, nnz, shift, radix, ntiles, blocks);
-        else if (L.lpr == 32) fwdh_hist_go<32>(c, ta, keys, nnz, shift, radix, ntiles, blocks);
-        else fwdh_hist_go<64>(c, ta, keys, nnz, shift, radix, ntiles, blocks);
+        if (L.lpr == 8) fwdh_hist_go<8>(c, ta, keys, nnz, shift, radix, ntiles, blocks, ea);
+        else if (L.lpr == 16) fwdh_hist_go<16>(c, ta, keys, nnz, shift, radix, ntiles, blocks, ea);
+        else if (L.lpr == 32) fwdh_hist_go<32>(c, ta, keys, nnz, shift, radix, ntiles, blocks, ea);
+        else fwdh_hist_go<64>(c, ta, keys, nnz, shift, radix, ntiles, blocks, ea);
         f->forward_done = true;
         return true;
     }
-    const ForwardArgs fa{inc->a_colidx, f->p->ent, inc->b, inc->k, c->cfg.dim, c->cfg.margin, f->scale, f->scores,
+    const ForwardArgs fa{colidx, f->p->ent, inc->b, inc->k, c->cfg.dim, c->cfg.margin, f->scale, f->scores,
                          c->gbuf[0], packed_stride(c->cfg.dim), c->loss_partials, f->p->rel_weight,
                          (int32_t)c->cfg.n_ent};
     ProfScope prof(c, "k_fwd_hist");
-    if (L.lpr == 8) fwd_hist_go<8>(c, fa, keys, nnz, shift, radix, ntiles, blocks);
-    else if (L.lpr == 16) fwd_hist_go<16>(c, fa, keys, nnz, shift, radix, ntiles, blocks);
-    else if (L.lpr == 32) fwd_hist_go<32>(c, fa, keys, nnz, shift, radix, ntiles, blocks);
-    else fwd_hist_go<64>(c, fa, keys, nnz, shift, radix, ntiles, blocks);
+    if (L.lpr == 8) fwd_hist_go<8>(c, fa, keys, nnz, shift, radix, ntiles, blocks, ea);
+    else if (L.lpr == 16) fwd_hist_go<16>(c, fa, keys, nnz, shift, radix, ntiles, blocks, ea);
+    else if (L.lpr == 32) fwd_hist_go<32>(c, fa, keys, nnz, shift, radix, ntiles, blocks, ea);
+    else fwd_hist_go<64>(c, fa, keys, nnz, shift, radix, ntiles, blocks, ea);
     f->forward_done = true;
     return true;
 }
@@ -172,7 +212,7 @@ void launch_scatter_finish(stx_ctx *c, StepFusion *f, const ScatterArgs &sa)
     f->finish_done = true;
 }
 
-bool launch_fwd_scatter(stx_ctx *c, const stx_incidence *inc, StepFusion *f, const ScatterArgs &sa)
+bool launch_fwd_scatter(stx_ctx *c, const stx_incidence *inc, StepFusion *f, const ScatterArgs &sa, bool first)
 {
     const bool stacked = c->cfg.model == STX_TRANSE || c->cfg.model == STX_TORUSE;
     const bool transh = c->cfg.model == STX_TRANSH;
@@ -182,28 +222,30 @@ bool launch_fwd_scatter(stx_ctx *c, const stx_incidence *inc, StepFusion *f, con
     if (c->cfg.reduce == STX_MEAN && inc->k > 0) f->scale = 1.0f / (float)((int64_t)inc->b * inc->k);
     const int groups = kThreads / L.lpr;
     f->n_partials = (inc->b + groups - 1) / groups;
+    const int32_t *colidx = f->colidx ? f->colidx : inc->a_colidx;
+    const EmitAhead ea = first ? EmitAhead{} : take_emit_ahead(c);
     if (transh) {
-        const TranshArgs ta{inc->a_colidx, f->p->ent, f->p->rel, f->p->w, (int32_t)c->cfg.n_ent, inc->b, inc->k,
+        const TranshArgs ta{colidx, f->p->ent, f->p->rel, f->p->w, (int32_t)c->cfg.n_ent, inc->b, inc->k,
                             c->cfg.dim, c->cfg.margin, f->scale, f->scores, c->gbuf[0], c->gbuf[1], c->gbuf[2],
                             c->loss_partials};
-        const unsigned blocks = (unsigned)(sa.ntiles + f->n_partials);
+        const unsigned blocks = (unsigned)(sa.ntiles + ea.ntiles + f->n_partials);
         ProfScope prof(c, "k_fwdh_scatter");
-        if (L.lpr == 8) fwdh_scatter_go<8, 1>(c, ta, sa, blocks);
-        else if (L.lpr == 16) fwdh_scatter_go<16, 1>(c, ta, sa, blocks);
-        else if (L.lpr == 32) fwdh_scatter_go<32, 1>(c, ta, sa, blocks);
-        else fwdh_scatter_go<64, 1>(c, ta, sa, blocks);
+        if (L.lpr == 8) fwdh_scatter_go<8, 1>(c, ta, sa, blocks, first, ea);
+        else if (L.lpr == 16) fwdh_scatter_go<16, 1>(c, ta, sa, blocks, first, ea);
+        else if (L.lpr == 32) fwdh_scatter_go<32, 1>(c, ta, sa, blocks, first, ea);
+        else fwdh_scatter_go<64, 1>(c, ta, sa, blocks, first, ea);
         f->forward_done = true;
         return true;
     }
-    const ForwardArgs fa{inc->a_colidx, f->p->ent, inc->b, inc->k, c->cfg.dim, c->cfg.margin, f->scale, f->scores,
+    const ForwardArgs fa{colidx, f->p->ent, inc->b, inc->k, c->cfg.dim, c->cfg.margin, f->scale, f->scores,
                          c->gbuf[0], packed_stride(c->cfg.dim), c->loss_partials, f->p->rel_weight,
                          (int32_t)c->cfg.n_ent};
-    const unsigned blocks = (unsigned)(sa.ntiles + f->n_partials);
+    const unsigned blocks = (unsigned)(sa.ntiles + ea.ntiles + f->n_partials);
     ProfScope prof(c, "k_fwd_scatter");
-    if (L.lpr == 8) fwd_scatter_go<8, 1>(c, fa, sa, blocks);
-    else if (L.lpr == 16) fwd_scatter_go<16, 1>(c, fa, sa, blocks);
-    else if (L.lpr == 32) fwd_scatter_go<32, 1>(c, fa, sa, blocks);
-    else fwd_scatter_go<64, 1>(c, fa, sa, blocks);
+    if (L.lpr == 8) fwd_scatter_go<8, 1>(c, fa, sa, blocks, first, ea);
+    else if (L.lpr == 16) fwd_scatter_go<16, 1>(c, fa, sa, blocks, first, ea);
+    else if (L.lpr == 32) fwd_scatter_go<32, 1>(c, fa, sa, blocks, first, ea);
+    else fwd_scatter_go<64, 1>(c, fa, sa, blocks, first, ea);
     f->forward_done = true;
     return true;
 }
@@ -212,7 +254,7 @@ void launch_hist_finish(stx_ctx *c, StepFusion *f, const int32_t *keys, int32_t 
 {
     ProfScope prof(c, "k_hist_finish");
     hipLaunchKernelGGL(k_hist_finish, dim3((unsigned)ntiles + 1), dim3(kThreads), 0, c->stream, keys, nnz, shift, radix,
-                       c->table, c->loss_partials, f->n_partials, f->scale, f->loss);
+                       c->table1, c->loss_partials, f->n_partials, f->scale, f->loss);
     f->finish_done = true;
 }
 
