@@ -55,10 +55,6 @@ TRAFFIC_BYTES = {("mid", "k_fwd_scatter", True): 26.10e6 + 7.33e6,
                  # mean of the two batches of an epoch (393,216 and 89,926 positives), like the timed mean
                  ("paper_transe", "k_seg_reduce", True): (9761.85e6 + 104.19e6 + 2281.04e6 + 99.90e6) / 2,
                  # with the look-ahead (the next batch's first build kernels ride in these launches)
-                 ("mid", "k_seg_reduce", "rides"): 25.72e6 + 11.79e6,
-                 ("mid", "k_fwd_hist", "rides"): 24.93e6 + 2.78e6,
-                 ("transh", "k_seg_reduce", "rides"): 140.66e6 + 12.62e6,
-                 ("transh", "k_fwdh_hist", "rides"): 31.28e6 + 98.76e6,
                  # the other modes (profiles/semiring_complex_*_kernel_trace.txt, profiles/rank_mid_kernel_trace.txt)
                  ("semiring complex", "mid", "k_semiring_terms"): 66.64e6 + 100.66e6,
                  ("semiring complex", "toruse", "k_semiring_terms"): 1560.16e6 + 2013.27e6}
@@ -98,17 +94,22 @@ def parse():
 def kernel_work(wl, kernel, rows, touched, fused=False, rides=False, segw=False):
     """Algorithmic work of ONE launch of `kernel` on a full batch: (amount, unit, bound, peak).
     row = 4*dim bytes.  rows = b*(1+k) matrix rows, nnz = 3*rows, touched = distinct columns.
-    rides: the launch of k_seg_reduce also runs the next batch's k_emit (about 28 B per entry: indices in, CSR
-    arrays, keys and negatives out), that of k_seg_fixup its first scatter pass (16 B per entry).
+    rides: the launch of the forward pass and the sort's last scatter pass (k_fwd_scatter, k_fwdh_scatter) also
+    runs the next batch's k_emit (about 28 B per entry: indices in, CSR arrays, keys and negatives out), that of
+    k_seg_reduce its first scatter pass (16 B per entry), that of k_seg_fixup the histogram pass of its second
+    digit (4 B per entry).
     segw: the launch of k_seg_reduce also runs the last kernel of this batch's build (sorted key and payload in,
     segment, row, packed entry and sign out: 21 B per entry)."""
     row = 4 * wl.dim
     nnz = 3 * rows
     if kernel == "k_seg_reduce" and (rides or segw):
         w, unit, bound, peak = kernel_work(wl, kernel, rows, touched, fused, False, False)
-        return w + nnz * ((28 if rides else 0) + (21 if segw else 0)), unit, bound, peak
+        return w + nnz * ((16 if rides else 0) + (21 if segw else 0)), unit, bound, peak
+    if kernel in ("k_fwd_scatter", "k_fwdh_scatter") and rides:
+        w, unit, bound, peak = kernel_work(wl, kernel, rows, touched, fused, False, False)
+        return w + nnz * 28, unit, bound, peak
     if kernel == "k_seg_fixup" and rides:
-        return nnz * 16, "GB/s", "hbm", HBM_PEAK_GBS
+        return nnz * 4, "GB/s", "hbm", HBM_PEAK_GBS
     if kernel in ("k_fwd_hist", "k_fwdh_hist"):      # the forward pass and a histogram pass (4 B per key) in one launch
         w, unit, bound, peak = kernel_work(wl, "k_forward_stacked" if kernel == "k_fwd_hist" else "k_forward_transh", rows,
                                            touched, fused, False)
@@ -534,7 +535,7 @@ def main():
     if kernel == "k_seg_reduce" and (rides or segw):
         kernel_note = ("this launch also runs " +
                        " and ".join((["the last kernel of this batch's build (21 B per entry)"] if segw else []) +
-                                    (["the first build kernel of the next batch (about 28 B per entry)"] if rides else [])) +
+                                    (["the first scatter pass of the next batch's sort (16 B per entry)"] if rides else [])) +
                        ", counted")
     per_launch = kernel_n * prof_every / args.steps if args.steps else 0
     achieved = (work / (kernel_us * 1e-6)) / (1e9 if unit == "GB/s" else 1e12) if kernel_us > 0 else 0.0
