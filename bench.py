@@ -27,11 +27,11 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 # The kernel whose roofline is reported: the one with the largest share of GPU time in the
 # rocprofv3 kernel trace of the same command (profiles/).
-DOMINANT = {"mid": "k_seg_reduce", "tiny": "k_seg_reduce", "toruse": "k_seg_reduce", "transh": "k_seg_reduce",
+DOMINANT = {"mid": "k_seg_reduce", "tiny": "k_seg_reduce", "toruse": "k_seg_reduce", "transh": "k_fwdh_scatter",
             "transr": "k_transr_project", "paper_transe": "k_seg_reduce", "paper_toruse": "k_seg_reduce",
             "paper_transr": "k_transr_project"}
 # ... without the look-ahead (--no-lookahead) the forward pass and the first scatter pass share the longest launch
-DOMINANT_PLAIN = dict(DOMINANT, mid="k_fwd_scatter", tiny="k_fwd_scatter")
+DOMINANT_PLAIN = dict(DOMINANT, mid="k_fwd_scatter", tiny="k_fwd_scatter", transh="k_seg_reduce")
 # ... and when the step is made of the separate calls (--api fused | separate)
 DOMINANT_CALLS = {"mid": "k_seg_reduce", "tiny": "k_seg_reduce", "toruse": "k_seg_reduce", "transh": "k_forward_transh",
                   "transr": "k_transr_project", "paper_transe": "k_seg_reduce", "paper_toruse": "k_seg_reduce",
@@ -55,6 +55,12 @@ TRAFFIC_BYTES = {("mid", "k_fwd_scatter", True): 26.10e6 + 7.33e6,
                  # mean of the two batches of an epoch (393,216 and 89,926 positives), like the timed mean
                  ("paper_transe", "k_seg_reduce", True): (9761.85e6 + 104.19e6 + 2281.04e6 + 99.90e6) / 2,
                  # with the look-ahead (the next batch's first build kernels ride in these launches)
+                 ("mid", "k_seg_reduce", "rides"): 28.40e6 + 13.93e6,
+                 ("mid", "k_fwd_scatter", "rides"): 27.46e6 + 9.24e6,
+                 ("mid", "k_seg_fixup", "rides"): 3.62e6 + 0.42e6,
+                 ("transh", "k_seg_reduce", "rides"): 142.21e6 + 14.78e6,
+                 ("transh", "k_fwdh_scatter", "rides"): 33.72e6 + 105.21e6,
+                 ("transh", "k_seg_fixup", "rides"): 4.01e6 + 0.48e6,
                  # the other modes (profiles/semiring_complex_*_kernel_trace.txt, profiles/rank_mid_kernel_trace.txt)
                  ("semiring complex", "mid", "k_semiring_terms"): 66.64e6 + 100.66e6,
                  ("semiring complex", "toruse", "k_semiring_terms"): 1560.16e6 + 2013.27e6}

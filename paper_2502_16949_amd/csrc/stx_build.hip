@@ -267,7 +267,8 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
             map = ColMap{c->colmap[c->map_cur], c->colmap[(c->map_cur + 1) % 3], c->map_words};
             c->map_cur = (c->map_cur + 1) % 3;
         }
-        if (fusion) { colidx2 = c->cix[c->cix_cur]; c->cix_cur ^= 1; }
+        // (no copy of the column ids: only a batch that was prepared ahead runs its forward pass in a launch
+        // that takes the next batch's first kernel along)
     }
     if (fusion) {
         fusion->colidx = colidx2;

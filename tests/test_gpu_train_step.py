@@ -126,6 +126,9 @@ LOOKAHEAD_CASES = [
     ("transe", "l2", 400, 9, 777, 3, 128, 0),                    # dense rows, several negatives
     ("toruse", "torus_l1", 1000, 20, 1024, 4, 64, 0),
     ("transh", "l2", 1000, 20, 1024, 1, 128, B.STX_FLAG_RENORM_W),   # two transposed products in the launch
+    ("transe", "l1", 50, 5, 20, 1, 128, 0),                      # one sort pass, one tile: no fix-up launch to ride in
+    ("transe", "l2", 3000, 5, 20, 1, 128, 0),                    # two sort passes, no fix-up launch: only k_emit runs ahead
+    ("toruse", "torus_l1", 40000, 100, 5000, 2, 128, 0),         # 16 key bits, 30,000 entries: 30 sort tiles
     ("transe", "l2", 70000, 5, 3000, 1, 32, 0),                  # no presence bitmap: `next` is ignored
     ("transe", "l2", 300, 5, 200, 1, 512, 0),                    # wide rows (column slices): `next` is ignored
     ("transr", "l2", 300, 8, 500, 1, 64, B.STX_FLAG_BF16_PROJ),  # TransR counts rows per relation: `next` is ignored
@@ -135,8 +138,8 @@ LOOKAHEAD_CASES = [
 @pytest.mark.parametrize("model,dist,n_ent,n_rel,b,k,dim,flags", LOOKAHEAD_CASES)
 def test_train_step_with_the_next_batch_named_gives_the_same_bits(model, dist, n_ent, n_rel, b, k, dim, flags):
     """Seven steps over three batches (the last one shorter; the walk wraps around twice), once plain and once with
-    every call naming the batch of the call after it, whose first build kernel then runs inside the launch of this
-    step's transposed product.  After every step: same scores, loss, tables, A^T arrays; and the A arrays and
+    every call naming the batch of the call after it, whose first build kernels then run inside this step's launches
+    (from the third linked step on all three stages that can run ahead have).  After every step: same scores, loss, tables, A^T arrays; and the A arrays and
     negatives already those of the next batch.  Then a call that is given another batch than the one named."""
     wl = W.Workload("case", 12, model, dist, n_ent, n_rel, 3 * b, dim, dim, b, k, 1.0, 0.01, 1, 1.1, 1.1,
                     bool(flags & B.STX_FLAG_BF16_PROJ))
