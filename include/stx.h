@@ -214,11 +214,11 @@ stx_status stx_backward_sgd(stx_ctx *ctx, const stx_incidence *inc, stx_params *
 /* One training step in one call.  The batch's positives plus what stx_sample_negatives needs to draw its
  * negatives; neg_h / neg_t ([b*k], device, out) receive the negatives drawn (not needed when k == 0).
  * next (host, may be null): the batch the NEXT stx_train_step call on this context will be given, with the
- * same inc.  The first two kernels of a build (the one that writes A, the sort keys and the negatives, and
- * the first scatter pass of the sort) depend on nothing the step before computes, so they then run inside
- * the two launches of this step's transposed product, and the next call, if it is given exactly that batch,
- * starts from there (its forward pass shares the launch of the next histogram pass instead); results are
- * the same bit for bit.  With next set, on return the A arrays of inc (a_rowptr, a_colidx, a_vals) and
+ * same inc.  The first kernels of a build (the one that writes A, the sort keys and the negatives, the
+ * first scatter pass of the sort, the histogram pass after it) depend on nothing the step before computes,
+ * so they then run inside this step's launches, one stage per launch, and the next call, if it is given
+ * exactly that batch, starts from where they stopped (in steady state a step is three launches); results
+ * are the same bit for bit.  With next set, on return the A arrays of inc (a_rowptr, a_colidx, a_vals) and
  * next's neg_h / neg_t already hold the next batch's, the A^T arrays this batch's.  A next call with
  * another batch, or any other call, simply builds as usual.  Used when the configuration keeps a column
  * bitmap (n_ent + n_rel <= 65,536), for TransE / TorusE / TransH with dim <= 256 and batches of at most
