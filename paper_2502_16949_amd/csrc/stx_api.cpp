@@ -613,7 +613,9 @@ stx_status stx_train_step(stx_ctx *ctx, const stx_batch *bt, stx_incidence *inc,
     };
     if (s != STX_OK) { launch_seg_write_late(ctx); unwind_ahead(); return s; }
     if (!fusion.forward_done) {
-        ctx->defer_finish = ctx->cfg.model == STX_TRANSR;   // its loss sum rides in the backward pass's first launch
+        // the sum of the loss rides in the backward pass's first launch: TransR's row products take it along, and
+        // so does a transposed product that takes the build's last kernel along
+        ctx->defer_finish = ctx->cfg.model == STX_TRANSR || ctx->segw.armed;
         s = stx_forward(ctx, inc, p, scores, loss);
         ctx->defer_finish = false;
     } else {   // the forward pass shared a launch with the sort; the sum of the loss may still be missing

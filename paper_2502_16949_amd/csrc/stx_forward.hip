@@ -122,7 +122,7 @@ static void forward_go(stx_ctx *c, const stx_incidence *inc, const stx_params *p
     }
 #undef STX_FWD2
 #undef STX_FWD
-    if (from_y && c->defer_finish) { c->fin_n = (int)grid.x; c->fin_scale = scale; c->fin_loss = loss; }
+    if (c->defer_finish) { c->fin_n = (int)grid.x; c->fin_scale = scale; c->fin_loss = loss; }
     else launch_finish_loss(c, (int)grid.x, scale, loss);
 }
 

@@ -172,8 +172,8 @@ struct stx_ctx {
     const int32_t *cnt_ptr;        // counts of the last build ...
     const stx_incidence *cnt_inc;  // ... which was of this incidence
     const stx_incidence *prep_inc; // incidence whose TransR preparation already ran beside its sort
-    // stx_train_step, TransR: the final sum of the loss is not launched by the forward pass but rides in the
-    // first launch of the backward pass (nothing in between needs it)
+    // stx_train_step: the final sum of the loss is not launched by the forward pass but rides in the first
+    // launch of the backward pass (nothing in between needs it), when that launch can take it along
     bool defer_finish;
     int fin_n;                     // loss partials waiting to be summed (0: none)
     float fin_scale;

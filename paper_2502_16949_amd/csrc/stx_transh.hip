@@ -38,7 +38,8 @@ static void transh_go(stx_ctx *c, const stx_incidence *inc, const stx_params *p,
     }
     }
 #undef STX_FWD
-    launch_finish_loss(c, (int)grid.x, scale, loss);
+    if (c->defer_finish) { c->fin_n = (int)grid.x; c->fin_scale = scale; c->fin_loss = loss; }
+    else launch_finish_loss(c, (int)grid.x, scale, loss);
 }
 
 stx_status launch_forward_transh(stx_ctx *c, const stx_incidence *inc, const stx_params *p, float *scores,
