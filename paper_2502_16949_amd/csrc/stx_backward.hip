@@ -105,7 +105,10 @@ struct FusedArgs {             // the update that replaces the store of a gradie
 };
 __device__ inline float *fused_row(const FusedArgs &fu, int32_t col, int ld_tab)
 {
-    return col < fu.n_split ? fu.table + (int64_t)col * ld_tab : fu.table_b + (int64_t)(col - fu.n_split) * ld_tab;
+    // (unsigned 32 x 32 -> 64 bit product: one instruction, where signed 64-bit operands take six)
+    const bool first = col < fu.n_split;
+    const uint32_t r = (uint32_t)(first ? col : col - fu.n_split);
+    return (first ? fu.table : fu.table_b) + (uint64_t)r * (uint32_t)ld_tab;
 }
 
 // A second, independent transposed product that shares the launch (TransH: the sums of gw over the
@@ -251,6 +254,8 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
     __shared__ int32_t s_col_last[GROUPS], s_fin_src[GROUPS];
 
     const int lig = threadIdx.x % LPR, grp = threadIdx.x / LPR;
+    const int pk_sh = PACKED ? 31 - __clz(ld_src) : 0;
+    const uint8_t *pk_lane = reinterpret_cast<const uint8_t *>(src_a) + pk_off + lig;
     const int32_t tile0 = e_begin + block * TILE;
     const int32_t ec0 = tile0 + grp * CHUNK;
     const int32_t ec1 = min(ec0 + CHUNK, e_end);
@@ -332,21 +337,22 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
             }
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
-                const int64_t row = mu[u] >> 2;
+                const uint32_t row = (uint32_t)mu[u] >> 2;
                 if constexpr (FUSED) {   // a run begins here: its table row comes along with its first source row
                     if (mu[u] & 2) load_row<LPR, ITERS>(fused_row(fu, cu[u], ld_tab), d4, lig, xr[u]);
                 }
                 if constexpr (PACKED) {
-                    const uint8_t *pb = reinterpret_cast<const uint8_t *>(src_a) + row * ld_src + pk_off;
+                    // (records of 1 << pk_sh bytes: a shift and an add give the address)
+                    const uint8_t *pb = pk_lane + ((uint64_t)row << pk_sh);
 #pragma unroll
                     for (int it = 0; it < ITERS; ++it) {
                         const int j = lig + it * LPR;
-                        sb[u][it] = j < d4 ? pb[j] : (uint8_t)0;
+                        sb[u][it] = j < d4 ? pb[it * LPR] : (uint8_t)0;
                     }
                     cf[u] = src_b[row];
                 } else {   // entries before `split` read src_a, the rest src_b (entity vs relation columns)
                     // (tail_off: where the rows that tail entries read sit, relative to the head entries' rows)
-                    load_row<LPR, ITERS>((ec0 + j0 + u < split ? src_a : src_b) + row * ld_src + ((mu[u] & 1) ? tail_off : 0),
+                    load_row<LPR, ITERS>((ec0 + j0 + u < split ? src_a : src_b) + (uint64_t)row * (uint32_t)ld_src + ((mu[u] & 1) ? tail_off : 0),
                                          d4, lig, v[u]);
                 }
             }

@@ -335,7 +335,13 @@ inline bool packed_grad(const stx_ctx *c)
     return (c->cfg.model == STX_TRANSE || c->cfg.model == STX_TORUSE) &&
            (c->cfg.dist == STX_L1 || c->cfg.dist == STX_TORUS_L1);
 }
-inline int packed_stride(int dim) { return (dim / 4 + 31) / 32 * 32; }
+// (bytes per sign record: a power of two, so that a record's address is a shift of its row)
+inline int packed_stride(int dim)
+{
+    int s = 32;
+    while (s < dim / 4) s <<= 1;
+    return s;
+}
 // byte offset of the coefficient array from the start of the records of a batch of `rows` rows
 __host__ __device__ inline int64_t packed_coef_offset(int64_t rows, int stride) { return (rows * stride + 255) / 256 * 256; }
 
