@@ -412,12 +412,12 @@ def main():
     kernel = args.kernel or ((DOMINANT_PLAIN if args.no_lookahead else DOMINANT) if args.api == "step"
                              else DOMINANT_CALLS)[wl.name]
     # batches whose first build kernels can run inside the previous step's launches (see stx_batch.next)
-    rides = (args.api == "step" and not args.no_lookahead and wl.model in ("transe", "toruse", "transh")
+    rides = (args.api == "step" and not args.no_lookahead and (wl.model != "transr" or wl.n_rel <= 4096)
              and wl.n_ent + wl.n_rel <= 65536 and 3 * wl.rows_per_batch <= (1 << 18) and wl.dim <= 256)
 
     # the one-call step leaves the last kernel of the build to the launch of the transposed product (rows of one
-    # float4 per lane, not TransR)
-    segw = args.api == "step" and wl.model != "transr" and wl.dim <= 256
+    # float4 per lane; TransR when its work items come from the rows-per-relation counts)
+    segw = args.api == "step" and (wl.model != "transr" or wl.n_rel <= 4096) and wl.dim <= 256
 
     h, r, t = W.make_graph(wl)
     tabs = W.make_tables(wl)

@@ -600,7 +600,8 @@ stx_status stx_train_step(stx_ctx *ctx, const stx_batch *bt, stx_incidence *inc,
     // (the next batch's first build kernels may ride in this step's launches: the build prepares them)
     StepFusion fusion{p, scores, loss, false, false, 0, 1.0f, b > 0 ? bt->next : nullptr, nullptr};
     // the fused transposed product of one float4 per lane can run the build's last kernel in its own launch
-    ctx->segw.allowed = ctx->cfg.model != STX_TRANSR && row_launch(ctx->cfg.dim).iters == 1;
+    // (TransR: when its work items come from the rows-per-relation counts, not from the segment lists)
+    ctx->segw.allowed = (ctx->cfg.model != STX_TRANSR || ctx->rel_cnt[0] != nullptr) && row_launch(ctx->cfg.dim).iters == 1;
     s = launch_build(ctx, bt->h, bt->r, bt->t, nullptr, nullptr, b, k, inc, &sa, &fusion);
     ctx->segw.allowed = false;
     // a stage of the next build that no launch took along: the buffers go back to their roles
@@ -609,6 +610,7 @@ stx_status stx_train_step(stx_ctx *ctx, const stx_batch *bt, stx_incidence *inc,
             ctx->ahead.armed = false;
             ctx->map_cur = (ctx->map_cur + 2) % 3;
             ctx->cix_cur ^= 1;
+            if (ctx->ahead.args.rc.cur) ctx->cnt_cur ^= 1;
         }
     };
     if (s != STX_OK) { launch_seg_write_late(ctx); unwind_ahead(); return s; }

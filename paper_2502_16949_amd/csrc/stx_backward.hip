@@ -173,7 +173,7 @@ __device__ inline void apply_update(float *__restrict__ row, int d4, int lig, co
 // row, sign, column and whether it heads a segment from them), and the first sw.ntiles workgroups run the
 // build's last kernel, whose arrays nothing reads before the fix-up launch.
 // RIDE: 0 none of this; 1 RAW; 2 RAW, and the first kernel of the next batch's build comes along; 3 RAW, and the
-// first scatter pass of the next batch's sort comes along.
+// first scatter pass of the next batch's sort comes along; 4 as 2, and that kernel counts the rows per relation.
 template <int LPR, int ITERS, bool PACKED, int CHUNK, bool FUSED, int RIDE>
 __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restrict__ packed,
                                                          const int32_t *__restrict__ seg_id, int32_t e_begin,
@@ -202,9 +202,9 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
             --block;
         }
     }
-    if constexpr (RIDE == 2) {
+    if constexpr (RIDE == 2 || RIDE == 4) {
         if (block < ea.ntiles) {      // uniform in the workgroup
-            emit_body<kSortItems, true, true, false>(block, ea.ntiles, ea.args);
+            emit_body<kSortItems, true, true, RIDE == 4>(block, ea.ntiles, ea.args);
             return;
         }
         block -= ea.ntiles;
@@ -769,6 +769,7 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
         {                                                                                                       \
             ProfScope prof(c, "k_seg_reduce");                                                                  \
             if (F && ITERS == 1 && raw_now && r_scat.ntiles) STX_SEG_R(P, CH, F, 3);                            \
+            else if (F && ITERS == 1 && raw_now && r_emit.ntiles && r_emit.args.rc.cur) STX_SEG_R(P, CH, F, 4); \
             else if (F && ITERS == 1 && raw_now && r_emit.ntiles) STX_SEG_R(P, CH, F, 2);                       \
             else if (F && ITERS == 1 && raw_now) STX_SEG_R(P, CH, F, 1);                                        \
             else                                                                                                \

@@ -165,7 +165,8 @@ bool prepare_emit_ahead(stx_ctx *c, const stx_batch *next, stx_incidence *inc)
     if (!next || next->b <= 0 || next->k < 0 || next->b > c->cfg.max_batch || next->k > c->cfg.max_neg) return false;
     if (!next->h || !next->r || !next->t || (next->k > 0 && (!next->neg_h || !next->neg_t))) return false;
     if (next->m_total < 0 || next->global_offset < 0) return false;
-    if (c->map_words <= 0 || c->rel_cnt[0] != nullptr) return false;   // needs the bitmap path, no relation counts
+    if (c->map_words <= 0) return false;                               // needs the bitmap path
+    if (c->cfg.model == STX_TRANSR && !c->rel_cnt[0]) return false;     // TransR: its work items must come from counts
     const int64_t nnz = 3 * (int64_t)next->b * (1 + next->k);
     if (nnz > (1 << 19)) return false;                                  // the small-sort shape of the first kernel only
     const int ntiles = (int)((nnz + kThreads * kSortItems - 1) / (kThreads * kSortItems));
@@ -175,9 +176,14 @@ bool prepare_emit_ahead(stx_ctx *c, const stx_batch *next, stx_incidence *inc)
                        next->neg_h, next->neg_t, next->seed, base_ctr};
     const ColMap map{c->colmap[c->map_cur], c->colmap[(c->map_cur + 1) % 3], c->map_words};
     c->map_cur = (c->map_cur + 1) % 3;
+    RelCnt rc{nullptr, nullptr, 0};
+    if (c->rel_cnt[0]) {   // TransR: the rows per relation are counted on the way (the two buffers alternate)
+        rc = RelCnt{c->rel_cnt[c->cnt_cur], c->rel_cnt[c->cnt_cur ^ 1], (int)c->cfg.n_rel};
+        c->cnt_cur ^= 1;
+    }
     c->ahead.args = EmitArgs{bp, (int32_t)c->cfg.n_ent, (int32_t)c->cfg.n_rel, (int32_t)nnz, inc->a_rowptr, inc->a_colidx,
-                             inc->a_vals, c->keys[2], 1 << bits0, ntiles, c->table, c->ctrl, map,
-                             RelCnt{nullptr, nullptr, 0}, c->cix[c->cix_cur]};
+                             inc->a_vals, c->keys[2], 1 << bits0, ntiles, c->table, c->ctrl, map, rc,
+                             c->cix[c->cix_cur]};
     c->cix_cur ^= 1;
     c->ahead.ntiles = ntiles;
     c->ahead.inc = inc;
@@ -270,22 +276,24 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
         // (no copy of the column ids: only a batch that was prepared ahead runs its forward pass in a launch
         // that takes the next batch's first kernel along)
     }
-    if (fusion) {
-        fusion->colidx = colidx2;
-        // this batch has its map and its copy of the column ids: the next batch's first kernels can be prepared,
-        // for the launches below and those of the backward pass to take along
-        if (fusion->next) prepare_emit_ahead(c, fusion->next, inc);
-    }
+    if (fusion) fusion->colidx = colidx2;
 
     int bits0 = c->sort_bits < c->digit_bits ? c->sort_bits : c->digit_bits;
     const bool use_rc = c->rel_cnt[0] != nullptr;
     RelCnt rc{nullptr, nullptr, 0};
-    if (use_rc) {
+    if (use_rc && emitted) {   // counted when the first kernel ran ahead
+        c->cnt_ptr = pa.rc.cur;
+        c->cnt_inc = inc;
+    } else if (use_rc) {
         rc = RelCnt{c->rel_cnt[c->cnt_cur], c->rel_cnt[c->cnt_cur ^ 1], n_rel};
         c->cnt_ptr = rc.cur;
         c->cnt_inc = inc;
         c->cnt_cur ^= 1;
     }
+    // this batch has its map, its counts and its copy of the column ids: the next batch's first kernels can be
+    // prepared (the rotating buffers go to the batches in their order), for the launches below and those of the
+    // backward pass to take along
+    if (fusion && fusion->next) prepare_emit_ahead(c, fusion->next, inc);
     // keys[2] receives the unsorted keys: the sorted keys of the previous batch (in keys[0] or keys[1]) stay
     // readable while this batch's first kernel runs
     const EmitArgs ea{bp, n_ent, n_rel, nnz, inc->a_rowptr, inc->a_colidx, inc->a_vals, c->keys[2], 1 << bits0, ntiles,
@@ -343,7 +351,8 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
         } else if (p == 1 && counted1 && fusion && !fusion->forward_done && !two_level && items == kSortItems &&
                    launch_fwd_scatter(c, inc, fusion, sa, false)) {
             // the forward pass shares the launch of the sort's last pass
-        } else if (p == 0 && fusion && !two_level && items == kSortItems && launch_prep_scatter(c, inc, fusion->p, sa)) {
+        } else if (fusion && !two_level && items == kSortItems && (p == 0 || (p == 1 && scattered0)) &&
+                   launch_prep_scatter(c, inc, fusion->p, sa, p == 0)) {
             // TransR: the item lists and the bf16 copies of M_r were made in the same launch
         } else if (p > 0 && scattered0 && fusion && fusion->forward_done && !fusion->finish_done && !two_level &&
                    items == kSortItems) {

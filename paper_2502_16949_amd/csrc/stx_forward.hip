@@ -8,6 +8,7 @@
 // The fused forward kernel gives one group a positive row and its k negatives: it computes the
 // distances (Sec. 4.3, 4.6), the margin-ranking hinge (Sec. 5.3) and writes dL/dx of each of those
 // rows straight away, so x itself never goes to memory.
+#include "stx_emit_body.h"
 #include "stx_forward_body.h"
 
 namespace stx {
@@ -40,6 +41,15 @@ template <int LPR, int ITERS, int DIST, bool FROM_Y, bool PACKED>
 __global__ __launch_bounds__(kThreads) void k_forward_stacked(ForwardArgs a)
 {
     forward_stacked_body<LPR, ITERS, DIST, FROM_Y, PACKED>((int)blockIdx.x, a);
+}
+
+// TransR in stx_train_step: the first kernel of the next batch's build (which also counts the rows per relation)
+// rides with the distances over the rows of y; nothing after this launch reads the A arrays it overwrites.
+template <int LPR, int ITERS, int DIST>
+__global__ __launch_bounds__(kThreads) void k_forward_y_emit(ForwardArgs a, EmitAhead ea)
+{
+    if ((int)blockIdx.x < ea.ntiles) emit_body<kSortItems, true, true, true>((int)blockIdx.x, ea.ntiles, ea.args);
+    else forward_stacked_body<LPR, ITERS, DIST, true, false>((int)blockIdx.x - ea.ntiles, a);
 }
 
 __global__ void k_zero_loss(float *loss) { loss[0] = 0.f; }
@@ -102,11 +112,17 @@ static void forward_go(stx_ctx *c, const stx_incidence *inc, const stx_params *p
     const ForwardArgs fa{inc->a_colidx, p->ent, inc->b, inc->k, width, c->cfg.margin, scale, scores, c->gbuf[0],
                          packed_stride(c->cfg.dim), c->loss_partials, from_y ? nullptr : p->rel_weight,
                          (int32_t)c->cfg.n_ent};
+    // (the next batch's first build kernel, if one is due and counts rows per relation as TransR's do)
+    EmitAhead ea{};
+    if (from_y && c->ahead.armed && !c->ahead.emit_done && c->ahead.args.rc.cur) ea = take_emit_ahead(c);
+    const dim3 grid_e(grid.x + (unsigned)ea.ntiles);
 #define STX_FWD(D, Y, P)                                                                                        \
     hipLaunchKernelGGL((k_forward_stacked<LPR, ITERS, D, Y, P>), grid, dim3(kThreads), 0, c->stream, fa)
 #define STX_FWD2(D)                                                                                             \
     do {                                                                                                        \
-        if (from_y) STX_FWD(D, true, false);                                                                    \
+        if (from_y && ea.ntiles)                                                                                \
+            hipLaunchKernelGGL((k_forward_y_emit<LPR, ITERS, D>), grid_e, dim3(kThreads), 0, c->stream, fa, ea); \
+        else if (from_y) STX_FWD(D, true, false);                                                               \
         else if (is_sign_kind(D)) STX_FWD(D, false, is_sign_kind(D));                                           \
         else STX_FWD(D, false, false);                                                                          \
     } while (0)

@@ -253,7 +253,7 @@ ScatterAhead take_scatter_ahead(stx_ctx *);
 HistAhead take_hist_ahead(stx_ctx *);
 stx_status launch_seg_write_late(stx_ctx *);
 // stx_transr.hip: item lists and bf16 copies of M_r in the launch of the first scatter pass; false: not possible
-bool launch_prep_scatter(stx_ctx *, const stx_incidence *, const stx_params *, const ScatterArgs &);
+bool launch_prep_scatter(stx_ctx *, const stx_incidence *, const stx_params *, const ScatterArgs &, bool first);
 // stx_step.hip
 // (first: the sort's first pass, whose payloads are the positions; false: shape not covered)
 bool launch_fwd_scatter(stx_ctx *, const stx_incidence *, StepFusion *, const ScatterArgs &, bool first);

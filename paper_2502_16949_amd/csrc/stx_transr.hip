@@ -268,9 +268,11 @@ __global__ __launch_bounds__(kThreads) void k_transr_prepare(PrepArgs p)
 
 // stx_train_step: with the rows per relation counted while A was written, the preparation depends on
 // nothing the sort produces and shares the launch of its first scatter pass (whose workgroups come first).
+// (FIRST false: a later pass, when the first one ran ahead of time in a launch of the previous step)
+template <bool FIRST>
 __global__ __launch_bounds__(kThreads) void k_prep_scatter(PrepArgs p, ScatterArgs sa)
 {
-    if ((int)blockIdx.x < sa.ntiles) scatter_body<true, false, kSortItems>((int)blockIdx.x, sa);
+    if ((int)blockIdx.x < sa.ntiles) scatter_body<FIRST, false, kSortItems>((int)blockIdx.x, sa);
     else transr_prepare_body<true>((int)blockIdx.x - sa.ntiles, p);
 }
 
@@ -278,6 +280,7 @@ struct RowsArgs {
     const int4 *items;
     const int32_t *counts;       // [0] = number of row items
     const int32_t *colidx, *packed;
+    const int32_t *pay;          // the sort's payloads (3*row + slot) in place of `packed`, or null
     const float *E, *Rv;
     const uint16_t *Mb;          // operand-order copies of M_r: n_out rows, reduction n_red
     uint16_t *tiles;             // per item: the 64-entry operand tile transposed, n_red rows in operand order
@@ -326,7 +329,7 @@ __global__ __launch_bounds__(kThreads) void k_transr_rows(RowsArgs p, const floa
     if (tid < 64) {
         int32_t row = -1, hh = 0, tt = 0;
         if (tid < count) {
-            row = p.packed[begin + tid] >> 2;
+            row = p.pay ? p.pay[begin + tid] / 3 : p.packed[begin + tid] >> 2;
             if (!GX) { hh = p.colidx[3 * row]; tt = p.colidx[3 * row + 2]; }
         }
         s_row[tid] = row; s_h[tid] = hh; s_t[tid] = tt;
@@ -589,6 +592,8 @@ static RowsArgs rows_args(stx_ctx *c, const stx_incidence *inc, const stx_params
     a.items = (const int4 *)c->tr_items;
     a.counts = c->tr_counts;
     a.colidx = inc->a_colidx; a.packed = inc->at_packed;
+    // (stx_train_step may have left the last kernel of the build, which writes `packed`, to a later launch)
+    a.pay = (c->segw.armed && c->sorted_inc == inc) ? c->segw.args.pay : nullptr;
     a.E = p->ent; a.Rv = p->rel;
     a.Mb = gx ? c->tr_m16t : c->tr_m16;
     a.tiles = gx ? c->tr_gyt : c->tr_xt;
@@ -621,14 +626,15 @@ static PrepArgs prep_args(stx_ctx *c, const stx_incidence *inc, const stx_params
     return a;
 }
 
-bool launch_prep_scatter(stx_ctx *c, const stx_incidence *inc, const stx_params *p, const ScatterArgs &sa)
+bool launch_prep_scatter(stx_ctx *c, const stx_incidence *inc, const stx_params *p, const ScatterArgs &sa, bool first)
 {
     if (c->cfg.model != STX_TRANSR || inc->n_rows == 0) return false;
     const PrepArgs a = prep_args(c, inc, p);
     if (!a.rel_cnt) return false;
     ProfScope prof(c, "k_prep_scatter");
-    hipLaunchKernelGGL(k_prep_scatter, dim3((unsigned)(sa.ntiles + c->cfg.n_rel + a.nplan)), dim3(kThreads), 0,
-                       c->stream, a, sa);
+    const dim3 grid((unsigned)(sa.ntiles + c->cfg.n_rel + a.nplan));
+    if (first) hipLaunchKernelGGL(k_prep_scatter<true>, grid, dim3(kThreads), 0, c->stream, a, sa);
+    else hipLaunchKernelGGL(k_prep_scatter<false>, grid, dim3(kThreads), 0, c->stream, a, sa);
     c->prep_inc = inc;
     return true;
 }
@@ -637,6 +643,7 @@ stx_status launch_transr_project(stx_ctx *c, const stx_incidence *inc, const stx
 {
     if (inc->n_rows == 0) return STX_OK;
     if (c->prep_inc != inc) {   // not yet prepared beside the sort
+        launch_seg_write_late(c);   // (the segment lists may be needed)
         const PrepArgs a = prep_args(c, inc, p);
         ProfScope prof(c, "k_transr_prepare");
         if (a.rel_cnt)
