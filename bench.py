@@ -61,6 +61,7 @@ TRAFFIC_BYTES = {("mid", "k_fwd_scatter", True): 26.10e6 + 7.33e6,
                  ("transh", "k_seg_reduce", "rides"): 142.21e6 + 14.78e6,
                  ("transh", "k_fwdh_scatter", "rides"): 33.72e6 + 105.21e6,
                  ("transh", "k_seg_fixup", "rides"): 4.01e6 + 0.48e6,
+                 ("transr", "k_transr_project", "rides"): 28.35e6 + 25.11e6,
                  # the other modes (profiles/semiring_complex_*_kernel_trace.txt, profiles/rank_mid_kernel_trace.txt)
                  ("semiring complex", "mid", "k_semiring_terms"): 66.64e6 + 100.66e6,
                  ("semiring complex", "toruse", "k_semiring_terms"): 1560.16e6 + 2013.27e6}

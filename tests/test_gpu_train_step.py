@@ -131,7 +131,8 @@ LOOKAHEAD_CASES = [
     ("toruse", "torus_l1", 40000, 100, 5000, 2, 128, 0),         # 16 key bits, 30,000 entries: 30 sort tiles
     ("transe", "l2", 70000, 5, 3000, 1, 32, 0),                  # no presence bitmap: `next` is ignored
     ("transe", "l2", 300, 5, 200, 1, 512, 0),                    # wide rows (column slices): `next` is ignored
-    ("transr", "l2", 300, 8, 500, 1, 64, B.STX_FLAG_BF16_PROJ),  # TransR counts rows per relation: `next` is ignored
+    ("transr", "l2", 300, 8, 500, 1, 64, B.STX_FLAG_BF16_PROJ),  # TransR: the early kernel also counts rows per relation
+    ("transr", "l2", 2000, 40, 3000, 2, 128, B.STX_FLAG_BF16_PROJ),  # ... at the benchmark's width, several negatives
 ]
 
 
