@@ -719,7 +719,9 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
     ScatterAhead r_scat{}, f_scat{};
     HistAhead f_hist{};
     if (raw_now) {
-        r_scat = take_scatter_ahead(c);
+        // (the scatter pass writes one of the sort's buffers: not in this launch if that is the one this product
+        // reads, as after a sort of one or three passes; the fix-up launch reads neither)
+        if (!c->ahead.scatter_ok || c->ahead.sargs.keys_out != segw.args.keys) r_scat = take_scatter_ahead(c);
         if (r_scat.ntiles == 0) r_emit = take_emit_ahead(c);
         if (ntiles > 1) {   // a fix-up launch follows
             f_hist = take_hist_ahead(c);

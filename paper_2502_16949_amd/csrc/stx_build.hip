@@ -218,6 +218,10 @@ ScatterAhead take_scatter_ahead(stx_ctx *c)
 {
     if (!c->ahead.armed || !c->ahead.emit_done || !c->ahead.scatter_ok || c->ahead.scatter_done) return ScatterAhead{};
     c->ahead.scatter_done = true;
+    if (c->ahead.sargs.keys_out == c->sorted_keys) {   // the last build's sorted keys are about to be overwritten
+        c->sorted_inc = nullptr;
+        c->sorted_keys = nullptr;
+    }
     return ScatterAhead{c->ahead.sargs, c->ahead.ntiles};
 }
 

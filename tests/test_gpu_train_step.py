@@ -133,6 +133,7 @@ LOOKAHEAD_CASES = [
     ("transe", "l2", 300, 5, 200, 1, 512, 0),                    # wide rows (column slices): `next` is ignored
     ("transr", "l2", 300, 8, 500, 1, 64, B.STX_FLAG_BF16_PROJ),  # TransR: the early kernel also counts rows per relation
     ("transr", "l2", 2000, 40, 3000, 2, 128, B.STX_FLAG_BF16_PROJ),  # ... at the benchmark's width, several negatives
+    ("transr", "l2", 100, 4, 700, 1, 64, B.STX_FLAG_BF16_PROJ),  # one sort pass: the early scatter pass must wait for the fix-up launch
 ]
 
 
