@@ -38,7 +38,7 @@ __global__ __launch_bounds__(kThreads) void k_finish_loss(const float *__restric
 }
 
 template <int LPR, int ITERS, int DIST, bool FROM_Y, bool PACKED>
-__global__ __launch_bounds__(kThreads) void k_forward_stacked(ForwardArgs a)
+__global__ __launch_bounds__(kThreads, ITERS == 1 ? 8 : 1) void k_forward_stacked(ForwardArgs a)
 {
     forward_stacked_body<LPR, ITERS, DIST, FROM_Y, PACKED>((int)blockIdx.x, a);
 }
