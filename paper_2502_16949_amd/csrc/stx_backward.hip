@@ -185,18 +185,30 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
                                                          ScatterAhead sca)
 {
     constexpr bool RAW = RIDE != 0;
+    // One block of LDS for whichever part a workgroup plays (the parts' own arrays would add up and cost the
+    // launch wavefronts per CU): the product's arrays below, or those of a body that rides.
+    constexpr int GROUPS_ = kThreads / LPR, ROWF_ = ITERS * LPR * 4;
+    constexpr int OWN_LDS = (GROUPS_ * 2 * ROWF_ + (FUSED ? GROUPS_ * ROWF_ : 4) + 5 * GROUPS_) * 4;
+    constexpr int RIDE_LDS = RIDE == 0 ? 0
+                             : RIDE == 3 ? kScatterLds
+                             : (RIDE == 2 || RIDE == 4) ? emit_lds(true, RIDE == 4)
+                                                         : (kFinishLds > kSegWriteLds ? kFinishLds : kSegWriteLds);
+    constexpr int ARENA_LDS = OWN_LDS > RIDE_LDS ? OWN_LDS : RIDE_LDS;
+    static_assert(kFinishLds <= OWN_LDS || RIDE == 0 || kFinishLds <= RIDE_LDS, "the loss sum fits the block");
+    __shared__ __align__(16) unsigned char s_arena[ARENA_LDS];
     int block = (int)blockIdx.x;
     if constexpr (RAW) {
         static_assert(FUSED, "the segment of an entry is not known here");
+        static_assert(kSegWriteLds <= ARENA_LDS && kFinishLds <= ARENA_LDS, "riders fit the block of LDS");
         if (block < sw.ntiles) {      // uniform in the workgroup
-            if (sw.use_map) seg_write_body<true>(block, sw.ntiles, sw.args);
-            else seg_write_body<false>(block, sw.ntiles, sw.args);
+            if (sw.use_map) seg_write_body<true, true>(block, sw.ntiles, sw.args, s_arena);
+            else seg_write_body<false, true>(block, sw.ntiles, sw.args, s_arena);
             return;
         }
         block -= sw.ntiles;
         if (sw.fin_n > 0) {
             if (block == 0) {
-                finish_loss_body(sw.fin_partials, sw.fin_n, sw.fin_scale, sw.fin_loss);
+                finish_loss_body<true>(sw.fin_partials, sw.fin_n, sw.fin_scale, sw.fin_loss, s_arena);
                 return;
             }
             --block;
@@ -204,14 +216,14 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
     }
     if constexpr (RIDE == 2 || RIDE == 4) {
         if (block < ea.ntiles) {      // uniform in the workgroup
-            emit_body<kSortItems, true, true, RIDE == 4>(block, ea.ntiles, ea.args);
+            emit_body<kSortItems, true, true, RIDE == 4, true>(block, ea.ntiles, ea.args, s_arena);
             return;
         }
         block -= ea.ntiles;
     }
     if constexpr (RIDE == 3) {
         if (block < sca.ntiles) {
-            scatter_body<true, false, kSortItems>(block, sca.args);
+            scatter_body<true, false, kSortItems, true>(block, sca.args, s_arena);
             return;
         }
         block -= sca.ntiles;
@@ -245,13 +257,14 @@ __global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restri
     static_assert(CHUNK <= LPR && CHUNK % UNROLL == 0, "one entry per lane per chunk");
     constexpr int VROWS = PACKED ? 1 : UNROLL;
     constexpr int ROWF = ITERS * LPR * 4;   // floats per staged row in LDS
-    __shared__ float s_part[GROUPS][2][ROWF];
-    __shared__ int s_info[GROUPS];
-    __shared__ int32_t s_seg_first[GROUPS], s_seg_last[GROUPS];
+    static_assert(GROUPS == GROUPS_ && ROWF == ROWF_, "sizes of the block of LDS");
+    float (*s_part)[2][ROWF] = reinterpret_cast<float (*)[2][ROWF]>(s_arena);
     // FUSED: table row and column of the run that leaves each chunk to the right; which chunk's they are for
     // the stitched run that closes in a chunk (-1: none closes there)
-    __shared__ float s_x[FUSED ? GROUPS : 1][FUSED ? ROWF : 4];
-    __shared__ int32_t s_col_last[GROUPS], s_fin_src[GROUPS];
+    float (*s_x)[FUSED ? ROWF : 4] = reinterpret_cast<float (*)[FUSED ? ROWF : 4]>(s_arena + GROUPS * 2 * ROWF * 4);
+    int32_t *s_small = reinterpret_cast<int32_t *>(s_arena + (GROUPS * 2 * ROWF + (FUSED ? GROUPS * ROWF : 4)) * 4);
+    int32_t *s_info = s_small, *s_seg_first = s_small + GROUPS, *s_seg_last = s_small + 2 * GROUPS;
+    int32_t *s_col_last = s_small + 3 * GROUPS, *s_fin_src = s_small + 4 * GROUPS;
 
     const int lig = threadIdx.x % LPR, grp = threadIdx.x / LPR;
     const int pk_sh = PACKED ? 31 - __clz(ld_src) : 0;

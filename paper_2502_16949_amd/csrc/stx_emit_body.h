@@ -20,8 +20,9 @@ __device__ inline uint64_t splitmix64_at(uint64_t seed, uint64_t ctr)
 }
 
 // `block` of `nblocks`: the index of the workgroup among those of the emit (the launch may hold others).
-template <int ITEMS, bool MAP, bool SAMPLE, bool RC>
-__device__ inline void emit_body(const int block, const int nblocks, const EmitArgs &a)
+// ARENA: the body's LDS arrays live in the emit_lds(MAP, RC) bytes at `lds` instead of arrays of its own.
+template <int ITEMS, bool MAP, bool SAMPLE, bool RC, bool ARENA = false>
+__device__ inline void emit_body(const int block, const int nblocks, const EmitArgs &a, unsigned char *lds = nullptr)
 {
     const BatchPtrs &bp = a.bp;
     const int32_t n_ent = a.n_ent, n_rel = a.n_rel, nnz = a.nnz;
@@ -34,9 +35,18 @@ __device__ inline void emit_body(const int block, const int nblocks, const EmitA
     int32_t *__restrict__ ctrl = a.ctrl;
     const ColMap &map = a.map;
     const RelCnt &rc = a.rc;
-    __shared__ int32_t s_hist[256];
-    __shared__ uint32_t s_map[MAP ? kMapMaxWords : 1];
-    __shared__ int32_t s_rc[RC ? kRelCntMax : 1];
+    int32_t *s_hist, *s_rc;
+    uint32_t *s_map;
+    if constexpr (ARENA) {
+        s_hist = reinterpret_cast<int32_t *>(lds);
+        s_map = reinterpret_cast<uint32_t *>(lds) + 256;
+        s_rc = s_hist + 256 + (MAP ? kMapMaxWords : 4);
+    } else {
+        __shared__ int32_t o_hist[256];
+        __shared__ uint32_t o_map[MAP ? kMapMaxWords : 1];
+        __shared__ int32_t o_rc[RC ? kRelCntMax : 1];
+        s_hist = o_hist; s_map = o_map; s_rc = o_rc;
+    }
     const int tid = threadIdx.x;
     s_hist[tid] = 0;
     if (RC) {

@@ -36,10 +36,18 @@ __device__ inline void write_grad_row(float *__restrict__ g, int d4, int lig, co
 }
 
 // Sum of the per-workgroup loss partials in a fixed order (one workgroup, after the forward kernel).
+// ARENA: the body's LDS array lives in the kFinishLds bytes at `lds` (8-byte aligned) instead of its own.
+template <bool ARENA = false>
 __device__ inline void finish_loss_body(const float *__restrict__ partials, int n, float scale,
-                                        float *__restrict__ loss)
+                                        float *__restrict__ loss, unsigned char *lds = nullptr)
 {
-    __shared__ double s_acc[kThreads];
+    double *s_acc;
+    if constexpr (ARENA) {
+        s_acc = reinterpret_cast<double *>(lds);
+    } else {
+        __shared__ double o_acc[kThreads];
+        s_acc = o_acc;
+    }
     const int tid = threadIdx.x;
     double a = 0.0;
     int i = tid;

@@ -38,6 +38,13 @@ inline Launch row_launch(int width)
 }
 
 
+// LDS bytes of the kernel bodies that can run as part of another kernel's launch.  Such a kernel hands every
+// body the same block of LDS (the bodies' own arrays would add up and cost it wavefronts per CU).
+constexpr int kScatterLds = (256 + 4 * 256 + 2 * 1024) * 4;
+constexpr int kSegWriteLds = (kThreads + 4) * 4;
+constexpr int kFinishLds = kThreads * 8;
+constexpr int emit_lds(bool map, bool rc) { return (256 + (map ? kMapMaxWords : 4) + (rc ? kRelCntMax : 4)) * 4; }
+
 // What the first kernel of a build (k_emit, stx_emit_body.h) takes; plain data, shared with the host code
 // that prepares a build ahead of time.
 struct BatchPtrs {

@@ -13,14 +13,24 @@ namespace stx {
 // MAP: the segment of an entry is the rank of its column in the presence bitmap (every workgroup counts the
 // bits of the map itself: a prefix per thread's share of the words in LDS, the words in between read again
 // from the cached map); otherwise it is counted from the heads of the earlier tiles (k_seg_count).
-template <bool MAP>
-__device__ inline void seg_write_body(const int block, const int nblocks, const SegWriteArgs &a)
+// ARENA: the body's LDS arrays live in the kSegWriteLds bytes at `lds` instead of arrays of its own.
+template <bool MAP, bool ARENA = false>
+__device__ inline void seg_write_body(const int block, const int nblocks, const SegWriteArgs &a,
+                                      unsigned char *lds = nullptr)
 {
     const int32_t *__restrict__ keys = a.keys;
     const int32_t *__restrict__ pay = a.pay;
     const int32_t nnz = a.nnz;
-    __shared__ int32_t s_base;
-    __shared__ int32_t s_chunk[MAP ? kThreads : 1];
+    int32_t *s_base_p, *s_chunk;
+    if constexpr (ARENA) {
+        s_chunk = reinterpret_cast<int32_t *>(lds);
+        s_base_p = s_chunk + kThreads;
+    } else {
+        __shared__ int32_t o_base;
+        __shared__ int32_t o_chunk[MAP ? kThreads : 1];
+        s_base_p = &o_base; s_chunk = o_chunk;
+    }
+    int32_t &s_base = *s_base_p;
     const int tid = threadIdx.x;
     if (tid == 0) s_base = 0;
     __syncthreads();

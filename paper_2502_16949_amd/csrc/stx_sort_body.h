@@ -42,8 +42,9 @@ __device__ inline void hist_body(const int block, const int32_t *__restrict__ ke
 // derived here from the raw tile counts: directly when there are few tiles (TWO_LEVEL false), through
 // the group sums of k_super_sums otherwise.
 // `block` is the tile (the index of the workgroup among those of the scatter; the launch may hold others).
-template <bool FIRST, bool TWO_LEVEL, int ITEMS>
-__device__ inline void scatter_body(const int block, const ScatterArgs &a)
+// ARENA: the body's LDS arrays live in the kScatterLds bytes at `lds` instead of arrays of its own.
+template <bool FIRST, bool TWO_LEVEL, int ITEMS, bool ARENA = false>
+__device__ inline void scatter_body(const int block, const ScatterArgs &a, unsigned char *lds = nullptr)
 {
     const int32_t *__restrict__ keys_in = a.keys_in;
     const int32_t *__restrict__ pay_in = a.pay_in;
@@ -53,8 +54,16 @@ __device__ inline void scatter_body(const int block, const ScatterArgs &a)
     const int shift = a.shift, bits = a.bits, ntiles = a.ntiles;
     const int32_t *__restrict__ table = a.table;
     const int32_t *__restrict__ super = a.super;
-    __shared__ int32_t s_goff[256];
-    __shared__ int32_t s_hist[4][256];
+    int32_t *s_goff, (*s_hist)[256], *s_tot, *s_bel;
+    if constexpr (ARENA) {
+        int32_t *p = reinterpret_cast<int32_t *>(lds);
+        s_goff = p; s_hist = reinterpret_cast<int32_t (*)[256]>(p + 256); s_tot = p + 1280; s_bel = p + 2304;
+    } else {
+        __shared__ int32_t o_goff[256];
+        __shared__ int32_t o_hist[4][256];
+        __shared__ int32_t o_tot[TWO_LEVEL ? 1 : 1024], o_bel[TWO_LEVEL ? 1 : 1024];
+        s_goff = o_goff; s_hist = o_hist; s_tot = o_tot; s_bel = o_bel;
+    }
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int radix = 1 << bits;
     for (int i = tid; i < 4 * 256; i += kThreads) (&s_hist[0][0])[i] = 0;
@@ -81,23 +90,24 @@ __device__ inline void scatter_body(const int block, const ScatterArgs &a)
         s_goff[tid] = base + below;
     } else {
         // All 256 threads share the table: a thread owns four neighbouring digits (one 16-byte load per
-        // tile row) and every `parts`-th tile; up to 16 loads are in flight per thread.
-        __shared__ int32_t s_tot[1024], s_bel[1024];
+        // tile row) and every `parts`-th tile; up to SCAN loads are in flight per thread (few enough registers
+        // that this body does not lower the occupancy of the kernels it shares launches with).
         const int me = block;
         int32_t below = 0, total = 0;
         if (radix >= 4) {
             const int r4 = radix >> 2, parts = kThreads / r4, d4 = tid % r4, q = tid / r4;
             int4 tot = make_int4(0, 0, 0, 0), bel = make_int4(0, 0, 0, 0);
-            for (int t0 = q; t0 < ntiles; t0 += 16 * parts) {
-                int4 v[16];
+            constexpr int SCAN = 8;
+            for (int t0 = q; t0 < ntiles; t0 += SCAN * parts) {
+                int4 v[SCAN];
 #pragma unroll
-                for (int u = 0; u < 16; ++u) {
+                for (int u = 0; u < SCAN; ++u) {
                     const int t = t0 + u * parts;
                     v[u] = t < ntiles ? *reinterpret_cast<const int4 *>(table + t * radix + 4 * d4)
                                       : make_int4(0, 0, 0, 0);
                 }
 #pragma unroll
-                for (int u = 0; u < 16; ++u) {
+                for (int u = 0; u < SCAN; ++u) {
                     const int t = t0 + u * parts;
                     tot.x += v[u].x; tot.y += v[u].y; tot.z += v[u].z; tot.w += v[u].w;
                     if (t < me) { bel.x += v[u].x; bel.y += v[u].y; bel.z += v[u].z; bel.w += v[u].w; }
