@@ -16,15 +16,19 @@
 
 namespace stx {
 
+// LDS of the launches below that run bodies of the sort beside a forward pass: the larger of the two bodies' needs
+constexpr int kRideLds = kScatterLds > emit_lds(true, false) ? kScatterLds : emit_lds(true, false);
+
 // (a later pass, FIRST false, can also take the first kernel of the next batch's build along: ea.ntiles > 0)
 template <int LPR, int ITERS, int DIST, bool PACKED, bool FIRST>
 __global__ __launch_bounds__(kThreads) void k_fwd_scatter(ForwardArgs fa, ScatterArgs sa, EmitAhead ea)
 {
+    __shared__ __align__(16) unsigned char s_arena[kRideLds];   // one block of LDS for the sort's bodies
     int block = (int)blockIdx.x;
-    if (block < sa.ntiles) { scatter_body<FIRST, false, kSortItems>(block, sa); return; }
+    if (block < sa.ntiles) { scatter_body<FIRST, false, kSortItems, true>(block, sa, s_arena); return; }
     block -= sa.ntiles;
     if constexpr (!FIRST) {
-        if (block < ea.ntiles) { emit_body<kSortItems, true, true, false>(block, ea.ntiles, ea.args); return; }
+        if (block < ea.ntiles) { emit_body<kSortItems, true, true, false, true>(block, ea.ntiles, ea.args, s_arena); return; }
         block -= ea.ntiles;
     }
     forward_stacked_body<LPR, ITERS, DIST, false, PACKED>(block, fa);
@@ -33,11 +37,12 @@ __global__ __launch_bounds__(kThreads) void k_fwd_scatter(ForwardArgs fa, Scatte
 template <int LPR, int ITERS, int DIST, bool FIRST>
 __global__ __launch_bounds__(kThreads) void k_fwdh_scatter(TranshArgs ta, ScatterArgs sa, EmitAhead ea)
 {
+    __shared__ __align__(16) unsigned char s_arena[kRideLds];
     int block = (int)blockIdx.x;
-    if (block < sa.ntiles) { scatter_body<FIRST, false, kSortItems>(block, sa); return; }
+    if (block < sa.ntiles) { scatter_body<FIRST, false, kSortItems, true>(block, sa, s_arena); return; }
     block -= sa.ntiles;
     if constexpr (!FIRST) {
-        if (block < ea.ntiles) { emit_body<kSortItems, true, true, false>(block, ea.ntiles, ea.args); return; }
+        if (block < ea.ntiles) { emit_body<kSortItems, true, true, false, true>(block, ea.ntiles, ea.args, s_arena); return; }
         block -= ea.ntiles;
     }
     forward_transh_body<LPR, ITERS, DIST>(block, ta);
@@ -60,10 +65,11 @@ __global__ __launch_bounds__(kThreads) void k_fwd_hist(ForwardArgs fa, const int
                                                        int shift, int radix, int32_t *__restrict__ table, int ntiles,
                                                        EmitAhead ea)
 {
+    __shared__ __align__(16) unsigned char s_arena[emit_lds(true, false)];
     int block = (int)blockIdx.x;
     if (block < ntiles) { hist_body<kSortItems>(block, keys, nnz, shift, radix, table); return; }
     block -= ntiles;
-    if (block < ea.ntiles) { emit_body<kSortItems, true, true, false>(block, ea.ntiles, ea.args); return; }
+    if (block < ea.ntiles) { emit_body<kSortItems, true, true, false, true>(block, ea.ntiles, ea.args, s_arena); return; }
     forward_stacked_body<LPR, ITERS, DIST, false, PACKED>(block - ea.ntiles, fa);
 }
 
@@ -72,10 +78,11 @@ __global__ __launch_bounds__(kThreads) void k_fwdh_hist(TranshArgs ta, const int
                                                         int shift, int radix, int32_t *__restrict__ table, int ntiles,
                                                         EmitAhead ea)
 {
+    __shared__ __align__(16) unsigned char s_arena[emit_lds(true, false)];
     int block = (int)blockIdx.x;
     if (block < ntiles) { hist_body<kSortItems>(block, keys, nnz, shift, radix, table); return; }
     block -= ntiles;
-    if (block < ea.ntiles) { emit_body<kSortItems, true, true, false>(block, ea.ntiles, ea.args); return; }
+    if (block < ea.ntiles) { emit_body<kSortItems, true, true, false, true>(block, ea.ntiles, ea.args, s_arena); return; }
     forward_transh_body<LPR, ITERS, DIST>(block - ea.ntiles, ta);
 }
 
