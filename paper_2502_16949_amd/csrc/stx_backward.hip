@@ -175,7 +175,7 @@ __device__ inline void apply_update(float *__restrict__ row, int d4, int lig, co
 // RIDE: 0 none of this; 1 RAW; 2 RAW, and the first kernel of the next batch's build comes along; 3 RAW, and the
 // first scatter pass of the next batch's sort comes along; 4 as 2, and that kernel counts the rows per relation.
 template <int LPR, int ITERS, bool PACKED, int CHUNK, bool FUSED, int RIDE>
-__global__ __launch_bounds__(kThreads) void k_seg_reduce(const int32_t *__restrict__ packed,
+__global__ __launch_bounds__(kThreads, (ITERS == 1 && PACKED && FUSED && RIDE != 4) ? 8 : 1) void k_seg_reduce(const int32_t *__restrict__ packed,
                                                          const int32_t *__restrict__ seg_id, int32_t e_begin,
                                                          int32_t e_end, const float *__restrict__ src_a,
                                                          const float *__restrict__ src_b, int32_t split,
