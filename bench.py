@@ -55,8 +55,8 @@ TRAFFIC_BYTES = {("mid", "k_fwd_scatter", True): 26.10e6 + 7.33e6,
                  # mean of the two batches of an epoch (393,216 and 89,926 positives), like the timed mean
                  ("paper_transe", "k_seg_reduce", True): (9761.85e6 + 104.19e6 + 2281.04e6 + 99.90e6) / 2,
                  # with the look-ahead (the next batch's first build kernels ride in these launches)
-                 ("mid", "k_seg_reduce", "rides"): 28.40e6 + 13.93e6,
-                 ("mid", "k_fwd_scatter", "rides"): 27.46e6 + 9.24e6,
+                 ("mid", "k_seg_reduce", "rides"): 28.03e6 + 17.01e6,
+                 ("mid", "k_fwd_scatter", "rides"): 27.48e6 + 9.24e6,
                  ("mid", "k_seg_fixup", "rides"): 3.62e6 + 0.42e6,
                  ("transh", "k_seg_reduce", "rides"): 142.21e6 + 14.78e6,
                  ("transh", "k_fwdh_scatter", "rides"): 33.72e6 + 105.21e6,
