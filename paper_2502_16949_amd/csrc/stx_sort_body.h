@@ -24,10 +24,21 @@ __device__ inline void hist_body(const int block, const int32_t *__restrict__ ke
         const int32_t e = base + it * kThreads + tid;
         kv[it] = e < nnz ? keys[e] : 0;
     }
+    // The lanes of a wavefront that hold the same digit are found by a ballot per bit, and one of them adds their
+    // number: power-law keys put many lanes on one counter, and LDS serialises atomics on one address.
+    const int bits = 31 - __clz(radix), lane = tid & 63;
 #pragma unroll
     for (int it = 0; it < ITEMS; ++it) {
         const int32_t e = base + it * kThreads + tid;
-        if (e < nnz) atomicAdd(&s_hist[(kv[it] >> shift) & (radix - 1)], 1);
+        const bool valid = e < nnz;
+        const int dgt = (kv[it] >> shift) & (radix - 1);
+        uint64_t m = __ballot(valid);
+        for (int bit = 0; bit < bits; ++bit) {
+            const bool one = (dgt >> bit) & 1;
+            const uint64_t bm = __ballot(one);
+            m &= one ? bm : ~bm;
+        }
+        if (valid && ((m >> lane) >> 1) == 0) atomicAdd(&s_hist[dgt], (int32_t)__popcll(m));   // highest lane of its class
     }
     __syncthreads();
     if (tid < radix) table[block * radix + tid] = s_hist[tid];
