@@ -104,7 +104,8 @@ __global__ __launch_bounds__(kThreads) void k_seg_count(const int32_t *__restric
         int32_t e = base + it * kThreads + tid;
         if (e < nnz) c += (e == 0 || keys[e] != keys[e - 1]) ? 1 : 0;
     }
-    if (c) atomicAdd(&s_cnt, c);
+    for (int m = 32; m >= 1; m >>= 1) c += __shfl_xor(c, m, 64);   // one LDS atomic per wavefront, not per thread
+    if ((tid & 63) == 0 && c) atomicAdd(&s_cnt, c);
     __syncthreads();
     if (tid == 0) tile_heads[blockIdx.x] = s_cnt;
 }

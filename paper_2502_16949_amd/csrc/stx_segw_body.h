@@ -49,7 +49,8 @@ __device__ inline void seg_write_body(const int block, const int nblocks, const 
     } else {   // segments that start in earlier tiles
         int32_t h = 0;
         for (int t = tid; t < block; t += kThreads) h += a.tile_heads[t];
-        if (h) atomicAdd(&s_base, h);
+        for (int m = 32; m >= 1; m >>= 1) h += __shfl_xor(h, m, 64);   // one LDS atomic per wavefront
+        if ((tid & 63) == 0 && h) atomicAdd(&s_base, h);
     }
     const int32_t e0 = block * kSegWTile + tid * kSegWItems;
     int32_t kk[kSegWItems + 1];
