@@ -30,6 +30,24 @@ __device__ inline int32_t block_exclusive_scan(int32_t v, int32_t *total)
     return s_scan[tid] - v;
 }
 
+// The lanes of the wavefront (among those with `valid`) whose digit equals this lane's: one ballot per bit of the
+// digit, and per lane an exclusive-nor of the ballot with the lane's own bit spread over a word.
+__device__ inline uint64_t digit_class_mask(int dgt, bool valid, int bits)
+{
+    const uint64_t v = __ballot(valid);
+    uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+#pragma unroll
+    for (int bit = 0; bit < 8; ++bit) {
+        if (bit < bits) {   // uniform
+            const uint32_t x = (uint32_t)(-(int32_t)((dgt >> bit) & 1));   // all ones when the lane's bit is set
+            const uint64_t bm = __ballot(x != 0u);
+            lo &= ~((uint32_t)bm ^ x);
+            hi &= ~((uint32_t)(bm >> 32) ^ x);
+        }
+    }
+    return (uint64_t)hi << 32 | lo;
+}
+
 // Sum over the LPR consecutive lanes that share a row (LPR a power of two <= 64, groups aligned).
 // Butterfly: every lane of the group ends with the same bits.
 template <int LPR>

@@ -32,12 +32,7 @@ __device__ inline void hist_body(const int block, const int32_t *__restrict__ ke
         const int32_t e = base + it * kThreads + tid;
         const bool valid = e < nnz;
         const int dgt = (kv[it] >> shift) & (radix - 1);
-        uint64_t m = __ballot(valid);
-        for (int bit = 0; bit < bits; ++bit) {
-            const bool one = (dgt >> bit) & 1;
-            const uint64_t bm = __ballot(one);
-            m &= one ? bm : ~bm;
-        }
+        const uint64_t m = digit_class_mask(dgt, valid, bits);
         if (valid && ((m >> lane) >> 1) == 0) atomicAdd(&s_hist[dgt], (int32_t)__popcll(m));   // highest lane of its class
     }
     __syncthreads();
@@ -159,12 +154,7 @@ __device__ inline void scatter_body(const int block, const ScatterArgs &a, unsig
         int32_t e = wave_base + it * 64 + lane;
         bool valid = e < nnz;
         int dgt = (key[it] >> shift) & (radix - 1);
-        uint64_t m = __ballot(valid);
-        for (int bit = 0; bit < bits; ++bit) {
-            bool one = (dgt >> bit) & 1;
-            uint64_t bm = __ballot(one);
-            m &= one ? bm : ~bm;
-        }
+        const uint64_t m = digit_class_mask(dgt, valid, bits);
         int32_t prior = s_hist[w][dgt];
         rank[it] = prior + __popcll(m & below);
         bool leader = valid && ((m >> lane) >> 1) == 0;   // highest lane of its digit class
