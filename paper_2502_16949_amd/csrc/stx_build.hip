@@ -255,7 +255,7 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
     const int32_t nnz = (int32_t)inc->nnz;
     // keys per thread: few when the sort is small (more workgroups, shorter serial ranking per workgroup),
     // more when it is large (fewer tiles, smaller histogram table)
-    const int items = nnz <= (1 << 19) ? kSortItems : 2 * kSortItems;
+    const int items = nnz <= (1 << 19) ? kSortItems : kBigSortItems;
     const int ntiles = (nnz + kThreads * items - 1) / (kThreads * items);
     const int n_ent = (int)c->cfg.n_ent, n_rel = (int)c->cfg.n_rel;
     BatchPtrs bp{h, r, t, nh, nt, b, k > 0 ? k : 1, nullptr, nullptr, 0, 0};
@@ -309,7 +309,7 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
 #define STX_EMIT3(I, M, S) do { if (use_rc) STX_EMIT(I, M, S, true); else STX_EMIT(I, M, S, false); } while (0)
 #define STX_EMIT2(I, M) do { if (sample) STX_EMIT3(I, M, true); else STX_EMIT3(I, M, false); } while (0)
     if (items == kSortItems) { if (use_map) STX_EMIT2(kSortItems, true); else STX_EMIT2(kSortItems, false); }
-    else                     { if (use_map) STX_EMIT2(2 * kSortItems, true); else STX_EMIT2(2 * kSortItems, false); }
+    else                     { if (use_map) STX_EMIT2(kBigSortItems, true); else STX_EMIT2(kBigSortItems, false); }
 #undef STX_EMIT2
 #undef STX_EMIT3
 #undef STX_EMIT
@@ -338,7 +338,7 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
                 hipLaunchKernelGGL(k_hist<kSortItems>, dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], nnz, shift,
                                    1 << bits, c->table1);
             else
-                hipLaunchKernelGGL(k_hist<2 * kSortItems>, dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], nnz, shift,
+                hipLaunchKernelGGL(k_hist<kBigSortItems>, dim3(ntiles), dim3(kThreads), 0, s, c->keys[cur], nnz, shift,
                                    1 << bits, c->table1);
         }
         if (two_level) {
@@ -350,7 +350,7 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
                              bits, ntiles, p == 0 ? c->table : c->table1, c->super};
 #define STX_SCATTER(F, S, I)                                                                                  \
     hipLaunchKernelGGL((k_scatter<F, S, I>), dim3(ntiles), dim3(kThreads), 0, s, sa)
-#define STX_SCATTER2(F, S) do { if (items == kSortItems) STX_SCATTER(F, S, kSortItems); else STX_SCATTER(F, S, 2 * kSortItems); } while (0)
+#define STX_SCATTER2(F, S) do { if (items == kSortItems) STX_SCATTER(F, S, kSortItems); else STX_SCATTER(F, S, kBigSortItems); } while (0)
         if (p == 0 && fusion && !two_level && items == kSortItems && launch_fwd_scatter(c, inc, fusion, sa, true)) {
             // the forward pass ran in the same launch
         } else if (p == 1 && counted1 && fusion && !fusion->forward_done && !two_level && items == kSortItems &&

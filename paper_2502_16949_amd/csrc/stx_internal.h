@@ -11,6 +11,7 @@ namespace stx {
 constexpr int kThreads = 256;          // every kernel here runs 256-thread workgroups (4 wavefronts)
 constexpr int kSortItems = 4;          // keys per thread in the radix-sort kernels
 constexpr int kSortTile = kThreads * kSortItems;
+constexpr int kBigSortItems = 16;      // ... in large sorts: a digit's keys of one tile then fill whole memory lines
 constexpr int kSegWItems = 8;          // sorted entries per thread in the kernels that derive the segments
 constexpr int kSegWTile = kThreads * kSegWItems;
 constexpr int kSegTileMin = 64;        // fewest sorted entries a workgroup of the transposed product may own

@@ -161,24 +161,55 @@ __device__ inline void scatter_body(const int block, const ScatterArgs &a, unsig
         if (leader) s_hist[w][dgt] = prior + __popcll(m);
     }
     __syncthreads();
+    int32_t tile_count = 0;                              // keys of the tile with digit `tid`
     if (tid < radix) {
-        int32_t a = 0;
 #pragma unroll
         for (int w2 = 0; w2 < 4; ++w2) {
             int32_t c = s_hist[w2][tid];
-            s_hist[w2][tid] = a;
-            a += c;
+            s_hist[w2][tid] = tile_count;
+            tile_count += c;
         }
     }
-    __syncthreads();
+    // Large sorts (tiles of kBigSortItems keys per thread): the tile is put in order in LDS first and written from
+    // there, so that neighbouring lanes write neighbouring addresses and a digit's keys of one tile (16 on
+    // average with 256 digits: 64 bytes) fill whole sectors; written straight from the registers every key is a
+    // partial write of its own, and the pass moves 2.5 times the bytes it has to.
+    constexpr bool LOCAL = ITEMS > kSortItems && !ARENA;
+    if constexpr (LOCAL) {
+        __shared__ int32_t s_dstart[256];
+        __shared__ int32_t s_k[kThreads * ITEMS], s_p[kThreads * ITEMS];
+        s_dstart[tid] = block_exclusive_scan(tile_count, nullptr);   // (its barriers also publish s_hist)
+        __syncthreads();
 #pragma unroll
-    for (int it = 0; it < ITEMS; ++it) {
-        int32_t e = wave_base + it * 64 + lane;
-        if (e < nnz) {
-            int dgt = (key[it] >> shift) & (radix - 1);
-            int32_t pos = s_goff[dgt] + s_hist[w][dgt] + rank[it];
-            keys_out[pos] = key[it];
-            pay_out[pos] = pay[it];
+        for (int it = 0; it < ITEMS; ++it) {
+            const int32_t e = wave_base + it * 64 + lane;
+            if (e < nnz) {
+                const int dgt = (key[it] >> shift) & (radix - 1);
+                const int32_t lp = s_dstart[dgt] + s_hist[w][dgt] + rank[it];
+                s_k[lp] = key[it];
+                s_p[lp] = pay[it];
+            }
+        }
+        __syncthreads();
+        const int32_t tile_n = min(kThreads * ITEMS, nnz - block * (kThreads * ITEMS));
+        for (int32_t i = tid; i < tile_n; i += kThreads) {
+            const int32_t kv = s_k[i];
+            const int dgt = (kv >> shift) & (radix - 1);
+            const int32_t pos = s_goff[dgt] + (i - s_dstart[dgt]);
+            keys_out[pos] = kv;
+            pay_out[pos] = s_p[i];
+        }
+    } else {
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it) {
+            int32_t e = wave_base + it * 64 + lane;
+            if (e < nnz) {
+                int dgt = (key[it] >> shift) & (radix - 1);
+                int32_t pos = s_goff[dgt] + s_hist[w][dgt] + rank[it];
+                keys_out[pos] = key[it];
+                pay_out[pos] = pay[it];
+            }
         }
     }
 }
