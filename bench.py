@@ -49,9 +49,9 @@ TRAFFIC_BYTES = {("mid", "k_fwd_scatter", True): 26.10e6 + 7.33e6,
                  ("transh", "k_fwdh_scatter", True): 32.45e6 + 101.56e6,
                  ("transr", "k_transr_project", True): 28.28e6 + 25.11e6,
                  ("transr", "k_transr_project", False): 28.28e6 + 25.11e6,
-                 ("toruse", "k_seg_reduce", True): 1142.3e6 + 532.2e6,
-                 ("toruse", "k_forward_stacked", True): 702.7e6 + 53.5e6,
-                 ("toruse", "k_forward_stacked", False): 702.7e6 + 53.5e6,
+                 ("toruse", "k_seg_reduce", True): 1165.6e6 + 623.2e6,
+                 ("toruse", "k_forward_stacked", True): 701.8e6 + 53.6e6,
+                 ("toruse", "k_forward_stacked", False): 701.8e6 + 53.6e6,
                  # mean of the two batches of an epoch (393,216 and 89,926 positives), like the timed mean
                  ("paper_transe", "k_seg_reduce", True): (9761.85e6 + 104.19e6 + 2281.04e6 + 99.90e6) / 2,
                  # with the look-ahead (the next batch's first build kernels ride in these launches)
