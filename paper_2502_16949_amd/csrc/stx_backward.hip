@@ -492,6 +492,10 @@ __global__ __launch_bounds__(kThreads) void k_seg_fixup(const int32_t *__restric
         }
         block -= ha.ntiles;
     }
+    // The tiles are taken from the last one down: the relation columns sort last and own the longest runs (one
+    // relation has a fifth of a batch's rows), whose closing workgroups add up the most partial rows; started
+    // last, after the other workgroups have come and gone, their chains would set the time of the launch.
+    block = ((int)gridDim.x - (RIDE == 1 ? sa.ntiles : RIDE == 2 ? ha.ntiles : 0)) - 1 - block;
     if (block >= sec.first_block) {   // uniform in the workgroup
         block -= sec.first_block;
         e_begin = sec.e_begin; e_end = sec.e_end;
