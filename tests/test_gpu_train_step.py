@@ -129,6 +129,9 @@ LOOKAHEAD_CASES = [
     ("transe", "l1", 50, 5, 20, 1, 128, 0),                      # one sort pass, one tile: no fix-up launch to ride in
     ("transe", "l2", 3000, 5, 20, 1, 128, 0),                    # two sort passes, no fix-up launch: only k_emit runs ahead
     ("toruse", "torus_l1", 40000, 100, 5000, 2, 128, 0),         # 16 key bits, 30,000 entries: 30 sort tiles
+    ("transe", "l1", 500, 10, 600, 1, 256, 0),                   # 64 lanes per row
+    ("transe", "l2", 300, 6, 500, 2, 32, 0),                     # 8 lanes per row
+    ("transh", "l1", 300, 6, 500, 2, 32, B.STX_FLAG_RENORM_W),
     ("transe", "l2", 70000, 5, 3000, 1, 32, 0),                  # no presence bitmap: `next` is ignored
     ("transe", "l2", 300, 5, 200, 1, 512, 0),                    # wide rows (column slices): `next` is ignored
     ("transr", "l2", 300, 8, 500, 1, 64, B.STX_FLAG_BF16_PROJ),  # TransR: the early kernel also counts rows per relation
