@@ -414,7 +414,7 @@ def main():
                              else DOMINANT_CALLS)[wl.name]
     # batches whose first build kernels can run inside the previous step's launches (see stx_batch.next)
     rides = (args.api == "step" and not args.no_lookahead and (wl.model != "transr" or wl.n_rel <= 4096)
-             and wl.n_ent + wl.n_rel <= 65536 and 3 * wl.rows_per_batch <= (1 << 18) and wl.dim <= 256)
+             and wl.n_ent + wl.n_rel <= 65536 and 3 * wl.rows_per_batch <= (1 << 19) and wl.dim <= 256)
 
     # the one-call step leaves the last kernel of the build to the launch of the transposed product (rows of one
     # float4 per lane; TransR when its work items come from the rows-per-relation counts)

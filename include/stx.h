@@ -222,7 +222,7 @@ stx_status stx_backward_sgd(stx_ctx *ctx, const stx_incidence *inc, stx_params *
  * next's neg_h / neg_t already hold the next batch's, the A^T arrays this batch's.  A next call with
  * another batch, or any other call, simply builds as usual.  Used when the configuration keeps a column
  * bitmap (n_ent + n_rel <= 65,536), with dim <= 256 (TransR: also n_rel <= 4,096) and batches of at most
- * 2^19 entries of A (all three stages up to 2^18); ignored otherwise.  next->next is ignored.            */
+ * 2^19 entries of A; ignored otherwise.  next->next is ignored.                                          */
 typedef struct stx_batch {
     const int32_t *h, *r, *t; /* [b], device */
     int32_t b, k;

@@ -16,7 +16,7 @@ constexpr int kSegWItems = 8;          // sorted entries per thread in the kerne
 constexpr int kSegWTile = kThreads * kSegWItems;
 constexpr int kSegTileMin = 64;        // fewest sorted entries a workgroup of the transposed product may own
 constexpr int kSuperTile = 32;         // sort tiles per group when the histogram table is scanned in two levels
-constexpr int kSelfScanTiles = 256;   // up to this many sort tiles, scatter workgroups scan the histograms themselves
+constexpr int kSelfScanTiles = 512;   // up to this many sort tiles, scatter workgroups scan the histograms themselves
 constexpr int kMapMaxWords = 2048;     // presence bitmap of the columns: kept when n_ent + n_rel <= 32 * this
 constexpr int kRelCntMax = 4096;       // TransR: rows per relation are counted while A is written when n_rel <= this
 constexpr int kMaxDim = 1024;

@@ -132,6 +132,7 @@ LOOKAHEAD_CASES = [
     ("transe", "l1", 500, 10, 600, 1, 256, 0),                   # 64 lanes per row
     ("transe", "l2", 300, 6, 500, 2, 32, 0),                     # 8 lanes per row
     ("transh", "l1", 300, 6, 500, 2, 32, B.STX_FLAG_RENORM_W),
+    ("transe", "l1", 20000, 50, 50000, 1, 32, 0),                # 293 sort tiles: the longest table scan in a scatter workgroup
     ("transe", "l2", 70000, 5, 3000, 1, 32, 0),                  # no presence bitmap: `next` is ignored
     ("transe", "l2", 300, 5, 200, 1, 512, 0),                    # wide rows (column slices): `next` is ignored
     ("transr", "l2", 300, 8, 500, 1, 64, B.STX_FLAG_BF16_PROJ),  # TransR: the early kernel also counts rows per relation
