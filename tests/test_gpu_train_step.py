@@ -3,6 +3,8 @@ the separate calls stx_sample_negatives + stx_build_incidence + stx_forward + st
 The separate calls are checked against the oracle in the other GPU test files; the one-call step does
 the same arithmetic in the same order, so every output must have the same bits.  The full-size checks
 of the step against the oracle itself are in test_gpu_fullsize.py."""
+import ctypes
+
 import numpy as np
 import pytest
 import torch
@@ -196,4 +198,63 @@ def test_train_step_with_the_next_batch_named_gives_the_same_bits(model, dist, n
     for name in ("ent", "rel", "w", "proj"):
         ta, tb = getattr(ma.params, name), getattr(mb.params, name)
         assert (ta is None and tb is None) or torch.equal(ta, tb), name
+    assert B.stx_check_indices(ma.ctx) == 0 and B.stx_check_indices(mb.ctx) == 0
+
+
+RANDOM_CHAIN_CASES = [
+    ("transe", "l1", 1000, 20, 128, 1, 0),
+    ("toruse", "torus_l1", 3000, 30, 128, 2, 0),
+    ("transh", "l2", 1000, 20, 128, 1, B.STX_FLAG_RENORM_W),
+    ("transr", "l2", 500, 12, 64, 1, B.STX_FLAG_BF16_PROJ),
+    ("transr", "l2", 100, 4, 128, 2, B.STX_FLAG_BF16_PROJ),   # one sort pass
+    ("transe", "l1", 120, 3, 32, 1, 0),                        # one sort pass, 8 lanes per row
+]
+
+
+@pytest.mark.parametrize("model,dist,n_ent,n_rel,dim,k,flags", RANDOM_CHAIN_CASES)
+def test_random_chains_of_linked_steps_give_the_same_bits(model, dist, n_ent, n_rel, dim, k, flags):
+    """Eighty steps over five batches of very different sizes (1 to 1,500 positives) in random order, once plain
+    and once with most calls naming a next batch: usually the one that follows, sometimes another one, sometimes
+    none; now and then a separate build + forward on the same context comes in between.  Whatever stages of the
+    next build ran ahead or were thrown away, every step leaves the same scores, loss, A^T arrays and tables."""
+    rng = np.random.default_rng(1000 * n_ent + 10 * dim + k)
+    bmax = 1500
+    wl = W.Workload("case", 12, model, dist, n_ent, n_rel, 5 * bmax, dim, dim, bmax, k, 1.0, 0.01, 1, 1.1, 1.1,
+                    bool(flags & B.STX_FLAG_BF16_PROJ))
+    tabs = W.make_tables(wl)
+    m_total = 5 * bmax
+    hd = G.dev_i32(rng.integers(0, n_ent, m_total))
+    rd = G.dev_i32(rng.integers(0, n_rel, m_total))
+    td = G.dev_i32(rng.integers(0, n_ent, m_total))
+    slices = [(q * bmax, q * bmax + s) for q, s in enumerate([bmax, 700, 1, 1499, 64])]
+    ma, mb = G.GpuModel(wl, tabs, flags=flags), G.GpuModel(wl, tabs, flags=flags)
+    nk = bmax * k
+    neg_a = [tuple(torch.zeros(nk, dtype=torch.int32, device=G.DEV) for _ in range(2)) for _ in slices]
+    neg_b = [tuple(torch.zeros(nk, dtype=torch.int32, device=G.DEV) for _ in range(2)) for _ in slices]
+    mk = lambda neg: [B.make_batch(hd[lo:hi], rd[lo:hi], td[lo:hi], k, 99, 1, m_total, lo, *neg[i])
+                      for i, (lo, hi) in enumerate(slices)]
+    plain, linked = mk(neg_a), mk(neg_b)
+    steps = 80
+    order = rng.integers(0, len(slices), steps + 1)
+    for s in range(steps):
+        i = int(order[s])
+        named = int(order[s + 1]) if rng.random() < 0.8 else int(rng.integers(0, len(slices)))
+        linked[i].next = ctypes.addressof(linked[named]) if rng.random() < 0.9 else None
+        B.stx_train_step(ma.ctx, plain[i], ma.inc, ma.params, ma.grads, 0.01, ma.scores, ma.loss)
+        B.stx_train_step(mb.ctx, linked[i], mb.inc, mb.params, mb.grads, 0.01, mb.scores, mb.loss)
+        if rng.random() < 0.1:
+            lo, hi = slices[0]
+            for m in (ma, mb):
+                B.stx_build_incidence(m.ctx, hd[lo:hi], rd[lo:hi], td[lo:hi], neg_a[0][0], neg_a[0][1], k, m.inc)
+                m.forward()
+        torch.cuda.synchronize()
+        sa, la = ma.scores_numpy()
+        sb, lb = mb.scores_numpy()
+        assert np.array_equal(sa, sb) and la == lb, s
+        ia, ib = ma.incidence_numpy(), mb.incidence_numpy()
+        for name in ("touched_cols", "seg_ptr", "row_idx", "sign", "seg_id", "packed", "n_touched"):
+            assert np.array_equal(ia[name], ib[name]), (s, name)
+        for name in ("ent", "rel", "w", "proj"):
+            ta, tb = getattr(ma.params, name), getattr(mb.params, name)
+            assert (ta is None and tb is None) or torch.equal(ta, tb), (s, name)
     assert B.stx_check_indices(ma.ctx) == 0 and B.stx_check_indices(mb.ctx) == 0
