@@ -35,7 +35,7 @@ __global__ __launch_bounds__(kThreads) void k_fwd_scatter(ForwardArgs fa, Scatte
 }
 
 template <int LPR, int ITERS, int DIST, bool FIRST>
-__global__ __launch_bounds__(kThreads) void k_fwdh_scatter(TranshArgs ta, ScatterArgs sa, EmitAhead ea)
+__global__ __launch_bounds__(kThreads, 4) void k_fwdh_scatter(TranshArgs ta, ScatterArgs sa, EmitAhead ea)
 {
     __shared__ __align__(16) unsigned char s_arena[kRideLds];
     int block = (int)blockIdx.x;
