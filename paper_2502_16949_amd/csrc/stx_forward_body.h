@@ -76,7 +76,9 @@ __device__ inline void finish_loss_body(const float *__restrict__ partials, int 
 // PACKED (L1 kinds, gathered rows only): dL/dx is written as records of gstride bytes at G (sign bytes), the
 // rows' coefficients behind the records of the batch.
 // `block` is the index of the workgroup among those of the forward pass (the launch may hold others).
-template <int LPR, int ITERS, int DIST, bool FROM_Y, bool PACKED>
+// K1: at most one negative per positive (the benchmarks' shape): no registers are kept for a batch of them, and
+// more wavefronts fit (same arithmetic in the same order, so the same bits).
+template <int LPR, int ITERS, int DIST, bool FROM_Y, bool PACKED, bool K1 = false>
 __device__ inline void forward_stacked_body(const int block, const ForwardArgs &a)
 {
     const int32_t *__restrict__ colidx = a.colidx;
@@ -100,7 +102,7 @@ __device__ inline void forward_stacked_body(const int block, const ForwardArgs &
     if (i < b) {   // uniform within the group; shuffles below stay inside the group
         // Negatives are taken NB at a time so that the kernel pays two memory round trips per batch (all
         // column ids, then all table rows) instead of two per row; the positive rides with the first batch.
-        constexpr int NB = ITERS <= 2 ? 4 : 2;
+        constexpr int NB = K1 ? 1 : (ITERS <= 2 ? 4 : 2);
         RowVec<ITERS> xp;
         float dpos = 0.f, npos = 0.f;   // the positive's score and its norm (they differ by the relation's weight)
         int n_active = 0;

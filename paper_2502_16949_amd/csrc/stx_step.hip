@@ -20,7 +20,7 @@ namespace stx {
 constexpr int kRideLds = kScatterLds > emit_lds(true, false) ? kScatterLds : emit_lds(true, false);
 
 // (a later pass, FIRST false, can also take the first kernel of the next batch's build along: ea.ntiles > 0)
-template <int LPR, int ITERS, int DIST, bool PACKED, bool FIRST>
+template <int LPR, int ITERS, int DIST, bool PACKED, bool FIRST, bool K1>
 __global__ __launch_bounds__(kThreads) void k_fwd_scatter(ForwardArgs fa, ScatterArgs sa, EmitAhead ea)
 {
     __shared__ __align__(16) unsigned char s_arena[kRideLds];   // one block of LDS for the sort's bodies
@@ -31,10 +31,10 @@ __global__ __launch_bounds__(kThreads) void k_fwd_scatter(ForwardArgs fa, Scatte
         if (block < ea.ntiles) { emit_body<kSortItems, true, true, false, true>(block, ea.ntiles, ea.args, s_arena); return; }
         block -= ea.ntiles;
     }
-    forward_stacked_body<LPR, ITERS, DIST, false, PACKED>(block, fa);
+    forward_stacked_body<LPR, ITERS, DIST, false, PACKED, K1>(block, fa);
 }
 
-template <int LPR, int ITERS, int DIST, bool FIRST>
+template <int LPR, int ITERS, int DIST, bool FIRST, bool K1>
 __global__ __launch_bounds__(kThreads, 4) void k_fwdh_scatter(TranshArgs ta, ScatterArgs sa, EmitAhead ea)
 {
     __shared__ __align__(16) unsigned char s_arena[kRideLds];
@@ -45,7 +45,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_fwdh_scatter(TranshArgs ta, Sca
         if (block < ea.ntiles) { emit_body<kSortItems, true, true, false, true>(block, ea.ntiles, ea.args, s_arena); return; }
         block -= ea.ntiles;
     }
-    forward_transh_body<LPR, ITERS, DIST>(block, ta);
+    forward_transh_body<LPR, ITERS, DIST, K1>(block, ta);
 }
 
 __global__ __launch_bounds__(kThreads) void k_hist_finish(const int32_t *__restrict__ keys, int32_t nnz, int shift,
@@ -99,12 +99,18 @@ static void fwd_scatter_go(stx_ctx *c, const ForwardArgs &fa, const ScatterArgs 
 {
 #define STX_FS(D, P)                                                                                            \
     do {                                                                                                        \
-        if (first)                                                                                              \
-            hipLaunchKernelGGL((k_fwd_scatter<LPR, ITERS, D, P, true>), dim3(blocks), dim3(kThreads), 0,        \
+        if (first && fa.k <= 1)                                                                                 \
+            hipLaunchKernelGGL((k_fwd_scatter<LPR, ITERS, D, P, true, true>), dim3(blocks), dim3(kThreads), 0,  \
+                               c->stream, fa, sa, ea);                                                          \
+        else if (first)                                                                                         \
+            hipLaunchKernelGGL((k_fwd_scatter<LPR, ITERS, D, P, true, false>), dim3(blocks), dim3(kThreads), 0, \
+                               c->stream, fa, sa, ea);                                                          \
+        else if (fa.k <= 1)                                                                                     \
+            hipLaunchKernelGGL((k_fwd_scatter<LPR, ITERS, D, P, false, true>), dim3(blocks), dim3(kThreads), 0, \
                                c->stream, fa, sa, ea);                                                          \
         else                                                                                                    \
-            hipLaunchKernelGGL((k_fwd_scatter<LPR, ITERS, D, P, false>), dim3(blocks), dim3(kThreads), 0,       \
-                               c->stream, fa, sa, ea);                                                          \
+            hipLaunchKernelGGL((k_fwd_scatter<LPR, ITERS, D, P, false, false>), dim3(blocks), dim3(kThreads),   \
+                               0, c->stream, fa, sa, ea);                                                       \
     } while (0)
     switch (c->cfg.dist) {
     case STX_L1: STX_FS(STX_L1, true); break;
@@ -122,11 +128,17 @@ static void fwdh_scatter_go(stx_ctx *c, const TranshArgs &ta, const ScatterArgs 
 {
 #define STX_FS(D)                                                                                               \
     do {                                                                                                        \
-        if (first)                                                                                              \
-            hipLaunchKernelGGL((k_fwdh_scatter<LPR, ITERS, D, true>), dim3(blocks), dim3(kThreads), 0,          \
+        if (first && ta.k <= 1)                                                                                 \
+            hipLaunchKernelGGL((k_fwdh_scatter<LPR, ITERS, D, true, true>), dim3(blocks), dim3(kThreads), 0,    \
+                               c->stream, ta, sa, ea);                                                          \
+        else if (first)                                                                                         \
+            hipLaunchKernelGGL((k_fwdh_scatter<LPR, ITERS, D, true, false>), dim3(blocks), dim3(kThreads), 0,   \
+                               c->stream, ta, sa, ea);                                                          \
+        else if (ta.k <= 1)                                                                                     \
+            hipLaunchKernelGGL((k_fwdh_scatter<LPR, ITERS, D, false, true>), dim3(blocks), dim3(kThreads), 0,   \
                                c->stream, ta, sa, ea);                                                          \
         else                                                                                                    \
-            hipLaunchKernelGGL((k_fwdh_scatter<LPR, ITERS, D, false>), dim3(blocks), dim3(kThreads), 0,         \
+            hipLaunchKernelGGL((k_fwdh_scatter<LPR, ITERS, D, false, false>), dim3(blocks), dim3(kThreads), 0,  \
                                c->stream, ta, sa, ea);                                                          \
     } while (0)
     switch (c->cfg.dist) {

@@ -68,11 +68,12 @@ struct HRow {
 // relation of its positive (the build writes the batch that way), so w_r and d_r are fetched once per
 // group; the negatives are taken NB at a time so that their column ids, then their entity rows, are
 // in flight together.  `block` is the index of the workgroup among those of the forward pass.
-template <int LPR, int ITERS, int DIST>
+// K1: at most one negative per positive (the benchmarks' shape): no registers are kept for a batch of them.
+template <int LPR, int ITERS, int DIST, bool K1 = false>
 __device__ inline void forward_transh_body(const int block, const TranshArgs &a)
 {
     constexpr int GROUPS = kThreads / LPR;
-    constexpr int NB = ITERS <= 2 ? 4 : 2;
+    constexpr int NB = K1 ? 1 : (ITERS <= 2 ? 4 : 2);
     __shared__ float s_loss[GROUPS];
     const int lig = threadIdx.x % LPR, grp = threadIdx.x / LPR;
     const int64_t i = (int64_t)block * GROUPS + grp;
