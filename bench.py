@@ -27,11 +27,11 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 # The kernel whose roofline is reported: the one with the largest share of GPU time in the
 # rocprofv3 kernel trace of the same command (profiles/).
-DOMINANT = {"mid": "k_seg_reduce", "tiny": "k_seg_reduce", "toruse": "k_seg_reduce", "transh": "k_fwdh_scatter",
+DOMINANT = {"mid": "k_seg_reduce", "tiny": "k_seg_reduce", "toruse": "k_seg_reduce", "transh": "k_seg_reduce",
             "transr": "k_transr_project", "paper_transe": "k_seg_reduce", "paper_toruse": "k_seg_reduce",
             "paper_transr": "k_transr_project"}
 # ... without the look-ahead (--no-lookahead) the forward pass and the first scatter pass share the longest launch
-DOMINANT_PLAIN = dict(DOMINANT, mid="k_fwd_scatter", tiny="k_fwd_scatter", transh="k_seg_reduce")
+DOMINANT_PLAIN = dict(DOMINANT, mid="k_fwd_scatter", tiny="k_fwd_scatter")
 # ... and when the step is made of the separate calls (--api fused | separate)
 DOMINANT_CALLS = {"mid": "k_seg_reduce", "tiny": "k_seg_reduce", "toruse": "k_seg_reduce", "transh": "k_forward_transh",
                   "transr": "k_transr_project", "paper_transe": "k_seg_reduce", "paper_toruse": "k_seg_reduce",
