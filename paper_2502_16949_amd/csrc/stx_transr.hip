@@ -462,11 +462,12 @@ __global__ __launch_bounds__(kThreads) void k_transr_dm(DmArgs p)
 #pragma unroll
     for (int i = 0; i < 4; ++i) acc[i >> 1][i & 1] = zero16();
     const int ntile = (entries + 63) >> 6;
-    for (int t = 0; t < ntile; ++t) {
+    // the fragments of tile t + 1 are requested before the products of tile t are issued (two sets of registers,
+    // taken in turn): a workgroup walks its tiles one after the other, and a batch has few workgroups here
+    auto load_tile = [&](int t, uint4 (&fa)[4][2], uint4 (&fb)[4][2]) {
         const int nks = (min(64, entries - 64 * t) + 15) >> 4;
         const uint16_t *ga = p.gyt + ((int64_t)(tile0 + t) * 64 * p.k) + (int64_t)l * 8;
         const uint16_t *xb = p.xt + ((int64_t)(tile0 + t) * 64 * p.d) + (int64_t)l * 8;
-        uint4 fa[4][2], fb[4][2];
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             fa[ks][0] = fa[ks][1] = fb[ks][0] = fb[ks][1] = make_uint4(0, 0, 0, 0);
@@ -477,6 +478,9 @@ __global__ __launch_bounds__(kThreads) void k_transr_dm(DmArgs p)
                 if (n1) fb[ks][1] = ld16(xb + (int64_t)(ks * ntl + nt0 + 1) * 512);
             }
         }
+    };
+    auto mma_tile = [&](int t, const uint4 (&fa)[4][2], const uint4 (&fb)[4][2]) {
+        const int nks = (min(64, entries - 64 * t) + 15) >> 4;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             if (ks < nks) {
@@ -485,6 +489,16 @@ __global__ __launch_bounds__(kThreads) void k_transr_dm(DmArgs p)
                 if (m1) acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(fa[ks][1]), as_frag(fb[ks][0]), acc[1][0], 0, 0, 0);
                 if (m1 && n1) acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(fa[ks][1]), as_frag(fb[ks][1]), acc[1][1], 0, 0, 0);
             }
+        }
+    };
+    uint4 fa0[4][2], fb0[4][2], fa1[4][2], fb1[4][2];
+    load_tile(0, fa0, fb0);
+    for (int t = 0; t < ntile; t += 2) {
+        if (t + 1 < ntile) load_tile(t + 1, fa1, fb1);
+        mma_tile(t, fa0, fb0);
+        if (t + 1 < ntile) {
+            if (t + 2 < ntile) load_tile(t + 2, fa0, fb0);
+            mma_tile(t + 1, fa1, fb1);
         }
     }
     const int64_t kd = (int64_t)p.k * p.d;
