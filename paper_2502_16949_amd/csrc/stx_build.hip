@@ -14,8 +14,12 @@
 //   k_hist     x P-1  tile histograms of digit p (between scatters)
 //   k_seg_count       segment heads per tile (only without the presence bitmap)
 //   k_seg_write       touched_cols, seg_ptr, row_idx, sign, seg_id, packed, U
-// stx_train_step lets independent work of the step share the launches of the first scatter pass and of
-// the following histogram pass (stx_step.hip, stx_transr.hip).
+// stx_train_step lets independent work of the step share the launches of the scatter and histogram passes
+// (stx_step.hip, stx_transr.hip), leaves k_seg_write to the launch of the fused transposed product
+// (stx_backward.hip), and, when a call names the batch of the next call, runs k_emit, the first scatter pass
+// and the second histogram pass of that batch inside this step's launches (prepare_emit_ahead, take_*_ahead).
+// Histograms of digit 0 and of the later digits live in two tables, so that the next batch's k_emit can run
+// beside a later pass of this batch.
 // The tile histograms (tile-major table[tile][digit]) must become global offsets before a scatter.
 // With few tiles every scatter workgroup derives its own offsets from the raw table (a few coalesced
 // reads per thread); with many tiles a small k_super_sums first adds the histograms up in groups of tiles.

@@ -5,10 +5,12 @@
 // Two links of that chain do not depend on each other: the forward pass (SparseTransX Sec. 4.3) needs
 // only A, which the first kernel of the build writes, while the sort that produces A^T for the
 // backward pass (Appendix G) goes on for several more launches; and the final sum of the loss needs
-// only the forward pass.  stx_train_step therefore runs the forward pass in the launch of the sort's
-// first scatter pass, and the loss sum in the launch of the next histogram pass.  The sort's
-// workgroups take the low block indices so that they start first: they are few and long, the forward
-// workgroups many and short.
+// only the forward pass.  stx_train_step therefore runs the forward pass in the launch of a scatter pass
+// of the sort (the first one; or, when the first stages of this batch's build already ran inside the
+// previous step's launches, the histogram pass or the last scatter pass), and the loss sum in the launch
+// of a later pass or of the transposed product.  In those later launches the first kernel of the next
+// batch's build comes along as well.  The sort's workgroups take the low block indices so that they start
+// first: they are few and long, the forward workgroups many and short.
 #include "stx_emit_body.h"
 #include "stx_forward_body.h"
 #include "stx_sort_body.h"
