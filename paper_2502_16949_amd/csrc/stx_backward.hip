@@ -24,6 +24,11 @@
 // same two roundings as k_sgd_rows, so the gradient rows never travel to memory and back.  The table
 // row of a run is fetched together with the run's first source row, so closing a run costs no extra
 // memory round trip.
+//
+// In stx_train_step the launches of both kernels carry more (template parameter RIDE): the product reads the
+// sorted keys and payloads of the build itself, so that the build's last kernel and the sum of the loss run
+// as extra workgroups of its launch, and one stage of the next batch's build rides in each launch.  All parts
+// of a launch share one block of LDS.
 #include "stx_emit_body.h"
 #include "stx_forward_body.h"
 #include "stx_rowops.h"
