@@ -552,7 +552,8 @@ int stxo_rank(const stxo_cfg *c, const stxo_tables *tb, const int32_t *h, const 
  * gy_out (optional, rows x out_dim doubles): dL/dy of every row.
  * ambiguous (optional, rows bytes): set to 1 for rows of TransH/TransR with an L1-kind distance in
  * which some y_j lies within 1e-5 * sum|terms of y_j| of a point where the subgradient jumps (0, or
- * fractional part 0 / one half on the torus): there an fp32 evaluation may pick the other branch. */
+ * fractional part 0 / one half on the torus): there an fp32 evaluation may pick the other branch.
+ * An element whose terms are all zero is zero in any precision and never sets the flag. */
 #define STXO_TIE_WIDTH 1e-5
 int stxo_backward(const stxo_cfg *c, const stxo_tables *tb, const stxo_batch *bt,
                   const uint8_t *active_override,
@@ -611,6 +612,8 @@ int stxo_backward(const stxo_cfg *c, const stxo_tables *tb, const stxo_batch *bt
                 } else if (c->dist == STXO_L2_SQ) {
                     double alt = 2.0 * fabs(coef[i]) * yabs[j];
                     if (alt > ug[j]) ug[j] = alt;
+                } else if (yabs[j] == 0.0) {
+                    continue;                           /* every term is 0: y_j is 0 in any precision */
                 } else if (c->dist == STXO_L1) {
                     if (fabs(y[j]) <= STXO_TIE_WIDTH * yabs[j]) amb = 1;
                 } else {
