@@ -11,6 +11,8 @@ from tests.util import oracle_batch, oracle_config, oracle_tables
 
 pytestmark = pytest.mark.gpu
 
+MAX_AMBIGUOUS_ROWS = 0.02   # largest share of a batch's rows that may sit on a jump of an L1-kind subgradient
+
 
 def check_transh_step(wl, tabs, bt, reduce, renorm=True, lr=0.01):
     cfg = oracle_config(wl, reduce=reduce)
@@ -33,23 +35,18 @@ def check_transh_step(wl, tabs, bt, reduce, renorm=True, lr=0.01):
     rows = m.grads.rows[:u].cpu().numpy()
     w_rows = m.grads.w_rows[:u].cpu().numpy()
     is_ent = cols < wl.n_ent
-    # Rows in which an L1-kind subgradient sits on a jump (y_j within 1e-5 of its own rounding scale
-    # from 0) may legitimately take the other branch in fp32: the columns they feed are only checked
-    # loosely.  They must be rare.
+    # Rows in which an L1-kind subgradient sits on a jump (y_j within 1e-5 of its own rounding scale from a
+    # point where the subgradient changes) may legitimately take the other branch in fp32: the elements they feed
+    # get the bound of G.ambiguous_allowance added to their bar; every other element is held to the fp32 bar
+    # with headroom.  Such rows must be rare.
     amb = g.ambiguous.astype(bool)
-    assert amb.mean() <= 0.1
-    hh = np.concatenate([bt.h, bt.nh]); tt = np.concatenate([bt.t, bt.nt]); rr = np.concatenate([bt.r, np.repeat(bt.r, bt.k)])
-    loose_ent = np.zeros(wl.n_ent, bool); loose_ent[hh[amb]] = True; loose_ent[tt[amb]] = True
-    loose_rel = np.zeros(wl.n_rel, bool); loose_rel[rr[amb]] = True
+    mean = reduce == B.STX_MEAN
+    assert amb.mean() <= MAX_AMBIGUOUS_ROWS, amb.mean()
+    allow = G.ambiguous_allowance(wl, tabs, bt, active, amb, mean) or {"ent": None, "rel": None, "w": None}
     ec, rc = cols[is_ent], cols[~is_ent] - wl.n_ent
-    ke, kr = ~loose_ent[ec], ~loose_rel[rc]
-    G.check_grad_rows(ec[ke], rows[is_ent][ke], g.ent, g.ent_abs, wl.dim, what="dE", all_cols=ec)
-    G.check_grad_rows(rc[kr], rows[~is_ent][kr], g.rel, g.rel_abs, wl.dim, what="d(d_r)", all_cols=rc)
-    G.check_grad_rows(rc[kr], w_rows[~is_ent][kr], g.w, g.w_abs, wl.dim, what="dw", all_cols=rc)
-    scale = 1.0 / (bt.b * bt.k) if reduce == B.STX_MEAN else 1.0
-    for got, ref, sel in ((rows[is_ent][~ke], g.ent[ec[~ke]], None), (rows[~is_ent][~kr], g.rel[rc[~kr]], None)):
-        if len(got):                                                    # a flipped sign moves an element by <= 2*coef
-            assert np.abs(got - ref).max() <= 2.0 * bt.k * scale * amb.sum() + 1e-4
+    G.check_grad_rows(ec, rows[is_ent], g.ent, g.ent_abs, wl.dim, what="transh dE", allowance=allow["ent"])
+    G.check_grad_rows(rc, rows[~is_ent], g.rel, g.rel_abs, wl.dim, what="transh d(d_r)", allowance=allow["rel"])
+    G.check_grad_rows(rc, w_rows[~is_ent], g.w, g.w_abs, wl.dim, what="transh dw", allowance=allow["w"])
     # update
     tb = oracle_tables(tabs)
     m_ent, m_rel = stxo.touched_masks(cfg, bt)
@@ -65,7 +62,8 @@ def check_transh_step(wl, tabs, bt, reduce, renorm=True, lr=0.01):
         assert np.array_equal(new[mask == 0], old[mask == 0]), name
         diff = np.abs(new.astype(np.float64) - ref)
         slack = 4 if (name == "w" and renorm) else 1                    # the rescale adds a norm and a product
-        assert np.all(diff <= slack * (G.REL_TOL * (lr * gabs + np.abs(old) * 2.0**-23) + 2.0**-23)), (name, diff.max())
+        extra = 0.0 if allow[name] is None else slack * lr * allow[name]
+        assert np.all(diff <= slack * (G.REL_TOL * (lr * gabs + np.abs(old) * 2.0**-23) + 2.0**-23) + extra), (name, diff.max())
     if renorm:
         wn = np.linalg.norm(m.params.w.cpu().numpy().astype(np.float64), axis=1)
         np.testing.assert_allclose(wn[m_rel == 1], 1.0, atol=1e-6)

@@ -15,14 +15,24 @@ pytestmark = pytest.mark.gpu
 BF16_TOL = 1e-2          # bar for quantities that pass through a bfloat16 rounding of a computed value
 
 
-def _bulk_and_bar(got, ref, scale, what, bulk_tol=2e-5, bulk_frac=0.995):
+BULK_TOL, BULK_FRAC = 1e-5, 0.999  # share of the elements of dE / dM that must meet the fp32 bar itself
+MAX_AMBIGUOUS_ROWS = 0.02          # largest share of a batch's rows that may sit on a jump of an L1-kind subgradient
+
+
+def _bulk_and_bar(got, ref, scale, what, allowance=None):
     """Elementwise: everything within BF16_TOL * scale (a computed dL/dy that lands on the other side
-    of a bfloat16 rounding boundary moves one product by 2^-8 of itself), and nearly everything within
-    the fp32 bar."""
+    of a bfloat16 rounding boundary moves one product by 2^-8 of itself), with headroom, and nearly everything
+    within the fp32 bar.  allowance: see G.ambiguous_allowance."""
+    extra = np.zeros_like(ref) if allowance is None else allowance
     err = np.abs(got.astype(np.float64) - ref)
-    assert np.all(err <= BF16_TOL * scale + 1e-30), (what, float((err / (scale + 1e-30)).max()))
-    ok = err <= bulk_tol * scale + 1e-30
-    assert ok.mean() >= bulk_frac, (what, float(ok.mean()))
+    assert np.all(err <= BF16_TOL * scale + extra + 1e-30), (what, float((err / (scale + 1e-30)).max()))
+    tight = extra == 0
+    used = float((err[tight] / (BF16_TOL * scale[tight] + 1e-30)).max()) if tight.any() else 0.0
+    G.USAGE.append((what + " (1e-2 bar)", used))
+    assert used <= G.HEADROOM, (what, used)
+    ok = err[tight] <= BULK_TOL * scale[tight] + 1e-30
+    G.USAGE.append((what + " (share within 1e-5)", float(ok.mean()) if ok.size else 1.0))
+    assert ok.size == 0 or ok.mean() >= BULK_FRAC, (what, float(ok.mean()))
 
 
 def check_transr_step(wl, tabs, bt, reduce, lr=0.01):
@@ -45,18 +55,18 @@ def check_transr_step(wl, tabs, bt, reduce, lr=0.01):
     rows = m.grads.rows[:u].cpu().numpy()
     is_ent = cols < wl.n_ent
     ec, rc = cols[is_ent], cols[~is_ent] - wl.n_ent
+    # rows whose L1-kind subgradient sits on a jump: the elements they feed get G.ambiguous_allowance on top of
+    # their bar, nothing is left out of the comparison
     amb = g.ambiguous.astype(bool)                                           # only L1 kinds can set it
-    assert amb.mean() <= 0.1
-    hh = np.concatenate([bt.h, bt.nh]); tt = np.concatenate([bt.t, bt.nt]); rr = np.concatenate([bt.r, np.repeat(bt.r, bt.k)])
-    loose_ent = np.zeros(wl.n_ent, bool); loose_ent[hh[amb]] = True; loose_ent[tt[amb]] = True
-    loose_rel = np.zeros(wl.n_rel, bool); loose_rel[rr[amb]] = True
-    ke, kr = ~loose_ent[ec], ~loose_rel[rc]
-    _bulk_and_bar(rows[is_ent][ke][:, :wl.dim], g.ent[ec[ke]], g.ent_abs[ec[ke]], "dE")
+    assert amb.mean() <= MAX_AMBIGUOUS_ROWS, amb.mean()
+    allow = G.ambiguous_allowance(wl, tabs, bt, active, amb, reduce == B.STX_MEAN, bf16=True) or \
+        {"ent": None, "rel": None, "proj": None}
+    pick = lambda a, sel: None if a is None else a[sel]
+    _bulk_and_bar(rows[is_ent][:, :wl.dim], g.ent[ec], g.ent_abs[ec], "transr dE", pick(allow["ent"], ec))
     # dL/dr is a plain fp32 sum of dL/dy: the fp32 bar applies
-    G.check_grad_rows(rc[kr], rows[~is_ent][kr], g.rel, g.rel_abs, wl.rel_dim, what="dr", all_cols=rc)
+    G.check_grad_rows(rc, rows[~is_ent], g.rel, g.rel_abs, wl.rel_dim, what="transr dr", allowance=allow["rel"])
     proj = m.grads.proj.cpu().numpy()
-    sel = rc[kr]
-    _bulk_and_bar(proj[sel], g.proj[sel], g.proj_abs[sel], "dM")
+    _bulk_and_bar(proj[rc], g.proj[rc], g.proj_abs[rc], "transr dM", pick(allow["proj"], rc))
     # relations absent from the batch got no gradient in the oracle either
     absent = np.ones(wl.n_rel, bool); absent[rc] = False
     assert not np.any(g.proj_abs[absent])
@@ -68,16 +78,16 @@ def check_transr_step(wl, tabs, bt, reduce, lr=0.01):
     stxo.sgd(tb.proj, g.proj, m_rel, lr, 0)
     m.sgd(lr)
     torch.cuda.synchronize()
-    for name, new, ref, old, gabs, mask, loose in (
-            ("ent", m.params.ent, tb.ent, tabs["ent"], g.ent_abs, m_ent, loose_ent),
-            ("rel", m.params.rel, tb.rel, tabs["rel"], g.rel_abs, m_rel, loose_rel),
-            ("proj", m.params.proj, tb.proj, tabs["proj"], g.proj_abs, m_rel, loose_rel)):
+    for name, new, ref, old, gabs, mask in (
+            ("ent", m.params.ent, tb.ent, tabs["ent"], g.ent_abs, m_ent),
+            ("rel", m.params.rel, tb.rel, tabs["rel"], g.rel_abs, m_rel),
+            ("proj", m.params.proj, tb.proj, tabs["proj"], g.proj_abs, m_rel)):
         new = new.cpu().numpy()
         assert np.array_equal(new[mask == 0], old[mask == 0]), name
-        keep = ~loose
-        diff = np.abs(new.astype(np.float64) - ref)[keep]
+        diff = np.abs(new.astype(np.float64) - ref)
         tol = G.REL_TOL if name == "rel" else BF16_TOL
-        assert np.all(diff <= tol * lr * gabs[keep] + np.abs(old[keep]) * 2.0**-22 + 2.0**-23), (name, diff.max())
+        extra = 0.0 if allow[name] is None else lr * allow[name]
+        assert np.all(diff <= tol * lr * gabs + np.abs(old) * 2.0**-22 + 2.0**-23 + extra), (name, diff.max())
 
 
 CASES = [

@@ -242,3 +242,52 @@ def test_single_precision_evaluation_sits_well_inside_the_scales(model, dist):
         used = np.abs(v.astype(np.float64) - ref) / (1e-5 * a + 1e-300)
         assert used.max() <= 0.25, (name, float(used.max()))
         assert used.max() >= 5e-4, (name, float(used.max()))
+
+
+# ----------------------------------------------------------------------------- the allowance of flagged rows
+@pytest.mark.parametrize("model", ["transh", "transr"])
+def test_allowance_of_flagged_rows_covers_any_other_branch(model):
+    """tests/gpu_util.ambiguous_allowance bounds how far gradients move when flagged rows take other branches of
+    an L1-kind subgradient: replace dL/dy of some rows by any vector of entries in {-1, 0, +1} * coef, push it
+    through the backward formulas in numpy, and compare the movement with the bound."""
+    from tests import gpu_util as G
+    wl, tabs, bt = small_problem(model, "l1", n_ent=30, n_rel=4, b=48, k=2, dim=8, rel_dim=8, seed=51)
+    cfg = oracle_config(wl, bf16=False)
+    g = stxo.backward(cfg, oracle_tables(tabs), bt, want_gy=True)
+    fw = stxo.forward(cfg, oracle_tables(tabs), bt)
+    active = fw.hinge_arg > 0
+    rng = np.random.default_rng(7)
+    amb = rng.random(bt.rows) < 0.1
+    allow = G.ambiguous_allowance(wl, tabs, bt, active, amb, False)
+    hh, rr, tt = _rows(bt)
+    coef = G.pair_coefficients(active, bt.b, bt.k, False)
+    gy2 = g.gy.copy()
+    gy2[amb] = rng.integers(-1, 2, gy2[amb].shape) * coef[amb][:, None]
+    x = (tabs["ent"][hh] - tabs["ent"][tt]).astype(np.float64)
+
+    def grads(gy):
+        out = {}
+        if model == "transh":
+            w = tabs["w"].astype(np.float64)[rr]
+            a = (gy * w).sum(1, keepdims=True)
+            s = (x * w).sum(1, keepdims=True)
+            gx = gy - a * w
+            out["w"] = np.zeros((wl.n_rel, wl.dim)); np.add.at(out["w"], rr, -(a * x + s * gy))
+        else:
+            M = tabs["proj"].astype(np.float64)[rr]
+            gx = np.einsum("na,nad->nd", gy, M)
+            out["proj"] = np.zeros((wl.n_rel, wl.rel_dim, wl.dim)); np.add.at(out["proj"], rr, gy[:, :, None] * x[:, None, :])
+        out["rel"] = np.zeros((wl.n_rel, gy.shape[1])); np.add.at(out["rel"], rr, gy)
+        out["ent"] = np.zeros((wl.n_ent, wl.dim)); np.add.at(out["ent"], hh, gx); np.add.at(out["ent"], tt, -gx)
+        return out
+
+    g1, g2 = grads(g.gy), grads(gy2)
+    for name in g1:
+        np.testing.assert_allclose(g1[name], getattr(g, name), rtol=0, atol=1e-12)     # the formulas are the oracle's
+        moved = np.abs(g2[name] - g1[name])
+        assert np.all(moved <= allow[name] + 1e-12), name
+        assert moved.max() > 0.05 * allow[name].max(), name                            # ... and the bound is not idle
+        assert np.all((allow[name] == 0) | (moved >= 0)), name
+    # rows that are not flagged contribute nothing to the allowance
+    none = G.ambiguous_allowance(wl, tabs, bt, active, np.zeros(bt.rows, bool), False)
+    assert none is None
