@@ -38,7 +38,8 @@ typedef enum {
     STX_ERR_WORKSPACE = 4,   /* workspace smaller than stx_workspace_bytes, or misaligned */
     STX_ERR_STATE = 5,       /* call order violated (e.g. backward before forward) */
     STX_ERR_UNSUPPORTED = 6, /* valid request this build does not implement */
-    STX_ERR_HIP = 7          /* a HIP runtime call failed */
+    STX_ERR_HIP = 7,         /* a HIP runtime call failed */
+    STX_ERR_STATIC_LIMIT = 8 /* stx_spmm_semiring_t_static: the batch needs more than STX_STATIC_WORK_BYTES */
 } stx_status;
 
 /* Score functions of Table 2 (Sec. 4.2): which incidence form is used and what follows it. */
@@ -183,6 +184,19 @@ stx_status stx_spmm_semiring(stx_ctx *ctx, const stx_incidence *inc, const stx_p
  * stx_backward.  work: 3 * n_rows * dim floats of device scratch owned by the caller (the per-row terms). */
 stx_status stx_spmm_semiring_t(stx_ctx *ctx, const stx_incidence *inc, const stx_params *p, int32_t kind,
                                const float *gz, float *work, stx_grads *g);
+
+/* stx_spmm_semiring_t for callers that cannot allocate device memory and have no work buffer to hand over
+ * (code under HIP graph capture, serving loops, harnesses that forbid hipMalloc): the same kernels and the
+ * same results bit for bit, with the per-row terms kept in a fixed array of STX_STATIC_WORK_BYTES bytes that
+ * is part of the library's device code (every GPU the library runs on holds its own copy until the process
+ * ends).  Calls no allocator.  The context's GPU must be the current device.
+ * A batch with 3 * n_rows * dim * 4 > STX_STATIC_WORK_BYTES is refused with STX_ERR_STATIC_LIMIT before
+ * anything is launched (at dim 128: up to 65,536 rows).  All calls on one GPU share the array, from every
+ * context and thread: calls that overlap in time on one GPU race on it; calls on one stream do not.  Nothing
+ * in it needs clearing between calls: every element a call reads it has written before.                  */
+#define STX_STATIC_WORK_BYTES (96u << 20)
+stx_status stx_spmm_semiring_t_static(stx_ctx *ctx, const stx_incidence *inc, const stx_params *p, int32_t kind,
+                                      const float *gz, stx_grads *g);
 
 /* Forward (Sec. 4.3-4.6, 5.3): scores[i] = distance of row i (n_rows, fp32); *loss (device, fp32) =
  * sum (or mean) over pairs of max(0, margin + score[i] - score[b + i*k + kk]).  Also stores dL/dy of

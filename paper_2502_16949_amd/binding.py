@@ -15,7 +15,8 @@ LIB_PATH = os.path.join(_HERE, "libstx.so")
 
 STX_OK = 0
 STX_ERR_NULL, STX_ERR_BAD_ARG, STX_ERR_INDEX_RANGE, STX_ERR_WORKSPACE = 1, 2, 3, 4
-STX_ERR_STATE, STX_ERR_UNSUPPORTED, STX_ERR_HIP = 5, 6, 7
+STX_ERR_STATE, STX_ERR_UNSUPPORTED, STX_ERR_HIP, STX_ERR_STATIC_LIMIT = 5, 6, 7, 8
+STX_STATIC_WORK_BYTES = 96 << 20
 STX_TRANSE, STX_TRANSH, STX_TRANSR, STX_TORUSE = 0, 1, 2, 3
 STX_L1, STX_L2, STX_TORUS_L1, STX_TORUS_L2, STX_L2_SQ = 0, 1, 2, 3, 4
 STX_SUM, STX_MEAN = 0, 1
@@ -27,7 +28,7 @@ MODELS = {"transe": STX_TRANSE, "transh": STX_TRANSH, "transr": STX_TRANSR, "tor
 DISTS = {"l1": STX_L1, "l2": STX_L2, "torus_l1": STX_TORUS_L1, "torus_l2": STX_TORUS_L2, "l2_sq": STX_L2_SQ}
 
 EXPORTS = ["stx_workspace_bytes", "stx_create", "stx_destroy", "stx_sample_negatives", "stx_build_incidence",
-           "stx_check_indices", "stx_spmm", "stx_spmm_semiring", "stx_spmm_semiring_t", "stx_rank", "stx_rank_work_bytes", "stx_forward", "stx_backward", "stx_sgd_step", "stx_backward_sgd", "stx_train_step", "stx_profile_kernel",
+           "stx_check_indices", "stx_spmm", "stx_spmm_semiring", "stx_spmm_semiring_t", "stx_spmm_semiring_t_static", "stx_rank", "stx_rank_work_bytes", "stx_forward", "stx_backward", "stx_sgd_step", "stx_backward_sgd", "stx_train_step", "stx_profile_kernel",
            "stx_profile_every", "stx_profile_read", "stx_profile_dump", "stx_copy_f32", "stx_status_string"]
 
 
@@ -88,6 +89,8 @@ def lib():
         L.stx_spmm_semiring.argtypes = [vp, C.POINTER(stx_incidence), C.POINTER(stx_params), i32, vp]
         L.stx_spmm_semiring_t.argtypes = [vp, C.POINTER(stx_incidence), C.POINTER(stx_params), i32, vp, vp,
                                           C.POINTER(stx_grads)]
+        L.stx_spmm_semiring_t_static.argtypes = [vp, C.POINTER(stx_incidence), C.POINTER(stx_params), i32, vp,
+                                                 C.POINTER(stx_grads)]
         L.stx_rank.argtypes = [vp, C.POINTER(stx_params), vp, vp, vp, i64, i32, vp, vp, vp, vp, C.c_size_t]
         L.stx_rank_work_bytes.argtypes = [vp, i64, C.POINTER(C.c_size_t)]
         L.stx_forward.argtypes = [vp, C.POINTER(stx_incidence), C.POINTER(stx_params), vp, vp]
@@ -273,6 +276,13 @@ def stx_spmm_semiring_t(ctx: Context, inc: Incidence, p: Params, kind: int, gz, 
     assert gz.numel() >= inc.n_rows * ctx.cfg.dim and work.numel() >= 3 * inc.n_rows * ctx.cfg.dim
     _check("stx_spmm_semiring_t", lib().stx_spmm_semiring_t(ctx.handle, C.byref(inc.c), C.byref(p.c), kind,
                                                             gz.data_ptr(), work.data_ptr(), C.byref(g.c)))
+
+
+def stx_spmm_semiring_t_static(ctx: Context, inc: Incidence, p: Params, kind: int, gz, g: Grads):
+    assert gz.is_cuda and gz.dtype == torch.float32 and gz.is_contiguous()
+    assert gz.numel() >= inc.n_rows * ctx.cfg.dim
+    _check("stx_spmm_semiring_t_static", lib().stx_spmm_semiring_t_static(ctx.handle, C.byref(inc.c), C.byref(p.c),
+                                                                          kind, gz.data_ptr(), C.byref(g.c)))
 
 
 def stx_rank_work_bytes(ctx: Context, nq: int) -> int:

@@ -431,6 +431,24 @@ stx_status stx_spmm_semiring_t(stx_ctx *ctx, const stx_incidence *inc, const stx
     return launch_semiring_t(ctx, inc, p, kind, gz, work, g->rows);
 }
 
+stx_status stx_spmm_semiring_t_static(stx_ctx *ctx, const stx_incidence *inc, const stx_params *p, int32_t kind,
+                                      const float *gz, stx_grads *g)
+{
+    if (!ctx) return STX_ERR_NULL;
+    stx_status s = check_built(ctx, inc);
+    if (s != STX_OK) return s;
+    if (!p || !p->ent || !gz || !g || !g->rows) return STX_ERR_NULL;
+    if (kind < STX_DISTMULT || kind > STX_ROTATE) return STX_ERR_BAD_ARG;
+    if ((uintptr_t)gz & 15u) return STX_ERR_BAD_ARG;
+    if (!stacked(ctx)) return STX_ERR_UNSUPPORTED;
+    if ((uint64_t)inc->n_rows * 3u * (uint64_t)ctx->cfg.dim * sizeof(float) > (uint64_t)STX_STATIC_WORK_BYTES)
+        return STX_ERR_STATIC_LIMIT;
+    float *work = nullptr;
+    s = static_work(&work);
+    if (s != STX_OK) return s;
+    return launch_semiring_t(ctx, inc, p, kind, gz, work, g->rows);
+}
+
 stx_status stx_rank_work_bytes(const stx_ctx *ctx, int64_t nq, size_t *bytes)
 {
     if (!ctx || !bytes) return STX_ERR_NULL;
@@ -666,6 +684,7 @@ const char *stx_status_string(stx_status s)
     case STX_ERR_STATE: return "call order violated";
     case STX_ERR_UNSUPPORTED: return "not supported";
     case STX_ERR_HIP: return "HIP runtime error";
+    case STX_ERR_STATIC_LIMIT: return "request larger than the library's fixed scratch (STX_STATIC_WORK_BYTES)";
     }
     return "unknown status";
 }

@@ -324,6 +324,8 @@ size_t rank_work_bytes(const stx_ctx *, int64_t nq);   // scratch launch_rank ne
 stx_status launch_semiring(stx_ctx *, const stx_incidence *, const stx_params *, int kind, float *z_out);
 stx_status launch_semiring_t(stx_ctx *, const stx_incidence *, const stx_params *, int kind, const float *gz,
                              float *work, float *out_rows);
+// device address, on the current GPU, of the library's fixed scratch array of STX_STATIC_WORK_BYTES bytes
+stx_status static_work(float **out);
 // stx_transr.hip
 stx_status launch_transr_project(stx_ctx *, const stx_incidence *, const stx_params *);
 // fused_lr: if not null, M_r <- M_r - lr * dL/dM_r is applied in place of the store of dL/dM_r (g may be null)

@@ -10,6 +10,8 @@
 // product of the row's other two factors.  k_semiring_terms writes these three rows per matrix row (the
 // tail's negated), and the transposed product of the translational models sums them per column: head and
 // relation entries add their row, tail entries subtract theirs.
+#include <mutex>
+
 #include "stx_rowops.h"
 
 namespace stx {
@@ -145,6 +147,32 @@ stx_status launch_semiring(stx_ctx *c, const stx_incidence *inc, const stx_param
     Launch L = row_launch(c->cfg.dim);
     STX_DISPATCH_ROW(L, semiring_go, c, inc, p, kind, nullptr, z_out);
     return hip_ok(hipGetLastError());
+}
+
+// Scratch of stx_spmm_semiring_t_static: the per-row terms of the backward product, for callers that can bring
+// no work buffer.  Every GPU the library runs on holds its own copy of the array, at its own address, until the
+// process ends.  In host code the array's name is only a handle for the symbol look-up below, never an address.
+static __device__ __align__(256) unsigned char scratch[STX_STATIC_WORK_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each GPU, null until first asked for
+}  // namespace
+
+stx_status static_work(float **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return STX_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return STX_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return STX_ERR_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = static_cast<float *>(g_scratch_ptr[dev]);
+    return STX_OK;
 }
 
 stx_status launch_semiring_t(stx_ctx *c, const stx_incidence *inc, const stx_params *p, int kind, const float *gz,

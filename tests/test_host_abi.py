@@ -26,8 +26,8 @@ def test_library_exports_every_declared_symbol():
 
 def test_status_strings():
     assert B.status_string(B.STX_OK) == "ok"
-    seen = {B.status_string(i) for i in range(8)}
-    assert len(seen) == 8 and "unknown status" not in seen
+    seen = {B.status_string(i) for i in range(9)}
+    assert len(seen) == 9 and "unknown status" not in seen
     assert B.status_string(99) == "unknown status"
 
 
