@@ -24,6 +24,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+TRANSR_PRODUCTS = ("k_transr_project", "k_transr_gx", "k_transr_dm")
 
 # The kernel whose roofline is reported: the one with the largest share of GPU time in the
 # rocprofv3 kernel trace of the same command (profiles/).
@@ -81,6 +82,12 @@ def parse():
     ap.add_argument("--no-lookahead", action="store_true",
                     help="--api step: do not tell a step which batch follows (its first build kernel then runs on its own "
                          "instead of inside the previous step's transposed product)")
+    ap.add_argument("--windows", type=int, default=5,
+                    help="timed regions of --steps steps each; `value` is the median one, mean / median / min are printed")
+    ap.add_argument("--no-hbm-leg", action="store_true",
+                    help="default run (mid, --api step) only: leave out the short run of the HBM-resident configuration")
+    ap.add_argument("--no-build-rates", action="store_true",
+                    help="leave out the untimed pass that times negative sampling and the incidence build by themselves")
     ap.add_argument("--all-kernels", action="store_true",
                     help="extra untimed pass that brackets every kernel with events and adds 'kernels_us' to the output")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -376,6 +383,250 @@ def bench_semiring(args, wl, dev):
     print(json.dumps(out))
 
 
+# Last-level cache of the part (the memory-side Infinity Cache): a working set below it is served from cache after
+# the first touch, and a "fraction of the HBM peak" is then a nominal figure.
+LLC_BYTES = 256 << 20
+
+
+def host_info():
+    model = "unknown"
+    try:
+        for ln in open("/proc/cpuinfo"):
+            if ln.startswith("model name"):
+                model = ln.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count() or 1
+    return {"nproc": os.cpu_count() or 1, "usable_cores": usable, "cpu_model": model}
+
+
+def roof_of(wl, kernel, us):
+    """Which roof a kernel's byte figure can meaningfully be held against."""
+    table = (wl.n_ent + wl.n_rel) * wl.dim * 4
+    packed = wl.model in ("transe", "toruse") and wl.dist in ("l1", "torus_l1")
+    g = wl.rows_per_batch * ((wl.dim // 4 + 4) if packed else 4 * wl.dim * (3 if wl.model in ("transh", "transr") else 1))
+    if table + g > LLC_BYTES:
+        return "hbm: the working set (%.0f MB of tables and per-row buffers) exceeds the %d MB last-level cache" % (
+            (table + g) / 1e6, LLC_BYTES >> 20)
+    if us < 12.0 and kernel in ("k_seg_fixup", "k_scatter", "k_scatter_finish", "k_hist_finish", "k_emit", "k_finish_loss"):
+        return "latency: a few dependent memory round trips on little data; bytes per second say nothing here"
+    return ("cache: tables and per-row buffers (%.0f MB) stay in the %d MB last-level cache, so the algorithmic bytes are "
+            "mostly not HBM traffic and the fraction of the HBM peak is nominal" % ((table + g) / 1e6, LLC_BYTES >> 20))
+
+
+class Job:
+    """One workload set up on the GPU: context, tables, marshalled argument lists of every batch."""
+
+    def __init__(self, wl, dev, api, lookahead):
+        import ctypes as C
+
+        import torch
+
+        from paper_2502_16949_amd import binding as B
+        from paper_2502_16949_amd import workloads as W
+        self.wl, self.api, self.B, self.torch = wl, api, B, torch
+        self.fused = api != "separate"
+        self.one_call = api == "step"
+        # batches whose first build kernels can run inside the previous step's launches (see stx_batch.next)
+        self.rides = (self.one_call and lookahead and (wl.model != "transr" or wl.n_rel <= 4096)
+                      and wl.n_ent + wl.n_rel <= 65536 and 3 * wl.rows_per_batch <= (1 << 19) and wl.dim <= 256)
+        # the one-call step leaves the last kernel of the build to the launch of the transposed product (rows of
+        # one float4 per lane; TransR when its work items come from the rows-per-relation counts)
+        self.segw = self.one_call and (wl.model != "transr" or wl.n_rel <= 4096) and wl.dim <= 256
+        self.h, self.r, self.t = W.make_graph(wl)
+        self.tabs = W.make_tables(wl)
+        hd, rd, td = (torch.from_numpy(a).to(dev) for a in (self.h, self.r, self.t))
+        flags = {"transh": B.STX_FLAG_RENORM_W, "transr": B.STX_FLAG_BF16_PROJ}.get(wl.model, 0)
+        cfg = B.make_config(wl.model, wl.dist, wl.n_ent, wl.n_rel, wl.dim, wl.batch, wl.n_neg, rel_dim=wl.rel_dim,
+                            margin=wl.margin, flags=flags)
+        self.ctx = ctx = B.Context(cfg, dev)
+        self.params = params = B.Params(*(None if self.tabs.get(k) is None else torch.from_numpy(self.tabs[k]).to(dev)
+                                          for k in ("ent", "rel", "w", "proj")))
+        self.inc = inc = B.Incidence(ctx)
+        self.grads = grads = B.Grads(ctx)
+        self.scores = scores = torch.empty(ctx.rows_max, dtype=torch.float32, device=dev)
+        self.loss = loss = torch.zeros(1, dtype=torch.float32, device=dev)
+        nh = torch.empty(wl.batch * wl.n_neg, dtype=torch.int32, device=dev)
+        nt = torch.empty(wl.batch * wl.n_neg, dtype=torch.int32, device=dev)
+        self.keep = (hd, rd, td, nh, nt)
+        self.slices = W.batch_slices(wl)
+        seed = W.negative_seed(wl)
+        byref = C.byref
+        self.L = B.lib()
+
+        # Argument lists are marshalled once per batch; the timed loop makes only the C calls.
+        def marshal(lo, hi):
+            hb, rb, tb = (a.data_ptr() + 4 * lo for a in (hd, rd, td))
+            b = hi - lo
+            return ((ctx.handle, hb, rb, tb, b, wl.n_neg, seed, 0, wl.n_triplets, lo, nh.data_ptr(), nt.data_ptr()),
+                    (ctx.handle, hb, rb, tb, nh.data_ptr(), nt.data_ptr(), b, wl.n_neg, byref(inc.c)),
+                    (ctx.handle, byref(inc.c), byref(params.c), scores.data_ptr(), loss.data_ptr()),
+                    (ctx.handle, byref(inc.c), byref(params.c), byref(grads.c)),
+                    (ctx.handle, byref(params.c), byref(inc.c), byref(grads.c), wl.lr),
+                    (ctx.handle, byref(inc.c), byref(params.c), byref(grads.c), wl.lr),
+                    (ctx.handle, byref(B.make_batch(hd[lo:hi], rd[lo:hi], td[lo:hi], wl.n_neg, seed, 0, wl.n_triplets, lo,
+                                                    nh, nt)),
+                     byref(inc.c), byref(params.c), byref(grads.c), wl.lr, scores.data_ptr(), loss.data_ptr()),
+                    b * (1 + wl.n_neg))
+        self.calls = [marshal(lo, hi) for lo, hi in self.slices]
+        if self.one_call and lookahead:
+            # every step names the batch of the step after it (steps walk the batches cyclically)
+            B.link_batches([c[6][1]._obj for c in self.calls], cyclic=True)
+        self.next_step = 0
+
+    def step(self, ev=None):
+        """The next step of the walk over the batches; returns its number of matrix rows."""
+        i = self.next_step
+        self.next_step += 1
+        L = self.L
+        a_s, a_b, a_f, a_g, a_u, a_bu, a_step, rows = self.calls[i % len(self.calls)]
+        if self.one_call:
+            if L.stx_train_step(*a_step):
+                raise RuntimeError(f"stx_train_step failed in step {i}")
+            return rows
+        if ev: ev[0].record()
+        st = L.stx_sample_negatives(*a_s)
+        if ev: ev[1].record()
+        st |= L.stx_build_incidence(*a_b)
+        if ev: ev[2].record()
+        st |= L.stx_forward(*a_f)
+        if ev: ev[3].record()
+        if self.fused:
+            st |= L.stx_backward_sgd(*a_bu)
+            if ev: ev[4].record()
+        else:
+            st |= L.stx_backward(*a_g)
+            if ev: ev[4].record()
+            st |= L.stx_sgd_step(*a_u)
+        if ev: ev[5].record()
+        if st:
+            raise RuntimeError(f"a library call failed in step {i} (or-ed status {st})")
+        return rows
+
+    def run(self, n):
+        rows = 0
+        for _ in range(n):
+            rows += self.step()
+        return rows
+
+    def timed_windows(self, steps, windows):
+        """`windows` regions of exactly `steps` steps, each between two device synchronisations, with nothing
+        else on the stream (no event brackets).  Returns [(seconds, rows, host seconds to enqueue)]."""
+        out = []
+        for _ in range(windows):
+            self.torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            rows = self.run(steps)
+            t_enq = time.perf_counter() - t0
+            self.torch.cuda.synchronize()
+            out.append((time.perf_counter() - t0, rows, t_enq))
+        return out
+
+    def bracketed(self, name, steps, cap_per_step=40):
+        """Untimed pass: `steps` more steps with the launches of kernel `name` ("*": every kernel) bracketed by HIP
+        events on the library's stream.  Returns ({kernel: (mean us, launches per step)}, mean rows per step)."""
+        B = self.B
+        B.stx_profile_kernel(self.ctx, name, cap_per_step * steps)
+        rows = self.run(steps)
+        if name == "*":
+            got = {k: (v[0], v[1] / steps) for k, v in B.stx_profile_dump(self.ctx).items()}
+        else:
+            us, n = B.stx_profile_read(self.ctx)
+            got = {name: (us, n / steps)}
+        B.stx_profile_kernel(self.ctx, None, 0)
+        return got, rows / steps
+
+    def phases(self, steps):
+        """Separate calls only: mean microseconds of each call of a step (events on the current stream)."""
+        torch = self.torch
+        events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(steps)]
+        rows = 0
+        for ev in events:
+            rows += self.step(ev)
+        torch.cuda.synchronize()
+        tot = [0.0] * 5
+        for ev in events:
+            for p in range(5):
+                tot[p] += ev[p].elapsed_time(ev[p + 1])
+        names = ("sample", "build", "forward", "backward_sgd" if self.fused else "backward", "sgd")
+        return {k: v / steps * 1e3 for k, v in zip(names, tot)}, rows / steps
+
+    def kernel_entry(self, kname, us, mean_rows, touched):
+        """Roofline entry of one kernel from its mean launch time: algorithmic bytes, the fewest bytes the launch
+        could move, the measured traffic where a profile has it, and the roof the figures are held against."""
+        wl = self.wl
+        u = touched * mean_rows / wl.rows_per_batch
+        w, unit, bound, peak = kernel_work(wl, kname, mean_rows, u, self.fused, self.rides, self.segw)
+        ach = w / (us * 1e-6) / (1e9 if unit == "GB/s" else 1e12) if us > 0 else 0.0
+        e = {"bound": bound, "kernel": kname, "achieved": round(ach, 1), "peak": peak, "unit": unit,
+             "frac": round(ach / peak, 4),
+             "traffic": TRAFFIC_BYTES.get((wl.name, kname, "rides" if self.rides else self.fused)),
+             "work_per_launch": int(w), "avg_launch_us": round(us, 2), "roof": roof_of(wl, kname, us)}
+        bmin = kernel_min_bytes(wl, kname, mean_rows, u, self.fused)
+        if bmin is not None and us > 0:
+            e["min_bytes_per_launch"] = int(bmin)
+            e["achieved_min_bytes"] = round(bmin / (us * 1e-6) / 1e9, 1)
+        if e["traffic"] and us > 0:
+            e["achieved_traffic"] = round(e["traffic"] / (us * 1e-6) / 1e9, 1)
+        return e
+
+
+def summarize(windows, steps):
+    ms = sorted(w[0] / steps * 1e3 for w in windows)
+    n = len(ms)
+    med = ms[n // 2] if n % 2 else 0.5 * (ms[n // 2 - 1] + ms[n // 2])
+    return {"windows": n, "steps_per_window": steps, "ms_per_step_mean": round(sum(ms) / n, 5),
+            "ms_per_step_median": round(med, 5), "ms_per_step_min": round(ms[0], 5), "ms_per_step_max": round(ms[-1], 5)}
+
+
+def median_window(windows):
+    order = sorted(windows, key=lambda w: w[0] / max(w[1], 1))
+    return order[(len(order) - 1) // 2]
+
+
+def hbm_resident_leg(args, dev):
+    """The HBM-resident configuration ("toruse": 2 GB table, 1.3 M rows per batch) on the same line as the headline:
+    a short run of linked stx_train_step calls, then untimed bracketed passes for the kernels the 60 % target is
+    about: the fused transposed product, the forward gather, and the stand-alone update (separate calls)."""
+    import torch
+
+    from paper_2502_16949_amd import workloads as W
+    wl = W.WORKLOADS["toruse"]
+    steps, warm = max(20, min(args.steps, 40)), 5
+    job = Job(wl, dev, "step", True)
+    job.run(warm)
+    wins = job.timed_windows(steps, 3)
+    dt, rows, _ = median_window(wins)
+    u = int(job.inc.n_touched.item())
+    got, mean_rows = job.bracketed("*", 20)
+    kernels = {}
+    for kname in ("k_seg_reduce", "k_forward_stacked"):
+        if kname in got:
+            kernels[kname + (" (fused update)" if kname == "k_seg_reduce" else "")] = job.kernel_entry(kname, got[kname][0], mean_rows, u)
+    leg = {"workload": f"toruse: toruse torus_l1, {wl.n_ent} entities, {wl.n_rel} relations, dim {wl.dim}, batch {wl.batch}, "
+                       f"{wl.n_neg} negatives per positive ({wl.rows_per_batch} rows per step, {u} touched rows)",
+           "value": round(rows / dt, 1), "unit": "triplets/s", "ms_per_step": round(dt / steps * 1e3, 4),
+           "timing": summarize(wins, steps), "kernels_us": {k: [round(v[0], 2), round(v[1], 2)] for k, v in got.items()}}
+    # the stand-alone update and the unfused product: the same batches through the separate calls
+    del job
+    torch.cuda.empty_cache()
+    sep = Job(wl, dev, "separate", False)
+    sep.run(3)
+    got2, mean_rows2 = sep.bracketed("*", 10)
+    u2 = int(sep.inc.n_touched.item())
+    for kname in ("k_sgd_rows", "k_seg_reduce"):
+        if kname in got2:
+            kernels[kname + (" (gradient rows stored)" if kname == "k_seg_reduce" else "")] = sep.kernel_entry(kname, got2[kname][0], mean_rows2, u2)
+    ph, _ = sep.phases(6)
+    leg["separate_calls_us"] = {k: round(v, 1) for k, v in ph.items()}
+    leg["kernels"] = kernels
+    return leg
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -394,14 +645,7 @@ def main():
         sys.exit(2)
     dev = "cuda:0"
     if args.copy_calibration:
-        n = args.copy_calibration * (1 << 20) // 4
-        cctx = B.Context(B.make_config("transe", "l1", 16, 1, 4, 1, 0), dev)
-        src = torch.ones(n, dtype=torch.float32, device=dev)
-        dst = torch.empty_like(src)
-        for _ in range(20):
-            B.stx_copy_f32(cctx, dst, src)
-        torch.cuda.synchronize()
-        print(json.dumps({"copy_calibration_bytes_read": 4 * n, "bytes_written": 4 * n, "launches": 20}))
+        copy_calibration(args, dev)
         return
     wl = W.WORKLOADS[args.config]
     if args.semiring:
@@ -412,156 +656,34 @@ def main():
         return
     kernel = args.kernel or ((DOMINANT_PLAIN if args.no_lookahead else DOMINANT) if args.api == "step"
                              else DOMINANT_CALLS)[wl.name]
-    # batches whose first build kernels can run inside the previous step's launches (see stx_batch.next)
-    rides = (args.api == "step" and not args.no_lookahead and (wl.model != "transr" or wl.n_rel <= 4096)
-             and wl.n_ent + wl.n_rel <= 65536 and 3 * wl.rows_per_batch <= (1 << 19) and wl.dim <= 256)
+    job = Job(wl, dev, args.api, not args.no_lookahead)
+    job.run(args.warmup)
 
-    # the one-call step leaves the last kernel of the build to the launch of the transposed product (rows of one
-    # float4 per lane; TransR when its work items come from the rows-per-relation counts)
-    segw = args.api == "step" and (wl.model != "transr" or wl.n_rel <= 4096) and wl.dim <= 256
+    # ---- timed region: windows of exactly --steps steps, each between two device synchronisations; nothing but
+    # the steps is on the stream (no event brackets).  `value` is the median window. ---------------------------
+    wins = job.timed_windows(args.steps, max(1, args.windows))
+    dt, rows_done, t_enq = median_window(wins)
+    loss_last = float(job.loss.item())
+    u_last = int(job.inc.n_touched.item())
 
-    h, r, t = W.make_graph(wl)
-    tabs = W.make_tables(wl)
-    hd, rd, td = (torch.from_numpy(a).to(dev) for a in (h, r, t))
-    flags = {"transh": B.STX_FLAG_RENORM_W, "transr": B.STX_FLAG_BF16_PROJ}.get(wl.model, 0)
-    cfg = B.make_config(wl.model, wl.dist, wl.n_ent, wl.n_rel, wl.dim, wl.batch, wl.n_neg, rel_dim=wl.rel_dim,
-                        margin=wl.margin, flags=flags)
-    ctx = B.Context(cfg, dev)
-    params = B.Params(*(None if tabs.get(k) is None else torch.from_numpy(tabs[k]).to(dev)
-                        for k in ("ent", "rel", "w", "proj")))
-    inc = B.Incidence(ctx)
-    grads = B.Grads(ctx)
-    scores = torch.empty(ctx.rows_max, dtype=torch.float32, device=dev)
-    loss = torch.zeros(1, dtype=torch.float32, device=dev)
-    nh = torch.empty(wl.batch * wl.n_neg, dtype=torch.int32, device=dev)
-    nt = torch.empty(wl.batch * wl.n_neg, dtype=torch.int32, device=dev)
-    slices = W.batch_slices(wl)
-    seed = W.negative_seed(wl)
-
-    # Argument lists are marshalled once per batch; the timed loop makes only the C calls: sample, build,
-    # forward and the fused backward + update (stx_backward_sgd), or backward and update separately (--unfused).
-    fused = args.api != "separate"
-    one_call = args.api == "step"
-    L = B.lib()
-    import ctypes as C
-    byref = C.byref
-
-    def marshal(lo, hi):
-        hb, rb, tb = (a.data_ptr() + 4 * lo for a in (hd, rd, td))
-        b = hi - lo
-        return ((ctx.handle, hb, rb, tb, b, wl.n_neg, seed, 0, wl.n_triplets, lo, nh.data_ptr(), nt.data_ptr()),
-                (ctx.handle, hb, rb, tb, nh.data_ptr(), nt.data_ptr(), b, wl.n_neg, byref(inc.c)),
-                (ctx.handle, byref(inc.c), byref(params.c), scores.data_ptr(), loss.data_ptr()),
-                (ctx.handle, byref(inc.c), byref(params.c), byref(grads.c)),
-                (ctx.handle, byref(params.c), byref(inc.c), byref(grads.c), wl.lr),
-                (ctx.handle, byref(inc.c), byref(params.c), byref(grads.c), wl.lr),
-                (ctx.handle, byref(B.make_batch(hd[lo:hi], rd[lo:hi], td[lo:hi], wl.n_neg, seed, 0, wl.n_triplets, lo,
-                                                nh, nt)),
-                 byref(inc.c), byref(params.c), byref(grads.c), wl.lr, scores.data_ptr(), loss.data_ptr()),
-                b * (1 + wl.n_neg))
-    calls = [marshal(lo, hi) for lo, hi in slices]
-    if one_call and not args.no_lookahead:
-        # every step names the batch of the step after it (steps walk the batches cyclically)
-        batch_objs = [c[6][1]._obj for c in calls]
-        B.link_batches(batch_objs, cyclic=True)
-
-    def step(i, ev=None):
-        a_s, a_b, a_f, a_g, a_u, a_bu, a_step, rows = calls[i % len(calls)]
-        if one_call and not ev:
-            if L.stx_train_step(*a_step):
-                raise RuntimeError(f"stx_train_step failed in step {i}")
-            return rows
-        if ev: ev[0].record()
-        st = L.stx_sample_negatives(*a_s)
-        if ev: ev[1].record()
-        st |= L.stx_build_incidence(*a_b)
-        if ev: ev[2].record()
-        st |= L.stx_forward(*a_f)
-        if ev: ev[3].record()
-        if fused:
-            st |= L.stx_backward_sgd(*a_bu)
-            if ev: ev[4].record()
-        else:
-            st |= L.stx_backward(*a_g)
-            if ev: ev[4].record()
-            st |= L.stx_sgd_step(*a_u)
-        if ev: ev[5].record()
-        if st:
-            raise RuntimeError(f"a library call failed in step {i} (or-ed status {st})")
-        return rows
-
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-
-    # ---- timed region: exactly --steps steps; the library brackets the launches of `kernel` with HIP
-    # events on the stream that kernel runs on ---------------------------------------------------------
-    # every eighth launch of the kernel is bracketed: an event pair costs a few microseconds of stream time, and
-    # at 50 us per step bracketing them all would slow the steps that are being timed by a tenth
-    B.stx_profile_kernel(ctx, kernel, 8 * args.steps)
-    prof_every = 8 if args.steps >= 64 else 1
-    if prof_every > 1:      # the sample must walk through all batches of the epoch (the last one is shorter)
-        import math
-        while math.gcd(prof_every, len(calls)) != 1:
-            prof_every += 1
-    B.stx_profile_every(ctx, prof_every)
-    rows_done = 0
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        rows_done += step(args.warmup + i)
-    t_enq = time.perf_counter() - t0
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    kernel_us, kernel_n = B.stx_profile_read(ctx)
-    B.stx_profile_kernel(ctx, None, 0)
-    loss_last = float(loss.item())
-    u_last = int(inc.n_touched.item())
-
-    # ---- untimed extra pass: where the time goes, call by call (events on the context's stream) ----
-
-    n_ph = min(args.steps, 60)
-    phase_us = None
-    if not one_call:   # the one-call step has no phases to separate: its per-kernel times are listed instead
-        events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(n_ph)]
-        for i in range(n_ph):
-            step(args.warmup + args.steps + i, events[i])
-        torch.cuda.synchronize()
-        phase = np.zeros(5)
-        for ev in events:
-            for p in range(5):
-                phase[p] += ev[p].elapsed_time(ev[p + 1])
-        phase_us = phase / n_ph * 1e3
-
-    # ---- roofline of the dominant kernel.  The mean launch time covers every batch of the timed region
-    # (the partial last batch of an epoch included), so the work figure is averaged the same way. ----------
-    mean_rows = rows_done / args.steps
-    work, unit, bound, peak = kernel_work(wl, kernel, mean_rows, u_last * mean_rows / wl.rows_per_batch, fused, rides,
-                                          segw)
-    kernel_note = ""
-    if kernel == "k_seg_reduce" and (rides or segw):
-        kernel_note = ("this launch also runs " +
-                       " and ".join((["the last kernel of this batch's build (21 B per entry)"] if segw else []) +
-                                    (["the first scatter pass of the next batch's sort (16 B per entry)"] if rides else [])) +
-                       ", counted")
-    per_launch = kernel_n * prof_every / args.steps if args.steps else 0
-    achieved = (work / (kernel_us * 1e-6)) / (1e9 if unit == "GB/s" else 1e12) if kernel_us > 0 else 0.0
-    roofline = {"bound": bound, "kernel": kernel, "achieved": round(achieved, 1), "peak": peak, "unit": unit,
-                "frac": round(achieved / peak, 4),
-                "traffic": TRAFFIC_BYTES.get((wl.name, kernel, "rides" if rides else fused)), "work_per_launch": int(work),
-                "avg_launch_us": round(kernel_us, 2), "launches_per_step": round(per_launch, 2)}
-    bmin = kernel_min_bytes(wl, kernel, mean_rows, u_last * mean_rows / wl.rows_per_batch, fused)
-    if bmin is not None and kernel_us > 0:
-        # the same launch priced by the fewest bytes it could move (distinct rows once): a second, lower figure
-        roofline["min_bytes_per_launch"] = int(bmin)
-        roofline["achieved_min_bytes"] = round(bmin / (kernel_us * 1e-6) / 1e9, 1)
-    if kernel_note:
-        roofline["note"] = kernel_note
-    if kernel in ("k_transr_project", "k_transr_gx", "k_transr_dm") and kernel_us > 0:
+    # ---- untimed passes: the dominant kernel's launches bracketed by HIP events on the library's stream (its
+    # roofline entry), then every kernel (where the time goes), then, for separate calls, the calls themselves ----
+    n_ph = max(min(args.steps, 60), min(len(job.calls), 30))
+    got, mean_rows = job.bracketed(kernel, n_ph)
+    kernel_us, per_launch = got[kernel]
+    roofline = job.kernel_entry(kernel, kernel_us, mean_rows, u_last)
+    roofline["launches_per_step"] = round(per_launch, 2)
+    if kernel == "k_seg_reduce" and (job.rides or job.segw):
+        roofline["note"] = ("this launch also runs " +
+                            " and ".join((["the last kernel of this batch's build (21 B per entry)"] if job.segw else []) +
+                                         (["the first scatter pass of the next batch's sort (16 B per entry)"] if job.rides else [])) +
+                            ", counted")
+    if kernel in TRANSR_PRODUCTS and kernel_us > 0:
         # the same launch priced as a contraction, against the dense bf16 matrix-core peak
         tf = 2.0 * mean_rows * wl.dim * wl.rel_dim / (kernel_us * 1e-6) / 1e12
         roofline["mfma"] = {"achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                            "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4)}
+                            "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                            "counters": "profiles/transr_kernel_trace.txt (matrix-core busy cycles and operations from rocprofv3 --pmc)"}
 
     out = {
         "metric": "training triplets/sec (pos+neg) TransE d=128 fp32" if wl.name == "mid"
@@ -574,56 +696,83 @@ def main():
                                f"{wl.n_triplets} triplets (Zipf {wl.zipf_ent}/{wl.zipf_rel}), dim {wl.dim}, "
                                f"batch {wl.batch}, {wl.n_neg} negative(s) per positive, margin {wl.margin}, "
                                f"SGD lr {wl.lr}",
-                   "rows_per_full_batch": wl.rows_per_batch, "batches_per_epoch": len(slices),
+                   "rows_per_full_batch": wl.rows_per_batch, "batches_per_epoch": len(job.slices),
                    "step": ("stx_train_step: sample negatives + build incidence + forward + backward with fused sgd, one call"
-                            + ("" if args.no_lookahead else "; each call names the next batch") if one_call else "sample negatives + build incidence + forward + " +
-                            ("backward with fused sgd (stx_backward_sgd)" if fused else "backward + sgd")),
+                            + ("" if args.no_lookahead else "; each call names the next batch") if job.one_call else "sample negatives + build incidence + forward + " +
+                            ("backward with fused sgd (stx_backward_sgd)" if job.fused else "backward + sgd")),
                    "api": args.api},
+        "timing": dict(summarize(wins, args.steps), value_is="the median window; no event brackets inside any window"),
         "host_enqueue_us_per_step": round(t_enq / args.steps * 1e6, 2),
         "touched_rows_last_step": u_last,
         "loss_last_step": loss_last,
         "roofline": roofline,
     }
 
-    if phase_us is not None:
-        out["phase_us"] = {k: round(float(v), 2) for k, v in
-                           zip(("sample", "build", "forward", "backward_sgd" if fused else "backward", "sgd"), phase_us)}
-    if args.all_kernels or one_call:
-        # an extra, untimed pass with every kernel bracketed by events: [mean microseconds, launches per step]
-        # (each bracket adds about 2 us to what the kernel trace in profiles/ shows for the same kernel)
-        B.stx_profile_kernel(ctx, "*", 40 * n_ph)
-        for i in range(n_ph):
-            step(args.warmup + args.steps + n_ph + i)
-        out["kernels_us"] = {k: [round(v[0], 2), round(v[1] / n_ph, 2)] for k, v in B.stx_profile_dump(ctx).items()}
-        B.stx_profile_kernel(ctx, None, 0)
-        # the same byte models for the other kernels of the step that have one, from this pass's means: where two
-        # kernels take nearly the same time (forward and transposed product at "mid") both figures are on record
+    if not job.one_call:
+        ph, ph_rows = job.phases(min(args.steps, 60))
+        out["phase_us"] = {k: round(v, 2) for k, v in ph.items()}
+    if args.all_kernels or job.one_call:
+        # every kernel bracketed: [mean microseconds, launches per step] (a bracket adds 2-4 us to a kernel)
+        allk, rows_k = job.bracketed("*", n_ph)
+        out["kernels_us"] = {k: [round(v[0], 2), round(v[1], 2)] for k, v in allk.items()}
         others = {}
-        for kname, (us, per_step) in out["kernels_us"].items():
+        for kname, (us, _) in allk.items():
             if kname == kernel or us <= 0:
                 continue
             try:
-                w, unit, bound, peak = kernel_work(wl, kname, mean_rows, u_last * mean_rows / wl.rows_per_batch, fused, rides,
-                                                   segw)
+                others[kname] = job.kernel_entry(kname, us, rows_k, u_last)
             except ValueError:
                 continue
-            ach = w / (us * 1e-6) / (1e9 if unit == "GB/s" else 1e12)
-            others[kname] = {"bound": bound, "achieved": round(ach, 1), "peak": peak, "unit": unit,
-                             "frac": round(ach / peak, 4),
-                             "traffic": TRAFFIC_BYTES.get((wl.name, kname, "rides" if rides else fused)),
-                             "work_per_launch": int(w), "avg_launch_us": us}
         out["roofline_other_kernels"] = others
+
+    # ---- sampling and build throughput by themselves (untimed for the headline): the same batches through the
+    # separate calls, each call between events -------------------------------------------------------------
+    if not args.no_build_rates:
+        if job.one_call:
+            peak_bytes = torch.cuda.max_memory_allocated()
+            aux = Job(wl, dev, "separate", False)
+            aux.run(3)
+        else:
+            aux = job
+        ph, ph_rows = aux.phases(min(max(args.steps, 10), 30))
+        nneg = ph_rows * wl.n_neg / (1 + wl.n_neg)
+        out["build_keys_per_s"] = round(3 * ph_rows / (ph["build"] * 1e-6), 1) if ph["build"] > 0 else None
+        out["sample_negs_per_s"] = round(nneg / (ph["sample"] * 1e-6), 1) if ph["sample"] > 0 and nneg else None
+        out["build_us"], out["sample_us"] = round(ph["build"], 2), round(ph["sample"], 2)
+        if aux is not job:
+            del aux
+    out["peak_device_bytes"] = int(torch.cuda.max_memory_allocated())
 
     if not args.no_cpu_baseline:
         n = args.cpu_steps
         if n <= 0:
-            _, _, dt1 = cpu_baseline(wl, h, r, t, tabs, 1)
+            _, _, dt1 = cpu_baseline(wl, job.h, job.r, job.t, job.tabs, 1)
             n = max(2, min(400, int(15.0 / max(dt1, 1e-3))))
-        v, done, cdt = cpu_baseline(wl, h, r, t, tabs, n)
-        out["cpu_baseline"] = {"value": round(v, 1), "unit": "triplets/s", "cores": 1, "kind": "oracle",
-                               "sample": f"first {done} steps of the same workload (sampling, incidence build, "
-                                         f"forward, backward, sgd), {cdt:.1f} s, single thread"}
+        v, done, cdt = cpu_baseline(wl, job.h, job.r, job.t, job.tabs, n)
+        out["cpu_baseline"] = dict({"value": round(v, 1), "unit": "triplets/s", "cores": 1, "kind": "oracle",
+                                    "sample": f"first {done} steps of the same workload (sampling, incidence build, "
+                                              f"forward, backward, sgd), {cdt:.1f} s, single thread"}, **host_info())
+
+    # ---- the HBM-resident configuration beside the cache-resident headline ---------------------------------
+    if wl.name == "mid" and args.api == "step" and not args.no_hbm_leg:
+        del job
+        torch.cuda.empty_cache()
+        out["hbm_resident"] = hbm_resident_leg(args, dev)
     print(json.dumps(out))
+
+
+def copy_calibration(args, dev):
+    import torch
+
+    from paper_2502_16949_amd import binding as B
+    n = args.copy_calibration * (1 << 20) // 4
+    cctx = B.Context(B.make_config("transe", "l1", 16, 1, 4, 1, 0), dev)
+    src = torch.ones(n, dtype=torch.float32, device=dev)
+    dst = torch.empty_like(src)
+    for _ in range(20):
+        B.stx_copy_f32(cctx, dst, src)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_calibration_bytes_read": 4 * n, "bytes_written": 4 * n, "launches": 20}))
 
 
 if __name__ == "__main__":
