@@ -771,8 +771,15 @@ def copy_calibration(args, dev):
     dst = torch.empty_like(src)
     for _ in range(20):
         B.stx_copy_f32(cctx, dst, src)
+    # the second pattern: one 32-byte read per lane, slots 512 bytes apart, every slot once per launch
+    n_slots = 4 * n // 512
+    sink = torch.zeros(16384, dtype=torch.float32, device=dev)
+    for _ in range(20):
+        B.stx_read_sectors(cctx, src, n_slots, 512, n_slots, sink)
     torch.cuda.synchronize()
-    print(json.dumps({"copy_calibration_bytes_read": 4 * n, "bytes_written": 4 * n, "launches": 20}))
+    print(json.dumps({"k_copy_f32": {"bytes_read": 4 * n, "bytes_written": 4 * n, "launches": 20},
+                      "k_read_sectors": {"bytes_read": 32 * n_slots, "reads": n_slots, "slot_bytes": 512,
+                                         "bytes_written": 0, "launches": 20}}))
 
 
 if __name__ == "__main__":

@@ -11,8 +11,9 @@
  * Conventions for every entry point
  *   - Unless a parameter says "host", pointers are DEVICE pointers owned by the caller.  The library
  *     never allocates or frees device memory: its scratch lives in the workspace given to stx_create.
- *   - All work is enqueued on the stream given to stx_create and the calls return without waiting;
- *     only stx_check_indices synchronises.  Calls on one context must not overlap in time.
+ *   - All work is enqueued on the stream given to stx_create and the calls return without waiting, except
+ *     stx_check_indices (waits for the stream to read the counter) and stx_rank on a TransR context (waits
+ *     once, to learn the sizes of the relation groups).  Calls on one context must not overlap in time.
  *   - Every call returns a stx_status.  Host-detectable argument errors (null pointers, sizes beyond
  *     the configured maxima, bad enums) are reported before anything is launched.
  *   - Indices are int32, counts int64.  Tables are fp32, row-major, 16-byte aligned, with
@@ -233,8 +234,12 @@ stx_status stx_backward_sgd(stx_ctx *ctx, const stx_incidence *inc, stx_params *
  * so they then run inside this step's launches, one stage per launch, and the next call, if it is given
  * exactly that batch, starts from where they stopped (in steady state a step is three launches); results
  * are the same bit for bit.  With next set, on return the A arrays of inc (a_rowptr, a_colidx, a_vals) and
- * next's neg_h / neg_t already hold the next batch's, the A^T arrays this batch's.  A next call with
- * another batch, or any other call, simply builds as usual.  Used when the configuration keeps a column
+ * next's neg_h / neg_t already hold the next batch's, the A^T arrays this batch's; until inc is built again
+ * (by the next stx_train_step or by stx_build_incidence) the calls that read A through it (stx_spmm,
+ * stx_spmm_semiring, stx_spmm_semiring_t, stx_forward) return STX_ERR_STATE, the calls that read only A^T
+ * (stx_backward, stx_sgd_step) work as usual.  A next call with another batch simply builds as usual (an
+ * out-of-range index of a batch that was announced and then not given is counted once more when its
+ * batch is written again).  Used when the configuration keeps a column
  * bitmap (n_ent + n_rel <= 65,536), with dim <= 256 (TransR: also n_rel <= 4,096) and batches of at most
  * 2^19 entries of A; ignored otherwise.  next->next is ignored.                                          */
 typedef struct stx_batch {
@@ -285,29 +290,6 @@ stx_status stx_rank_work_bytes(const stx_ctx *ctx, int64_t nq, size_t *bytes /* 
 stx_status stx_rank(stx_ctx *ctx, const stx_params *p, const int32_t *h, const int32_t *r, const int32_t *t,
                     int64_t nq, int32_t side, float *true_score, int32_t *n_less, int32_t *n_equal, void *work,
                     size_t work_bytes);
-
-/* Live timing of one kernel, for benchmarks.  stx_profile_kernel: from now on every launch of the kernel
- * called `kernel_name` (e.g. "k_forward_stacked", "k_seg_reduce", "k_sgd_rows", "k_scatter") on this
- * context is bracketed by a pair of HIP events on the context's stream, for at most max_records
- * launches; a null name or max_records == 0 switches timing off.  stx_profile_read: waits for the
- * stream, then *avg_us (host) = mean bracketed time in microseconds and *n (host) = launches recorded;
- * recording restarts from zero.  The name "*" brackets every kernel that has a bracket (all but a few
- * one-workgroup helpers); stx_profile_dump then writes one line "name mean_us launches" per kernel into
- * text (host, text_bytes long, NUL-terminated) and restarts recording.  Bracketing every kernel adds
- * event work to the stream: use it to see where time goes, not to time a whole step.  Not to be used
- * while the stream is being captured into a graph.                                                     */
-stx_status stx_profile_kernel(stx_ctx *ctx, const char *kernel_name /* host */, int32_t max_records);
-/* Bracket only every `every`-th launch that stx_profile_kernel selects (1 = all, the default after every
- * stx_profile_kernel call).  An event pair costs a few microseconds of stream time: a benchmark that times
- * whole steps and one kernel together samples the kernel sparsely so that the steps are not slowed.    */
-stx_status stx_profile_every(stx_ctx *ctx, int32_t every);
-stx_status stx_profile_read(stx_ctx *ctx, double *avg_us, int32_t *n);
-stx_status stx_profile_dump(stx_ctx *ctx, char *text, size_t text_bytes);
-
-/* Measurement aid: dst[i] = src[i] for n floats (n % 4 == 0, both 16-byte aligned) by a plain
- * grid-stride copy kernel ("k_copy_f32") that reads 4n and writes 4n bytes.  Profilers' hardware byte
- * counters are scaled by what they report for this known traffic.                                     */
-stx_status stx_copy_f32(stx_ctx *ctx, float *dst, const float *src, int64_t n);
 
 const char *stx_status_string(stx_status s);
 

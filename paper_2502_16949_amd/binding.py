@@ -29,7 +29,7 @@ DISTS = {"l1": STX_L1, "l2": STX_L2, "torus_l1": STX_TORUS_L1, "torus_l2": STX_T
 
 EXPORTS = ["stx_workspace_bytes", "stx_create", "stx_destroy", "stx_sample_negatives", "stx_build_incidence",
            "stx_check_indices", "stx_spmm", "stx_spmm_semiring", "stx_spmm_semiring_t", "stx_spmm_semiring_t_static", "stx_rank", "stx_rank_work_bytes", "stx_forward", "stx_backward", "stx_sgd_step", "stx_backward_sgd", "stx_train_step", "stx_profile_kernel",
-           "stx_profile_every", "stx_profile_read", "stx_profile_dump", "stx_copy_f32", "stx_status_string"]
+           "stx_profile_every", "stx_profile_read", "stx_profile_dump", "stx_copy_f32", "stx_read_sectors", "stx_status_string"]
 
 
 class StxError(RuntimeError):
@@ -106,6 +106,7 @@ def lib():
         L.stx_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32)]
         L.stx_profile_dump.argtypes = [vp, C.c_char_p, C.c_size_t]
         L.stx_copy_f32.argtypes = [vp, vp, vp, i64]
+        L.stx_read_sectors.argtypes = [vp, vp, i64, i32, i64, vp]
         L.stx_status_string.argtypes = [C.c_int]
         L.stx_status_string.restype = C.c_char_p
         for name in EXPORTS[:-1]:
@@ -374,6 +375,13 @@ def stx_profile_read(ctx: Context):
 def stx_copy_f32(ctx: Context, dst, src):
     assert dst.numel() == src.numel() and dst.dtype == src.dtype == torch.float32
     _check("stx_copy_f32", lib().stx_copy_f32(ctx.handle, dst.data_ptr(), src.data_ptr(), src.numel()))
+
+
+def stx_read_sectors(ctx: Context, src, n_slots: int, slot_bytes: int, n_reads: int, sink):
+    assert src.is_cuda and src.numel() * src.element_size() >= n_slots * slot_bytes
+    assert sink.is_cuda and sink.dtype == torch.float32 and sink.numel() >= 16384
+    _check("stx_read_sectors", lib().stx_read_sectors(ctx.handle, src.data_ptr(), n_slots, slot_bytes, n_reads,
+                                                      sink.data_ptr()))
 
 
 def stx_profile_dump(ctx: Context) -> dict:

@@ -135,6 +135,13 @@ stx_status check_params(const stx_ctx *ctx, const stx_params *p)
 
 bool stacked(const stx_ctx *c) { return c->cfg.model == STX_TRANSE || c->cfg.model == STX_TORUSE; }
 
+// After a stx_train_step that named its next batch, the A arrays of inc already hold that next batch while
+// inc->b, k, n_rows and the A^T arrays describe the batch just trained: a call that reads A must not pair them.
+stx_status check_a_current(const stx_ctx *ctx, const stx_incidence *inc)
+{
+    return (ctx->ahead.armed && ctx->ahead.emit_done && ctx->ahead.inc == inc) ? STX_ERR_STATE : STX_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -211,6 +218,8 @@ stx_status stx_create(const stx_config *cfg, void *workspace, size_t workspace_b
     c->ahead.scatter_ok = c->ahead.hist_ok = false;
     c->ahead.inc = nullptr;
     c->sorted_inc = nullptr;
+    c->sampled_inc = nullptr;
+    c->fwd_serial = 0;
     c->sorted_keys = nullptr;
     c->prof_ev = nullptr;
     c->prof_tag = nullptr;
@@ -404,6 +413,7 @@ stx_status stx_spmm(stx_ctx *ctx, const stx_incidence *inc, const stx_params *p,
     stx_status s = check_built(ctx, inc);
     if (s != STX_OK) return s;
     if (!p || !p->ent || !c_out) return STX_ERR_NULL;
+    if ((s = check_a_current(ctx, inc)) != STX_OK) return s;
     return launch_spmm(ctx, inc, p, c_out);
 }
 
@@ -415,6 +425,7 @@ stx_status stx_spmm_semiring(stx_ctx *ctx, const stx_incidence *inc, const stx_p
     if (!p || !p->ent || !z_out) return STX_ERR_NULL;
     if (kind < STX_DISTMULT || kind > STX_ROTATE) return STX_ERR_BAD_ARG;
     if (!stacked(ctx)) return STX_ERR_UNSUPPORTED;
+    if ((s = check_a_current(ctx, inc)) != STX_OK) return s;
     return launch_semiring(ctx, inc, p, kind, z_out);
 }
 
@@ -428,6 +439,7 @@ stx_status stx_spmm_semiring_t(stx_ctx *ctx, const stx_incidence *inc, const stx
     if (kind < STX_DISTMULT || kind > STX_ROTATE) return STX_ERR_BAD_ARG;
     if (((uintptr_t)gz & 15u) || ((uintptr_t)work & 15u)) return STX_ERR_BAD_ARG;
     if (!stacked(ctx)) return STX_ERR_UNSUPPORTED;
+    if ((s = check_a_current(ctx, inc)) != STX_OK) return s;
     return launch_semiring_t(ctx, inc, p, kind, gz, work, g->rows);
 }
 
@@ -443,6 +455,7 @@ stx_status stx_spmm_semiring_t_static(stx_ctx *ctx, const stx_incidence *inc, co
     if (!stacked(ctx)) return STX_ERR_UNSUPPORTED;
     if ((uint64_t)inc->n_rows * 3u * (uint64_t)ctx->cfg.dim * sizeof(float) > (uint64_t)STX_STATIC_WORK_BYTES)
         return STX_ERR_STATIC_LIMIT;
+    if ((s = check_a_current(ctx, inc)) != STX_OK) return s;
     float *work = nullptr;
     s = static_work(&work);
     if (s != STX_OK) return s;
@@ -474,7 +487,9 @@ stx_status stx_rank(stx_ctx *ctx, const stx_params *p, const int32_t *h, const i
     return launch_rank(ctx, p, h, r, t, nq, side, true_score, n_less, n_equal, work);
 }
 
-stx_status stx_forward(stx_ctx *ctx, const stx_incidence *inc, const stx_params *p, float *scores, float *loss)
+// The forward pass; from_step: called by stx_train_step, whose own launches keep A and A^T paired.
+static stx_status run_forward(stx_ctx *ctx, const stx_incidence *inc, const stx_params *p, float *scores, float *loss,
+                              bool from_step)
 {
     if (!ctx) return STX_ERR_NULL;
     stx_status s = check_built(ctx, inc);
@@ -482,6 +497,7 @@ stx_status stx_forward(stx_ctx *ctx, const stx_incidence *inc, const stx_params 
     s = check_params(ctx, p);
     if (s != STX_OK) return s;
     if (!scores || !loss) return STX_ERR_NULL;
+    if (!from_step && (s = check_a_current(ctx, inc)) != STX_OK) return s;
     if (stacked(ctx)) s = launch_forward_stacked(ctx, inc, p, scores, loss);
     else if (ctx->cfg.model == STX_TRANSH) s = launch_forward_transh(ctx, inc, p, scores, loss);
     else {   // TransR: y = M_r (h - t) + r on the matrix cores, then distances / hinge / dL/dy over the rows of y
@@ -496,6 +512,11 @@ stx_status stx_forward(stx_ctx *ctx, const stx_incidence *inc, const stx_params 
         ctx->fwd_rows = inc->n_rows;
     }
     return s;
+}
+
+stx_status stx_forward(stx_ctx *ctx, const stx_incidence *inc, const stx_params *p, float *scores, float *loss)
+{
+    return run_forward(ctx, inc, p, scores, loss, false);
 }
 
 // The backward pass.  lr == nullptr: gradients go to g.  Otherwise the update is applied where a
@@ -636,7 +657,7 @@ stx_status stx_train_step(stx_ctx *ctx, const stx_batch *bt, stx_incidence *inc,
         // the sum of the loss rides in the backward pass's first launch: TransR's row products take it along, and
         // so does a transposed product that takes the build's last kernel along
         ctx->defer_finish = ctx->cfg.model == STX_TRANSR || ctx->segw.armed;
-        s = stx_forward(ctx, inc, p, scores, loss);
+        s = run_forward(ctx, inc, p, scores, loss, true);
         ctx->defer_finish = false;
     } else {   // the forward pass shared a launch with the sort; the sum of the loss may still be missing
         if (!fusion.finish_done) {
@@ -671,6 +692,15 @@ stx_status stx_copy_f32(stx_ctx *ctx, float *dst, const float *src, int64_t n)
     if (!ctx || !dst || !src) return STX_ERR_NULL;
     if (n < 0 || n % 4 != 0 || ((uintptr_t)dst & 15u) || ((uintptr_t)src & 15u)) return STX_ERR_BAD_ARG;
     return launch_copy_f32(ctx, dst, src, n);
+}
+
+stx_status stx_read_sectors(stx_ctx *ctx, const void *src, int64_t n_slots, int32_t slot_bytes, int64_t n_reads,
+                            float *sink)
+{
+    if (!ctx || !src || !sink) return STX_ERR_NULL;
+    if (n_slots <= 0 || n_reads < 0 || slot_bytes < 32 || slot_bytes % 16 != 0 || ((uintptr_t)src & 15u))
+        return STX_ERR_BAD_ARG;
+    return launch_read_sectors(ctx, src, n_slots, slot_bytes, n_reads, sink);
 }
 
 const char *stx_status_string(stx_status s)

@@ -698,14 +698,6 @@ __global__ __launch_bounds__(kThreads) void k_sgd_rows(const int32_t *__restrict
 }
 
 // ---- dispatch --------------------------------------------------------------------------------------
-// Tables beyond the reach of the last-level cache: their updated rows are stored past the caches.  Rows of a
-// small table are read again by the next step's forward pass, which runs measurably faster when the
-// update leaves them cached (TransH at 15,000 entities: 30 against 37 microseconds).
-static int big_tables(const stx_ctx *c)
-{
-    return (c->cfg.n_ent + c->cfg.n_rel) * (int64_t)c->cfg.dim * 4 > ((int64_t)128 << 20) ? 1 : 0;
-}
-
 template <int LPR, int ITERS>
 static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_t e_end, const float *src_a,
                    const float *src_b, int32_t split, int ld_src, int width, float *out_rows, int ld_out,

@@ -245,6 +245,7 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
     if (c->segw.armed) launch_seg_write_late(c);   // (a build whose last kernel nobody took along)
     c->sorted_inc = nullptr;
     c->sorted_keys = nullptr;
+    c->sampled_inc = sample ? inc : nullptr;   // negatives drawn here keep the relation and one entity of their positive
     c->cnt_inc = nullptr;
     c->cnt_ptr = nullptr;
     c->prep_inc = nullptr;

@@ -37,10 +37,20 @@ __global__ __launch_bounds__(kThreads) void k_finish_loss(const float *__restric
     finish_loss_body(partials, n, scale, loss);
 }
 
+// general_flag (may be null): the kernel runs only if *general_flag == serial, i.e. if the fast kernel before it met
+// a positive whose negatives it does not cover; it then redoes the whole batch (the same bits where both apply).
 template <int LPR, int ITERS, int DIST, bool FROM_Y, bool PACKED>
-__global__ __launch_bounds__(kThreads, ITERS == 1 ? 8 : 1) void k_forward_stacked(ForwardArgs a)
+__global__ __launch_bounds__(kThreads, ITERS == 1 ? 8 : 1) void k_forward_stacked(ForwardArgs a, const int32_t *general_flag,
+                                                                                 int32_t serial)
 {
+    if (general_flag && *general_flag != serial) return;
     forward_stacked_body<LPR, ITERS, DIST, FROM_Y, PACKED>((int)blockIdx.x, a);
+}
+
+template <int LPR, int DIST, bool PACKED, int NB>
+__global__ __launch_bounds__(kThreads, 8) void k_forward_fast(ForwardArgs a, int32_t *general_flag, int32_t serial)
+{
+    forward_fast_body<LPR, DIST, PACKED, NB>((int)blockIdx.x, a, general_flag, serial);
 }
 
 // TransR in stx_train_step: the first kernel of the next batch's build (which also counts the rows per relation)
@@ -66,6 +76,33 @@ stx_status launch_copy_f32(stx_ctx *c, float *dst, const float *src, int64_t n)
     int64_t n4 = n / 4, blocks = (n4 + kThreads - 1) / kThreads;
     if (blocks > 16384) blocks = 16384;
     hipLaunchKernelGGL(k_copy_f32, dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, dst, src, n4);
+    return hip_ok(hipGetLastError());
+}
+
+// Scattered reads of known volume: thread i reads the 32 bytes at the start of slot (i * 40503) mod n_slots (an
+// odd multiplier, so a power-of-two number of slots is visited once each when n_reads == n_slots), `slot_bytes`
+// apart: like the sign records the transposed product fetches, one memory sector per lane with no two lanes of a
+// wavefront in one line when slot_bytes >= 128.  The sums go to `sink` so that the loads are kept.
+__global__ __launch_bounds__(kThreads) void k_read_sectors(const char *__restrict__ src, int64_t n_slots, int slot_bytes,
+                                                           int64_t n_reads, float *__restrict__ sink)
+{
+    float acc = 0.f;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n_reads; i += (int64_t)gridDim.x * kThreads) {
+        const int64_t slot = (i * 40503) % n_slots;
+        const float *q = reinterpret_cast<const float *>(src + slot * slot_bytes);
+        const float4 a = ld4(q), b = ld4(q + 4);
+        acc += (a.x + a.y + a.z + a.w) + (b.x + b.y + b.z + b.w);
+    }
+    if (acc == 12345.678f) sink[blockIdx.x] = acc;   // practically never: the loads must only be kept
+}
+
+stx_status launch_read_sectors(stx_ctx *c, const void *src, int64_t n_slots, int slot_bytes, int64_t n_reads, float *sink)
+{
+    if (n_reads == 0) return STX_OK;
+    int64_t blocks = (n_reads + kThreads - 1) / kThreads;
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL(k_read_sectors, dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, static_cast<const char *>(src),
+                       n_slots, slot_bytes, n_reads, sink);
     return hip_ok(hipGetLastError());
 }
 
@@ -111,31 +148,68 @@ static void forward_go(stx_ctx *c, const stx_incidence *inc, const stx_params *p
     dim3 grid((unsigned)((inc->b + GROUPS - 1) / GROUPS));
     const ForwardArgs fa{inc->a_colidx, p->ent, inc->b, inc->k, width, c->cfg.margin, scale, scores, c->gbuf[0],
                          packed_stride(c->cfg.dim), c->loss_partials, from_y ? nullptr : p->rel_weight,
-                         (int32_t)c->cfg.n_ent};
+                         (int32_t)c->cfg.n_ent, from_y ? 0 : big_tables(c)};
     // (the next batch's first build kernel, if one is due and counts rows per relation as TransR's do)
     EmitAhead ea{};
     if (from_y && c->ahead.armed && !c->ahead.emit_done && c->ahead.args.rc.cur) ea = take_emit_ahead(c);
     const dim3 grid_e(grid.x + (unsigned)ea.ntiles);
+    // Rows of one float4 per lane and few negatives per positive: the kernel that fetches the positive's rows once
+    // (forward_fast_body).  It covers negatives that keep the relation and one entity of their positive; when the
+    // batch was not drawn by the library's sampler in this build, the general kernel is enqueued behind it and runs
+    // only if the fast one met another kind of negative.
+    bool fast = false;
+    if constexpr (ITERS == 1) fast = !from_y && inc->k <= fast_negatives<LPR>();
+    const bool sampled = c->sampled_inc == inc;
+    int32_t *flag = c->ctrl + CTRL_GENERAL;
+    const int32_t serial = fast ? ++c->fwd_serial : 0;
 #define STX_FWD(D, Y, P)                                                                                        \
-    hipLaunchKernelGGL((k_forward_stacked<LPR, ITERS, D, Y, P>), grid, dim3(kThreads), 0, c->stream, fa)
+    hipLaunchKernelGGL((k_forward_stacked<LPR, ITERS, D, Y, P>), grid, dim3(kThreads), 0, c->stream, fa,        \
+                       fast ? flag : nullptr, serial)
+#define STX_FAST(D, P)                                                                                          \
+    do {                                                                                                        \
+        if constexpr (ITERS == 1) {                                                                             \
+            if (inc->k <= 1)                                                                                    \
+                hipLaunchKernelGGL((k_forward_fast<LPR, D, P, 1>), grid, dim3(kThreads), 0, c->stream, fa, flag, serial); \
+            else                                                                                                \
+                hipLaunchKernelGGL((k_forward_fast<LPR, D, P, fast_negatives<LPR>()>), grid, dim3(kThreads), 0, c->stream, \
+                                   fa, flag, serial);                                                           \
+        }                                                                                                       \
+    } while (0)
 #define STX_FWD2(D)                                                                                             \
     do {                                                                                                        \
         if (from_y && ea.ntiles)                                                                                \
             hipLaunchKernelGGL((k_forward_y_emit<LPR, ITERS, D>), grid_e, dim3(kThreads), 0, c->stream, fa, ea); \
         else if (from_y) STX_FWD(D, true, false);                                                               \
-        else if (is_sign_kind(D)) STX_FWD(D, false, is_sign_kind(D));                                           \
-        else STX_FWD(D, false, false);                                                                          \
+        else {                                                                                                  \
+            if (fast) {                                                                                         \
+                ProfScope prof(c, "k_forward_stacked");                                                         \
+                STX_FAST(D, is_sign_kind(D));                                                                   \
+            }                                                                                                   \
+            if (!fast || !sampled) {                                                                            \
+                ProfScope prof(c, fast ? "k_forward_general" : "k_forward_stacked");                            \
+                STX_FWD(D, false, is_sign_kind(D));                                                             \
+            }                                                                                                   \
+        }                                                                                                       \
     } while (0)
-    {
-    ProfScope prof(c, "k_forward_stacked");
-    switch (c->cfg.dist) {
-    case STX_L1: STX_FWD2(STX_L1); break;
-    case STX_L2: STX_FWD2(STX_L2); break;
-    case STX_TORUS_L1: STX_FWD2(STX_TORUS_L1); break;
-    case STX_L2_SQ: STX_FWD2(STX_L2_SQ); break;
-    default: STX_FWD2(STX_TORUS_L2); break;
+    if (from_y) {
+        ProfScope prof(c, "k_forward_stacked");
+        switch (c->cfg.dist) {
+        case STX_L1: STX_FWD2(STX_L1); break;
+        case STX_L2: STX_FWD2(STX_L2); break;
+        case STX_TORUS_L1: STX_FWD2(STX_TORUS_L1); break;
+        case STX_L2_SQ: STX_FWD2(STX_L2_SQ); break;
+        default: STX_FWD2(STX_TORUS_L2); break;
+        }
+    } else {
+        switch (c->cfg.dist) {
+        case STX_L1: STX_FWD2(STX_L1); break;
+        case STX_L2: STX_FWD2(STX_L2); break;
+        case STX_TORUS_L1: STX_FWD2(STX_TORUS_L1); break;
+        case STX_L2_SQ: STX_FWD2(STX_L2_SQ); break;
+        default: STX_FWD2(STX_TORUS_L2); break;
+        }
     }
-    }
+#undef STX_FAST
 #undef STX_FWD2
 #undef STX_FWD
     if (c->defer_finish) { c->fin_n = (int)grid.x; c->fin_scale = scale; c->fin_loss = loss; }

@@ -68,6 +68,103 @@ __device__ inline void finish_loss_body(const float *__restrict__ partials, int 
     if (tid == 0) loss[0] = (float)(s_acc[0] * (double)scale);
 }
 
+// The forward step for batches whose negatives come from the sampler (Sec. 5.3: every negative keeps the relation
+// and one entity of its positive), rows of one float4 per lane, at most NB negatives per positive.  One group per
+// positive: its lanes fetch the 3 + 3k column ids in ONE load (lane s < 3: id s of the positive; lane 3 + 3q + s: id
+// s of negative q) and share them by shuffles; then the positive's three rows and the ONE row in which each negative
+// differs are requested together (3 + k table rows instead of 3 + 3k), so a wavefront pays two dependent memory
+// round trips in all.  x is formed by the same two roundings in the same order as a full gather would: the bits
+// are those of forward_stacked_body.  A group that finds another kind of negative (a caller's own) does nothing
+// and stores `serial` in *general_flag: the caller then runs the general kernel over those groups.
+template <int LPR, int DIST, bool PACKED, int NB>
+__device__ inline void forward_fast_body(const int block, const ForwardArgs &a, int32_t *general_flag, int32_t serial)
+{
+    static_assert(LPR >= 3 + 3 * NB, "one lane per column id");
+    const int32_t *__restrict__ colidx = a.colidx;
+    const float *__restrict__ X = a.X;
+    const int32_t b = a.b, k = a.k;
+    const int dim = a.dim, gstride = a.gstride;
+    float *__restrict__ scores = a.scores;
+    constexpr int GROUPS = kThreads / LPR;
+    __shared__ float s_loss[GROUPS];
+    const int lig = threadIdx.x % LPR, grp = threadIdx.x / LPR;
+    const int32_t i = block * GROUPS + grp;
+    float hinge_sum = 0.f;
+    if (i < b) {
+        const int32_t row0 = b + i * k;
+        int32_t mine = 0;
+        if (lig < 3 + 3 * k) mine = colidx[lig < 3 ? 3 * (int64_t)i + lig : 3 * (int64_t)row0 + (lig - 3)];
+        const int32_t c0 = __shfl(mine, 0, LPR), c1 = __shfl(mine, 1, LPR), c2 = __shfl(mine, 2, LPR);
+        int32_t ce[NB];
+        unsigned tail_mask = 0;
+        bool shared = true;
+#pragma unroll
+        for (int q = 0; q < NB; ++q) {
+            const int32_t nh = __shfl(mine, 3 + 3 * q, LPR), nr = __shfl(mine, 4 + 3 * q, LPR), nt = __shfl(mine, 5 + 3 * q, LPR);
+            const bool ts = nh == c0;
+            ce[q] = ts ? nt : nh;
+            tail_mask |= ts ? 1u << q : 0u;
+            if (q < k) shared = shared && nr == c1 && (ts || nt == c2);
+        }
+        if (shared) {
+            const float wr = a.rel_weight ? a.rel_weight[c1 - a.n_ent] : 1.0f;
+            // (lanes past the row's width hold zeros and take part in the reductions only)
+            const bool in_row = lig < dim / 4;
+            const float *xl = X + 4 * lig;
+            const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+            float4 hr = in_row ? ld4(xl + (int64_t)c0 * dim) : zero;
+            const float4 pr = in_row ? ld4(xl + (int64_t)c1 * dim) : zero, pt = in_row ? ld4(xl + (int64_t)c2 * dim) : zero;
+            float4 e[NB];
+#pragma unroll
+            for (int q = 0; q < NB; ++q)
+                if (q < k) {
+                    // a row used once does not displace the others when the table is far larger than the caches
+                    e[q] = !in_row ? zero : a.stream_rows ? ld4_stream(xl + (int64_t)ce[q] * dim) : ld4(xl + (int64_t)ce[q] * dim);
+                }
+            hr = add4(hr, pr);
+            RowVec<1> x;
+            x.v[0] = sub4(hr, pt);
+            const float npos = row_distance<LPR, 1, DIST>(x);
+            const float dpos = wr * npos;
+            if (lig == 0) scores[i] = dpos;
+            uint8_t *recs = reinterpret_cast<uint8_t *>(a.G);
+            float *gcoef = PACKED ? reinterpret_cast<float *>(recs + packed_coef_offset((int64_t)b * (1 + k), gstride)) : nullptr;
+            int n_active = 0;
+            const RowVec<1> xp = x;
+#pragma unroll
+            for (int q = 0; q < NB; ++q)
+                if (q < k) {
+                    x.v[0] = (tail_mask >> q & 1u) ? sub4(hr, e[q]) : sub4(add4(e[q], pr), pt);
+                    const float nneg = row_distance<LPR, 1, DIST>(x);
+                    const float dneg = wr * nneg;
+                    const float arg = (a.margin + dpos) - dneg;
+                    const bool active = arg > 0.f;
+                    const int32_t row = row0 + q;
+                    if (lig == 0) scores[row] = dneg;
+                    if (active) { hinge_sum += arg; ++n_active; }
+                    if (PACKED)
+                        write_grad_row_packed<LPR, 1, DIST>(recs, gstride, gcoef, row, dim / 4, lig, x, active ? -a.scale * wr : 0.f);
+                    else
+                        write_grad_row<LPR, 1, DIST>(a.G + (int64_t)row * dim, dim / 4, lig, x, active ? -a.scale * wr : 0.f, nneg);
+                }
+            if (PACKED)
+                write_grad_row_packed<LPR, 1, DIST>(recs, gstride, gcoef, i, dim / 4, lig, xp, (float)n_active * a.scale * wr);
+            else
+                write_grad_row<LPR, 1, DIST>(a.G + (int64_t)i * dim, dim / 4, lig, xp, (float)n_active * a.scale * wr, npos);
+        } else if (lig == 0 && general_flag) {
+            *general_flag = serial;
+        }
+    }
+    if (lig == 0) s_loss[grp] = hinge_sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float sum = 0.f;
+#pragma unroll
+        for (int g = 0; g < GROUPS; ++g) sum += s_loss[g];
+        a.loss_partials[block] = sum;
+    }
+}
+
 // One group per positive i: rows i and b + i*k + kk (kk < k).
 // FROM_Y = false: the translated vector of a row is gathered from the stacked table X (TransE/TorusE).
 // FROM_Y = true : it is row `row` of the dense buffer G (TransR: y = M_r (h - t) + r was put there by
@@ -171,6 +268,29 @@ __device__ inline void forward_stacked_body(const int block, const ForwardArgs &
 #pragma unroll
         for (int g = 0; g < GROUPS; ++g) sum += s_loss[g];
         loss_partials[block] = sum;
+    }
+}
+
+}  // namespace stx
+
+namespace stx {
+
+// Most negatives per positive that forward_fast_body takes with groups of LPR lanes (one lane per column id).
+template <int LPR>
+constexpr int fast_negatives() { return LPR >= 16 ? 4 : 1; }
+
+// The forward step inside the launches of stx_train_step, whose negatives are the sampler's: the fast body where the
+// row width and the number of negatives allow it.  K1: the launch was chosen for at most one negative per positive.
+template <int LPR, int ITERS, int DIST, bool PACKED, bool K1>
+__device__ inline void forward_step_body(const int block, const ForwardArgs &fa)
+{
+    if constexpr (ITERS == 1 && K1) {
+        forward_fast_body<LPR, DIST, PACKED, 1>(block, fa, nullptr, 0);
+    } else if constexpr (ITERS == 1 && LPR >= 16) {
+        if (fa.k <= 4) forward_fast_body<LPR, DIST, PACKED, 4>(block, fa, nullptr, 0);
+        else forward_stacked_body<LPR, ITERS, DIST, false, PACKED, K1>(block, fa);
+    } else {
+        forward_stacked_body<LPR, ITERS, DIST, false, PACKED, K1>(block, fa);
     }
 }
 

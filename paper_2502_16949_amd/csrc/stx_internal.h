@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "stx.h"
+#include "stx_measure.h"
 
 namespace stx {
 
@@ -25,7 +26,7 @@ constexpr int kProjRows = 64;           // TransR: entries of one relation per w
 constexpr int kProjRowsDm = 256;        // ... and per work item of the product that forms dL/dM_r
 
 // Slots of the control block at the start of the workspace (int32 each).
-enum { CTRL_BAD_INDEX = 0, CTRL_WORDS = 64 };
+enum { CTRL_BAD_INDEX = 0, CTRL_GENERAL = 1 /* see k_forward_fast */, CTRL_WORDS = 64 };
 
 struct Launch {            // how a row of `width` floats maps onto lanes
     int lpr;               // lanes per row: power of two in 8..64
@@ -195,6 +196,8 @@ struct stx_ctx {
     // host-side call-order state
     const stx_incidence *sorted_inc;   // incidence of the last build, whose sorted keys are still in keys[]
     const int32_t *sorted_keys;
+    const stx_incidence *sampled_inc;  // incidence whose negatives the library's sampler drew inside its build, or null
+    int32_t fwd_serial;            // number of the last forward pass that used the fast kernel (never 0 once used)
     const stx_incidence *fwd_inc;  // incidence of the last stx_forward, null if none
     int64_t fwd_rows;
     stx::EmitAheadState ahead;
@@ -215,6 +218,7 @@ struct ForwardArgs {
     float *loss_partials;
     const float *rel_weight;   // fixed weight of every relation's distance, or null (gathered rows only)
     int32_t n_ent;
+    int32_t stream_rows;       // the table is far larger than the caches: rows used once are fetched past them
 };
 
 
@@ -278,6 +282,7 @@ stx_status launch_clear_rel_counts(stx_ctx *);
 stx_status launch_spmm(stx_ctx *, const stx_incidence *, const stx_params *, float *c_out);
 stx_status launch_forward_stacked(stx_ctx *, const stx_incidence *, const stx_params *, float *scores, float *loss);
 stx_status launch_copy_f32(stx_ctx *, float *dst, const float *src, int64_t n);
+stx_status launch_read_sectors(stx_ctx *, const void *src, int64_t n_slots, int slot_bytes, int64_t n_reads, float *sink);
 // stx_backward.hip
 // out_rows[segment] = signed sum of source rows over the sorted entries [e_begin, e_end); entries
 // before `split` read src_a, the others src_b (both with ld_src floats per row, `width` of them used).
@@ -354,6 +359,15 @@ inline int packed_stride(int dim)
 }
 // byte offset of the coefficient array from the start of the records of a batch of `rows` rows
 __host__ __device__ inline int64_t packed_coef_offset(int64_t rows, int stride) { return (rows * stride + 255) / 256 * 256; }
+
+// Tables beyond the reach of the last-level cache: their updated rows are stored past the caches, and rows the
+// forward pass uses once are fetched past them.  Rows of a small table are read again by the next step's forward
+// pass, which runs measurably faster when the update leaves them cached (TransH at 15,000 entities: 30 against 37
+// microseconds).
+inline int big_tables(const stx_ctx *c)
+{
+    return (c->cfg.n_ent + c->cfg.n_rel) * (int64_t)c->cfg.dim * 4 > ((int64_t)128 << 20) ? 1 : 0;
+}
 
 inline stx_status hip_ok(hipError_t e) { return e == hipSuccess ? STX_OK : STX_ERR_HIP; }
 

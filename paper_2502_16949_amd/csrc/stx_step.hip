@@ -33,7 +33,7 @@ __global__ __launch_bounds__(kThreads) void k_fwd_scatter(ForwardArgs fa, Scatte
         if (block < ea.ntiles) { emit_body<kSortItems, true, true, false, true>(block, ea.ntiles, ea.args, s_arena); return; }
         block -= ea.ntiles;
     }
-    forward_stacked_body<LPR, ITERS, DIST, false, PACKED, K1>(block, fa);
+    forward_step_body<LPR, ITERS, DIST, PACKED, K1>(block, fa);
 }
 
 template <int LPR, int ITERS, int DIST, bool FIRST, bool K1>
@@ -72,7 +72,7 @@ __global__ __launch_bounds__(kThreads) void k_fwd_hist(ForwardArgs fa, const int
     if (block < ntiles) { hist_body<kSortItems>(block, keys, nnz, shift, radix, table); return; }
     block -= ntiles;
     if (block < ea.ntiles) { emit_body<kSortItems, true, true, false, true>(block, ea.ntiles, ea.args, s_arena); return; }
-    forward_stacked_body<LPR, ITERS, DIST, false, PACKED>(block - ea.ntiles, fa);
+    forward_step_body<LPR, ITERS, DIST, PACKED, false>(block - ea.ntiles, fa);
 }
 
 template <int LPR, int ITERS, int DIST>

@@ -139,6 +139,27 @@ def test_training_step_matches_oracle(model, dist, n_ent, n_rel, b, k, dim, zipf
     _check_step(wl, tabs, bt, model, dim, reduce)
 
 
+@pytest.mark.parametrize("model,dist,dim,k", [("transe", "l1", 128, 1), ("transe", "l2", 128, 4), ("toruse", "torus_l1", 64, 3),
+                                              ("transe", "l2", 32, 1), ("transe", "l1", 256, 2)])
+def test_negatives_of_the_callers_own_choice(model, dist, dim, k):
+    """Negatives need not be the sampler's: here most replace BOTH entities of their positive (some keep one, some
+    equal it), which the kernel that fetches a positive's rows once for its negatives does not cover: the general
+    kernel behind it must take over, for the whole batch."""
+    wl, tabs, bt = _problem(model, dist, 500, 7, 700, k, dim, seed=dim + k, zipf=1.1)
+    rng = np.random.default_rng(dim)
+    nh = rng.integers(0, wl.n_ent, bt.b * k).astype(np.int32)
+    nt = rng.integers(0, wl.n_ent, bt.b * k).astype(np.int32)
+    keep = rng.random(bt.b * k)
+    nh = np.where(keep < 0.2, np.repeat(bt.h, k), nh).astype(np.int32)          # a fifth keep the head, ...
+    nt = np.where(keep > 0.9, np.repeat(bt.t, k), nt).astype(np.int32)          # ... a tenth the tail
+    bt2 = stxo.Batch(bt.h, bt.r, bt.t, nh, nt)
+    _check_step(wl, tabs, bt2, model, dim, B.STX_SUM)
+    # and a batch in which a single negative is of that kind
+    nh3, nt3 = bt.nh.copy(), bt.nt.copy()
+    nh3[5], nt3[5] = (bt.h[5 // k] + 1) % wl.n_ent, (bt.t[5 // k] + 1) % wl.n_ent
+    _check_step(wl, tabs, stxo.Batch(bt.h, bt.r, bt.t, nh3, nt3), model, dim, B.STX_MEAN)
+
+
 @pytest.mark.parametrize("model,dist,dim", [("transe", "l1", 128), ("transe", "l2", 128), ("transe", "l2_sq", 64),
                                             ("toruse", "torus_l2", 128), ("toruse", "torus_l1", 256)])
 def test_relation_weights_match_oracle(model, dist, dim):

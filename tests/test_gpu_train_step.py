@@ -258,3 +258,34 @@ def test_random_chains_of_linked_steps_give_the_same_bits(model, dist, n_ent, n_
             ta, tb = getattr(ma.params, name), getattr(mb.params, name)
             assert (ta is None and tb is None) or torch.equal(ta, tb), (s, name)
     assert B.stx_check_indices(ma.ctx) == 0 and B.stx_check_indices(mb.ctx) == 0
+
+
+def test_calls_that_read_A_are_refused_while_it_holds_the_next_batch():
+    """After a step that named its next batch, the A arrays of inc are the next batch's and the A^T arrays this
+    batch's: stx_forward / stx_spmm / the semiring products on that inc return STX_ERR_STATE until it is built
+    again; a step that did not name a batch leaves inc whole."""
+    wl = W.Workload("case", 12, "transe", "l1", 1000, 20, 3000, 128, 128, 1000, 1, 1.0, 0.01, 1, 1.1, 1.1)
+    tabs = W.make_tables(wl)
+    h, r, t = W.make_graph(wl)
+    hd, rd, td = G.dev_i32(h), G.dev_i32(r), G.dev_i32(t)
+    m = G.GpuModel(wl, tabs)
+    neg = [tuple(torch.zeros(1000, dtype=torch.int32, device=G.DEV) for _ in range(2)) for _ in range(3)]
+    bts = B.link_batches([B.make_batch(hd[lo:lo + 1000], rd[lo:lo + 1000], td[lo:lo + 1000], 1, 5, 0, 3000, lo, *neg[i])
+                          for i, lo in enumerate((0, 1000, 2000))])
+    out = torch.empty(2000, 128, dtype=torch.float32, device=G.DEV)
+    B.stx_train_step(m.ctx, bts[0], m.inc, m.params, None, 0.01, m.scores, m.loss)
+    for call in (lambda: m.forward(), lambda: B.stx_spmm(m.ctx, m.inc, m.params, out),
+                 lambda: B.stx_spmm_semiring(m.ctx, m.inc, m.params, B.STX_DISTMULT, out)):
+        with pytest.raises(B.StxError) as e:
+            call()
+        assert e.value.status == B.STX_ERR_STATE
+    B.stx_train_step(m.ctx, bts[1], m.inc, m.params, None, 0.01, m.scores, m.loss)
+    B.stx_train_step(m.ctx, bts[2], m.inc, m.params, None, 0.01, m.scores, m.loss)   # names no batch
+    B.stx_spmm(m.ctx, m.inc, m.params, out)
+    m.forward()
+    torch.cuda.synchronize()
+    want = (tabs_after := m.params.ent.cpu().numpy())
+    hh = np.concatenate([h[2000:], neg[2][0].cpu().numpy()]); tt = np.concatenate([t[2000:], neg[2][1].cpu().numpy()])
+    rr = np.concatenate([r[2000:], r[2000:]])
+    x = (want[hh] + want[wl.n_ent + rr]) - want[tt]
+    assert np.array_equal(out.cpu().numpy(), x)

@@ -12,7 +12,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared():
-    src = open(os.path.join(ROOT, "include", "stx.h")).read()
+    src = "".join(open(os.path.join(ROOT, "include", f)).read() for f in ("stx.h", "stx_measure.h"))
     return sorted(set(re.findall(r"\b(stx_[a-z0-9_]+)\s*\(", src)))
 
 
