@@ -54,6 +54,10 @@ Layout make_layout(const stx_config *c)
     L.ntiles_max = (int)((L.nnz_max + kSortTile - 1) / kSortTile);
     Launch rl = row_launch(c->dim);
     L.fwd_blocks_max = (int)((c->max_batch + (kThreads / rl.lpr) - 1) / (kThreads / rl.lpr));
+    if (c->model == STX_TRANSR) {   // one loss partial per row item of the fused forward kernel
+        const int64_t items = L.rows_max / kProjRows + (L.rows_max < c->n_rel ? L.rows_max : c->n_rel) + 1;
+        if (items > L.fwd_blocks_max) L.fwd_blocks_max = (int)items;
+    }
     int64_t ncol = c->n_ent + c->n_rel;
     L.sort_bits = 1;
     while (((int64_t)1 << L.sort_bits) < ncol) ++L.sort_bits;
@@ -207,6 +211,10 @@ stx_status stx_create(const stx_config *cfg, void *workspace, size_t workspace_b
     c->cnt_ptr = nullptr;
     c->cnt_inc = nullptr;
     c->prep_inc = nullptr;
+    c->prep_whole = 0;
+    c->tr_fused_inc = nullptr;
+    c->step_colidx = nullptr;
+    c->step_colidx_inc = nullptr;
     c->defer_finish = false;
     c->fin_n = 0;
     c->fin_scale = 1.0f;
@@ -502,7 +510,9 @@ static stx_status run_forward(stx_ctx *ctx, const stx_incidence *inc, const stx_
     else if (ctx->cfg.model == STX_TRANSH) s = launch_forward_transh(ctx, inc, p, scores, loss);
     else {   // TransR: y = M_r (h - t) + r on the matrix cores, then distances / hinge / dL/dy over the rows of y
         if (inc->n_rows == 0) s = launch_finish_loss(ctx, 0, 1.0f, loss);
-        else {
+        else if (transr_fused_ok(ctx, inc)) {
+            s = launch_transr_fused(ctx, inc, p, scores, loss);
+        } else {
             s = launch_transr_project(ctx, inc, p);
             if (s == STX_OK) s = launch_forward_from_y(ctx, inc, p, scores, loss);
         }

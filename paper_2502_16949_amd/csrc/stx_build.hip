@@ -249,6 +249,7 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
     c->cnt_inc = nullptr;
     c->cnt_ptr = nullptr;
     c->prep_inc = nullptr;
+    c->tr_fused_inc = nullptr;
     // the first kernels may already have run, in launches of the previous step
     const EmitAheadState prev = c->ahead;
     clear_ahead(c);
@@ -287,6 +288,8 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
         // that takes the next batch's first kernel along)
     }
     if (fusion) fusion->colidx = colidx2;
+    c->step_colidx = fusion ? colidx2 : nullptr;
+    c->step_colidx_inc = inc;
 
     int bits0 = c->sort_bits < c->digit_bits ? c->sort_bits : c->digit_bits;
     const bool use_rc = c->rel_cnt[0] != nullptr;

@@ -181,6 +181,10 @@ struct stx_ctx {
     const int32_t *cnt_ptr;        // counts of the last build ...
     const stx_incidence *cnt_inc;  // ... which was of this incidence
     const stx_incidence *prep_inc; // incidence whose TransR preparation already ran beside its sort
+    int prep_whole;                // ... with row items that name whole lists (k_transr_fused) or 64-entry pieces
+    const stx_incidence *tr_fused_inc;   // incidence whose forward pass was k_transr_fused (dL/dx and the tiles exist)
+    const int32_t *step_colidx;    // stx_train_step: the context's own copy of this batch's column ids, or null ...
+    const stx_incidence *step_colidx_inc;   // ... of this incidence
     // stx_train_step: the final sum of the loss is not launched by the forward pass but rides in the first
     // launch of the backward pass (nothing in between needs it), when that launch can take it along
     bool defer_finish;
@@ -333,6 +337,9 @@ stx_status launch_semiring_t(stx_ctx *, const stx_incidence *, const stx_params 
 stx_status static_work(float **out);
 // stx_transr.hip
 stx_status launch_transr_project(stx_ctx *, const stx_incidence *, const stx_params *);
+// the forward pass, dL/dy, dL/dx and the tiles of the dM product in one kernel, for the shapes transr_fused_ok names
+bool transr_fused_ok(const stx_ctx *, const stx_incidence *);
+stx_status launch_transr_fused(stx_ctx *, const stx_incidence *, const stx_params *, float *scores, float *loss);
 // fused_lr: if not null, M_r <- M_r - lr * dL/dM_r is applied in place of the store of dL/dM_r (g may be null)
 stx_status launch_transr_backward(stx_ctx *, const stx_incidence *, const stx_params *, stx_grads *,
                                   const float *fused_lr = nullptr);

@@ -28,6 +28,7 @@
 // product, reduction over d; rows = output columns of GX, reduction over k) and for the transposed
 // tiles X^T and GY^T (rows = columns of x / gy, reduction over the 64 entries of an item) which the
 // row kernels leave behind for the dM product while they have the tile in LDS anyway.
+#include "stx_emit_body.h"
 #include "stx_forward_body.h"
 #include "stx_sort_body.h"
 
@@ -69,6 +70,7 @@ struct PrepArgs {
     const int32_t *rel_cnt;
     int32_t n_rel;
     int nplan;                   // workgroups that build the item lists (the others convert one M_r each)
+    int whole_lists;             // row items name their relation's whole list and their index in it (k_transr_fused)
 };
 
 // Item lists of the relation segments (one workgroup).  Row item: {relation, first sorted entry,
@@ -165,7 +167,8 @@ __device__ inline void transr_plan(const int block, const PrepArgs &p)
                 if (s_o64[mid] <= w) lo = mid; else hi = mid;
             }
             const int32_t li = w - s_o64[lo];
-            p.items[base64 + w] = make_int4(s_rel[lo], s_beg[lo] + 64 * li, min(64, s_len[lo] - 64 * li), 0);
+            p.items[base64 + w] = p.whole_lists ? make_int4(s_rel[lo], s_beg[lo], s_len[lo], li)
+                                                : make_int4(s_rel[lo], s_beg[lo] + 64 * li, min(64, s_len[lo] - 64 * li), 0);
         }
         for (int32_t w = tid; w < t256; w += kThreads) {
             int lo = 0, hi = kThreads;
@@ -429,6 +432,242 @@ __global__ __launch_bounds__(kThreads) void k_transr_rows(RowsArgs p, const floa
     }
 }
 
+struct FusedArgs {
+    const int4 *items;
+    const int32_t *counts;       // [0] = number of row items
+    const int32_t *colidx, *packed;
+    const int32_t *pay;          // the sort's payloads (3*row + slot) in place of `packed`, or null
+    const float *E, *Rv;
+    const uint16_t *Mf, *Mg;     // operand-order copies of M_r: forward (rows a, reduction over j), GX (rows j, reduction over a)
+    uint16_t *xt, *gyt;          // per item: the transposed 64-entry tiles of x and of dL/dy for the dM product
+    float *gy, *gx;              // rows x k: dL/dy;  rows x d: dL/dx
+    float *scores, *loss_partials;
+    int d, k;
+    int32_t kneg;                // negatives per positive; 1 + kneg divides 64
+    float margin, scale;
+};
+
+// TransR, both widths <= 128 and 1 + kneg a divisor of 64: the whole of a row's way through the model in one
+// kernel (Sec. 4.4 forward, the distance and hinge of Sec. 5.3, and the first backward product).  A work item is up
+// to 64 / (1 + kneg) positives of one relation TOGETHER WITH their negatives, which keep the relation and
+// therefore sit in the same list of the sorted A^T (positives first, in row order, then their negatives in the
+// same order), so the hinge of every pair is decided inside the workgroup:
+//   x = E[h] - E[t] staged as bfloat16, stored transposed for the dM product;  Y = X M_r^T + r on the matrix cores;
+//   distances of the 64 rows of Y from LDS;  hinge, coefficients, scores, the item's share of the loss;
+//   dL/dy to memory (dL/dr sums it per relation) and, as bfloat16, back into LDS and transposed to memory;
+//   dL/dx = dL/dy M_r on the matrix cores, to memory for the transposed product over the entity columns.
+// Tile slots: positives 0 .. P'-1, then negative kk of positive i at P' + i*kneg + kk.
+// The first workgroups of the launch may run the first kernel of the next batch's build (ea.ntiles > 0), which
+// overwrites the caller's A arrays: the launcher lets it ride only when p.colidx is the context's own copy of this
+// batch's column ids.
+template <int DIST>
+__global__ __launch_bounds__(kThreads, 3) void k_transr_fused(FusedArgs p, EmitAhead ea)
+{
+    constexpr int kW = 128;
+    __shared__ __attribute__((aligned(16))) uint16_t s_a[64 * (kW + kLdsPad)];
+    __shared__ __attribute__((aligned(16))) float s_y[64 * (kW + 4)];
+    __shared__ int32_t s_row[64], s_h[64], s_t[64];
+    __shared__ float s_dist[64], s_cs[64];
+    static_assert(sizeof(float) * 64 * (kW + 4) >= (size_t)emit_lds(true, true), "the rider's arrays fit the tile of y");
+    const int tid = threadIdx.x;
+    int block = (int)blockIdx.x;
+    if (block < ea.ntiles) {
+        emit_body<kSortItems, true, true, true, true>(block, ea.ntiles, ea.args, reinterpret_cast<unsigned char *>(s_y));
+        return;
+    }
+    block -= ea.ntiles;
+    const int4 item = p.items[block];                     // the list is allocated for the launch bound
+    if (block >= p.counts[0]) {
+        if (tid == 0) p.loss_partials[block] = 0.f;
+        return;
+    }
+    const int rel = item.x, seg_begin = item.y, len = item.z, li = item.w;
+    const int rpp = 1 + p.kneg, P = 64 / rpp, n_pos = len / rpp, p0 = li * P;
+    const int Pn = min(P, n_pos - p0), count = Pn * rpp;
+    const int l = tid & 63, w = tid >> 6, wr = w >> 1, wc = w & 1, l31 = l & 31, kg = l >> 5;
+    const int d = p.d, k = p.k;
+    // ---- forward fragments of M_r, requested before the gather so that their latency hides behind it
+    const int ntl_f = k >> 5, ntw_f = (ntl_f - wc + 1) >> 1, KS_f = d >> 4;
+    const uint16_t *Mf = p.Mf + (int64_t)rel * d * k;
+    uint4 bpre[8][2];
+    if (32 * wr < count) {
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+                if (ks < KS_f && q < ntw_f) bpre[ks][q] = ld16(Mf + ((int64_t)(ks * ntl_f + wc + 2 * q) * 64 + l) * 8);
+        }
+    }
+    if (tid < 64) {
+        int32_t row = -1, hh = 0, tt = 0;
+        if (tid < count) {
+            const int e = tid < Pn ? seg_begin + p0 + tid
+                                   : seg_begin + n_pos + (p0 + (tid - Pn) / p.kneg) * p.kneg + (tid - Pn) % p.kneg;
+            row = p.pay ? p.pay[e] / 3 : p.packed[e] >> 2;
+            hh = p.colidx[3 * row]; tt = p.colidx[3 * row + 2];
+        }
+        s_row[tid] = row; s_h[tid] = hh; s_t[tid] = tt;
+    }
+    __syncthreads();
+    // ---- x = E[h] - E[t] of the 64 slots as bfloat16 (slots past `count` are zero)
+    {
+        const int stride = d + kLdsPad, q4 = d >> 2, total = 64 * q4;
+        for (int g0 = tid; g0 < total; g0 += 8 * kThreads) {
+            float4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int g = g0 + u * kThreads;
+                v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (g < total) {
+                    const int i = g / q4, c4 = 4 * (g - i * q4);
+                    if (i < count) v[u] = sub4(ld4(p.E + (int64_t)s_h[i] * d + c4), ld4(p.E + (int64_t)s_t[i] * d + c4));
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int g = g0 + u * kThreads;
+                if (g < total) {
+                    const int i = g / q4, c4 = 4 * (g - i * q4);
+                    *reinterpret_cast<uint2 *>(s_a + i * stride + c4) = make_uint2(pack2(v[u].x, v[u].y), pack2(v[u].z, v[u].w));
+                }
+            }
+        }
+    }
+    __syncthreads();
+    // ---- a tile of 64 slots, transposed into operand order for the dM product
+    auto put_transposed = [&](uint16_t *tiles, int width) {
+        const int stride = width + kLdsPad, rt = width >> 5, pieces = ((count + 15) >> 4) * rt * 64;
+        uint16_t *tile = tiles + (int64_t)block * 64 * width;
+        for (int pc = tid; pc < pieces; pc += kThreads) {
+            const int ll = pc & 63, blk = pc >> 6, ks = blk / rt, mt = blk - ks * rt;
+            const uint16_t *src = s_a + (16 * ks + 8 * (ll >> 5)) * stride + 32 * mt + (ll & 31);
+            uint4 o;
+            o.x = (uint32_t)src[0] | (uint32_t)src[stride] << 16;
+            o.y = (uint32_t)src[2 * stride] | (uint32_t)src[3 * stride] << 16;
+            o.z = (uint32_t)src[4 * stride] | (uint32_t)src[5 * stride] << 16;
+            o.w = (uint32_t)src[6 * stride] | (uint32_t)src[7 * stride] << 16;
+            *reinterpret_cast<uint4 *>(tile + (int64_t)pc * 8) = o;
+        }
+    };
+    put_transposed(p.xt, d);
+    // ---- Y = X M_r^T + r: wavefront w takes rows 32*(w/2).. and the column tiles w%2, w%2 + 2
+    constexpr int kYS = kW + 4;                            // floats per row of the tile of y
+    if (32 * wr < count) {
+        const uint16_t *arow = s_a + (32 * wr + l31) * (d + kLdsPad) + 8 * kg;
+        floatx16 acc[2] = {zero16(), zero16()};
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            if (ks < KS_f) {
+                const uint4 a = *reinterpret_cast<const uint4 *>(arow + 16 * ks);
+#pragma unroll
+                for (int q = 0; q < 2; ++q)
+                    if (q < ntw_f)
+                        acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(a), as_frag(bpre[ks][q]), acc[q], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            if (q < ntw_f) {
+                const int n = (wc + 2 * q) * 32 + l31;
+                const float add = p.Rv[(int64_t)rel * k + n];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) s_y[(32 * wr + 8 * (v >> 2) + 4 * kg + (v & 3)) * kYS + n] = acc[q][v] + add;
+            }
+        }
+    }
+    __syncthreads();
+    // ---- the GX fragments of M_r: requested now, used after the distances and the hinge
+    const int ntl_g = d >> 5, ntw_g = (ntl_g - wc + 1) >> 1, KS_g = k >> 4;
+    const uint16_t *Mg = p.Mg + (int64_t)rel * d * k;
+    if (32 * wr < count) {
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+                if (ks < KS_g && q < ntw_g) bpre[ks][q] = ld16(Mg + ((int64_t)(ks * ntl_g + wc + 2 * q) * 64 + l) * 8);
+        }
+    }
+    // ---- distances: four lanes per slot, each over every fourth element, added across the four
+    {
+        const int slot = tid >> 2, c = tid & 3;
+        float acc = 0.f;
+        if (slot < count)
+            for (int n = c; n < k; n += 4) acc += term<DIST>(s_y[slot * kYS + n]);
+        acc += __shfl_xor(acc, 1);
+        acc += __shfl_xor(acc, 2);
+        if (c == 0) s_dist[slot] = slot < count ? finish<DIST>(acc) : 0.f;
+    }
+    __syncthreads();
+    // ---- hinge of every (positive, negative) pair of the item; coefficient of every slot; scores; loss share
+    if (tid < 64) {
+        float hs = 0.f;
+        if (tid < Pn) {
+            const float dpos = s_dist[tid];
+            int n_active = 0;
+            for (int kk = 0; kk < p.kneg; ++kk) {
+                const int ns = Pn + tid * p.kneg + kk;
+                const float dneg = s_dist[ns];
+                const float arg = (p.margin + dpos) - dneg;
+                const bool active = arg > 0.f;
+                if (active) { hs += arg; ++n_active; }
+                s_cs[ns] = coef_scale<DIST>(active ? -p.scale : 0.f, dneg);
+                p.scores[s_row[ns]] = dneg;
+            }
+            s_cs[tid] = coef_scale<DIST>((float)n_active * p.scale, dpos);
+            p.scores[s_row[tid]] = dpos;
+        } else if (tid >= count) {
+            s_cs[tid] = 0.f;
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) hs += __shfl_xor(hs, off);
+        if (tid == 0) p.loss_partials[block] = hs;
+    }
+    __syncthreads();
+    // ---- dL/dy: to memory in fp32, and as bfloat16 into the operand tile (the products over x are done with it)
+    {
+        const int stride = k + kLdsPad, q4 = k >> 2, total = 64 * q4;
+        for (int g = tid; g < total; g += kThreads) {
+            const int i = g / q4, c4 = 4 * (g - i * q4);
+            float4 gy = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (i < count) {
+                const float4 y = *reinterpret_cast<const float4 *>(s_y + i * kYS + c4);
+                const float cs = s_cs[i];
+                gy = make_float4(dterm<DIST>(y.x, cs), dterm<DIST>(y.y, cs), dterm<DIST>(y.z, cs), dterm<DIST>(y.w, cs));
+                st4(p.gy + (int64_t)s_row[i] * k + c4, gy);
+            }
+            *reinterpret_cast<uint2 *>(s_a + i * stride + c4) = make_uint2(pack2(gy.x, gy.y), pack2(gy.z, gy.w));
+        }
+    }
+    __syncthreads();
+    put_transposed(p.gyt, k);
+    // ---- dL/dx = dL/dy M_r
+    if (32 * wr < count) {
+        const uint16_t *arow = s_a + (32 * wr + l31) * (k + kLdsPad) + 8 * kg;
+        floatx16 acc[2] = {zero16(), zero16()};
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            if (ks < KS_g) {
+                const uint4 a = *reinterpret_cast<const uint4 *>(arow + 16 * ks);
+#pragma unroll
+                for (int q = 0; q < 2; ++q)
+                    if (q < ntw_g)
+                        acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(a), as_frag(bpre[ks][q]), acc[q], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            if (q < ntw_g) {
+                const int n = (wc + 2 * q) * 32 + l31;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int32_t row_m = s_row[32 * wr + 8 * (v >> 2) + 4 * kg + (v & 3)];
+                    if (row_m >= 0) p.gx[(int64_t)row_m * d + n] = acc[q][v];
+                }
+            }
+        }
+    }
+}
+
 struct DmArgs {
     const int4 *dm_items;
     const int32_t *counts;       // [1] = number of dM items
@@ -438,6 +677,11 @@ struct DmArgs {
     float *M;                    // fused update: M_r <- M_r - lr * dL/dM_r replaces the store of dL/dM_r
     float lr;
     int fused;
+    int n_items;                 // workgroups (blockIdx.x) that are dM items; one more may follow:
+    const float *fin_partials;   // a deferred final sum of the loss that the launch takes along (fin_n == 0: none)
+    int fin_n;
+    float fin_scale;
+    float *fin_loss;
 };
 
 // dL/dM_r = sum over the rows i of relation r of bf16(gy_i) bf16(x_i)^T, x_i = E[h_i] - E[t_i].
@@ -448,6 +692,10 @@ struct DmArgs {
 // matrix into its slot and k_transr_dm_fixup adds the slots in order.
 __global__ __launch_bounds__(kThreads) void k_transr_dm(DmArgs p)
 {
+    if ((int)blockIdx.x >= p.n_items) {                   // the extra workgroup(s) of the launch
+        if (blockIdx.y == 0 && p.fin_n > 0) finish_loss_body(p.fin_partials, p.fin_n, p.fin_scale, p.fin_loss);
+        return;
+    }
     const int4 it = p.dm_items[2 * blockIdx.x];           // readable for every workgroup of the launch bound
     if ((int32_t)blockIdx.x >= p.counts[1]) return;
     const int rel = it.x, tile0 = it.y, entries = it.z, slot = it.w;
@@ -636,26 +884,29 @@ static PrepArgs prep_args(stx_ctx *c, const stx_incidence *inc, const stx_params
     a.n_rel = (int32_t)c->cfg.n_rel;
     const int64_t lists = inc->n_rows < c->cfg.n_rel ? inc->n_rows : c->cfg.n_rel;   // most touched relations
     a.nplan = (int)(((a.rel_cnt ? c->cfg.n_rel : lists) + kThreads - 1) / kThreads);
+    a.whole_lists = 0;
     return a;
 }
 
 bool launch_prep_scatter(stx_ctx *c, const stx_incidence *inc, const stx_params *p, const ScatterArgs &sa, bool first)
 {
     if (c->cfg.model != STX_TRANSR || inc->n_rows == 0) return false;
-    const PrepArgs a = prep_args(c, inc, p);
+    PrepArgs a = prep_args(c, inc, p);
     if (!a.rel_cnt) return false;
+    a.whole_lists = transr_fused_ok(c, inc) ? 1 : 0;      // (stx_train_step runs the forward pass this prepares)
     ProfScope prof(c, "k_prep_scatter");
     const dim3 grid((unsigned)(sa.ntiles + c->cfg.n_rel + a.nplan));
     if (first) hipLaunchKernelGGL(k_prep_scatter<true>, grid, dim3(kThreads), 0, c->stream, a, sa);
     else hipLaunchKernelGGL(k_prep_scatter<false>, grid, dim3(kThreads), 0, c->stream, a, sa);
     c->prep_inc = inc;
+    c->prep_whole = a.whole_lists;
     return true;
 }
 
 stx_status launch_transr_project(stx_ctx *c, const stx_incidence *inc, const stx_params *p)
 {
     if (inc->n_rows == 0) return STX_OK;
-    if (c->prep_inc != inc) {   // not yet prepared beside the sort
+    if (c->prep_inc != inc || c->prep_whole != 0) {   // not yet prepared beside the sort
         launch_seg_write_late(c);   // (the segment lists may be needed)
         const PrepArgs a = prep_args(c, inc, p);
         ProfScope prof(c, "k_transr_prepare");
@@ -675,11 +926,64 @@ stx_status launch_transr_project(stx_ctx *c, const stx_incidence *inc, const stx
     return hip_ok(hipGetLastError());
 }
 
+// Which batches k_transr_fused takes: both widths at most 128 and whole positives with their negatives per 64-slot tile.
+bool transr_fused_ok(const stx_ctx *c, const stx_incidence *inc)
+{
+    return c->cfg.model == STX_TRANSR && c->cfg.dim <= 128 && c->cfg.rel_dim <= 128 && inc->k < 64 && 64 % (1 + inc->k) == 0;
+}
+
+stx_status launch_transr_fused(stx_ctx *c, const stx_incidence *inc, const stx_params *p, float *scores, float *loss)
+{
+    float scale = 1.0f;
+    if (c->cfg.reduce == STX_MEAN && inc->k > 0) scale = 1.0f / (float)((int64_t)inc->b * inc->k);
+    if (c->prep_inc != inc || c->prep_whole != 1) {   // not yet prepared beside the sort
+        launch_seg_write_late(c);   // (the segment lists may be needed)
+        PrepArgs a = prep_args(c, inc, p);
+        a.whole_lists = 1;
+        ProfScope prof(c, "k_transr_prepare");
+        if (a.rel_cnt)
+            hipLaunchKernelGGL(k_transr_prepare<true>, dim3((unsigned)(c->cfg.n_rel + a.nplan)), dim3(kThreads), 0, c->stream, a);
+        else
+            hipLaunchKernelGGL(k_transr_prepare<false>, dim3((unsigned)(c->cfg.n_rel + a.nplan)), dim3(kThreads), 0, c->stream, a);
+    }
+    c->prep_inc = nullptr;      // the copies of M_r are good for this forward pass only: the update changes M_r
+    FusedArgs a;
+    a.items = (const int4 *)c->tr_items; a.counts = c->tr_counts;
+    const bool own_ids = c->step_colidx && c->step_colidx_inc == inc;
+    a.colidx = own_ids ? c->step_colidx : inc->a_colidx;
+    a.packed = inc->at_packed;
+    a.pay = (c->segw.armed && c->sorted_inc == inc) ? c->segw.args.pay : nullptr;
+    a.E = p->ent; a.Rv = p->rel; a.Mf = c->tr_m16; a.Mg = c->tr_m16t;
+    a.xt = c->tr_xt; a.gyt = c->tr_gyt;
+    a.gy = c->gbuf[0]; a.gx = c->gbuf[1];
+    a.scores = scores; a.loss_partials = c->loss_partials;
+    a.d = c->cfg.dim; a.k = c->cfg.rel_dim; a.kneg = inc->k;
+    a.margin = c->cfg.margin; a.scale = scale;
+    EmitAhead ea{};
+    if (own_ids && c->ahead.armed && !c->ahead.emit_done && c->ahead.args.rc.cur) ea = take_emit_ahead(c);
+    const unsigned items = row_items_max(c, inc->n_rows);
+    const dim3 grid(items + (unsigned)ea.ntiles);
+    {
+        ProfScope prof(c, "k_transr_fused");
+        switch (c->cfg.dist) {
+        case STX_L1: hipLaunchKernelGGL(k_transr_fused<STX_L1>, grid, dim3(kThreads), 0, c->stream, a, ea); break;
+        case STX_L2: hipLaunchKernelGGL(k_transr_fused<STX_L2>, grid, dim3(kThreads), 0, c->stream, a, ea); break;
+        case STX_TORUS_L1: hipLaunchKernelGGL(k_transr_fused<STX_TORUS_L1>, grid, dim3(kThreads), 0, c->stream, a, ea); break;
+        case STX_L2_SQ: hipLaunchKernelGGL(k_transr_fused<STX_L2_SQ>, grid, dim3(kThreads), 0, c->stream, a, ea); break;
+        default: hipLaunchKernelGGL(k_transr_fused<STX_TORUS_L2>, grid, dim3(kThreads), 0, c->stream, a, ea); break;
+        }
+    }
+    c->tr_fused_inc = inc;
+    if (c->defer_finish) { c->fin_n = (int)items; c->fin_scale = scale; c->fin_loss = loss; return hip_ok(hipGetLastError()); }
+    return launch_finish_loss(c, (int)items, scale, loss);
+}
+
 stx_status launch_transr_backward(stx_ctx *c, const stx_incidence *inc, const stx_params *p, stx_grads *g,
                                   const float *fused_lr)
 {
     if (inc->n_rows == 0) return STX_OK;
-    {
+    const bool fused_rows = c->tr_fused_inc == inc;       // the forward kernel already formed dL/dx and the tiles
+    if (!fused_rows) {
         RowsArgs ra = rows_args(c, inc, p, true);
         unsigned blocks = row_items_max(c, inc->n_rows);
         if (c->fin_n > 0) {
@@ -702,9 +1006,15 @@ stx_status launch_transr_backward(stx_ctx *c, const stx_incidence *inc, const st
     a.d = c->cfg.dim; a.k = c->cfg.rel_dim;
     a.M = p->proj; a.lr = fused_lr ? *fused_lr : 0.f; a.fused = fused_lr ? 1 : 0;
     const unsigned items = dm_items_max(c, inc->n_rows);
+    a.n_items = (int)items;
+    a.fin_partials = nullptr; a.fin_n = 0; a.fin_scale = 1.0f; a.fin_loss = nullptr;
+    if (c->fin_n > 0) {   // a deferred sum of the loss: one more workgroup
+        a.fin_partials = c->loss_partials; a.fin_n = c->fin_n; a.fin_scale = c->fin_scale; a.fin_loss = c->fin_loss;
+        c->fin_n = 0;
+    }
     {
         ProfScope prof(c, "k_transr_dm");
-        hipLaunchKernelGGL(k_transr_dm, dim3(items, (unsigned)(((a.k + 127) / 128) * ((a.d + 127) / 128))),
+        hipLaunchKernelGGL(k_transr_dm, dim3(items + (a.fin_n > 0 ? 1u : 0u), (unsigned)(((a.k + 127) / 128) * ((a.d + 127) / 128))),
                            dim3(kThreads), 0, c->stream, a);
     }
     if (inc->n_rows > kProjRowsDm) {                      // otherwise no relation can have two items

@@ -48,8 +48,13 @@ def run_rank(wl, X, h, r, t, side, max_batch=8):
     return ctx, ts.cpu().numpy()[:nq], less.cpu().numpy()[:nq], equal.cpu().numpy()[:nq]
 
 
-def check_counts(ts, less, equal, ref, tol):
+def check_counts(ts, less, equal, ref, tol, what=None):
+    """what: a name under which the share of these queries whose counts the band decides (another candidate than
+    the true entity sits in it) and the largest band, as a share of the candidates, go on record (G.USAGE)."""
     ref_ts, ref_less, ref_band = ref
+    if what is not None:
+        G.USAGE.append((what + ": share of queries with another candidate in the band", float((ref_band > 1).mean())))
+        G.USAGE.append((what + ": mean band size", float(ref_band.mean())))
     np.testing.assert_allclose(ts, ref_ts, rtol=tol, atol=0)
     assert np.all(equal >= 1), "the true entity ties with itself"
     assert np.all(less >= ref_less), int((less < ref_less).sum())
@@ -176,7 +181,7 @@ def test_rank_full_size(name, nq, n_sample):
         assert np.all(np.isfinite(ts)) and np.all(ts >= 0)
         assert np.all(equal >= 1) and np.all(less >= 0) and np.all(less.astype(np.int64) + equal <= wl.n_ent)
         ref = stxo.rank(oracle_config(wl), X, h[pick], r[pick], t[pick], oside, tol=tol)
-        check_counts(ts[pick], less[pick], equal[pick], ref, tol)
+        check_counts(ts[pick], less[pick], equal[pick], ref, tol, what=f"rank {name} full size")
         hits[side] = float((1 + less <= 10).mean())
     # identical (h, r, t) queries give identical counts wherever they sit in the launch
     key = h.astype(np.int64) * (wl.n_rel + 1) * (wl.n_ent + 1) + r.astype(np.int64) * (wl.n_ent + 1) + t
@@ -262,7 +267,7 @@ def test_rank_transh_full_size():
         assert np.all(np.isfinite(ts)) and np.all(equal >= 1) and np.all(less.astype(np.int64) + equal <= wl.n_ent)
         extra = transh_abs_tol(tabs, h[pick], r[pick], t[pick], side, wl.dim)
         ref = stxo.rank(oracle_config(wl), ot, h[pick], r[pick], t[pick], oside, tol=tol, abs_tol=extra)
-        check_counts(ts[pick], less[pick], equal[pick], ref, 4 * tol)
+        check_counts(ts[pick], less[pick], equal[pick], ref, 4 * tol, what="rank transh full size")
 
 
 # ------------------------------------------------------------------------------------------ TransR
@@ -356,7 +361,7 @@ def test_rank_transr_full_size_and_workspace_errors():
         assert np.all(np.isfinite(ts)) and np.all(equal >= 1) and np.all(less.astype(np.int64) + equal <= wl.n_ent)
         extra = transr_abs_tol(tabs, h[pick], r[pick], t[pick], side, wl.dim)
         ref = stxo.rank(oracle_config(wl, bf16=False), ot, h[pick], r[pick], t[pick], oside, tol=tol, abs_tol=extra)
-        check_counts(ts[pick], less[pick], equal[pick], ref, 4 * tol)
+        check_counts(ts[pick], less[pick], equal[pick], ref, 4 * tol, what="rank transr full size")
     # a missing or short work buffer is refused before anything is launched
     m = G.GpuModel(_wl_r("l2", 50, 3, 32, 32), W.make_tables(_wl_r("l2", 50, 3, 32, 32)), flags=B.STX_FLAG_BF16_PROJ)
     z = G.dev_i32(np.zeros(3, np.int32))
