@@ -24,19 +24,20 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
-TRANSR_PRODUCTS = ("k_transr_project", "k_transr_gx", "k_transr_dm")
+# kernels that run TransR products on the matrix cores, and how many products of 2*rows*d*k flops each runs
+TRANSR_PRODUCTS = {"k_transr_fused": 2, "k_transr_project": 1, "k_transr_gx": 1, "k_transr_dm": 1}
 
 # The kernel whose roofline is reported: the one with the largest share of GPU time in the
 # rocprofv3 kernel trace of the same command (profiles/).
 DOMINANT = {"mid": "k_seg_reduce", "tiny": "k_seg_reduce", "toruse": "k_seg_reduce", "transh": "k_seg_reduce",
-            "transr": "k_transr_project", "paper_transe": "k_seg_reduce", "paper_toruse": "k_seg_reduce",
-            "paper_transr": "k_transr_project"}
+            "transr": "k_transr_fused", "paper_transe": "k_seg_reduce", "paper_toruse": "k_seg_reduce",
+            "paper_transr": "k_transr_fused"}
 # ... without the look-ahead (--no-lookahead) the forward pass and the first scatter pass share the longest launch
 DOMINANT_PLAIN = dict(DOMINANT, mid="k_fwd_scatter", tiny="k_fwd_scatter")
 # ... and when the step is made of the separate calls (--api fused | separate)
 DOMINANT_CALLS = {"mid": "k_seg_reduce", "tiny": "k_seg_reduce", "toruse": "k_seg_reduce", "transh": "k_forward_transh",
-                  "transr": "k_transr_project", "paper_transe": "k_seg_reduce", "paper_toruse": "k_seg_reduce",
-                  "paper_transr": "k_transr_project"}
+                  "transr": "k_transr_fused", "paper_transe": "k_seg_reduce", "paper_toruse": "k_seg_reduce",
+                  "paper_transr": "k_transr_fused"}
 
 
 # HBM bytes per launch of those kernels, measured: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (separate runs),
@@ -169,6 +170,10 @@ def kernel_work(wl, kernel, rows, touched, fused=False, rides=False, segw=False)
     # the ridge (2.5 PFLOP/s / 8 TB/s = 312 flop per byte): their roofline is the memory one.  Bytes: the gathered
     # fp32 rows, the fp32 rows written, the bf16 transposed tiles, and the bf16 copy of M_r once per relation.
     nrel = min(wl.n_rel, rows)
+    if kernel == "k_transr_fused":     # forward product, distances, hinge and GX product on one staged tile:
+        # h and t rows and 12 B of ids in; dL/dy row, dL/dx row, both bf16 tiles and the score out; both copies of M_r
+        return (rows * (2 * row + 12 + 4 * wl.rel_dim + row + 2 * wl.dim + 2 * wl.rel_dim + 4)
+                + nrel * 4 * wl.dim * wl.rel_dim), "GB/s", "hbm", HBM_PEAK_GBS
     if kernel == "k_transr_project":   # h and t rows, 12 B of ids, y row out, x tile out
         return rows * (2 * row + 12 + 4 * wl.rel_dim + 2 * wl.dim) + nrel * 2 * wl.dim * wl.rel_dim, "GB/s", "hbm", HBM_PEAK_GBS
     if kernel == "k_transr_gx":        # dL/dy row in, dL/dx row out, dL/dy tile out
@@ -680,7 +685,7 @@ def main():
                             ", counted")
     if kernel in TRANSR_PRODUCTS and kernel_us > 0:
         # the same launch priced as a contraction, against the dense bf16 matrix-core peak
-        tf = 2.0 * mean_rows * wl.dim * wl.rel_dim / (kernel_us * 1e-6) / 1e12
+        tf = TRANSR_PRODUCTS[kernel] * 2.0 * mean_rows * wl.dim * wl.rel_dim / (kernel_us * 1e-6) / 1e12
         roofline["mfma"] = {"achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                             "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
                             "counters": "profiles/transr_kernel_trace.txt (matrix-core busy cycles and operations from rocprofv3 --pmc)"}
