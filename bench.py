@@ -45,25 +45,23 @@ DOMINANT_CALLS = {"mid": "k_seg_reduce", "tiny": "k_seg_reduce", "toruse": "k_se
 # x1.0); the runs and their numbers are in profiles/<workload>_kernel_trace.txt and profiles/copy_calibration.txt.
 # A different kernel (--kernel) or workload has no measured figure here and reports null.
 # Keys: (workload, kernel, fused step or not).
-TRAFFIC_BYTES = {("mid", "k_fwd_scatter", True): 26.10e6 + 7.33e6,
-                 ("mid", "k_seg_reduce", True): 28.19e6 + 8.47e6,
-                 ("transh", "k_seg_reduce", True): 140.49e6 + 9.29e6,
-                 ("transh", "k_fwdh_scatter", True): 32.45e6 + 101.56e6,
-                 ("transr", "k_transr_project", True): 28.28e6 + 25.11e6,
-                 ("transr", "k_transr_project", False): 28.28e6 + 25.11e6,
-                 ("toruse", "k_seg_reduce", True): 1165.6e6 + 623.2e6,
-                 ("toruse", "k_forward_stacked", True): 701.8e6 + 53.6e6,
-                 ("toruse", "k_forward_stacked", False): 701.8e6 + 53.6e6,
+TRAFFIC_BYTES = {("toruse", "k_seg_reduce", True): 1165.49e6 + 623.17e6,
+                 ("toruse", "k_forward_stacked", True): 693.53e6 + 53.52e6,
+                 ("toruse", "k_forward_stacked", False): 693.55e6 + 53.52e6,
+                 ("toruse", "k_seg_reduce", False): 561.81e6 + 532.18e6,
+                 ("toruse", "k_sgd_rows", False): 1056.93e6 + 526.37e6,
                  # mean of the two batches of an epoch (393,216 and 89,926 positives), like the timed mean
                  ("paper_transe", "k_seg_reduce", True): (9761.85e6 + 104.19e6 + 2281.04e6 + 99.90e6) / 2,
                  # with the look-ahead (the next batch's first build kernels ride in these launches)
-                 ("mid", "k_seg_reduce", "rides"): 28.03e6 + 17.01e6,
-                 ("mid", "k_fwd_scatter", "rides"): 27.48e6 + 9.24e6,
-                 ("mid", "k_seg_fixup", "rides"): 3.62e6 + 0.42e6,
-                 ("transh", "k_seg_reduce", "rides"): 142.21e6 + 14.78e6,
-                 ("transh", "k_fwdh_scatter", "rides"): 33.72e6 + 105.21e6,
-                 ("transh", "k_seg_fixup", "rides"): 4.01e6 + 0.48e6,
-                 ("transr", "k_transr_project", "rides"): 28.35e6 + 25.11e6,
+                 ("mid", "k_seg_reduce", "rides"): 28.04e6 + 17.01e6,
+                 ("mid", "k_fwd_scatter", "rides"): 27.44e6 + 9.25e6,
+                 ("mid", "k_seg_fixup", "rides"): 3.67e6 + 0.42e6,
+                 ("transh", "k_seg_reduce", "rides"): 142.54e6 + 14.81e6,
+                 ("transh", "k_fwdh_scatter", "rides"): 34.67e6 + 105.22e6,
+                 ("transh", "k_seg_fixup", "rides"): 4.06e6 + 0.48e6,
+                 ("transr", "k_transr_fused", "rides"): 40.20e6 + 52.83e6,
+                 ("transr", "k_transr_dm", "rides"): 31.90e6 + 21.21e6,
+                 ("transr", "k_seg_reduce", "rides"): 56.33e6 + 9.05e6,
                  # the other modes (profiles/semiring_complex_*_kernel_trace.txt, profiles/rank_mid_kernel_trace.txt)
                  ("semiring complex", "mid", "k_semiring_terms"): 66.64e6 + 100.66e6,
                  ("semiring complex", "toruse", "k_semiring_terms"): 1560.16e6 + 2013.27e6}
