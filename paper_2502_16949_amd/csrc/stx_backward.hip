@@ -79,6 +79,16 @@ __device__ inline void load_row(const float *__restrict__ p, int d4, int lig, Ac
         a.v[it] = j < d4 ? ld4(p + 4 * j) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
 }
+// ... of a table far larger than the caches, read once and rewritten: fetched past them
+template <int LPR, int ITERS>
+__device__ inline void load_row_stream(const float *__restrict__ p, int d4, int lig, Acc<ITERS> &a)
+{
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        int j = lig + it * LPR;
+        a.v[it] = j < d4 ? ld4_stream(p + 4 * j) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+}
 template <int LPR, int ITERS>
 __device__ inline void store_row_stream(float *__restrict__ p, int d4, int lig, const Acc<ITERS> &a)
 {
@@ -357,7 +367,10 @@ __global__ __launch_bounds__(kThreads, (ITERS == 1 && PACKED && FUSED && RIDE !=
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t row = (uint32_t)mu[u] >> 2;
                 if constexpr (FUSED) {   // a run begins here: its table row comes along with its first source row
-                    if (mu[u] & 2) load_row<LPR, ITERS>(fused_row(fu, cu[u], ld_tab), d4, lig, xr[u]);
+                    if (mu[u] & 2) {   // (a row of a table beyond the caches is read once here and rewritten: past them)
+                        if (fu.stream) load_row_stream<LPR, ITERS>(fused_row(fu, cu[u], ld_tab), d4, lig, xr[u]);
+                        else load_row<LPR, ITERS>(fused_row(fu, cu[u], ld_tab), d4, lig, xr[u]);
+                    }
                 }
                 if constexpr (PACKED) {
                     // (records of 1 << pk_sh bytes: a shift and an add give the address)
@@ -543,7 +556,10 @@ __global__ __launch_bounds__(kThreads) void k_seg_fixup(const int32_t *__restric
     const int n = j - j0 + 1;                                   // partial rows: (j0, slot 1), (j0+1 .. j, slot 0)
     Acc<ITERS> xrow;                                            // FUSED: the table row, fetched beside the partial rows
     xrow.zero();
-    if (FUSED && grp == 0) load_row<LPR, ITERS>(fused_row(fu, col, ld_tab), d4, lig, xrow);
+    if (FUSED && grp == 0) {
+        if (fu.stream) load_row_stream<LPR, ITERS>(fused_row(fu, col, ld_tab), d4, lig, xrow);
+        else load_row<LPR, ITERS>(fused_row(fu, col, ld_tab), d4, lig, xrow);
+    }
     const int per = (n + GROUPS - 1) / GROUPS;
     const int lo = min(grp * per, n), hi = min(lo + per, n);
     Acc<ITERS> acc;
@@ -645,7 +661,8 @@ __global__ __launch_bounds__(kThreads) void k_sgd_rows(const int32_t *__restrict
             Acc<ITERS> x[UB], g[UB];
 #pragma unroll
             for (int u = 0; u < UB; ++u) {
-                load_row<LPR, ITERS>(table_a + (int64_t)col[u] * d4_a * 4, d4_a, lig, x[u]);
+                if (stream) load_row_stream<LPR, ITERS>(table_a + (int64_t)col[u] * d4_a * 4, d4_a, lig, x[u]);
+                else load_row<LPR, ITERS>(table_a + (int64_t)col[u] * d4_a * 4, d4_a, lig, x[u]);
                 const float *pg = grad_rows + min(s0 + u, (int64_t)U - 1) * ld;
 #pragma unroll
                 for (int it = 0; it < ITERS; ++it) {
