@@ -45,11 +45,7 @@ __device__ inline void gather_row(const float *__restrict__ X, int dim, int d4, 
     for (int it = 0; it < ITERS; ++it) {
         int j = lig + it * LPR;
         if (j < d4) {
-#ifdef STX_NT_ALL
-            float4 a = ld4_stream(p0 + 4 * j), c = ld4_stream(p2 + 4 * j);
-#else
             float4 a = ld4(p0 + 4 * j), c = ld4(p2 + 4 * j);
-#endif
             if (HRT) {
                 float4 b = ld4(p1 + 4 * j);
                 a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
