@@ -213,6 +213,7 @@ stx_status stx_create(const stx_config *cfg, void *workspace, size_t workspace_b
     c->prep_inc = nullptr;
     c->prep_whole = 0;
     c->tr_fused_inc = nullptr;
+    c->dm_ride = DmRideState{};
     c->step_colidx = nullptr;
     c->step_colidx_inc = nullptr;
     c->defer_finish = false;
@@ -559,14 +560,19 @@ static stx_status run_backward(stx_ctx *ctx, const stx_incidence *inc, const stx
     // and relation columns sum gy (width rel_dim)
     stx_status s = launch_transr_backward(ctx, inc, p, g, lr);
     if (s != STX_OK) return s;
-    if (dim == ctx->cfg.rel_dim)   // rows of equal width: one product over all columns, as for TransH
-        return launch_seg_reduce(ctx, inc, 0, inc->nnz, ctx->gbuf[1], ctx->gbuf[0], ent_end, dim, dim, rows, ctx->ld,
-                                 false, lr ? &fh : nullptr);
-    s = launch_seg_reduce(ctx, inc, 0, ent_end, ctx->gbuf[1], ctx->gbuf[1], ent_end, dim, dim, rows, ctx->ld, false,
-                          lr ? &fh : nullptr);
+    // (the first of these launches takes the dL/dM_r product along or launches it)
+    if (dim == ctx->cfg.rel_dim) {   // rows of equal width: one product over all columns, as for TransH
+        s = launch_seg_reduce(ctx, inc, 0, inc->nnz, ctx->gbuf[1], ctx->gbuf[0], ent_end, dim, dim, rows, ctx->ld,
+                              false, lr ? &fh : nullptr);
+    } else {
+        s = launch_seg_reduce(ctx, inc, 0, ent_end, ctx->gbuf[1], ctx->gbuf[1], ent_end, dim, dim, rows, ctx->ld, false,
+                              lr ? &fh : nullptr);
+        if (s != STX_OK) return s;
+        s = launch_seg_reduce(ctx, inc, ent_end, inc->nnz, ctx->gbuf[0], ctx->gbuf[0], inc->nnz, ctx->cfg.rel_dim,
+                              ctx->cfg.rel_dim, rows, ctx->ld, false, lr ? &fh : nullptr);
+    }
     if (s != STX_OK) return s;
-    return launch_seg_reduce(ctx, inc, ent_end, inc->nnz, ctx->gbuf[0], ctx->gbuf[0], inc->nnz, ctx->cfg.rel_dim,
-                             ctx->cfg.rel_dim, rows, ctx->ld, false, lr ? &fh : nullptr);
+    return launch_transr_dm_late(ctx);   // (nothing left to do unless no launch above ran)
 }
 
 stx_status stx_backward(stx_ctx *ctx, const stx_incidence *inc, const stx_params *p, stx_grads *g)

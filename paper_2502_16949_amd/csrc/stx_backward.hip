@@ -34,6 +34,7 @@
 #include "stx_rowops.h"
 #include "stx_segw_body.h"
 #include "stx_sort_body.h"
+#include "stx_transr_dm_body.h"
 
 namespace stx {
 
@@ -188,16 +189,18 @@ __device__ inline void apply_update(float *__restrict__ row, int d4, int lig, co
 // row, sign, column and whether it heads a segment from them), and the first sw.ntiles workgroups run the
 // build's last kernel, whose arrays nothing reads before the fix-up launch.
 // RIDE: 0 none of this; 1 RAW; 2 RAW, and the first kernel of the next batch's build comes along; 3 RAW, and the
-// first scatter pass of the next batch's sort comes along; 4 as 2, and that kernel counts the rows per relation.
+// first scatter pass of the next batch's sort comes along; 4 as 2, and that kernel counts the rows per relation;
+// 5 as 3, and TransR's dL/dM_r product comes along (its 128 registers still leave four workgroups on a CU, more
+// than such a batch gives this product).
 template <int LPR, int ITERS, bool PACKED, int CHUNK, bool FUSED, int RIDE>
-__global__ __launch_bounds__(kThreads, (ITERS == 1 && PACKED && FUSED && RIDE != 4) ? 8 : 1) void k_seg_reduce(const int32_t *__restrict__ packed,
+__global__ __launch_bounds__(kThreads, RIDE == 5 ? 4 : (ITERS == 1 && PACKED && FUSED && RIDE != 4) ? 8 : 1) void k_seg_reduce(const int32_t *__restrict__ packed,
                                                          const int32_t *__restrict__ seg_id, int32_t e_begin,
                                                          int32_t e_end, const float *__restrict__ src_a,
                                                          const float *__restrict__ src_b, int32_t split,
                                                          int ld_src, int tail_off, int d4, float *__restrict__ out_rows,
                                                          int ld_out, float *__restrict__ partials, FusedArgs fu,
                                                          SegSecond sec, SegWriteRide sw, EmitAhead ea,
-                                                         ScatterAhead sca)
+                                                         ScatterAhead sca, DmRide dm)
 {
     constexpr bool RAW = RIDE != 0;
     // One block of LDS for whichever part a workgroup plays (the parts' own arrays would add up and cost the
@@ -205,7 +208,7 @@ __global__ __launch_bounds__(kThreads, (ITERS == 1 && PACKED && FUSED && RIDE !=
     constexpr int GROUPS_ = kThreads / LPR, ROWF_ = ITERS * LPR * 4;
     constexpr int OWN_LDS = (GROUPS_ * 2 * ROWF_ + (FUSED ? GROUPS_ * ROWF_ : 4) + 5 * GROUPS_) * 4;
     constexpr int RIDE_LDS = RIDE == 0 ? 0
-                             : RIDE == 3 ? kScatterLds
+                             : (RIDE == 3 || RIDE == 5) ? kScatterLds
                              : (RIDE == 2 || RIDE == 4) ? emit_lds(true, RIDE == 4)
                                                          : (kFinishLds > kSegWriteLds ? kFinishLds : kSegWriteLds);
     constexpr int ARENA_LDS = OWN_LDS > RIDE_LDS ? OWN_LDS : RIDE_LDS;
@@ -236,7 +239,14 @@ __global__ __launch_bounds__(kThreads, (ITERS == 1 && PACKED && FUSED && RIDE !=
         }
         block -= ea.ntiles;
     }
-    if constexpr (RIDE == 3) {
+    if constexpr (RIDE == 5) {
+        if (block < dm.blocks) {      // uniform in the workgroup
+            transr_dm_body(block, 0, dm.args);
+            return;
+        }
+        block -= dm.blocks;
+    }
+    if constexpr (RIDE == 3 || RIDE == 5) {
         if (block < sca.ntiles) {
             scatter_body<true, false, kSortItems, true>(block, sca.args, s_arena);
             return;
@@ -486,16 +496,25 @@ __global__ __launch_bounds__(kThreads, (ITERS == 1 && PACKED && FUSED && RIDE !=
     }
 }
 
-// RIDE: 1 the first scatter pass of the next batch's sort comes along, 2 its histogram pass of the second digit.
+// RIDE: 1 the first scatter pass of the next batch's sort comes along, 2 its histogram pass of the second digit,
+// 3 as 2, and the sums of TransR's partial dL/dM_r matrices come along.
 template <int LPR, int ITERS, int CHUNK, bool FUSED, int RIDE>
 __global__ __launch_bounds__(kThreads) void k_seg_fixup(const int32_t *__restrict__ packed,
                                                         const int32_t *__restrict__ seg_id,
                                                         const int32_t *__restrict__ seg_ptr, int32_t e_begin,
                                                         int32_t e_end, int d4, float *__restrict__ out_rows,
                                                         int ld_out, const float *__restrict__ partials, FusedArgs fu,
-                                                        SegSecond sec, ScatterAhead sa, HistAhead ha)
+                                                        SegSecond sec, ScatterAhead sa, HistAhead ha, DmRide dm)
 {
     int block = (int)blockIdx.x;
+    if constexpr (RIDE == 3) {
+        if (block < dm.blocks) {      // uniform in the workgroup
+            const int slices = (dm.args.k * dm.args.d + kDmFixupSlice - 1) / kDmFixupSlice;
+            transr_dm_fixup_body(block / slices, block % slices, dm.args);
+            return;
+        }
+        block -= dm.blocks;
+    }
     if constexpr (RIDE == 1) {
         if (block < sa.ntiles) {      // uniform in the workgroup
             scatter_body<true, false, kSortItems>(block, sa.args);
@@ -503,7 +522,7 @@ __global__ __launch_bounds__(kThreads) void k_seg_fixup(const int32_t *__restric
         }
         block -= sa.ntiles;
     }
-    if constexpr (RIDE == 2) {
+    if constexpr (RIDE == 2 || RIDE == 3) {
         if (block < ha.ntiles) {
             hist_body<kSortItems>(block, ha.args.keys, ha.args.nnz, ha.args.shift, ha.args.radix, ha.args.table);
             return;
@@ -513,7 +532,7 @@ __global__ __launch_bounds__(kThreads) void k_seg_fixup(const int32_t *__restric
     // The tiles are taken from the last one down: the relation columns sort last and own the longest runs (one
     // relation has a fifth of a batch's rows), whose closing workgroups add up the most partial rows; started
     // last, after the other workgroups have come and gone, their chains would set the time of the launch.
-    block = ((int)gridDim.x - (RIDE == 1 ? sa.ntiles : RIDE == 2 ? ha.ntiles : 0)) - 1 - block;
+    block = ((int)gridDim.x - (RIDE == 1 ? sa.ntiles : RIDE == 2 ? ha.ntiles : RIDE == 3 ? ha.ntiles + dm.blocks : 0)) - 1 - block;
     if (block >= sec.first_block) {   // uniform in the workgroup
         block -= sec.first_block;
         e_begin = sec.e_begin; e_end = sec.e_end;
@@ -759,7 +778,26 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
             if (f_hist.ntiles == 0) f_scat = take_scatter_ahead(c);
         }
     }
-    const int r_blocks = r_emit.ntiles + r_scat.ntiles, f_blocks = f_scat.ntiles + f_hist.ntiles;
+    // TransR's dL/dM_r product, left by the backward pass: along with the launch that also takes the scatter pass
+    // (the steady state of stx_train_step), its sums along with the fix-up launch; ahead of any other launch.
+    DmRide r_dm{}, f_dm{};
+    bool dm_fixup_after = false;
+    if (c->dm_ride.armed) {
+        if (raw_now && r_scat.ntiles && !packed_src && LPR <= 32) {
+            c->dm_ride.armed = false;
+            r_dm = DmRide{c->dm_ride.args, c->dm_ride.items};
+            if (c->dm_ride.fixup) {
+                const DmArgs &da = c->dm_ride.args;
+                if (ntiles > 1 && f_hist.ntiles)
+                    f_dm = DmRide{da, c->dm_ride.items * ((da.k * da.d + kDmFixupSlice - 1) / kDmFixupSlice)};
+                else
+                    dm_fixup_after = true;
+            }
+        } else {
+            launch_transr_dm_late(c);
+        }
+    }
+    const int r_blocks = r_emit.ntiles + r_scat.ntiles + r_dm.blocks, f_blocks = f_scat.ntiles + f_hist.ntiles + f_dm.blocks;
     // Wide rows (more than one float4 per lane) run as column slices of the one-float4 kernels: more rows in
     // flight per lane and ITERS times the workgroups.  The unit-length rescale needs whole rows.
     const bool whole_rows = fused && (fu.mode == 2 || sec.fused_mode == 2);
@@ -772,13 +810,13 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
             hipLaunchKernelGGL((k_seg_reduce<LPR, 1, P, CH, F, 0>), grid, dim3(kThreads), 0, c->stream,         \
                                inc->at_packed, inc->at_seg_id, e_begin, e_end, src_a, src_b, split, ld_src,     \
                                tail_off, width / 4, out_rows, ld_out, c->partials, fu, sec, no_segw, r_emit,    \
-                               r_scat);                                                                         \
+                               r_scat, r_dm);                                                                   \
         }                                                                                                       \
         if (ntiles > 1) {                                                                                       \
             ProfScope prof(c, "k_seg_fixup");                                                                   \
             hipLaunchKernelGGL((k_seg_fixup<LPR, 1, CH, F, 0>), grid, dim3(kThreads), 0, c->stream,             \
                                inc->at_packed, inc->at_seg_id, inc->at_seg_ptr, e_begin, e_end, width / 4,      \
-                               out_rows, ld_out, c->partials, fu, sec, f_scat, f_hist);                         \
+                               out_rows, ld_out, c->partials, fu, sec, f_scat, f_hist, f_dm);                   \
         }                                                                                                       \
     } while (0)
 #define STX_SLICED2(P, CH) do { if (fused) STX_SLICED(P, CH, true); else STX_SLICED(P, CH, false); } while (0)
@@ -789,19 +827,20 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
         return;
     }
 #define STX_SEG_R(P, CH, F, R)                                                                                  \
-    hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH, F, (F && ITERS == 1) ? R : 0>),                         \
+    hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH, F, (F && ITERS == 1 && !(R == 5 && (P || LPR > 32))) ? R : 0>), \
                        dim3(ntiles + segw_blocks + r_blocks), dim3(kThreads), 0, c->stream, segw.args.pay,      \
                        segw.args.keys, e_begin, e_end, src_a, src_b, split, ld_src, tail_off, width / 4,        \
-                       out_rows, ld_out, c->partials, fu, sec, segw, r_emit, r_scat)
+                       out_rows, ld_out, c->partials, fu, sec, segw, r_emit, r_scat, r_dm)
 #define STX_SEG_F(CH, F, R)                                                                                     \
-    hipLaunchKernelGGL((k_seg_fixup<LPR, ITERS, CH, F, (F && ITERS == 1) ? R : 0>), dim3(ntiles + f_blocks),    \
+    hipLaunchKernelGGL((k_seg_fixup<LPR, ITERS, CH, F, (F && ITERS == 1 && !(R == 3 && LPR > 32)) ? R : 0>), dim3(ntiles + f_blocks), \
                        dim3(kThreads), 0, c->stream, inc->at_packed, inc->at_seg_id, inc->at_seg_ptr, e_begin,  \
-                       e_end, width / 4, out_rows, ld_out, c->partials, fu, sec, f_scat, f_hist)
+                       e_end, width / 4, out_rows, ld_out, c->partials, fu, sec, f_scat, f_hist, f_dm)
 #define STX_SEG(P, CH, F)                                                                                       \
     do {                                                                                                        \
         {                                                                                                       \
             ProfScope prof(c, "k_seg_reduce");                                                                  \
-            if (F && ITERS == 1 && raw_now && r_scat.ntiles) STX_SEG_R(P, CH, F, 3);                            \
+            if (F && ITERS == 1 && raw_now && r_scat.ntiles && r_dm.blocks) STX_SEG_R(P, CH, F, 5);             \
+            else if (F && ITERS == 1 && raw_now && r_scat.ntiles) STX_SEG_R(P, CH, F, 3);                       \
             else if (F && ITERS == 1 && raw_now && r_emit.ntiles && r_emit.args.rc.cur) STX_SEG_R(P, CH, F, 4); \
             else if (F && ITERS == 1 && raw_now && r_emit.ntiles) STX_SEG_R(P, CH, F, 2);                       \
             else if (F && ITERS == 1 && raw_now) STX_SEG_R(P, CH, F, 1);                                        \
@@ -809,11 +848,12 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
                 hipLaunchKernelGGL((k_seg_reduce<LPR, ITERS, P, CH, F, 0>), dim3(ntiles), dim3(kThreads), 0,    \
                                    c->stream, inc->at_packed, inc->at_seg_id, e_begin, e_end, src_a, src_b,     \
                                    split, ld_src, tail_off, width / 4, out_rows, ld_out, c->partials, fu, sec,  \
-                                   no_segw, r_emit, r_scat);                                                    \
+                                   no_segw, r_emit, r_scat, r_dm);                                              \
         }                                                                                                       \
         if (ntiles > 1) {                                                                                       \
             ProfScope prof(c, "k_seg_fixup");                                                                   \
-            if (F && ITERS == 1 && f_hist.ntiles) STX_SEG_F(CH, F, 2);                                          \
+            if (F && ITERS == 1 && f_hist.ntiles && f_dm.blocks) STX_SEG_F(CH, F, 3);                           \
+            else if (F && ITERS == 1 && f_hist.ntiles) STX_SEG_F(CH, F, 2);                                     \
             else if (F && ITERS == 1 && f_scat.ntiles) STX_SEG_F(CH, F, 1);                                     \
             else STX_SEG_F(CH, F, 0);                                                                           \
         }                                                                                                       \
@@ -821,6 +861,7 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
 #define STX_SEG2(P, CH) do { if (fused) STX_SEG(P, CH, true); else STX_SEG(P, CH, false); } while (0)
     if (packed_src) { if (small) STX_SEG2(true, CH_SHORT); else STX_SEG2(true, CH_LONG); }
     else            { if (small) STX_SEG2(false, CH_SHORT); else STX_SEG2(false, CH_LONG); }
+    if (dm_fixup_after) launch_transr_dm_fixup_late(c);
 #undef STX_SEG2
 #undef STX_SEG
 #undef STX_SEG_F

@@ -149,6 +149,30 @@ struct EmitAheadState {
 
 }  // namespace stx
 
+// TransR: arguments of the product that forms dL/dM_r and of the sum of its partial matrices (stx_transr.hip).
+struct DmArgs {
+    const int4 *dm_items;
+    const int32_t *counts;       // [1] = number of dM items
+    const uint16_t *gyt, *xt;    // operand-order transposed tiles written by the row kernels
+    float *g_proj, *partials;
+    int d, k;
+    float *M;                    // fused update: M_r <- M_r - lr * dL/dM_r replaces the store of dL/dM_r
+    float lr;
+    int fused;
+    int n_items;                 // workgroups (blockIdx.x) that are dM items; one more may follow:
+    const float *fin_partials;   // a deferred final sum of the loss that the launch takes along (fin_n == 0: none)
+    int fin_n;
+    float fin_scale;
+    float *fin_loss;
+};
+// Those two, left by the backward pass of stx_train_step for the launches of the transposed incidence product to
+// take along (both widths at most 128: one workgroup per dM item).  fixup: a relation can have several items.
+struct DmRideState {
+    bool armed, fixup;
+    DmArgs args;
+    int items;
+};
+
 struct stx_ctx {
     stx_config cfg;
     hipStream_t stream;
@@ -183,6 +207,7 @@ struct stx_ctx {
     const stx_incidence *prep_inc; // incidence whose TransR preparation already ran beside its sort
     int prep_whole;                // ... with row items that name whole lists (k_transr_fused) or 64-entry pieces
     const stx_incidence *tr_fused_inc;   // incidence whose forward pass was k_transr_fused (dL/dx and the tiles exist)
+    DmRideState dm_ride;
     const int32_t *step_colidx;    // stx_train_step: the context's own copy of this batch's column ids, or null ...
     const stx_incidence *step_colidx_inc;   // ... of this incidence
     // stx_train_step: the final sum of the loss is not launched by the forward pass but rides in the first
@@ -264,6 +289,10 @@ struct HistAhead {
     HistArgs args;
     int ntiles;
 };
+struct DmRide {
+    DmArgs args;
+    int blocks;                    // workgroups of the launch that play this part (0: none)
+};
 EmitAhead take_emit_ahead(stx_ctx *);
 ScatterAhead take_scatter_ahead(stx_ctx *);
 HistAhead take_hist_ahead(stx_ctx *);
@@ -343,6 +372,10 @@ stx_status launch_transr_fused(stx_ctx *, const stx_incidence *, const stx_param
 // fused_lr: if not null, M_r <- M_r - lr * dL/dM_r is applied in place of the store of dL/dM_r (g may be null)
 stx_status launch_transr_backward(stx_ctx *, const stx_incidence *, const stx_params *, stx_grads *,
                                   const float *fused_lr = nullptr);
+// launches what dm_ride holds as kernels of its own (a launch that could not take it along calls this first)
+stx_status launch_transr_dm_late(stx_ctx *);
+// the sum of the partial matrices alone, after a launch that took the product of dm_ride along but not the sum
+stx_status launch_transr_dm_fixup_late(stx_ctx *);
 stx_status launch_transr_sgd_proj(stx_ctx *, const stx_incidence *, stx_params *, const stx_grads *, float lr);
 // stx_transh.hip
 stx_status launch_forward_transh(stx_ctx *, const stx_incidence *, const stx_params *, float *scores, float *loss);

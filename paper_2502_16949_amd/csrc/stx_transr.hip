@@ -31,27 +31,9 @@
 #include "stx_emit_body.h"
 #include "stx_forward_body.h"
 #include "stx_sort_body.h"
+#include "stx_transr_dm_body.h"
 
 namespace stx {
-
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
-
-__device__ inline uint32_t bf16_bits(float v) { return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)v); }
-__device__ inline uint32_t pack2(float lo, float hi) { return bf16_bits(lo) | (bf16_bits(hi) << 16); }
-__device__ inline uint4 pack8(float4 a, float4 b)
-{
-    return make_uint4(pack2(a.x, a.y), pack2(a.z, a.w), pack2(b.x, b.y), pack2(b.z, b.w));
-}
-__device__ inline bf16x8 as_frag(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
-__device__ inline uint4 ld16(const uint16_t *p) { return *reinterpret_cast<const uint4 *>(p); }
-__device__ inline floatx16 zero16()
-{
-    floatx16 r;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) r[i] = 0.f;
-    return r;
-}
 
 constexpr int kMaxNT = kMaxProjDim / 32 / 2;   // 32-column tiles per wavefront (two wavefronts share the columns)
 constexpr int kLdsPad = 8;                      // halfwords added to every LDS row: 16-byte reads stay conflict-free
@@ -668,146 +650,21 @@ __global__ __launch_bounds__(kThreads, 3) void k_transr_fused(FusedArgs p, EmitA
     }
 }
 
-struct DmArgs {
-    const int4 *dm_items;
-    const int32_t *counts;       // [1] = number of dM items
-    const uint16_t *gyt, *xt;    // operand-order transposed tiles written by the row kernels
-    float *g_proj, *partials;
-    int d, k;
-    float *M;                    // fused update: M_r <- M_r - lr * dL/dM_r replaces the store of dL/dM_r
-    float lr;
-    int fused;
-    int n_items;                 // workgroups (blockIdx.x) that are dM items; one more may follow:
-    const float *fin_partials;   // a deferred final sum of the loss that the launch takes along (fin_n == 0: none)
-    int fin_n;
-    float fin_scale;
-    float *fin_loss;
-};
-
-// dL/dM_r = sum over the rows i of relation r of bf16(gy_i) bf16(x_i)^T, x_i = E[h_i] - E[t_i].
-// One workgroup per dM item (up to four 64-entry tiles of one relation) and per 128 x 128 block of
-// the matrix (blockIdx.y); the reduction runs over entries, 16 per MFMA, both operands read in
-// operand order from the transposed tiles.  Wavefront w owns the 64 x 64 quarter (w/2, w%2).
-// A relation with one item gets its matrix written directly; otherwise every item writes a partial
-// matrix into its slot and k_transr_dm_fixup adds the slots in order.
-__global__ __launch_bounds__(kThreads) void k_transr_dm(DmArgs p)
+// dL/dM_r (transr_dm_body): one workgroup per dM item and per 128 x 128 block of the matrix (blockIdx.y); one
+// more workgroup may follow the items and take a deferred final sum of the loss along.
+__global__ __launch_bounds__(kThreads, 4) void k_transr_dm(DmArgs p)
 {
-    if ((int)blockIdx.x >= p.n_items) {                   // the extra workgroup(s) of the launch
+    if ((int)blockIdx.x >= p.n_items) {
         if (blockIdx.y == 0 && p.fin_n > 0) finish_loss_body(p.fin_partials, p.fin_n, p.fin_scale, p.fin_loss);
         return;
     }
-    const int4 it = p.dm_items[2 * blockIdx.x];           // readable for every workgroup of the launch bound
-    if ((int32_t)blockIdx.x >= p.counts[1]) return;
-    const int rel = it.x, tile0 = it.y, entries = it.z, slot = it.w;
-    const int l = threadIdx.x & 63, w = threadIdx.x >> 6, l31 = l & 31, kg = l >> 5;
-    const int mtl = p.k >> 5, ntl = p.d >> 5, dblocks = (p.d + 127) >> 7;
-    const int kb = (int)blockIdx.y / dblocks, db = (int)blockIdx.y - kb * dblocks;
-    const int mt0 = 4 * kb + 2 * (w >> 1), nt0 = 4 * db + 2 * (w & 1);
-    if (mt0 >= mtl || nt0 >= ntl) return;                 // no barrier in this kernel
-    const bool m1 = mt0 + 1 < mtl, n1 = nt0 + 1 < ntl;
-    floatx16 acc[2][2];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) acc[i >> 1][i & 1] = zero16();
-    const int ntile = (entries + 63) >> 6;
-    // the fragments of tile t + 1 are requested before the products of tile t are issued (two sets of registers,
-    // taken in turn): a workgroup walks its tiles one after the other, and a batch has few workgroups here
-    auto load_tile = [&](int t, uint4 (&fa)[4][2], uint4 (&fb)[4][2]) {
-        const int nks = (min(64, entries - 64 * t) + 15) >> 4;
-        const uint16_t *ga = p.gyt + ((int64_t)(tile0 + t) * 64 * p.k) + (int64_t)l * 8;
-        const uint16_t *xb = p.xt + ((int64_t)(tile0 + t) * 64 * p.d) + (int64_t)l * 8;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            fa[ks][0] = fa[ks][1] = fb[ks][0] = fb[ks][1] = make_uint4(0, 0, 0, 0);
-            if (ks < nks) {
-                fa[ks][0] = ld16(ga + (int64_t)(ks * mtl + mt0) * 512);
-                if (m1) fa[ks][1] = ld16(ga + (int64_t)(ks * mtl + mt0 + 1) * 512);
-                fb[ks][0] = ld16(xb + (int64_t)(ks * ntl + nt0) * 512);
-                if (n1) fb[ks][1] = ld16(xb + (int64_t)(ks * ntl + nt0 + 1) * 512);
-            }
-        }
-    };
-    auto mma_tile = [&](int t, const uint4 (&fa)[4][2], const uint4 (&fb)[4][2]) {
-        const int nks = (min(64, entries - 64 * t) + 15) >> 4;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            if (ks < nks) {
-                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(fa[ks][0]), as_frag(fb[ks][0]), acc[0][0], 0, 0, 0);
-                if (n1) acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(fa[ks][0]), as_frag(fb[ks][1]), acc[0][1], 0, 0, 0);
-                if (m1) acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(fa[ks][1]), as_frag(fb[ks][0]), acc[1][0], 0, 0, 0);
-                if (m1 && n1) acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(fa[ks][1]), as_frag(fb[ks][1]), acc[1][1], 0, 0, 0);
-            }
-        }
-    };
-    uint4 fa0[4][2], fb0[4][2], fa1[4][2], fb1[4][2];
-    load_tile(0, fa0, fb0);
-    for (int t = 0; t < ntile; t += 2) {
-        if (t + 1 < ntile) load_tile(t + 1, fa1, fb1);
-        mma_tile(t, fa0, fb0);
-        if (t + 1 < ntile) {
-            if (t + 2 < ntile) load_tile(t + 2, fa0, fb0);
-            mma_tile(t + 1, fa1, fb1);
-        }
-    }
-    const int64_t kd = (int64_t)p.k * p.d;
-    const bool update = slot < 0 && p.fused;             // the relation's only item: apply the step right here
-    float *dst = slot >= 0 ? p.partials + slot * kd : (update ? p.M + rel * kd : p.g_proj + rel * kd);
-#pragma unroll
-    for (int mi = 0; mi < 2; ++mi) {
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni) {
-            if ((mi == 0 || m1) && (ni == 0 || n1)) {
-                const int j = 32 * (nt0 + ni) + l31;
-                float old[16];
-                if (update) {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        old[v] = dst[(int64_t)(32 * (mt0 + mi) + 8 * (v >> 2) + 4 * kg + (v & 3)) * p.d + j];
-                }
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int a = 32 * (mt0 + mi) + 8 * (v >> 2) + 4 * kg + (v & 3);
-                    float val = acc[mi][ni][v];
-                    if (update) { const float step = p.lr * val; val = old[v] - step; }
-                    dst[(int64_t)a * p.d + j] = val;
-                }
-            }
-        }
-    }
+    transr_dm_body((int)blockIdx.x, (int)blockIdx.y, p);
 }
 
-// The last dM item of a relation that has several adds up the relation's partial matrices in item order.
+// The sums of the partial matrices (transr_dm_fixup_body): blockIdx.y slices the matrix.
 __global__ __launch_bounds__(kThreads) void k_transr_dm_fixup(DmArgs p)
 {
-    if ((int32_t)blockIdx.x >= p.counts[1]) return;
-    const int4 tail = p.dm_items[2 * blockIdx.x + 1];
-    const int parts = tail.y;
-    if (parts == 0) return;
-    const int64_t kd = (int64_t)p.k * p.d;
-    // blockIdx.y slices the matrix: 4 consecutive elements per thread, 1024 per workgroup
-    const int64_t idx = ((int64_t)blockIdx.y * kThreads + threadIdx.x) * 4;
-    if (idx >= kd) return;
-    const float *src = p.partials + (int64_t)tail.x * kd + idx;
-    float4 a = ld4(src);
-    int u = 1;
-    for (; u + 3 < parts; u += 4) {   // four partial matrices in flight, added in item order
-        float4 v[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) v[q] = ld4(src + (int64_t)(u + q) * kd);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) { a.x += v[q].x; a.y += v[q].y; a.z += v[q].z; a.w += v[q].w; }
-    }
-    for (; u < parts; ++u) {
-        float4 v = ld4(src + (int64_t)u * kd);
-        a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
-    }
-    const int64_t off = (int64_t)p.dm_items[2 * blockIdx.x].x * kd + idx;
-    if (p.fused) {
-        const float4 m = ld4(p.M + off);
-        const float s0 = p.lr * a.x, s1 = p.lr * a.y, s2 = p.lr * a.z, s3 = p.lr * a.w;
-        st4(p.M + off, make_float4(m.x - s0, m.y - s1, m.z - s2, m.w - s3));
-    } else {
-        st4(p.g_proj + off, a);
-    }
+    transr_dm_fixup_body((int)blockIdx.x, (int)blockIdx.y, p);
 }
 
 // M_r <- M_r - lr * dL/dM_r for every relation present in the batch: workgroup (r, y) looks relation r's
@@ -1005,24 +862,47 @@ stx_status launch_transr_backward(stx_ctx *c, const stx_incidence *inc, const st
     a.g_proj = fused_lr ? nullptr : g->proj; a.partials = c->gbuf[2];
     a.d = c->cfg.dim; a.k = c->cfg.rel_dim;
     a.M = p->proj; a.lr = fused_lr ? *fused_lr : 0.f; a.fused = fused_lr ? 1 : 0;
-    const unsigned items = dm_items_max(c, inc->n_rows);
-    a.n_items = (int)items;
+    a.n_items = (int)dm_items_max(c, inc->n_rows);
     a.fin_partials = nullptr; a.fin_n = 0; a.fin_scale = 1.0f; a.fin_loss = nullptr;
+    // Left for the launches of the transposed incidence product, which follow at once; in stx_train_step they take
+    // this along (one workgroup per dM item: both widths at most 128), otherwise they launch it first.
+    c->dm_ride = DmRideState{true, inc->n_rows > kProjRowsDm /* else no relation can have two items */, a, a.n_items};
+    if (!(fused_lr && fused_rows && a.d <= 128 && a.k <= 128 && c->segw.armed && c->sorted_inc == inc))
+        return launch_transr_dm_late(c);
+    return hip_ok(hipGetLastError());
+}
+
+static void launch_dm_fixup(stx_ctx *c, const DmArgs &a)
+{
+    ProfScope prof(c, "k_transr_dm_fixup");
+    hipLaunchKernelGGL(k_transr_dm_fixup,
+                       dim3((unsigned)a.n_items, (unsigned)(((int64_t)a.k * a.d + kDmFixupSlice - 1) / kDmFixupSlice)),
+                       dim3(kThreads), 0, c->stream, a);
+}
+
+stx_status launch_transr_dm_late(stx_ctx *c)
+{
+    if (!c->dm_ride.armed) return STX_OK;
+    c->dm_ride.armed = false;
+    DmArgs a = c->dm_ride.args;
     if (c->fin_n > 0) {   // a deferred sum of the loss: one more workgroup
         a.fin_partials = c->loss_partials; a.fin_n = c->fin_n; a.fin_scale = c->fin_scale; a.fin_loss = c->fin_loss;
         c->fin_n = 0;
     }
     {
         ProfScope prof(c, "k_transr_dm");
-        hipLaunchKernelGGL(k_transr_dm, dim3(items + (a.fin_n > 0 ? 1u : 0u), (unsigned)(((a.k + 127) / 128) * ((a.d + 127) / 128))),
+        hipLaunchKernelGGL(k_transr_dm, dim3((unsigned)a.n_items + (a.fin_n > 0 ? 1u : 0u),
+                                             (unsigned)(((a.k + 127) / 128) * ((a.d + 127) / 128))),
                            dim3(kThreads), 0, c->stream, a);
     }
-    if (inc->n_rows > kProjRowsDm) {                      // otherwise no relation can have two items
-        ProfScope prof(c, "k_transr_dm_fixup");
-        hipLaunchKernelGGL(k_transr_dm_fixup,
-                           dim3(items, (unsigned)(((int64_t)a.k * a.d + 4 * kThreads - 1) / (4 * kThreads))),
-                           dim3(kThreads), 0, c->stream, a);
-    }
+    if (c->dm_ride.fixup) launch_dm_fixup(c, a);
+    return hip_ok(hipGetLastError());
+}
+
+// The sum of the partial matrices alone, after a launch that took the product along but not the sum.
+stx_status launch_transr_dm_fixup_late(stx_ctx *c)
+{
+    launch_dm_fixup(c, c->dm_ride.args);
     return hip_ok(hipGetLastError());
 }
 
