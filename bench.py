@@ -45,11 +45,11 @@ DOMINANT_CALLS = {"mid": "k_seg_reduce", "tiny": "k_seg_reduce", "toruse": "k_se
 # x1.0); the runs and their numbers are in profiles/<workload>_kernel_trace.txt and profiles/copy_calibration.txt.
 # A different kernel (--kernel) or workload has no measured figure here and reports null.
 # Keys: (workload, kernel, fused step or not).
-TRAFFIC_BYTES = {("toruse", "k_seg_reduce", True): 1165.49e6 + 623.17e6,
+TRAFFIC_BYTES = {("toruse", "k_seg_reduce", True): 1133.78e6 + 623.17e6,
                  ("toruse", "k_forward_stacked", True): 693.53e6 + 53.52e6,
                  ("toruse", "k_forward_stacked", False): 693.55e6 + 53.52e6,
-                 ("toruse", "k_seg_reduce", False): 561.81e6 + 532.18e6,
-                 ("toruse", "k_sgd_rows", False): 1056.93e6 + 526.37e6,
+                 ("toruse", "k_seg_reduce", False): 561.76e6 + 532.18e6,
+                 ("toruse", "k_sgd_rows", False): 1056.94e6 + 526.37e6,
                  # mean of the two batches of an epoch (393,216 and 89,926 positives), like the timed mean
                  ("paper_transe", "k_seg_reduce", True): (9761.85e6 + 104.19e6 + 2281.04e6 + 99.90e6) / 2,
                  # with the look-ahead (the next batch's first build kernels ride in these launches)
@@ -60,8 +60,8 @@ TRAFFIC_BYTES = {("toruse", "k_seg_reduce", True): 1165.49e6 + 623.17e6,
                  ("transh", "k_fwdh_scatter", "rides"): 34.67e6 + 105.22e6,
                  ("transh", "k_seg_fixup", "rides"): 4.06e6 + 0.48e6,
                  ("transr", "k_transr_fused", "rides"): 40.20e6 + 52.83e6,
-                 ("transr", "k_transr_dm", "rides"): 31.90e6 + 21.21e6,
-                 ("transr", "k_seg_reduce", "rides"): 56.33e6 + 9.05e6,
+                 ("transr", "k_seg_reduce", "rides"): 89.63e6 + 31.34e6,
+                 ("transr", "k_seg_fixup", "rides"): 9.85e6 + 1.26e6,
                  # the other modes (profiles/semiring_complex_*_kernel_trace.txt, profiles/rank_mid_kernel_trace.txt)
                  ("semiring complex", "mid", "k_semiring_terms"): 66.64e6 + 100.66e6,
                  ("semiring complex", "toruse", "k_semiring_terms"): 1560.16e6 + 2013.27e6}
@@ -111,12 +111,16 @@ def kernel_work(wl, kernel, rows, touched, fused=False, rides=False, segw=False)
     runs the next batch's k_emit (about 28 B per entry: indices in, CSR arrays, keys and negatives out), that of
     k_seg_reduce its first scatter pass (16 B per entry), that of k_seg_fixup the histogram pass of its second
     digit (4 B per entry).
+    With TransR (both widths at most 128) the launch of k_seg_reduce also runs the dL/dM_r product and that of
+    k_seg_fixup the sums of its partial matrices.
     segw: the launch of k_seg_reduce also runs the last kernel of this batch's build (sorted key and payload in,
     segment, row, packed entry and sign out: 21 B per entry)."""
     row = 4 * wl.dim
     nnz = 3 * rows
     if kernel == "k_seg_reduce" and (rides or segw):
         w, unit, bound, peak = kernel_work(wl, kernel, rows, touched, fused, False, False)
+        if rides and wl.model == "transr" and wl.dim <= 128 and wl.rel_dim <= 128:
+            w += kernel_work(wl, "k_transr_dm", rows, touched)[0]      # TransR's dL/dM_r product rides here too
         return w + nnz * ((16 if rides else 0) + (21 if segw else 0)), unit, bound, peak
     if kernel in ("k_fwd_scatter", "k_fwdh_scatter") and rides:
         w, unit, bound, peak = kernel_work(wl, kernel, rows, touched, fused, False, False)

@@ -22,6 +22,14 @@ pytestmark = pytest.mark.gpu
 SIDES = [(B.STX_TAIL, stxo.TAIL), (B.STX_HEAD, stxo.HEAD)]
 
 
+# Full-size checks against the double-precision counts (see check_counts): the share of sampled queries whose
+# counts must be exactly those, and the most candidates the kernel's rounding may move across the true entity,
+# for the tables of up to 15,000 entities (measured: 0.94 to 1 and at most 1) and, second, for the 4M-entity
+# table, where a few of the millions of candidates always sit within rounding of the true score (measured: 4).
+EXACT_SMALL = (0.9, 3)
+EXACT_LARGE = (0.0, 16)
+
+
 def band_tol(dim):
     return max(G.REL_TOL, (dim + 2) * 2.0**-24)
 
@@ -48,13 +56,24 @@ def run_rank(wl, X, h, r, t, side, max_batch=8):
     return ctx, ts.cpu().numpy()[:nq], less.cpu().numpy()[:nq], equal.cpu().numpy()[:nq]
 
 
-def check_counts(ts, less, equal, ref, tol, what=None):
+def check_counts(ts, less, equal, ref, tol, what=None, exact=None, exact_bar=EXACT_SMALL):
     """what: a name under which the share of these queries whose counts the band decides (another candidate than
-    the true entity sits in it) and the largest band, as a share of the candidates, go on record (G.USAGE)."""
+    the true entity sits in it) and the mean band size go on record (G.USAGE).
+    exact: the oracle's counts with an empty band (double precision decides every comparison).  The band is a
+    worst-case bound and wide where scores crowd; what the kernel's rounding really moves is far less, so the
+    distance of the GPU count from the double-precision count may use only a small part of the band."""
     ref_ts, ref_less, ref_band = ref
     if what is not None:
         G.USAGE.append((what + ": share of queries with another candidate in the band", float((ref_band > 1).mean())))
         G.USAGE.append((what + ": mean band size", float(ref_band.mean())))
+    if exact is not None:
+        _, ex_less, ex_ties = exact
+        off = np.maximum(0, np.maximum(ex_less - less.astype(np.int64), (less.astype(np.int64) + equal) - (ex_less + ex_ties)))
+        if what is not None:
+            G.USAGE.append((what + ": share of queries whose counts are the double-precision ones", float((off == 0).mean())))
+            G.USAGE.append((what + ": largest distance from the double-precision counts", float(off.max())))
+        assert (off == 0).mean() >= exact_bar[0], float((off == 0).mean())
+        assert off.max() <= exact_bar[1], int(off.max())
     np.testing.assert_allclose(ts, ref_ts, rtol=tol, atol=0)
     assert np.all(equal >= 1), "the true entity ties with itself"
     assert np.all(less >= ref_less), int((less < ref_less).sum())
@@ -181,7 +200,9 @@ def test_rank_full_size(name, nq, n_sample):
         assert np.all(np.isfinite(ts)) and np.all(ts >= 0)
         assert np.all(equal >= 1) and np.all(less >= 0) and np.all(less.astype(np.int64) + equal <= wl.n_ent)
         ref = stxo.rank(oracle_config(wl), X, h[pick], r[pick], t[pick], oside, tol=tol)
-        check_counts(ts[pick], less[pick], equal[pick], ref, tol, what=f"rank {name} full size")
+        exact = stxo.rank(oracle_config(wl), X, h[pick], r[pick], t[pick], oside, tol=0.0)
+        check_counts(ts[pick], less[pick], equal[pick], ref, tol, what=f"rank {name} full size", exact=exact,
+                     exact_bar=EXACT_LARGE if wl.n_ent > 100_000 else EXACT_SMALL)
         hits[side] = float((1 + less <= 10).mean())
     # identical (h, r, t) queries give identical counts wherever they sit in the launch
     key = h.astype(np.int64) * (wl.n_rel + 1) * (wl.n_ent + 1) + r.astype(np.int64) * (wl.n_ent + 1) + t
@@ -267,7 +288,8 @@ def test_rank_transh_full_size():
         assert np.all(np.isfinite(ts)) and np.all(equal >= 1) and np.all(less.astype(np.int64) + equal <= wl.n_ent)
         extra = transh_abs_tol(tabs, h[pick], r[pick], t[pick], side, wl.dim)
         ref = stxo.rank(oracle_config(wl), ot, h[pick], r[pick], t[pick], oside, tol=tol, abs_tol=extra)
-        check_counts(ts[pick], less[pick], equal[pick], ref, 4 * tol, what="rank transh full size")
+        exact = stxo.rank(oracle_config(wl), ot, h[pick], r[pick], t[pick], oside, tol=0.0)
+        check_counts(ts[pick], less[pick], equal[pick], ref, 4 * tol, what="rank transh full size", exact=exact)
 
 
 # ------------------------------------------------------------------------------------------ TransR
@@ -353,7 +375,7 @@ def test_rank_transr_full_size_and_workspace_errors():
     tabs = W.make_tables(wl)
     nq = 20_466
     h, r, t = W.make_test_triplets(wl, nq)
-    pick = np.sort(np.random.default_rng(7).choice(nq, 6, replace=False))
+    pick = np.sort(np.random.default_rng(7).choice(nq, 16, replace=False))
     tol = max(G.REL_TOL, (wl.rel_dim + wl.dim + 8) * 2.0**-24)
     ot = stxo.Tables(tabs["ent"], tabs["rel"], None, tabs["proj"])
     for side, oside in SIDES:
@@ -361,7 +383,8 @@ def test_rank_transr_full_size_and_workspace_errors():
         assert np.all(np.isfinite(ts)) and np.all(equal >= 1) and np.all(less.astype(np.int64) + equal <= wl.n_ent)
         extra = transr_abs_tol(tabs, h[pick], r[pick], t[pick], side, wl.dim)
         ref = stxo.rank(oracle_config(wl, bf16=False), ot, h[pick], r[pick], t[pick], oside, tol=tol, abs_tol=extra)
-        check_counts(ts[pick], less[pick], equal[pick], ref, 4 * tol, what="rank transr full size")
+        exact = stxo.rank(oracle_config(wl, bf16=False), ot, h[pick], r[pick], t[pick], oside, tol=0.0)
+        check_counts(ts[pick], less[pick], equal[pick], ref, 4 * tol, what="rank transr full size", exact=exact)
     # a missing or short work buffer is refused before anything is launched
     m = G.GpuModel(_wl_r("l2", 50, 3, 32, 32), W.make_tables(_wl_r("l2", 50, 3, 32, 32)), flags=B.STX_FLAG_BF16_PROJ)
     z = G.dev_i32(np.zeros(3, np.int32))
