@@ -47,10 +47,13 @@ __global__ __launch_bounds__(kThreads, ITERS == 1 ? 8 : 1) void k_forward_stacke
     forward_stacked_body<LPR, ITERS, DIST, FROM_Y, PACKED>((int)blockIdx.x, a);
 }
 
-template <int LPR, int DIST, bool PACKED, int NB>
-__global__ __launch_bounds__(kThreads, 8) void k_forward_fast(ForwardArgs a, int32_t *general_flag, int32_t serial)
+// (rows of one float4 per lane: 64 registers, every workgroup of a large batch resident at once; wider rows hold
+// four rows of ITERS float4 per lane)
+template <int LPR, int ITERS, int DIST, bool PACKED, int NB>
+__global__ __launch_bounds__(kThreads, ITERS == 1 ? 8 : (ITERS == 2 ? 4 : 2)) void k_forward_fast(ForwardArgs a, int32_t *general_flag,
+                                                                                                 int32_t serial)
 {
-    forward_fast_body<LPR, DIST, PACKED, NB>((int)blockIdx.x, a, general_flag, serial);
+    forward_fast_body<LPR, ITERS, DIST, PACKED, NB>((int)blockIdx.x, a, general_flag, serial);
 }
 
 // TransR in stx_train_step: the first kernel of the next batch's build (which also counts the rows per relation)
@@ -153,12 +156,11 @@ static void forward_go(stx_ctx *c, const stx_incidence *inc, const stx_params *p
     EmitAhead ea{};
     if (from_y && c->ahead.armed && !c->ahead.emit_done && c->ahead.args.rc.cur) ea = take_emit_ahead(c);
     const dim3 grid_e(grid.x + (unsigned)ea.ntiles);
-    // Rows of one float4 per lane and few negatives per positive: the kernel that fetches the positive's rows once
-    // (forward_fast_body).  It covers negatives that keep the relation and one entity of their positive; when the
+    // Few negatives per positive (four with rows of one float4 per lane, one with wider rows): the kernel that
+    // fetches the positive's rows once (forward_fast_body).  It covers negatives that keep the relation and one entity of their positive; when the
     // batch was not drawn by the library's sampler in this build, the general kernel is enqueued behind it and runs
     // only if the fast one met another kind of negative.
-    bool fast = false;
-    if constexpr (ITERS == 1) fast = !from_y && inc->k <= fast_negatives<LPR>();
+    const bool fast = !from_y && inc->k <= fast_negatives<LPR, ITERS>();
     const bool sampled = c->sampled_inc == inc;
     int32_t *flag = c->ctrl + CTRL_GENERAL;
     const int32_t serial = fast ? ++c->fwd_serial : 0;
@@ -167,13 +169,11 @@ static void forward_go(stx_ctx *c, const stx_incidence *inc, const stx_params *p
                        fast ? flag : nullptr, serial)
 #define STX_FAST(D, P)                                                                                          \
     do {                                                                                                        \
-        if constexpr (ITERS == 1) {                                                                             \
-            if (inc->k <= 1)                                                                                    \
-                hipLaunchKernelGGL((k_forward_fast<LPR, D, P, 1>), grid, dim3(kThreads), 0, c->stream, fa, flag, serial); \
-            else                                                                                                \
-                hipLaunchKernelGGL((k_forward_fast<LPR, D, P, fast_negatives<LPR>()>), grid, dim3(kThreads), 0, c->stream, \
-                                   fa, flag, serial);                                                           \
-        }                                                                                                       \
+        if (inc->k <= 1)                                                                                        \
+            hipLaunchKernelGGL((k_forward_fast<LPR, ITERS, D, P, 1>), grid, dim3(kThreads), 0, c->stream, fa, flag, serial); \
+        else                                                                                                    \
+            hipLaunchKernelGGL((k_forward_fast<LPR, ITERS, D, P, fast_negatives<LPR, ITERS>()>), grid, dim3(kThreads), 0, \
+                               c->stream, fa, flag, serial);                                                    \
     } while (0)
 #define STX_FWD2(D)                                                                                             \
     do {                                                                                                        \

@@ -69,21 +69,21 @@ __device__ inline void finish_loss_body(const float *__restrict__ partials, int 
 }
 
 // The forward step for batches whose negatives come from the sampler (Sec. 5.3: every negative keeps the relation
-// and one entity of its positive), rows of one float4 per lane, at most NB negatives per positive.  One group per
-// positive: its lanes fetch the 3 + 3k column ids in ONE load (lane s < 3: id s of the positive; lane 3 + 3q + s: id
-// s of negative q) and share them by shuffles; then the positive's three rows and the ONE row in which each negative
-// differs are requested together (3 + k table rows instead of 3 + 3k), so a wavefront pays two dependent memory
-// round trips in all.  x is formed by the same two roundings in the same order as a full gather would: the bits
-// are those of forward_stacked_body.  A group that finds another kind of negative (a caller's own) does nothing
-// and stores `serial` in *general_flag: the caller then runs the general kernel over those groups.
-template <int LPR, int DIST, bool PACKED, int NB>
+// and one entity of its positive), at most NB negatives per positive.  One group per positive: its lanes fetch the
+// 3 + 3k column ids in ONE load (lane s < 3: id s of the positive; lane 3 + 3q + s: id s of negative q) and share
+// them by shuffles; then the positive's three rows and the ONE row in which each negative differs are requested
+// together (3 + k table rows instead of 3 + 3k), so a wavefront pays two dependent memory round trips in all.
+// x is formed by the same two roundings in the same order as a full gather would: the bits are those of
+// forward_stacked_body.  A group that finds another kind of negative (a caller's own) does nothing and stores
+// `serial` in *general_flag: the caller then runs the general kernel over those groups.
+template <int LPR, int ITERS, int DIST, bool PACKED, int NB>
 __device__ inline void forward_fast_body(const int block, const ForwardArgs &a, int32_t *general_flag, int32_t serial)
 {
     static_assert(LPR >= 3 + 3 * NB, "one lane per column id");
     const int32_t *__restrict__ colidx = a.colidx;
     const float *__restrict__ X = a.X;
     const int32_t b = a.b, k = a.k;
-    const int dim = a.dim, gstride = a.gstride;
+    const int dim = a.dim, d4 = dim / 4, gstride = a.gstride;
     float *__restrict__ scores = a.scores;
     constexpr int GROUPS = kThreads / LPR;
     __shared__ float s_loss[GROUPS];
@@ -109,33 +109,37 @@ __device__ inline void forward_fast_body(const int block, const ForwardArgs &a, 
         if (shared) {
             const float wr = a.rel_weight ? a.rel_weight[c1 - a.n_ent] : 1.0f;
             // (lanes past the row's width hold zeros and take part in the reductions only)
-            const bool in_row = lig < dim / 4;
-            const float *xl = X + 4 * lig;
-            const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
-            float4 hr = in_row ? ld4(xl + (int64_t)c0 * dim) : zero;
-            const float4 pr = in_row ? ld4(xl + (int64_t)c1 * dim) : zero, pt = in_row ? ld4(xl + (int64_t)c2 * dim) : zero;
-            float4 e[NB];
+            RowVec<ITERS> hr, pr, pt, e[NB];
+            load_vec<LPR, ITERS>(X + (int64_t)c0 * dim, d4, lig, hr);
+            load_vec<LPR, ITERS>(X + (int64_t)c1 * dim, d4, lig, pr);
+            load_vec<LPR, ITERS>(X + (int64_t)c2 * dim, d4, lig, pt);
 #pragma unroll
             for (int q = 0; q < NB; ++q)
                 if (q < k) {
                     // a row used once does not displace the others when the table is far larger than the caches
-                    e[q] = !in_row ? zero : a.stream_rows ? ld4_stream(xl + (int64_t)ce[q] * dim) : ld4(xl + (int64_t)ce[q] * dim);
+                    if (a.stream_rows) load_vec_stream<LPR, ITERS>(X + (int64_t)ce[q] * dim, d4, lig, e[q]);
+                    else load_vec<LPR, ITERS>(X + (int64_t)ce[q] * dim, d4, lig, e[q]);
                 }
-            hr = add4(hr, pr);
-            RowVec<1> x;
-            x.v[0] = sub4(hr, pt);
-            const float npos = row_distance<LPR, 1, DIST>(x);
+            RowVec<ITERS> x;
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) {
+                hr.v[it] = add4(hr.v[it], pr.v[it]);
+                x.v[it] = sub4(hr.v[it], pt.v[it]);
+            }
+            const float npos = row_distance<LPR, ITERS, DIST>(x);
             const float dpos = wr * npos;
             if (lig == 0) scores[i] = dpos;
             uint8_t *recs = reinterpret_cast<uint8_t *>(a.G);
             float *gcoef = PACKED ? reinterpret_cast<float *>(recs + packed_coef_offset((int64_t)b * (1 + k), gstride)) : nullptr;
             int n_active = 0;
-            const RowVec<1> xp = x;
+            const RowVec<ITERS> xp = x;
 #pragma unroll
             for (int q = 0; q < NB; ++q)
                 if (q < k) {
-                    x.v[0] = (tail_mask >> q & 1u) ? sub4(hr, e[q]) : sub4(add4(e[q], pr), pt);
-                    const float nneg = row_distance<LPR, 1, DIST>(x);
+#pragma unroll
+                    for (int it = 0; it < ITERS; ++it)
+                        x.v[it] = (tail_mask >> q & 1u) ? sub4(hr.v[it], e[q].v[it]) : sub4(add4(e[q].v[it], pr.v[it]), pt.v[it]);
+                    const float nneg = row_distance<LPR, ITERS, DIST>(x);
                     const float dneg = wr * nneg;
                     const float arg = (a.margin + dpos) - dneg;
                     const bool active = arg > 0.f;
@@ -143,14 +147,14 @@ __device__ inline void forward_fast_body(const int block, const ForwardArgs &a, 
                     if (lig == 0) scores[row] = dneg;
                     if (active) { hinge_sum += arg; ++n_active; }
                     if (PACKED)
-                        write_grad_row_packed<LPR, 1, DIST>(recs, gstride, gcoef, row, dim / 4, lig, x, active ? -a.scale * wr : 0.f);
+                        write_grad_row_packed<LPR, ITERS, DIST>(recs, gstride, gcoef, row, d4, lig, x, active ? -a.scale * wr : 0.f);
                     else
-                        write_grad_row<LPR, 1, DIST>(a.G + (int64_t)row * dim, dim / 4, lig, x, active ? -a.scale * wr : 0.f, nneg);
+                        write_grad_row<LPR, ITERS, DIST>(a.G + (int64_t)row * dim, d4, lig, x, active ? -a.scale * wr : 0.f, nneg);
                 }
             if (PACKED)
-                write_grad_row_packed<LPR, 1, DIST>(recs, gstride, gcoef, i, dim / 4, lig, xp, (float)n_active * a.scale * wr);
+                write_grad_row_packed<LPR, ITERS, DIST>(recs, gstride, gcoef, i, d4, lig, xp, (float)n_active * a.scale * wr);
             else
-                write_grad_row<LPR, 1, DIST>(a.G + (int64_t)i * dim, dim / 4, lig, xp, (float)n_active * a.scale * wr, npos);
+                write_grad_row<LPR, ITERS, DIST>(a.G + (int64_t)i * dim, d4, lig, xp, (float)n_active * a.scale * wr, npos);
         } else if (lig == 0 && general_flag) {
             *general_flag = serial;
         }
@@ -275,9 +279,10 @@ __device__ inline void forward_stacked_body(const int block, const ForwardArgs &
 
 namespace stx {
 
-// Most negatives per positive that forward_fast_body takes with groups of LPR lanes (one lane per column id).
-template <int LPR>
-constexpr int fast_negatives() { return LPR >= 16 ? 4 : 1; }
+// Most negatives per positive that forward_fast_body takes with groups of LPR lanes (one lane per column id) and
+// ITERS float4 per lane (wide rows: one, or the rows in flight would not fit the registers).
+template <int LPR, int ITERS = 1>
+constexpr int fast_negatives() { return (LPR >= 16 && ITERS == 1) ? 4 : 1; }
 
 // The forward step inside the launches of stx_train_step, whose negatives are the sampler's: the fast body where the
 // row width and the number of negatives allow it.  K1: the launch was chosen for at most one negative per positive.
@@ -285,9 +290,9 @@ template <int LPR, int ITERS, int DIST, bool PACKED, bool K1>
 __device__ inline void forward_step_body(const int block, const ForwardArgs &fa)
 {
     if constexpr (ITERS == 1 && K1) {
-        forward_fast_body<LPR, DIST, PACKED, 1>(block, fa, nullptr, 0);
+        forward_fast_body<LPR, 1, DIST, PACKED, 1>(block, fa, nullptr, 0);
     } else if constexpr (ITERS == 1 && LPR >= 16) {
-        if (fa.k <= 4) forward_fast_body<LPR, DIST, PACKED, 4>(block, fa, nullptr, 0);
+        if (fa.k <= 4) forward_fast_body<LPR, 1, DIST, PACKED, 4>(block, fa, nullptr, 0);
         else forward_stacked_body<LPR, ITERS, DIST, false, PACKED, K1>(block, fa);
     } else {
         forward_stacked_body<LPR, ITERS, DIST, false, PACKED, K1>(block, fa);

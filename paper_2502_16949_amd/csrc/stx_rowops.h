@@ -24,6 +24,16 @@ __device__ inline void load_vec(const float *__restrict__ p, int d4, int lig, Ro
         x.v[it] = j < d4 ? ld4(p + 4 * j) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
 }
+// the same with non-temporal loads: for rows that are used once and should not displace others in the caches
+template <int LPR, int ITERS>
+__device__ inline void load_vec_stream(const float *__restrict__ p, int d4, int lig, RowVec<ITERS> &x)
+{
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        int j = lig + it * LPR;
+        x.v[it] = j < d4 ? ld4_stream(p + 4 * j) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+}
 template <int LPR, int ITERS>
 __device__ inline void store_vec(float *__restrict__ p, int d4, int lig, const RowVec<ITERS> &x)
 {

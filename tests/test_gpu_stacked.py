@@ -140,7 +140,9 @@ def test_training_step_matches_oracle(model, dist, n_ent, n_rel, b, k, dim, zipf
 
 
 @pytest.mark.parametrize("model,dist,dim,k", [("transe", "l1", 128, 1), ("transe", "l2", 128, 4), ("toruse", "torus_l1", 64, 3),
-                                              ("transe", "l2", 32, 1), ("transe", "l1", 256, 2)])
+                                              ("transe", "l2", 32, 1), ("transe", "l1", 256, 2),
+                                              # rows wider than one float4 per lane
+                                              ("transe", "l2", 512, 1), ("transe", "l1", 1024, 1), ("toruse", "torus_l2", 768, 1)])
 def test_negatives_of_the_callers_own_choice(model, dist, dim, k):
     """Negatives need not be the sampler's: here most replace BOTH entities of their positive (some keep one, some
     equal it), which the kernel that fetches a positive's rows once for its negatives does not cover: the general
@@ -161,7 +163,8 @@ def test_negatives_of_the_callers_own_choice(model, dist, dim, k):
 
 
 @pytest.mark.parametrize("model,dist,dim", [("transe", "l1", 128), ("transe", "l2", 128), ("transe", "l2_sq", 64),
-                                            ("toruse", "torus_l2", 128), ("toruse", "torus_l1", 256)])
+                                            ("toruse", "torus_l2", 128), ("toruse", "torus_l1", 256),
+                                            ("transe", "l2", 1024)])
 def test_relation_weights_match_oracle(model, dist, dim):
     """Table 2, TransM row: a fixed weight per relation multiplies the distance."""
     wl, tabs, bt = _problem(model, dist, 400, 9, 777, 3, dim, seed=31, zipf=1.1)
