@@ -73,24 +73,46 @@ __device__ inline void scatter_body(const int block, const ScatterArgs &a, unsig
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int radix = 1 << bits;
     for (int i = tid; i < 4 * 256; i += kThreads) (&s_hist[0][0])[i] = 0;
+    int32_t key[ITEMS], pay[ITEMS], rank[ITEMS];
+    const int32_t wave_base = block * (kThreads * ITEMS) + w * (64 * ITEMS);
+    const uint64_t lanes_below = (1ull << lane) - 1ull;
+    auto load_items = [&]() {
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it) {             // all loads at once, so that they are in flight together
+            const int32_t e = wave_base + it * 64 + lane;
+            const bool valid = e < nnz;
+            key[it] = valid ? keys_in[e] : 0;
+            pay[it] = FIRST ? e : (valid ? pay_in[e] : 0);
+        }
+    };
+    // Large sorts: the tile's keys are requested before the offsets are derived from the histogram tables (a dozen
+    // dependent round trips with the two-level table), so that the two waits overlap.  The small sorts share
+    // launches with kernels that are capped at 64 registers and keep the order that needs fewer of them.
+    constexpr bool EARLY = ITEMS > kSortItems && !ARENA;
+    if constexpr (EARLY) load_items();
     if (TWO_LEVEL) {
         int32_t below = 0, total = 0;
         if (tid < radix) {
             const int me = block, g_me = me / kSuperTile, ngroups = (ntiles + kSuperTile - 1) / kSuperTile;
-            int g = 0;
-            for (; g + 3 < ngroups; g += 4) {
-                int32_t v0 = super[g * radix + tid], v1 = super[(g + 1) * radix + tid];
-                int32_t v2 = super[(g + 2) * radix + tid], v3 = super[(g + 3) * radix + tid];
-                total += (v0 + v1) + (v2 + v3);
-                below += (g < g_me ? v0 : 0) + (g + 1 < g_me ? v1 : 0) + (g + 2 < g_me ? v2 : 0) + (g + 3 < g_me ? v3 : 0);
+            // (integer sums: any order gives the same offsets; eight loads are in flight per step)
+            constexpr int U = 8;
+            for (int g0 = 0; g0 < ngroups; g0 += U) {
+                int32_t v[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) v[u] = g0 + u < ngroups ? super[(g0 + u) * radix + tid] : 0;
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    total += v[u];
+                    below += g0 + u < g_me ? v[u] : 0;
+                }
             }
-            for (; g < ngroups; ++g) {
-                int32_t v = super[g * radix + tid];
-                total += v;
-                below += g < g_me ? v : 0;
+            for (int t0 = g_me * kSuperTile; t0 < me; t0 += U) {
+                int32_t v[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) v[u] = t0 + u < me ? table[(t0 + u) * radix + tid] : 0;
+#pragma unroll
+                for (int u = 0; u < U; ++u) below += v[u];
             }
-#pragma unroll 8
-            for (int t = g_me * kSuperTile; t < me; ++t) below += table[t * radix + tid];
         }
         int32_t base = block_exclusive_scan(total, nullptr);
         s_goff[tid] = base + below;
@@ -139,16 +161,7 @@ __device__ inline void scatter_body(const int block, const ScatterArgs &a, unsig
     }
     __syncthreads();
 
-    int32_t key[ITEMS], pay[ITEMS], rank[ITEMS];
-    const int32_t wave_base = block * (kThreads * ITEMS) + w * (64 * ITEMS);
-    const uint64_t below = (1ull << lane) - 1ull;
-#pragma unroll
-    for (int it = 0; it < ITEMS; ++it) {                 // all loads first, so that they are in flight together
-        const int32_t e = wave_base + it * 64 + lane;
-        const bool valid = e < nnz;
-        key[it] = valid ? keys_in[e] : 0;
-        pay[it] = FIRST ? e : (valid ? pay_in[e] : 0);
-    }
+    if constexpr (!EARLY) load_items();
 #pragma unroll
     for (int it = 0; it < ITEMS; ++it) {
         int32_t e = wave_base + it * 64 + lane;
@@ -156,7 +169,7 @@ __device__ inline void scatter_body(const int block, const ScatterArgs &a, unsig
         int dgt = (key[it] >> shift) & (radix - 1);
         const uint64_t m = digit_class_mask(dgt, valid, bits);
         int32_t prior = s_hist[w][dgt];
-        rank[it] = prior + __popcll(m & below);
+        rank[it] = prior + __popcll(m & lanes_below);
         bool leader = valid && ((m >> lane) >> 1) == 0;   // highest lane of its digit class
         if (leader) s_hist[w][dgt] = prior + __popcll(m);
     }
