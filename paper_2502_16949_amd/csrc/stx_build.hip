@@ -309,8 +309,10 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
     if (fusion && fusion->next) prepare_emit_ahead(c, fusion->next, inc);
     // keys[2] receives the unsorted keys: the sorted keys of the previous batch (in keys[0] or keys[1]) stay
     // readable while this batch's first kernel runs
-    const EmitArgs ea{bp, n_ent, n_rel, nnz, inc->a_rowptr, inc->a_colidx, inc->a_vals, c->keys[2], 1 << bits0, ntiles,
-                      c->table, c->ctrl, map, rc, colidx2};
+    // (a large sort reads its unsorted keys, which are the column ids, from A itself: 4 bytes per entry less to write)
+    const bool keys_in_a = items == kBigSortItems;
+    const EmitArgs ea{bp, n_ent, n_rel, nnz, inc->a_rowptr, inc->a_colidx, inc->a_vals, keys_in_a ? nullptr : c->keys[2],
+                      1 << bits0, ntiles, c->table, c->ctrl, map, rc, colidx2};
     if (!emitted) {
     ProfScope prof(c, "k_emit");
 #define STX_EMIT(I, M, S, R) hipLaunchKernelGGL((k_emit<I, M, S, R>), dim3(ntiles), dim3(kThreads), 0, s, ea)
@@ -354,7 +356,8 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
             hipLaunchKernelGGL(k_super_sums, dim3(ngroups), dim3(kThreads), 0, s, p == 0 ? c->table : c->table1, 1 << bits,
                                ntiles, c->super);
         }
-        const ScatterArgs sa{p == 0 ? c->keys[2] : c->keys[cur], c->pay[cur], c->keys[cur ^ 1], c->pay[cur ^ 1], nnz, shift,
+        const ScatterArgs sa{p == 0 ? (keys_in_a ? inc->a_colidx : c->keys[2]) : c->keys[cur], c->pay[cur], c->keys[cur ^ 1],
+                             c->pay[cur ^ 1], nnz, shift,
                              bits, ntiles, p == 0 ? c->table : c->table1, c->super};
 #define STX_SCATTER(F, S, I)                                                                                  \
     hipLaunchKernelGGL((k_scatter<F, S, I>), dim3(ntiles), dim3(kThreads), 0, s, sa)

@@ -105,7 +105,7 @@ __device__ inline void emit_body(const int block, const int nblocks, const EmitA
             vals[e] = slot == 2 ? -1.0f : 1.0f;
             if (slot == 0) rowptr[row] = e;
             if (e == nnz - 1) rowptr[row + 1] = nnz;
-            keys[e] = col;
+            if (keys) keys[e] = col;           // (null: the first pass of the sort reads colidx instead)
             atomicAdd(&s_hist[col & (radix - 1)], 1);
             if (MAP) atomicOr(&s_map[col >> 5], 1u << (col & 31));
             if (RC && slot == 1) atomicAdd(&s_rc[idx], 1);
