@@ -169,15 +169,18 @@ __device__ inline void transr_plan(const int block, const PrepArgs &p)
     }
 }
 
-// Workgroup 0 builds the item lists; workgroup 1 + r writes the two bfloat16 operand-order copies of
-// M_r if relation r occurs in the batch (known from the counted rows, else it looks its column up in
-// the sorted touched list).
+// The first nplan workgroups build the item lists; each of the others writes the two bfloat16 operand-order
+// copies of kPrepRows rows of one M_r (k / kPrepRows workgroups per relation) if that relation occurs in the
+// batch (known from the counted rows, else it looks its column up in the sorted touched list).
+constexpr int kPrepRows = 32;
 template <bool FROM_COUNTS>
 __device__ inline void transr_prepare_body(const int block, const PrepArgs &p)
 {
     if (block < p.nplan) { transr_plan<FROM_COUNTS>(block, p); return; }
     const int tid = threadIdx.x;
-    const int32_t r = block - p.nplan;
+    const int nsplit = p.k / kPrepRows;
+    const int32_t r = (block - p.nplan) / nsplit;
+    const int a0 = ((block - p.nplan) - r * nsplit) * kPrepRows;
     if (FROM_COUNTS) {
         if (p.rel_cnt[r] == 0) return;
     } else {
@@ -190,17 +193,17 @@ __device__ inline void transr_prepare_body(const int block, const PrepArgs &p)
         }
         if (lo >= n_seg || p.touched_cols[lo] != target) return;
     }
-    // 64 rows of M_r at a time go through LDS as bfloat16: the fp32 rows are read with whole-row float4
-    // accesses, and both operand-order copies are written 16 bytes per thread, contiguous across threads.
-    __shared__ __attribute__((aligned(16))) uint16_t s_m[64 * (kMaxProjDim + kLdsPad)];
+    // The rows go through LDS as bfloat16: the fp32 rows are read with whole-row float4 accesses, and both
+    // operand-order copies are written 16 bytes per thread, contiguous across threads.
+    __shared__ __attribute__((aligned(16))) uint16_t s_m[kPrepRows * (kMaxProjDim + kLdsPad)];
     const int64_t kd = (int64_t)p.k * p.d;
     const float *__restrict__ M = p.M + r * kd;
     uint16_t *__restrict__ fwd = p.m16 + r * kd;          // rows a, reduction over j
     uint16_t *__restrict__ gx = p.m16t + r * kd;          // rows j, reduction over a
     const int stride = p.d + kLdsPad, q4 = p.d >> 2;
     const int rt_f = p.k >> 5, rt_g = p.d >> 5, ks_d = p.d >> 4;
-    for (int a0 = 0; a0 < p.k; a0 += 64) {
-        const int rows = min(64, p.k - a0);               // 32 or 64
+    {
+        constexpr int rows = kPrepRows;
         for (int g0 = tid; g0 < rows * q4; g0 += 8 * kThreads) {
             float4 v[8];
 #pragma unroll
@@ -240,7 +243,6 @@ __device__ inline void transr_prepare_body(const int block, const PrepArgs &p)
                 *reinterpret_cast<uint4 *>(gx + ((int64_t)(((a0 >> 4) + ksl) * rt_g + nt) * 64 + l) * 8) = o;
             }
         }
-        __syncthreads();
     }
 }
 
@@ -745,6 +747,12 @@ static PrepArgs prep_args(stx_ctx *c, const stx_incidence *inc, const stx_params
     return a;
 }
 
+// workgroups of the preparation: the planners, then k / kPrepRows per relation
+static unsigned prep_blocks(const stx_ctx *c, const PrepArgs &a)
+{
+    return (unsigned)(a.nplan + c->cfg.n_rel * (c->cfg.rel_dim / kPrepRows));
+}
+
 bool launch_prep_scatter(stx_ctx *c, const stx_incidence *inc, const stx_params *p, const ScatterArgs &sa, bool first)
 {
     if (c->cfg.model != STX_TRANSR || inc->n_rows == 0) return false;
@@ -752,7 +760,7 @@ bool launch_prep_scatter(stx_ctx *c, const stx_incidence *inc, const stx_params 
     if (!a.rel_cnt) return false;
     a.whole_lists = transr_fused_ok(c, inc) ? 1 : 0;      // (stx_train_step runs the forward pass this prepares)
     ProfScope prof(c, "k_prep_scatter");
-    const dim3 grid((unsigned)(sa.ntiles + c->cfg.n_rel + a.nplan));
+    const dim3 grid((unsigned)(sa.ntiles + prep_blocks(c, a)));
     if (first) hipLaunchKernelGGL(k_prep_scatter<true>, grid, dim3(kThreads), 0, c->stream, a, sa);
     else hipLaunchKernelGGL(k_prep_scatter<false>, grid, dim3(kThreads), 0, c->stream, a, sa);
     c->prep_inc = inc;
@@ -768,9 +776,9 @@ stx_status launch_transr_project(stx_ctx *c, const stx_incidence *inc, const stx
         const PrepArgs a = prep_args(c, inc, p);
         ProfScope prof(c, "k_transr_prepare");
         if (a.rel_cnt)
-            hipLaunchKernelGGL(k_transr_prepare<true>, dim3((unsigned)(c->cfg.n_rel + a.nplan)), dim3(kThreads), 0, c->stream, a);
+            hipLaunchKernelGGL(k_transr_prepare<true>, dim3(prep_blocks(c, a)), dim3(kThreads), 0, c->stream, a);
         else
-            hipLaunchKernelGGL(k_transr_prepare<false>, dim3((unsigned)(c->cfg.n_rel + a.nplan)), dim3(kThreads), 0, c->stream, a);
+            hipLaunchKernelGGL(k_transr_prepare<false>, dim3(prep_blocks(c, a)), dim3(kThreads), 0, c->stream, a);
     }
     c->prep_inc = nullptr;      // the copies of M_r are good for this forward pass only: the update changes M_r
     ProfScope prof(c, "k_transr_project");
@@ -799,9 +807,9 @@ stx_status launch_transr_fused(stx_ctx *c, const stx_incidence *inc, const stx_p
         a.whole_lists = 1;
         ProfScope prof(c, "k_transr_prepare");
         if (a.rel_cnt)
-            hipLaunchKernelGGL(k_transr_prepare<true>, dim3((unsigned)(c->cfg.n_rel + a.nplan)), dim3(kThreads), 0, c->stream, a);
+            hipLaunchKernelGGL(k_transr_prepare<true>, dim3(prep_blocks(c, a)), dim3(kThreads), 0, c->stream, a);
         else
-            hipLaunchKernelGGL(k_transr_prepare<false>, dim3((unsigned)(c->cfg.n_rel + a.nplan)), dim3(kThreads), 0, c->stream, a);
+            hipLaunchKernelGGL(k_transr_prepare<false>, dim3(prep_blocks(c, a)), dim3(kThreads), 0, c->stream, a);
     }
     c->prep_inc = nullptr;      // the copies of M_r are good for this forward pass only: the update changes M_r
     FusedArgs a;

@@ -114,7 +114,16 @@ __device__ inline void transr_dm_fixup_body(const int item, const int yslice, co
     const float *src = p.partials + (int64_t)tail.x * kd + idx;
     float4 a = ld4(src);
     int u = 1;
-    for (; u + 3 < parts; u += 4) {   // four partial matrices in flight, added in item order
+    // (a relation with a quarter of a large batch's rows has more than a hundred partial matrices: sixteen in
+    // flight, then four, added in item order)
+    for (; u + 15 < parts; u += 16) {
+        float4 v[16];
+#pragma unroll
+        for (int q = 0; q < 16; ++q) v[q] = ld4(src + (int64_t)(u + q) * kd);
+#pragma unroll
+        for (int q = 0; q < 16; ++q) { a.x += v[q].x; a.y += v[q].y; a.z += v[q].z; a.w += v[q].w; }
+    }
+    for (; u + 3 < parts; u += 4) {
         float4 v[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) v[q] = ld4(src + (int64_t)(u + q) * kd);
