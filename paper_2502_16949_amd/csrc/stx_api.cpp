@@ -13,7 +13,7 @@ inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 struct Layout {
     size_t ctrl, keys[3], pay[2], cix[2], table, table1, super, tile_heads, loss_partials, partials, gbuf[4], total;
-    size_t tr_items, tr_dm_items, tr_counts, tr_m16, tr_m16t, tr_xt, tr_gyt;
+    size_t tr_items, tr_dm_items, tr_fix_items, tr_counts, tr_m16, tr_m16t, tr_xt, tr_gyt;
     size_t colmap, rel_cnt;
     int map_words;
     int64_t rows_max, nnz_max, cols_max;
@@ -98,7 +98,8 @@ Layout make_layout(const stx_config *c)
         const size_t items = (size_t)L.rows_max / kProjRows + segs, dm_items = (size_t)L.rows_max / kProjRowsDm + segs;
         const size_t kd = (size_t)c->rel_dim * c->dim;
         L.tr_items = take((items + 1) * 16);
-        L.tr_dm_items = take((dm_items + 1) * 32);
+        L.tr_dm_items = take((dm_items + 1) * 16);
+        L.tr_fix_items = take(((size_t)L.rows_max / (kProjRowsDm + 1) + 1) * 16);
         L.tr_counts = take(64 * sizeof(int32_t));
         L.tr_m16 = take((size_t)c->n_rel * kd * 2);
         L.tr_m16t = take((size_t)c->n_rel * kd * 2);
@@ -199,6 +200,7 @@ stx_status stx_create(const stx_config *cfg, void *workspace, size_t workspace_b
     const bool tr = cfg->model == STX_TRANSR;
     c->tr_items = tr ? (int32_t *)(base + L.tr_items) : nullptr;
     c->tr_dm_items = tr ? (int32_t *)(base + L.tr_dm_items) : nullptr;
+    c->tr_fix_items = tr ? (int32_t *)(base + L.tr_fix_items) : nullptr;
     c->tr_counts = tr ? (int32_t *)(base + L.tr_counts) : nullptr;
     c->tr_m16 = tr ? (uint16_t *)(base + L.tr_m16) : nullptr;
     c->tr_m16t = tr ? (uint16_t *)(base + L.tr_m16t) : nullptr;

@@ -789,7 +789,7 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
             if (c->dm_ride.fixup) {
                 const DmArgs &da = c->dm_ride.args;
                 if (ntiles > 1 && f_hist.ntiles)
-                    f_dm = DmRide{da, c->dm_ride.items * ((da.k * da.d + kDmFixupSlice - 1) / kDmFixupSlice)};
+                    f_dm = DmRide{da, da.n_fix * ((da.k * da.d + kDmFixupSlice - 1) / kDmFixupSlice)};
                 else
                     dm_fixup_after = true;
             }

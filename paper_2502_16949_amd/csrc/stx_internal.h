@@ -151,8 +151,9 @@ struct EmitAheadState {
 
 // TransR: arguments of the product that forms dL/dM_r and of the sum of its partial matrices (stx_transr.hip).
 struct DmArgs {
-    const int4 *dm_items;
-    const int32_t *counts;       // [1] = number of dM items
+    const int4 *dm_items, *fix_items;
+    const int32_t *counts;       // [1] = number of dM items, [2] = number of fix-up items
+    int n_fix;                   // most fix-up items the batch can have (launch bound of the sums)
     const uint16_t *gyt, *xt;    // operand-order transposed tiles written by the row kernels
     float *g_proj, *partials;
     int d, k;
@@ -198,7 +199,7 @@ struct stx_ctx {
     uint32_t *colmap[3];           // presence bitmaps of the columns (adjacent), or null when the table is too wide
     int map_words, map_cur;        // words per map (0: not kept); which map the next build fills (they rotate)
     // TransR only: work items, bfloat16 operand copies of the projection matrices, transposed operand tiles
-    int32_t *tr_items, *tr_dm_items, *tr_counts;
+    int32_t *tr_items, *tr_dm_items, *tr_fix_items, *tr_counts;
     uint16_t *tr_m16, *tr_m16t, *tr_xt, *tr_gyt;
     int32_t *rel_cnt[2];           // rows per relation of a batch (two buffers alternate, like the bitmaps), or null
     int cnt_cur;

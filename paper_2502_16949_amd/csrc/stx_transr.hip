@@ -43,7 +43,7 @@ struct PrepArgs {
     int32_t n_ent, e_begin;
     const float *M;
     uint16_t *m16, *m16t;
-    int4 *items, *dm_items;
+    int4 *items, *dm_items, *fix_items;
     int32_t *counts;
     int d, k;
     // Rows per relation in the batch, counted while A was written (null: not available).  With them
@@ -56,43 +56,44 @@ struct PrepArgs {
 };
 
 // Item lists of the relation segments (one workgroup).  Row item: {relation, first sorted entry,
-// entries (<= 64), 0}.  dM item, two int4: {relation, first row item, entries (<= 256), slot} and
-// {first slot of the segment, parts to add if this is the segment's last item else 0, 0, 0}; slot is
-// -1 when the segment has a single dM item, which then writes dL/dM_r itself.
+// entries (<= 64), 0}.  dM item: {relation, first row item, entries (<= 256), slot}; slot is -1 when the
+// segment has a single dM item, which then writes dL/dM_r itself.  Fix-up item, one per segment with
+// several dM items: {relation, first slot of the segment, its number of slots, 0}.
 // Workgroup `block` of the planners handles relations (or touched segments) 256*block .. and first adds
 // up what the lists before them need, so the planners do not wait for each other.
 template <bool FROM_COUNTS>
 __device__ inline void transr_plan(const int block, const PrepArgs &p)
 {
     __shared__ int32_t s_o64[kThreads + 1], s_o256[kThreads + 1], s_op[kThreads], s_beg[kThreads], s_len[kThreads],
-        s_rel[kThreads], s_wave[kThreads / 64][4];
+        s_rel[kThreads], s_wave[kThreads / 64][5];
     const int tid = threadIdx.x;
     // the relations' lists, in the order of the sorted A^T: by touched segment, or by relation id with the
     // counted rows (an absent relation has no rows and gets no item)
     const int32_t first = FROM_COUNTS ? 0 : p.seg_id[p.e_begin], last = FROM_COUNTS ? p.n_rel : p.n_touched[0];
     const int32_t sb = first + block * kThreads;
     if (sb >= last) return;
-    int32_t base64 = 0, base256 = 0, basep = 0, base_len = 0;
-    {   // items, slots and entries of the lists before this workgroup's
-        int32_t pre[4] = {0, 0, 0, 0};
+    int32_t base64 = 0, base256 = 0, basep = 0, base_len = 0, basef = 0;
+    {   // items, slots, entries and fix-up items of the lists before this workgroup's
+        int32_t pre[5] = {0, 0, 0, 0, 0};
         for (int32_t s = first + tid; s < sb; s += kThreads) {
             const int32_t len = FROM_COUNTS ? p.rel_cnt[s] : p.seg_ptr[s + 1] - p.seg_ptr[s];
             const int32_t n256 = (len + 255) >> 8;
-            pre[0] += (len + 63) >> 6; pre[1] += n256; pre[2] += n256 > 1 ? n256 : 0; pre[3] += len;
+            pre[0] += (len + 63) >> 6; pre[1] += n256; pre[2] += n256 > 1 ? n256 : 0; pre[3] += len; pre[4] += n256 > 1 ? 1 : 0;
         }
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) pre[q] += __shfl_xor(pre[q], off);
+            for (int q = 0; q < 5; ++q) pre[q] += __shfl_xor(pre[q], off);
         }
         if ((tid & 63) == 0) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) s_wave[tid >> 6][q] = pre[q];
+            for (int q = 0; q < 5; ++q) s_wave[tid >> 6][q] = pre[q];
         }
         __syncthreads();
 #pragma unroll
         for (int ww = 0; ww < kThreads / 64; ++ww) {
             base64 += s_wave[ww][0]; base256 += s_wave[ww][1]; basep += s_wave[ww][2]; base_len += s_wave[ww][3];
+            basef += s_wave[ww][4];
         }
         __syncthreads();
     }
@@ -110,26 +111,26 @@ __device__ inline void transr_plan(const int block, const PrepArgs &p)
             }
         }
         const int32_t n64 = (len + 63) >> 6, n256 = (len + 255) >> 8;
-        // four exclusive scans across the workgroup at once: shuffles inside a wavefront, LDS across the four
-        int32_t inc3[4] = {n64, n256, n256 > 1 ? n256 : 0, len};
+        // five exclusive scans across the workgroup at once: shuffles inside a wavefront, LDS across the four
+        int32_t inc3[5] = {n64, n256, n256 > 1 ? n256 : 0, len, n256 > 1 ? 1 : 0};
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < 5; ++q) {
                 const int32_t up = __shfl_up(inc3[q], off);
                 if ((tid & 63) >= off) inc3[q] += up;
             }
         }
         if ((tid & 63) == 63) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) s_wave[tid >> 6][q] = inc3[q];
+            for (int q = 0; q < 5; ++q) s_wave[tid >> 6][q] = inc3[q];
         }
         __syncthreads();
-        int32_t before[4] = {0, 0, 0, 0}, tot[4] = {0, 0, 0, 0};
+        int32_t before[5] = {0, 0, 0, 0, 0}, tot[5] = {0, 0, 0, 0, 0};
 #pragma unroll
         for (int ww = 0; ww < kThreads / 64; ++ww) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < 5; ++q) {
                 if (ww < (tid >> 6)) before[q] += s_wave[ww][q];
                 tot[q] += s_wave[ww][q];
             }
@@ -159,12 +160,15 @@ __device__ inline void transr_plan(const int block, const PrepArgs &p)
                 if (s_o256[mid] <= w) lo = mid; else hi = mid;
             }
             const int32_t li = w - s_o256[lo], parts = (s_len[lo] + 255) >> 8, first = basep + s_op[lo];
-            p.dm_items[2 * (base256 + w)] = make_int4(s_rel[lo], base64 + s_o64[lo] + 4 * li,
-                                                      min(256, s_len[lo] - 256 * li), parts > 1 ? first + li : -1);
-            p.dm_items[2 * (base256 + w) + 1] = make_int4(first, (parts > 1 && li == parts - 1) ? parts : 0, 0, 0);
+            p.dm_items[base256 + w] = make_int4(s_rel[lo], base64 + s_o64[lo] + 4 * li,
+                                                min(256, s_len[lo] - 256 * li), parts > 1 ? first + li : -1);
         }
+        if (n256 > 1)   // this thread's segment has several dM items: its partial matrices are summed afterwards
+            p.fix_items[basef + before[4] + inc3[4] - 1] = make_int4(rel, basep + op, n256, 0);
         // the planner of the last lists knows the totals
-        if (sb + kThreads >= last && tid == 0) { p.counts[0] = base64 + t64; p.counts[1] = base256 + t256; }
+        if (sb + kThreads >= last && tid == 0) {
+            p.counts[0] = base64 + t64; p.counts[1] = base256 + t256; p.counts[2] = basef + tot[4];
+        }
         (void)tp;
     }
 }
@@ -728,6 +732,8 @@ static RowsArgs rows_args(stx_ctx *c, const stx_incidence *inc, const stx_params
 static int64_t max_segments(const stx_ctx *c, int64_t rows) { return rows < c->cfg.n_rel ? rows : c->cfg.n_rel; }
 static unsigned row_items_max(const stx_ctx *c, int64_t rows) { return (unsigned)(rows / 64 + max_segments(c, rows)); }
 static unsigned dm_items_max(const stx_ctx *c, int64_t rows) { return (unsigned)(rows / 256 + max_segments(c, rows)); }
+// (a segment with several dM items has more than 256 rows)
+static unsigned fix_items_max(int64_t rows) { return (unsigned)(rows / (kProjRowsDm + 1)); }
 
 static PrepArgs prep_args(stx_ctx *c, const stx_incidence *inc, const stx_params *p)
 {
@@ -737,7 +743,8 @@ static PrepArgs prep_args(stx_ctx *c, const stx_incidence *inc, const stx_params
     a.n_ent = (int32_t)c->cfg.n_ent;
     a.e_begin = (int32_t)(2 * inc->n_rows);               // relation columns follow the entity columns
     a.M = p->proj; a.m16 = c->tr_m16; a.m16t = c->tr_m16t;
-    a.items = (int4 *)c->tr_items; a.dm_items = (int4 *)c->tr_dm_items; a.counts = c->tr_counts;
+    a.items = (int4 *)c->tr_items; a.dm_items = (int4 *)c->tr_dm_items; a.fix_items = (int4 *)c->tr_fix_items;
+    a.counts = c->tr_counts;
     a.d = c->cfg.dim; a.k = c->cfg.rel_dim;
     a.rel_cnt = c->cnt_inc == inc ? c->cnt_ptr : nullptr;  // the counts of the last build, if that was this incidence
     a.n_rel = (int32_t)c->cfg.n_rel;
@@ -865,7 +872,8 @@ stx_status launch_transr_backward(stx_ctx *c, const stx_incidence *inc, const st
                                c->gbuf[1]);
     }
     DmArgs a;
-    a.dm_items = (const int4 *)c->tr_dm_items; a.counts = c->tr_counts;
+    a.dm_items = (const int4 *)c->tr_dm_items; a.fix_items = (const int4 *)c->tr_fix_items; a.counts = c->tr_counts;
+    a.n_fix = (int)fix_items_max(inc->n_rows);
     a.gyt = c->tr_gyt; a.xt = c->tr_xt;
     a.g_proj = fused_lr ? nullptr : g->proj; a.partials = c->gbuf[2];
     a.d = c->cfg.dim; a.k = c->cfg.rel_dim;
@@ -874,7 +882,7 @@ stx_status launch_transr_backward(stx_ctx *c, const stx_incidence *inc, const st
     a.fin_partials = nullptr; a.fin_n = 0; a.fin_scale = 1.0f; a.fin_loss = nullptr;
     // Left for the launches of the transposed incidence product, which follow at once; in stx_train_step they take
     // this along (one workgroup per dM item: both widths at most 128), otherwise they launch it first.
-    c->dm_ride = DmRideState{true, inc->n_rows > kProjRowsDm /* else no relation can have two items */, a, a.n_items};
+    c->dm_ride = DmRideState{true, a.n_fix > 0 /* else no relation can have two items */, a, a.n_items};
     if (!(fused_lr && fused_rows && a.d <= 128 && a.k <= 128 && c->segw.armed && c->sorted_inc == inc))
         return launch_transr_dm_late(c);
     return hip_ok(hipGetLastError());
@@ -884,7 +892,7 @@ static void launch_dm_fixup(stx_ctx *c, const DmArgs &a)
 {
     ProfScope prof(c, "k_transr_dm_fixup");
     hipLaunchKernelGGL(k_transr_dm_fixup,
-                       dim3((unsigned)a.n_items, (unsigned)(((int64_t)a.k * a.d + kDmFixupSlice - 1) / kDmFixupSlice)),
+                       dim3((unsigned)a.n_fix, (unsigned)(((int64_t)a.k * a.d + kDmFixupSlice - 1) / kDmFixupSlice)),
                        dim3(kThreads), 0, c->stream, a);
 }
 

@@ -38,7 +38,7 @@ __device__ inline floatx16 zero16()
 // ahead as far as 128 registers allow, which keeps four workgroups on a CU.
 __device__ inline void transr_dm_body(const int item, const int yblock, const DmArgs &p)
 {
-    const int4 it = p.dm_items[2 * item];                 // readable for every item of the launch bound
+    const int4 it = p.dm_items[item];                     // readable for every item of the launch bound
     if (item >= p.counts[1]) return;
     const int rel = it.x, tile0 = it.y, entries = it.z, slot = it.w;
     const int l = threadIdx.x & 63, w = threadIdx.x >> 6, l31 = l & 31, kg = l >> 5;
@@ -100,18 +100,17 @@ __device__ inline void transr_dm_body(const int item, const int yblock, const Dm
 // Elements of the matrix per workgroup of the sum below: four consecutive ones per thread.
 constexpr int kDmFixupSlice = 4 * kThreads;
 
-// The last dM item of a relation that has several adds up the relation's partial matrices in item
+// Fix-up item `item` (a relation with several dM items): adds up the relation's partial matrices in item
 // order (slice `yslice` of the matrix) and stores the sum, or applies the update with it.
 __device__ inline void transr_dm_fixup_body(const int item, const int yslice, const DmArgs &p)
 {
-    if (item >= p.counts[1]) return;
-    const int4 tail = p.dm_items[2 * item + 1];
-    const int parts = tail.y;
-    if (parts == 0) return;
+    if (item >= p.counts[2]) return;
+    const int4 tail = p.fix_items[item];                  // {relation, first slot, slots, 0}
+    const int parts = tail.z;
     const int64_t kd = (int64_t)p.k * p.d;
     const int64_t idx = ((int64_t)yslice * kThreads + threadIdx.x) * 4;
     if (idx >= kd) return;
-    const float *src = p.partials + (int64_t)tail.x * kd + idx;
+    const float *src = p.partials + (int64_t)tail.y * kd + idx;
     float4 a = ld4(src);
     int u = 1;
     // (a relation with a quarter of a large batch's rows has more than a hundred partial matrices: sixteen in
@@ -134,7 +133,7 @@ __device__ inline void transr_dm_fixup_body(const int item, const int yslice, co
         float4 v = ld4(src + (int64_t)u * kd);
         a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
     }
-    const int64_t off = (int64_t)p.dm_items[2 * item].x * kd + idx;
+    const int64_t off = (int64_t)tail.x * kd + idx;
     if (p.fused) {
         const float4 m = ld4(p.M + off);
         const float s0 = p.lr * a.x, s1 = p.lr * a.y, s2 = p.lr * a.z, s3 = p.lr * a.w;
