@@ -45,8 +45,8 @@ DOMINANT_CALLS = {"mid": "k_seg_reduce", "tiny": "k_seg_reduce", "toruse": "k_se
 # x1.0); the runs and their numbers are in profiles/<workload>_kernel_trace.txt and profiles/copy_calibration.txt.
 # A different kernel (--kernel) or workload has no measured figure here and reports null.
 # Keys: (workload, kernel, fused step or not).
-TRAFFIC_BYTES = {("toruse", "k_seg_reduce", True): 1133.78e6 + 623.17e6,
-                 ("toruse", "k_forward_stacked", True): 693.53e6 + 53.52e6,
+TRAFFIC_BYTES = {("toruse", "k_seg_reduce", True): 1133.94e6 + 623.18e6,
+                 ("toruse", "k_forward_stacked", True): 684.45e6 + 53.52e6,
                  ("toruse", "k_forward_stacked", False): 693.55e6 + 53.52e6,
                  ("toruse", "k_seg_reduce", False): 561.76e6 + 532.18e6,
                  ("toruse", "k_sgd_rows", False): 1056.94e6 + 526.37e6,
@@ -60,8 +60,8 @@ TRAFFIC_BYTES = {("toruse", "k_seg_reduce", True): 1133.78e6 + 623.17e6,
                  ("transh", "k_fwdh_scatter", "rides"): 34.67e6 + 105.22e6,
                  ("transh", "k_seg_fixup", "rides"): 4.06e6 + 0.48e6,
                  ("transr", "k_transr_fused", "rides"): 40.20e6 + 52.83e6,
-                 ("transr", "k_seg_reduce", "rides"): 89.63e6 + 31.34e6,
-                 ("transr", "k_seg_fixup", "rides"): 9.85e6 + 1.26e6,
+                 ("transr", "k_seg_reduce", "rides"): 89.66e6 + 31.35e6,
+                 ("transr", "k_seg_fixup", "rides"): 9.78e6 + 1.26e6,
                  # the other modes (profiles/semiring_complex_*_kernel_trace.txt, profiles/rank_mid_kernel_trace.txt)
                  ("semiring complex", "mid", "k_semiring_terms"): 66.64e6 + 100.66e6,
                  ("semiring complex", "toruse", "k_semiring_terms"): 1560.16e6 + 2013.27e6}
