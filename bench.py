@@ -579,6 +579,12 @@ class Job:
             e["achieved_min_bytes"] = round(bmin / (us * 1e-6) / 1e9, 1)
         if e["traffic"] and us > 0:
             e["achieved_traffic"] = round(e["traffic"] / (us * 1e-6) / 1e9, 1)
+        if ach > peak and kname in ("k_forward_stacked", "k_fwd_scatter"):
+            # the algorithmic figure counts three gathered table rows per matrix row; the kernel requests a positive's
+            # rows once for all of its negatives and repeated rows come from the caches
+            e["note"] = ("above the peak because the algorithmic bytes (three table rows per matrix row) are more than "
+                         "this kernel moves: it fetches a positive's rows once for its negatives and hot rows hit in "
+                         "cache; hold it against achieved_traffic and achieved_min_bytes instead")
         return e
 
 
