@@ -27,8 +27,9 @@
 //
 // In stx_train_step the launches of both kernels carry more (template parameter RIDE): the product reads the
 // sorted keys and payloads of the build itself, so that the build's last kernel and the sum of the loss run
-// as extra workgroups of its launch, and one stage of the next batch's build rides in each launch.  All parts
-// of a launch share one block of LDS.
+// as extra workgroups of its launch, and one stage of the next batch's build rides in each launch; with TransR
+// the dL/dM_r product (stx_transr_dm_body.h) rides in the product's launch and the sums of its partial matrices
+// in the fix-up's.  All parts of a launch share one block of LDS.
 #include "stx_emit_body.h"
 #include "stx_forward_body.h"
 #include "stx_rowops.h"

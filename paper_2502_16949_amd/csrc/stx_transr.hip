@@ -7,7 +7,7 @@
 //
 //   forward   Y_g  = X_g . M_r^T + r        (n_g x d)(d x k)      k_transr_rows<false>
 //   backward  GX_g = GY_g . M_r             (n_g x k)(k x d)      k_transr_rows<true>
-//             dM_r = GY_g^T . X_g           (k x n_g)(n_g x d)    k_transr_dm (+ k_transr_dm_fixup)
+//             dM_r = GY_g^T . X_g           (k x n_g)(n_g x d)    k_transr_dm (+ k_transr_dm_fixup); bodies in stx_transr_dm_body.h
 //
 // Operands are bfloat16 (round to nearest even), products accumulate in fp32 in
 // v_mfma_f32_32x32x16_bf16; x = h - t is formed in fp32 first.
@@ -15,8 +15,9 @@
 // Work items.  Group sizes are power-law distributed, so the list of every relation is cut into
 // items of at most 64 entries (the two row products) and 256 entries (the dM product); an item never
 // spans two relations, so a workgroup loads one M_r and runs dense tiles.  k_transr_prepare builds
-// both item lists with one scan over the relation segments, and the kernels are launched with the
-// largest possible item count; workgroups past the real count leave at once.
+// the item lists (and the list of relations whose several dM items leave partial matrices to add up)
+// with one scan over the relation segments, and the kernels are launched with the largest possible
+// item count; workgroups past the real count leave at once.
 //
 // Operand order.  The 32x32x16 MFMA wants, from lane l of 64, row (l % 32) of its operand and the
 // eight consecutive reduction elements 8*(l / 32) .. of that row, for A and B alike; accumulator
