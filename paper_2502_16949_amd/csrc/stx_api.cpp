@@ -227,6 +227,7 @@ stx_status stx_create(const stx_config *cfg, void *workspace, size_t workspace_b
     c->ahead.armed = false;
     c->ahead.emit_done = c->ahead.scatter_done = c->ahead.hist_done = false;
     c->ahead.scatter_ok = c->ahead.hist_ok = false;
+    c->ahead.late_only = false;
     c->ahead.inc = nullptr;
     c->sorted_inc = nullptr;
     c->sampled_inc = nullptr;
@@ -665,9 +666,11 @@ stx_status stx_train_step(stx_ctx *ctx, const stx_batch *bt, stx_incidence *inc,
     auto unwind_ahead = [&]() {
         if (ctx->ahead.armed && !ctx->ahead.emit_done) {
             ctx->ahead.armed = false;
-            ctx->map_cur = (ctx->map_cur + 2) % 3;
-            ctx->cix_cur ^= 1;
-            if (ctx->ahead.args.rc.cur) ctx->cnt_cur ^= 1;
+            if (!ctx->ahead.late_only) {   // (a large sort's first kernel takes no rotating buffer)
+                ctx->map_cur = (ctx->map_cur + 2) % 3;
+                ctx->cix_cur ^= 1;
+                if (ctx->ahead.args.rc.cur) ctx->cnt_cur ^= 1;
+            }
         }
     };
     if (s != STX_OK) { launch_seg_write_late(ctx); unwind_ahead(); return s; }

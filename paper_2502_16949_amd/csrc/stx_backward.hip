@@ -498,16 +498,25 @@ __global__ __launch_bounds__(kThreads, RIDE == 5 ? 4 : (ITERS == 1 && PACKED && 
 }
 
 // RIDE: 1 the first scatter pass of the next batch's sort comes along, 2 its histogram pass of the second digit,
-// 3 as 2, and the sums of TransR's partial dL/dM_r matrices come along.
+// 3 as 2, and the sums of TransR's partial dL/dM_r matrices come along, 4 the first kernel of the next batch's
+// build when that sort is a large one (nothing after this launch reads the A arrays it overwrites).
 template <int LPR, int ITERS, int CHUNK, bool FUSED, int RIDE>
 __global__ __launch_bounds__(kThreads) void k_seg_fixup(const int32_t *__restrict__ packed,
                                                         const int32_t *__restrict__ seg_id,
                                                         const int32_t *__restrict__ seg_ptr, int32_t e_begin,
                                                         int32_t e_end, int d4, float *__restrict__ out_rows,
                                                         int ld_out, const float *__restrict__ partials, FusedArgs fu,
-                                                        SegSecond sec, ScatterAhead sa, HistAhead ha, DmRide dm)
+                                                        SegSecond sec, ScatterAhead sa, HistAhead ha, DmRide dm,
+                                                        EmitAhead ea)
 {
     int block = (int)blockIdx.x;
+    if constexpr (RIDE == 4) {
+        if (block < ea.ntiles) {      // uniform in the workgroup
+            emit_body<kBigSortItems, false, true, false>(block, ea.ntiles, ea.args);
+            return;
+        }
+        block -= ea.ntiles;
+    }
     if constexpr (RIDE == 3) {
         if (block < dm.blocks) {      // uniform in the workgroup
             const int slices = (dm.args.k * dm.args.d + kDmFixupSlice - 1) / kDmFixupSlice;
@@ -533,7 +542,8 @@ __global__ __launch_bounds__(kThreads) void k_seg_fixup(const int32_t *__restric
     // The tiles are taken from the last one down: the relation columns sort last and own the longest runs (one
     // relation has a fifth of a batch's rows), whose closing workgroups add up the most partial rows; started
     // last, after the other workgroups have come and gone, their chains would set the time of the launch.
-    block = ((int)gridDim.x - (RIDE == 1 ? sa.ntiles : RIDE == 2 ? ha.ntiles : RIDE == 3 ? ha.ntiles + dm.blocks : 0)) - 1 - block;
+    block = ((int)gridDim.x - (RIDE == 1 ? sa.ntiles : RIDE == 2 ? ha.ntiles : RIDE == 3 ? ha.ntiles + dm.blocks
+                               : RIDE == 4 ? ea.ntiles : 0)) - 1 - block;
     if (block >= sec.first_block) {   // uniform in the workgroup
         block -= sec.first_block;
         e_begin = sec.e_begin; e_end = sec.e_end;
@@ -798,7 +808,11 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
             launch_transr_dm_late(c);
         }
     }
-    const int r_blocks = r_emit.ntiles + r_scat.ntiles + r_dm.blocks, f_blocks = f_scat.ntiles + f_hist.ntiles + f_dm.blocks;
+    // the first kernel of a large next build: in the fix-up launch, the last one of the step
+    EmitAhead f_emit{};
+    if (fused && ITERS == 1 && ntiles > 1 && c->ahead.armed && c->ahead.late_only) f_emit = take_emit_ahead(c, true);
+    const int r_blocks = r_emit.ntiles + r_scat.ntiles + r_dm.blocks,
+              f_blocks = f_scat.ntiles + f_hist.ntiles + f_dm.blocks + f_emit.ntiles;
     // Wide rows (more than one float4 per lane) run as column slices of the one-float4 kernels: more rows in
     // flight per lane and ITERS times the workgroups.  The unit-length rescale needs whole rows.
     const bool whole_rows = fused && (fu.mode == 2 || sec.fused_mode == 2);
@@ -817,7 +831,7 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
             ProfScope prof(c, "k_seg_fixup");                                                                   \
             hipLaunchKernelGGL((k_seg_fixup<LPR, 1, CH, F, 0>), grid, dim3(kThreads), 0, c->stream,             \
                                inc->at_packed, inc->at_seg_id, inc->at_seg_ptr, e_begin, e_end, width / 4,      \
-                               out_rows, ld_out, c->partials, fu, sec, f_scat, f_hist, f_dm);                   \
+                               out_rows, ld_out, c->partials, fu, sec, f_scat, f_hist, f_dm, f_emit);           \
         }                                                                                                       \
     } while (0)
 #define STX_SLICED2(P, CH) do { if (fused) STX_SLICED(P, CH, true); else STX_SLICED(P, CH, false); } while (0)
@@ -835,7 +849,7 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
 #define STX_SEG_F(CH, F, R)                                                                                     \
     hipLaunchKernelGGL((k_seg_fixup<LPR, ITERS, CH, F, (F && ITERS == 1 && !(R == 3 && LPR > 32)) ? R : 0>), dim3(ntiles + f_blocks), \
                        dim3(kThreads), 0, c->stream, inc->at_packed, inc->at_seg_id, inc->at_seg_ptr, e_begin,  \
-                       e_end, width / 4, out_rows, ld_out, c->partials, fu, sec, f_scat, f_hist, f_dm)
+                       e_end, width / 4, out_rows, ld_out, c->partials, fu, sec, f_scat, f_hist, f_dm, f_emit)
 #define STX_SEG(P, CH, F)                                                                                       \
     do {                                                                                                        \
         {                                                                                                       \
@@ -856,6 +870,7 @@ static void seg_go(stx_ctx *c, const stx_incidence *inc, int32_t e_begin, int32_
             if (F && ITERS == 1 && f_hist.ntiles && f_dm.blocks) STX_SEG_F(CH, F, 3);                           \
             else if (F && ITERS == 1 && f_hist.ntiles) STX_SEG_F(CH, F, 2);                                     \
             else if (F && ITERS == 1 && f_scat.ntiles) STX_SEG_F(CH, F, 1);                                     \
+            else if (F && ITERS == 1 && f_emit.ntiles) STX_SEG_F(CH, F, 4);                                     \
             else STX_SEG_F(CH, F, 0);                                                                           \
         }                                                                                                       \
     } while (0)

@@ -162,6 +162,7 @@ static void clear_ahead(stx_ctx *c)
     c->ahead.armed = false;
     c->ahead.emit_done = c->ahead.scatter_done = c->ahead.hist_done = false;
     c->ahead.scatter_ok = c->ahead.hist_ok = false;
+    c->ahead.late_only = false;
 }
 
 bool prepare_emit_ahead(stx_ctx *c, const stx_batch *next, stx_incidence *inc)
@@ -170,10 +171,27 @@ bool prepare_emit_ahead(stx_ctx *c, const stx_batch *next, stx_incidence *inc)
     if (!next || next->b <= 0 || next->k < 0 || next->b > c->cfg.max_batch || next->k > c->cfg.max_neg) return false;
     if (!next->h || !next->r || !next->t || (next->k > 0 && (!next->neg_h || !next->neg_t))) return false;
     if (next->m_total < 0 || next->global_offset < 0) return false;
-    if (c->map_words <= 0) return false;                               // needs the bitmap path
-    if (c->cfg.model == STX_TRANSR && !c->rel_cnt[0]) return false;     // TransR: its work items must come from counts
     const int64_t nnz = 3 * (int64_t)next->b * (1 + next->k);
-    if (nnz > (1 << 19)) return false;                                  // the small-sort shape of the first kernel only
+    if (nnz > (1 << 19)) {
+        // A large sort: its first kernel (no bitmap, no row counts: the shapes of the large benchmark) can run in the
+        // fix-up launch that ends this step, whose own workgroups mostly wait for memory.
+        if (c->map_words > 0 || c->rel_cnt[0] || c->cfg.model == STX_TRANSR) return false;
+        const int ntiles = (int)((nnz + kThreads * kBigSortItems - 1) / (kThreads * kBigSortItems));
+        const int bits0 = c->sort_bits < c->digit_bits ? c->sort_bits : c->digit_bits;
+        const uint64_t base_ctr = (next->epoch * (uint64_t)next->m_total + (uint64_t)next->global_offset) * (uint64_t)next->k;
+        const BatchPtrs bp{next->h, next->r, next->t, nullptr, nullptr, next->b, next->k > 0 ? next->k : 1,
+                           next->neg_h, next->neg_t, next->seed, base_ctr};
+        c->ahead.args = EmitArgs{bp, (int32_t)c->cfg.n_ent, (int32_t)c->cfg.n_rel, (int32_t)nnz, inc->a_rowptr, inc->a_colidx,
+                                 inc->a_vals, nullptr, 1 << bits0, ntiles, c->table, c->ctrl, ColMap{nullptr, nullptr, 0},
+                                 RelCnt{nullptr, nullptr, 0}, nullptr};
+        c->ahead.ntiles = ntiles;
+        c->ahead.inc = inc;
+        c->ahead.armed = true;
+        c->ahead.late_only = true;
+        return true;
+    }
+    if (c->map_words <= 0) return false;                               // small sorts: needs the bitmap path
+    if (c->cfg.model == STX_TRANSR && !c->rel_cnt[0]) return false;     // TransR: its work items must come from counts
     const int ntiles = (int)((nnz + kThreads * kSortItems - 1) / (kThreads * kSortItems));
     const int bits0 = c->sort_bits < c->digit_bits ? c->sort_bits : c->digit_bits;
     const uint64_t base_ctr = (next->epoch * (uint64_t)next->m_total + (uint64_t)next->global_offset) * (uint64_t)next->k;
@@ -212,9 +230,9 @@ bool prepare_emit_ahead(stx_ctx *c, const stx_batch *next, stx_incidence *inc)
 
 // The stages of the next build in their order; a launch that asks gets the stage that is due, at most one per
 // launch because every stage reads what the whole of the one before it wrote.
-EmitAhead take_emit_ahead(stx_ctx *c)
+EmitAhead take_emit_ahead(stx_ctx *c, bool fixup_launch)
 {
-    if (!c->ahead.armed || c->ahead.emit_done) return EmitAhead{};
+    if (!c->ahead.armed || c->ahead.emit_done || c->ahead.late_only != fixup_launch) return EmitAhead{};
     c->ahead.emit_done = true;
     return EmitAhead{c->ahead.args, c->ahead.ntiles};
 }
@@ -268,7 +286,7 @@ stx_status launch_build(stx_ctx *c, const int32_t *h, const int32_t *r, const in
     if (sample) { bp.nh_out = sample->neg_h; bp.nt_out = sample->neg_t; bp.seed = sample->seed; bp.base_ctr = sample->base_ctr; }
     const bool use_map = c->map_words > 0;
     const EmitArgs &pa = prev.args;
-    const bool emitted = prev.armed && prev.emit_done && sample && use_map && prev.inc == inc && pa.bp.h == h && pa.bp.r == r &&
+    const bool emitted = prev.armed && prev.emit_done && sample && (use_map || prev.late_only) && prev.inc == inc && pa.bp.h == h && pa.bp.r == r &&
                          pa.bp.t == t && pa.bp.b == b && pa.bp.k == bp.k && pa.nnz == nnz &&
                          pa.bp.nh_out == bp.nh_out && pa.bp.nt_out == bp.nt_out && pa.bp.seed == bp.seed &&
                          pa.bp.base_ctr == bp.base_ctr;

@@ -140,6 +140,9 @@ struct EmitAheadState {
     bool armed;
     bool emit_done, scatter_done, hist_done;
     bool scatter_ok, hist_ok;
+    // a large sort: the first kernel alone runs ahead, and only in the fix-up launch that ends the step (it
+    // overwrites the caller's A arrays, of which no copy is kept for the launches before that one)
+    bool late_only;
     EmitArgs args;
     ScatterArgs sargs;
     HistArgs hargs;
@@ -294,7 +297,8 @@ struct DmRide {
     DmArgs args;
     int blocks;                    // workgroups of the launch that play this part (0: none)
 };
-EmitAhead take_emit_ahead(stx_ctx *);
+// (fixup_launch: the caller is the fix-up launch of the transposed product, the last launch of a step)
+EmitAhead take_emit_ahead(stx_ctx *, bool fixup_launch = false);
 ScatterAhead take_scatter_ahead(stx_ctx *);
 HistAhead take_hist_ahead(stx_ctx *);
 stx_status launch_seg_write_late(stx_ctx *);

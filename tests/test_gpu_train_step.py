@@ -137,6 +137,8 @@ LOOKAHEAD_CASES = [
     ("transe", "l1", 20000, 50, 50000, 1, 32, 0),                # 293 sort tiles: the longest table scan in a scatter workgroup
     ("transe", "l2", 70000, 5, 3000, 1, 32, 0),                  # no presence bitmap: `next` is ignored
     ("transe", "l2", 300, 5, 200, 1, 512, 0),                    # wide rows (column slices): `next` is ignored
+    ("toruse", "torus_l1", 300000, 50, 60000, 2, 32, 0),         # a large sort (540,000 entries, no bitmap): its first kernel alone
+    ("transe", "l2", 200000, 30, 90000, 1, 32, 0),               # ... runs ahead, in the fix-up launch that ends the step
     ("transr", "l2", 300, 8, 500, 1, 64, B.STX_FLAG_BF16_PROJ),  # TransR: the early kernel also counts rows per relation
     ("transr", "l2", 2000, 40, 3000, 2, 128, B.STX_FLAG_BF16_PROJ),  # ... at the benchmark's width, several negatives
     ("transr", "l2", 100, 4, 700, 1, 64, B.STX_FLAG_BF16_PROJ),  # one sort pass: the early scatter pass must wait for the fix-up launch
