@@ -241,7 +241,9 @@ stx_status stx_backward_sgd(stx_ctx *ctx, const stx_incidence *inc, stx_params *
  * out-of-range index of a batch that was announced and then not given is counted once more when its
  * batch is written again).  Used when the configuration keeps a column
  * bitmap (n_ent + n_rel <= 65,536), with dim <= 256 (TransR: also n_rel <= 4,096) and batches of at most
- * 2^19 entries of A; ignored otherwise.  next->next is ignored.                                          */
+ * 2^19 entries of A.  Batches of more entries, on configurations without that bitmap (TransE, TorusE, TransH,
+ * dim <= 256): the first of those kernels alone runs ahead, in the last launch of this step, with the same
+ * effects on return.  Ignored otherwise.  next->next is ignored.                                          */
 typedef struct stx_batch {
     const int32_t *h, *r, *t; /* [b], device */
     int32_t b, k;
